@@ -1,0 +1,180 @@
+/*
+ * conf_kv.h -- C ABI of the Conf-KV per-decode-step library for AMD MI355X (gfx950).
+ *
+ * The library keeps, for every unit (layer, batch, kv-head), a position-sorted KV
+ * cache whose oldest tokens are INT8 (per-token, per-kv-head fp16 absmax scales) and
+ * whose newest tokens are FP16, plus per-slot metadata (original position, fp32 EMA of
+ * attention mass).  One decode step is
+ *
+ *     for every layer:  conf_kv_attend          (append + attention + mass EMA)
+ *     once:             conf_kv_step            (confidence -> tight/loose budget)
+ *     once:             conf_kv_evict_compact   (rank, evict, compact, demote)
+ *
+ * which is the paper's Algorithm 1 with the append moved in front of the step's own
+ * attention (a decode query attends to its own key).
+ *
+ * Conventions
+ *   - "dev" pointers are device memory owned by the CALLER and valid until
+ *     conf_kv_destroy; "host" pointers are ordinary host memory.  The library never
+ *     allocates or frees device memory.
+ *   - The three hot calls only enqueue kernels on the given stream; they never
+ *     synchronise.  Lengths and budgets live on the device; the host keeps upper bounds.
+ *   - A handle is driven from one host thread, on one stream at a time.
+ *   - Every function returns CONF_KV_OK (0) or a negative conf_kv_status; nothing throws.
+ *   - Tensors are dense, row-major, in the index order written next to each argument.
+ *   - fp16 data is IEEE binary16; "int8" codes are two's complement in [-127, 127].
+ */
+#ifndef CONF_KV_H
+#define CONF_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct conf_kv_handle conf_kv_handle;
+typedef void *conf_kv_stream;            /* a hipStream_t; NULL = the default stream */
+
+typedef enum conf_kv_status {
+  CONF_KV_OK = 0,
+  CONF_KV_ERR_INVALID_ARG = -1,  /* null pointer, negative size, misaligned buffer            */
+  CONF_KV_ERR_BAD_SHAPE = -2,    /* a config field outside what the kernels are built for     */
+  CONF_KV_ERR_BAD_LAYER = -3,    /* layer index outside [0, n_layers)                          */
+  CONF_KV_ERR_CAPACITY = -4,     /* the operation would need more slots than `capacity`       */
+  CONF_KV_ERR_BAD_STATE = -5,    /* call order violated (see each function)                    */
+  CONF_KV_ERR_HIP = -6,          /* a HIP call failed; see conf_kv_last_hip_error             */
+  CONF_KV_ERR_DEVICE = -7        /* a kernel reported an internal error (bounded wait expired) */
+} conf_kv_status;
+
+/*
+ * Problem statement of Algorithm 1 (its REQUIRE line: thresholds tau, budgets
+ * N_high / N_low, protected window P, ranker weight alpha, FP16 window W) plus the
+ * shape of the model's attention.  Weights of Eq. 1 are (w_entropy, w_margin, w_top).
+ */
+typedef struct conf_kv_config {
+  int32_t n_layers;          /* L  >= 1                                                        */
+  int32_t batch;             /* B  >= 1 sequences, all at the same decode position             */
+  int32_t n_q_heads;         /* Hq, a multiple of n_kv_heads; group G = Hq / Hkv in {1,2,4,5,8} */
+  int32_t n_kv_heads;        /* Hkv                                                            */
+  int32_t head_dim;          /* D in {64, 128}                                                 */
+  int32_t vocab;             /* V >= 2                                                         */
+  int32_t capacity;          /* slots per unit; a multiple of 16; must exceed every budget     */
+  int32_t fp16_window;       /* W >= 0: newest W retained tokens stay FP16; < 0: FP16-only     */
+  int32_t protected_window;  /* P >= 0: the newest P tokens are never evicted                  */
+  float tau;                 /* tight budget when c >= tau (paper: 0.7)                        */
+  float alpha;               /* ranker weight on attention mass (paper: 0.65)                  */
+  float ema_decay;           /* lambda of the mass EMA (paper: 0.9)                            */
+  float sm_scale;            /* softmax scale, usually 1/sqrt(D)                               */
+  float w_entropy, w_margin, w_top; /* Eq. 1 weights (paper: 0.4, 0.3, 0.3)                    */
+  const int32_t *n_tight;    /* host [L]: N_high per layer (budget on confident steps)         */
+  const int32_t *n_loose;    /* host [L]: N_low  per layer; n_tight[l] <= n_loose[l]           */
+} conf_kv_config;
+
+typedef struct conf_kv_stats {
+  uint64_t evicted;          /* tokens evicted, summed over units                              */
+  uint64_t demoted;          /* tokens quantised FP16 -> INT8 by conf_kv_evict_compact         */
+  uint64_t tight_steps;      /* sequence-steps that selected the tight budget                  */
+  uint64_t loose_steps;      /* sequence-steps that selected the loose budget                  */
+  uint64_t device_errors;    /* bounded waits that expired inside kernels (0 in a healthy run) */
+} conf_kv_stats;
+
+/* Bytes of device memory the caller must provide for the cache state and for scratch
+ * (split partials, arrival counters, ranking work arrays).  0 on an invalid config. */
+size_t conf_kv_state_bytes(const conf_kv_config *cfg);
+size_t conf_kv_scratch_bytes(const conf_kv_config *cfg);
+
+/* Validates cfg, copies it, lays the cache out inside dev_state (256-byte aligned, at
+ * least conf_kv_state_bytes) and dev_scratch (likewise), zeroes lengths / counters /
+ * scratch with synchronous HIP calls on the current device, and sets every budget to the
+ * loose one.  All units start empty.  On error *out is NULL. */
+int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_state,
+                   void *dev_scratch);
+
+/* Frees the host-side handle only (device buffers belong to the caller). */
+int conf_kv_destroy(conf_kv_handle *h);
+
+/* Replaces the cache of one layer by T0 prompt tokens at positions 0..T0-1
+ * (Algorithm 1's input cache).  dev_k16 / dev_v16: fp16 [B][Hkv][T0][D].
+ * dev_ema0: fp32 [B][Hkv][T0] initial EMA importance, or NULL for zeros.
+ * All but the newest W tokens are quantised to INT8 ("Tiled attention and mixed
+ * precision": symmetric, scale = max|x|/127, here per token and kv-head).
+ * 0 <= T0 <= capacity - 1, else CONF_KV_ERR_CAPACITY.  Enqueues on `stream`. */
+int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16,
+                         const void *dev_v16, int32_t T0, const float *dev_ema0,
+                         conf_kv_stream stream);
+
+/*
+ * Decode attention of one layer with the importance update fused in
+ * (Algorithm 1: forward pass attention, "update EMA attention metadata", "append new K/V
+ * in FP16"; "Tiled attention and mixed precision"; "Budget and ranker").
+ *   1. appends (k_new, v_new) in FP16 at the next position with EMA 0;
+ *   2. out[b][h] = softmax_i(sm_scale * q[b][h] . K_i) V_i over ALL stored slots of the
+ *      unit (b, h / G), K_i/V_i being the fp16 value or int8 code * fp16 scale, computed
+ *      as split-K blockwise online softmax with fp32 accumulation;
+ *   3. per slot, A_i = sum over the G query heads of the exact normalised probability
+ *      (so sum_i A_i = G), then ema_i <- lambda * ema_i + (1 - lambda) * A_i.
+ * dev_q16: fp16 [B][Hq][D]; dev_knew16 / dev_vnew16: fp16 [B][Hkv][D]; dev_out16: fp16
+ * [B][Hq][D], written.  All 16-byte aligned.
+ * Exactly one conf_kv_attend per layer between two conf_kv_evict_compact calls
+ * (CONF_KV_ERR_BAD_STATE otherwise); CONF_KV_ERR_CAPACITY, before anything is launched,
+ * if the unit could already hold `capacity` tokens.
+ */
+int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const void *dev_knew16,
+                   const void *dev_vnew16, void *dev_out16, conf_kv_stream stream);
+
+/*
+ * Confidence estimator and budget selector (Eq. 1; "Budget and ranker"; Algorithm 1,
+ * lines softmax / c / N).  For every sequence b: p = softmax(logits[b]),
+ * c = w_entropy (1 - H(p)/log V) + w_margin sigmoid(log p_(1) - log p_(2)) + w_top p_(1);
+ * tight = (c >= tau); the per-layer budget N[l][b] = tight ? n_tight[l] : n_loose[l]
+ * stays on the device for the next conf_kv_evict_compact.
+ * dev_logits: fp32 [B][V] (-inf entries allowed).  dev_conf: fp32 [B] written.
+ * dev_sel: uint8 [B] written, 1 = tight.  Either output may be NULL.
+ */
+int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
+                 conf_kv_stream stream);
+
+/*
+ * Ranker, eviction, in-place compaction and demotion for every layer (Algorithm 1's
+ * per-layer tail; "Budget and ranker"; "Cache manager").  For each unit with
+ * n > N[l][b]: the newest min(P, n) slots are protected; over the other slots
+ * s_i = alpha * minmax(ema_i) + (1 - alpha) * minmax(pos_i) (min-max over those
+ * candidates, 0 when degenerate), the min(n - N, n - P) lowest are evicted (equal
+ * scores: oldest first), survivors are gathered in place keeping position order, and
+ * then the oldest FP16 slots are quantised until at most W stay FP16.
+ * Uses the budgets of the last conf_kv_step (the loose ones before any).  Commits the
+ * appends made by conf_kv_attend since the previous call.
+ */
+int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream);
+
+/* ---- inspection: these synchronise the device; meant for tests and monitoring ---- */
+
+/* host_len: int32 [L][B] current cache length (appends included); host_n16: int32
+ * [L][B][Hkv] FP16 slots per unit, or NULL. */
+int conf_kv_lengths(conf_kv_handle *h, int32_t *host_len, int32_t *host_n16);
+
+/* Position-sorted view of one unit into host buffers sized for `capacity` slots; any
+ * output pointer may be NULL.  pos int32 [n]; ema fp32 [n]; is_fp16 uint8 [n];
+ * k16 / v16: fp16 bits [n][D] (zeros on INT8 slots); k8 / v8: int8 [n][D] (zeros on FP16
+ * slots); k_scale / v_scale: fp16 bits [n] (zero on FP16 slots); *n_out = n. */
+int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head, int32_t *pos,
+                   float *ema, uint8_t *is_fp16, uint16_t *k16, uint16_t *v16, int8_t *k8,
+                   int8_t *v8, uint16_t *k_scale, uint16_t *v_scale, int32_t *n_out);
+
+/* Device-side counters since conf_kv_create.  Returns CONF_KV_ERR_DEVICE if any kernel
+ * reported an internal error (the counters are still filled in). */
+int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *host_stats);
+
+/* Split count conf_kv_attend would use for `layer` now (diagnostics / benchmarks). */
+int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer);
+
+const char *conf_kv_strerror(int status);
+/* The hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
+int conf_kv_last_hip_error(conf_kv_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONF_KV_H */

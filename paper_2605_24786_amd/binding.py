@@ -1,0 +1,208 @@
+"""ctypes binding of libconfkv.so: argument marshalling only.
+
+Every step of the decode path runs inside the HIP library; this module passes device
+pointers of torch tensors and the current HIP stream through the C ABI declared in
+include/conf_kv.h and owns the two device buffers the library asks the caller for.
+There is no CPU fallback: importing works without a GPU (so the ABI can be inspected),
+creating a ``ConfKV`` does not.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconfkv.so")
+
+OK = 0
+ERR_INVALID_ARG, ERR_BAD_SHAPE, ERR_BAD_LAYER, ERR_CAPACITY, ERR_BAD_STATE, ERR_HIP, ERR_DEVICE = (
+    -1, -2, -3, -4, -5, -6, -7)
+
+
+class ConfKVConfig(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("batch", C.c_int32), ("n_q_heads", C.c_int32),
+        ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("vocab", C.c_int32),
+        ("capacity", C.c_int32), ("fp16_window", C.c_int32), ("protected_window", C.c_int32),
+        ("tau", C.c_float), ("alpha", C.c_float), ("ema_decay", C.c_float), ("sm_scale", C.c_float),
+        ("w_entropy", C.c_float), ("w_margin", C.c_float), ("w_top", C.c_float),
+        ("n_tight", C.POINTER(C.c_int32)), ("n_loose", C.POINTER(C.c_int32)),
+    ]
+
+
+class ConfKVStats(C.Structure):
+    _fields_ = [("evicted", C.c_uint64), ("demoted", C.c_uint64), ("tight_steps", C.c_uint64),
+                ("loose_steps", C.c_uint64), ("device_errors", C.c_uint64)]
+
+
+class ConfKVError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {strerror(status)} (status {status})")
+        self.status = status
+
+
+# every symbol include/conf_kv.h declares: name -> (restype, argtypes)
+_P = C.c_void_p
+SYMBOLS = {
+    "conf_kv_state_bytes": (C.c_size_t, [C.POINTER(ConfKVConfig)]),
+    "conf_kv_scratch_bytes": (C.c_size_t, [C.POINTER(ConfKVConfig)]),
+    "conf_kv_create": (C.c_int, [C.POINTER(_P), C.POINTER(ConfKVConfig), _P, _P]),
+    "conf_kv_destroy": (C.c_int, [_P]),
+    "conf_kv_load_prefill": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, _P]),
+    "conf_kv_attend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P]),
+    "conf_kv_step": (C.c_int, [_P, _P, _P, _P, _P]),
+    "conf_kv_evict_compact": (C.c_int, [_P, _P]),
+    "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
+    "conf_kv_export": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32] + [_P] * 10),
+    "conf_kv_counters": (C.c_int, [_P, C.POINTER(ConfKVStats)]),
+    "conf_kv_attend_splits": (C.c_int, [_P, C.c_int32]),
+    "conf_kv_strerror": (C.c_char_p, [C.c_int]),
+    "conf_kv_last_hip_error": (C.c_int, [_P]),
+}
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libconfkv.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load_library().conf_kv_strerror(status).decode()
+
+
+def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacity, fp16_window,
+                protected_window, n_tight: Sequence[int], n_loose: Sequence[int], tau=0.7, alpha=0.65,
+                ema_decay=0.9, sm_scale=None, w_entropy=0.4, w_margin=0.3, w_top=0.3):
+    """A ConfKVConfig plus the two int32 arrays it points to (keep the tuple alive)."""
+    nt = (C.c_int32 * len(n_tight))(*[int(x) for x in n_tight])
+    nl = (C.c_int32 * len(n_loose))(*[int(x) for x in n_loose])
+    if sm_scale is None:
+        sm_scale = 1.0 / float(np.sqrt(head_dim))
+    cfg = ConfKVConfig(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacity,
+                       fp16_window, protected_window, tau, alpha, ema_decay, sm_scale,
+                       w_entropy, w_margin, w_top, nt, nl)
+    return cfg, nt, nl
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class ConfKV:
+    """One cache manager instance on the current CUDA/HIP device (torch owns the memory)."""
+
+    def __init__(self, **kw):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("ConfKV needs a GPU: the decode path has no CPU implementation")
+        self._torch = torch
+        self.lib = load_library()
+        self.cfg, self._nt, self._nl = make_config(**kw)
+        sb = self.lib.conf_kv_state_bytes(C.byref(self.cfg))
+        kb = self.lib.conf_kv_scratch_bytes(C.byref(self.cfg))
+        if sb == 0:
+            raise ConfKVError(ERR_BAD_SHAPE, "conf_kv_state_bytes")
+        self.state = torch.empty(sb, dtype=torch.uint8, device="cuda")
+        self.scratch = torch.empty(kb, dtype=torch.uint8, device="cuda")
+        h = _P()
+        self._check(self.lib.conf_kv_create(C.byref(h), C.byref(self.cfg), self.state.data_ptr(),
+                                            self.scratch.data_ptr()), "conf_kv_create")
+        self.h = h
+
+    # -- plumbing --
+    def _check(self, status: int, what: str) -> int:
+        if status < 0:
+            raise ConfKVError(status, what)
+        return status
+
+    def _stream(self):
+        return self._torch.cuda.current_stream().cuda_stream
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.conf_kv_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the C ABI, same names --
+    def load_prefill(self, layer: int, k16, v16, ema0=None):
+        T0 = int(k16.shape[2])
+        return self._check(self.lib.conf_kv_load_prefill(self.h, layer, _ptr(k16), _ptr(v16), T0,
+                                                         _ptr(ema0), self._stream()), "conf_kv_load_prefill")
+
+    def attend(self, layer: int, q16, knew16, vnew16, out16):
+        return self._check(self.lib.conf_kv_attend(self.h, layer, _ptr(q16), _ptr(knew16), _ptr(vnew16),
+                                                   _ptr(out16), self._stream()), "conf_kv_attend")
+
+    def step(self, logits, conf=None, sel=None):
+        return self._check(self.lib.conf_kv_step(self.h, _ptr(logits), _ptr(conf), _ptr(sel),
+                                                 self._stream()), "conf_kv_step")
+
+    def evict_compact(self):
+        return self._check(self.lib.conf_kv_evict_compact(self.h, self._stream()), "conf_kv_evict_compact")
+
+    def lengths(self):
+        c = self.cfg
+        ln = np.zeros((c.n_layers, c.batch), dtype=np.int32)
+        n16 = np.zeros((c.n_layers, c.batch, c.n_kv_heads), dtype=np.int32)
+        self._check(self.lib.conf_kv_lengths(self.h, ln.ctypes.data, n16.ctypes.data), "conf_kv_lengths")
+        return ln, n16
+
+    def export(self, layer: int, b: int, kv_head: int):
+        c = self.cfg
+        cap, D = c.capacity, c.head_dim
+        pos = np.zeros(cap, np.int32); ema = np.zeros(cap, np.float32); is16 = np.zeros(cap, np.uint8)
+        k16 = np.zeros((cap, D), np.uint16); v16 = np.zeros((cap, D), np.uint16)
+        k8 = np.zeros((cap, D), np.int8); v8 = np.zeros((cap, D), np.int8)
+        ks = np.zeros(cap, np.uint16); vs = np.zeros(cap, np.uint16)
+        n = C.c_int32(0)
+        self._check(self.lib.conf_kv_export(self.h, layer, b, kv_head, pos.ctypes.data, ema.ctypes.data,
+                                            is16.ctypes.data, k16.ctypes.data, v16.ctypes.data,
+                                            k8.ctypes.data, v8.ctypes.data, ks.ctypes.data, vs.ctypes.data,
+                                            C.addressof(n)), "conf_kv_export")
+        m = n.value
+        return dict(n=m, pos=pos[:m], ema=ema[:m], is16=is16[:m].astype(bool),
+                    k16=k16[:m].view(np.float16), v16=v16[:m].view(np.float16), k8=k8[:m], v8=v8[:m],
+                    ks=ks[:m].view(np.float16), vs=vs[:m].view(np.float16))
+
+    def counters(self, check: bool = True) -> ConfKVStats:
+        st = ConfKVStats()
+        rc = self.lib.conf_kv_counters(self.h, C.byref(st))
+        if check:
+            self._check(rc, "conf_kv_counters")
+        return st
+
+    def attend_splits(self, layer: int) -> int:
+        return self._check(self.lib.conf_kv_attend_splits(self.h, layer), "conf_kv_attend_splits")
+
+
+def from_workload(wl, **override) -> ConfKV:
+    """A ConfKV shaped like a ``synth.workloads.Workload`` (duck-typed; no import of synth)."""
+    kw = dict(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+              head_dim=wl.head_dim, vocab=wl.vocab, capacity=wl.capacity, fp16_window=wl.fp16_window,
+              protected_window=wl.protected, n_tight=wl.n_tight, n_loose=wl.n_loose, tau=wl.tau,
+              alpha=wl.alpha, ema_decay=wl.ema_decay, w_entropy=wl.w_entropy, w_margin=wl.w_margin,
+              w_top=wl.w_top)
+    kw.update(override)
+    return ConfKV(**kw)

@@ -1,0 +1,419 @@
+// Host side of the C ABI declared in include/conf_kv.h: argument validation, the layout of
+// the caller's device buffers, per-layer host bookkeeping (upper bounds of the lengths,
+// next position, pending appends, arrival-counter bases) and kernel launches.
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "conf_kv.h"
+#include "confkv_dev.h"
+#include "launch.h"
+
+using namespace confkv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct StateLayout {
+  size_t len, n8, head16, budget, n_tight, n_loose, stats, ema, pos, ks, vs, k8, v8, k16, v16, total;
+  size_t header_bytes;   // [0, header_bytes) is zeroed at create
+  int cap8, cap16;
+};
+
+struct ScratchLayout {
+  size_t conf_partial, conf_arrive, arrive_ml, arrive_o, part_ml, part_o, score, src, sel, total;
+  size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
+};
+
+bool config_ok(const conf_kv_config *c) {
+  if (!c || !c->n_tight || !c->n_loose) return false;
+  if (c->n_layers < 1 || c->n_layers > kMaxLayers || c->batch < 1) return false;
+  if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads) return false;
+  if (!attend_supported(c->head_dim, c->n_q_heads / c->n_kv_heads)) return false;
+  if (c->vocab < 2) return false;
+  if (c->capacity < 16 || c->capacity % 16) return false;
+  if (c->protected_window < 0) return false;
+  if (!(c->alpha >= 0.f && c->alpha <= 1.f)) return false;
+  if (!(c->ema_decay >= 0.f && c->ema_decay <= 1.f)) return false;
+  if (!(c->sm_scale > 0.f)) return false;
+  for (int l = 0; l < c->n_layers; ++l) {
+    if (c->n_tight[l] < 1 || c->n_tight[l] > c->n_loose[l]) return false;
+    if (std::max(c->n_loose[l], c->protected_window) + 1 > c->capacity) return false;
+  }
+  return true;
+}
+
+StateLayout state_layout(const conf_kv_config *c) {
+  StateLayout s{};
+  const size_t U = (size_t)c->n_layers * c->batch * c->n_kv_heads;
+  const size_t cap = c->capacity, D = c->head_dim;
+  s.cap8 = c->fp16_window < 0 ? 0 : c->capacity;
+  if (c->fp16_window < 0) {
+    s.cap16 = c->capacity;
+  } else {
+    long long want = ((long long)c->fp16_window + 1 + 15) / 16 * 16;
+    s.cap16 = (int)std::min<long long>(want, c->capacity);
+  }
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  s.len = take(U * 4);
+  s.n8 = take(U * 4);
+  s.head16 = take(U * 4);
+  s.stats = take(kStatSlots * 8);
+  s.header_bytes = off;
+  s.budget = take((size_t)c->n_layers * c->batch * 4);
+  s.n_tight = take((size_t)c->n_layers * 4);
+  s.n_loose = take((size_t)c->n_layers * 4);
+  s.ema = take(U * cap * 4);
+  s.pos = take(U * cap * 4);
+  s.ks = take(U * s.cap8 * 2);
+  s.vs = take(U * s.cap8 * 2);
+  s.k8 = take(U * s.cap8 * D);
+  s.v8 = take(U * s.cap8 * D);
+  s.k16 = take(U * s.cap16 * D * 2);
+  s.v16 = take(U * s.cap16 * D * 2);
+  s.total = off;
+  return s;
+}
+
+ScratchLayout scratch_layout(const conf_kv_config *c) {
+  ScratchLayout s{};
+  const size_t UPL = (size_t)c->batch * c->n_kv_heads, U = UPL * c->n_layers;
+  const size_t G = c->n_q_heads / c->n_kv_heads, D = c->head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  s.conf_arrive = take((size_t)c->batch * 4);
+  s.arrive_ml = take(U * 4);
+  s.arrive_o = take(U * 4);
+  s.zero_bytes = off;
+  s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
+  s.part_ml = take(UPL * kAttendMaxSplits * G * 2 * 4);
+  s.part_o = take(UPL * kAttendMaxSplits * G * D * 4);
+  s.score = take(U * c->capacity * 8);
+  s.src = take(U * c->capacity * 4);
+  s.sel = take(U * kSelInts * 4);
+  s.total = off;
+  return s;
+}
+
+}  // namespace
+
+struct conf_kv_handle {
+  conf_kv_config cfg;
+  std::vector<int32_t> n_tight, n_loose;
+  StateLayout sl;
+  ScratchLayout kl;
+  uint8_t *state = nullptr;
+  uint8_t *scratch = nullptr;
+  CacheView cv{};
+  // per layer
+  std::vector<int32_t> len_ub;       // upper bound of the committed length
+  std::vector<int32_t> next_pos;     // position the next appended token gets
+  std::vector<uint8_t> appended;     // an append awaits its commit
+  std::vector<uint32_t> arrive_base; // value of the layer's arrival counters
+  int forced_splits = 0;
+  int last_hip = 0;
+};
+
+#define CK_HIP(h, expr)                         \
+  do {                                          \
+    hipError_t e_ = (expr);                     \
+    if (e_ != hipSuccess) {                     \
+      if (h) (h)->last_hip = (int)e_;           \
+      return CONF_KV_ERR_HIP;                   \
+    }                                           \
+  } while (0)
+
+extern "C" {
+
+size_t conf_kv_state_bytes(const conf_kv_config *cfg) {
+  return config_ok(cfg) ? state_layout(cfg).total : 0;
+}
+
+size_t conf_kv_scratch_bytes(const conf_kv_config *cfg) {
+  return config_ok(cfg) ? scratch_layout(cfg).total : 0;
+}
+
+int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_state,
+                   void *dev_scratch) {
+  if (!out) return CONF_KV_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!cfg || !dev_state || !dev_scratch || !cfg->n_tight || !cfg->n_loose)
+    return CONF_KV_ERR_INVALID_ARG;
+  if (((uintptr_t)dev_state % kAlign) || ((uintptr_t)dev_scratch % kAlign))
+    return CONF_KV_ERR_INVALID_ARG;
+  if (!config_ok(cfg)) return CONF_KV_ERR_BAD_SHAPE;
+  conf_kv_handle *h = new (std::nothrow) conf_kv_handle();
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  h->cfg = *cfg;
+  h->n_tight.assign(cfg->n_tight, cfg->n_tight + cfg->n_layers);
+  h->n_loose.assign(cfg->n_loose, cfg->n_loose + cfg->n_layers);
+  h->cfg.n_tight = h->n_tight.data();
+  h->cfg.n_loose = h->n_loose.data();
+  h->sl = state_layout(&h->cfg);
+  h->kl = scratch_layout(&h->cfg);
+  h->state = (uint8_t *)dev_state;
+  h->scratch = (uint8_t *)dev_scratch;
+  const int L = cfg->n_layers;
+  h->len_ub.assign(L, 0);
+  h->next_pos.assign(L, 0);
+  h->appended.assign(L, 0);
+  h->arrive_base.assign(L, 0u);
+  if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
+
+  CacheView &cv = h->cv;
+  uint8_t *s = h->state;
+  cv.k8 = (int8_t *)(s + h->sl.k8);
+  cv.v8 = (int8_t *)(s + h->sl.v8);
+  cv.ks = (__half *)(s + h->sl.ks);
+  cv.vs = (__half *)(s + h->sl.vs);
+  cv.k16 = (__half *)(s + h->sl.k16);
+  cv.v16 = (__half *)(s + h->sl.v16);
+  cv.ema = (float *)(s + h->sl.ema);
+  cv.pos = (int32_t *)(s + h->sl.pos);
+  cv.len = (int32_t *)(s + h->sl.len);
+  cv.n8 = (int32_t *)(s + h->sl.n8);
+  cv.head16 = (int32_t *)(s + h->sl.head16);
+  cv.budget = (int32_t *)(s + h->sl.budget);
+  cv.n_tight = (const int32_t *)(s + h->sl.n_tight);
+  cv.n_loose = (const int32_t *)(s + h->sl.n_loose);
+  cv.stats = (unsigned long long *)(s + h->sl.stats);
+  cv.L = L;
+  cv.B = cfg->batch;
+  cv.Hkv = cfg->n_kv_heads;
+  cv.G = cfg->n_q_heads / cfg->n_kv_heads;
+  cv.D = cfg->head_dim;
+  cv.cap = cfg->capacity;
+  cv.cap8 = h->sl.cap8;
+  cv.cap16 = h->sl.cap16;
+  cv.W = cfg->fp16_window;
+  cv.P = cfg->protected_window;
+
+  std::vector<int32_t> budget((size_t)L * cfg->batch);
+  for (int l = 0; l < L; ++l)
+    for (int b = 0; b < cfg->batch; ++b) budget[(size_t)l * cfg->batch + b] = h->n_loose[l];
+  hipError_t e = hipMemset(h->state, 0, h->sl.header_bytes);
+  if (e == hipSuccess) e = hipMemset(h->scratch, 0, h->kl.zero_bytes);
+  if (e == hipSuccess) e = hipMemcpy(cv.budget, budget.data(), budget.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy((void *)cv.n_tight, h->n_tight.data(), (size_t)L * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy((void *)cv.n_loose, h->n_loose.data(), (size_t)L * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    delete h;
+    return CONF_KV_ERR_HIP;
+  }
+  *out = h;
+  return CONF_KV_OK;
+}
+
+int conf_kv_destroy(conf_kv_handle *h) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  delete h;
+  return CONF_KV_OK;
+}
+
+int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, const void *dev_v16,
+                         int32_t T0, const float *dev_ema0, conf_kv_stream stream) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  if (T0 < 0) return CONF_KV_ERR_INVALID_ARG;
+  if (T0 > 0 && (!dev_k16 || !dev_v16)) return CONF_KV_ERR_INVALID_ARG;
+  if (T0 > h->cfg.capacity - 1) return CONF_KV_ERR_CAPACITY;
+  CK_HIP(h, launch_load_prefill(h->cv, layer, (const __half *)dev_k16, (const __half *)dev_v16, T0,
+                                dev_ema0, (hipStream_t)stream));
+  h->len_ub[layer] = T0;
+  h->next_pos[layer] = T0;
+  h->appended[layer] = 0;
+  return CONF_KV_OK;
+}
+
+static int plan_for_layer(conf_kv_handle *h, int layer, AttendPlan *plan) {
+  const int n_ub = h->len_ub[layer] + 1;
+  const int W = h->cfg.fp16_window;
+  const int n16_ub = W < 0 ? n_ub : std::min(n_ub, W + 1);
+  if (!attend_plan(h->cfg.head_dim, h->cv.G, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
+                   h->forced_splits, plan))
+    return CONF_KV_ERR_BAD_SHAPE;
+  return CONF_KV_OK;
+}
+
+int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const void *dev_knew16,
+                   const void *dev_vnew16, void *dev_out16, conf_kv_stream stream) {
+  if (!h || !dev_q16 || !dev_knew16 || !dev_vnew16 || !dev_out16) return CONF_KV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  if (((uintptr_t)dev_q16 | (uintptr_t)dev_knew16 | (uintptr_t)dev_vnew16 | (uintptr_t)dev_out16) & 15)
+    return CONF_KV_ERR_INVALID_ARG;
+  if (h->appended[layer]) return CONF_KV_ERR_BAD_STATE;
+  if (h->len_ub[layer] + 1 > h->cfg.capacity) return CONF_KV_ERR_CAPACITY;
+  AttendPlan plan;
+  int rc = plan_for_layer(h, layer, &plan);
+  if (rc != CONF_KV_OK) return rc;
+  const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
+  AttendLaunch a{};
+  a.layer = layer;
+  a.q = (const __half *)dev_q16;
+  a.knew = (const __half *)dev_knew16;
+  a.vnew = (const __half *)dev_vnew16;
+  a.out = (__half *)dev_out16;
+  a.part_ml = (float *)(h->scratch + h->kl.part_ml);
+  a.part_o = (float *)(h->scratch + h->kl.part_o);
+  a.arrive_ml = (unsigned *)(h->scratch + h->kl.arrive_ml) + (size_t)layer * UPL;
+  a.arrive_o = (unsigned *)(h->scratch + h->kl.arrive_o) + (size_t)layer * UPL;
+  a.arrive_base = h->arrive_base[layer];
+  a.max_splits = kAttendMaxSplits;
+  a.sm_scale = h->cfg.sm_scale;
+  a.ema_decay = h->cfg.ema_decay;
+  a.pos_new = h->next_pos[layer];
+  CK_HIP(h, launch_attend(h->cv, a, plan, (hipStream_t)stream));
+  h->arrive_base[layer] += (uint32_t)plan.splits;
+  h->appended[layer] = 1;
+  return CONF_KV_OK;
+}
+
+int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  AttendPlan plan;
+  int rc = plan_for_layer(h, layer, &plan);
+  return rc != CONF_KV_OK ? rc : plan.splits;
+}
+
+int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
+                 conf_kv_stream stream) {
+  if (!h || !dev_logits) return CONF_KV_ERR_INVALID_ARG;
+  CK_HIP(h, launch_conf_reduce(h->cv, dev_logits, h->cfg.vocab,
+                               (float *)(h->scratch + h->kl.conf_partial),
+                               (unsigned *)(h->scratch + h->kl.conf_arrive), dev_conf, dev_sel,
+                               (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
+                               (double)h->cfg.w_top, (hipStream_t)stream));
+  return CONF_KV_OK;
+}
+
+int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  LayerMask m{};
+  for (int l = 0; l < h->cfg.n_layers; ++l)
+    if (h->appended[l]) m.set(l);
+  CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, (double *)(h->scratch + h->kl.score),
+                                 (int32_t *)(h->scratch + h->kl.src),
+                                 (int32_t *)(h->scratch + h->kl.sel), (hipStream_t)stream));
+  const int P = h->cfg.protected_window;
+  for (int l = 0; l < h->cfg.n_layers; ++l) {
+    if (h->appended[l]) {
+      h->len_ub[l] += 1;
+      h->next_pos[l] += 1;
+      h->appended[l] = 0;
+    }
+    // any budget the step may have chosen is at most the loose one
+    const int n = h->len_ub[l], NL = h->n_loose[l];
+    if (n > NL) h->len_ub[l] = std::max(NL, std::min(P, n));
+  }
+  return CONF_KV_OK;
+}
+
+int conf_kv_lengths(conf_kv_handle *h, int32_t *host_len, int32_t *host_n16) {
+  if (!h || !host_len) return CONF_KV_ERR_INVALID_ARG;
+  const int L = h->cfg.n_layers, B = h->cfg.batch, H = h->cfg.n_kv_heads;
+  const size_t U = (size_t)L * B * H;
+  std::vector<int32_t> len(U), n8(U);
+  CK_HIP(h, hipDeviceSynchronize());
+  CK_HIP(h, hipMemcpy(len.data(), h->cv.len, U * 4, hipMemcpyDeviceToHost));
+  CK_HIP(h, hipMemcpy(n8.data(), h->cv.n8, U * 4, hipMemcpyDeviceToHost));
+  for (int l = 0; l < L; ++l)
+    for (int b = 0; b < B; ++b) {
+      const size_t u0 = ((size_t)l * B + b) * H;
+      host_len[(size_t)l * B + b] = len[u0] + h->appended[l];
+      if (host_n16)
+        for (int g = 0; g < H; ++g) host_n16[u0 + g] = len[u0 + g] + h->appended[l] - n8[u0 + g];
+    }
+  return CONF_KV_OK;
+}
+
+int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head, int32_t *pos,
+                   float *ema, uint8_t *is_fp16, uint16_t *k16, uint16_t *v16, int8_t *k8, int8_t *v8,
+                   uint16_t *k_scale, uint16_t *v_scale, int32_t *n_out) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  if (b < 0 || b >= h->cfg.batch || kv_head < 0 || kv_head >= h->cfg.n_kv_heads)
+    return CONF_KV_ERR_INVALID_ARG;
+  const CacheView &cv = h->cv;
+  const size_t u = ((size_t)layer * cv.B + b) * cv.Hkv + kv_head;
+  const size_t D = cv.D;
+  CK_HIP(h, hipDeviceSynchronize());
+  int32_t len = 0, n8 = 0, head = 0;
+  CK_HIP(h, hipMemcpy(&len, cv.len + u, 4, hipMemcpyDeviceToHost));
+  CK_HIP(h, hipMemcpy(&n8, cv.n8 + u, 4, hipMemcpyDeviceToHost));
+  CK_HIP(h, hipMemcpy(&head, cv.head16 + u, 4, hipMemcpyDeviceToHost));
+  const int n = len + h->appended[layer];
+  const int n16 = n - n8;
+  if (n_out) *n_out = n;
+  if (n == 0) return CONF_KV_OK;
+  if (pos) CK_HIP(h, hipMemcpy(pos, cv.pos + u * cv.cap, (size_t)n * 4, hipMemcpyDeviceToHost));
+  if (ema) CK_HIP(h, hipMemcpy(ema, cv.ema + u * cv.cap, (size_t)n * 4, hipMemcpyDeviceToHost));
+  if (is_fp16)
+    for (int i = 0; i < n; ++i) is_fp16[i] = i >= n8;
+  for (int which = 0; which < 2; ++which) {
+    uint16_t *d16 = which ? v16 : k16;
+    int8_t *d8 = which ? v8 : k8;
+    uint16_t *dsc = which ? v_scale : k_scale;
+    const __half *p16 = (which ? cv.v16 : cv.k16) + u * cv.cap16 * D;
+    const int8_t *p8 = (which ? cv.v8 : cv.k8) + u * cv.cap8 * D;
+    const __half *psc = (which ? cv.vs : cv.ks) + u * cv.cap8;
+    if (d16) {
+      memset(d16, 0, (size_t)n8 * D * 2);
+      if (n16 > 0) {
+        const int first = std::min(n16, cv.cap16 - head);
+        CK_HIP(h, hipMemcpy(d16 + (size_t)n8 * D, p16 + (size_t)head * D, (size_t)first * D * 2,
+                            hipMemcpyDeviceToHost));
+        if (n16 > first)
+          CK_HIP(h, hipMemcpy(d16 + (size_t)(n8 + first) * D, p16, (size_t)(n16 - first) * D * 2,
+                              hipMemcpyDeviceToHost));
+      }
+    }
+    if (d8) {
+      if (n8 > 0) CK_HIP(h, hipMemcpy(d8, p8, (size_t)n8 * D, hipMemcpyDeviceToHost));
+      memset(d8 + (size_t)n8 * D, 0, (size_t)n16 * D);
+    }
+    if (dsc) {
+      if (n8 > 0) CK_HIP(h, hipMemcpy(dsc, psc, (size_t)n8 * 2, hipMemcpyDeviceToHost));
+      memset(dsc + n8, 0, (size_t)n16 * 2);
+    }
+  }
+  return CONF_KV_OK;
+}
+
+int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *st) {
+  if (!h || !st) return CONF_KV_ERR_INVALID_ARG;
+  unsigned long long raw[kStatSlots];
+  CK_HIP(h, hipDeviceSynchronize());
+  CK_HIP(h, hipMemcpy(raw, h->cv.stats, sizeof(raw), hipMemcpyDeviceToHost));
+  st->evicted = raw[kStatEvicted];
+  st->demoted = raw[kStatDemoted];
+  st->tight_steps = raw[kStatTight];
+  st->loose_steps = raw[kStatLoose];
+  st->device_errors = raw[kStatDeviceErr];
+  return raw[kStatDeviceErr] ? CONF_KV_ERR_DEVICE : CONF_KV_OK;
+}
+
+const char *conf_kv_strerror(int status) {
+  switch (status) {
+    case CONF_KV_OK: return "ok";
+    case CONF_KV_ERR_INVALID_ARG: return "invalid argument (null pointer, negative size or misaligned buffer)";
+    case CONF_KV_ERR_BAD_SHAPE: return "configuration outside what the kernels support";
+    case CONF_KV_ERR_BAD_LAYER: return "layer index out of range";
+    case CONF_KV_ERR_CAPACITY: return "cache capacity exceeded";
+    case CONF_KV_ERR_BAD_STATE: return "call order violated (one conf_kv_attend per layer between conf_kv_evict_compact calls)";
+    case CONF_KV_ERR_HIP: return "a HIP call failed (see conf_kv_last_hip_error)";
+    case CONF_KV_ERR_DEVICE: return "a kernel reported an internal error";
+    default: return "unknown status";
+  }
+}
+
+int conf_kv_last_hip_error(conf_kv_handle *h) { return h ? h->last_hip : 0; }
+
+}  // extern "C"

@@ -1,0 +1,519 @@
+// Decode attention over the mixed INT8 / FP16 cache with the attention-mass EMA fused in
+// (paper: "Tiled attention and mixed precision" -- blockwise read, running max and
+// normaliser, dequantisation fused into the read; "Budget and ranker" -- EMA of attention
+// mass; Algorithm 1 -- append in FP16, update EMA metadata).
+//
+// One launch per layer, grid (splits, B * Hkv), 256 threads.  The `splits` workgroups of a
+// unit (b, kv-head) each stream a contiguous, byte-balanced slice of the unit's slots and
+// serve all G query heads of the group from that single read:
+//
+//   K pass   raw scores s[h][i] of the slice -> LDS; slice maximum m[h]
+//   publish  p[h][i] = exp(s - m[h]) kept in LDS, l[h] = sum p; (m, l) -> global, arrive
+//   V pass   o[h][:] = sum_i p[h][i] * V_i (un-normalised) -> global, arrive; the last
+//            workgroup to arrive merges the splits' (m, l, o) into out (online-softmax merge)
+//   mass     wait until every split of the unit has published (m, l) (they did so before
+//            their own V pass, so the wait is normally over already), form the exact
+//            global (M, L), then per slot A_i = sum_h p[h][i] e^{m[h]-M[h]} / L[h] and
+//            ema_i <- lambda ema_i + (1 - lambda) A_i.
+//
+// Every K/V byte is read once; the scores never leave the chip.  The wait is between
+// workgroups of one launch, so the host only launches grids that are co-resident
+// (splits * units <= occupancy * CUs) and the wait itself is bounded.
+//
+// Lane mapping: a slot's row is D channels; lane c of a group of D/16 lanes owns channels
+// [16c, 16c+16) -- one 128-bit load of an INT8 row, two of an FP16 row -- so a wavefront
+// load instruction covers 64/(D/16) whole rows, contiguous in memory.
+#include <algorithm>
+#include <map>
+#include <tuple>
+
+#include "confkv_dev.h"
+#include "launch.h"
+
+namespace confkv {
+
+constexpr int kAttThreads = 256;
+constexpr int kAttWaves = 4;
+constexpr int kUnroll = 4;
+constexpr int kSpinLimit = 4000000;
+
+__device__ __forceinline__ void unpack_i8x16(const int4 &r, float (&f)[16]) {
+  const int wds[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[4 * k + e] = (float)((wds[k] << (24 - 8 * e)) >> 24);
+  }
+}
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, float (&f)[16]) {
+  half8_t a = __builtin_bit_cast(half8_t, r0), b = __builtin_bit_cast(half8_t, r1);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { f[e] = (float)a[e]; f[8 + e] = (float)b[e]; }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
+                                                             int S) {
+  constexpr int LPT = D / 16;            // lanes per slot row
+  constexpr int TW = kWave / LPT;        // slots per wavefront pass
+  constexpr int TB = kAttWaves * TW;     // slots per workgroup pass
+  extern __shared__ float smem[];
+  float *stash = smem;                   // [G][S] scores, then probabilities
+  float *red = stash + (size_t)G * S;    // [4][G][D] cross-wave reduction of o
+  float *wred = red + kAttWaves * G * D; // [4][G] per-wave max / sum
+  double *fac = (double *)(wred + kAttWaves * G + (((kAttWaves * G) & 1) ? 1 : 0));  // [G]
+  __shared__ int s_last, s_ok;
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = lane % LPT, ts = lane / LPT;
+  const int ul = blockIdx.y, j = blockIdx.x;
+  const int UPL = cv.B * cv.Hkv;
+  const int u = a.layer * UPL + ul;
+  const int b = ul / cv.Hkv, g = ul % cv.Hkv;
+  const int cap = cv.cap, cap8 = cv.cap8, cap16 = cv.cap16;
+  const int n8 = cv.n8[u];
+  const int n = cv.len[u] + 1;           // the appended token included
+  const int h16 = cv.head16[u];
+  const int n16 = n - n8;
+  const float NEG = -INFINITY;
+
+  // byte-balanced split: an FP16 slot weighs two INT8 slots
+  const long long nv = (long long)n8 + 2ll * n16;
+  const long long vlo = nv * j / ns, vhi = nv * (j + 1) / ns;
+  // (rounding down keeps the tail slice non-empty, so its owner always holds slot n-1)
+  int lo = vlo <= n8 ? (int)vlo : n8 + (int)((vlo - n8) >> 1);
+  int hi = vhi <= n8 ? (int)vhi : n8 + (int)((vhi - n8) >> 1);
+  if (hi - lo > S) {                     // cannot happen when the host plan is right
+    if (tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+    hi = lo + S;
+  }
+  const int ntok = hi - lo;
+
+  const int8_t *K8 = cv.k8 + (size_t)u * cap8 * D;
+  const int8_t *V8 = cv.v8 + (size_t)u * cap8 * D;
+  const __half *KS = cv.ks + (size_t)u * cap8;
+  const __half *VS = cv.vs + (size_t)u * cap8;
+  __half *K16 = cv.k16 + (size_t)u * cap16 * D;
+  __half *V16 = cv.v16 + (size_t)u * cap16 * D;
+  float *EMA = cv.ema + (size_t)u * cap;
+
+  // ---- append: the workgroup that owns the tail writes the new token into the ring ----
+  if (j == ns - 1) {
+    const int row = ring_row(h16, n16 - 1, cap16);
+    if (tid < D / 8) {
+      const int4 *src = (const int4 *)(a.knew + (size_t)ul * D);
+      ((int4 *)(K16 + (size_t)row * D))[tid] = src[tid];
+    } else if (tid < D / 4) {
+      const int t = tid - D / 8;
+      const int4 *src = (const int4 *)(a.vnew + (size_t)ul * D);
+      ((int4 *)(V16 + (size_t)row * D))[t] = src[t];
+    }
+    if (tid == 0) cv.pos[(size_t)u * cap + n - 1] = a.pos_new;
+    __syncthreads();
+  }
+
+  const int hi8 = min(hi, n8), lo16 = max(lo, n8);
+  const float sm = a.sm_scale;
+
+  // ================= K pass: scores of the slice =================
+  float mx[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) mx[h] = NEG;
+  {
+    float qf[G][16];
+    const int Hq = cv.Hkv * G;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const int4 *qp = (const int4 *)(a.q + ((size_t)(b * Hq + g * G + h)) * D + c * 16);
+      unpack_h16x16(qp[0], qp[1], qf[h]);
+    }
+    // INT8 slots
+    for (int base = lo; base < hi8; base += TB * kUnroll) {
+      int4 kr[kUnroll];
+      float sc[kUnroll];
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        kr[r] = make_int4(0, 0, 0, 0);
+        sc[r] = 0.f;
+        if (i < hi8) {
+          kr[r] = *(const int4 *)(K8 + (size_t)i * D + c * 16);
+          sc[r] = __half2float(KS[i]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        float kf[16], part[G];
+        unpack_i8x16(kr[r], kf);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          float acc = 0.f;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc = fmaf(qf[h][e], kf[e], acc);
+          part[h] = acc;
+        }
+#pragma unroll
+        for (int m = 1; m < LPT; m <<= 1) {
+#pragma unroll
+          for (int h = 0; h < G; ++h) part[h] += __shfl_xor(part[h], m, kWave);
+        }
+        if (i < hi8) {
+          const float f = sc[r] * sm;
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            const float s = part[h] * f;
+            mx[h] = fmaxf(mx[h], s);
+            if (c == 0) stash[h * S + (i - lo)] = s;
+          }
+        }
+      }
+    }
+    // FP16 slots (ring)
+    for (int base = lo16; base < hi; base += TB * kUnroll) {
+      int4 kr[kUnroll][2];
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        kr[r][0] = kr[r][1] = make_int4(0, 0, 0, 0);
+        if (i < hi) {
+          const int4 *p = (const int4 *)(K16 + (size_t)ring_row(h16, i - n8, cap16) * D + c * 16);
+          kr[r][0] = p[0];
+          kr[r][1] = p[1];
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        float kf[16], part[G];
+        unpack_h16x16(kr[r][0], kr[r][1], kf);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          float acc = 0.f;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc = fmaf(qf[h][e], kf[e], acc);
+          part[h] = acc;
+        }
+#pragma unroll
+        for (int m = 1; m < LPT; m <<= 1) {
+#pragma unroll
+          for (int h = 0; h < G; ++h) part[h] += __shfl_xor(part[h], m, kWave);
+        }
+        if (i < hi) {
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            const float s = part[h] * sm;
+            mx[h] = fmaxf(mx[h], s);
+            if (c == 0) stash[h * S + (i - lo)] = s;
+          }
+        }
+      }
+    }
+  }
+  // slice maximum per head
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    mx[h] = wave_max(mx[h]);
+    if (lane == 0) wred[w * G + h] = mx[h];
+  }
+  __syncthreads();
+  float mloc[G], lloc[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    mloc[h] = fmaxf(fmaxf(wred[h], wred[G + h]), fmaxf(wred[2 * G + h], wred[3 * G + h]));
+    lloc[h] = 0.f;
+  }
+  // probabilities relative to the slice maximum, and the slice normaliser
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    for (int t = tid; t < ntok; t += kAttThreads) {
+      const float p = expf(stash[h * S + t] - mloc[h]);
+      stash[h * S + t] = p;
+      lloc[h] += p;
+    }
+    lloc[h] = wave_sum(lloc[h]);
+  }
+  __syncthreads();                        // wred (max) fully read, stash rewritten
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+    if (lane == 0) wred[w * G + h] = lloc[h];
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < G; ++h) lloc[h] = (wred[h] + wred[G + h]) + (wred[2 * G + h] + wred[3 * G + h]);
+
+  float *ml = a.part_ml + ((size_t)ul * a.max_splits + j) * G * 2;
+  if (tid < G) {
+    ml[tid * 2 + 0] = mloc[tid];
+    ml[tid * 2 + 1] = lloc[tid];
+    __threadfence();
+  }
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    atomicAdd(&a.arrive_ml[ul], 1u);
+  }
+
+  // ================= V pass: un-normalised output of the slice =================
+  {
+    float acc[G][16];
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[h][e] = 0.f;
+
+    for (int base = lo; base < hi8; base += TB * kUnroll) {
+      int4 vr[kUnroll];
+      float sc[kUnroll];
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        vr[r] = make_int4(0, 0, 0, 0);
+        sc[r] = 0.f;
+        if (i < hi8) {
+          vr[r] = *(const int4 *)(V8 + (size_t)i * D + c * 16);
+          sc[r] = __half2float(VS[i]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        if (i < hi8) {
+          float vf[16];
+          unpack_i8x16(vr[r], vf);
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            const float p = stash[h * S + (i - lo)] * sc[r];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
+          }
+        }
+      }
+    }
+    for (int base = lo16; base < hi; base += TB * kUnroll) {
+      int4 vr[kUnroll][2];
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        vr[r][0] = vr[r][1] = make_int4(0, 0, 0, 0);
+        if (i < hi) {
+          const int4 *p = (const int4 *)(V16 + (size_t)ring_row(h16, i - n8, cap16) * D + c * 16);
+          vr[r][0] = p[0];
+          vr[r][1] = p[1];
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const int i = base + r * TB + w * TW + ts;
+        if (i < hi) {
+          float vf[16];
+          unpack_h16x16(vr[r][0], vr[r][1], vf);
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            const float p = stash[h * S + (i - lo)];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
+          }
+        }
+      }
+    }
+    // sum over the slot lanes of the wavefront, then over the four wavefronts
+#pragma unroll
+    for (int m = LPT; m < kWave; m <<= 1) {
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[h][e] += __shfl_xor(acc[h][e], m, kWave);
+    }
+    if (ts == 0) {
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[(w * G + h) * D + c * 16 + e] = acc[h][e];
+    }
+  }
+  __syncthreads();
+  float *po = a.part_o + ((size_t)ul * a.max_splits + j) * G * D;
+  for (int idx = tid; idx < G * D; idx += kAttThreads) {
+    po[idx] = (red[idx] + red[G * D + idx]) + (red[2 * G * D + idx] + red[3 * G * D + idx]);
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const unsigned ticket = atomicAdd(&a.arrive_o[ul], 1u);
+    s_last = (ticket == a.arrive_base + (unsigned)ns - 1u);
+  }
+  __syncthreads();
+  if (s_last) {
+    // ---- last arrival: merge the splits (online-softmax merge) and write out ----
+    __threadfence();
+    const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
+    const float *pou = a.part_o + (size_t)ul * a.max_splits * G * D;
+    const int Hq = cv.Hkv * G;
+    for (int idx = tid; idx < G * D; idx += kAttThreads) {
+      const int h = idx / D;
+      float M = NEG;
+      for (int s = 0; s < ns; ++s) M = fmaxf(M, mlu[(s * G + h) * 2]);
+      float L = 0.f, o = 0.f;
+      for (int s = 0; s < ns; ++s) {
+        const float ms = mlu[(s * G + h) * 2];
+        if (ms > NEG) {
+          const float wgt = expf(ms - M);
+          L += wgt * mlu[(s * G + h) * 2 + 1];
+          o += wgt * pou[(size_t)s * G * D + idx];
+        }
+      }
+      a.out[((size_t)(b * Hq + g * G)) * D + idx] = __float2half_rn(o / L);
+    }
+  }
+
+  // ================= mass + EMA =================
+  if (ns > 1) {
+    if (tid == 0) {
+      const unsigned want = a.arrive_base + (unsigned)ns;
+      int spins = 0, ok = 1;
+      while ((int)(__hip_atomic_load(&a.arrive_ml[ul], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                   want) < 0) {
+        __builtin_amdgcn_s_sleep(8);
+        if (++spins > kSpinLimit) { ok = 0; break; }
+      }
+      if (!ok) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+      s_ok = ok;
+    }
+    __syncthreads();
+    if (!s_ok) return;
+    __threadfence();
+  } else {
+    __syncthreads();
+  }
+  if (tid < G) {
+    const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
+    float M = NEG;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, mlu[(s * G + tid) * 2]);
+    double L = 0.0;
+    for (int s = 0; s < ns; ++s) {
+      const float ms = mlu[(s * G + tid) * 2];
+      if (ms > NEG) L += exp((double)ms - (double)M) * (double)mlu[(s * G + tid) * 2 + 1];
+    }
+    const float mine = mlu[(j * G + tid) * 2];
+    fac[tid] = (mine > NEG) ? exp((double)mine - (double)M) / L : 0.0;
+  }
+  __syncthreads();
+  const double lam = (double)a.ema_decay, oml = 1.0 - lam;
+  for (int t = tid; t < ntok; t += kAttThreads) {
+    double A = 0.0;
+#pragma unroll
+    for (int h = 0; h < G; ++h) A += (double)stash[h * S + t] * fac[h];
+    const int slot = lo + t;
+    const double old = (slot == n - 1) ? 0.0 : (double)EMA[slot];
+    EMA[slot] = (float)(lam * old + oml * A);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+
+typedef void (*AttendFn)(CacheView, AttendLaunch, int, int);
+
+static AttendFn attend_fn(int D, int G) {
+#define CONFKV_CASE(d, g) \
+  if (D == d && G == g) return attend_kernel<d, g>;
+  CONFKV_CASE(64, 1) CONFKV_CASE(64, 2) CONFKV_CASE(64, 4) CONFKV_CASE(64, 5) CONFKV_CASE(64, 8)
+  CONFKV_CASE(128, 1) CONFKV_CASE(128, 2) CONFKV_CASE(128, 4) CONFKV_CASE(128, 5) CONFKV_CASE(128, 8)
+#undef CONFKV_CASE
+  return nullptr;
+}
+
+bool attend_supported(int D, int G) { return attend_fn(D, G) != nullptr; }
+
+static size_t attend_lds_bytes(int D, int G, int S) {
+  size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + kAttWaves * G + 1;
+  return floats * sizeof(float) + (size_t)G * sizeof(double) + 16;
+}
+
+struct DeviceLimits {
+  int cus = 0;
+  size_t max_lds = 0;
+  bool ok = false;
+};
+
+static const DeviceLimits &device_limits() {
+  static DeviceLimits lim;
+  if (!lim.ok) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+      lim.cus = prop.multiProcessorCount;
+      lim.max_lds = prop.sharedMemPerBlockOptin ? prop.sharedMemPerBlockOptin
+                                                : prop.sharedMemPerBlock;
+      if (lim.max_lds > 160 * 1024) lim.max_lds = 160 * 1024;
+      lim.ok = lim.cus > 0;
+    }
+  }
+  return lim;
+}
+
+// Resident workgroups per CU of attend_kernel<D,G> with `lds` bytes of dynamic LDS.
+static int attend_occupancy(int D, int G, size_t lds) {
+  static std::map<std::tuple<int, int, size_t>, int> cache;
+  auto key = std::make_tuple(D, G, lds);
+  auto it = cache.find(key);
+  if (it != cache.end()) return it->second;
+  AttendFn fn = attend_fn(D, G);
+  int nb = 0;
+  if (lds > 64 * 1024)
+    (void)hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void *)fn, kAttThreads, lds) !=
+      hipSuccess)
+    nb = 0;
+  cache[key] = nb;
+  return nb;
+}
+
+bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
+                 AttendPlan *plan) {
+  const DeviceLimits &lim = device_limits();
+  if (!lim.ok || !attend_fn(D, G)) return false;
+  const long long nv = (long long)n_ub + n16_ub;
+  // aim for about three workgroups per CU, but keep at least 128 virtual slots per split
+  int want = forced_splits > 0 ? forced_splits : (3 * lim.cus + units_per_layer - 1) / units_per_layer;
+  want = std::min<long long>(want, std::max<long long>(1, nv / 128));
+  want = std::max(1, std::min(want, kAttendMaxSplits));
+  // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
+  // splits shrink the LDS stash when a long unit does not fit otherwise)
+  for (int k = 0; k < kAttendMaxSplits; ++k) {
+    const int ns = k < want ? want - k : k + 1;
+    // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
+    int S = (int)((nv + ns - 1) / ns) + 2;
+    S = (S + 255) / 256 * 256;
+    size_t lds = attend_lds_bytes(D, G, S);
+    if (lds > lim.max_lds) continue;
+    if (ns > 1) {
+      int occ = attend_occupancy(D, G, lds);
+      if ((long long)occ * lim.cus < (long long)ns * units_per_layer) continue;
+    } else if (lds > 64 * 1024) {
+      (void)attend_occupancy(D, G, lds);        // raises the dynamic-LDS limit
+    }
+    plan->splits = ns;
+    plan->stash_tokens = S;
+    plan->lds_bytes = lds;
+    return true;
+  }
+  return false;
+}
+
+hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
+                         hipStream_t stream) {
+  AttendFn fn = attend_fn(cv.D, cv.G);
+  if (!fn) return hipErrorInvalidValue;
+  dim3 grid(plan.splits, cv.B * cv.Hkv);
+  hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
+                     plan.stash_tokens);
+  return hipGetLastError();
+}
+
+}  // namespace confkv

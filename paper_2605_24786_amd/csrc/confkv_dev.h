@@ -1,0 +1,113 @@
+// Device-side view of the cache state and small wavefront / workgroup helpers shared by
+// the kernels of the Conf-KV decode-step library.  gfx950 only: 64-lane wavefronts.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace confkv {
+
+constexpr int kWave = 64;
+constexpr int kMaxLayers = 256;
+
+// Indices into the device statistics block (unsigned long long each).
+enum StatSlot { kStatEvicted = 0, kStatDemoted = 1, kStatTight = 2, kStatLoose = 3,
+                kStatDeviceErr = 4, kStatSlots = 8 };
+
+// All planes of the cache, for every unit u = (layer * B + b) * Hkv + kv_head.
+//   k8, v8   int8  [U][cap8][D]   INT8 rows; slot i < n8[u] lives in row i
+//   ks, vs   fp16  [U][cap8]      per-token scales of those rows
+//   k16, v16 fp16  [U][cap16][D]  FP16 ring; slot i >= n8[u] lives in ring row
+//                                 (head16[u] + i - n8[u]) mod cap16
+//   ema      fp32  [U][cap]       EMA of attention mass, by slot
+//   pos      int32 [U][cap]       original position, by slot (strictly increasing)
+//   len, n8, head16  int32 [U]    committed length, INT8 count, ring head
+//   budget   int32 [L][B]         N selected by the last confidence step
+struct CacheView {
+  int8_t *k8, *v8;
+  __half *ks, *vs;
+  __half *k16, *v16;
+  float *ema;
+  int32_t *pos;
+  int32_t *len, *n8, *head16, *budget;
+  const int32_t *n_tight, *n_loose;
+  unsigned long long *stats;
+  int32_t L, B, Hkv, G, D, cap, cap8, cap16, W, P;
+};
+
+// One bit per layer: did conf_kv_attend append a token since the last commit?
+struct LayerMask {
+  unsigned long long w[kMaxLayers / 64];
+  __host__ __device__ bool get(int l) const { return (w[l >> 6] >> (l & 63)) & 1ull; }
+  __host__ __device__ void set(int l) { w[l >> 6] |= 1ull << (l & 63); }
+};
+
+__device__ __forceinline__ int ring_row(int head, int idx, int cap16) {
+  int r = head + idx;
+  return r >= cap16 ? r - cap16 : r;
+}
+
+// ---- wavefront reductions (all 64 lanes end with the result) ----
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fminf(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_min(int v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = min(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+__device__ __forceinline__ int wave_scan_incl(int v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    int t = __shfl_up(v, d, kWave);
+    if (lane >= d) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix sum over a 256-thread workgroup; *total gets the workgroup sum.
+// `tmp` is 4 ints of LDS.  Contains two barriers; all 256 threads must call it.
+__device__ __forceinline__ int block256_scan_excl(int v, int *tmp, int *total) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+  int inc = wave_scan_incl(v);
+  __syncthreads();                       // tmp may still be read from a previous call
+  if (lane == kWave - 1) tmp[w] = inc;
+  __syncthreads();
+  int off = 0, tot = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    int t = tmp[k];
+    if (k < w) off += t;
+    tot += t;
+  }
+  *total = tot;
+  return off + inc - v;
+}
+
+}  // namespace confkv

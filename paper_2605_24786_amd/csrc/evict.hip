@@ -1,0 +1,378 @@
+// Ranker, top-k eviction, in-place compaction and FP16 -> INT8 demotion, plus the prompt
+// loader (paper: "Budget and ranker" -- composite score of min-max-normalised EMA mass and
+// recency over the non-protected candidates, evict the lowest until the budget holds,
+// always keep the newest P; "Cache manager" -- gather survivors into contiguous storage;
+// "Tiled attention and mixed precision" -- symmetric INT8 with scale max|x|/127 outside
+// the FP16 window; Algorithm 1, per-layer tail).
+//
+// Three launches cover every layer:
+//   rank_select   one workgroup per unit: float64 scores, radix select of the eviction
+//                 cut-off, ordered survivor list
+//   compact       one workgroup per (unit, plane): in-place, order-preserving gather
+//   demote        one wavefront per unit: quantise the FP16 slots that left the window,
+//                 commit the new lengths
+#include "confkv_dev.h"
+#include "launch.h"
+
+namespace confkv {
+
+constexpr int kEvThreads = 256;
+
+// ---------------------------------------------------------------------------------------
+// Quantiser shared by the prompt loader and the demotion kernel.
+// One wavefront quantises one D-vector: scale = fl16(fl32(amax / 127)),
+// code = clamp(rint(x / scale), -127, 127) with IEEE fp32 division and round-half-even.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void quantize_row_wave(const __half *__restrict__ src,
+                                                  int8_t *__restrict__ dst_codes,
+                                                  __half *__restrict__ dst_scale, int lane) {
+  constexpr int EPL = D / kWave;                 // elements per lane (1 or 2)
+  float x[EPL];
+  float amax = 0.f;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    x[e] = __half2float(src[lane * EPL + e]);
+    amax = fmaxf(amax, fabsf(x[e]));
+  }
+  amax = wave_max(amax);
+  const __half hs = __float2half_rn(__fdiv_rn(amax, 127.0f));
+  const float sf = __half2float(hs);
+  const bool dead = !(sf > 0.f) || isinf(sf);
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    float r = dead ? 0.f : rintf(__fdiv_rn(x[e], sf));
+    r = fminf(fmaxf(r, -127.f), 127.f);
+    dst_codes[lane * EPL + e] = (int8_t)(int)r;
+  }
+  if (lane == 0) *dst_scale = dead ? __float2half_rn(0.f) : hs;
+}
+
+// ---------------------------------------------------------------------------------------
+// Prompt loader: grid (ceil(T0 / 4), B * Hkv), one wavefront per token.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
+    CacheView cv, int layer, const __half *__restrict__ k16, const __half *__restrict__ v16, int T0,
+    const float *__restrict__ ema0) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int ul = blockIdx.y;
+  const int u = layer * cv.B * cv.Hkv + ul;
+  const int t = blockIdx.x * 4 + w;
+  const int n8 = (cv.W < 0) ? 0 : max(0, T0 - cv.W);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    cv.len[u] = T0;
+    cv.n8[u] = n8;
+    cv.head16[u] = 0;
+  }
+  if (t >= T0) return;
+  const __half *ksrc = k16 + ((size_t)ul * T0 + t) * D;
+  const __half *vsrc = v16 + ((size_t)ul * T0 + t) * D;
+  if (lane == 0) {
+    cv.pos[(size_t)u * cv.cap + t] = t;
+    cv.ema[(size_t)u * cv.cap + t] = ema0 ? ema0[(size_t)ul * T0 + t] : 0.f;
+  }
+  if (t < n8) {
+    quantize_row_wave<D>(ksrc, cv.k8 + ((size_t)u * cv.cap8 + t) * D, cv.ks + (size_t)u * cv.cap8 + t, lane);
+    quantize_row_wave<D>(vsrc, cv.v8 + ((size_t)u * cv.cap8 + t) * D, cv.vs + (size_t)u * cv.cap8 + t, lane);
+  } else {
+    constexpr int EPL = D / kWave;
+    const int row = t - n8;                       // head16 = 0 after a load
+    __half *kd = cv.k16 + ((size_t)u * cv.cap16 + row) * D;
+    __half *vd = cv.v16 + ((size_t)u * cv.cap16 + row) * D;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      kd[lane * EPL + e] = ksrc[lane * EPL + e];
+      vd[lane * EPL + e] = vsrc[lane * EPL + e];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// rank_select: grid (U), 256 threads.
+//
+// score_i = alpha * a_hat_i + (1 - alpha) * r_hat_i in float64 with every operation
+// rounded separately (no fused multiply-add), so equal inputs give bit-equal scores on
+// any IEEE machine.  The e lowest (score, slot) pairs are evicted: an 8-bit-digit radix
+// select over the score's bit pattern (non-negative doubles order like unsigned integers)
+// finds the cut-off, stopping as soon as the cut-off bucket is evicted whole; slots that
+// tie with the cut-off go oldest first.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kEvThreads) void rank_select_kernel(CacheView cv, LayerMask appended,
+                                                                 double alpha,
+                                                                 double *__restrict__ score_all,
+                                                                 int32_t *__restrict__ src_all,
+                                                                 int32_t *__restrict__ sel_all) {
+  __shared__ int hist[256];
+  __shared__ int s_tmp[4];
+  __shared__ float s_fmin[4], s_fmax[4];
+  __shared__ unsigned long long s_prefix;
+  __shared__ int s_krem, s_done, s_hole[4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int u = blockIdx.x;
+  const int UPL = cv.B * cv.Hkv;
+  const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
+  const int n = cv.len[u] + (appended.get(layer) ? 1 : 0);
+  const int n8 = cv.n8[u];
+  const int N = cv.budget[layer * cv.B + b];
+  int32_t *sel = sel_all + (size_t)u * kSelInts;
+  const int p_eff = min(cv.P, n);
+  const int ncand = n - p_eff;
+  const int e = min(n - N, ncand);
+  if (n <= N || e <= 0) {
+    if (tid == 0) { sel[0] = n; sel[1] = n8; sel[2] = n; sel[3] = 0; }
+    return;
+  }
+  const float *ema = cv.ema + (size_t)u * cv.cap;
+  const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  double *score = score_all + (size_t)u * cv.cap;
+  int32_t *src = src_all + (size_t)u * cv.cap;
+
+  // min / max of the EMA over the candidates
+  float fmin_ = INFINITY, fmax_ = -INFINITY;
+  for (int i = tid; i < ncand; i += kEvThreads) {
+    float a = ema[i];
+    fmin_ = fminf(fmin_, a);
+    fmax_ = fmaxf(fmax_, a);
+  }
+  fmin_ = wave_min(fmin_);
+  fmax_ = wave_max(fmax_);
+  if (lane == 0) { s_fmin[w] = fmin_; s_fmax[w] = fmax_; }
+  __syncthreads();
+  const double a_lo = (double)fminf(fminf(s_fmin[0], s_fmin[1]), fminf(s_fmin[2], s_fmin[3]));
+  const double a_hi = (double)fmaxf(fmaxf(s_fmax[0], s_fmax[1]), fmaxf(s_fmax[2], s_fmax[3]));
+  const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
+  const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
+  const double oma = __dsub_rn(1.0, alpha);
+  for (int i = tid; i < ncand; i += kEvThreads) {
+    const double ah = (a_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)ema[i], a_lo), a_rng);
+    const double rh = (p_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)pos[i], p_lo), p_rng);
+    score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
+  }
+  if (tid == 0) { s_prefix = 0ull; s_krem = e; s_done = 0; }
+  __syncthreads();                                  // also orders the score writes before reads
+
+  // radix select of the e-th smallest score
+  unsigned long long mask = 0ull;
+  for (int shift = 56; shift >= 0; shift -= 8) {
+    hist[tid] = 0;
+    __syncthreads();
+    const unsigned long long prefix = s_prefix;
+    for (int i = tid; i < ncand; i += kEvThreads) {
+      const unsigned long long key = (unsigned long long)__double_as_longlong(score[i]);
+      if ((key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255ull)], 1);
+    }
+    __syncthreads();
+    const int cnt = hist[tid];
+    int total;
+    const int before = block256_scan_excl(cnt, s_tmp, &total);
+    const int krem = s_krem;
+    __syncthreads();                                // every thread has read s_krem
+    if (before < krem && krem <= before + cnt) {    // exactly one bin holds the cut-off
+      s_prefix = prefix | ((unsigned long long)tid << shift);
+      s_krem = krem - before;
+      s_done = (krem - before == cnt);              // the whole bucket goes
+    }
+    mask |= 255ull << shift;
+    __syncthreads();
+    if (s_done) break;
+  }
+  const unsigned long long prefix = s_prefix;
+  const int krem = s_krem;
+
+  // survivor list in slot order; ties with the cut-off are evicted oldest first
+  int carry_keep = 0, carry_tie = 0, kept8 = 0, hole = n;
+  for (int base = 0; base < n; base += kEvThreads) {
+    const int i = base + tid;
+    int tie = 0, below = 0;
+    if (i < ncand) {
+      const unsigned long long km = (unsigned long long)__double_as_longlong(score[i]) & mask;
+      below = km < prefix;
+      tie = km == prefix;
+    }
+    int tot_tie;
+    const int tie_rank = carry_tie + block256_scan_excl(tie, s_tmp, &tot_tie);
+    carry_tie += tot_tie;
+    const int evict = below | (tie & (tie_rank < krem));
+    const int keep = (i < n) & !evict;
+    int tot_keep;
+    const int j = carry_keep + block256_scan_excl(keep, s_tmp, &tot_keep);
+    carry_keep += tot_keep;
+    if (keep) {
+      src[j] = i;
+      kept8 += (i < n8);
+    }
+    if (evict) hole = min(hole, i);
+  }
+  kept8 = wave_sum(kept8);
+  hole = wave_min(hole);
+  __syncthreads();
+  if (lane == 0) { s_tmp[w] = kept8; s_hole[w] = hole; }
+  __syncthreads();
+  if (tid == 0) {
+    sel[0] = carry_keep;                              // = n - e
+    sel[1] = s_tmp[0] + s_tmp[1] + s_tmp[2] + s_tmp[3];
+    sel[2] = min(min(s_hole[0], s_hole[1]), min(s_hole[2], s_hole[3]));
+    sel[3] = e;
+    atomicAdd(&cv.stats[kStatEvicted], (unsigned long long)e);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// compact: grid (U, 5 planes), 256 threads.  Destination slot j takes source slot src[j]
+// >= j.  A workgroup walks its plane front to back in chunks: load a chunk into registers,
+// barrier, store.  Earlier chunks only wrote below the chunk start, later sources all lie
+// at or above it, so nothing is overwritten before it is read.
+// planes: 0 = K INT8 rows, 1 = V INT8 rows, 2 = scales + EMA + position, 3 = K FP16 rows,
+// 4 = V FP16 rows.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
+                                                             const int32_t *__restrict__ src_all,
+                                                             const int32_t *__restrict__ sel_all) {
+  const int u = blockIdx.x, plane = blockIdx.y, tid = threadIdx.x;
+  const int32_t *sel = sel_all + (size_t)u * kSelInts;
+  const int n_new = sel[0], n8_new = sel[1], hole = sel[2];
+  if (hole >= n_new) return;                          // nothing moves
+  const int n8_old = cv.n8[u], h16 = cv.head16[u];
+  const int32_t *src = src_all + (size_t)u * cv.cap;
+  const int cap8 = cv.cap8, cap16 = cv.cap16;
+
+  if (plane <= 1) {
+    // INT8 rows: destination slots [hole, n8_new)
+    constexpr int LPR = D / 16, RPP = kEvThreads / LPR, PASSES = 4;
+    int8_t *base_ptr = (plane == 0 ? cv.k8 : cv.v8) + (size_t)u * cap8 * D;
+    const int c = tid % LPR, r0 = tid / LPR;
+    for (int base = hole; base < n8_new; base += RPP * PASSES) {
+      int4 buf[PASSES];
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int j = base + p * RPP + r0;
+        if (j < n8_new) buf[p] = *(const int4 *)(base_ptr + (size_t)src[j] * D + c * 16);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int j = base + p * RPP + r0;
+        if (j < n8_new) *(int4 *)(base_ptr + (size_t)j * D + c * 16) = buf[p];
+      }
+    }
+  } else if (plane == 2) {
+    // per-slot metadata: EMA and position for [hole, n_new), scales for [hole, n8_new)
+    float *ema = cv.ema + (size_t)u * cv.cap;
+    int32_t *pos = cv.pos + (size_t)u * cv.cap;
+    __half *ks = cv.ks + (size_t)u * cap8, *vs = cv.vs + (size_t)u * cap8;
+    constexpr int PASSES = 4;
+    for (int base = hole; base < n_new; base += kEvThreads * PASSES) {
+      float fa[PASSES];
+      int32_t fp[PASSES];
+      __half fk[PASSES], fv[PASSES];
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int j = base + p * kEvThreads + tid;
+        if (j < n_new) {
+          const int s = src[j];
+          fa[p] = ema[s];
+          fp[p] = pos[s];
+          if (j < n8_new) { fk[p] = ks[s]; fv[p] = vs[s]; }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int j = base + p * kEvThreads + tid;
+        if (j < n_new) {
+          ema[j] = fa[p];
+          pos[j] = fp[p];
+          if (j < n8_new) { ks[j] = fk[p]; vs[j] = fv[p]; }
+        }
+      }
+    }
+  } else {
+    // FP16 ring rows: destination slots [max(hole, n8_new), n_new)
+    constexpr int ROWB = 2 * D, LPR = ROWB / 16, RPP = kEvThreads / LPR, PASSES = 4;
+    uint8_t *base_ptr = (uint8_t *)((plane == 3 ? cv.k16 : cv.v16) + (size_t)u * cap16 * D);
+    const int c = tid % LPR, r0 = tid / LPR;
+    const int j0 = max(hole, n8_new);
+    for (int base = j0; base < n_new; base += RPP * PASSES) {
+      int4 buf[PASSES];
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int j = base + p * RPP + r0;
+        if (j < n_new) {
+          const int s = ring_row(h16, src[j] - n8_old, cap16);
+          buf[p] = *(const int4 *)(base_ptr + (size_t)s * ROWB + c * 16);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int j = base + p * RPP + r0;
+        if (j < n_new) {
+          const int d = ring_row(h16, j - n8_new, cap16);
+          *(int4 *)(base_ptr + (size_t)d * ROWB + c * 16) = buf[p];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// demote: grid (U), one wavefront.  Quantises the oldest FP16 slots until at most W stay
+// FP16, appends them to the INT8 rows, and commits (len, n8, head16).
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kWave) void demote_kernel(CacheView cv,
+                                                       const int32_t *__restrict__ sel_all) {
+  const int u = blockIdx.x, lane = threadIdx.x;
+  const int32_t *sel = sel_all + (size_t)u * kSelInts;
+  const int n_new = sel[0], n8_new = sel[1];
+  const int h16 = cv.head16[u];
+  const int n16 = n_new - n8_new;
+  const int cnt = (cv.W < 0) ? 0 : max(0, n16 - cv.W);
+  for (int t = 0; t < cnt; ++t) {
+    const int row = ring_row(h16, t, cv.cap16);
+    const size_t dst = (size_t)u * cv.cap8 + n8_new + t;
+    quantize_row_wave<D>(cv.k16 + ((size_t)u * cv.cap16 + row) * D, cv.k8 + dst * D, cv.ks + dst, lane);
+    quantize_row_wave<D>(cv.v16 + ((size_t)u * cv.cap16 + row) * D, cv.v8 + dst * D, cv.vs + dst, lane);
+  }
+  if (lane == 0) {
+    cv.len[u] = n_new;
+    cv.n8[u] = n8_new + cnt;
+    cv.head16[u] = ring_row(h16, cnt % cv.cap16, cv.cap16);
+    if (cnt) atomicAdd(&cv.stats[kStatDemoted], (unsigned long long)cnt);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+
+hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
+                               int T0, const float *ema0, hipStream_t stream) {
+  dim3 grid((T0 + 3) / 4 > 0 ? (T0 + 3) / 4 : 1, cv.B * cv.Hkv);
+  if (cv.D == 64)
+    hipLaunchKernelGGL(load_prefill_kernel<64>, grid, dim3(kEvThreads), 0, stream, cv, layer, k16, v16, T0, ema0);
+  else
+    hipLaunchKernelGGL(load_prefill_kernel<128>, grid, dim3(kEvThreads), 0, stream, cv, layer, k16, v16, T0, ema0);
+  return hipGetLastError();
+}
+
+hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
+                                double *score, int32_t *src, int32_t *sel, hipStream_t stream) {
+  const int U = cv.L * cv.B * cv.Hkv;
+  hipLaunchKernelGGL(rank_select_kernel, dim3(U), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                     score, src, sel);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  if (cv.D == 64) {
+    hipLaunchKernelGGL(compact_kernel<64>, dim3(U, 5), dim3(kEvThreads), 0, stream, cv, src, sel);
+    hipLaunchKernelGGL(demote_kernel<64>, dim3(U), dim3(kWave), 0, stream, cv, sel);
+  } else {
+    hipLaunchKernelGGL(compact_kernel<128>, dim3(U, 5), dim3(kEvThreads), 0, stream, cv, src, sel);
+    hipLaunchKernelGGL(demote_kernel<128>, dim3(U), dim3(kWave), 0, stream, cv, sel);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace confkv

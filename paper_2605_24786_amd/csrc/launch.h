@@ -1,0 +1,53 @@
+// Host-side launchers of the kernels, one per source file.  Internal to the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "confkv_dev.h"
+
+namespace confkv {
+
+// ---- conf_reduce.hip ----
+size_t conf_reduce_scratch_floats(int B, int V);
+hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, float *partial,
+                              unsigned *arrive, float *conf, uint8_t *sel, double tau, double wH,
+                              double wm, double wp, hipStream_t stream);
+
+// ---- attend.hip ----
+struct AttendPlan {
+  int splits;        // workgroups per unit
+  int stash_tokens;  // score slots per workgroup held in LDS
+  size_t lds_bytes;  // dynamic LDS per workgroup
+};
+struct AttendLaunch {
+  int layer;
+  const __half *q, *knew, *vnew;
+  __half *out;
+  float *part_ml;          // [units per layer][max splits][G][2]
+  float *part_o;           // [units per layer][max splits][G][D]
+  unsigned *arrive_ml;     // [units per layer], this layer's counters
+  unsigned *arrive_o;      // [units per layer]
+  unsigned arrive_base;    // counter value before this launch
+  int max_splits;
+  float sm_scale, ema_decay;
+  int pos_new;
+};
+constexpr int kAttendMaxSplits = 64;
+bool attend_supported(int D, int G);
+// Largest split count and LDS plan for a unit of at most n_ub tokens (after the append)
+// of which at most n16_ub are FP16.  Returns false when no plan fits the device.
+bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
+                 AttendPlan *plan);
+hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
+                         hipStream_t stream);
+
+// ---- evict.hip ----
+constexpr int kSelInts = 4;  // per unit: new length, new INT8 count, first moved slot, spare
+hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
+                               int T0, const float *ema0, hipStream_t stream);
+hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
+                                double *score, int32_t *src, int32_t *sel, hipStream_t stream);
+
+}  // namespace confkv

@@ -1,0 +1,311 @@
+"""GPU parity: every C-ABI entry point of the HIP library against the CPU oracle.
+
+All tests here need an MI355X and call through the C ABI (ctypes -> libconfkv.so).
+Tolerances: attention output 2e-3 relative / 1e-3 absolute; confidence 1e-5 absolute;
+budget choices, kept-token sets and cache contents bit-exact except ties within 1e-6
+relative of the threshold or cut-off, which the harness counts.
+"""
+import math
+import os
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import confkv_oracle as O
+from synth import generate as gen
+from synth.workloads import small, workload
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from harness import CONF_ATOL, Lockstep, f32, policy_of  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+def _mk(lib, **kw):
+    base = dict(n_layers=1, batch=1, n_q_heads=4, n_kv_heads=1, head_dim=128, vocab=1000, capacity=256,
+                fp16_window=16, protected_window=8, n_tight=[64], n_loose=[128])
+    base.update(kw)
+    return lib.ConfKV(**base)
+
+
+# ------------------------------------------------------------------ confidence / budget
+
+@pytest.mark.parametrize("V,B", [(2, 1), (4096, 2), (4097, 3), (50257, 1), (128256, 8), (152064, 1)])
+def test_confidence_matches_oracle(lib, torch_cuda, V, B):
+    torch = torch_cuda
+    say(f"confidence V={V} B={B}")
+    kv = _mk(lib, vocab=V, batch=B)
+    rng = np.random.default_rng(V + B)
+    conf = torch.zeros(B, dtype=torch.float32, device="cuda")
+    sel = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    w = (f32(0.4), f32(0.3), f32(0.3))
+    for std in (0.5, 3.0, 6.0, 12.0):
+        x = (rng.standard_normal((B, V)) * std).astype(np.float32) + np.float32(rng.normal() * 30)
+        kv.step(torch.from_numpy(x).cuda(), conf, sel)
+        c = conf.cpu().numpy()
+        ref = np.array([O.confidence(r, w) for r in x])
+        assert np.max(np.abs(c - ref)) <= CONF_ATOL, (std, c, ref)
+        far = np.abs(ref - f32(0.7)) > 1e-5
+        assert np.array_equal(sel.cpu().numpy().astype(bool)[far], (ref >= f32(0.7))[far])
+    kv.close()
+
+
+def test_confidence_closed_forms_and_budgets(lib, torch_cuda):
+    torch = torch_cuda
+    V, B, L = 50257, 4, 3
+    kv = _mk(lib, vocab=V, batch=B, n_layers=L, n_tight=[64, 48, 32], n_loose=[128, 96, 64])
+    x = np.zeros((B, V), dtype=np.float32)
+    x[1] = 5.0                                   # uniform at another level
+    x[2] = -1.0e4; x[2, 123] = 0.0               # one-hot -> c = 1
+    x[3] = -np.inf; x[3, :3] = 1.5               # three equal maxima, rest -inf
+    conf = torch.zeros(B, dtype=torch.float32, device="cuda")
+    sel = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    kv.step(torch.from_numpy(x).cuda(), conf, sel)
+    c = conf.cpu().numpy().astype(np.float64)
+    assert abs(c[0] - (0.15 + 0.3 / V)) < CONF_ATOL and abs(c[1] - c[0]) < 1e-7
+    assert abs(c[2] - 1.0) < CONF_ATOL
+    assert abs(c[3] - (0.4 * (1 - math.log(3) / math.log(V)) + 0.15 + 0.1)) < CONF_ATOL
+    assert list(sel.cpu().numpy()) == [0, 0, 1, 0]
+    st = kv.counters()
+    assert (st.tight_steps, st.loose_steps) == (1, 3)
+    # the chosen budgets act in the next eviction: fill every layer past both budgets
+    D = 128
+    rng = np.random.default_rng(0)
+    for l in range(L):
+        K = torch.from_numpy(rng.standard_normal((B, 1, 200, D)).astype(np.float16)).cuda()
+        kv.load_prefill(l, K, K)
+    kv.evict_compact()
+    ln, _ = kv.lengths()
+    assert ln.tolist() == [[128, 128, 64, 128], [96, 96, 48, 96], [64, 64, 32, 64]]
+    kv.close()
+
+
+# ------------------------------------------------------------------ prompt load / export
+
+@pytest.mark.parametrize("D,W,T0", [(128, 16, 100), (64, 8, 37), (128, -1, 50), (64, 0, 20), (128, 300, 40)])
+def test_prefill_quantiser_bit_exact(lib, torch_cuda, D, W, T0):
+    torch = torch_cuda
+    say(f"prefill D={D} W={W} T0={T0}")
+    B, H = 2, 2
+    kv = _mk(lib, batch=B, n_q_heads=2 * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=320 if W < 300 else 512,
+             n_tight=[200], n_loose=[300])
+    rng = np.random.default_rng(D + T0)
+    mag = rng.choice([1e-3, 0.05, 1.0, 40.0], size=(B, H, T0, 1))
+    K = (rng.standard_normal((B, H, T0, D)) * mag).astype(np.float16)
+    V = (rng.standard_normal((B, H, T0, D)) * mag).astype(np.float16)
+    K[0, 0, 3] = 0                                         # a zero vector
+    K[1, 1, 5] = np.float16(6e-8)                          # scale underflows to zero
+    K[0, 1, 7, :8] = np.array([127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.25], np.float16)  # exact ties
+    e0 = rng.random((B, H, T0)).astype(np.float32)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(), torch.from_numpy(e0).cuda())
+    for b in range(B):
+        for g in range(H):
+            u = O.load_prefill(K[b, g], V[b, g], W, e0[b, g])
+            ex = kv.export(0, b, g)
+            assert ex["n"] == T0 and np.array_equal(ex["pos"], np.arange(T0))
+            assert np.array_equal(ex["is16"], u.is16) and np.array_equal(ex["ema"], e0[b, g])
+            m8 = ~u.is16
+            assert np.array_equal(ex["k8"][m8], u.k8[m8]) and np.array_equal(ex["v8"][m8], u.v8[m8])
+            assert np.array_equal(ex["ks"][m8].view(np.uint16), u.ks[m8].view(np.uint16))
+            assert np.array_equal(ex["vs"][m8].view(np.uint16), u.vs[m8].view(np.uint16))
+            assert np.array_equal(ex["k16"][u.is16].view(np.uint16), K[b, g][u.is16].view(np.uint16))
+            assert np.array_equal(ex["v16"][u.is16].view(np.uint16), V[b, g][u.is16].view(np.uint16))
+    kv.close()
+
+
+# ------------------------------------------------------------------ attention + mass EMA
+
+def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0):
+    say(f"attend D={D} G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits}")
+    if splits:
+        os.environ["CONF_KV_SPLITS"] = str(splits)
+    else:
+        os.environ.pop("CONF_KV_SPLITS", None)
+    try:
+        cap = ((T0 + 8 + 63) // 64) * 64
+        kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
+                 protected_window=4, n_tight=[cap - 2], n_loose=[cap - 1])
+    finally:
+        os.environ.pop("CONF_KV_SPLITS", None)
+    rng = np.random.default_rng(seed)
+    K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    e0 = rng.random((B, H, T0)).astype(np.float32)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(), torch.from_numpy(e0).cuda())
+    units = {(b, g): O.load_prefill(K[b, g], V[b, g], W, e0[b, g]) for b in range(B) for g in range(H)}
+    out = torch.zeros((B, G * H, D), dtype=torch.float16, device="cuda")
+    sm, lam = f32(1 / math.sqrt(D)), f32(0.9)
+    for t in range(3):
+        q = (rng.standard_normal((B, G * H, D)) * scale_q).astype(np.float16)
+        kn = rng.standard_normal((B, H, D)).astype(np.float16)
+        vn = rng.standard_normal((B, H, D)).astype(np.float16)
+        kv.attend(0, torch.from_numpy(q).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda(), out)
+        got = out.cpu().numpy().astype(np.float64)
+        for (b, g), u in units.items():
+            ref, A = O.attend_unit(u, q[b, g * G:(g + 1) * G], kn[b, g], vn[b, g], T0 + t, sm, lam)
+            err = np.max(np.abs(got[b, g * G:(g + 1) * G] - ref) / (1e-3 + 2e-3 * np.abs(ref)))
+            assert err <= 1.0, f"step {t} unit {(b, g)}: out off by {err:.3g} x tol"
+            ex = kv.export(0, b, g)
+            assert ex["n"] == u.n and ex["pos"][-1] == T0 + t and ex["is16"][-1]
+            assert np.array_equal(ex["k16"][-1].view(np.uint16), kn[b, g].view(np.uint16))
+            assert np.array_equal(ex["v16"][-1].view(np.uint16), vn[b, g].view(np.uint16))
+            e_ref = u.ema.astype(np.float64)
+            e_err = np.abs(ex["ema"].astype(np.float64) - e_ref)
+            assert np.all(e_err <= 1e-7 + 2e-5 * e_ref), f"step {t} unit {(b, g)}: EMA off, max rel {np.max(e_err / (e_ref + 1e-30)):.3g}"
+        kv.evict_compact()                          # budgets above the length: commits the append only
+    assert kv.counters().evicted == 0
+    kv.close()
+
+
+
+@pytest.mark.parametrize("D,G,H,B,T0,W,splits", [
+    (64, 1, 3, 1, 200, -1, 0),        # GPT-2-like: MHA, FP16-only
+    (64, 1, 2, 2, 700, -1, 5),
+    (128, 4, 2, 2, 777, 40, 0),       # Llama-like GQA, mixed INT8 / FP16
+    (128, 4, 2, 1, 777, 40, 1),       # one workgroup per unit
+    (128, 4, 1, 1, 1500, 128, 7),     # ragged splits across the INT8 / FP16 boundary
+    (128, 5, 2, 1, 600, 24, 3),       # Qwen-like group of five
+    (128, 2, 1, 1, 300, 0, 2),        # W = 0: only the new token is FP16
+    (128, 8, 1, 1, 260, 16, 2),
+    (64, 4, 2, 1, 130, 100, 4),
+    (128, 4, 1, 1, 5, 2, 0),          # a tiny cache
+    (128, 1, 1, 1, 0, 4, 0),          # empty cache: the query sees only itself
+])
+def test_attend_matches_oracle(lib, torch_cuda, D, G, H, B, T0, W, splits):
+    _attend_case(lib, torch_cuda, D, G, H, B, T0, W, splits, seed=D + G + T0)
+
+
+def test_attend_sharp_softmax(lib, torch_cuda):
+    # large-magnitude queries: a few slots take nearly all the mass, the rest underflow
+    _attend_case(lib, torch_cuda, 128, 4, 1, 1, 900, 32, 6, seed=5, scale_q=6.0)
+
+
+def test_ema_mass_invariant_without_eviction(lib, torch_cuda):
+    # no eviction: sum_i ema_i = G (1 - lambda^t) after t steps (EMA starts at 0)
+    torch = torch_cuda
+    D, G, H, T0, W = 128, 4, 2, 500, 32
+    kv = _mk(lib, n_q_heads=G * H, n_kv_heads=H, fp16_window=W, capacity=640, n_tight=[600], n_loose=[620])
+    rng = np.random.default_rng(3)
+    K = torch.from_numpy(rng.standard_normal((1, H, T0, D)).astype(np.float16)).cuda()
+    kv.load_prefill(0, K, K)
+    out = torch.zeros((1, G * H, D), dtype=torch.float16, device="cuda")
+    lam = float(f32(0.9))
+    for t in range(10):
+        q = torch.from_numpy(rng.standard_normal((1, G * H, D)).astype(np.float16)).cuda()
+        kn = torch.from_numpy(rng.standard_normal((1, H, D)).astype(np.float16)).cuda()
+        kv.attend(0, q, kn, kn, out)
+        kv.evict_compact()
+        for g in range(H):
+            ex = kv.export(0, 0, g)
+            assert abs(ex["ema"].astype(np.float64).sum() - G * (1 - lam ** (t + 1))) < 2e-5
+    kv.close()
+
+
+# ------------------------------------------------------------------ ranking / eviction / compaction
+
+def _evict_case(lib, torch, n, N, P, W, alpha, ema, D=64, seed=0):
+    rng = np.random.default_rng(seed)
+    cap = ((max(n, N, P) + 1 + 63) // 64) * 64
+    kv = _mk(lib, n_q_heads=1, n_kv_heads=1, head_dim=D, fp16_window=W, protected_window=P, capacity=cap,
+             n_tight=[N], n_loose=[N], alpha=alpha)
+    K = rng.standard_normal((1, 1, n, D)).astype(np.float16)
+    V = rng.standard_normal((1, 1, n, D)).astype(np.float16)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(),
+                    torch.from_numpy(ema.reshape(1, 1, n).astype(np.float32)).cuda())
+    u = O.load_prefill(K[0, 0], V[0, 0], W, ema.astype(np.float32))
+    kv.evict_compact()
+    gone = O.evict_compact_unit(u, N, P, f32(alpha), W)
+    ex = kv.export(0, 0, 0)
+    assert ex["n"] == u.n, (ex["n"], u.n)
+    assert np.array_equal(ex["pos"], u.pos.astype(np.int32))
+    assert np.array_equal(ex["is16"], u.is16) and np.array_equal(ex["ema"], u.ema)
+    m8 = ~u.is16
+    assert np.array_equal(ex["k8"][m8], u.k8[m8]) and np.array_equal(ex["v8"][m8], u.v8[m8])
+    assert np.array_equal(ex["ks"][m8].view(np.uint16), u.ks[m8].view(np.uint16))
+    assert np.array_equal(ex["k16"][u.is16].view(np.uint16), u.k16[u.is16].view(np.uint16))
+    assert np.array_equal(ex["v16"][u.is16].view(np.uint16), u.v16[u.is16].view(np.uint16))
+    assert kv.counters().evicted == gone.size
+    kv.close()
+    return u
+
+
+@pytest.mark.parametrize("n,N,P,W", [(300, 100, 20, 30), (300, 100, 20, -1), (1000, 999, 1, 16),
+                                     (515, 64, 64, 8), (200, 50, 0, 0), (4000, 512, 128, 64),
+                                     (260, 100, 10, 150), (90, 200, 10, 16)])
+def test_evict_random_ema(lib, torch_cuda, n, N, P, W):
+    say(f"evict n={n} N={N} P={P} W={W}")
+    rng = np.random.default_rng(n + N)
+    _evict_case(lib, torch_cuda, n, N, P, W, 0.65, rng.random(n), seed=n)
+
+
+def test_evict_ties_and_degenerate(lib, torch_cuda):
+    torch = torch_cuda
+    n = 400
+    # all-equal EMA and alpha = 1: every score ties, the oldest go first
+    u = _evict_case(lib, torch, n, 100, 16, 32, 1.0, np.full(n, 0.25))
+    assert list(u.pos) == list(range(300, 400))
+    # few distinct EMA levels: many exact ties at the cut-off
+    rng = np.random.default_rng(1)
+    _evict_case(lib, torch, n, 150, 16, 32, 1.0, rng.integers(0, 4, n) / 4.0)
+    # alpha = 0: pure recency (sliding window)
+    u = _evict_case(lib, torch, n, 150, 16, 32, 0.0, rng.random(n))
+    assert list(u.pos) == list(range(250, 400))
+    # protected window larger than the budget: the window wins
+    u = _evict_case(lib, torch, n, 8, 50, 16, 0.65, rng.random(n))
+    assert list(u.pos) == list(range(350, 400))
+    # a single candidate
+    _evict_case(lib, torch, 20, 19, 19, 4, 0.65, rng.random(20))
+
+
+# ------------------------------------------------------------------ whole decode steps
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_lockstep_small_workloads(lib, torch_cuda, idx):
+    wl = small(idx)
+    say(f"lockstep workload {idx}: {wl.name} (reduced) steps={wl.steps}")
+    ls = Lockstep(lib, wl, seed=idx)
+    for t in range(wl.steps):
+        ls.step()
+    rep = ls.report
+    st = ls.kv.counters()
+    say(f"  out_err={rep.max_out_err:.3f}xtol conf_err={rep.max_conf_err:.2e} ema_rel={rep.max_ema_rel:.2e} "
+        f"evictions={rep.evictions} tight={rep.tight_steps} ties(evict/budget)={rep.evict_ties}/{rep.budget_ties} "
+        f"flips={rep.evict_flips}/{rep.budget_flips} demoted={st.demoted}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.evictions > 0 and st.device_errors == 0
+    if wl.fp16_window >= 0:
+        assert st.demoted > 0
+    ls.close()
+
+
+def test_call_order_and_capacity_errors(lib, torch_cuda):
+    torch = torch_cuda
+    kv = _mk(lib, capacity=64, n_tight=[32], n_loose=[60], protected_window=4)
+    z = torch.zeros((1, 4, 128), dtype=torch.float16, device="cuda")
+    kn = torch.zeros((1, 1, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(lib.ConfKVError) as e:
+        kv.load_prefill(0, torch.zeros((1, 1, 64, 128), dtype=torch.float16, device="cuda"), kn)
+    assert e.value.status == -4
+    kv.attend(0, z, kn, kn, z)
+    with pytest.raises(lib.ConfKVError) as e:
+        kv.attend(0, z, kn, kn, z)                      # second append before the commit
+    assert e.value.status == -5
+    with pytest.raises(lib.ConfKVError) as e:
+        kv.attend(3, z, kn, kn, z)
+    assert e.value.status == -3
+    kv.evict_compact()
+    ln, n16 = kv.lengths()
+    assert ln.tolist() == [[1]] and n16.tolist() == [[[1]]]
+    kv.close()
