@@ -164,7 +164,9 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0):
             e_ref = u.ema.astype(np.float64)
             e_err = np.abs(ex["ema"].astype(np.float64) - e_ref)
             assert np.all(e_err <= 1e-7 + 2e-5 * e_ref), f"step {t} unit {(b, g)}: EMA off, max rel {np.max(e_err / (e_ref + 1e-30)):.3g}"
-        kv.evict_compact()                          # budgets above the length: commits the append only
+        kv.evict_compact()                          # budgets above the length: commit + demotion only
+        for u in units.values():
+            O.demote(u, W)
     assert kv.counters().evicted == 0
     kv.close()
 
