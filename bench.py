@@ -1,0 +1,214 @@
+"""Benchmark of the Conf-KV decode step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+L x conf_kv_attend, conf_kv_step, conf_kv_evict_compact, all through the C ABI.
+Workload: the Llama-3-8B-shape single-step microbenchmark (32 layers, 32/8 heads,
+D = 128, V = 128256, batch 8, 4096-token cache per unit with the newest 128 tokens FP16
+and the rest INT8; budgets 1024/2048; protected window 128; logits N(0, 3)).
+
+The step shrinks every cache (4097 -> 2048 or 1024 slots), so the cache is re-loaded from
+the resident FP16 prompt tensors between timed steps; the re-load is outside the timed
+region.  Each step is bracketed by HIP events on the launch stream with a device
+synchronisation on both sides; `ms_per_step` is the mean event time of the K steps.
+
+Prints ONE JSON line.  `roofline` describes the attention + mass-EMA kernel (the dominant
+kernel): algorithmic bytes per launch / its mean launch duration, against 8 TB/s.
+`cpu_baseline` is the float64 numpy oracle timed on this machine's host cores on a bounded
+sample of the same workload's units, extrapolated to the whole step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def attend_bytes_per_launch(wl, n8, n16):
+    """Algorithmic HBM bytes of one conf_kv_attend launch (one layer), n16 counting the new token.
+
+    Per unit: INT8 slots (2D codes + 2 fp16 scales), FP16 slots (4D), EMA read + write
+    (8 B per slot), q and out (4 G D), the new K/V read and written (8 D + 8 D... the write
+    is counted once: 4D) and its position.
+    """
+    D, G = wl.head_dim, wl.group
+    n = n8 + n16
+    per_unit = n8 * (2 * D + 4) + n16 * 4 * D + 8 * n + 4 * G * D + 8 * D + 4
+    return per_unit * wl.batch * wl.n_kv_heads
+
+
+def step_bytes(wl, n8, n16, n_after, n_moved):
+    """Algorithmic bytes of the whole step: attention, logits, ranking and compaction moves."""
+    D = wl.head_dim
+    att = attend_bytes_per_launch(wl, n8, n16) * wl.n_layers
+    logits = 4 * wl.vocab * wl.batch
+    n = n8 + n16
+    rank = 8 * max(0, n - wl.protected) * wl.units
+    moved = 2 * n_moved * (2 * D + 4 + 8)          # INT8 survivors behind the first hole, read + write
+    demote = wl.units * (4 * D + 2 * D + 4)
+    return att + logits + rank + moved + demote, att
+
+
+def cpu_baseline(wl, seed, budget_s=15.0):
+    """The oracle, as it stands, on a bounded sample of units of the same workload."""
+    from threadpoolctl import threadpool_limits
+    from oracle import confkv_oracle as O
+    from synth import generate as gen
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import policy_of
+    pol = policy_of(wl)
+    G = wl.group
+    rng = np.random.default_rng(seed)
+    done, t_total = 0, 0.0
+    logits = gen.step_logits(wl, seed, 0)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        c = O.confidence(logits[0], pol.weights)
+        t_conf = time.perf_counter() - t0
+        tight = c >= pol.tau
+        while t_total < budget_s and done < 64:
+            l, b, g = int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch)), int(rng.integers(wl.n_kv_heads))
+            K, V = gen.prefill_unit(wl, seed, l, b, g)
+            u = O.load_prefill(K, V, wl.fp16_window)
+            q, kn, vn = gen.step_inputs(wl, seed, l, 0)
+            t0 = time.perf_counter()
+            O.attend_unit(u, q[b, g * G:(g + 1) * G], kn[b, g], vn[b, g], wl.prefill, pol.sm_scale, pol.ema_decay)
+            N = pol.n_tight[l] if tight else pol.n_loose[l]
+            O.evict_compact_unit(u, N, pol.protected, pol.alpha, pol.fp16_window)
+            t_total += time.perf_counter() - t0
+            done += 1
+    per_unit = t_total / done
+    step_s = per_unit * wl.units + t_conf * wl.batch
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} of {wl.units} units of workload {wl.name} (attend + evict/compact/demote, "
+                      f"{per_unit * 1e3:.2f} ms per unit) plus 1 of {wl.batch} confidence rows "
+                      f"({t_conf * 1e3:.2f} ms), single thread, extrapolated to all units"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    import paper_2605_24786_amd as pkg
+    from synth import generate as gen
+    from synth.workloads import workload
+
+    wl = workload(args.workload)
+    L = wl.n_layers
+    t_setup = time.time()
+    kv = pkg.from_workload(wl)
+    prompts = []
+    for l in range(L):
+        K, V = gen.prefill_layer(wl, args.seed, l, threads=16)
+        prompts.append((torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()))
+    qs, ks, vs = [], [], []
+    for l in range(L):
+        q, k, v = gen.step_inputs(wl, args.seed, l, 0)
+        qs.append(torch.from_numpy(q).cuda()); ks.append(torch.from_numpy(k).cuda()); vs.append(torch.from_numpy(v).cuda())
+    logits = torch.from_numpy(gen.step_logits(wl, args.seed, 0)).cuda()
+    out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float16, device="cuda")
+    conf = torch.empty(wl.batch, dtype=torch.float32, device="cuda")
+    sel = torch.empty(wl.batch, dtype=torch.uint8, device="cuda")
+    print(f"# setup {time.time() - t_setup:.1f}s: {wl.name}, state {kv.state.numel() / 2**30:.2f} GiB", file=sys.stderr, flush=True)
+
+    def reload():
+        for l in range(L):
+            kv.load_prefill(l, prompts[l][0], prompts[l][1])
+
+    def one_step(ev=None):
+        # returns per-phase events when ev is given: [start, after attends, after step, end]
+        if ev: ev[0].record()
+        for l in range(L):
+            kv.attend(l, qs[l], ks[l], vs[l], out)
+        if ev: ev[1].record()
+        kv.step(logits, conf, sel)
+        if ev: ev[2].record()
+        kv.evict_compact()
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        reload(); torch.cuda.synchronize()
+        one_step(); torch.cuda.synchronize()
+
+    len_before = wl.prefill + 1
+    n8_b = max(0, wl.prefill - wl.fp16_window) if wl.fp16_window >= 0 else 0
+    n16_b = len_before - n8_b
+    t_step, t_att, t_conf, t_evict = [], [], [], []
+    for _ in range(args.steps):
+        reload(); torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        one_step(ev)
+        torch.cuda.synchronize()
+        t_step.append(ev[0].elapsed_time(ev[3]))
+        t_att.append(ev[0].elapsed_time(ev[1]))
+        t_conf.append(ev[1].elapsed_time(ev[2]))
+        t_evict.append(ev[2].elapsed_time(ev[3]))
+    ln, n16 = kv.lengths()
+    st = kv.counters()
+
+    # the dominant kernel alone: per-launch HIP events around each conf_kv_attend
+    reload(); torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+    for l in range(L):
+        evs[l][0].record()
+        kv.attend(l, qs[l], ks[l], vs[l], out)
+        evs[l][1].record()
+    torch.cuda.synchronize()
+    t_launch = [a.elapsed_time(b) for a, b in evs]
+    kv.step(logits, conf, sel); kv.evict_compact(); torch.cuda.synchronize()
+
+    ms_step = float(np.mean(t_step))
+    att_launch_ms = float(np.mean(t_launch))
+    att_bytes = attend_bytes_per_launch(wl, n8_b, n16_b)
+    n_after = int(ln.mean())
+    n_moved = int(ln.sum()) * wl.n_kv_heads          # survivors (all sit behind the first hole, to first order)
+    total_bytes, att_total = step_bytes(wl, n8_b, n16_b, n_after, n_moved)
+    achieved = att_bytes / (att_launch_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "batch": wl.batch, "q_heads": wl.n_q_heads,
+                   "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "vocab": wl.vocab,
+                   "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
+                   "protected": wl.protected, "kv_storage": "int8+fp16", "attend_splits": kv.attend_splits(0),
+                   "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
+        "roofline": {"bound": "hbm", "kernel": "attend_kernel<128,4>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_launch": att_bytes, "launch_ms": att_launch_ms},
+        "step_breakdown_ms": {"attend_x_layers": float(np.mean(t_att)), "confidence": float(np.mean(t_conf)),
+                              "evict_compact": float(np.mean(t_evict))},
+        "step_hbm": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (ms_step * 1e-3) / 1e9,
+                     "frac_of_peak": total_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "attend_GBps": att_total / (float(np.mean(t_att)) * 1e-3) / 1e9},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, args.seed)
+    kv.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -48,6 +48,21 @@ __device__ __forceinline__ void unpack_i8x16(const int4 &r, float (&f)[16]) {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
+// Partials travel between workgroups (possibly on different XCDs, whose L2s are not
+// coherent for ordinary accesses) through agent-scope relaxed atomics: such loads and
+// stores are coherent across the device by themselves, so no cache-wide release/acquire
+// fence (an L2 write-back plus invalidate on this hardware) is ever issued.  Ordering is
+// by completion: a publisher waits for its stores to complete before the workgroup
+// barrier that precedes the arrival increment; a consumer only issues its loads after it
+// has observed the arrival count.
+__device__ __forceinline__ void st_agent(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0); }
+
 __device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, float (&f)[16]) {
   half8_t a = __builtin_bit_cast(half8_t, r0), b = __builtin_bit_cast(half8_t, r1);
 #pragma unroll
@@ -246,15 +261,13 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 
   float *ml = a.part_ml + ((size_t)ul * a.max_splits + j) * G * 2;
   if (tid < G) {
-    ml[tid * 2 + 0] = mloc[tid];
-    ml[tid * 2 + 1] = lloc[tid];
-    __threadfence();
+    st_agent(&ml[tid * 2 + 0], mloc[tid]);
+    st_agent(&ml[tid * 2 + 1], lloc[tid]);
+    wait_stores_done();
   }
   __syncthreads();
-  if (tid == 0) {
-    __threadfence();
-    atomicAdd(&a.arrive_ml[ul], 1u);
-  }
+  if (tid == 0)
+    __hip_atomic_fetch_add(&a.arrive_ml[ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
   // ================= V pass: un-normalised output of the slice =================
   {
@@ -337,33 +350,33 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   __syncthreads();
   float *po = a.part_o + ((size_t)ul * a.max_splits + j) * G * D;
   for (int idx = tid; idx < G * D; idx += kAttThreads) {
-    po[idx] = (red[idx] + red[G * D + idx]) + (red[2 * G * D + idx] + red[3 * G * D + idx]);
+    st_agent(&po[idx],
+             (red[idx] + red[G * D + idx]) + (red[2 * G * D + idx] + red[3 * G * D + idx]));
   }
-  __threadfence();
+  wait_stores_done();
   __syncthreads();
   if (tid == 0) {
-    __threadfence();
-    const unsigned ticket = atomicAdd(&a.arrive_o[ul], 1u);
+    const unsigned ticket = __hip_atomic_fetch_add(&a.arrive_o[ul], 1u, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == a.arrive_base + (unsigned)ns - 1u);
   }
   __syncthreads();
   if (s_last) {
     // ---- last arrival: merge the splits (online-softmax merge) and write out ----
-    __threadfence();
     const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
     const float *pou = a.part_o + (size_t)ul * a.max_splits * G * D;
     const int Hq = cv.Hkv * G;
     for (int idx = tid; idx < G * D; idx += kAttThreads) {
       const int h = idx / D;
       float M = NEG;
-      for (int s = 0; s < ns; ++s) M = fmaxf(M, mlu[(s * G + h) * 2]);
+      for (int s = 0; s < ns; ++s) M = fmaxf(M, ld_agent(&mlu[(s * G + h) * 2]));
       float L = 0.f, o = 0.f;
       for (int s = 0; s < ns; ++s) {
-        const float ms = mlu[(s * G + h) * 2];
+        const float ms = ld_agent(&mlu[(s * G + h) * 2]);
         if (ms > NEG) {
           const float wgt = expf(ms - M);
-          L += wgt * mlu[(s * G + h) * 2 + 1];
-          o += wgt * pou[(size_t)s * G * D + idx];
+          L += wgt * ld_agent(&mlu[(s * G + h) * 2 + 1]);
+          o += wgt * ld_agent(&pou[(size_t)s * G * D + idx]);
         }
       }
       a.out[((size_t)(b * Hq + g * G)) * D + idx] = __float2half_rn(o / L);
@@ -385,20 +398,19 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
     }
     __syncthreads();
     if (!s_ok) return;
-    __threadfence();
   } else {
     __syncthreads();
   }
   if (tid < G) {
     const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
     float M = NEG;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, mlu[(s * G + tid) * 2]);
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, ld_agent(&mlu[(s * G + tid) * 2]));
     double L = 0.0;
     for (int s = 0; s < ns; ++s) {
-      const float ms = mlu[(s * G + tid) * 2];
-      if (ms > NEG) L += exp((double)ms - (double)M) * (double)mlu[(s * G + tid) * 2 + 1];
+      const float ms = ld_agent(&mlu[(s * G + tid) * 2]);
+      if (ms > NEG) L += exp((double)ms - (double)M) * (double)ld_agent(&mlu[(s * G + tid) * 2 + 1]);
     }
-    const float mine = mlu[(j * G + tid) * 2];
+    const float mine = ld_agent(&mlu[(j * G + tid) * 2]);
     fac[tid] = (mine > NEG) ? exp((double)mine - (double)M) / L : 0.0;
   }
   __syncthreads();

@@ -289,7 +289,9 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
       }
     }
   } else {
-    // FP16 ring rows: destination slots [max(hole, n8_new), n_new)
+    // FP16 ring rows: destination slots [max(hole, n8_new), n_new).  When every evicted
+    // slot was INT8 the ring rows keep their place and nothing moves.
+    if (sel[3] == n8_old - n8_new) return;
     constexpr int ROWB = 2 * D, LPR = ROWB / 16, RPP = kEvThreads / LPR, PASSES = 4;
     uint8_t *base_ptr = (uint8_t *)((plane == 3 ? cv.k16 : cv.v16) + (size_t)u * cap16 * D);
     const int c = tid % LPR, r0 = tid / LPR;
