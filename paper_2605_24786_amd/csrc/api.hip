@@ -26,7 +26,7 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-  size_t conf_partial, conf_arrive, arrive_ml, arrive_o, part_ml, part_o, score, src, sel, total;
+  size_t conf_partial, conf_arrive, arrive, part_ml, part_o, score, src, sel, total;
   size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
 };
 
@@ -88,8 +88,7 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   s.conf_arrive = take((size_t)c->batch * 4);
-  s.arrive_ml = take(U * 4);
-  s.arrive_o = take(U * 4);
+  s.arrive = take(U * 4);
   s.zero_bytes = off;
   s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
   s.part_ml = take(UPL * kAttendMaxSplits * G * 2 * 4);
@@ -262,8 +261,7 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
   a.out = (__half *)dev_out16;
   a.part_ml = (float *)(h->scratch + h->kl.part_ml);
   a.part_o = (float *)(h->scratch + h->kl.part_o);
-  a.arrive_ml = (unsigned *)(h->scratch + h->kl.arrive_ml) + (size_t)layer * UPL;
-  a.arrive_o = (unsigned *)(h->scratch + h->kl.arrive_o) + (size_t)layer * UPL;
+  a.arrive = (unsigned *)(h->scratch + h->kl.arrive) + (size_t)layer * UPL;
   a.arrive_base = h->arrive_base[layer];
   a.max_splits = kAttendMaxSplits;
   a.sm_scale = h->cfg.sm_scale;

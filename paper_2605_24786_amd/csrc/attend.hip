@@ -4,17 +4,16 @@
 // mass; Algorithm 1 -- append in FP16, update EMA metadata).
 //
 // One launch per layer, grid (splits, B * Hkv), 256 threads.  The `splits` workgroups of a
-// unit (b, kv-head) each stream a contiguous, byte-balanced slice of the unit's slots and
-// serve all G query heads of the group from that single read:
+// unit (b, kv-head) each stream a contiguous, byte-balanced slice of the unit's slots once
+// and serve all G query heads of the group from that single read:
 //
-//   K pass   raw scores s[h][i] of the slice -> LDS; slice maximum m[h]
-//   publish  p[h][i] = exp(s - m[h]) kept in LDS, l[h] = sum p; (m, l) -> global, arrive
-//   V pass   o[h][:] = sum_i p[h][i] * V_i (un-normalised) -> global, arrive; the last
-//            workgroup to arrive merges the splits' (m, l, o) into out (online-softmax merge)
-//   mass     wait until every split of the unit has published (m, l) (they did so before
-//            their own V pass, so the wait is normally over already), form the exact
-//            global (M, L), then per slot A_i = sum_h p[h][i] e^{m[h]-M[h]} / L[h] and
-//            ema_i <- lambda ema_i + (1 - lambda) A_i.
+//   stream   every slot lane-group keeps a running (max, normaliser, output) per head
+//            (online softmax); raw scores s[h][i] of the slice stay in LDS
+//   publish  lane-groups -> wavefront -> workgroup merge; (m, l, o) -> global, arrive; the
+//            last workgroup to arrive merges the splits' partials into out
+//   mass     the others wait until every split of the unit has arrived (they all publish
+//            at about the same time), form the exact global (M, L), then per slot
+//            A_i = sum_h e^{s[h][i]-M[h]} / L[h] and ema_i <- lambda ema_i + (1-lambda) A_i.
 //
 // Every K/V byte is read once; the scores never leave the chip.  The wait is between
 // workgroups of one launch, so the host only launches grids that are co-resident
@@ -34,7 +33,6 @@ namespace confkv {
 
 constexpr int kAttThreads = 256;
 constexpr int kAttWaves = 4;
-constexpr int kUnroll = 4;
 constexpr int kSpinLimit = 4000000;
 
 __device__ __forceinline__ void unpack_i8x16(const int4 &r, float (&f)[16]) {
@@ -69,18 +67,61 @@ __device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, fl
   for (int e = 0; e < 8; ++e) { f[e] = (float)a[e]; f[8 + e] = (float)b[e]; }
 }
 
+// Running softmax state of one slot lane-group: per head the maximum so far, the
+// normaliser and this lane's 16 channels of the un-normalised output.
+template <int G>
+struct Stream {
+  float m[G], l[G], acc[G][16];
+};
+
+// Fold a batch of R slots into the running state.  s[r][h] are the slots' scores,
+// vf[r] the value channels owned by this lane, vsc[r] the value scale, ok[r] validity.
+template <int G, int R>
+__device__ __forceinline__ void fold_batch(Stream<G> &st, const float (&s)[R][G],
+                                           const float (&vf)[R][16], const float (&vsc)[R],
+                                           const bool (&ok)[R]) {
+  const float NEG = -INFINITY;
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    float bm = NEG;
+#pragma unroll
+    for (int r = 0; r < R; ++r) bm = ok[r] ? fmaxf(bm, s[r][h]) : bm;
+    const float mn = fmaxf(st.m[h], bm);
+    const float corr = (mn == NEG) ? 1.f : __expf(st.m[h] - mn);
+    st.m[h] = mn;
+    float p[R], lsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      p[r] = ok[r] ? __expf(s[r][h] - mn) : 0.f;
+      lsum += p[r];
+      p[r] *= vsc[r];
+    }
+    st.l[h] = fmaf(st.l[h], corr, lsum);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float t = st.acc[h][e] * corr;
+#pragma unroll
+      for (int r = 0; r < R; ++r) t = fmaf(p[r], vf[r][e], t);
+      st.acc[h][e] = t;
+    }
+  }
+}
+
 template <int D, int G>
 __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
                                                              int S) {
   constexpr int LPT = D / 16;            // lanes per slot row
   constexpr int TW = kWave / LPT;        // slots per wavefront pass
   constexpr int TB = kAttWaves * TW;     // slots per workgroup pass
+  constexpr int R8 = 4, R16 = 2;         // slots per lane-group per loop trip (INT8 / FP16)
   extern __shared__ float smem[];
-  float *stash = smem;                   // [G][S] scores, then probabilities
-  float *red = stash + (size_t)G * S;    // [4][G][D] cross-wave reduction of o
-  float *wred = red + kAttWaves * G * D; // [4][G] per-wave max / sum
-  double *fac = (double *)(wred + kAttWaves * G + (((kAttWaves * G) & 1) ? 1 : 0));  // [G]
-  __shared__ int s_last, s_ok;
+  float *stash = smem;                          // [G][S] raw scores of the slice
+  float *wo = stash + (size_t)G * S;            // [4][G][D] per-wave un-normalised output
+  float *wm = wo + kAttWaves * G * D;           // [4][G] per-wave maximum
+  float *wl = wm + kAttWaves * G;               // [4][G] per-wave normaliser
+  float *gm = wl + kAttWaves * G;               // [G] global maximum (mass phase)
+  double *ginv = (double *)(gm + G + (G & 1));  // [G] 1 / global normaliser
+  __shared__ int s_ok;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int c = lane % LPT, ts = lane / LPT;
@@ -133,295 +174,242 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   const int hi8 = min(hi, n8), lo16 = max(lo, n8);
   const float sm = a.sm_scale;
 
-  // ================= K pass: scores of the slice =================
-  float mx[G];
+  // ================= one streaming pass over the slice =================
+  Stream<G> st;
 #pragma unroll
-  for (int h = 0; h < G; ++h) mx[h] = NEG;
+  for (int h = 0; h < G; ++h) {
+    st.m[h] = NEG;
+    st.l[h] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) st.acc[h][e] = 0.f;
+  }
+  float qf[G][16];
   {
-    float qf[G][16];
     const int Hq = cv.Hkv * G;
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       const int4 *qp = (const int4 *)(a.q + ((size_t)(b * Hq + g * G + h)) * D + c * 16);
       unpack_h16x16(qp[0], qp[1], qf[h]);
     }
-    // INT8 slots
-    for (int base = lo; base < hi8; base += TB * kUnroll) {
-      int4 kr[kUnroll];
-      float sc[kUnroll];
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        kr[r] = make_int4(0, 0, 0, 0);
-        sc[r] = 0.f;
-        if (i < hi8) {
-          kr[r] = *(const int4 *)(K8 + (size_t)i * D + c * 16);
-          sc[r] = __half2float(KS[i]);
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        float kf[16], part[G];
-        unpack_i8x16(kr[r], kf);
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          float acc = 0.f;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc = fmaf(qf[h][e], kf[e], acc);
-          part[h] = acc;
-        }
-#pragma unroll
-        for (int m = 1; m < LPT; m <<= 1) {
-#pragma unroll
-          for (int h = 0; h < G; ++h) part[h] += __shfl_xor(part[h], m, kWave);
-        }
-        if (i < hi8) {
-          const float f = sc[r] * sm;
-#pragma unroll
-          for (int h = 0; h < G; ++h) {
-            const float s = part[h] * f;
-            mx[h] = fmaxf(mx[h], s);
-            if (c == 0) stash[h * S + (i - lo)] = s;
-          }
-        }
-      }
-    }
-    // FP16 slots (ring)
-    for (int base = lo16; base < hi; base += TB * kUnroll) {
-      int4 kr[kUnroll][2];
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        kr[r][0] = kr[r][1] = make_int4(0, 0, 0, 0);
-        if (i < hi) {
-          const int4 *p = (const int4 *)(K16 + (size_t)ring_row(h16, i - n8, cap16) * D + c * 16);
-          kr[r][0] = p[0];
-          kr[r][1] = p[1];
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        float kf[16], part[G];
-        unpack_h16x16(kr[r][0], kr[r][1], kf);
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          float acc = 0.f;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc = fmaf(qf[h][e], kf[e], acc);
-          part[h] = acc;
-        }
-#pragma unroll
-        for (int m = 1; m < LPT; m <<= 1) {
-#pragma unroll
-          for (int h = 0; h < G; ++h) part[h] += __shfl_xor(part[h], m, kWave);
-        }
-        if (i < hi) {
-#pragma unroll
-          for (int h = 0; h < G; ++h) {
-            const float s = part[h] * sm;
-            mx[h] = fmaxf(mx[h], s);
-            if (c == 0) stash[h * S + (i - lo)] = s;
-          }
-        }
-      }
-    }
   }
-  // slice maximum per head
+  // INT8 slots
+  for (int base = lo; base < hi8; base += TB * R8) {
+    int4 kr[R8], vr[R8];
+    float ksc[R8], vsc[R8];
+    bool ok[R8];
+#pragma unroll
+    for (int r = 0; r < R8; ++r) {
+      const int i = base + r * TB + w * TW + ts;
+      ok[r] = i < hi8;
+      kr[r] = vr[r] = make_int4(0, 0, 0, 0);
+      ksc[r] = vsc[r] = 0.f;
+      if (ok[r]) {
+        kr[r] = *(const int4 *)(K8 + (size_t)i * D + c * 16);
+        vr[r] = *(const int4 *)(V8 + (size_t)i * D + c * 16);
+        ksc[r] = __half2float(KS[i]);
+        vsc[r] = __half2float(VS[i]);
+      }
+    }
+    float s[R8][G], vf[R8][16];
+#pragma unroll
+    for (int r = 0; r < R8; ++r) {
+      float kf[16];
+      unpack_i8x16(kr[r], kf);
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc = fmaf(qf[h][e], kf[e], acc);
+        s[r][h] = acc;
+      }
+    }
+#pragma unroll
+    for (int m = 1; m < LPT; m <<= 1) {
+#pragma unroll
+      for (int r = 0; r < R8; ++r)
+#pragma unroll
+        for (int h = 0; h < G; ++h) s[r][h] += __shfl_xor(s[r][h], m, kWave);
+    }
+#pragma unroll
+    for (int r = 0; r < R8; ++r) {
+      const int i = base + r * TB + w * TW + ts;
+      const float f = ksc[r] * sm;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        s[r][h] *= f;
+        if (ok[r] && c == 0) stash[h * S + (i - lo)] = s[r][h];
+      }
+      unpack_i8x16(vr[r], vf[r]);
+    }
+    fold_batch<G, R8>(st, s, vf, vsc, ok);
+  }
+  // FP16 slots (ring)
+  for (int base = lo16; base < hi; base += TB * R16) {
+    int4 kr[R16][2], vr[R16][2];
+    float vsc[R16];
+    bool ok[R16];
+#pragma unroll
+    for (int r = 0; r < R16; ++r) {
+      const int i = base + r * TB + w * TW + ts;
+      ok[r] = i < hi;
+      vsc[r] = 1.f;
+      kr[r][0] = kr[r][1] = vr[r][0] = vr[r][1] = make_int4(0, 0, 0, 0);
+      if (ok[r]) {
+        const size_t off = (size_t)ring_row(h16, i - n8, cap16) * D + c * 16;
+        const int4 *pk = (const int4 *)(K16 + off), *pv = (const int4 *)(V16 + off);
+        kr[r][0] = pk[0]; kr[r][1] = pk[1];
+        vr[r][0] = pv[0]; vr[r][1] = pv[1];
+      }
+    }
+    float s[R16][G], vf[R16][16];
+#pragma unroll
+    for (int r = 0; r < R16; ++r) {
+      float kf[16];
+      unpack_h16x16(kr[r][0], kr[r][1], kf);
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc = fmaf(qf[h][e], kf[e], acc);
+        s[r][h] = acc;
+      }
+    }
+#pragma unroll
+    for (int m = 1; m < LPT; m <<= 1) {
+#pragma unroll
+      for (int r = 0; r < R16; ++r)
+#pragma unroll
+        for (int h = 0; h < G; ++h) s[r][h] += __shfl_xor(s[r][h], m, kWave);
+    }
+#pragma unroll
+    for (int r = 0; r < R16; ++r) {
+      const int i = base + r * TB + w * TW + ts;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        s[r][h] *= sm;
+        if (ok[r] && c == 0) stash[h * S + (i - lo)] = s[r][h];
+      }
+      unpack_h16x16(vr[r][0], vr[r][1], vf[r]);
+    }
+    fold_batch<G, R16>(st, s, vf, vsc, ok);
+  }
+
+  // ---- merge the slot lane-groups of the wavefront, then the four wavefronts ----
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    mx[h] = wave_max(mx[h]);
-    if (lane == 0) wred[w * G + h] = mx[h];
-  }
-  __syncthreads();
-  float mloc[G], lloc[G];
+    const float mw = wave_max(st.m[h]);
+    const float f = (st.m[h] == NEG) ? 0.f : __expf(st.m[h] - mw);
+    float l = st.l[h] * f;
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    mloc[h] = fmaxf(fmaxf(wred[h], wred[G + h]), fmaxf(wred[2 * G + h], wred[3 * G + h]));
-    lloc[h] = 0.f;
-  }
-  // probabilities relative to the slice maximum, and the slice normaliser
+    for (int m = LPT; m < kWave; m <<= 1) l += __shfl_xor(l, m, kWave);
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    for (int t = tid; t < ntok; t += kAttThreads) {
-      const float p = expf(stash[h * S + t] - mloc[h]);
-      stash[h * S + t] = p;
-      lloc[h] += p;
+    for (int e = 0; e < 16; ++e) {
+      float t = st.acc[h][e] * f;
+#pragma unroll
+      for (int m = LPT; m < kWave; m <<= 1) t += __shfl_xor(t, m, kWave);
+      st.acc[h][e] = t;
     }
-    lloc[h] = wave_sum(lloc[h]);
-  }
-  __syncthreads();                        // wred (max) fully read, stash rewritten
-#pragma unroll
-  for (int h = 0; h < G; ++h)
-    if (lane == 0) wred[w * G + h] = lloc[h];
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < G; ++h) lloc[h] = (wred[h] + wred[G + h]) + (wred[2 * G + h] + wred[3 * G + h]);
-
-  float *ml = a.part_ml + ((size_t)ul * a.max_splits + j) * G * 2;
-  if (tid < G) {
-    st_agent(&ml[tid * 2 + 0], mloc[tid]);
-    st_agent(&ml[tid * 2 + 1], lloc[tid]);
-    wait_stores_done();
-  }
-  __syncthreads();
-  if (tid == 0)
-    __hip_atomic_fetch_add(&a.arrive_ml[ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-  // ================= V pass: un-normalised output of the slice =================
-  {
-    float acc[G][16];
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[h][e] = 0.f;
-
-    for (int base = lo; base < hi8; base += TB * kUnroll) {
-      int4 vr[kUnroll];
-      float sc[kUnroll];
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        vr[r] = make_int4(0, 0, 0, 0);
-        sc[r] = 0.f;
-        if (i < hi8) {
-          vr[r] = *(const int4 *)(V8 + (size_t)i * D + c * 16);
-          sc[r] = __half2float(VS[i]);
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        if (i < hi8) {
-          float vf[16];
-          unpack_i8x16(vr[r], vf);
-#pragma unroll
-          for (int h = 0; h < G; ++h) {
-            const float p = stash[h * S + (i - lo)] * sc[r];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
-          }
-        }
-      }
-    }
-    for (int base = lo16; base < hi; base += TB * kUnroll) {
-      int4 vr[kUnroll][2];
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        vr[r][0] = vr[r][1] = make_int4(0, 0, 0, 0);
-        if (i < hi) {
-          const int4 *p = (const int4 *)(V16 + (size_t)ring_row(h16, i - n8, cap16) * D + c * 16);
-          vr[r][0] = p[0];
-          vr[r][1] = p[1];
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        const int i = base + r * TB + w * TW + ts;
-        if (i < hi) {
-          float vf[16];
-          unpack_h16x16(vr[r][0], vr[r][1], vf);
-#pragma unroll
-          for (int h = 0; h < G; ++h) {
-            const float p = stash[h * S + (i - lo)];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
-          }
-        }
-      }
-    }
-    // sum over the slot lanes of the wavefront, then over the four wavefronts
-#pragma unroll
-    for (int m = LPT; m < kWave; m <<= 1) {
-#pragma unroll
-      for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[h][e] += __shfl_xor(acc[h][e], m, kWave);
-    }
+    if (lane == 0) { wm[w * G + h] = mw; wl[w * G + h] = l; }
     if (ts == 0) {
 #pragma unroll
-      for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) red[(w * G + h) * D + c * 16 + e] = acc[h][e];
+      for (int e = 0; e < 16; ++e) wo[(w * G + h) * D + c * 16 + e] = st.acc[h][e];
     }
   }
   __syncthreads();
+  float *ml = a.part_ml + ((size_t)ul * a.max_splits + j) * G * 2;
   float *po = a.part_o + ((size_t)ul * a.max_splits + j) * G * D;
   for (int idx = tid; idx < G * D; idx += kAttThreads) {
-    st_agent(&po[idx],
-             (red[idx] + red[G * D + idx]) + (red[2 * G * D + idx] + red[3 * G * D + idx]));
+    const int h = idx / D;
+    const float M = fmaxf(fmaxf(wm[h], wm[G + h]), fmaxf(wm[2 * G + h], wm[3 * G + h]));
+    float o = 0.f, l = 0.f;
+#pragma unroll
+    for (int k = 0; k < kAttWaves; ++k) {
+      const float mk = wm[k * G + h];
+      const float f = (mk == NEG) ? 0.f : __expf(mk - M);
+      o = fmaf(wo[k * G * D + idx], f, o);
+      l = fmaf(wl[k * G + h], f, l);
+    }
+    st_agent(&po[idx], o);
+    if (idx % D == 0) {
+      st_agent(&ml[h * 2 + 0], M);
+      st_agent(&ml[h * 2 + 1], l);
+    }
   }
   wait_stores_done();
   __syncthreads();
   if (tid == 0) {
-    const unsigned ticket = __hip_atomic_fetch_add(&a.arrive_o[ul], 1u, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (ticket == a.arrive_base + (unsigned)ns - 1u);
-  }
-  __syncthreads();
-  if (s_last) {
-    // ---- last arrival: merge the splits (online-softmax merge) and write out ----
-    const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
-    const float *pou = a.part_o + (size_t)ul * a.max_splits * G * D;
-    const int Hq = cv.Hkv * G;
-    for (int idx = tid; idx < G * D; idx += kAttThreads) {
-      const int h = idx / D;
-      float M = NEG;
-      for (int s = 0; s < ns; ++s) M = fmaxf(M, ld_agent(&mlu[(s * G + h) * 2]));
-      float L = 0.f, o = 0.f;
-      for (int s = 0; s < ns; ++s) {
-        const float ms = ld_agent(&mlu[(s * G + h) * 2]);
-        if (ms > NEG) {
-          const float wgt = expf(ms - M);
-          L += wgt * ld_agent(&mlu[(s * G + h) * 2 + 1]);
-          o += wgt * ld_agent(&pou[(size_t)s * G * D + idx]);
-        }
-      }
-      a.out[((size_t)(b * Hq + g * G)) * D + idx] = __float2half_rn(o / L);
-    }
-  }
-
-  // ================= mass + EMA =================
-  if (ns > 1) {
-    if (tid == 0) {
+    __hip_atomic_fetch_add(&a.arrive[ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int ok = 1;
+    if (ns > 1) {
+      // bounded wait until all splits of the unit have published
       const unsigned want = a.arrive_base + (unsigned)ns;
-      int spins = 0, ok = 1;
-      while ((int)(__hip_atomic_load(&a.arrive_ml[ul], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+      int spins = 0;
+      while ((int)(__hip_atomic_load(&a.arrive[ul], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                    want) < 0) {
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(2);
         if (++spins > kSpinLimit) { ok = 0; break; }
       }
       if (!ok) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
-      s_ok = ok;
     }
-    __syncthreads();
-    if (!s_ok) return;
-  } else {
-    __syncthreads();
-  }
-  if (tid < G) {
-    const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
-    float M = NEG;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, ld_agent(&mlu[(s * G + tid) * 2]));
-    double L = 0.0;
-    for (int s = 0; s < ns; ++s) {
-      const float ms = ld_agent(&mlu[(s * G + tid) * 2]);
-      if (ms > NEG) L += exp((double)ms - (double)M) * (double)ld_agent(&mlu[(s * G + tid) * 2 + 1]);
-    }
-    const float mine = ld_agent(&mlu[(j * G + tid) * 2]);
-    fac[tid] = (mine > NEG) ? exp((double)mine - (double)M) / L : 0.0;
+    s_ok = ok;
   }
   __syncthreads();
+  if (!s_ok) return;
+
+  // ---- all (m, l) partials of the unit -> LDS in one round trip; global (M, 1/L) ----
+  const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
+  float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
+  for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
+  __syncthreads();
+  if (tid < G) {
+    float M = NEG;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, pml[(s * G + tid) * 2]);
+    double L = 0.0;
+    for (int s = 0; s < ns; ++s) {
+      const float ms = pml[(s * G + tid) * 2];
+      if (ms > NEG) L += exp((double)ms - (double)M) * (double)pml[(s * G + tid) * 2 + 1];
+    }
+    gm[tid] = M;
+    ginv[tid] = 1.0 / L;
+  }
+  __syncthreads();
+
+  // ---- mass + EMA of the slice (EMA reads go out first, the output merge overlaps them) ----
   const double lam = (double)a.ema_decay, oml = 1.0 - lam;
   for (int t = tid; t < ntok; t += kAttThreads) {
-    double A = 0.0;
-#pragma unroll
-    for (int h = 0; h < G; ++h) A += (double)stash[h * S + t] * fac[h];
     const int slot = lo + t;
     const double old = (slot == n - 1) ? 0.0 : (double)EMA[slot];
+    double A = 0.0;
+#pragma unroll
+    for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
     EMA[slot] = (float)(lam * old + oml * A);
+  }
+
+  // ---- this split normalises its share of the unit's output (online-softmax merge) ----
+  {
+    const float *pou = a.part_o + (size_t)ul * a.max_splits * G * D;
+    const int Hq = cv.Hkv * G;
+    const int per = (G * D + ns - 1) / ns;
+    const int i1 = min(G * D, (j + 1) * per);
+    for (int idx = j * per + tid; idx < i1; idx += kAttThreads) {
+      const int h = idx / D;
+      const float M = gm[h];
+      float o = 0.f;
+      for (int s0 = 0; s0 < ns; s0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          v[k] = (s0 + k < ns) ? ld_agent(&pou[(size_t)(s0 + k) * G * D + idx]) : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          if (s0 + k < ns) {
+            const float ms = pml[((s0 + k) * G + h) * 2];
+            if (ms > NEG) o = fmaf(v[k], expf(ms - M), o);
+          }
+        }
+      }
+      a.out[((size_t)(b * Hq + g * G)) * D + idx] = __float2half_rn((float)((double)o * ginv[h]));
+    }
   }
 }
 
@@ -443,7 +431,7 @@ static AttendFn attend_fn(int D, int G) {
 bool attend_supported(int D, int G) { return attend_fn(D, G) != nullptr; }
 
 static size_t attend_lds_bytes(int D, int G, int S) {
-  size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + kAttWaves * G + 1;
+  size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + 2 * kAttWaves * G + G + 2;
   return floats * sizeof(float) + (size_t)G * sizeof(double) + 16;
 }
 

@@ -27,8 +27,7 @@ struct AttendLaunch {
   __half *out;
   float *part_ml;          // [units per layer][max splits][G][2]
   float *part_o;           // [units per layer][max splits][G][D]
-  unsigned *arrive_ml;     // [units per layer], this layer's counters
-  unsigned *arrive_o;      // [units per layer]
+  unsigned *arrive;        // [units per layer], this layer's arrival counters
   unsigned arrive_base;    // counter value before this launch
   int max_splits;
   float sm_scale, ema_decay;
