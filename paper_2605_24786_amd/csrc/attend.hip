@@ -7,21 +7,28 @@
 // unit (b, kv-head) each stream a contiguous, byte-balanced slice of the unit's slots once
 // and serve all G query heads of the group from that single read:
 //
-//   stream   every slot lane-group keeps a running (max, normaliser, output) per head
-//            (online softmax); raw scores s[h][i] of the slice stay in LDS
-//   publish  lane-groups -> wavefront -> workgroup merge; (m, l, o) -> global, arrive; the
-//            last workgroup to arrive merges the splits' partials into out
-//   mass     the others wait until every split of the unit has arrived (they all publish
-//            at about the same time), form the exact global (M, L), then per slot
-//            A_i = sum_h e^{s[h][i]-M[h]} / L[h] and ema_i <- lambda ema_i + (1-lambda) A_i.
+//   stream   running (max, normaliser, output) per head (online softmax); the raw scores
+//            s[h][i] of the slice stay in LDS
+//   publish  workgroup merge; (m, l, o) -> global, arrive
+//   mass     wait until every split of the unit has arrived (they all publish at about the
+//            same time), form the exact global (M, L), then per slot
+//            A_i = sum_h e^{s[h][i]-M[h]} / L[h] and ema_i <- lambda ema_i + (1-lambda) A_i;
+//            every split also normalises its share of the unit's output row.
 //
 // Every K/V byte is read once; the scores never leave the chip.  The wait is between
 // workgroups of one launch, so the host only launches grids that are co-resident
 // (splits * units <= occupancy * CUs) and the wait itself is bounded.
 //
-// Lane mapping: a slot's row is D channels; lane c of a group of D/16 lanes owns channels
-// [16c, 16c+16) -- one 128-bit load of an INT8 row, two of an FP16 row -- so a wavefront
-// load instruction covers 64/(D/16) whole rows, contiguous in memory.
+// Two streaming bodies share the prologue and the epilogue:
+//   * vector-ALU body (any G, any D): lane c of a group of D/16 lanes owns channels
+//     [16c, 16c+16) of a slot row, so a wavefront load covers whole rows, contiguous in
+//     memory; each lane-group keeps its own running softmax state.
+//   * matrix-core body (G >= 2, D = 128) for the INT8 slots: the G query heads against a
+//     32-slot tile are two small contractions (scores: [G x 128] x [128 x 32]; output:
+//     [G x 32] x [32 x 128]) issued as v_mfma_f32_16x16x32_f16 with the head dimension
+//     padded to 16.  The vector ALU then only converts int8 -> fp16 and keeps the softmax
+//     state, which is what lets the kernel stay memory-bound for grouped-query shapes.
+//     FP16 slots (at most W + 1 per unit) still take the vector-ALU body.
 #include <algorithm>
 #include <map>
 #include <tuple>
@@ -35,16 +42,9 @@ constexpr int kAttThreads = 256;
 constexpr int kAttWaves = 4;
 constexpr int kSpinLimit = 4000000;
 
-__device__ __forceinline__ void unpack_i8x16(const int4 &r, float (&f)[16]) {
-  const int wds[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) f[4 * k + e] = (float)((wds[k] << (24 - 8 * e)) >> 24);
-  }
-}
-
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 // Partials travel between workgroups (possibly on different XCDs, whose L2s are not
 // coherent for ordinary accesses) through agent-scope relaxed atomics: such loads and
@@ -61,17 +61,101 @@ __device__ __forceinline__ float ld_agent(const float *p) {
 }
 __device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0); }
 
+// LDS traffic between lanes of one wavefront: LDS operations of a wavefront execute in
+// program order, so a compiler-level barrier is all that is needed between a write phase
+// and the read phase that consumes other lanes' data.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ void unpack_i8x16(const int4 &r, float (&f)[16]) {
+  const int wds[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[4 * k + e] = (float)((wds[k] << (24 - 8 * e)) >> 24);
+  }
+}
+
 __device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, float (&f)[16]) {
   half8_t a = __builtin_bit_cast(half8_t, r0), b = __builtin_bit_cast(half8_t, r1);
 #pragma unroll
   for (int e = 0; e < 8; ++e) { f[e] = (float)a[e]; f[8 + e] = (float)b[e]; }
 }
 
+// ---------------------------------------------------------------------------------------
+// Slice bookkeeping shared by both bodies
+// ---------------------------------------------------------------------------------------
+struct Slice {
+  int u, ul, b, g, j;          // unit, unit within the layer, batch, kv-head, split
+  int n, n8, h16, n16;         // length with the append, INT8 slots, ring head, FP16 slots
+  int lo, hi, hi8, lo16, ntok; // slot range of this split
+};
+
+__device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLaunch &a, int ns, int S) {
+  Slice s;
+  s.ul = blockIdx.y;
+  s.j = blockIdx.x;
+  s.u = a.layer * cv.B * cv.Hkv + s.ul;
+  s.b = s.ul / cv.Hkv;
+  s.g = s.ul % cv.Hkv;
+  s.n8 = cv.n8[s.u];
+  s.n = cv.len[s.u] + 1;                  // the appended token included
+  s.h16 = cv.head16[s.u];
+  s.n16 = s.n - s.n8;
+  // byte-balanced split: an FP16 slot weighs two INT8 slots; rounding down keeps the tail
+  // slice non-empty, so its owner always holds slot n-1
+  const long long nv = (long long)s.n8 + 2ll * s.n16;
+  const long long vlo = nv * s.j / ns, vhi = nv * (s.j + 1) / ns;
+  s.lo = vlo <= s.n8 ? (int)vlo : s.n8 + (int)((vlo - s.n8) >> 1);
+  s.hi = vhi <= s.n8 ? (int)vhi : s.n8 + (int)((vhi - s.n8) >> 1);
+  if (s.hi - s.lo > S) {                  // cannot happen when the host plan is right
+    if (threadIdx.x == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+    s.hi = s.lo + S;
+  }
+  s.ntok = s.hi - s.lo;
+  s.hi8 = min(s.hi, s.n8);
+  s.lo16 = max(s.lo, s.n8);
+  return s;
+}
+
+// The workgroup that owns the tail writes the new token into the FP16 ring.
+template <int D>
+__device__ __forceinline__ void append_new_token(const CacheView &cv, const AttendLaunch &a,
+                                                 const Slice &s, int ns) {
+  if (s.j != ns - 1) return;
+  const int tid = threadIdx.x;
+  const int row = ring_row(s.h16, s.n16 - 1, cv.cap16);
+  __half *K16 = cv.k16 + ((size_t)s.u * cv.cap16 + row) * D;
+  __half *V16 = cv.v16 + ((size_t)s.u * cv.cap16 + row) * D;
+  if (tid < D / 8) {
+    ((int4 *)K16)[tid] = ((const int4 *)(a.knew + (size_t)s.ul * D))[tid];
+  } else if (tid < D / 4) {
+    ((int4 *)V16)[tid - D / 8] = ((const int4 *)(a.vnew + (size_t)s.ul * D))[tid - D / 8];
+  }
+  if (tid == 0) cv.pos[(size_t)s.u * cv.cap + s.n - 1] = a.pos_new;
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------
+// Vector-ALU streaming body
+// ---------------------------------------------------------------------------------------
+
 // Running softmax state of one slot lane-group: per head the maximum so far, the
 // normaliser and this lane's 16 channels of the un-normalised output.
 template <int G>
 struct Stream {
   float m[G], l[G], acc[G][16];
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      m[h] = -INFINITY;
+      l[h] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[h][e] = 0.f;
+    }
+  }
 };
 
 // Fold a batch of R slots into the running state.  s[r][h] are the slots' scores,
@@ -108,99 +192,38 @@ __device__ __forceinline__ void fold_batch(Stream<G> &st, const float (&s)[R][G]
 }
 
 template <int D, int G>
-__global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
-                                                             int S) {
-  constexpr int LPT = D / 16;            // lanes per slot row
-  constexpr int TW = kWave / LPT;        // slots per wavefront pass
-  constexpr int TB = kAttWaves * TW;     // slots per workgroup pass
-  constexpr int R8 = 4, R16 = 2;         // slots per lane-group per loop trip (INT8 / FP16)
-  extern __shared__ float smem[];
-  float *stash = smem;                          // [G][S] raw scores of the slice
-  float *wo = stash + (size_t)G * S;            // [4][G][D] per-wave un-normalised output
-  float *wm = wo + kAttWaves * G * D;           // [4][G] per-wave maximum
-  float *wl = wm + kAttWaves * G;               // [4][G] per-wave normaliser
-  float *gm = wl + kAttWaves * G;               // [G] global maximum (mass phase)
-  double *ginv = (double *)(gm + G + (G & 1));  // [G] 1 / global normaliser
-  __shared__ int s_ok;
-
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int c = lane % LPT, ts = lane / LPT;
-  const int ul = blockIdx.y, j = blockIdx.x;
-  const int UPL = cv.B * cv.Hkv;
-  const int u = a.layer * UPL + ul;
-  const int b = ul / cv.Hkv, g = ul % cv.Hkv;
-  const int cap = cv.cap, cap8 = cv.cap8, cap16 = cv.cap16;
-  const int n8 = cv.n8[u];
-  const int n = cv.len[u] + 1;           // the appended token included
-  const int h16 = cv.head16[u];
-  const int n16 = n - n8;
-  const float NEG = -INFINITY;
-
-  // byte-balanced split: an FP16 slot weighs two INT8 slots
-  const long long nv = (long long)n8 + 2ll * n16;
-  const long long vlo = nv * j / ns, vhi = nv * (j + 1) / ns;
-  // (rounding down keeps the tail slice non-empty, so its owner always holds slot n-1)
-  int lo = vlo <= n8 ? (int)vlo : n8 + (int)((vlo - n8) >> 1);
-  int hi = vhi <= n8 ? (int)vhi : n8 + (int)((vhi - n8) >> 1);
-  if (hi - lo > S) {                     // cannot happen when the host plan is right
-    if (tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
-    hi = lo + S;
-  }
-  const int ntok = hi - lo;
-
-  const int8_t *K8 = cv.k8 + (size_t)u * cap8 * D;
-  const int8_t *V8 = cv.v8 + (size_t)u * cap8 * D;
-  const __half *KS = cv.ks + (size_t)u * cap8;
-  const __half *VS = cv.vs + (size_t)u * cap8;
-  __half *K16 = cv.k16 + (size_t)u * cap16 * D;
-  __half *V16 = cv.v16 + (size_t)u * cap16 * D;
-  float *EMA = cv.ema + (size_t)u * cap;
-
-  // ---- append: the workgroup that owns the tail writes the new token into the ring ----
-  if (j == ns - 1) {
-    const int row = ring_row(h16, n16 - 1, cap16);
-    if (tid < D / 8) {
-      const int4 *src = (const int4 *)(a.knew + (size_t)ul * D);
-      ((int4 *)(K16 + (size_t)row * D))[tid] = src[tid];
-    } else if (tid < D / 4) {
-      const int t = tid - D / 8;
-      const int4 *src = (const int4 *)(a.vnew + (size_t)ul * D);
-      ((int4 *)(V16 + (size_t)row * D))[t] = src[t];
-    }
-    if (tid == 0) cv.pos[(size_t)u * cap + n - 1] = a.pos_new;
-    __syncthreads();
-  }
-
-  const int hi8 = min(hi, n8), lo16 = max(lo, n8);
-  const float sm = a.sm_scale;
-
-  // ================= one streaming pass over the slice =================
-  Stream<G> st;
+__device__ __forceinline__ void load_q_slices(const CacheView &cv, const AttendLaunch &a,
+                                              const Slice &sl, float (&qf)[G][16]) {
+  constexpr int LPT = D / 16;
+  const int c = (threadIdx.x & 63) % LPT;
+  const int Hq = cv.Hkv * G;
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    st.m[h] = NEG;
-    st.l[h] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) st.acc[h][e] = 0.f;
+    const int4 *qp = (const int4 *)(a.q + ((size_t)(sl.b * Hq + sl.g * G + h)) * D + c * 16);
+    unpack_h16x16(qp[0], qp[1], qf[h]);
   }
-  float qf[G][16];
-  {
-    const int Hq = cv.Hkv * G;
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const int4 *qp = (const int4 *)(a.q + ((size_t)(b * Hq + g * G + h)) * D + c * 16);
-      unpack_h16x16(qp[0], qp[1], qf[h]);
-    }
-  }
-  // INT8 slots
-  for (int base = lo; base < hi8; base += TB * R8) {
+}
+
+// INT8 slots [lo, hi8) on the vector ALU.
+template <int D, int G>
+__device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slice &sl, float sm,
+                                                 const float (&qf)[G][16], Stream<G> &st,
+                                                 float *stash, int S) {
+  constexpr int LPT = D / 16, TW = kWave / LPT, TB = kAttWaves * TW, R8 = 4;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane % LPT, ts = lane / LPT;
+  const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
+  const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
+  const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
+  const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
+  for (int base = sl.lo; base < sl.hi8; base += TB * R8) {
     int4 kr[R8], vr[R8];
     float ksc[R8], vsc[R8];
     bool ok[R8];
 #pragma unroll
     for (int r = 0; r < R8; ++r) {
       const int i = base + r * TB + w * TW + ts;
-      ok[r] = i < hi8;
+      ok[r] = i < sl.hi8;
       kr[r] = vr[r] = make_int4(0, 0, 0, 0);
       ksc[r] = vsc[r] = 0.f;
       if (ok[r]) {
@@ -237,25 +260,36 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         s[r][h] *= f;
-        if (ok[r] && c == 0) stash[h * S + (i - lo)] = s[r][h];
+        if (ok[r] && c == 0) stash[h * S + (i - sl.lo)] = s[r][h];
       }
       unpack_i8x16(vr[r], vf[r]);
     }
     fold_batch<G, R8>(st, s, vf, vsc, ok);
   }
-  // FP16 slots (ring)
-  for (int base = lo16; base < hi; base += TB * R16) {
+}
+
+// FP16 ring slots [lo16, hi) on the vector ALU.
+template <int D, int G>
+__device__ __forceinline__ void stream_fp16_valu(const CacheView &cv, const Slice &sl, float sm,
+                                                 const float (&qf)[G][16], Stream<G> &st,
+                                                 float *stash, int S) {
+  constexpr int LPT = D / 16, TW = kWave / LPT, TB = kAttWaves * TW, R16 = 2;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane % LPT, ts = lane / LPT;
+  const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
+  const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
+  for (int base = sl.lo16; base < sl.hi; base += TB * R16) {
     int4 kr[R16][2], vr[R16][2];
     float vsc[R16];
     bool ok[R16];
 #pragma unroll
     for (int r = 0; r < R16; ++r) {
       const int i = base + r * TB + w * TW + ts;
-      ok[r] = i < hi;
+      ok[r] = i < sl.hi;
       vsc[r] = 1.f;
       kr[r][0] = kr[r][1] = vr[r][0] = vr[r][1] = make_int4(0, 0, 0, 0);
       if (ok[r]) {
-        const size_t off = (size_t)ring_row(h16, i - n8, cap16) * D + c * 16;
+        const size_t off = (size_t)ring_row(sl.h16, i - sl.n8, cv.cap16) * D + c * 16;
         const int4 *pk = (const int4 *)(K16 + off), *pv = (const int4 *)(V16 + off);
         kr[r][0] = pk[0]; kr[r][1] = pk[1];
         vr[r][0] = pv[0]; vr[r][1] = pv[1];
@@ -287,14 +321,23 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         s[r][h] *= sm;
-        if (ok[r] && c == 0) stash[h * S + (i - lo)] = s[r][h];
+        if (ok[r] && c == 0) stash[h * S + (i - sl.lo)] = s[r][h];
       }
       unpack_h16x16(vr[r][0], vr[r][1], vf[r]);
     }
     fold_batch<G, R16>(st, s, vf, vsc, ok);
   }
+}
 
-  // ---- merge the slot lane-groups of the wavefront, then the four wavefronts ----
+// Merge the slot lane-groups of a wavefront and store the wavefront's partial
+// (m, l, o[G][D]) as entry `pidx` of the workgroup's LDS partial arrays.
+template <int D, int G>
+__device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, float *wm, float *wl,
+                                                     float *wo) {
+  constexpr int LPT = D / 16;
+  const int lane = threadIdx.x & 63;
+  const int c = lane % LPT, ts = lane / LPT;
+  const float NEG = -INFINITY;
 #pragma unroll
   for (int h = 0; h < G; ++h) {
     const float mw = wave_max(st.m[h]);
@@ -309,21 +352,35 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
       for (int m = LPT; m < kWave; m <<= 1) t += __shfl_xor(t, m, kWave);
       st.acc[h][e] = t;
     }
-    if (lane == 0) { wm[w * G + h] = mw; wl[w * G + h] = l; }
+    if (lane == 0) { wm[pidx * G + h] = mw; wl[pidx * G + h] = l; }
     if (ts == 0) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) wo[(w * G + h) * D + c * 16 + e] = st.acc[h][e];
+      for (int e = 0; e < 16; ++e) wo[(pidx * G + h) * D + c * 16 + e] = st.acc[h][e];
     }
   }
-  __syncthreads();
-  float *ml = a.part_ml + ((size_t)ul * a.max_splits + j) * G * 2;
-  float *po = a.part_o + ((size_t)ul * a.max_splits + j) * G * D;
+}
+
+// ---------------------------------------------------------------------------------------
+// Epilogue shared by both bodies.  On entry wm/wl/wo hold NP per-wavefront partials
+// (after a workgroup barrier); stash holds the slice's raw scores.
+// ---------------------------------------------------------------------------------------
+template <int D, int G, int NP>
+__device__ __forceinline__ void attend_epilogue(const CacheView &cv, const AttendLaunch &a,
+                                                const Slice &sl, int ns, int S, float *stash,
+                                                float *wm, float *wl, float *wo, float *gm,
+                                                double *ginv, int *s_ok) {
+  const int tid = threadIdx.x;
+  const float NEG = -INFINITY;
+  float *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
+  float *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
   for (int idx = tid; idx < G * D; idx += kAttThreads) {
     const int h = idx / D;
-    const float M = fmaxf(fmaxf(wm[h], wm[G + h]), fmaxf(wm[2 * G + h], wm[3 * G + h]));
+    float M = NEG;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) M = fmaxf(M, wm[k * G + h]);
     float o = 0.f, l = 0.f;
 #pragma unroll
-    for (int k = 0; k < kAttWaves; ++k) {
+    for (int k = 0; k < NP; ++k) {
       const float mk = wm[k * G + h];
       const float f = (mk == NEG) ? 0.f : __expf(mk - M);
       o = fmaf(wo[k * G * D + idx], f, o);
@@ -338,26 +395,26 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   wait_stores_done();
   __syncthreads();
   if (tid == 0) {
-    __hip_atomic_fetch_add(&a.arrive[ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(&a.arrive[sl.ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int ok = 1;
     if (ns > 1) {
       // bounded wait until all splits of the unit have published
       const unsigned want = a.arrive_base + (unsigned)ns;
       int spins = 0;
-      while ((int)(__hip_atomic_load(&a.arrive[ul], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+      while ((int)(__hip_atomic_load(&a.arrive[sl.ul], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                    want) < 0) {
         __builtin_amdgcn_s_sleep(2);
         if (++spins > kSpinLimit) { ok = 0; break; }
       }
       if (!ok) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
     }
-    s_ok = ok;
+    *s_ok = ok;
   }
   __syncthreads();
-  if (!s_ok) return;
+  if (!*s_ok) return;
 
   // ---- all (m, l) partials of the unit -> LDS in one round trip; global (M, 1/L) ----
-  const float *mlu = a.part_ml + (size_t)ul * a.max_splits * G * 2;
+  const float *mlu = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
   float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
   for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
   __syncthreads();
@@ -374,11 +431,12 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   }
   __syncthreads();
 
-  // ---- mass + EMA of the slice (EMA reads go out first, the output merge overlaps them) ----
+  // ---- mass + EMA of the slice ----
+  float *EMA = cv.ema + (size_t)sl.u * cv.cap;
   const double lam = (double)a.ema_decay, oml = 1.0 - lam;
-  for (int t = tid; t < ntok; t += kAttThreads) {
-    const int slot = lo + t;
-    const double old = (slot == n - 1) ? 0.0 : (double)EMA[slot];
+  for (int t = tid; t < sl.ntok; t += kAttThreads) {
+    const int slot = sl.lo + t;
+    const double old = (slot == sl.n - 1) ? 0.0 : (double)EMA[slot];
     double A = 0.0;
 #pragma unroll
     for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
@@ -387,11 +445,11 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
   {
-    const float *pou = a.part_o + (size_t)ul * a.max_splits * G * D;
+    const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
     const int Hq = cv.Hkv * G;
     const int per = (G * D + ns - 1) / ns;
-    const int i1 = min(G * D, (j + 1) * per);
-    for (int idx = j * per + tid; idx < i1; idx += kAttThreads) {
+    const int i1 = min(G * D, (sl.j + 1) * per);
+    for (int idx = sl.j * per + tid; idx < i1; idx += kAttThreads) {
       const int h = idx / D;
       const float M = gm[h];
       float o = 0.f;
@@ -408,9 +466,276 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
           }
         }
       }
-      a.out[((size_t)(b * Hq + g * G)) * D + idx] = __float2half_rn((float)((double)o * ginv[h]));
+      a.out[((size_t)(sl.b * Hq + sl.g * G)) * D + idx] = __float2half_rn((float)((double)o * ginv[h]));
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// Kernel 1: vector-ALU body for every slot
+// ---------------------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
+                                                             int S) {
+  constexpr int NP = kAttWaves;
+  extern __shared__ float smem[];
+  float *stash = smem;                          // [G][S] raw scores of the slice
+  float *wo = stash + (size_t)G * S;            // [NP][G][D] per-wave un-normalised output
+  float *wm = wo + NP * G * D;                  // [NP][G] per-wave maximum
+  float *wl = wm + NP * G;                      // [NP][G] per-wave normaliser
+  float *gm = wl + NP * G;                      // [G] global maximum
+  double *ginv = (double *)(gm + G + (G & 1));  // [G] 1 / global normaliser
+  __shared__ int s_ok;
+
+  const Slice sl = make_slice(cv, a, ns, S);
+  append_new_token<D>(cv, a, sl, ns);
+
+  Stream<G> st;
+  st.reset();
+  float qf[G][16];
+  load_q_slices<D, G>(cv, a, sl, qf);
+  stream_int8_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
+  stream_fp16_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
+  store_stream_partial<D, G>(st, threadIdx.x >> 6, wm, wl, wo);
+  __syncthreads();
+  attend_epilogue<D, G, NP>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+}
+
+// ---------------------------------------------------------------------------------------
+// Kernel 2: matrix-core body for the INT8 slots (D = 128), vector ALU for the FP16 slots
+// ---------------------------------------------------------------------------------------
+constexpr int kTile = 32;              // slots per wavefront tile
+constexpr int kKRow = 128 + 16;        // LDS row stride of the K tile (bytes)
+constexpr int kVRow = 32 + 4;          // LDS row stride of the transposed V tile (bytes)
+constexpr int kPRow = 32 + 8;          // LDS row stride of the probability tile (halfs)
+constexpr int kTileBytes = kTile * kKRow + 128 * kVRow + 16 * kPRow * 2;   // per wavefront
+
+// 4 int8 (one dword) -> 4 fp16 (two dwords), exact: c ^ 0x80 is c + 128 as an unsigned byte,
+// 0x6400 | byte is the fp16 number 1024 + byte, and subtracting 1152 leaves c.
+__device__ __forceinline__ void cvt_i8x4_f16x4(unsigned w, half2_t &lo, half2_t &hi) {
+  const unsigned x = w ^ 0x80808080u;
+  const unsigned a = __builtin_amdgcn_perm(x, 0x64646464u, 0x00050004u);
+  const unsigned b = __builtin_amdgcn_perm(x, 0x64646464u, 0x00070006u);
+  const half2_t bias = {(_Float16)1152.0f, (_Float16)1152.0f};
+  lo = __builtin_bit_cast(half2_t, a) - bias;
+  hi = __builtin_bit_cast(half2_t, b) - bias;
+}
+
+__device__ __forceinline__ half8_t cvt_i8x8_f16x8(unsigned w0, unsigned w1) {
+  half2_t p0, p1, p2, p3;
+  cvt_i8x4_f16x4(w0, p0, p1);
+  cvt_i8x4_f16x4(w1, p2, p3);
+  half8_t r;
+  r[0] = p0[0]; r[1] = p0[1]; r[2] = p1[0]; r[3] = p1[1];
+  r[4] = p2[0]; r[5] = p2[1]; r[6] = p3[0]; r[7] = p3[1];
+  return r;
+}
+
+// max / sum over the 16 lanes of a DPP row; every lane of the row gets the result
+#define CONFKV_DPP(v, ctrl) \
+  __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, false))
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, CONFKV_DPP(v, 0xB1));    // quad_perm [1,0,3,2]
+  v = fmaxf(v, CONFKV_DPP(v, 0x4E));    // quad_perm [2,3,0,1]
+  v = fmaxf(v, CONFKV_DPP(v, 0x141));   // row_half_mirror
+  v = fmaxf(v, CONFKV_DPP(v, 0x140));   // row_mirror
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += CONFKV_DPP(v, 0xB1);
+  v += CONFKV_DPP(v, 0x4E);
+  v += CONFKV_DPP(v, 0x141);
+  v += CONFKV_DPP(v, 0x140);
+  return v;
+}
+#undef CONFKV_DPP
+
+template <int G>
+__global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, AttendLaunch a,
+                                                                  int ns, int S) {
+  constexpr int D = 128;
+  constexpr int NP = 2 * kAttWaves;             // matrix-core partial + FP16 partial per wave
+  extern __shared__ float smem[];
+  float *stash = smem;                          // [G][S]
+  float *gm = stash + (size_t)G * S;            // [G]
+  double *ginv = (double *)(gm + G + (G & 1));  // [G]
+  float *wm = (float *)(ginv + G);              // [NP][G]
+  float *wl = wm + NP * G;                      // [NP][G]
+  // per-wave tile buffers (16-byte aligned), later the [NP][G][D] partials
+  float *tiles = (float *)(((uintptr_t)(wl + NP * G) + 15) & ~(uintptr_t)15);
+  float *wo = tiles;
+  __shared__ int s_ok;
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const Slice sl = make_slice(cv, a, ns, S);
+  append_new_token<D>(cv, a, sl, ns);
+  const float NEG = -INFINITY;
+  const float sm = a.sm_scale;
+
+  // ---------------- INT8 slots on the matrix cores ----------------
+  const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
+  const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
+  uint8_t *Kt = (uint8_t *)tiles + (size_t)w * kTileBytes;   // [32][kKRow]
+  uint8_t *Vt = Kt + kTile * kKRow;                           // [128][kVRow], slots permuted
+  _Float16 *Pb = (_Float16 *)(Vt + 128 * kVRow);              // [16][kPRow], rows >= G stay 0
+  for (int i = lane; i < 16 * kPRow / 2; i += kWave) ((unsigned *)Pb)[i] = 0u;
+
+  // A operand of the score contraction: Q padded to 16 rows; k-step s covers channels
+  // g4*32 + 8s + [0,8), matching the K bytes this lane reads from the tile below.
+  half8_t qa[4];
+  {
+    const int Hq = cv.Hkv * G;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      int4 raw = make_int4(0, 0, 0, 0);
+      if (t16 < G)
+        raw = *(const int4 *)(a.q + ((size_t)(sl.b * Hq + sl.g * G + t16)) * D + g4 * 32 + 8 * s);
+      qa[s] = __builtin_bit_cast(half8_t, raw);
+    }
+  }
+  floatx4_t O[8];
+#pragma unroll
+  for (int nt = 0; nt < 8; ++nt) O[nt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  float mrun[4], lrun[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { mrun[i] = NEG; lrun[i] = 0.f; }
+
+  const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
+  const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
+  const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
+  const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
+
+  const int ntiles = (sl.hi8 - sl.lo + kTile - 1) / kTile;     // <= 0 when no INT8 slot
+  int4 kq[4], vq[4];
+  float ksc[2], vsc[2];
+  auto issue_loads = [&](int tile) {
+    const int base = sl.lo + tile * kTile;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = base + 8 * r + r8;
+      kq[r] = vq[r] = make_int4(0, 0, 0, 0);
+      if (i < sl.hi8) {
+        kq[r] = *(const int4 *)(K8 + (size_t)i * D + c8 * 16);
+        vq[r] = *(const int4 *)(V8 + (size_t)i * D + c8 * 16);
+      }
+    }
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const int i = base + 16 * sb + t16;
+      ksc[sb] = vsc[sb] = 0.f;
+      if (i < sl.hi8) { ksc[sb] = __half2float(KS[i]); vsc[sb] = __half2float(VS[i]); }
+    }
+  };
+  if (w < ntiles) issue_loads(w);
+  for (int tile = w; tile < ntiles; tile += kAttWaves) {
+    const int base = sl.lo + tile * kTile;
+    // ---- registers -> LDS: K rows as they are, V transposed to [channel][slot] ----
+#pragma unroll
+    for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (8 * r + r8) * kKRow + c8 * 16) = kq[r];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const unsigned x0 = ((const unsigned *)&vq[0])[q4], x1 = ((const unsigned *)&vq[1])[q4];
+      const unsigned x2 = ((const unsigned *)&vq[2])[q4], x3 = ((const unsigned *)&vq[3])[q4];
+      const unsigned t0 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), t1 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
+      const unsigned t2 = __builtin_amdgcn_perm(x3, x2, 0x05010400u), t3 = __builtin_amdgcn_perm(x3, x2, 0x07030602u);
+      const unsigned o0 = __builtin_amdgcn_perm(t2, t0, 0x05040100u), o1 = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+      const unsigned o2 = __builtin_amdgcn_perm(t3, t1, 0x05040100u), o3 = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+      // byte r of o_e is slot 8r + r8 at channel 16*c8 + 4*q4 + e; it lands at column 4*r8 + r
+      uint8_t *dst = Vt + (16 * c8 + 4 * q4) * kVRow + 4 * r8;
+      *(unsigned *)(dst) = o0;
+      *(unsigned *)(dst + kVRow) = o1;
+      *(unsigned *)(dst + 2 * kVRow) = o2;
+      *(unsigned *)(dst + 3 * kVRow) = o3;
+    }
+    const float kscale[2] = {ksc[0] * sm, ksc[1] * sm};
+    const float vscale[2] = {vsc[0], vsc[1]};
+    wave_lds_sync();
+    // the registers are free again: fetch this wavefront's next tile while computing
+    if (tile + kAttWaves < ntiles) issue_loads(tile + kAttWaves);
+
+    // ---- scores: S[head][slot] for the two 16-slot halves of the tile ----
+    floatx4_t sc[2];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const uint8_t *krow = Kt + (16 * sb + t16) * kKRow + g4 * 32;
+      const int4 b0 = *(const int4 *)(krow), b1 = *(const int4 *)(krow + 16);
+      floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[0], cvt_i8x8_f16x8(b0.x, b0.y), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[1], cvt_i8x8_f16x8(b0.z, b0.w), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[2], cvt_i8x8_f16x8(b1.x, b1.y), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[3], cvt_i8x8_f16x8(b1.z, b1.w), acc, 0, 0, 0);
+      const bool valid = base + 16 * sb + t16 < sl.hi8;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float s = acc[i] * kscale[sb];
+        sc[sb][i] = valid ? s : NEG;
+        const int h = 4 * g4 + i;
+        if (valid && h < G) stash[h * S + (base + 16 * sb + t16 - sl.lo)] = s;
+      }
+    }
+    // ---- online softmax per head row (rows of this lane: heads 4*g4 + i) ----
+    float corr[4];
+    bool changed = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float tm = row16_max(fmaxf(sc[0][i], sc[1][i]));
+      const float mn = fmaxf(mrun[i], tm);
+      corr[i] = (mn == NEG) ? 1.f : __expf(mrun[i] - mn);
+      changed |= (mn != mrun[i]);
+      mrun[i] = mn;
+      float psum = 0.f;
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+        const float p = (sc[sb][i] == NEG) ? 0.f : __expf(sc[sb][i] - mn);
+        psum += p;
+        const int h = 4 * g4 + i;
+        if (h < G) {
+          const int tau = 16 * sb + t16;                     // slot within the tile
+          Pb[h * kPRow + 4 * (tau & 7) + (tau >> 3)] = (_Float16)(p * vscale[sb]);
+        }
+      }
+      lrun[i] = fmaf(lrun[i], corr[i], psum);
+    }
+    if (__builtin_amdgcn_ballot_w64(changed)) {
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) O[nt][i] *= corr[i];
+    }
+    wave_lds_sync();
+    // ---- output: O[head][channel] += P[head][slot] V[slot][channel] ----
+    const half8_t pa = *(const half8_t *)(Pb + t16 * kPRow + 8 * g4);
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+      const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + 8 * g4);   // 4-byte aligned
+      O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, cvt_i8x8_f16x8(vb[0], vb[1]), O[nt], 0, 0, 0);
+    }
+    wave_lds_sync();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) lrun[i] = row16_sum(lrun[i]);
+
+  // ---------------- FP16 slots on the vector ALU ----------------
+  Stream<G> st;
+  st.reset();
+  if (sl.lo16 < sl.hi) {
+    float qf[G][16];
+    load_q_slices<D, G>(cv, a, sl, qf);
+    stream_fp16_valu<D, G>(cv, sl, sm, qf, st, stash, S);
+  }
+  __syncthreads();                              // tile buffers are dead: reuse them for partials
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int h = 4 * g4 + i;
+    if (h < G) {
+      if (t16 == 0) { wm[w * G + h] = mrun[i]; wl[w * G + h] = lrun[i]; }
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) wo[(w * G + h) * D + 16 * nt + t16] = O[nt][i];
+    }
+  }
+  store_stream_partial<D, G>(st, kAttWaves + w, wm, wl, wo);
+  __syncthreads();
+  attend_epilogue<D, G, NP>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -419,7 +744,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 
 typedef void (*AttendFn)(CacheView, AttendLaunch, int, int);
 
-static AttendFn attend_fn(int D, int G) {
+static bool g_use_mfma = true;
+
+static AttendFn attend_fn_valu(int D, int G) {
 #define CONFKV_CASE(d, g) \
   if (D == d && G == g) return attend_kernel<d, g>;
   CONFKV_CASE(64, 1) CONFKV_CASE(64, 2) CONFKV_CASE(64, 4) CONFKV_CASE(64, 5) CONFKV_CASE(64, 8)
@@ -428,9 +755,31 @@ static AttendFn attend_fn(int D, int G) {
   return nullptr;
 }
 
-bool attend_supported(int D, int G) { return attend_fn(D, G) != nullptr; }
+static AttendFn attend_fn_mfma(int D, int G) {
+  if (D != 128) return nullptr;
+  switch (G) {
+    case 2: return attend_mfma_kernel<2>;
+    case 4: return attend_mfma_kernel<4>;
+    case 5: return attend_mfma_kernel<5>;
+    case 8: return attend_mfma_kernel<8>;
+    default: return nullptr;
+  }
+}
 
-static size_t attend_lds_bytes(int D, int G, int S) {
+// The matrix-core kernel serves grouped-query shapes whose units hold INT8 slots.
+static bool wants_mfma(int D, int G, bool has_int8) {
+  return g_use_mfma && has_int8 && attend_fn_mfma(D, G) != nullptr;
+}
+
+bool attend_supported(int D, int G) { return attend_fn_valu(D, G) != nullptr; }
+
+static size_t attend_lds_bytes(int D, int G, int S, bool mfma) {
+  if (mfma) {
+    const int NP = 2 * kAttWaves;
+    size_t floats = (size_t)G * S + G + 2 + 2 * NP * G;
+    size_t tiles = std::max<size_t>((size_t)kAttWaves * kTileBytes, (size_t)NP * G * D * sizeof(float));
+    return floats * sizeof(float) + (size_t)G * sizeof(double) + tiles + 32;
+  }
   size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + 2 * kAttWaves * G + G + 2;
   return floats * sizeof(float) + (size_t)G * sizeof(double) + 16;
 }
@@ -452,18 +801,18 @@ static const DeviceLimits &device_limits() {
                                                 : prop.sharedMemPerBlock;
       if (lim.max_lds > 160 * 1024) lim.max_lds = 160 * 1024;
       lim.ok = lim.cus > 0;
+      if (const char *e = getenv("CONF_KV_NO_MFMA")) g_use_mfma = atoi(e) == 0;
     }
   }
   return lim;
 }
 
-// Resident workgroups per CU of attend_kernel<D,G> with `lds` bytes of dynamic LDS.
-static int attend_occupancy(int D, int G, size_t lds) {
-  static std::map<std::tuple<int, int, size_t>, int> cache;
-  auto key = std::make_tuple(D, G, lds);
+// Resident workgroups per CU of a kernel with `lds` bytes of dynamic LDS.
+static int attend_occupancy(AttendFn fn, size_t lds) {
+  static std::map<std::tuple<const void *, size_t>, int> cache;
+  auto key = std::make_tuple((const void *)fn, lds);
   auto it = cache.find(key);
   if (it != cache.end()) return it->second;
-  AttendFn fn = attend_fn(D, G);
   int nb = 0;
   if (lds > 64 * 1024)
     (void)hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -477,7 +826,9 @@ static int attend_occupancy(int D, int G, size_t lds) {
 bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
                  AttendPlan *plan) {
   const DeviceLimits &lim = device_limits();
-  if (!lim.ok || !attend_fn(D, G)) return false;
+  if (!lim.ok || !attend_fn_valu(D, G)) return false;
+  const bool mfma = wants_mfma(D, G, n16_ub < n_ub);
+  AttendFn fn = mfma ? attend_fn_mfma(D, G) : attend_fn_valu(D, G);
   const long long nv = (long long)n_ub + n16_ub;
   // aim for about three workgroups per CU, but keep at least 128 virtual slots per split
   int want = forced_splits > 0 ? forced_splits : (3 * lim.cus + units_per_layer - 1) / units_per_layer;
@@ -490,17 +841,18 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
     int S = (int)((nv + ns - 1) / ns) + 2;
     S = (S + 255) / 256 * 256;
-    size_t lds = attend_lds_bytes(D, G, S);
+    size_t lds = attend_lds_bytes(D, G, S, mfma);
     if (lds > lim.max_lds) continue;
     if (ns > 1) {
-      int occ = attend_occupancy(D, G, lds);
+      int occ = attend_occupancy(fn, lds);
       if ((long long)occ * lim.cus < (long long)ns * units_per_layer) continue;
     } else if (lds > 64 * 1024) {
-      (void)attend_occupancy(D, G, lds);        // raises the dynamic-LDS limit
+      (void)attend_occupancy(fn, lds);          // raises the dynamic-LDS limit
     }
     plan->splits = ns;
     plan->stash_tokens = S;
     plan->lds_bytes = lds;
+    plan->mfma = mfma;
     return true;
   }
   return false;
@@ -508,7 +860,7 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
 
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream) {
-  AttendFn fn = attend_fn(cv.D, cv.G);
+  AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, cv.G) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
   dim3 grid(plan.splits, cv.B * cv.Hkv);
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,

@@ -20,6 +20,7 @@ struct AttendPlan {
   int splits;        // workgroups per unit
   int stash_tokens;  // score slots per workgroup held in LDS
   size_t lds_bytes;  // dynamic LDS per workgroup
+  bool mfma;         // matrix-core body for the INT8 slots
 };
 struct AttendLaunch {
   int layer;
