@@ -478,7 +478,7 @@ template <int D, int G>
 __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
                                                              int S) {
   constexpr int NP = kAttWaves;
-  extern __shared__ float smem[];
+  extern __shared__ __align__(16) float smem[];
   float *stash = smem;                          // [G][S] raw scores of the slice
   float *wo = stash + (size_t)G * S;            // [NP][G][D] per-wave un-normalised output
   float *wm = wo + NP * G * D;                  // [NP][G] per-wave maximum
@@ -555,14 +555,15 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
                                                                   int ns, int S) {
   constexpr int D = 128;
   constexpr int NP = 2 * kAttWaves;             // matrix-core partial + FP16 partial per wave
-  extern __shared__ float smem[];
-  float *stash = smem;                          // [G][S]
+  constexpr int kTileFloats =
+      (kAttWaves * kTileBytes > NP * G * D * 4 ? kAttWaves * kTileBytes : NP * G * D * 4) / 4;
+  extern __shared__ __align__(16) float smem[];
+  float *tiles = smem;                          // per-wave tile buffers, later [NP][G][D] partials
+  float *stash = smem + kTileFloats;            // [G][S]
   float *gm = stash + (size_t)G * S;            // [G]
   double *ginv = (double *)(gm + G + (G & 1));  // [G]
   float *wm = (float *)(ginv + G);              // [NP][G]
   float *wl = wm + NP * G;                      // [NP][G]
-  // per-wave tile buffers (16-byte aligned), later the [NP][G][D] partials
-  float *tiles = (float *)(((uintptr_t)(wl + NP * G) + 15) & ~(uintptr_t)15);
   float *wo = tiles;
   __shared__ int s_ok;
 
