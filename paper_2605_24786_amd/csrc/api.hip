@@ -267,6 +267,12 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
   a.sm_scale = h->cfg.sm_scale;
   a.ema_decay = h->cfg.ema_decay;
   a.pos_new = h->next_pos[layer];
+  a.dbg = nullptr;
+#ifdef CONFKV_TRACE
+  // the ranking work arrays at the end of the scratch buffer are idle during conf_kv_attend
+  if (getenv("CONF_KV_TRACE") && h->kl.total - h->kl.score >= (size_t)8 * 32 * 4 * 4096)
+    a.dbg = (unsigned long long *)(h->scratch + h->kl.total - (size_t)8 * 32 * 4 * 4096);
+#endif
   CK_HIP(h, launch_attend(h->cv, a, plan, (hipStream_t)stream));
   h->arrive_base[layer] += (uint32_t)plan.splits;
   h->appended[layer] = 1;

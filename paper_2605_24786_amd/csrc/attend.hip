@@ -28,7 +28,7 @@
 //     [G x 32] x [32 x 128]) issued as v_mfma_f32_16x16x32_f16 with the head dimension
 //     padded to 16.  The vector ALU then only converts int8 -> fp16 and keeps the softmax
 //     state, which is what lets the kernel stay memory-bound for grouped-query shapes.
-//     FP16 slots (at most W + 1 per unit) still take the vector-ALU body.
+//     FP16 slots go through the same contractions in 16-slot tiles, no conversion needed.
 #include <algorithm>
 #include <map>
 #include <tuple>
@@ -44,7 +44,22 @@ constexpr int kSpinLimit = 4000000;
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+// Optional in-kernel phase trace (build with -DCONFKV_TRACE): lane 0 of every wavefront
+// stores the 100 MHz wall clock at numbered points into a debug buffer, 32 slots per
+// wavefront.  Compiled out otherwise.
+#ifdef CONFKV_TRACE
+#define TS(k)                                                                                   \
+  do {                                                                                          \
+    if (a.dbg && (threadIdx.x & 63) == 0)                                                       \
+      a.dbg[((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 32 + (k)] = \
+          wall_clock64();                                                                       \
+  } while (0)
+#else
+#define TS(k) do { } while (0)
+#endif
 
 // Partials travel between workgroups (possibly on different XCDs, whose L2s are not
 // coherent for ordinary accesses) through agent-scope relaxed atomics: such loads and
@@ -90,9 +105,16 @@ __device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, fl
 struct Slice {
   int u, ul, b, g, j;          // unit, unit within the layer, batch, kv-head, split
   int n, n8, h16, n16;         // length with the append, INT8 slots, ring head, FP16 slots
-  int lo, hi, hi8, lo16, ntok; // slot range of this split
+  int lo8, hi8;                // INT8 slots of this split
+  int lo16, hi16;              // FP16 slots of this split (slot numbers, >= n8)
+  int cnt8, ntok;              // hi8 - lo8, and cnt8 + (hi16 - lo16)
+  // stash index t in [0, ntok) <-> slot
+  __device__ __forceinline__ int slot_of(int t) const { return t < cnt8 ? lo8 + t : lo16 + (t - cnt8); }
 };
 
+// Every split takes an equal share of the INT8 slots (cut at multiples of 32, the tile of
+// the matrix-core body) and an equal share of the FP16 slots, so all splits of a unit carry
+// the same mix of work and reach the arrival point together.
 __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLaunch &a, int ns, int S) {
   Slice s;
   s.ul = blockIdx.y;
@@ -104,19 +126,19 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
   s.n = cv.len[s.u] + 1;                  // the appended token included
   s.h16 = cv.head16[s.u];
   s.n16 = s.n - s.n8;
-  // byte-balanced split: an FP16 slot weighs two INT8 slots; rounding down keeps the tail
-  // slice non-empty, so its owner always holds slot n-1
-  const long long nv = (long long)s.n8 + 2ll * s.n16;
-  const long long vlo = nv * s.j / ns, vhi = nv * (s.j + 1) / ns;
-  s.lo = vlo <= s.n8 ? (int)vlo : s.n8 + (int)((vlo - s.n8) >> 1);
-  s.hi = vhi <= s.n8 ? (int)vhi : s.n8 + (int)((vhi - s.n8) >> 1);
-  if (s.hi - s.lo > S) {                  // cannot happen when the host plan is right
+  s.lo8 = (int)((long long)s.n8 * s.j / ns) & ~31;
+  s.hi8 = s.j == ns - 1 ? s.n8 : (int)((long long)s.n8 * (s.j + 1) / ns) & ~31;
+  // the tail split's FP16 share is never empty (n16 >= 1), so its owner holds slot n-1
+  s.lo16 = s.n8 + (int)((long long)s.n16 * s.j / ns);
+  s.hi16 = s.n8 + (int)((long long)s.n16 * (s.j + 1) / ns);
+  s.cnt8 = s.hi8 - s.lo8;
+  s.ntok = s.cnt8 + (s.hi16 - s.lo16);
+  if (s.ntok > S) {                       // cannot happen when the host plan is right
     if (threadIdx.x == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
-    s.hi = s.lo + S;
+    s.hi8 = s.lo8; s.cnt8 = 0;
+    s.hi16 = min(s.hi16, s.lo16 + S);
+    s.ntok = s.hi16 - s.lo16;
   }
-  s.ntok = s.hi - s.lo;
-  s.hi8 = min(s.hi, s.n8);
-  s.lo16 = max(s.lo, s.n8);
   return s;
 }
 
@@ -216,22 +238,22 @@ __device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slic
   const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
   const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
   const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
-  for (int base = sl.lo; base < sl.hi8; base += TB * R8) {
+  for (int base = sl.lo8; base < sl.hi8; base += TB * R8) {
     int4 kr[R8], vr[R8];
-    float ksc[R8], vsc[R8];
+    unsigned short ksh[R8], vsh[R8];
+    float vsc[R8];
     bool ok[R8];
+    // branch-free loads (rows past the slice re-read its last row and are masked below), so
+    // that all of a trip's loads are in flight before the first one is waited for
 #pragma unroll
     for (int r = 0; r < R8; ++r) {
       const int i = base + r * TB + w * TW + ts;
       ok[r] = i < sl.hi8;
-      kr[r] = vr[r] = make_int4(0, 0, 0, 0);
-      ksc[r] = vsc[r] = 0.f;
-      if (ok[r]) {
-        kr[r] = *(const int4 *)(K8 + (size_t)i * D + c * 16);
-        vr[r] = *(const int4 *)(V8 + (size_t)i * D + c * 16);
-        ksc[r] = __half2float(KS[i]);
-        vsc[r] = __half2float(VS[i]);
-      }
+      const int ic = ok[r] ? i : sl.hi8 - 1;
+      kr[r] = *(const int4 *)(K8 + (size_t)ic * D + c * 16);
+      vr[r] = *(const int4 *)(V8 + (size_t)ic * D + c * 16);
+      ksh[r] = ((const unsigned short *)KS)[ic];
+      vsh[r] = ((const unsigned short *)VS)[ic];
     }
     float s[R8][G], vf[R8][16];
 #pragma unroll
@@ -256,11 +278,12 @@ __device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slic
 #pragma unroll
     for (int r = 0; r < R8; ++r) {
       const int i = base + r * TB + w * TW + ts;
-      const float f = ksc[r] * sm;
+      const float f = __half2float(__ushort_as_half(ksh[r])) * sm;
+      vsc[r] = __half2float(__ushort_as_half(vsh[r]));
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         s[r][h] *= f;
-        if (ok[r] && c == 0) stash[h * S + (i - sl.lo)] = s[r][h];
+        if (ok[r] && c == 0) stash[h * S + (i - sl.lo8)] = s[r][h];
       }
       unpack_i8x16(vr[r], vf[r]);
     }
@@ -278,22 +301,20 @@ __device__ __forceinline__ void stream_fp16_valu(const CacheView &cv, const Slic
   const int c = lane % LPT, ts = lane / LPT;
   const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
   const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
-  for (int base = sl.lo16; base < sl.hi; base += TB * R16) {
+  for (int base = sl.lo16; base < sl.hi16; base += TB * R16) {
     int4 kr[R16][2], vr[R16][2];
     float vsc[R16];
     bool ok[R16];
 #pragma unroll
     for (int r = 0; r < R16; ++r) {
       const int i = base + r * TB + w * TW + ts;
-      ok[r] = i < sl.hi;
+      ok[r] = i < sl.hi16;
       vsc[r] = 1.f;
-      kr[r][0] = kr[r][1] = vr[r][0] = vr[r][1] = make_int4(0, 0, 0, 0);
-      if (ok[r]) {
-        const size_t off = (size_t)ring_row(sl.h16, i - sl.n8, cv.cap16) * D + c * 16;
-        const int4 *pk = (const int4 *)(K16 + off), *pv = (const int4 *)(V16 + off);
-        kr[r][0] = pk[0]; kr[r][1] = pk[1];
-        vr[r][0] = pv[0]; vr[r][1] = pv[1];
-      }
+      const int ic = ok[r] ? i : sl.hi16 - 1;
+      const size_t off = (size_t)ring_row(sl.h16, ic - sl.n8, cv.cap16) * D + c * 16;
+      const int4 *pk = (const int4 *)(K16 + off), *pv = (const int4 *)(V16 + off);
+      kr[r][0] = pk[0]; kr[r][1] = pk[1];
+      vr[r][0] = pv[0]; vr[r][1] = pv[1];
     }
     float s[R16][G], vf[R16][16];
 #pragma unroll
@@ -321,7 +342,7 @@ __device__ __forceinline__ void stream_fp16_valu(const CacheView &cv, const Slic
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         s[r][h] *= sm;
-        if (ok[r] && c == 0) stash[h * S + (i - sl.lo)] = s[r][h];
+        if (ok[r] && c == 0) stash[h * S + sl.cnt8 + (i - sl.lo16)] = s[r][h];
       }
       unpack_h16x16(vr[r][0], vr[r][1], vf[r]);
     }
@@ -333,7 +354,7 @@ __device__ __forceinline__ void stream_fp16_valu(const CacheView &cv, const Slic
 // (m, l, o[G][D]) as entry `pidx` of the workgroup's LDS partial arrays.
 template <int D, int G>
 __device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, float *wm, float *wl,
-                                                     float *wo) {
+                                                     float *wo_p) {
   constexpr int LPT = D / 16;
   const int lane = threadIdx.x & 63;
   const int c = lane % LPT, ts = lane / LPT;
@@ -355,16 +376,17 @@ __device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, fl
     if (lane == 0) { wm[pidx * G + h] = mw; wl[pidx * G + h] = l; }
     if (ts == 0) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) wo[(pidx * G + h) * D + c * 16 + e] = st.acc[h][e];
+      for (int e = 0; e < 16; ++e) wo_p[h * D + c * 16 + e] = st.acc[h][e];
     }
   }
 }
 
 // ---------------------------------------------------------------------------------------
 // Epilogue shared by both bodies.  On entry wm/wl/wo hold NP per-wavefront partials
-// (after a workgroup barrier); stash holds the slice's raw scores.
+// (after a workgroup barrier): partial k is [G][D] floats at
+// wo + (k % 4) * WSTR + (k / 4) * G * D; stash holds the slice's raw scores.
 // ---------------------------------------------------------------------------------------
-template <int D, int G, int NP>
+template <int D, int G, int NP, int WSTR>
 __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const AttendLaunch &a,
                                                 const Slice &sl, int ns, int S, float *stash,
                                                 float *wm, float *wl, float *wo, float *gm,
@@ -381,10 +403,13 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     float o = 0.f, l = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
+      // partial k belongs to wavefront k % 4; an empty partial (m = -inf) is never read
       const float mk = wm[k * G + h];
-      const float f = (mk == NEG) ? 0.f : __expf(mk - M);
-      o = fmaf(wo[k * G * D + idx], f, o);
-      l = fmaf(wl[k * G + h], f, l);
+      if (mk > NEG) {
+        const float f = __expf(mk - M);
+        o = fmaf(wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx], f, o);
+        l = fmaf(wl[k * G + h], f, l);
+      }
     }
     st_agent(&po[idx], o);
     if (idx % D == 0) {
@@ -392,8 +417,10 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       st_agent(&ml[h * 2 + 1], l);
     }
   }
+  TS(19);
   wait_stores_done();
   __syncthreads();
+  TS(20);
   if (tid == 0) {
     __hip_atomic_fetch_add(&a.arrive[sl.ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int ok = 1;
@@ -411,6 +438,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     *s_ok = ok;
   }
   __syncthreads();
+  TS(21);
   if (!*s_ok) return;
 
   // ---- all (m, l) partials of the unit -> LDS in one round trip; global (M, 1/L) ----
@@ -431,11 +459,12 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   }
   __syncthreads();
 
+  TS(22);
   // ---- mass + EMA of the slice ----
   float *EMA = cv.ema + (size_t)sl.u * cv.cap;
   const double lam = (double)a.ema_decay, oml = 1.0 - lam;
   for (int t = tid; t < sl.ntok; t += kAttThreads) {
-    const int slot = sl.lo + t;
+    const int slot = sl.slot_of(t);
     const double old = (slot == sl.n - 1) ? 0.0 : (double)EMA[slot];
     double A = 0.0;
 #pragma unroll
@@ -443,6 +472,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     EMA[slot] = (float)(lam * old + oml * A);
   }
 
+  TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
   {
     const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
@@ -496,16 +526,17 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   load_q_slices<D, G>(cv, a, sl, qf);
   stream_int8_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
   stream_fp16_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
-  store_stream_partial<D, G>(st, threadIdx.x >> 6, wm, wl, wo);
+  store_stream_partial<D, G>(st, threadIdx.x >> 6, wm, wl, wo + (threadIdx.x >> 6) * G * D);
   __syncthreads();
-  attend_epilogue<D, G, NP>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+  attend_epilogue<D, G, NP, G * D>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
 // Kernel 2: matrix-core body for the INT8 slots (D = 128), vector ALU for the FP16 slots
 // ---------------------------------------------------------------------------------------
 constexpr int kTile = 32;              // slots per wavefront tile
-constexpr int kKRow = 128 + 16;        // LDS row stride of the K tile (bytes)
+constexpr int kKRow = 128 + 16;        // LDS row stride of the INT8 K tile (bytes)
+constexpr int kKRow16 = 256 + 16;      // LDS row stride of the 16-slot FP16 K tile (bytes)
 constexpr int kVRow = 32 + 4;          // LDS row stride of the transposed V tile (bytes)
 constexpr int kPRow = 32 + 8;          // LDS row stride of the probability tile (halfs)
 constexpr int kTileBytes = kTile * kKRow + 128 * kVRow + 16 * kPRow * 2;   // per wavefront
@@ -554,7 +585,7 @@ template <int G>
 __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, AttendLaunch a,
                                                                   int ns, int S) {
   constexpr int D = 128;
-  constexpr int NP = 2 * kAttWaves;             // matrix-core partial + FP16 partial per wave
+  constexpr int NP = kAttWaves;                 // one partial per wavefront
   constexpr int kTileFloats =
       (kAttWaves * kTileBytes > NP * G * D * 4 ? kAttWaves * kTileBytes : NP * G * D * 4) / 4;
   extern __shared__ __align__(16) float smem[];
@@ -568,10 +599,12 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
   __shared__ int s_ok;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  TS(0);
   const Slice sl = make_slice(cv, a, ns, S);
   append_new_token<D>(cv, a, sl, ns);
   const float NEG = -INFINITY;
   const float sm = a.sm_scale;
+  TS(1);
 
   // ---------------- INT8 slots on the matrix cores ----------------
   const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
@@ -606,30 +639,106 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
   const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
   const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
 
-  const int ntiles = (sl.hi8 - sl.lo + kTile - 1) / kTile;     // <= 0 when no INT8 slot
+  const int ntiles = (sl.cnt8 + kTile - 1) / kTile;            // 0 when the split has no INT8 slot
   int4 kq[4], vq[4];
-  float ksc[2], vsc[2];
+  unsigned short ksh[2], vsh[2];
+  // branch-free (rows past the slice re-read its last row; their scores are masked and their
+  // probabilities are zero), so the whole tile is in flight before anything is waited for
   auto issue_loads = [&](int tile) {
-    const int base = sl.lo + tile * kTile;
+    const int base = sl.lo8 + tile * kTile;
+    const int last = sl.hi8 - 1;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int i = base + 8 * r + r8;
-      kq[r] = vq[r] = make_int4(0, 0, 0, 0);
-      if (i < sl.hi8) {
-        kq[r] = *(const int4 *)(K8 + (size_t)i * D + c8 * 16);
-        vq[r] = *(const int4 *)(V8 + (size_t)i * D + c8 * 16);
-      }
+      const int i = min(base + 8 * r + r8, last);
+      kq[r] = *(const int4 *)(K8 + (size_t)i * D + c8 * 16);
+      vq[r] = *(const int4 *)(V8 + (size_t)i * D + c8 * 16);
     }
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
-      const int i = base + 16 * sb + t16;
-      ksc[sb] = vsc[sb] = 0.f;
-      if (i < sl.hi8) { ksc[sb] = __half2float(KS[i]); vsc[sb] = __half2float(VS[i]); }
+      const int i = min(base + 16 * sb + t16, last);
+      ksh[sb] = ((const unsigned short *)KS)[i];
+      vsh[sb] = ((const unsigned short *)VS)[i];
     }
   };
-  if (w < ntiles) issue_loads(w);
+  // ---------------- FP16 slots: 16-slot tiles on the matrix cores, taken first ----------------
+  // (tiles go to the wavefronts from the back, which hold the fewest INT8 tiles; the first
+  // INT8 tile's loads are already in flight while the FP16 tile is computed)
+  const int ntiles16 = (sl.hi16 - sl.lo16 + 15) / 16;
+  {
+    const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
+    const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
+    const int c16 = lane & 15, r4 = lane >> 4;   // load coordinates: 16-byte piece, row
+    bool first = true;
+    for (int f = kAttWaves - 1 - w; f < ntiles16; f += kAttWaves) {
+      const int base = sl.lo16 + 16 * f;
+      int4 kh[4], vh[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int slot = min(base + 4 * r + r4, sl.hi16 - 1);
+        const size_t off = (size_t)ring_row(sl.h16, slot - sl.n8, cv.cap16) * D + c16 * 8;
+        kh[r] = *(const int4 *)(K16 + off);
+        vh[r] = *(const int4 *)(V16 + off);
+      }
+      if (first && w < ntiles) issue_loads(w);
+      first = false;
+      // K rows as they are (row stride kKRow16 bytes), V transposed to [channel][slot]
+#pragma unroll
+      for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (4 * r + r4) * kKRow16 + c16 * 16) = kh[r];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const unsigned x0 = ((const unsigned *)&vh[0])[q4], x1 = ((const unsigned *)&vh[1])[q4];
+        const unsigned x2 = ((const unsigned *)&vh[2])[q4], x3 = ((const unsigned *)&vh[3])[q4];
+        // half r of each pair is slot 4r + r4; it lands at column 4*r4 + r
+        unsigned *dst = (unsigned *)(Vt + (8 * c16 + 2 * q4) * kVRow + 8 * r4);
+        dst[0] = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
+        dst[1] = __builtin_amdgcn_perm(x3, x2, 0x05040100u);
+        dst[kVRow / 4] = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
+        dst[kVRow / 4 + 1] = __builtin_amdgcn_perm(x3, x2, 0x07060302u);
+      }
+      wave_lds_sync();
+      const uint8_t *krow = Kt + t16 * kKRow16 + g4 * 64;
+      floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[s], *(const half8_t *)(krow + 16 * s), acc, 0, 0, 0);
+      const bool valid = base + t16 < sl.hi16;
+      float corr[4];
+      bool changed = false;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = 4 * g4 + i;
+        const float sv = valid ? acc[i] * sm : NEG;
+        if (valid && h < G) stash[h * S + sl.cnt8 + (base + t16 - sl.lo16)] = sv;
+        const float mn = fmaxf(mrun[i], row16_max(sv));
+        corr[i] = (mn == NEG) ? 1.f : __expf(mrun[i] - mn);
+        changed |= (mn != mrun[i]);
+        mrun[i] = mn;
+        const float p = valid ? __expf(sv - mn) : 0.f;
+        if (h < G) Pb[h * kPRow + 4 * (t16 & 3) + (t16 >> 2)] = (_Float16)p;
+        lrun[i] = fmaf(lrun[i], corr[i], p);
+      }
+      if (__builtin_amdgcn_ballot_w64(changed)) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) O[nt][i] *= corr[i];
+      }
+      wave_lds_sync();
+      const half4_t pa = *(const half4_t *)(Pb + t16 * kPRow + 4 * g4);
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) {
+        const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + 8 * g4);
+        const uint2 v2 = make_uint2(vb[0], vb[1]);
+        O[nt] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, __builtin_bit_cast(half4_t, v2), O[nt], 0, 0, 0);
+      }
+      wave_lds_sync();
+    }
+    if (first && w < ntiles) issue_loads(w);
+  }
+  int tix = 0;
   for (int tile = w; tile < ntiles; tile += kAttWaves) {
-    const int base = sl.lo + tile * kTile;
+    const int base = sl.lo8 + tile * kTile;
+    if (tix < 6) TS(4 + 2 * tix);
     // ---- registers -> LDS: K rows as they are, V transposed to [channel][slot] ----
 #pragma unroll
     for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (8 * r + r8) * kKRow + c8 * 16) = kq[r];
@@ -648,9 +757,13 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
       *(unsigned *)(dst + 2 * kVRow) = o2;
       *(unsigned *)(dst + 3 * kVRow) = o3;
     }
-    const float kscale[2] = {ksc[0] * sm, ksc[1] * sm};
-    const float vscale[2] = {vsc[0], vsc[1]};
+    const float kscale[2] = {__half2float(__ushort_as_half(ksh[0])) * sm,
+                             __half2float(__ushort_as_half(ksh[1])) * sm};
+    const float vscale[2] = {__half2float(__ushort_as_half(vsh[0])),
+                             __half2float(__ushort_as_half(vsh[1]))};
     wave_lds_sync();
+    if (tix < 6) TS(5 + 2 * tix);
+    ++tix;
     // the registers are free again: fetch this wavefront's next tile while computing
     if (tile + kAttWaves < ntiles) issue_loads(tile + kAttWaves);
 
@@ -671,9 +784,10 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
         const float s = acc[i] * kscale[sb];
         sc[sb][i] = valid ? s : NEG;
         const int h = 4 * g4 + i;
-        if (valid && h < G) stash[h * S + (base + 16 * sb + t16 - sl.lo)] = s;
+        if (valid && h < G) stash[h * S + (base + 16 * sb + t16 - sl.lo8)] = s;
       }
     }
+    if (tix <= 2) TS(24 + (tix - 1) * 3);
     // ---- online softmax per head row (rows of this lane: heads 4*g4 + i) ----
     float corr[4];
     bool changed = false;
@@ -704,6 +818,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
         for (int i = 0; i < 4; ++i) O[nt][i] *= corr[i];
     }
     wave_lds_sync();
+    if (tix <= 2) TS(25 + (tix - 1) * 3);
     // ---- output: O[head][channel] += P[head][slot] V[slot][channel] ----
     const half8_t pa = *(const half8_t *)(Pb + t16 * kPRow + 8 * g4);
 #pragma unroll
@@ -713,30 +828,26 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
     }
     wave_lds_sync();
   }
+  TS(16);
 #pragma unroll
   for (int i = 0; i < 4; ++i) lrun[i] = row16_sum(lrun[i]);
 
-  // ---------------- FP16 slots on the vector ALU ----------------
-  Stream<G> st;
-  st.reset();
-  if (sl.lo16 < sl.hi) {
-    float qf[G][16];
-    load_q_slices<D, G>(cv, a, sl, qf);
-    stream_fp16_valu<D, G>(cv, sl, sm, qf, st, stash, S);
-  }
-  __syncthreads();                              // tile buffers are dead: reuse them for partials
+  // the wavefront's matrix-core partial goes into its own (now idle) tile buffer
+  float *wo_w = tiles + w * (kTileBytes / 4);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int h = 4 * g4 + i;
     if (h < G) {
       if (t16 == 0) { wm[w * G + h] = mrun[i]; wl[w * G + h] = lrun[i]; }
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) wo[(w * G + h) * D + 16 * nt + t16] = O[nt][i];
+      for (int nt = 0; nt < 8; ++nt) wo_w[h * D + 16 * nt + t16] = O[nt][i];
     }
   }
-  store_stream_partial<D, G>(st, kAttWaves + w, wm, wl, wo);
+
+  TS(17);
   __syncthreads();
-  attend_epilogue<D, G, NP>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+  TS(18);
+  attend_epilogue<D, G, NP, kTileBytes / 4>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -776,7 +887,7 @@ bool attend_supported(int D, int G) { return attend_fn_valu(D, G) != nullptr; }
 
 static size_t attend_lds_bytes(int D, int G, int S, bool mfma) {
   if (mfma) {
-    const int NP = 2 * kAttWaves;
+    const int NP = kAttWaves;
     size_t floats = (size_t)G * S + G + 2 + 2 * NP * G;
     size_t tiles = std::max<size_t>((size_t)kAttWaves * kTileBytes, (size_t)NP * G * D * sizeof(float));
     return floats * sizeof(float) + (size_t)G * sizeof(double) + tiles + 32;
@@ -840,7 +951,7 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   for (int k = 0; k < kAttendMaxSplits; ++k) {
     const int ns = k < want ? want - k : k + 1;
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
-    int S = (int)((nv + ns - 1) / ns) + 2;
+    int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
     S = (S + 255) / 256 * 256;
     size_t lds = attend_lds_bytes(D, G, S, mfma);
     if (lds > lim.max_lds) continue;

@@ -33,6 +33,7 @@ struct AttendLaunch {
   int max_splits;
   float sm_scale, ema_decay;
   int pos_new;
+  unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
 };
 constexpr int kAttendMaxSplits = 64;
 bool attend_supported(int D, int G);
