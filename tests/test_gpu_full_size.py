@@ -1,0 +1,88 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The GPU runs every unit; the float64 oracle follows a seeded sample of units (units evolve
+independently given their inputs and their sequence's budget).  Long runs are truncated to
+a few decode steps here so the suite stays within minutes; the first step is always the
+heaviest one (full prompt length, largest eviction).  Properties that hold at any size are
+checked on ALL units from the GPU state: lengths within budget, FP16 window respected,
+positions strictly increasing with the protected window intact, EMA mass conservation.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+from synth import generate as gen
+from synth.workloads import workload
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from harness import Lockstep  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+# workload index -> (decode steps run here, oracle-followed units, layers kept)
+PLAN = {0: (6, 12, None), 1: (1, 6, None), 2: (3, 4, 16), 3: (2, 2, 4), 4: (2, 6, 8)}
+
+
+def _invariants_all_units(ls, wl, step):
+    kv = ls.kv
+    ln, n16 = kv.lengths()
+    sel = ls.sel.cpu().numpy().astype(bool)
+    for l in range(wl.n_layers):
+        for b in range(wl.batch):
+            N = wl.n_tight[l] if sel[b] else wl.n_loose[l]
+            assert ln[l, b] <= max(N, wl.protected), (l, b, ln[l, b], N)      # budget never exceeded
+    if wl.fp16_window >= 0:
+        assert n16.max() <= wl.fp16_window
+    rng = np.random.default_rng(step)
+    for _ in range(6):                                                          # spot-check exports
+        l, b, g = int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch)), int(rng.integers(wl.n_kv_heads))
+        ex = kv.export(l, b, g)
+        pos = ex["pos"]
+        assert np.all(np.diff(pos) > 0)
+        P = min(wl.protected, ex["n"])
+        newest = wl.prefill + step
+        assert np.array_equal(pos[-P:], np.arange(newest - P + 1, newest + 1))  # protected window kept
+        assert not ex["is16"][:ex["n"] - n16[l, b, g]].any() and ex["is16"][ex["n"] - n16[l, b, g]:].all()
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_full_size_workload(lib, idx):
+    steps, units, layers = PLAN[idx]
+    wl = workload(idx)
+    if layers is not None and layers < wl.n_layers:
+        # fewer layers bound the host-side generation time; per-layer shapes stay at full size
+        wl = wl.scaled(n_layers=layers, n_tight=wl.n_tight[:layers], n_loose=wl.n_loose[:layers])
+    print(f"full-size workload {idx}: {wl.name} layers={wl.n_layers} units={wl.units} steps={steps} "
+          f"oracle units={units}", flush=True)
+    ls = Lockstep(lib, wl, seed=0, units=units, threads=16)
+    print(f"  attend splits: {ls.kv.attend_splits(0)}", flush=True)
+    for t in range(steps):
+        ls.step()
+        _invariants_all_units(ls, wl, t)
+        print(f"  step {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    st = ls.kv.counters()
+    print(f"  conf_err={rep.max_conf_err:.2e} ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+          f"ties(evict/budget)={rep.evict_ties}/{rep.budget_ties} flips={rep.evict_flips}/{rep.budget_flips}", flush=True)
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert st.device_errors == 0
+    ls.close()
+
+
+def test_needle_retention_full_size(lib):
+    """Retrieval stress at full cache length (one layer): every planted needle survives the
+    32769 -> 4096 eviction after the first probe step, on every unit of the layer."""
+    wl = workload(3).scaled(n_layers=1, n_tight=(512,), n_loose=(4096,))
+    ls = Lockstep(lib, wl, seed=0, units=1, threads=16)
+    ls.step()
+    slots = gen.needle_slots(wl, 0)
+    kept = 0
+    for g in range(wl.n_kv_heads):
+        ex = ls.kv.export(0, 0, g)
+        assert ex["n"] == 4096
+        kept += int(np.isin(slots, ex["pos"]).sum())
+    print(f"needles retained: {kept}/{len(slots) * wl.n_kv_heads}", flush=True)
+    assert kept == len(slots) * wl.n_kv_heads
+    ls.close()
