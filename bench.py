@@ -30,6 +30,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per conf_kv_attend launch on the default workload from hardware counters
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scale factors from a plain 1 GiB copy); the runs and
+# readings are in profiles/bench_llama3_8b_b8_t4096_hbm_counters.txt.  None for other workloads.
+COUNTER_TRAFFIC_BYTES = {1: int((40027.7 * 2.0 + 25218.2) * 1024)}
 
 
 def attend_bytes_per_launch(wl, n8, n16):
@@ -101,6 +105,8 @@ def main():
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain 1 GiB device-to-device copy a few times and exit (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -110,6 +116,16 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        # known traffic for scaling the FETCH_SIZE / WRITE_SIZE counters: each copy reads 1 GiB
+        # and writes 1 GiB
+        x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        y = torch.empty_like(x)
+        for _ in range(5):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": 1 << 30, "copy_probe_bytes_written": 1 << 30, "copies": 5}))
+        return
     import paper_2605_24786_amd as pkg
     from synth import generate as gen
     from synth.workloads import workload
@@ -167,19 +183,10 @@ def main():
     ln, n16 = kv.lengths()
     st = kv.counters()
 
-    # the dominant kernel alone: per-launch HIP events around each conf_kv_attend
-    reload(); torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
-    for l in range(L):
-        evs[l][0].record()
-        kv.attend(l, qs[l], ks[l], vs[l], out)
-        evs[l][1].record()
-    torch.cuda.synchronize()
-    t_launch = [a.elapsed_time(b) for a, b in evs]
-    kv.step(logits, conf, sel); kv.evict_compact(); torch.cuda.synchronize()
-
     ms_step = float(np.mean(t_step))
-    att_launch_ms = float(np.mean(t_launch))
+    # the dominant kernel: the L attention launches of a step run back to back between two
+    # HIP events of the timed region, so their mean duration is that interval / L
+    att_launch_ms = float(np.mean(t_att)) / L
     att_bytes = attend_bytes_per_launch(wl, n8_b, n16_b)
     n_after = int(ln.mean())
     n_moved = int(ln.sum()) * wl.n_kv_heads          # survivors (all sit behind the first hole, to first order)
@@ -195,9 +202,10 @@ def main():
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
                    "protected": wl.protected, "kv_storage": "int8+fp16", "attend_splits": kv.attend_splits(0),
                    "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
-        "roofline": {"bound": "hbm", "kernel": "attend_kernel<128,4>", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel<4>" if wl.group > 1 and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "bytes_per_launch": att_bytes, "launch_ms": att_launch_ms},
+                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload), "bytes_per_launch": att_bytes,
+                     "launch_ms": att_launch_ms},
         "step_breakdown_ms": {"attend_x_layers": float(np.mean(t_att)), "confidence": float(np.mean(t_conf)),
                               "evict_compact": float(np.mean(t_evict))},
         "step_hbm": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (ms_step * 1e-3) / 1e9,
