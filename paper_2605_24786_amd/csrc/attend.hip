@@ -47,6 +47,11 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
+// q-th dword of a 128-bit register quad (q is a compile-time constant after unrolling)
+__device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
+  return (unsigned)(q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w);
+}
+
 // Optional in-kernel phase trace (build with -DCONFKV_TRACE): lane 0 of every wavefront
 // stores the 100 MHz wall clock at numbered points into a debug buffer, 32 slots per
 // wavefront.  Compiled out otherwise.
@@ -70,6 +75,11 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 // has observed the arrival count.
 __device__ __forceinline__ void st_agent(float *p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent2(float *p, float v0, float v1) {   // p 8-byte aligned
+  const unsigned long long bits =
+      (unsigned long long)__float_as_uint(v0) | ((unsigned long long)__float_as_uint(v1) << 32);
+  __hip_atomic_store((unsigned long long *)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float ld_agent(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -395,27 +405,38 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const float NEG = -INFINITY;
   float *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
   float *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
-  for (int idx = tid; idx < G * D; idx += kAttThreads) {
+  // the EMA values this thread will update: requested now, needed after the wait
+  constexpr int kPre = 4;
+  float *EMA = cv.ema + (size_t)sl.u * cv.cap;
+  float ema_old[kPre];
+#pragma unroll
+  for (int k = 0; k < kPre; ++k) {
+    const int t = tid + k * kAttThreads;
+    const int slot = sl.slot_of(min(t, sl.ntok - 1));
+    ema_old[k] = (t < sl.ntok && slot != sl.n - 1) ? EMA[slot] : 0.f;
+  }
+  // workgroup merge of the per-wavefront partials; two channels per thread, one 8-byte
+  // coherent store each
+  for (int idx = 2 * tid; idx < G * D; idx += 2 * kAttThreads) {
     const int h = idx / D;
     float M = NEG;
 #pragma unroll
     for (int k = 0; k < NP; ++k) M = fmaxf(M, wm[k * G + h]);
-    float o = 0.f, l = 0.f;
+    float o0 = 0.f, o1 = 0.f, l = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
       // partial k belongs to wavefront k % 4; an empty partial (m = -inf) is never read
       const float mk = wm[k * G + h];
       if (mk > NEG) {
         const float f = __expf(mk - M);
-        o = fmaf(wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx], f, o);
+        const float *w2 = &wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx];
+        o0 = fmaf(w2[0], f, o0);
+        o1 = fmaf(w2[1], f, o1);
         l = fmaf(wl[k * G + h], f, l);
       }
     }
-    st_agent(&po[idx], o);
-    if (idx % D == 0) {
-      st_agent(&ml[h * 2 + 0], M);
-      st_agent(&ml[h * 2 + 1], l);
-    }
+    st_agent2(&po[idx], o0, o1);
+    if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
   }
   TS(19);
   wait_stores_done();
@@ -441,9 +462,19 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   TS(21);
   if (!*s_ok) return;
 
-  // ---- all (m, l) partials of the unit -> LDS in one round trip; global (M, 1/L) ----
+  // ---- one round trip: all (m, l) partials of the unit -> LDS, and this split's share of
+  // the unit's output partials -> registers ----
   const float *mlu = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
+  const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
   float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
+  constexpr int kOutPre = 8;                         // splits whose partial is prefetched
+  const int per = (G * D + ns - 1) / ns;             // output elements per split (<= 256 threads each
+  const int oidx = sl.j * per + tid;                 //  for ns >= G*D/256)
+  const bool has_out = tid < per && oidx < G * D;
+  float opre[kOutPre];
+#pragma unroll
+  for (int k = 0; k < kOutPre; ++k)
+    opre[k] = (has_out && k < ns) ? ld_agent(&pou[(size_t)k * G * D + oidx]) : 0.f;
   for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
   __syncthreads();
   if (tid < G) {
@@ -458,12 +489,20 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     ginv[tid] = 1.0 / L;
   }
   __syncthreads();
-
   TS(22);
   // ---- mass + EMA of the slice ----
-  float *EMA = cv.ema + (size_t)sl.u * cv.cap;
   const double lam = (double)a.ema_decay, oml = 1.0 - lam;
-  for (int t = tid; t < sl.ntok; t += kAttThreads) {
+#pragma unroll
+  for (int k = 0; k < kPre; ++k) {
+    const int t = tid + k * kAttThreads;
+    if (t < sl.ntok) {
+      double A = 0.0;
+#pragma unroll
+      for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
+      EMA[sl.slot_of(t)] = (float)(lam * (double)ema_old[k] + oml * A);
+    }
+  }
+  for (int t = tid + kPre * kAttThreads; t < sl.ntok; t += kAttThreads) {
     const int slot = sl.slot_of(t);
     const double old = (slot == sl.n - 1) ? 0.0 : (double)EMA[slot];
     double A = 0.0;
@@ -471,23 +510,22 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
     EMA[slot] = (float)(lam * old + oml * A);
   }
-
   TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
   {
-    const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
     const int Hq = cv.Hkv * G;
-    const int per = (G * D + ns - 1) / ns;
     const int i1 = min(G * D, (sl.j + 1) * per);
-    for (int idx = sl.j * per + tid; idx < i1; idx += kAttThreads) {
+    for (int idx = oidx; idx < i1; idx += kAttThreads) {
       const int h = idx / D;
       const float M = gm[h];
       float o = 0.f;
       for (int s0 = 0; s0 < ns; s0 += 8) {
         float v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-          v[k] = (s0 + k < ns) ? ld_agent(&pou[(size_t)(s0 + k) * G * D + idx]) : 0.f;
+        for (int k = 0; k < 8; ++k) {
+          if (s0 == 0 && idx == oidx && has_out) v[k] = opre[k];        // prefetched above
+          else v[k] = (s0 + k < ns) ? ld_agent(&pou[(size_t)(s0 + k) * G * D + idx]) : 0.f;
+        }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           if (s0 + k < ns) {
@@ -582,7 +620,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 #undef CONFKV_DPP
 
 template <int G>
-__global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, AttendLaunch a,
+__global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void attend_mfma_kernel(CacheView cv, AttendLaunch a,
                                                                   int ns, int S) {
   constexpr int D = 128;
   constexpr int NP = kAttWaves;                 // one partial per wavefront
@@ -640,26 +678,36 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
   const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
 
   const int ntiles = (sl.cnt8 + kTile - 1) / kTile;            // 0 when the split has no INT8 slot
-  int4 kq[4], vq[4];
-  unsigned short ksh[2], vsh[2];
-  // branch-free (rows past the slice re-read its last row; their scores are masked and their
-  // probabilities are zero), so the whole tile is in flight before anything is waited for
-  auto issue_loads = [&](int tile) {
+  // One INT8 tile in flight: four 128-bit K pieces, four V pieces and the raw scale bits.
+  // Loads are branch-free (rows past the slice re-read its last row; their scores are masked
+  // and their probabilities are zero), so the whole tile is in flight before any wait.
+  struct TileRegs {
+    int4 k0, k1, k2, k3, v0, v1, v2, v3;
+    unsigned short ks0, ks1, vs0, vs1;
+  };
+  auto load_tile = [&](int tile) -> TileRegs {
+    TileRegs t;
     const int base = sl.lo8 + tile * kTile;
     const int last = sl.hi8 - 1;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int i = min(base + 8 * r + r8, last);
-      kq[r] = *(const int4 *)(K8 + (size_t)i * D + c8 * 16);
-      vq[r] = *(const int4 *)(V8 + (size_t)i * D + c8 * 16);
-    }
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      const int i = min(base + 16 * sb + t16, last);
-      ksh[sb] = ((const unsigned short *)KS)[i];
-      vsh[sb] = ((const unsigned short *)VS)[i];
-    }
+    const size_t col = (size_t)c8 * 16;
+    const int i0 = min(base + r8, last), i1 = min(base + 8 + r8, last);
+    const int i2 = min(base + 16 + r8, last), i3 = min(base + 24 + r8, last);
+    t.k0 = *(const int4 *)(K8 + (size_t)i0 * D + col);
+    t.v0 = *(const int4 *)(V8 + (size_t)i0 * D + col);
+    t.k1 = *(const int4 *)(K8 + (size_t)i1 * D + col);
+    t.v1 = *(const int4 *)(V8 + (size_t)i1 * D + col);
+    t.k2 = *(const int4 *)(K8 + (size_t)i2 * D + col);
+    t.v2 = *(const int4 *)(V8 + (size_t)i2 * D + col);
+    t.k3 = *(const int4 *)(K8 + (size_t)i3 * D + col);
+    t.v3 = *(const int4 *)(V8 + (size_t)i3 * D + col);
+    const int j0 = min(base + t16, last), j1 = min(base + 16 + t16, last);
+    t.ks0 = ((const unsigned short *)KS)[j0];
+    t.vs0 = ((const unsigned short *)VS)[j0];
+    t.ks1 = ((const unsigned short *)KS)[j1];
+    t.vs1 = ((const unsigned short *)VS)[j1];
+    return t;
   };
+  TileRegs tr = {};
   // ---------------- FP16 slots: 16-slot tiles on the matrix cores, taken first ----------------
   // (tiles go to the wavefronts from the back, which hold the fewest INT8 tiles; the first
   // INT8 tile's loads are already in flight while the FP16 tile is computed)
@@ -679,15 +727,15 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
         kh[r] = *(const int4 *)(K16 + off);
         vh[r] = *(const int4 *)(V16 + off);
       }
-      if (first && w < ntiles) issue_loads(w);
+      if (first && w < ntiles) tr = load_tile(w);
       first = false;
       // K rows as they are (row stride kKRow16 bytes), V transposed to [channel][slot]
 #pragma unroll
       for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (4 * r + r4) * kKRow16 + c16 * 16) = kh[r];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const unsigned x0 = ((const unsigned *)&vh[0])[q4], x1 = ((const unsigned *)&vh[1])[q4];
-        const unsigned x2 = ((const unsigned *)&vh[2])[q4], x3 = ((const unsigned *)&vh[3])[q4];
+        const unsigned x0 = dword_of(vh[0], q4), x1 = dword_of(vh[1], q4);
+        const unsigned x2 = dword_of(vh[2], q4), x3 = dword_of(vh[3], q4);
         // half r of each pair is slot 4r + r4; it lands at column 4*r4 + r
         unsigned *dst = (unsigned *)(Vt + (8 * c16 + 2 * q4) * kVRow + 8 * r4);
         dst[0] = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
@@ -733,19 +781,21 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
       }
       wave_lds_sync();
     }
-    if (first && w < ntiles) issue_loads(w);
+    if (first && w < ntiles) tr = load_tile(w);
   }
   int tix = 0;
   for (int tile = w; tile < ntiles; tile += kAttWaves) {
     const int base = sl.lo8 + tile * kTile;
     if (tix < 6) TS(4 + 2 * tix);
     // ---- registers -> LDS: K rows as they are, V transposed to [channel][slot] ----
-#pragma unroll
-    for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (8 * r + r8) * kKRow + c8 * 16) = kq[r];
+    *(int4 *)(Kt + (r8)*kKRow + c8 * 16) = tr.k0;
+    *(int4 *)(Kt + (8 + r8) * kKRow + c8 * 16) = tr.k1;
+    *(int4 *)(Kt + (16 + r8) * kKRow + c8 * 16) = tr.k2;
+    *(int4 *)(Kt + (24 + r8) * kKRow + c8 * 16) = tr.k3;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
-      const unsigned x0 = ((const unsigned *)&vq[0])[q4], x1 = ((const unsigned *)&vq[1])[q4];
-      const unsigned x2 = ((const unsigned *)&vq[2])[q4], x3 = ((const unsigned *)&vq[3])[q4];
+      const unsigned x0 = dword_of(tr.v0, q4), x1 = dword_of(tr.v1, q4);
+      const unsigned x2 = dword_of(tr.v2, q4), x3 = dword_of(tr.v3, q4);
       const unsigned t0 = __builtin_amdgcn_perm(x1, x0, 0x05010400u), t1 = __builtin_amdgcn_perm(x1, x0, 0x07030602u);
       const unsigned t2 = __builtin_amdgcn_perm(x3, x2, 0x05010400u), t3 = __builtin_amdgcn_perm(x3, x2, 0x07030602u);
       const unsigned o0 = __builtin_amdgcn_perm(t2, t0, 0x05040100u), o1 = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
@@ -757,15 +807,15 @@ __global__ __launch_bounds__(kAttThreads) void attend_mfma_kernel(CacheView cv, 
       *(unsigned *)(dst + 2 * kVRow) = o2;
       *(unsigned *)(dst + 3 * kVRow) = o3;
     }
-    const float kscale[2] = {__half2float(__ushort_as_half(ksh[0])) * sm,
-                             __half2float(__ushort_as_half(ksh[1])) * sm};
-    const float vscale[2] = {__half2float(__ushort_as_half(vsh[0])),
-                             __half2float(__ushort_as_half(vsh[1]))};
+    const float kscale[2] = {__half2float(__ushort_as_half(tr.ks0)) * sm,
+                             __half2float(__ushort_as_half(tr.ks1)) * sm};
+    const float vscale[2] = {__half2float(__ushort_as_half(tr.vs0)),
+                             __half2float(__ushort_as_half(tr.vs1))};
     wave_lds_sync();
     if (tix < 6) TS(5 + 2 * tix);
     ++tix;
     // the registers are free again: fetch this wavefront's next tile while computing
-    if (tile + kAttWaves < ntiles) issue_loads(tile + kAttWaves);
+    if (tile + kAttWaves < ntiles) tr = load_tile(tile + kAttWaves);
 
     // ---- scores: S[head][slot] for the two 16-slot halves of the tile ----
     floatx4_t sc[2];
@@ -942,8 +992,14 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   const bool mfma = wants_mfma(D, G, n16_ub < n_ub);
   AttendFn fn = mfma ? attend_fn_mfma(D, G) : attend_fn_valu(D, G);
   const long long nv = (long long)n_ub + n16_ub;
-  // aim for about three workgroups per CU, but keep at least 128 virtual slots per split
-  int want = forced_splits > 0 ? forced_splits : (3 * lim.cus + units_per_layer - 1) / units_per_layer;
+  // One workgroup per CU measured best: the exchange between the splits of a unit (arrival
+  // counter, partial gather) gets slower with more participants, and a grid that is not a
+  // whole number of waves over the CUs leaves a straggler round.  Two per CU only when a
+  // single split per unit would leave half of the chip idle.  Keep >= 128 virtual slots a split.
+  int want = lim.cus / units_per_layer;
+  if (want < 1) want = 1;
+  if (want == 1 && 2 * units_per_layer <= 2 * lim.cus && units_per_layer > lim.cus / 2) want = 2;
+  if (forced_splits > 0) want = forced_splits;
   want = std::min<long long>(want, std::max<long long>(1, nv / 128));
   want = std::max(1, std::min(want, kAttendMaxSplits));
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
