@@ -20,7 +20,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct StateLayout {
-  size_t len, n8, head16, budget, n_tight, n_loose, stats, ema, pos, ks, vs, k8, v8, k16, v16, total;
+  size_t len, n8, head16, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, ema, pos, ks, vs, k8, v8, k16, v16, total;
   size_t header_bytes;   // [0, header_bytes) is zeroed at create
   int cap8, cap16;
 };
@@ -65,6 +65,8 @@ StateLayout state_layout(const conf_kv_config *c) {
   s.n8 = take(U * 4);
   s.head16 = take(U * 4);
   s.stats = take(kStatSlots * 8);
+  s.unit_evicted = take(U * 4);
+  s.unit_demoted = take(U * 4);
   s.header_bytes = off;
   s.budget = take((size_t)c->n_layers * c->batch * 4);
   s.n_tight = take((size_t)c->n_layers * 4);
@@ -182,6 +184,8 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   cv.n_tight = (const int32_t *)(s + h->sl.n_tight);
   cv.n_loose = (const int32_t *)(s + h->sl.n_loose);
   cv.stats = (unsigned long long *)(s + h->sl.stats);
+  cv.unit_evicted = (unsigned *)(s + h->sl.unit_evicted);
+  cv.unit_demoted = (unsigned *)(s + h->sl.unit_demoted);
   cv.L = L;
   cv.B = cfg->batch;
   cv.Hkv = cfg->n_kv_heads;
@@ -301,11 +305,14 @@ int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, ui
 int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   if (!h) return CONF_KV_ERR_INVALID_ARG;
   LayerMask m{};
-  for (int l = 0; l < h->cfg.n_layers; ++l)
+  bool long_units = false;
+  for (int l = 0; l < h->cfg.n_layers; ++l) {
     if (h->appended[l]) m.set(l);
+    if (h->len_ub[l] + h->appended[l] >= 8192) long_units = true;
+  }
   CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, (double *)(h->scratch + h->kl.score),
                                  (int32_t *)(h->scratch + h->kl.src),
-                                 (int32_t *)(h->scratch + h->kl.sel), (hipStream_t)stream));
+                                 (int32_t *)(h->scratch + h->kl.sel), long_units, (hipStream_t)stream));
   const int P = h->cfg.protected_window;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     if (h->appended[l]) {
@@ -396,8 +403,12 @@ int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *st) {
   unsigned long long raw[kStatSlots];
   CK_HIP(h, hipDeviceSynchronize());
   CK_HIP(h, hipMemcpy(raw, h->cv.stats, sizeof(raw), hipMemcpyDeviceToHost));
-  st->evicted = raw[kStatEvicted];
-  st->demoted = raw[kStatDemoted];
+  const size_t U = (size_t)h->cfg.n_layers * h->cfg.batch * h->cfg.n_kv_heads;
+  std::vector<unsigned> ev(U), dm(U);
+  CK_HIP(h, hipMemcpy(ev.data(), h->cv.unit_evicted, U * 4, hipMemcpyDeviceToHost));
+  CK_HIP(h, hipMemcpy(dm.data(), h->cv.unit_demoted, U * 4, hipMemcpyDeviceToHost));
+  st->evicted = st->demoted = 0;
+  for (size_t u = 0; u < U; ++u) { st->evicted += ev[u]; st->demoted += dm[u]; }
   st->tight_steps = raw[kStatTight];
   st->loose_steps = raw[kStatLoose];
   st->device_errors = raw[kStatDeviceErr];

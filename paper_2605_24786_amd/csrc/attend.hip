@@ -602,7 +602,7 @@ __device__ __forceinline__ half8_t cvt_i8x8_f16x8(unsigned w0, unsigned w1) {
 
 // max / sum over the 16 lanes of a DPP row; every lane of the row gets the result
 #define CONFKV_DPP(v, ctrl) \
-  __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, false))
+  __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true))
 __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, CONFKV_DPP(v, 0xB1));    // quad_perm [1,0,3,2]
   v = fmaxf(v, CONFKV_DPP(v, 0x4E));    // quad_perm [2,3,0,1]

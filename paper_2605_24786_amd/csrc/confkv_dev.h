@@ -24,6 +24,7 @@ enum StatSlot { kStatEvicted = 0, kStatDemoted = 1, kStatTight = 2, kStatLoose =
 //   pos      int32 [U][cap]       original position, by slot (strictly increasing)
 //   len, n8, head16  int32 [U]    committed length, INT8 count, ring head
 //   budget   int32 [L][B]         N selected by the last confidence step
+//   unit_evicted, unit_demoted  uint32 [U]  tokens evicted / demoted so far, per unit
 struct CacheView {
   int8_t *k8, *v8;
   __half *ks, *vs;
@@ -33,6 +34,7 @@ struct CacheView {
   int32_t *len, *n8, *head16, *budget;
   const int32_t *n_tight, *n_loose;
   unsigned long long *stats;
+  unsigned *unit_evicted, *unit_demoted;   // [U] per-unit event counts
   int32_t L, B, Hkv, G, D, cap, cap8, cap16, W, P;
 };
 

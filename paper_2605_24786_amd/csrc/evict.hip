@@ -6,7 +6,7 @@
 // the FP16 window; Algorithm 1, per-layer tail).
 //
 // Three launches cover every layer:
-//   rank_select   one workgroup per unit: float64 scores, radix select of the eviction
+//   rank_select   one 1024-thread workgroup per unit: float64 scores, radix select of the eviction
 //                 cut-off, ordered survivor list
 //   compact       one workgroup per (unit, plane): in-place, order-preserving gather
 //   demote        one wavefront per unit: quantise the FP16 slots that left the window,
@@ -29,21 +29,31 @@ __device__ __forceinline__ void quantize_row_wave(const __half *__restrict__ src
                                                   __half *__restrict__ dst_scale, int lane) {
   constexpr int EPL = D / kWave;                 // elements per lane (1 or 2)
   float x[EPL];
+  if constexpr (EPL == 2) {
+    const __half2 v = ((const __half2 *)src)[lane];
+    x[0] = __low2float(v);
+    x[1] = __high2float(v);
+  } else {
+    x[0] = __half2float(src[lane]);
+  }
   float amax = 0.f;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) {
-    x[e] = __half2float(src[lane * EPL + e]);
-    amax = fmaxf(amax, fabsf(x[e]));
-  }
+  for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(x[e]));
   amax = wave_max(amax);
   const __half hs = __float2half_rn(__fdiv_rn(amax, 127.0f));
   const float sf = __half2float(hs);
   const bool dead = !(sf > 0.f) || isinf(sf);
+  int code[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) {
     float r = dead ? 0.f : rintf(__fdiv_rn(x[e], sf));
     r = fminf(fmaxf(r, -127.f), 127.f);
-    dst_codes[lane * EPL + e] = (int8_t)(int)r;
+    code[e] = (int)r;
+  }
+  if constexpr (EPL == 2) {
+    ((unsigned short *)dst_codes)[lane] = (unsigned short)((code[0] & 0xff) | ((code[1] & 0xff) << 8));
+  } else {
+    dst_codes[lane] = (int8_t)code[0];
   }
   if (lane == 0) *dst_scale = dead ? __float2half_rn(0.f) : hs;
 }
@@ -89,25 +99,46 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// rank_select: grid (U), 256 threads.
+// rank_select: grid (U), 256 threads (1024 for long units, which would otherwise take
+// dozens of chunk rounds).
 //
 // score_i = alpha * a_hat_i + (1 - alpha) * r_hat_i in float64 with every operation
 // rounded separately (no fused multiply-add), so equal inputs give bit-equal scores on
 // any IEEE machine.  The e lowest (score, slot) pairs are evicted: an 8-bit-digit radix
 // select over the score's bit pattern (non-negative doubles order like unsigned integers)
 // finds the cut-off, stopping as soon as the cut-off bucket is evicted whole; slots that
-// tie with the cut-off go oldest first.
+// tie with the cut-off go oldest first (this needs a second prefix sum only when the
+// select ran to the last digit and equal scores straddle the cut-off).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kEvThreads) void rank_select_kernel(CacheView cv, LayerMask appended,
+
+// Exclusive prefix sum over a workgroup of kRsWaves wavefronts (<= 16); *total gets the
+// workgroup sum.  `tmp` is kRsWaves ints of LDS.  Contains barriers; all threads must call it.
+template <int kRsWaves>
+__device__ __forceinline__ int block_scan_excl(int v, int *tmp, int *total) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+  const int inc = wave_scan_incl(v);
+  __syncthreads();                       // tmp may still be read from a previous call
+  if (lane == kWave - 1) tmp[w] = inc;
+  __syncthreads();
+  int mine = lane < kRsWaves ? tmp[lane] : 0;
+  const int incw = wave_scan_incl(mine);                 // every wave scans the 16 wave totals
+  const int off = __shfl(incw - mine, w, kWave);         // exclusive offset of this wave
+  *total = __shfl(incw, kRsWaves - 1, kWave);
+  return off + inc - v;
+}
+
+template <int kRsThreads>
+__global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, LayerMask appended,
                                                                  double alpha,
                                                                  double *__restrict__ score_all,
                                                                  int32_t *__restrict__ src_all,
                                                                  int32_t *__restrict__ sel_all) {
+  constexpr int kRsWaves = kRsThreads / kWave;
   __shared__ int hist[256];
-  __shared__ int s_tmp[4];
-  __shared__ float s_fmin[4], s_fmax[4];
+  __shared__ int s_tmp[kRsWaves];
+  __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
   __shared__ unsigned long long s_prefix;
-  __shared__ int s_krem, s_done, s_hole[4];
+  __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x;
   const int UPL = cv.B * cv.Hkv;
@@ -130,45 +161,47 @@ __global__ __launch_bounds__(kEvThreads) void rank_select_kernel(CacheView cv, L
 
   // min / max of the EMA over the candidates
   float fmin_ = INFINITY, fmax_ = -INFINITY;
-  for (int i = tid; i < ncand; i += kEvThreads) {
-    float a = ema[i];
+  for (int i = tid; i < ncand; i += kRsThreads) {
+    const float a = ema[i];
     fmin_ = fminf(fmin_, a);
     fmax_ = fmaxf(fmax_, a);
   }
   fmin_ = wave_min(fmin_);
   fmax_ = wave_max(fmax_);
   if (lane == 0) { s_fmin[w] = fmin_; s_fmax[w] = fmax_; }
+  if (tid == 0) { s_prefix = 0ull; s_krem = e; s_done = 0; }
   __syncthreads();
-  const double a_lo = (double)fminf(fminf(s_fmin[0], s_fmin[1]), fminf(s_fmin[2], s_fmin[3]));
-  const double a_hi = (double)fmaxf(fmaxf(s_fmax[0], s_fmax[1]), fmaxf(s_fmax[2], s_fmax[3]));
+  float lo_f = s_fmin[0], hi_f = s_fmax[0];
+#pragma unroll
+  for (int k = 1; k < kRsWaves; ++k) { lo_f = fminf(lo_f, s_fmin[k]); hi_f = fmaxf(hi_f, s_fmax[k]); }
+  const double a_lo = (double)lo_f, a_hi = (double)hi_f;
   const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
-  for (int i = tid; i < ncand; i += kEvThreads) {
+  for (int i = tid; i < ncand; i += kRsThreads) {
     const double ah = (a_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)ema[i], a_lo), a_rng);
     const double rh = (p_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)pos[i], p_lo), p_rng);
     score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
   }
-  if (tid == 0) { s_prefix = 0ull; s_krem = e; s_done = 0; }
-  __syncthreads();                                  // also orders the score writes before reads
+  __syncthreads();                                  // orders the score writes before the reads
 
   // radix select of the e-th smallest score
   unsigned long long mask = 0ull;
   for (int shift = 56; shift >= 0; shift -= 8) {
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     const unsigned long long prefix = s_prefix;
-    for (int i = tid; i < ncand; i += kEvThreads) {
+    for (int i = tid; i < ncand; i += kRsThreads) {
       const unsigned long long key = (unsigned long long)__double_as_longlong(score[i]);
       if ((key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255ull)], 1);
     }
     __syncthreads();
-    const int cnt = hist[tid];
+    const int cnt = tid < 256 ? hist[tid] : 0;
     int total;
-    const int before = block256_scan_excl(cnt, s_tmp, &total);
+    const int before = block_scan_excl<kRsWaves>(cnt, s_tmp, &total);
     const int krem = s_krem;
     __syncthreads();                                // every thread has read s_krem
-    if (before < krem && krem <= before + cnt) {    // exactly one bin holds the cut-off
+    if (tid < 256 && before < krem && krem <= before + cnt) {   // exactly one bin holds the cut-off
       s_prefix = prefix | ((unsigned long long)tid << shift);
       s_krem = krem - before;
       s_done = (krem - before == cnt);              // the whole bucket goes
@@ -179,10 +212,11 @@ __global__ __launch_bounds__(kEvThreads) void rank_select_kernel(CacheView cv, L
   }
   const unsigned long long prefix = s_prefix;
   const int krem = s_krem;
+  const bool whole_bucket = s_done != 0;            // no tie ranking needed
 
   // survivor list in slot order; ties with the cut-off are evicted oldest first
   int carry_keep = 0, carry_tie = 0, kept8 = 0, hole = n;
-  for (int base = 0; base < n; base += kEvThreads) {
+  for (int base = 0; base < n; base += kRsThreads) {
     const int i = base + tid;
     int tie = 0, below = 0;
     if (i < ncand) {
@@ -190,13 +224,18 @@ __global__ __launch_bounds__(kEvThreads) void rank_select_kernel(CacheView cv, L
       below = km < prefix;
       tie = km == prefix;
     }
-    int tot_tie;
-    const int tie_rank = carry_tie + block256_scan_excl(tie, s_tmp, &tot_tie);
-    carry_tie += tot_tie;
-    const int evict = below | (tie & (tie_rank < krem));
+    int evict;
+    if (whole_bucket) {
+      evict = below | tie;
+    } else {
+      int tot_tie;
+      const int tie_rank = carry_tie + block_scan_excl<kRsWaves>(tie, s_tmp, &tot_tie);
+      carry_tie += tot_tie;
+      evict = below | (tie & (tie_rank < krem));
+    }
     const int keep = (i < n) & !evict;
     int tot_keep;
-    const int j = carry_keep + block256_scan_excl(keep, s_tmp, &tot_keep);
+    const int j = carry_keep + block_scan_excl<kRsWaves>(keep, s_tmp, &tot_keep);
     carry_keep += tot_keep;
     if (keep) {
       src[j] = i;
@@ -206,15 +245,17 @@ __global__ __launch_bounds__(kEvThreads) void rank_select_kernel(CacheView cv, L
   }
   kept8 = wave_sum(kept8);
   hole = wave_min(hole);
-  __syncthreads();
-  if (lane == 0) { s_tmp[w] = kept8; s_hole[w] = hole; }
+  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; }
   __syncthreads();
   if (tid == 0) {
+    int k8 = 0, hl = n;
+#pragma unroll
+    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); }
     sel[0] = carry_keep;                              // = n - e
-    sel[1] = s_tmp[0] + s_tmp[1] + s_tmp[2] + s_tmp[3];
-    sel[2] = min(min(s_hole[0], s_hole[1]), min(s_hole[2], s_hole[3]));
+    sel[1] = k8;
+    sel[2] = hl;
     sel[3] = e;
-    atomicAdd(&cv.stats[kStatEvicted], (unsigned long long)e);
+    cv.unit_evicted[u] += (unsigned)e;              // per-unit counter: no contended atomic
   }
 }
 
@@ -320,13 +361,14 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
 }
 
 // ---------------------------------------------------------------------------------------
-// demote: grid (U), one wavefront.  Quantises the oldest FP16 slots until at most W stay
+// demote: grid (U / 4), one wavefront per unit.  Quantises the oldest FP16 slots until at most W stay
 // FP16, appends them to the INT8 rows, and commits (len, n8, head16).
 // ---------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kWave) void demote_kernel(CacheView cv,
-                                                       const int32_t *__restrict__ sel_all) {
-  const int u = blockIdx.x, lane = threadIdx.x;
+__global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
+                                                            const int32_t *__restrict__ sel_all, int U) {
+  const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (u >= U) return;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
   const int n_new = sel[0], n8_new = sel[1];
   const int h16 = cv.head16[u];
@@ -342,7 +384,7 @@ __global__ __launch_bounds__(kWave) void demote_kernel(CacheView cv,
     cv.len[u] = n_new;
     cv.n8[u] = n8_new + cnt;
     cv.head16[u] = ring_row(h16, cnt % cv.cap16, cv.cap16);
-    if (cnt) atomicAdd(&cv.stats[kStatDemoted], (unsigned long long)cnt);
+    if (cnt) cv.unit_demoted[u] += (unsigned)cnt;
   }
 }
 
@@ -361,18 +403,23 @@ hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16
 }
 
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
-                                double *score, int32_t *src, int32_t *sel, hipStream_t stream) {
+                                double *score, int32_t *src, int32_t *sel, bool long_units,
+                                hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
-  hipLaunchKernelGGL(rank_select_kernel, dim3(U), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                     score, src, sel);
+  if (long_units)
+    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha,
+                       score, src, sel);
+  else
+    hipLaunchKernelGGL(rank_select_kernel<256>, dim3(U), dim3(256), 0, stream, cv, appended, alpha,
+                       score, src, sel);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (cv.D == 64) {
     hipLaunchKernelGGL(compact_kernel<64>, dim3(U, 5), dim3(kEvThreads), 0, stream, cv, src, sel);
-    hipLaunchKernelGGL(demote_kernel<64>, dim3(U), dim3(kWave), 0, stream, cv, sel);
+    hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
   } else {
     hipLaunchKernelGGL(compact_kernel<128>, dim3(U, 5), dim3(kEvThreads), 0, stream, cv, src, sel);
-    hipLaunchKernelGGL(demote_kernel<128>, dim3(U), dim3(kWave), 0, stream, cv, sel);
+    hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
   }
   return hipGetLastError();
 }
