@@ -305,14 +305,14 @@ int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, ui
 int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   if (!h) return CONF_KV_ERR_INVALID_ARG;
   LayerMask m{};
-  bool long_units = false;
+  int n_max = 0;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     if (h->appended[l]) m.set(l);
-    if (h->len_ub[l] + h->appended[l] >= 8192) long_units = true;
+    n_max = std::max(n_max, h->len_ub[l] + (int)h->appended[l]);
   }
   CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, (double *)(h->scratch + h->kl.score),
                                  (int32_t *)(h->scratch + h->kl.src),
-                                 (int32_t *)(h->scratch + h->kl.sel), long_units, (hipStream_t)stream));
+                                 (int32_t *)(h->scratch + h->kl.sel), n_max, (hipStream_t)stream));
   const int P = h->cfg.protected_window;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     if (h->appended[l]) {

@@ -260,6 +260,237 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
 }
 
 // ---------------------------------------------------------------------------------------
+// rank_select, register-resident variant: grid (U), T threads; thread t owns the slots
+// t, t + T, t + 2T, .. (at most E of them), so every load is coalesced and the scores never
+// leave the registers between the select passes.  The survivor list is ranked with
+// wavefront ballots: for slot round k, the kept lanes of a wavefront are counted with one
+// ballot, the (round, wavefront) counts are prefix-summed once by the workgroup, and each
+// kept slot lands at base(round, wavefront) + its rank inside the ballot.  Same arithmetic
+// and same decisions as rank_select_kernel; used whenever the longest unit fits (n <= T * E).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int lanes_below(unsigned long long m) {   // set bits of m below this lane
+  return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0));
+}
+
+template <int T, int E>
+__global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerMask appended,
+                                                            double alpha,
+                                                            int32_t *__restrict__ src_all,
+                                                            int32_t *__restrict__ sel_all) {
+  constexpr int kRsWaves = T / kWave;
+  __shared__ int hist[256];
+  __shared__ int s_tmp[kRsWaves];
+  __shared__ int s_cnt[E * kRsWaves];               // kept (or tied) lanes per (round, wavefront)
+  __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
+  __shared__ unsigned long long s_prefix, s_kmin[kRsWaves], s_kmax[kRsWaves];
+  __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int u = blockIdx.x;
+  const int UPL = cv.B * cv.Hkv;
+  const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
+  const int n = cv.len[u] + (appended.get(layer) ? 1 : 0);
+  const int n8 = cv.n8[u];
+  const int N = cv.budget[layer * cv.B + b];
+  int32_t *sel = sel_all + (size_t)u * kSelInts;
+  const int p_eff = min(cv.P, n);
+  const int ncand = n - p_eff;
+  const int e = min(n - N, ncand);
+  if (n <= N || e <= 0) {
+    if (tid == 0) { sel[0] = n; sel[1] = n8; sel[2] = n; sel[3] = 0; }
+    return;
+  }
+  const float *ema = cv.ema + (size_t)u * cv.cap;
+  const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  int32_t *src = src_all + (size_t)u * cv.cap;
+  const int Ed = (n + T - 1) / T;                   // rounds in use, <= E (checked by the host)
+
+  // candidate EMA / position of the owned slots, min / max of the EMA
+  float av[E];
+  float fmin_ = INFINITY, fmax_ = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    const int i = tid + k * T;
+    av[k] = (k < Ed && i < ncand) ? ema[i] : 0.f;
+  }
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    if (k < Ed && tid + k * T < ncand) { fmin_ = fminf(fmin_, av[k]); fmax_ = fmaxf(fmax_, av[k]); }
+  }
+  fmin_ = wave_min(fmin_);
+  fmax_ = wave_max(fmax_);
+  if (lane == 0) { s_fmin[w] = fmin_; s_fmax[w] = fmax_; }
+  if (tid == 0) { s_prefix = 0ull; s_krem = e; s_done = 0; }
+  __syncthreads();
+  float lo_f = s_fmin[0], hi_f = s_fmax[0];
+#pragma unroll
+  for (int k = 1; k < kRsWaves; ++k) { lo_f = fminf(lo_f, s_fmin[k]); hi_f = fmaxf(hi_f, s_fmax[k]); }
+  const double a_lo = (double)lo_f, a_hi = (double)hi_f;
+  const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
+  const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
+  const double oma = __dsub_rn(1.0, alpha);
+  unsigned long long key[E];
+  unsigned long long kmin = ~0ull, kmax = 0ull;
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    const int i = tid + k * T;
+    key[k] = 0ull;
+    if (k < Ed && i < ncand) {
+      const double ah = (a_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)av[k], a_lo), a_rng);
+      const double rh = (p_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)pos[i], p_lo), p_rng);
+      key[k] = (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
+      kmin = key[k] < kmin ? key[k] : kmin;
+      kmax = key[k] > kmax ? key[k] : kmax;
+    }
+  }
+  // Keys are taken relative to the smallest candidate key, and the select starts at the top
+  // bit in which the candidates differ: the scores live in [0, 1], so the leading sign and
+  // exponent bits are the same for almost all of them and would put every candidate into one
+  // histogram bin (LDS atomics on one address serialise).
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const unsigned long long a2 = __shfl_xor(kmin, m, kWave), b2 = __shfl_xor(kmax, m, kWave);
+    kmin = a2 < kmin ? a2 : kmin;
+    kmax = b2 > kmax ? b2 : kmax;
+  }
+  if (lane == 0) { s_kmin[w] = kmin; s_kmax[w] = kmax; }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kRsWaves; ++k) {
+    kmin = s_kmin[k] < kmin ? s_kmin[k] : kmin;
+    kmax = s_kmax[k] > kmax ? s_kmax[k] : kmax;
+  }
+#pragma unroll
+  for (int k = 0; k < E; ++k) key[k] -= kmin;          // order-preserving
+  const unsigned long long span = kmax - kmin;
+  const int top = span ? 63 - __clzll((long long)span) : 0;   // highest differing bit
+
+  // radix select of the e-th smallest key, 8 bits (or what is left) per pass
+  unsigned long long mask = 0ull;
+  for (int hi_bit = top + 1; hi_bit > 0;) {
+    const int shift = hi_bit > 8 ? hi_bit - 8 : 0;
+    const unsigned dmask = (1u << (hi_bit - shift)) - 1u;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    const unsigned long long prefix = s_prefix;
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+      if (k < Ed && tid + k * T < ncand && (key[k] & mask) == prefix)
+        atomicAdd(&hist[(int)((unsigned)(key[k] >> shift) & dmask)], 1);
+    }
+    __syncthreads();
+    const int cnt = tid < 256 ? hist[tid] : 0;
+    int total;
+    const int before = block_scan_excl<kRsWaves>(cnt, s_tmp, &total);
+    const int krem = s_krem;
+    __syncthreads();                                // every thread has read s_krem
+    if (tid < 256 && before < krem && krem <= before + cnt) {   // exactly one bin holds the cut-off
+      s_prefix = prefix | ((unsigned long long)tid << shift);
+      s_krem = krem - before;
+      s_done = (krem - before == cnt);              // the whole bucket goes
+    }
+    mask = ~0ull << shift;
+    hi_bit = shift;
+    __syncthreads();
+    if (s_done) break;
+  }
+  const unsigned long long prefix = s_prefix;
+  const int krem = s_krem;
+  const bool whole = s_done != 0;                   // uniform over the workgroup
+
+  // Only part of the cut-off bucket goes: rank the tied slots in slot order (oldest first).
+  // tie_rank(round k, lane) = base(k, wavefront) + rank inside the round's ballot.
+  if (!whole) {
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+      if (k < Ed) {
+        const bool tie = tid + k * T < ncand && (key[k] & mask) == prefix;
+        const unsigned long long bm = __builtin_amdgcn_ballot_w64(tie);
+        if (lane == 0) s_cnt[k * kRsWaves + w] = __builtin_popcountll(bm);
+      }
+    }
+    __syncthreads();
+    for (int base = 0; base < Ed * kRsWaves; base += T) {       // in-place exclusive scan
+      const int idx = base + tid;
+      const int v = idx < Ed * kRsWaves ? s_cnt[idx] : 0;
+      int tot;
+      const int ex = block_scan_excl<kRsWaves>(v, s_tmp, &tot);
+      __syncthreads();
+      if (idx < Ed * kRsWaves) s_cnt[idx] = ex;                 // one chunk when Ed * waves <= T
+    }
+    __syncthreads();
+  }
+  // eviction flags as a bit per round
+  unsigned long long evbits = 0ull;                 // E <= 64
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    if (k < Ed) {
+      const int i = tid + k * T;
+      bool ev = false;
+      bool tie = false;
+      if (i < ncand) {
+        const unsigned long long km = key[k] & mask;
+        ev = km < prefix;
+        tie = km == prefix;
+      }
+      if (whole) {
+        ev |= tie;
+      } else {
+        const unsigned long long bm = __builtin_amdgcn_ballot_w64(tie);
+        if (tie) ev = s_cnt[k * kRsWaves + w] + lanes_below(bm) < krem;
+      }
+      if (ev) evbits |= 1ull << k;
+    }
+  }
+  __syncthreads();                                  // s_cnt is reused for the keep counts
+  int kept8 = 0, hole = n;
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    if (k < Ed) {
+      const int i = tid + k * T;
+      const bool ev = (evbits >> k) & 1ull;
+      const bool keep = i < n && !ev;
+      const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
+      if (lane == 0) s_cnt[k * kRsWaves + w] = __builtin_popcountll(bm);
+      kept8 += keep && i < n8;
+      if (ev) hole = min(hole, i);
+    }
+  }
+  __syncthreads();
+  int tot_keep = 0;
+  {
+    // Ed * waves <= T for both instantiations' limits (20 * 4, 33 * 16): one scan
+    const int v = tid < Ed * kRsWaves ? s_cnt[tid] : 0;
+    const int ex = block_scan_excl<kRsWaves>(v, s_tmp, &tot_keep);
+    __syncthreads();
+    if (tid < Ed * kRsWaves) s_cnt[tid] = ex;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    if (k < Ed) {
+      const int i = tid + k * T;
+      const bool keep = i < n && !((evbits >> k) & 1ull);
+      const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
+      if (keep) src[s_cnt[k * kRsWaves + w] + lanes_below(bm)] = i;
+    }
+  }
+  kept8 = wave_sum(kept8);
+  hole = wave_min(hole);
+  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; }
+  __syncthreads();
+  if (tid == 0) {
+    int k8 = 0, hl = n;
+#pragma unroll
+    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); }
+    sel[0] = tot_keep;                                // = n - e
+    sel[1] = k8;
+    sel[2] = hl;
+    sel[3] = e;
+    cv.unit_evicted[u] += (unsigned)e;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // compact: grid (U, 5 planes), 256 threads.  Destination slot j takes source slot src[j]
 // >= j.  A workgroup walks its plane front to back in chunks: load a chunk into registers,
 // barrier, store.  Earlier chunks only wrote below the chunk start, later sources all lie
@@ -403,14 +634,17 @@ hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16
 }
 
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
-                                double *score, int32_t *src, int32_t *sel, bool long_units,
+                                double *score, int32_t *src, int32_t *sel, int n_max,
                                 hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
-  if (long_units)
-    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha,
-                       score, src, sel);
+  if (n_max <= 256 * 20)
+    hipLaunchKernelGGL((rank_select_reg_kernel<256, 20>), dim3(U), dim3(256), 0, stream, cv, appended,
+                       alpha, src, sel);
+  else if (n_max <= 1024 * 33)
+    hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33>), dim3(U), dim3(1024), 0, stream, cv, appended,
+                       alpha, src, sel);
   else
-    hipLaunchKernelGGL(rank_select_kernel<256>, dim3(U), dim3(256), 0, stream, cv, appended, alpha,
+    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha,
                        score, src, sel);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;

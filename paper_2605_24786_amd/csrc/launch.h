@@ -49,7 +49,7 @@ constexpr int kSelInts = 4;  // per unit: new length, new INT8 count, first move
 hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
                                int T0, const float *ema0, hipStream_t stream);
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
-                                double *score, int32_t *src, int32_t *sel, bool long_units,
+                                double *score, int32_t *src, int32_t *sel, int n_max /* longest unit */,
                                 hipStream_t stream);
 
 }  // namespace confkv
