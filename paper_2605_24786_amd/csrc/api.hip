@@ -90,7 +90,7 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   s.conf_arrive = take((size_t)c->batch * 4);
-  s.arrive = take(U * 4);
+  s.arrive = take(U * kAttendMaxSplits * 4);
   s.zero_bytes = off;
   s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
   s.part_ml = take(UPL * kAttendMaxSplits * G * 2 * 4);
@@ -116,7 +116,7 @@ struct conf_kv_handle {
   std::vector<int32_t> len_ub;       // upper bound of the committed length
   std::vector<int32_t> next_pos;     // position the next appended token gets
   std::vector<uint8_t> appended;     // an append awaits its commit
-  std::vector<uint32_t> arrive_base; // value of the layer's arrival counters
+  std::vector<uint32_t> epoch;       // attend launches so far, per layer (arrival-flag value)
   int forced_splits = 0;
   int last_hip = 0;
 };
@@ -164,7 +164,7 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->len_ub.assign(L, 0);
   h->next_pos.assign(L, 0);
   h->appended.assign(L, 0);
-  h->arrive_base.assign(L, 0u);
+  h->epoch.assign(L, 0u);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
 
   CacheView &cv = h->cv;
@@ -265,8 +265,9 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
   a.out = (__half *)dev_out16;
   a.part_ml = (float *)(h->scratch + h->kl.part_ml);
   a.part_o = (float *)(h->scratch + h->kl.part_o);
-  a.arrive = (unsigned *)(h->scratch + h->kl.arrive) + (size_t)layer * UPL;
-  a.arrive_base = h->arrive_base[layer];
+  a.arrive = (unsigned *)(h->scratch + h->kl.arrive) + (size_t)layer * UPL * kAttendMaxSplits;
+  if (++h->epoch[layer] == 0u) h->epoch[layer] = 1u;     // flags start at 0: skip it on wrap
+  a.epoch = h->epoch[layer];
   a.max_splits = kAttendMaxSplits;
   a.sm_scale = h->cfg.sm_scale;
   a.ema_decay = h->cfg.ema_decay;
@@ -278,7 +279,6 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
     a.dbg = (unsigned long long *)(h->scratch + h->kl.total - (size_t)8 * 32 * 4 * 4096);
 #endif
   CK_HIP(h, launch_attend(h->cv, a, plan, (hipStream_t)stream));
-  h->arrive_base[layer] += (uint32_t)plan.splits;
   h->appended[layer] = 1;
   return CONF_KV_OK;
 }

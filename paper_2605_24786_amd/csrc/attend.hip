@@ -15,7 +15,8 @@
 //            A_i = sum_h e^{s[h][i]-M[h]} / L[h] and ema_i <- lambda ema_i + (1-lambda) A_i;
 //            every split also normalises its share of the unit's output row.
 //
-// Every K/V byte is read once; the scores never leave the chip.  The wait is between
+// Every K/V byte is read once; the scores never leave the chip.  The wait (on per-split
+// arrival flags carrying the launch's epoch) is between
 // workgroups of one launch, so the host only launches grids that are co-resident
 // (splits * units <= occupancy * CUs) and the wait itself is bounded.
 //
@@ -442,21 +443,25 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   wait_stores_done();
   __syncthreads();
   TS(20);
-  if (tid == 0) {
-    __hip_atomic_fetch_add(&a.arrive[sl.ul], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // Arrival: every split owns one flag word and stores the launch's epoch into it; nobody
+  // does a read-modify-write, so arrivals do not serialise at the memory side.  The first
+  // wavefront polls all flags of the unit with one coherent load per round (bounded).
+  unsigned *flags = a.arrive + (size_t)sl.ul * a.max_splits;
+  if (tid == 0) __hip_atomic_store(&flags[sl.j], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid < kWave) {
     int ok = 1;
     if (ns > 1) {
-      // bounded wait until all splits of the unit have published
-      const unsigned want = a.arrive_base + (unsigned)ns;
       int spins = 0;
-      while ((int)(__hip_atomic_load(&a.arrive[sl.ul], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
-                   want) < 0) {
-        __builtin_amdgcn_s_sleep(2);
+      for (;;) {
+        const bool here = tid >= ns || __hip_atomic_load(&flags[tid], __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+        if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
+        __builtin_amdgcn_s_sleep(1);
         if (++spins > kSpinLimit) { ok = 0; break; }
       }
-      if (!ok) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+      if (!ok && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
     }
-    *s_ok = ok;
+    if (tid == 0) *s_ok = ok;
   }
   __syncthreads();
   TS(21);

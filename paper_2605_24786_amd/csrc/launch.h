@@ -28,8 +28,8 @@ struct AttendLaunch {
   __half *out;
   float *part_ml;          // [units per layer][max splits][G][2]
   float *part_o;           // [units per layer][max splits][G][D]
-  unsigned *arrive;        // [units per layer], this layer's arrival counters
-  unsigned arrive_base;    // counter value before this launch
+  unsigned *arrive;        // [units per layer][max splits] arrival flags of this layer
+  unsigned epoch;          // value a split stores into its flag in this launch (never 0)
   int max_splits;
   float sm_scale, ema_decay;
   int pos_new;
