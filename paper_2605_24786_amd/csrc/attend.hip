@@ -844,19 +844,35 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     }
     if (tix <= 2) TS(24 + (tix - 1) * 3);
     // ---- online softmax per head row (rows of this lane: heads 4*g4 + i) ----
-    float corr[4];
-    bool changed = false;
+    // The running reference m only has to stay within a few units of the true maximum (the
+    // merge is exact for any reference), so the row reduction and the rescale of O run only
+    // when some score of the tile exceeds the reference by more than kSlack; e^kSlack times
+    // the largest fp16 value scale still fits fp16.
+    constexpr float kSlack = 4.0f;
+    float lm[4];
+    bool grow = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float tm = row16_max(fmaxf(sc[0][i], sc[1][i]));
-      const float mn = fmaxf(mrun[i], tm);
-      corr[i] = (mn == NEG) ? 1.f : __expf(mrun[i] - mn);
-      changed |= (mn != mrun[i]);
-      mrun[i] = mn;
+      lm[i] = fmaxf(sc[0][i], sc[1][i]);
+      grow |= lm[i] > mrun[i] + kSlack;             // also true on the first tile (m = -inf)
+    }
+    if (__builtin_amdgcn_ballot_w64(grow)) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float mn = fmaxf(mrun[i], row16_max(lm[i]));
+        const float corr = (mn == NEG) ? 1.f : __expf(mrun[i] - mn);
+        mrun[i] = mn;
+        lrun[i] *= corr;
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) O[nt][i] *= corr;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
       float psum = 0.f;
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
-        const float p = (sc[sb][i] == NEG) ? 0.f : __expf(sc[sb][i] - mn);
+        const float p = (sc[sb][i] == NEG) ? 0.f : __expf(sc[sb][i] - mrun[i]);
         psum += p;
         const int h = 4 * g4 + i;
         if (h < G) {
@@ -864,13 +880,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
           Pb[h * kPRow + 4 * (tau & 7) + (tau >> 3)] = (_Float16)(p * vscale[sb]);
         }
       }
-      lrun[i] = fmaf(lrun[i], corr[i], psum);
-    }
-    if (__builtin_amdgcn_ballot_w64(changed)) {
-#pragma unroll
-      for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) O[nt][i] *= corr[i];
+      lrun[i] += psum;
     }
     wave_lds_sync();
     if (tix <= 2) TS(25 + (tix - 1) * 3);
