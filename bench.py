@@ -97,6 +97,59 @@ def cpu_baseline(wl, seed, budget_s=15.0):
                       f"({t_conf * 1e3:.2f} ms), single thread, extrapolated to all units"}
 
 
+def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
+    """K consecutive decode steps after W warm-up steps on one loaded prompt (the cache sawtooths
+    between the budgets as the logits alternate between confident and uncertain runs)."""
+    L = wl.n_layers
+    logits_by_std = {}
+    def logits_for(t):
+        std = gen.logit_std(wl, t)
+        if std not in logits_by_std:
+            logits_by_std[std] = torch.from_numpy(gen.step_logits(wl, args.seed, t)).cuda()
+        return logits_by_std[std]
+    reload(); torch.cuda.synchronize()
+    rows = []
+    for t in range(args.warmup + args.steps):
+        lg = logits_for(t)
+        ln, n16 = kv.lengths()
+        n = ln.astype(np.int64) + 1
+        n16u = n16.astype(np.int64) + 1                                  # [L][B][Hkv], with the append
+        D, G = wl.head_dim, wl.group
+        att_bytes = int(((n[:, :, None] - n16u) * (2 * D + 4) + n16u * 4 * D + 8 * n[:, :, None]).sum()
+                        + wl.units * (4 * G * D + 8 * D + 4))
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ev[0].record()
+        for l in range(L):
+            kv.attend(l, qs[l], ks[l], vs[l], out)
+        ev[1].record()
+        kv.step(lg, conf, sel)
+        ev[2].record()
+        kv.evict_compact()
+        ev[3].record()
+        torch.cuda.synchronize()
+        if t >= args.warmup:
+            rows.append((ev[0].elapsed_time(ev[3]), ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]),
+                         ev[2].elapsed_time(ev[3]), att_bytes, float(n.mean())))
+    r = np.array(rows)
+    st = kv.counters()
+    ms_step = float(r[:, 0].mean())
+    att_gbps = float((r[:, 4] / (r[:, 1] * 1e-3)).mean() / 1e9)
+    print(json.dumps({
+        "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "mode": "steady-state", "layers": L, "batch": wl.batch,
+                   "mean_cache_len": float(r[:, 5].mean()), "attend_splits": kv.attend_splits(0)},
+        "roofline": {"bound": "hbm", "kernel": "attend", "achieved": att_gbps, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": att_gbps / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": float(r[:, 4].mean()) / L, "launch_ms": float(r[:, 1].mean()) / L},
+        "step_breakdown_ms": {"attend_x_layers": float(r[:, 1].mean()), "confidence": float(r[:, 2].mean()),
+                              "evict_compact": float(r[:, 3].mean())},
+        "counters": {"evicted": int(st.evicted), "demoted": int(st.demoted), "tight": int(st.tight_steps),
+                     "loose": int(st.loose_steps)},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +158,9 @@ def main():
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--steady", action="store_true",
+                    help="multi-step workloads: load the prompt once and time K consecutive decode steps")
+    ap.add_argument("--layers", type=int, default=0, help="keep only the first N layers (0 = all)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device-to-device copy a few times and exit (counter calibration)")
     args = ap.parse_args()
@@ -131,6 +187,8 @@ def main():
     from synth.workloads import workload
 
     wl = workload(args.workload)
+    if args.layers and args.layers < wl.n_layers:
+        wl = wl.scaled(n_layers=args.layers, n_tight=wl.n_tight[:args.layers], n_loose=wl.n_loose[:args.layers])
     L = wl.n_layers
     t_setup = time.time()
     kv = pkg.from_workload(wl)
@@ -163,6 +221,9 @@ def main():
         kv.evict_compact()
         if ev: ev[3].record()
 
+    if args.steady:
+        steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel)
+        return
     for _ in range(args.warmup):
         reload(); torch.cuda.synchronize()
         one_step(); torch.cuda.synchronize()

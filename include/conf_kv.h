@@ -56,7 +56,7 @@ typedef enum conf_kv_status {
 typedef struct conf_kv_config {
   int32_t n_layers;          /* L  >= 1                                                        */
   int32_t batch;             /* B  >= 1 sequences, all at the same decode position             */
-  int32_t n_q_heads;         /* Hq, a multiple of n_kv_heads; group G = Hq / Hkv in {1,2,4,5,8} */
+  int32_t n_q_heads;         /* Hq, a multiple of n_kv_heads; group G = Hq / Hkv in 1..8       */
   int32_t n_kv_heads;        /* Hkv                                                            */
   int32_t head_dim;          /* D in {64, 128}                                                 */
   int32_t vocab;             /* V >= 2                                                         */

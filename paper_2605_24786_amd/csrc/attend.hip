@@ -24,7 +24,7 @@
 //   * vector-ALU body (any G, any D): lane c of a group of D/16 lanes owns channels
 //     [16c, 16c+16) of a slot row, so a wavefront load covers whole rows, contiguous in
 //     memory; each lane-group keeps its own running softmax state.
-//   * matrix-core body (G >= 2, D = 128) for the INT8 slots: the G query heads against a
+//   * matrix-core body (2 <= G <= 8, D = 128) for the INT8 slots: the G query heads against a
 //     32-slot tile are two small contractions (scores: [G x 128] x [128 x 32]; output:
 //     [G x 32] x [32 x 128]) issued as v_mfma_f32_16x16x32_f16 with the head dimension
 //     padded to 16.  The vector ALU then only converts int8 -> fp16 and keeps the softmax
@@ -926,8 +926,10 @@ static bool g_use_mfma = true;
 static AttendFn attend_fn_valu(int D, int G) {
 #define CONFKV_CASE(d, g) \
   if (D == d && G == g) return attend_kernel<d, g>;
-  CONFKV_CASE(64, 1) CONFKV_CASE(64, 2) CONFKV_CASE(64, 4) CONFKV_CASE(64, 5) CONFKV_CASE(64, 8)
-  CONFKV_CASE(128, 1) CONFKV_CASE(128, 2) CONFKV_CASE(128, 4) CONFKV_CASE(128, 5) CONFKV_CASE(128, 8)
+  CONFKV_CASE(64, 1) CONFKV_CASE(64, 2) CONFKV_CASE(64, 3) CONFKV_CASE(64, 4) CONFKV_CASE(64, 5)
+  CONFKV_CASE(64, 6) CONFKV_CASE(64, 7) CONFKV_CASE(64, 8)
+  CONFKV_CASE(128, 1) CONFKV_CASE(128, 2) CONFKV_CASE(128, 3) CONFKV_CASE(128, 4) CONFKV_CASE(128, 5)
+  CONFKV_CASE(128, 6) CONFKV_CASE(128, 7) CONFKV_CASE(128, 8)
 #undef CONFKV_CASE
   return nullptr;
 }
@@ -936,8 +938,11 @@ static AttendFn attend_fn_mfma(int D, int G) {
   if (D != 128) return nullptr;
   switch (G) {
     case 2: return attend_mfma_kernel<2>;
+    case 3: return attend_mfma_kernel<3>;
     case 4: return attend_mfma_kernel<4>;
     case 5: return attend_mfma_kernel<5>;
+    case 6: return attend_mfma_kernel<6>;
+    case 7: return attend_mfma_kernel<7>;
     case 8: return attend_mfma_kernel<8>;
     default: return nullptr;
   }

@@ -181,6 +181,11 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0):
     (128, 5, 2, 1, 600, 24, 3),       # Qwen-like group of five
     (128, 2, 1, 1, 300, 0, 2),        # W = 0: only the new token is FP16
     (128, 8, 1, 1, 260, 16, 2),
+    (128, 3, 2, 1, 333, 20, 3),       # odd group sizes
+    (128, 7, 1, 2, 411, 48, 2),
+    (128, 6, 1, 1, 190, 8, 0),
+    (64, 3, 1, 1, 150, 10, 2),
+    (64, 7, 1, 1, 97, -1, 0),
     (64, 4, 2, 1, 130, 100, 4),
     (128, 4, 1, 1, 5, 2, 0),          # a tiny cache
     (128, 1, 1, 1, 0, 4, 0),          # empty cache: the query sees only itself
