@@ -41,7 +41,7 @@ namespace confkv {
 
 constexpr int kAttThreads = 256;
 constexpr int kAttWaves = 4;
-constexpr int kSpinLimit = 4000000;
+constexpr int kSpinLimit = 400000;   // polls (about a microsecond each) before a wait gives up
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));

@@ -16,6 +16,13 @@ constexpr int kConfPerThread = 16;
 constexpr int kConfChunk = kConfThreads * kConfPerThread;   // 4096 logits per workgroup
 constexpr int kPartialStride = 8;                           // floats per chunk partial
 
+__device__ __forceinline__ void st_coherent(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ void top2_merge(float &a1, float &a2, float b1, float b2) {
   // two largest of the multiset {a1, a2, b1, b2} given a1 >= a2 and b1 >= b2
   float lo = fminf(a1, b1);
@@ -77,26 +84,28 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   __syncthreads();
   if (tid == 0) {
     float *p = partial + ((size_t)b * nchunk + c) * kPartialStride;
-    p[0] = mx;
-    p[1] = (s_f[8] + s_f[9]) + (s_f[10] + s_f[11]);
-    p[2] = (s_f[12] + s_f[13]) + (s_f[14] + s_f[15]);
-    p[3] = v1;
-    p[4] = v2;
-    __threadfence();
-    unsigned ticket = atomicAdd(&arrive[b], 1u);
+    // agent-scope relaxed atomics are coherent across the XCDs by themselves; the stores
+    // are complete before the ticket is taken, and the last arrival loads them the same
+    // way, so no cache-wide fence is needed
+    st_coherent(&p[0], mx);
+    st_coherent(&p[1], (s_f[8] + s_f[9]) + (s_f[10] + s_f[11]));
+    st_coherent(&p[2], (s_f[12] + s_f[13]) + (s_f[14] + s_f[15]));
+    st_coherent(&p[3], v1);
+    st_coherent(&p[4], v2);
+    __builtin_amdgcn_s_waitcnt(0);
+    unsigned ticket = __hip_atomic_fetch_add(&arrive[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (ticket == (unsigned)(nchunk - 1));
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
 
   // ---- last workgroup of this sequence: merge the chunk partials in float64 ----
   const float *pb = partial + (size_t)b * nchunk * kPartialStride;
   float M = NEG, t1 = NEG, t2 = NEG;
   for (int k = tid; k < nchunk; k += kConfThreads) {
     const float *p = pb + (size_t)k * kPartialStride;
-    M = fmaxf(M, p[0]);
-    top2_merge(t1, t2, p[3], p[4]);
+    M = fmaxf(M, ld_coherent(&p[0]));
+    top2_merge(t1, t2, ld_coherent(&p[3]), ld_coherent(&p[4]));
   }
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) {
@@ -115,12 +124,12 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   double Sd = 0.0, Td = 0.0;
   for (int k = tid; k < nchunk; k += kConfThreads) {
     const float *p = pb + (size_t)k * kPartialStride;
-    float mk = p[0];
+    const float mk = ld_coherent(&p[0]), sk = ld_coherent(&p[1]), tk = ld_coherent(&p[2]);
     if (mk > NEG) {
       double shift = (double)mk - (double)M;       // <= 0
       double wgt = exp(shift);
-      Sd += wgt * (double)p[1];
-      Td += wgt * ((double)p[2] + shift * (double)p[1]);
+      Sd += wgt * (double)sk;
+      Td += wgt * ((double)tk + shift * (double)sk);
     }
   }
   Sd = wave_sum(Sd);
@@ -143,7 +152,7 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     if (sel) sel[b] = (uint8_t)tight;
     s_tight = tight;
     atomicAdd(&cv.stats[tight ? kStatTight : kStatLoose], 1ull);
-    arrive[b] = 0u;                                  // ready for the next launch
+    __hip_atomic_store(&arrive[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
   const int tight = s_tight;
