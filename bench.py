@@ -49,16 +49,17 @@ def attend_bytes_per_launch(wl, n8, n16):
     return per_unit * wl.batch * wl.n_kv_heads
 
 
-def step_bytes(wl, n8, n16, n_after, n_moved):
-    """Algorithmic bytes of the whole step: attention, logits, ranking and compaction moves."""
+def step_bytes(wl, n8, n16, moved_bytes):
+    """Algorithmic bytes of the whole step: attention, logits, ranking, compaction moves (the
+    rows the order-preserving compaction has to move on its cheaper side, read + written, as
+    counted by the library), demotion."""
     D = wl.head_dim
     att = attend_bytes_per_launch(wl, n8, n16) * wl.n_layers
     logits = 4 * wl.vocab * wl.batch
     n = n8 + n16
     rank = 8 * max(0, n - wl.protected) * wl.units
-    moved = 2 * n_moved * (2 * D + 4 + 8)          # INT8 survivors behind the first hole, read + write
     demote = wl.units * (4 * D + 2 * D + 4)
-    return att + logits + rank + moved + demote, att
+    return att + logits + rank + int(moved_bytes) + demote, att
 
 
 def cpu_baseline(wl, seed, budget_s=15.0):
@@ -109,7 +110,10 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
         return logits_by_std[std]
     reload(); torch.cuda.synchronize()
     rows = []
+    moved0 = 0
     for t in range(args.warmup + args.steps):
+        if t == args.warmup:
+            moved0 = kv.counters().compact_bytes
         lg = logits_for(t)
         ln, n16 = kv.lengths()
         n = ln.astype(np.int64) + 1
@@ -117,6 +121,8 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
         D, G = wl.head_dim, wl.group
         att_bytes = int(((n[:, :, None] - n16u) * (2 * D + 4) + n16u * 4 * D + 8 * n[:, :, None]).sum()
                         + wl.units * (4 * G * D + 8 * D + 4))
+        other_bytes = int(4 * wl.vocab * wl.batch + 8 * np.maximum(0, n - wl.protected).sum() * wl.n_kv_heads
+                          + wl.units * (6 * D + 4))                      # logits, ranking inputs, demotion
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         ev[0].record()
         for l in range(L):
@@ -129,10 +135,12 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
         torch.cuda.synchronize()
         if t >= args.warmup:
             rows.append((ev[0].elapsed_time(ev[3]), ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]),
-                         ev[2].elapsed_time(ev[3]), att_bytes, float(n.mean())))
+                         ev[2].elapsed_time(ev[3]), att_bytes, float(n.mean()), other_bytes))
     r = np.array(rows)
     st = kv.counters()
     ms_step = float(r[:, 0].mean())
+    moved = (st.compact_bytes - moved0) / args.steps
+    total_bytes = float(r[:, 4].mean() + r[:, 6].mean() + moved)
     att_gbps = float((r[:, 4] / (r[:, 1] * 1e-3)).mean() / 1e9)
     print(json.dumps({
         "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s", "n_gpus": 1,
@@ -145,6 +153,9 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
                      "bytes_per_launch": float(r[:, 4].mean()) / L, "launch_ms": float(r[:, 1].mean()) / L},
         "step_breakdown_ms": {"attend_x_layers": float(r[:, 1].mean()), "confidence": float(r[:, 2].mean()),
                               "evict_compact": float(r[:, 3].mean())},
+        "step_hbm": {"algorithmic_bytes": total_bytes, "compaction_bytes": moved,
+                     "achieved_GBps": total_bytes / (ms_step * 1e-3) / 1e9,
+                     "frac_of_peak": total_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "counters": {"evicted": int(st.evicted), "demoted": int(st.demoted), "tight": int(st.tight_steps),
                      "loose": int(st.loose_steps)},
     }))
@@ -232,6 +243,7 @@ def main():
     n8_b = max(0, wl.prefill - wl.fp16_window) if wl.fp16_window >= 0 else 0
     n16_b = len_before - n8_b
     t_step, t_att, t_conf, t_evict = [], [], [], []
+    moved0 = kv.counters().compact_bytes
     for _ in range(args.steps):
         reload(); torch.cuda.synchronize()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -250,8 +262,8 @@ def main():
     att_launch_ms = float(np.mean(t_att)) / L
     att_bytes = attend_bytes_per_launch(wl, n8_b, n16_b)
     n_after = int(ln.mean())
-    n_moved = int(ln.sum()) * wl.n_kv_heads          # survivors (all sit behind the first hole, to first order)
-    total_bytes, att_total = step_bytes(wl, n8_b, n16_b, n_after, n_moved)
+    moved = (st.compact_bytes - moved0) / args.steps
+    total_bytes, att_total = step_bytes(wl, n8_b, n16_b, moved)
     achieved = att_bytes / (att_launch_ms * 1e-3) / 1e9
     result = {
         "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s",
@@ -269,7 +281,7 @@ def main():
                      "launch_ms": att_launch_ms},
         "step_breakdown_ms": {"attend_x_layers": float(np.mean(t_att)), "confidence": float(np.mean(t_conf)),
                               "evict_compact": float(np.mean(t_evict))},
-        "step_hbm": {"algorithmic_bytes": total_bytes, "achieved_GBps": total_bytes / (ms_step * 1e-3) / 1e9,
+        "step_hbm": {"algorithmic_bytes": total_bytes, "compaction_bytes": moved, "achieved_GBps": total_bytes / (ms_step * 1e-3) / 1e9,
                      "frac_of_peak": total_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "attend_GBps": att_total / (float(np.mean(t_att)) * 1e-3) / 1e9},
     }

@@ -78,6 +78,7 @@ typedef struct conf_kv_stats {
   uint64_t tight_steps;      /* sequence-steps that selected the tight budget                  */
   uint64_t loose_steps;      /* sequence-steps that selected the loose budget                  */
   uint64_t device_errors;    /* bounded waits that expired inside kernels (0 in a healthy run) */
+  uint64_t compact_bytes;    /* bytes read + written by the compaction's in-place row moves    */
 } conf_kv_stats;
 
 /* Bytes of device memory the caller must provide for the cache state and for scratch

@@ -35,7 +35,7 @@ class ConfKVConfig(C.Structure):
 
 class ConfKVStats(C.Structure):
     _fields_ = [("evicted", C.c_uint64), ("demoted", C.c_uint64), ("tight_steps", C.c_uint64),
-                ("loose_steps", C.c_uint64), ("device_errors", C.c_uint64)]
+                ("loose_steps", C.c_uint64), ("device_errors", C.c_uint64), ("compact_bytes", C.c_uint64)]
 
 
 class ConfKVError(RuntimeError):

@@ -20,7 +20,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct StateLayout {
-  size_t len, n8, head16, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, ema, pos, ks, vs, k8, v8, k16, v16, total;
+  size_t len, n8, head16, head8, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, unit_moved, ema, pos, ks, vs, k8, v8, k16, v16, total;
   size_t header_bytes;   // [0, header_bytes) is zeroed at create
   int cap8, cap16;
 };
@@ -64,9 +64,11 @@ StateLayout state_layout(const conf_kv_config *c) {
   s.len = take(U * 4);
   s.n8 = take(U * 4);
   s.head16 = take(U * 4);
+  s.head8 = take(U * 4);
   s.stats = take(kStatSlots * 8);
   s.unit_evicted = take(U * 4);
   s.unit_demoted = take(U * 4);
+  s.unit_moved = take(U * 8);
   s.header_bytes = off;
   s.budget = take((size_t)c->n_layers * c->batch * 4);
   s.n_tight = take((size_t)c->n_layers * 4);
@@ -180,12 +182,14 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   cv.len = (int32_t *)(s + h->sl.len);
   cv.n8 = (int32_t *)(s + h->sl.n8);
   cv.head16 = (int32_t *)(s + h->sl.head16);
+  cv.head8 = (int32_t *)(s + h->sl.head8);
   cv.budget = (int32_t *)(s + h->sl.budget);
   cv.n_tight = (const int32_t *)(s + h->sl.n_tight);
   cv.n_loose = (const int32_t *)(s + h->sl.n_loose);
   cv.stats = (unsigned long long *)(s + h->sl.stats);
   cv.unit_evicted = (unsigned *)(s + h->sl.unit_evicted);
   cv.unit_demoted = (unsigned *)(s + h->sl.unit_demoted);
+  cv.unit_moved = (unsigned long long *)(s + h->sl.unit_moved);
   cv.L = L;
   cv.B = cfg->batch;
   cv.Hkv = cfg->n_kv_heads;
@@ -356,10 +360,12 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   const size_t u = ((size_t)layer * cv.B + b) * cv.Hkv + kv_head;
   const size_t D = cv.D;
   CK_HIP(h, hipDeviceSynchronize());
-  int32_t len = 0, n8 = 0, head = 0;
+  int32_t len = 0, n8 = 0, head = 0, head8 = 0;
   CK_HIP(h, hipMemcpy(&len, cv.len + u, 4, hipMemcpyDeviceToHost));
   CK_HIP(h, hipMemcpy(&n8, cv.n8 + u, 4, hipMemcpyDeviceToHost));
   CK_HIP(h, hipMemcpy(&head, cv.head16 + u, 4, hipMemcpyDeviceToHost));
+  CK_HIP(h, hipMemcpy(&head8, cv.head8 + u, 4, hipMemcpyDeviceToHost));
+  const int first8 = std::min(n8, cv.cap8 - head8);   // INT8 ring rows before the wrap
   const int n = len + h->appended[layer];
   const int n16 = n - n8;
   if (n_out) *n_out = n;
@@ -387,11 +393,17 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
       }
     }
     if (d8) {
-      if (n8 > 0) CK_HIP(h, hipMemcpy(d8, p8, (size_t)n8 * D, hipMemcpyDeviceToHost));
+      if (first8 > 0)
+        CK_HIP(h, hipMemcpy(d8, p8 + (size_t)head8 * D, (size_t)first8 * D, hipMemcpyDeviceToHost));
+      if (n8 > first8)
+        CK_HIP(h, hipMemcpy(d8 + (size_t)first8 * D, p8, (size_t)(n8 - first8) * D, hipMemcpyDeviceToHost));
       memset(d8 + (size_t)n8 * D, 0, (size_t)n16 * D);
     }
     if (dsc) {
-      if (n8 > 0) CK_HIP(h, hipMemcpy(dsc, psc, (size_t)n8 * 2, hipMemcpyDeviceToHost));
+      if (first8 > 0)
+        CK_HIP(h, hipMemcpy(dsc, psc + head8, (size_t)first8 * 2, hipMemcpyDeviceToHost));
+      if (n8 > first8)
+        CK_HIP(h, hipMemcpy(dsc + first8, psc, (size_t)(n8 - first8) * 2, hipMemcpyDeviceToHost));
       memset(dsc + n8, 0, (size_t)n16 * 2);
     }
   }
@@ -407,8 +419,10 @@ int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *st) {
   std::vector<unsigned> ev(U), dm(U);
   CK_HIP(h, hipMemcpy(ev.data(), h->cv.unit_evicted, U * 4, hipMemcpyDeviceToHost));
   CK_HIP(h, hipMemcpy(dm.data(), h->cv.unit_demoted, U * 4, hipMemcpyDeviceToHost));
-  st->evicted = st->demoted = 0;
-  for (size_t u = 0; u < U; ++u) { st->evicted += ev[u]; st->demoted += dm[u]; }
+  std::vector<unsigned long long> mv(U);
+  CK_HIP(h, hipMemcpy(mv.data(), h->cv.unit_moved, U * 8, hipMemcpyDeviceToHost));
+  st->evicted = st->demoted = st->compact_bytes = 0;
+  for (size_t u = 0; u < U; ++u) { st->evicted += ev[u]; st->demoted += dm[u]; st->compact_bytes += mv[u]; }
   st->tight_steps = raw[kStatTight];
   st->loose_steps = raw[kStatLoose];
   st->device_errors = raw[kStatDeviceErr];

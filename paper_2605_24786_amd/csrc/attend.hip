@@ -115,7 +115,8 @@ __device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, fl
 // ---------------------------------------------------------------------------------------
 struct Slice {
   int u, ul, b, g, j;          // unit, unit within the layer, batch, kv-head, split
-  int n, n8, h16, n16;         // length with the append, INT8 slots, ring head, FP16 slots
+  int n, n8, h16, n16;         // length with the append, INT8 slots, FP16 ring head, FP16 slots
+  int h8;                      // INT8 ring head
   int lo8, hi8;                // INT8 slots of this split
   int lo16, hi16;              // FP16 slots of this split (slot numbers, >= n8)
   int cnt8, ntok;              // hi8 - lo8, and cnt8 + (hi16 - lo16)
@@ -136,6 +137,7 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
   s.n8 = cv.n8[s.u];
   s.n = cv.len[s.u] + 1;                  // the appended token included
   s.h16 = cv.head16[s.u];
+  s.h8 = cv.head8[s.u];
   s.n16 = s.n - s.n8;
   s.lo8 = (int)((long long)s.n8 * s.j / ns) & ~31;
   s.hi8 = s.j == ns - 1 ? s.n8 : (int)((long long)s.n8 * (s.j + 1) / ns) & ~31;
@@ -260,7 +262,7 @@ __device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slic
     for (int r = 0; r < R8; ++r) {
       const int i = base + r * TB + w * TW + ts;
       ok[r] = i < sl.hi8;
-      const int ic = ok[r] ? i : sl.hi8 - 1;
+      const int ic = ring_row_u(sl.h8, ok[r] ? i : sl.hi8 - 1, cv.cap8);
       kr[r] = *(const int4 *)(K8 + (size_t)ic * D + c * 16);
       vr[r] = *(const int4 *)(V8 + (size_t)ic * D + c * 16);
       ksh[r] = ((const unsigned short *)KS)[ic];
@@ -695,8 +697,9 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     const int base = sl.lo8 + tile * kTile;
     const int last = sl.hi8 - 1;
     const size_t col = (size_t)c8 * 16;
-    const int i0 = min(base + r8, last), i1 = min(base + 8 + r8, last);
-    const int i2 = min(base + 16 + r8, last), i3 = min(base + 24 + r8, last);
+    const int h8 = sl.h8, cap8 = cv.cap8;
+    const int i0 = ring_row_u(h8, min(base + r8, last), cap8), i1 = ring_row_u(h8, min(base + 8 + r8, last), cap8);
+    const int i2 = ring_row_u(h8, min(base + 16 + r8, last), cap8), i3 = ring_row_u(h8, min(base + 24 + r8, last), cap8);
     t.k0 = *(const int4 *)(K8 + (size_t)i0 * D + col);
     t.v0 = *(const int4 *)(V8 + (size_t)i0 * D + col);
     t.k1 = *(const int4 *)(K8 + (size_t)i1 * D + col);
@@ -705,7 +708,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     t.v2 = *(const int4 *)(V8 + (size_t)i2 * D + col);
     t.k3 = *(const int4 *)(K8 + (size_t)i3 * D + col);
     t.v3 = *(const int4 *)(V8 + (size_t)i3 * D + col);
-    const int j0 = min(base + t16, last), j1 = min(base + 16 + t16, last);
+    const int j0 = ring_row_u(h8, min(base + t16, last), cap8), j1 = ring_row_u(h8, min(base + 16 + t16, last), cap8);
     t.ks0 = ((const unsigned short *)KS)[j0];
     t.vs0 = ((const unsigned short *)VS)[j0];
     t.ks1 = ((const unsigned short *)KS)[j1];

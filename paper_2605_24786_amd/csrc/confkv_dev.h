@@ -16,25 +16,28 @@ enum StatSlot { kStatEvicted = 0, kStatDemoted = 1, kStatTight = 2, kStatLoose =
                 kStatDeviceErr = 4, kStatSlots = 8 };
 
 // All planes of the cache, for every unit u = (layer * B + b) * Hkv + kv_head.
-//   k8, v8   int8  [U][cap8][D]   INT8 rows; slot i < n8[u] lives in row i
-//   ks, vs   fp16  [U][cap8]      per-token scales of those rows
+//   k8, v8   int8  [U][cap8][D]   INT8 ring; slot i < n8[u] lives in ring row
+//                                 (head8[u] + i) mod cap8
+//   ks, vs   fp16  [U][cap8]      per-token scales of those rows (same ring index)
 //   k16, v16 fp16  [U][cap16][D]  FP16 ring; slot i >= n8[u] lives in ring row
 //                                 (head16[u] + i - n8[u]) mod cap16
 //   ema      fp32  [U][cap]       EMA of attention mass, by slot
 //   pos      int32 [U][cap]       original position, by slot (strictly increasing)
-//   len, n8, head16  int32 [U]    committed length, INT8 count, ring head
+//   len, n8, head16, head8  int32 [U]  committed length, INT8 count, ring heads
 //   budget   int32 [L][B]         N selected by the last confidence step
 //   unit_evicted, unit_demoted  uint32 [U]  tokens evicted / demoted so far, per unit
+//   unit_moved  uint64 [U]        bytes read + written by compaction moves so far, per unit
 struct CacheView {
   int8_t *k8, *v8;
   __half *ks, *vs;
   __half *k16, *v16;
   float *ema;
   int32_t *pos;
-  int32_t *len, *n8, *head16, *budget;
+  int32_t *len, *n8, *head16, *head8, *budget;
   const int32_t *n_tight, *n_loose;
   unsigned long long *stats;
   unsigned *unit_evicted, *unit_demoted;   // [U] per-unit event counts
+  unsigned long long *unit_moved;          // [U] per-unit compaction traffic
   int32_t L, B, Hkv, G, D, cap, cap8, cap16, W, P;
 };
 
@@ -48,6 +51,12 @@ struct LayerMask {
 __device__ __forceinline__ int ring_row(int head, int idx, int cap16) {
   int r = head + idx;
   return r >= cap16 ? r - cap16 : r;
+}
+// Same for 0 <= head + idx < 2 * cap in two instructions: the subtraction wraps to a huge
+// unsigned value exactly when no wrap of the ring is due.
+__device__ __forceinline__ int ring_row_u(int head, int idx, int cap) {
+  const unsigned r = (unsigned)(head + idx);
+  return (int)min(r, r - (unsigned)cap);
 }
 
 // ---- wavefront reductions (all 64 lanes end with the result) ----
@@ -79,6 +88,11 @@ __device__ __forceinline__ int wave_sum(int v) {
 __device__ __forceinline__ int wave_min(int v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) v = min(v, __shfl_xor(v, m, kWave));
+  return v;
+}
+__device__ __forceinline__ int wave_max(int v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = max(v, __shfl_xor(v, m, kWave));
   return v;
 }
 

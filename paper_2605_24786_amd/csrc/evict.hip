@@ -74,6 +74,7 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
     cv.len[u] = T0;
     cv.n8[u] = n8;
     cv.head16[u] = 0;
+    cv.head8[u] = 0;
   }
   if (t >= T0) return;
   const __half *ksrc = k16 + ((size_t)ul * T0 + t) * D;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
     quantize_row_wave<D>(vsrc, cv.v8 + ((size_t)u * cv.cap8 + t) * D, cv.vs + (size_t)u * cv.cap8 + t, lane);
   } else {
     constexpr int EPL = D / kWave;
-    const int row = t - n8;                       // head16 = 0 after a load
+    const int row = t - n8;                       // both ring heads are 0 after a load
     __half *kd = cv.k16 + ((size_t)u * cv.cap16 + row) * D;
     __half *vd = cv.v16 + ((size_t)u * cv.cap16 + row) * D;
 #pragma unroll
@@ -95,6 +96,38 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
       kd[lane * EPL + e] = ksrc[lane * EPL + e];
       vd[lane * EPL + e] = vsrc[lane * EPL + e];
     }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Outcome of one unit's selection.  The INT8 rows are a ring, so the survivors can close the
+// holes from either side: rows behind the first hole shift left (head stays), or rows in
+// front of the last INT8 hole shift right (head advances by the INT8 evictions).  The side
+// with fewer rows to move is taken; in steady state the evicted slot is old, so the right
+// shift moves next to nothing.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void write_selection(const CacheView &cv, int u, int32_t *sel, int n_new,
+                                                int n8_old, int n8_new, int first_hole, int evicted,
+                                                int last_hole8) {
+  const int h8 = cv.head8[u];
+  const int e8 = n8_old - n8_new;
+  const int left_rows = n8_new - min(first_hole, n8_new);
+  const int right_rows = last_hole8 + 1 - e8;        // INT8 survivors in front of the last INT8 hole
+  const int right = e8 > 0 && right_rows < left_rows;
+  sel[0] = n_new;
+  sel[1] = n8_new;
+  sel[2] = first_hole;
+  sel[3] = evicted;
+  sel[4] = last_hole8;
+  sel[5] = right;
+  sel[6] = right ? ring_row(h8, e8, cv.cap8) : h8;
+  sel[7] = 0;
+  if (evicted > 0) {
+    // traffic of the moves the compaction kernel will make (each row is read and written once)
+    const long long rows8 = right ? right_rows : left_rows;
+    const long long rows16 = (evicted > e8) ? n_new - max(first_hole, n8_new) : 0;
+    const long long meta = n_new - min(first_hole, n_new);
+    cv.unit_moved[u] += 2ull * (unsigned long long)(rows8 * (2 * cv.D + 4) + rows16 * 4 * cv.D + meta * 8);
   }
 }
 
@@ -138,7 +171,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   __shared__ int s_tmp[kRsWaves];
   __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
   __shared__ unsigned long long s_prefix;
-  __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves];
+  __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves], s_last8[kRsWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x;
   const int UPL = cv.B * cv.Hkv;
@@ -151,7 +184,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
   if (n <= N || e <= 0) {
-    if (tid == 0) { sel[0] = n; sel[1] = n8; sel[2] = n; sel[3] = 0; }
+    if (tid == 0) write_selection(cv, u, sel, n, n8, n8, n, 0, -1);
     return;
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
@@ -215,7 +248,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const bool whole_bucket = s_done != 0;            // no tie ranking needed
 
   // survivor list in slot order; ties with the cut-off are evicted oldest first
-  int carry_keep = 0, carry_tie = 0, kept8 = 0, hole = n;
+  int carry_keep = 0, carry_tie = 0, kept8 = 0, hole = n, last8 = -1;
   for (int base = 0; base < n; base += kRsThreads) {
     const int i = base + tid;
     int tie = 0, below = 0;
@@ -241,20 +274,21 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
       src[j] = i;
       kept8 += (i < n8);
     }
-    if (evict) hole = min(hole, i);
+    if (evict) {
+      hole = min(hole, i);
+      if (i < n8) last8 = max(last8, i);
+    }
   }
   kept8 = wave_sum(kept8);
   hole = wave_min(hole);
-  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; }
+  last8 = wave_max(last8);
+  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; s_last8[w] = last8; }
   __syncthreads();
   if (tid == 0) {
-    int k8 = 0, hl = n;
+    int k8 = 0, hl = n, l8 = -1;
 #pragma unroll
-    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); }
-    sel[0] = carry_keep;                              // = n - e
-    sel[1] = k8;
-    sel[2] = hl;
-    sel[3] = e;
+    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); l8 = max(l8, s_last8[k]); }
+    write_selection(cv, u, sel, carry_keep /* = n - e */, n8, k8, hl, e, l8);
     cv.unit_evicted[u] += (unsigned)e;              // per-unit counter: no contended atomic
   }
 }
@@ -283,7 +317,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   __shared__ int s_cnt[E * kRsWaves];               // kept (or tied) lanes per (round, wavefront)
   __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
   __shared__ unsigned long long s_prefix, s_kmin[kRsWaves], s_kmax[kRsWaves];
-  __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves];
+  __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves], s_last8[kRsWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x;
   const int UPL = cv.B * cv.Hkv;
@@ -296,7 +330,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
   if (n <= N || e <= 0) {
-    if (tid == 0) { sel[0] = n; sel[1] = n8; sel[2] = n; sel[3] = 0; }
+    if (tid == 0) write_selection(cv, u, sel, n, n8, n8, n, 0, -1);
     return;
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
@@ -442,7 +476,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
     }
   }
   __syncthreads();                                  // s_cnt is reused for the keep counts
-  int kept8 = 0, hole = n;
+  int kept8 = 0, hole = n, last8 = -1;
 #pragma unroll
   for (int k = 0; k < E; ++k) {
     if (k < Ed) {
@@ -452,7 +486,10 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
       const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
       if (lane == 0) s_cnt[k * kRsWaves + w] = __builtin_popcountll(bm);
       kept8 += keep && i < n8;
-      if (ev) hole = min(hole, i);
+      if (ev) {
+        hole = min(hole, i);
+        if (i < n8) last8 = max(last8, i);
+      }
     }
   }
   __syncthreads();
@@ -476,27 +513,27 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   }
   kept8 = wave_sum(kept8);
   hole = wave_min(hole);
-  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; }
+  last8 = wave_max(last8);
+  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; s_last8[w] = last8; }
   __syncthreads();
   if (tid == 0) {
-    int k8 = 0, hl = n;
+    int k8 = 0, hl = n, l8 = -1;
 #pragma unroll
-    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); }
-    sel[0] = tot_keep;                                // = n - e
-    sel[1] = k8;
-    sel[2] = hl;
-    sel[3] = e;
+    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); l8 = max(l8, s_last8[k]); }
+    write_selection(cv, u, sel, tot_keep /* = n - e */, n8, k8, hl, e, l8);
     cv.unit_evicted[u] += (unsigned)e;
   }
 }
 
 // ---------------------------------------------------------------------------------------
 // compact: grid (U, 5 planes), 256 threads.  Destination slot j takes source slot src[j]
-// >= j.  A workgroup walks its plane front to back in chunks: load a chunk into registers,
-// barrier, store.  Earlier chunks only wrote below the chunk start, later sources all lie
-// at or above it, so nothing is overwritten before it is read.
+// >= j.  Left shift: a workgroup walks its plane front to back in chunks (load a chunk into
+// registers, barrier, store); earlier chunks only wrote below the chunk start and later
+// sources all lie at or above it, so nothing is overwritten before it is read.  Right shift
+// of the INT8 ring (new head = old head + INT8 evictions): survivor j moves from ring offset
+// src[j] to offset e8 + j >= src[j]; the walk goes back to front, the mirror argument holds.
 // planes: 0 = K INT8 rows, 1 = V INT8 rows, 2 = scales + EMA + position, 3 = K FP16 rows,
-// 4 = V FP16 rows.
+// 4 = V FP16 rows.  EMA and position are plain per-slot arrays and always shift left.
 // ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
@@ -506,39 +543,59 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
   const int n_new = sel[0], n8_new = sel[1], hole = sel[2];
   if (hole >= n_new) return;                          // nothing moves
-  const int n8_old = cv.n8[u], h16 = cv.head16[u];
+  const int n8_old = cv.n8[u], h16 = cv.head16[u], h8 = cv.head8[u];
   const int32_t *src = src_all + (size_t)u * cv.cap;
   const int cap8 = cv.cap8, cap16 = cv.cap16;
+  const bool right = sel[5] != 0;
+  const int e8 = n8_old - n8_new;
+  const int jr = sel[4] + 1 - e8;                     // right shift: survivors [0, jr) move
+  const int h8_new = sel[6];
 
   if (plane <= 1) {
-    // INT8 rows: destination slots [hole, n8_new)
     constexpr int LPR = D / 16, RPP = kEvThreads / LPR, PASSES = 4;
     int8_t *base_ptr = (plane == 0 ? cv.k8 : cv.v8) + (size_t)u * cap8 * D;
     const int c = tid % LPR, r0 = tid / LPR;
-    for (int base = hole; base < n8_new; base += RPP * PASSES) {
-      int4 buf[PASSES];
+    if (!right) {
+      // destination slots [hole, n8_new), front to back
+      for (int base = hole; base < n8_new; base += RPP * PASSES) {
+        int4 buf[PASSES];
 #pragma unroll
-      for (int p = 0; p < PASSES; ++p) {
-        const int j = base + p * RPP + r0;
-        if (j < n8_new) buf[p] = *(const int4 *)(base_ptr + (size_t)src[j] * D + c * 16);
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = base + p * RPP + r0;
+          if (j < n8_new) buf[p] = *(const int4 *)(base_ptr + (size_t)ring_row(h8, src[j], cap8) * D + c * 16);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = base + p * RPP + r0;
+          if (j < n8_new) *(int4 *)(base_ptr + (size_t)ring_row(h8, j, cap8) * D + c * 16) = buf[p];
+        }
       }
-      __syncthreads();
+    } else {
+      // destination slots [0, jr), back to front
+      for (int top = jr; top > 0; top -= RPP * PASSES) {
+        int4 buf[PASSES];
 #pragma unroll
-      for (int p = 0; p < PASSES; ++p) {
-        const int j = base + p * RPP + r0;
-        if (j < n8_new) *(int4 *)(base_ptr + (size_t)j * D + c * 16) = buf[p];
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = top - 1 - (p * RPP + r0);
+          if (j >= 0) buf[p] = *(const int4 *)(base_ptr + (size_t)ring_row(h8, src[j], cap8) * D + c * 16);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = top - 1 - (p * RPP + r0);
+          if (j >= 0) *(int4 *)(base_ptr + (size_t)ring_row(h8_new, j, cap8) * D + c * 16) = buf[p];
+        }
       }
     }
   } else if (plane == 2) {
-    // per-slot metadata: EMA and position for [hole, n_new), scales for [hole, n8_new)
+    // per-slot metadata: EMA and position for [hole, n_new)
     float *ema = cv.ema + (size_t)u * cv.cap;
     int32_t *pos = cv.pos + (size_t)u * cv.cap;
-    __half *ks = cv.ks + (size_t)u * cap8, *vs = cv.vs + (size_t)u * cap8;
     constexpr int PASSES = 4;
     for (int base = hole; base < n_new; base += kEvThreads * PASSES) {
       float fa[PASSES];
       int32_t fp[PASSES];
-      __half fk[PASSES], fv[PASSES];
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
         const int j = base + p * kEvThreads + tid;
@@ -546,7 +603,6 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
           const int s = src[j];
           fa[p] = ema[s];
           fp[p] = pos[s];
-          if (j < n8_new) { fk[p] = ks[s]; fv[p] = vs[s]; }
         }
       }
       __syncthreads();
@@ -556,7 +612,55 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
         if (j < n_new) {
           ema[j] = fa[p];
           pos[j] = fp[p];
-          if (j < n8_new) { ks[j] = fk[p]; vs[j] = fv[p]; }
+        }
+      }
+    }
+    // scales follow their INT8 rows
+    __half *ks = cv.ks + (size_t)u * cap8, *vs = cv.vs + (size_t)u * cap8;
+    if (!right) {
+      for (int base = hole; base < n8_new; base += kEvThreads * PASSES) {
+        __half fk[PASSES], fv[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = base + p * kEvThreads + tid;
+          if (j < n8_new) {
+            const int s = ring_row(h8, src[j], cap8);
+            fk[p] = ks[s];
+            fv[p] = vs[s];
+          }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = base + p * kEvThreads + tid;
+          if (j < n8_new) {
+            const int d = ring_row(h8, j, cap8);
+            ks[d] = fk[p];
+            vs[d] = fv[p];
+          }
+        }
+      }
+    } else {
+      for (int top = jr; top > 0; top -= kEvThreads * PASSES) {
+        __half fk[PASSES], fv[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = top - 1 - (p * kEvThreads + tid);
+          if (j >= 0) {
+            const int s = ring_row(h8, src[j], cap8);
+            fk[p] = ks[s];
+            fv[p] = vs[s];
+          }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int j = top - 1 - (p * kEvThreads + tid);
+          if (j >= 0) {
+            const int d = ring_row(h8_new, j, cap8);
+            ks[d] = fk[p];
+            vs[d] = fv[p];
+          }
         }
       }
     }
@@ -593,7 +697,7 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
 
 // ---------------------------------------------------------------------------------------
 // demote: grid (U / 4), one wavefront per unit.  Quantises the oldest FP16 slots until at most W stay
-// FP16, appends them to the INT8 rows, and commits (len, n8, head16).
+// FP16, appends them at the INT8 ring tail, and commits (len, n8, head16, head8).
 // ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
@@ -601,13 +705,13 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
   const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (u >= U) return;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
-  const int n_new = sel[0], n8_new = sel[1];
+  const int n_new = sel[0], n8_new = sel[1], h8 = sel[6];   // INT8 ring head after the compaction
   const int h16 = cv.head16[u];
   const int n16 = n_new - n8_new;
   const int cnt = (cv.W < 0) ? 0 : max(0, n16 - cv.W);
   for (int t = 0; t < cnt; ++t) {
     const int row = ring_row(h16, t, cv.cap16);
-    const size_t dst = (size_t)u * cv.cap8 + n8_new + t;
+    const size_t dst = (size_t)u * cv.cap8 + ring_row(h8, n8_new + t, cv.cap8);
     quantize_row_wave<D>(cv.k16 + ((size_t)u * cv.cap16 + row) * D, cv.k8 + dst * D, cv.ks + dst, lane);
     quantize_row_wave<D>(cv.v16 + ((size_t)u * cv.cap16 + row) * D, cv.v8 + dst * D, cv.vs + dst, lane);
   }
@@ -615,6 +719,7 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
     cv.len[u] = n_new;
     cv.n8[u] = n8_new + cnt;
     cv.head16[u] = ring_row(h16, cnt % cv.cap16, cv.cap16);
+    cv.head8[u] = h8;
     if (cnt) cv.unit_demoted[u] += (unsigned)cnt;
   }
 }

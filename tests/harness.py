@@ -160,6 +160,7 @@ class Lockstep:
         before = {key: u.copy() for key, u in self.run.units.items()}
         kv.evict_compact()
         gone = self.run.evict_compact(sel_gpu)      # the oracle follows the GPU's budget choice
+        self.last_before, self.last_gone = before, gone
         for key, u in self.run.units.items():
             ex_pos = self.kv.export(*key)["pos"].astype(np.int64)
             rep.evictions += int(gone[key].size)

@@ -297,6 +297,60 @@ def test_lockstep_small_workloads(lib, torch_cuda, idx):
     ls.close()
 
 
+@pytest.mark.parametrize("G,D,alpha", [(4, 128, 0.1), (1, 64, 0.65), (5, 128, 0.9), (1, 128, 0.9)])
+def test_lockstep_long_run_wraps_the_int8_ring(lib, torch_cuda, G, D, alpha):
+    """Many more steady-state steps than the unit has slots: the compaction closes holes from
+    whichever side moves fewer rows, so the INT8 ring head travels round the allocation
+    several times (a recency-heavy ranker evicts old slots, which makes the head-side shift
+    the cheap one), and budget switches (several holes at once) are mixed in."""
+    wl = small(1).scaled(n_layers=1, batch=1, n_q_heads=2 * G, n_kv_heads=2, head_dim=D, vocab=3001,
+                         prefill=100, steps=700, n_tight=(97,), n_loose=(104,), protected=8,
+                         fp16_window=8, logit_std=(0.5, 6.0), logit_run=7, alpha=alpha)
+    assert wl.capacity == 128
+    say(f"ring wrap: G={G} D={D} alpha={alpha} capacity={wl.capacity} steps={wl.steps}")
+    ls = Lockstep(lib, wl, seed=11)
+    travel = {key: 0 for key in ls.run.units}       # rows the INT8 ring head should have advanced
+    shifts = {"left": 0, "right": 0}
+    moved_bytes = 0                                 # traffic of the moves the compaction has to make
+    for t in range(wl.steps):
+        ls.step(check_state=(t % 3 == 0 or t > wl.steps - 10))
+        for key, gone_pos in ls.last_gone.items():
+            if gone_pos.size == 0:
+                continue
+            pre = ls.last_before[key]
+            idx = np.searchsorted(pre.pos, gone_pos)                    # evicted slot numbers
+            n8_old = int((~pre.is16).sum())
+            idx8 = idx[idx < n8_old]
+            n_new, n8_new, first = pre.n - idx.size, n8_old - idx8.size, int(idx.min())
+            rows8 = 0
+            if idx8.size:
+                left_rows = n8_new - min(first, n8_new)
+                right_rows = int(idx8.max()) + 1 - idx8.size
+                if right_rows < left_rows:
+                    travel[key] += idx8.size
+                    shifts["right"] += 1
+                else:
+                    shifts["left"] += 1
+                rows8 = min(left_rows, right_rows)
+            rows16 = n_new - max(first, n8_new) if idx.size > idx8.size else 0
+            moved_bytes += 2 * (rows8 * (2 * D + 4) + rows16 * 4 * D + (n_new - first) * 8)
+    say(f"  ring head travel per unit: {travel}, shifts {shifts}")
+    if alpha < 0.8:
+        assert min(travel.values()) > 2 * wl.capacity   # every unit's ring wrapped at least twice
+    else:
+        assert min(shifts.values()) > 50                # both directions, on a ring that has wrapped
+        assert min(travel.values()) > wl.capacity
+    rep = ls.report
+    st = ls.kv.counters()
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"tight={rep.tight_steps} flips={rep.evict_flips}/{rep.budget_flips} demoted={st.demoted}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.tight_steps > 0 and rep.tight_steps < wl.steps
+    assert st.demoted > 2 * wl.capacity and st.device_errors == 0
+    assert st.compact_bytes == moved_bytes, (st.compact_bytes, moved_bytes)
+    ls.close()
+
+
 def test_call_order_and_capacity_errors(lib, torch_cuda):
     torch = torch_cuda
     kv = _mk(lib, capacity=64, n_tight=[32], n_loose=[60], protected_window=4)
