@@ -39,8 +39,8 @@
 
 namespace confkv {
 
-constexpr int kAttThreads = 256;
-constexpr int kAttWaves = 4;
+constexpr int kAttThreads = 512;
+constexpr int kAttWaves = 8;
 constexpr int kSpinLimit = 400000;   // polls (about a microsecond each) before a wait gives up
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
@@ -60,7 +60,7 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 #define TS(k)                                                                                   \
   do {                                                                                          \
     if (a.dbg && (threadIdx.x & 63) == 0)                                                       \
-      a.dbg[((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 32 + (k)] = \
+      a.dbg[((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * kAttWaves + (threadIdx.x >> 6)) * 32 + (k)] = \
           wall_clock64();                                                                       \
   } while (0)
 #else
@@ -597,6 +597,20 @@ __device__ __forceinline__ void cvt_i8x4_f16x4(unsigned w, half2_t &lo, half2_t 
   hi = __builtin_bit_cast(half2_t, b) - bias;
 }
 
+// Same without the subtraction: the fp16 numbers c + 1152.  Used for the value operand, where
+// the constant is taken out again after the contraction (sum_i p_i (v_i + 1152) =
+// sum_i p_i v_i + 1152 sum_i p_i) at a cost of one accumulated sum per head.
+constexpr float kCodeBias = 1152.0f;
+__device__ __forceinline__ half8_t cvt_i8x8_f16x8_biased(unsigned w0, unsigned w1) {
+  const unsigned x0 = w0 ^ 0x80808080u, x1 = w1 ^ 0x80808080u;
+  uint4 r;
+  r.x = __builtin_amdgcn_perm(x0, 0x64646464u, 0x00050004u);
+  r.y = __builtin_amdgcn_perm(x0, 0x64646464u, 0x00070006u);
+  r.z = __builtin_amdgcn_perm(x1, 0x64646464u, 0x00050004u);
+  r.w = __builtin_amdgcn_perm(x1, 0x64646464u, 0x00070006u);
+  return __builtin_bit_cast(half8_t, r);
+}
+
 __device__ __forceinline__ half8_t cvt_i8x8_f16x8(unsigned w0, unsigned w1) {
   half2_t p0, p1, p2, p3;
   cvt_i8x4_f16x4(w0, p0, p1);
@@ -626,6 +640,54 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 #undef CONFKV_DPP
 
+// A 16x16 score tile leaves the matrix core with head 4 * (lane / 16) + i in element i, so at
+// G <= 4 only the first 16 lanes hold real rows and every softmax instruction would work on
+// three quarters of padding.  Two lane-row swaps regroup the real rows over the whole wavefront:
+//   G <= 4: one value per lane; lane row r = lane / 16 holds head r
+//   G  > 4: two values per lane; value j of lane row r holds head 2j + (r >> 1) + 4 (r & 1)
+// The slot (tile column lane % 16) stays where it is.
+template <int G>
+struct RowMap {
+  static constexpr int NV = G <= 4 ? 1 : 2;
+  static __device__ __forceinline__ int head(int j, int r) {
+    return G <= 4 ? r : 2 * j + (r >> 1) + 4 * (r & 1);
+  }
+};
+// rows (a0, b0, a2, b2) of the two operands
+__device__ __forceinline__ float swap16_even(float a, float b) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, a),
+                                                   __builtin_bit_cast(unsigned, b), false, false);
+  return __builtin_bit_cast(float, r[0]);
+}
+// rows (a0, a1, b0, b1) of the two operands
+__device__ __forceinline__ float swap32_low(float a, float b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, a),
+                                                   __builtin_bit_cast(unsigned, b), false, false);
+  return __builtin_bit_cast(float, r[0]);
+}
+template <int G>
+__device__ __forceinline__ void regroup_rows(const floatx4_t &acc, float (&z)[RowMap<G>::NV]) {
+  if constexpr (G <= 4) {
+    z[0] = swap32_low(swap16_even(acc[0], acc[1]), swap16_even(acc[2], acc[3]));
+  } else {
+    z[0] = swap32_low(acc[0], acc[1]);
+    z[1] = swap32_low(acc[2], acc[3]);
+  }
+}
+// A quantity that is uniform over each lane row of the regrouped layout, read back in the
+// matrix-core layout: the value of head 4 * g4 + i (rows that hold no head get anything).
+template <int G>
+__device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], int i, int g4) {
+  if constexpr (G <= 4) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[0]), 16 * i));
+  } else {
+    const int v = __builtin_bit_cast(int, x[i >> 1]);
+    const float lo = __builtin_bit_cast(float, __builtin_amdgcn_readlane(v, 32 * (i & 1)));
+    const float hi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(v, 32 * (i & 1) + 16));
+    return (g4 & 1) ? hi : lo;
+  }
+}
+
 template <int G>
 __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void attend_mfma_kernel(CacheView cv, AttendLaunch a,
                                                                   int ns, int S) {
@@ -646,14 +708,58 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   TS(0);
   const Slice sl = make_slice(cv, a, ns, S);
+  const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
+  const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
+  const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
+  const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
+  const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
+  const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
+
+  const int ntiles = (sl.cnt8 + kTile - 1) / kTile;            // 0 when the split has no INT8 slot
+  // One INT8 tile in flight: four 128-bit K pieces, four V pieces and the raw scale bits.
+  // Loads are branch-free (rows past the slice re-read its last row; their scores are masked
+  // and their probabilities are zero), so the whole tile is in flight before any wait.
+  struct TileRegs {
+    int4 k0, k1, k2, k3, v0, v1, v2, v3;
+    unsigned short ks0, ks1, vs0, vs1;
+  };
+  auto load_tile = [&](int tile) -> TileRegs {
+    TileRegs t;
+    const int base = sl.lo8 + tile * kTile;
+    const int last = sl.hi8 - 1;
+    // 32-bit byte offsets from the unit's (wavefront-uniform) plane bases
+    const unsigned col = (unsigned)c8 * 16u;
+    const int h8 = sl.h8, cap8 = cv.cap8;
+    const unsigned o0 = (unsigned)ring_row_u(h8, min(base + r8, last), cap8) * D + col;
+    const unsigned o1 = (unsigned)ring_row_u(h8, min(base + 8 + r8, last), cap8) * D + col;
+    const unsigned o2 = (unsigned)ring_row_u(h8, min(base + 16 + r8, last), cap8) * D + col;
+    const unsigned o3 = (unsigned)ring_row_u(h8, min(base + 24 + r8, last), cap8) * D + col;
+    t.k0 = *(const int4 *)(K8 + o0);
+    t.v0 = *(const int4 *)(V8 + o0);
+    t.k1 = *(const int4 *)(K8 + o1);
+    t.v1 = *(const int4 *)(V8 + o1);
+    t.k2 = *(const int4 *)(K8 + o2);
+    t.v2 = *(const int4 *)(V8 + o2);
+    t.k3 = *(const int4 *)(K8 + o3);
+    t.v3 = *(const int4 *)(V8 + o3);
+    const unsigned j0 = (unsigned)ring_row_u(h8, min(base + t16, last), cap8);
+    const unsigned j1 = (unsigned)ring_row_u(h8, min(base + 16 + t16, last), cap8);
+    t.ks0 = ((const unsigned short *)KS)[j0];
+    t.vs0 = ((const unsigned short *)VS)[j0];
+    t.ks1 = ((const unsigned short *)KS)[j1];
+    t.vs1 = ((const unsigned short *)VS)[j1];
+    return t;
+  };
+  TileRegs tr = {};
+  // the first INT8 tile is requested before anything else: its latency covers the append,
+  // the query loads and the FP16 tiles
+  if (w < ntiles) tr = load_tile(w);
   append_new_token<D>(cv, a, sl, ns);
   const float NEG = -INFINITY;
   const float sm = a.sm_scale;
   TS(1);
 
   // ---------------- INT8 slots on the matrix cores ----------------
-  const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
-  const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
   uint8_t *Kt = (uint8_t *)tiles + (size_t)w * kTileBytes;   // [32][kKRow]
   uint8_t *Vt = Kt + kTile * kKRow;                           // [128][kVRow], slots permuted
   _Float16 *Pb = (_Float16 *)(Vt + 128 * kVRow);              // [16][kPRow], rows >= G stay 0
@@ -675,56 +781,22 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
   floatx4_t O[8];
 #pragma unroll
   for (int nt = 0; nt < 8; ++nt) O[nt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-  float mrun[4], lrun[4];
+  // running softmax state in the regrouped layout: reference, normaliser (per-lane partial
+  // sum) and the sum of the fp16 probabilities that met biased INT8 values
+  constexpr int NV = RowMap<G>::NV;
+  float mrun[NV], lrun[NV], pbias[NV];
+  int hd[NV];                                    // head of value j of this lane
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { mrun[i] = NEG; lrun[i] = 0.f; }
+  for (int j = 0; j < NV; ++j) { mrun[j] = NEG; lrun[j] = 0.f; pbias[j] = 0.f; hd[j] = RowMap<G>::head(j, g4); }
 
-  const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
-  const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
-  const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
-  const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
-
-  const int ntiles = (sl.cnt8 + kTile - 1) / kTile;            // 0 when the split has no INT8 slot
-  // One INT8 tile in flight: four 128-bit K pieces, four V pieces and the raw scale bits.
-  // Loads are branch-free (rows past the slice re-read its last row; their scores are masked
-  // and their probabilities are zero), so the whole tile is in flight before any wait.
-  struct TileRegs {
-    int4 k0, k1, k2, k3, v0, v1, v2, v3;
-    unsigned short ks0, ks1, vs0, vs1;
-  };
-  auto load_tile = [&](int tile) -> TileRegs {
-    TileRegs t;
-    const int base = sl.lo8 + tile * kTile;
-    const int last = sl.hi8 - 1;
-    const size_t col = (size_t)c8 * 16;
-    const int h8 = sl.h8, cap8 = cv.cap8;
-    const int i0 = ring_row_u(h8, min(base + r8, last), cap8), i1 = ring_row_u(h8, min(base + 8 + r8, last), cap8);
-    const int i2 = ring_row_u(h8, min(base + 16 + r8, last), cap8), i3 = ring_row_u(h8, min(base + 24 + r8, last), cap8);
-    t.k0 = *(const int4 *)(K8 + (size_t)i0 * D + col);
-    t.v0 = *(const int4 *)(V8 + (size_t)i0 * D + col);
-    t.k1 = *(const int4 *)(K8 + (size_t)i1 * D + col);
-    t.v1 = *(const int4 *)(V8 + (size_t)i1 * D + col);
-    t.k2 = *(const int4 *)(K8 + (size_t)i2 * D + col);
-    t.v2 = *(const int4 *)(V8 + (size_t)i2 * D + col);
-    t.k3 = *(const int4 *)(K8 + (size_t)i3 * D + col);
-    t.v3 = *(const int4 *)(V8 + (size_t)i3 * D + col);
-    const int j0 = ring_row_u(h8, min(base + t16, last), cap8), j1 = ring_row_u(h8, min(base + 16 + t16, last), cap8);
-    t.ks0 = ((const unsigned short *)KS)[j0];
-    t.vs0 = ((const unsigned short *)VS)[j0];
-    t.ks1 = ((const unsigned short *)KS)[j1];
-    t.vs1 = ((const unsigned short *)VS)[j1];
-    return t;
-  };
-  TileRegs tr = {};
   // ---------------- FP16 slots: 16-slot tiles on the matrix cores, taken first ----------------
   // (tiles go to the wavefronts from the back, which hold the fewest INT8 tiles; the first
-  // INT8 tile's loads are already in flight while the FP16 tile is computed)
+  // INT8 tile's loads are in flight meanwhile)
   const int ntiles16 = (sl.hi16 - sl.lo16 + 15) / 16;
   {
     const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
     const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
     const int c16 = lane & 15, r4 = lane >> 4;   // load coordinates: 16-byte piece, row
-    bool first = true;
     for (int f = kAttWaves - 1 - w; f < ntiles16; f += kAttWaves) {
       const int base = sl.lo16 + 16 * f;
       int4 kh[4], vh[4];
@@ -735,8 +807,6 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
         kh[r] = *(const int4 *)(K16 + off);
         vh[r] = *(const int4 *)(V16 + off);
       }
-      if (first && w < ntiles) tr = load_tile(w);
-      first = false;
       // K rows as they are (row stride kKRow16 bytes), V transposed to [channel][slot]
 #pragma unroll
       for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (4 * r + r4) * kKRow16 + c16 * 16) = kh[r];
@@ -758,26 +828,30 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       for (int s = 0; s < 4; ++s)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[s], *(const half8_t *)(krow + 16 * s), acc, 0, 0, 0);
       const bool valid = base + t16 < sl.hi16;
-      float corr[4];
+      float z[NV], corr[NV];
+      regroup_rows<G>(acc, z);
       bool changed = false;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int h = 4 * g4 + i;
-        const float sv = valid ? acc[i] * sm : NEG;
-        if (valid && h < G) stash[h * S + sl.cnt8 + (base + t16 - sl.lo16)] = sv;
-        const float mn = fmaxf(mrun[i], row16_max(sv));
-        corr[i] = (mn == NEG) ? 1.f : __expf(mrun[i] - mn);
-        changed |= (mn != mrun[i]);
-        mrun[i] = mn;
-        const float p = valid ? __expf(sv - mn) : 0.f;
-        if (h < G) Pb[h * kPRow + 4 * (t16 & 3) + (t16 >> 2)] = (_Float16)p;
-        lrun[i] = fmaf(lrun[i], corr[i], p);
+      for (int j = 0; j < NV; ++j) {
+        const bool real = valid && hd[j] < G;
+        const float sv = real ? z[j] * sm : NEG;
+        if (real) stash[hd[j] * S + sl.cnt8 + (base + t16 - sl.lo16)] = sv;
+        const float mn = fmaxf(mrun[j], row16_max(sv));
+        corr[j] = (mn == NEG) ? 1.f : __expf(mrun[j] - mn);
+        changed |= (mn != mrun[j]);
+        mrun[j] = mn;
+        const float p = real ? __expf(sv - mn) : 0.f;
+        if (hd[j] < G) Pb[hd[j] * kPRow + 4 * (t16 & 3) + (t16 >> 2)] = (_Float16)p;
+        lrun[j] = fmaf(lrun[j], corr[j], p);
+        pbias[j] *= corr[j];
       }
       if (__builtin_amdgcn_ballot_w64(changed)) {
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt)
+        for (int i = 0; i < 4; ++i) {
+          const float c = rows_to_tile<G>(corr, i, g4);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) O[nt][i] *= corr[i];
+          for (int nt = 0; nt < 8; ++nt) O[nt][i] *= c;
+        }
       }
       wave_lds_sync();
       const half4_t pa = *(const half4_t *)(Pb + t16 * kPRow + 4 * g4);
@@ -789,7 +863,6 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       }
       wave_lds_sync();
     }
-    if (first && w < ntiles) tr = load_tile(w);
   }
   int tix = 0;
   for (int tile = w; tile < ntiles; tile += kAttWaves) {
@@ -826,7 +899,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     if (tile + kAttWaves < ntiles) tr = load_tile(tile + kAttWaves);
 
     // ---- scores: S[head][slot] for the two 16-slot halves of the tile ----
-    floatx4_t sc[2];
+    float sc[2][NV];
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
       const uint8_t *krow = Kt + (16 * sb + t16) * kKRow + g4 * 32;
@@ -837,53 +910,58 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[2], cvt_i8x8_f16x8(b1.x, b1.y), acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[3], cvt_i8x8_f16x8(b1.z, b1.w), acc, 0, 0, 0);
       const bool valid = base + 16 * sb + t16 < sl.hi8;
+      float z[NV];
+      regroup_rows<G>(acc, z);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float s = acc[i] * kscale[sb];
-        sc[sb][i] = valid ? s : NEG;
-        const int h = 4 * g4 + i;
-        if (valid && h < G) stash[h * S + (base + 16 * sb + t16 - sl.lo8)] = s;
+      for (int j = 0; j < NV; ++j) {
+        const float sv = z[j] * kscale[sb];
+        const bool real = valid && hd[j] < G;
+        sc[sb][j] = real ? sv : NEG;
+        if (real) stash[hd[j] * S + (base + 16 * sb + t16 - sl.lo8)] = sv;
       }
     }
     if (tix <= 2) TS(24 + (tix - 1) * 3);
-    // ---- online softmax per head row (rows of this lane: heads 4*g4 + i) ----
+    // ---- online softmax per head ----
     // The running reference m only has to stay within a few units of the true maximum (the
     // merge is exact for any reference), so the row reduction and the rescale of O run only
     // when some score of the tile exceeds the reference by more than kSlack; e^kSlack times
     // the largest fp16 value scale still fits fp16.
     constexpr float kSlack = 4.0f;
-    float lm[4];
+    float lm[NV];
     bool grow = false;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      lm[i] = fmaxf(sc[0][i], sc[1][i]);
-      grow |= lm[i] > mrun[i] + kSlack;             // also true on the first tile (m = -inf)
+    for (int j = 0; j < NV; ++j) {
+      lm[j] = fmaxf(sc[0][j], sc[1][j]);
+      grow |= lm[j] > mrun[j] + kSlack;             // also true on the first tile (m = -inf)
     }
     if (__builtin_amdgcn_ballot_w64(grow)) {
+      float corr[NV];
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const float mn = fmaxf(mrun[j], row16_max(lm[j]));
+        corr[j] = (mn == NEG) ? 1.f : __expf(mrun[j] - mn);
+        mrun[j] = mn;
+        lrun[j] *= corr[j];
+        pbias[j] *= corr[j];
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float mn = fmaxf(mrun[i], row16_max(lm[i]));
-        const float corr = (mn == NEG) ? 1.f : __expf(mrun[i] - mn);
-        mrun[i] = mn;
-        lrun[i] *= corr;
+        const float c = rows_to_tile<G>(corr, i, g4);
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) O[nt][i] *= corr;
+        for (int nt = 0; nt < 8; ++nt) O[nt][i] *= c;
       }
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float psum = 0.f;
+    for (int j = 0; j < NV; ++j) {
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
-        const float p = (sc[sb][i] == NEG) ? 0.f : __expf(sc[sb][i] - mrun[i]);
-        psum += p;
-        const int h = 4 * g4 + i;
-        if (h < G) {
-          const int tau = 16 * sb + t16;                     // slot within the tile
-          Pb[h * kPRow + 4 * (tau & 7) + (tau >> 3)] = (_Float16)(p * vscale[sb]);
-        }
+        const float p = (sc[sb][j] == NEG) ? 0.f : __expf(sc[sb][j] - mrun[j]);
+        lrun[j] += p;
+        const _Float16 ph = (_Float16)(p * vscale[sb]);
+        pbias[j] += (float)ph;                             // exactly what the matrix core will see
+        const int tau = 16 * sb + t16;                     // slot within the tile
+        if (hd[j] < G) Pb[hd[j] * kPRow + 4 * (tau & 7) + (tau >> 3)] = ph;
       }
-      lrun[i] += psum;
     }
     wave_lds_sync();
     if (tix <= 2) TS(25 + (tix - 1) * 3);
@@ -892,23 +970,29 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) {
       const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + 8 * g4);   // 4-byte aligned
-      O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, cvt_i8x8_f16x8(vb[0], vb[1]), O[nt], 0, 0, 0);
+      O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, cvt_i8x8_f16x8_biased(vb[0], vb[1]), O[nt], 0, 0, 0);
     }
     wave_lds_sync();
   }
   TS(16);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) lrun[i] = row16_sum(lrun[i]);
+  for (int j = 0; j < NV; ++j) {
+    lrun[j] = row16_sum(lrun[j]);
+    pbias[j] = row16_sum(pbias[j]) * kCodeBias;     // what the biased INT8 values added per channel
+  }
 
   // the wavefront's matrix-core partial goes into its own (now idle) tile buffer
   float *wo_w = tiles + w * (kTileBytes / 4);
 #pragma unroll
+  for (int j = 0; j < NV; ++j)
+    if (t16 == 0 && hd[j] < G) { wm[w * G + hd[j]] = mrun[j]; wl[w * G + hd[j]] = lrun[j]; }
+#pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int h = 4 * g4 + i;
+    const float bias = rows_to_tile<G>(pbias, i, g4);
     if (h < G) {
-      if (t16 == 0) { wm[w * G + h] = mrun[i]; wl[w * G + h] = lrun[i]; }
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) wo_w[h * D + 16 * nt + t16] = O[nt][i];
+      for (int nt = 0; nt < 8; ++nt) wo_w[h * D + 16 * nt + t16] = O[nt][i] - bias;
     }
   }
 
