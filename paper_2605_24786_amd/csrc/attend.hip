@@ -397,7 +397,7 @@ __device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, fl
 // ---------------------------------------------------------------------------------------
 // Epilogue shared by both bodies.  On entry wm/wl/wo hold NP per-wavefront partials
 // (after a workgroup barrier): partial k is [G][D] floats at
-// wo + (k % 4) * WSTR + (k / 4) * G * D; stash holds the slice's raw scores.
+// wo + (k % kAttWaves) * WSTR + (k / kAttWaves) * G * D; stash holds the slice's raw scores.
 // ---------------------------------------------------------------------------------------
 template <int D, int G, int NP, int WSTR>
 __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const AttendLaunch &a,
@@ -422,21 +422,28 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   // coherent store each
   for (int idx = 2 * tid; idx < G * D; idx += 2 * kAttThreads) {
     const int h = idx / D;
+    // branch-free, so that all LDS reads are in flight together; an empty partial (m = -inf)
+    // may hold anything and enters with weight zero through the selects
+    float mk[NP], lk[NP];
+    float2 ok2[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+      mk[k] = wm[k * G + h];
+      lk[k] = wl[k * G + h];
+      // partial k belongs to wavefront k % kAttWaves
+      ok2[k] = *(const float2 *)&wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx];
+    }
     float M = NEG;
 #pragma unroll
-    for (int k = 0; k < NP; ++k) M = fmaxf(M, wm[k * G + h]);
+    for (int k = 0; k < NP; ++k) M = fmaxf(M, mk[k]);
     float o0 = 0.f, o1 = 0.f, l = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
-      // partial k belongs to wavefront k % 4; an empty partial (m = -inf) is never read
-      const float mk = wm[k * G + h];
-      if (mk > NEG) {
-        const float f = __expf(mk - M);
-        const float *w2 = &wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx];
-        o0 = fmaf(w2[0], f, o0);
-        o1 = fmaf(w2[1], f, o1);
-        l = fmaf(wl[k * G + h], f, l);
-      }
+      const bool live = mk[k] > NEG;
+      const float f = live ? __expf(mk[k] - M) : 0.f;
+      o0 = fmaf(live ? ok2[k].x : 0.f, f, o0);
+      o1 = fmaf(live ? ok2[k].y : 0.f, f, o1);
+      l = fmaf(live ? lk[k] : 0.f, f, l);
     }
     st_agent2(&po[idx], o0, o1);
     if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
