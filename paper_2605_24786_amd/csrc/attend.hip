@@ -1109,12 +1109,14 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   // One workgroup per CU measured best: the exchange between the splits of a unit (arrival
   // counter, partial gather) gets slower with more participants, and a grid that is not a
   // whole number of waves over the CUs leaves a straggler round.  Two per CU only when a
-  // single split per unit would leave half of the chip idle.  Keep >= 128 virtual slots a split.
+  // single split per unit would leave half of the chip idle.
   int want = lim.cus / units_per_layer;
   if (want < 1) want = 1;
   if (want == 1 && 2 * units_per_layer <= 2 * lim.cus && units_per_layer > lim.cus / 2) want = 2;
-  if (forced_splits > 0) want = forced_splits;
-  want = std::min<long long>(want, std::max<long long>(1, nv / 128));
+  // a split below about 512 slots costs more in the exchange than it saves in streaming
+  // (measured on 8- and 12-unit layers of 500 to 4096 slots)
+  want = std::min<long long>(want, std::max<long long>(1, nv / 512));
+  if (forced_splits > 0) want = std::min<long long>(forced_splits, std::max<long long>(1, nv / 128));
   want = std::max(1, std::min(want, kAttendMaxSplits));
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
   // splits shrink the LDS stash when a long unit does not fit otherwise)

@@ -312,6 +312,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
                                                             int32_t *__restrict__ src_all,
                                                             int32_t *__restrict__ sel_all) {
   constexpr int kRsWaves = T / kWave;
+  constexpr int BPT = T >= 256 ? 1 : 256 / T;       // histogram bins per thread in the scan
   __shared__ int hist[256];
   __shared__ int s_tmp[kRsWaves];
   __shared__ int s_cnt[E * kRsWaves];               // kept (or tied) lanes per (round, wavefront)
@@ -403,7 +404,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   for (int hi_bit = top + 1; hi_bit > 0;) {
     const int shift = hi_bit > 8 ? hi_bit - 8 : 0;
     const unsigned dmask = (1u << (hi_bit - shift)) - 1u;
-    if (tid < 256) hist[tid] = 0;
+    for (int bin = tid; bin < 256; bin += T) hist[bin] = 0;
     __syncthreads();
     const unsigned long long prefix = s_prefix;
 #pragma unroll
@@ -412,15 +413,25 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
         atomicAdd(&hist[(int)((unsigned)(key[k] >> shift) & dmask)], 1);
     }
     __syncthreads();
-    const int cnt = tid < 256 ? hist[tid] : 0;
+    // thread t owns the bins [t * BPT, (t + 1) * BPT)
+    int cnt[BPT], mine = 0;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      cnt[j] = tid * BPT < 256 ? hist[tid * BPT + j] : 0;
+      mine += cnt[j];
+    }
     int total;
-    const int before = block_scan_excl<kRsWaves>(cnt, s_tmp, &total);
+    int before = block_scan_excl<kRsWaves>(mine, s_tmp, &total);
     const int krem = s_krem;
     __syncthreads();                                // every thread has read s_krem
-    if (tid < 256 && before < krem && krem <= before + cnt) {   // exactly one bin holds the cut-off
-      s_prefix = prefix | ((unsigned long long)tid << shift);
-      s_krem = krem - before;
-      s_done = (krem - before == cnt);              // the whole bucket goes
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      if (before < krem && krem <= before + cnt[j]) {   // exactly one bin holds the cut-off
+        s_prefix = prefix | ((unsigned long long)(tid * BPT + j) << shift);
+        s_krem = krem - before;
+        s_done = (krem - before == cnt[j]);             // the whole bucket goes
+      }
+      before += cnt[j];
     }
     mask = ~0ull << shift;
     hi_bit = shift;
@@ -742,7 +753,12 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 double *score, int32_t *src, int32_t *sel, int n_max,
                                 hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
-  if (n_max <= 256 * 20)
+  // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
+  // nothing); with few units the chip is filled by giving each unit four wavefronts.
+  if (n_max <= 64 * 33 && U >= 2048)
+    hipLaunchKernelGGL((rank_select_reg_kernel<64, 33>), dim3(U), dim3(64), 0, stream, cv, appended,
+                       alpha, src, sel);
+  else if (n_max <= 256 * 20)
     hipLaunchKernelGGL((rank_select_reg_kernel<256, 20>), dim3(U), dim3(256), 0, stream, cv, appended,
                        alpha, src, sel);
   else if (n_max <= 1024 * 33)
