@@ -445,39 +445,20 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       o1 = fmaf(live ? ok2[k].y : 0.f, f, o1);
       l = fmaf(live ? lk[k] : 0.f, f, l);
     }
-    st_agent2(&po[idx], o0, o1);
-    if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
-  }
-  TS(19);
-  wait_stores_done();
-  __syncthreads();
-  TS(20);
-  // Arrival: every split owns one flag word and stores the launch's epoch into it; nobody
-  // does a read-modify-write, so arrivals do not serialise at the memory side.  The first
-  // wavefront polls all flags of the unit with one coherent load per round (bounded).
-  unsigned *flags = a.arrive + (size_t)sl.ul * a.max_splits;
-  if (tid == 0) __hip_atomic_store(&flags[sl.j], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (tid < kWave) {
-    int ok = 1;
-    if (ns > 1) {
-      int spins = 0;
-      for (;;) {
-        const bool here = tid >= ns || __hip_atomic_load(&flags[tid], __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
-        if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
-        __builtin_amdgcn_s_sleep(1);
-        if (++spins > kSpinLimit) { ok = 0; break; }
-      }
-      if (!ok && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+    if (ns == 1) {
+      // a unit with a single split is complete here: same arithmetic as the general merge
+      // below (weight e^0 = 1), without the trip through device memory
+      const double inv = 1.0 / (double)l;
+      __half2 o2;
+      o2.x = __float2half_rn((float)((double)o0 * inv));
+      o2.y = __float2half_rn((float)((double)o1 * inv));
+      *(__half2 *)&a.out[((size_t)(sl.b * cv.Hkv * G + sl.g * G)) * D + idx] = o2;
+      if (idx % D == 0) { gm[h] = M; ginv[h] = inv; }
+    } else {
+      st_agent2(&po[idx], o0, o1);
+      if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
     }
-    if (tid == 0) *s_ok = ok;
   }
-  __syncthreads();
-  TS(21);
-  if (!*s_ok) return;
-
-  // ---- one round trip: all (m, l) partials of the unit -> LDS, and this split's share of
-  // the unit's output partials -> registers ----
   const float *mlu = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
   const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
   float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
@@ -485,23 +466,55 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const int per = (G * D + ns - 1) / ns;             // output elements per split (<= 256 threads each
   const int oidx = sl.j * per + tid;                 //  for ns >= G*D/256)
   const bool has_out = tid < per && oidx < G * D;
-  float opre[kOutPre];
-#pragma unroll
-  for (int k = 0; k < kOutPre; ++k)
-    opre[k] = (has_out && k < ns) ? ld_agent(&pou[(size_t)k * G * D + oidx]) : 0.f;
-  for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
-  __syncthreads();
-  if (tid < G) {
-    float M = NEG;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, pml[(s * G + tid) * 2]);
-    double L = 0.0;
-    for (int s = 0; s < ns; ++s) {
-      const float ms = pml[(s * G + tid) * 2];
-      if (ms > NEG) L += exp((double)ms - (double)M) * (double)pml[(s * G + tid) * 2 + 1];
+  float opre[kOutPre] = {};
+  TS(19);
+  if (ns > 1) {
+    wait_stores_done();
+    __syncthreads();
+    TS(20);
+    // Arrival: every split owns one flag word and stores the launch's epoch into it; nobody
+    // does a read-modify-write, so arrivals do not serialise at the memory side.  The first
+    // wavefront polls all flags of the unit with one coherent load per round (bounded).
+    unsigned *flags = a.arrive + (size_t)sl.ul * a.max_splits;
+    if (tid == 0) __hip_atomic_store(&flags[sl.j], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < kWave) {
+      int ok = 1;
+      if (ns > 1) {
+        int spins = 0;
+        for (;;) {
+          const bool here = tid >= ns || __hip_atomic_load(&flags[tid], __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+          if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
+          __builtin_amdgcn_s_sleep(1);
+          if (++spins > kSpinLimit) { ok = 0; break; }
+        }
+        if (!ok && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+      }
+      if (tid == 0) *s_ok = ok;
     }
-    gm[tid] = M;
-    ginv[tid] = 1.0 / L;
-  }
+    __syncthreads();
+    TS(21);
+    if (!*s_ok) return;
+
+    // ---- one round trip: all (m, l) partials of the unit -> LDS, and this split's share of
+    // the unit's output partials -> registers ----
+#pragma unroll
+    for (int k = 0; k < kOutPre; ++k)
+      opre[k] = (has_out && k < ns) ? ld_agent(&pou[(size_t)k * G * D + oidx]) : 0.f;
+    for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
+    __syncthreads();
+    if (tid < G) {
+      float M = NEG;
+      for (int s = 0; s < ns; ++s) M = fmaxf(M, pml[(s * G + tid) * 2]);
+      double L = 0.0;
+      for (int s = 0; s < ns; ++s) {
+        const float ms = pml[(s * G + tid) * 2];
+        if (ms > NEG) L += exp((double)ms - (double)M) * (double)pml[(s * G + tid) * 2 + 1];
+      }
+      gm[tid] = M;
+      ginv[tid] = 1.0 / L;
+    }
+  }  // ns > 1
   __syncthreads();
   TS(22);
   // ---- mass + EMA of the slice ----
@@ -526,7 +539,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   }
   TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
-  {
+  if (ns > 1) {
     const int Hq = cv.Hkv * G;
     const int i1 = min(G * D, (sl.j + 1) * per);
     for (int idx = oidx; idx < i1; idx += kAttThreads) {
@@ -1113,9 +1126,10 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   int want = lim.cus / units_per_layer;
   if (want < 1) want = 1;
   if (want == 1 && 2 * units_per_layer <= 2 * lim.cus && units_per_layer > lim.cus / 2) want = 2;
-  // a split below about 512 slots costs more in the exchange than it saves in streaming
+  // a split below about 128 KB of cache costs more in the exchange than it saves in streaming
   // (measured on 8- and 12-unit layers of 500 to 4096 slots)
-  want = std::min<long long>(want, std::max<long long>(1, nv / 512));
+  const long long unit_bytes = (long long)(n_ub - n16_ub) * (2 * D + 4) + (long long)n16_ub * 4 * D;
+  want = std::min<long long>(want, std::max<long long>(1, unit_bytes / (128 * 1024)));
   if (forced_splits > 0) want = std::min<long long>(forced_splits, std::max<long long>(1, nv / 128));
   want = std::max(1, std::min(want, kAttendMaxSplits));
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
