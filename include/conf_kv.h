@@ -164,6 +164,22 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
                    float *ema, uint8_t *is_fp16, uint16_t *k16, uint16_t *v16, int8_t *k8,
                    int8_t *v8, uint16_t *k_scale, uint16_t *v_scale, int32_t *n_out);
 
+/* The inverse of conf_kv_export: replaces the cache of one unit by n slots given in the same
+ * position-sorted view (harness re-synchronisation, cache hand-over between handles).
+ * pos int32 [n] strictly increasing; ema fp32 [n]; is_fp16 uint8 [n]: zeros (INT8 slots) then
+ * ones (FP16 slots), at most fp16_window ones, all ones for an FP16-only cache; k16 / v16 fp16
+ * bits [n][D], read on FP16 slots; k8 / v8 int8 [n][D] and k_scale / v_scale fp16 bits [n], read
+ * on INT8 slots (a plane no slot reads may be NULL).  0 <= n <= capacity - 1
+ * (CONF_KV_ERR_CAPACITY); malformed views give CONF_KV_ERR_INVALID_ARG and leave the unit
+ * unchanged.  Not allowed between conf_kv_attend of that layer and the next
+ * conf_kv_evict_compact (CONF_KV_ERR_BAD_STATE).  The next token appended to the layer gets a
+ * position above every imported one.  Budgets are per (layer, sequence): the caller keeps the
+ * kv-heads of one sequence at equal length. */
+int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head, int32_t n,
+                   const int32_t *pos, const float *ema, const uint8_t *is_fp16, const uint16_t *k16,
+                   const uint16_t *v16, const int8_t *k8, const int8_t *v8, const uint16_t *k_scale,
+                   const uint16_t *v_scale);
+
 /* Device-side counters since conf_kv_create.  Returns CONF_KV_ERR_DEVICE if any kernel
  * reported an internal error (the counters are still filled in). */
 int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *host_stats);

@@ -57,6 +57,7 @@ SYMBOLS = {
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
     "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
     "conf_kv_export": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32] + [_P] * 10),
+    "conf_kv_import": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [_P] * 9),
     "conf_kv_counters": (C.c_int, [_P, C.POINTER(ConfKVStats)]),
     "conf_kv_attend_splits": (C.c_int, [_P, C.c_int32]),
     "conf_kv_strerror": (C.c_char_p, [C.c_int]),
@@ -185,6 +186,22 @@ class ConfKV:
         return dict(n=m, pos=pos[:m], ema=ema[:m], is16=is16[:m].astype(bool),
                     k16=k16[:m].view(np.float16), v16=v16[:m].view(np.float16), k8=k8[:m], v8=v8[:m],
                     ks=ks[:m].view(np.float16), vs=vs[:m].view(np.float16))
+
+    def import_unit(self, layer: int, b: int, kv_head: int, view: dict):
+        """`view` is what export() returns (n, pos, ema, is16, k16, v16, k8, v8, ks, vs)."""
+        n = int(view["n"])
+        keep = [np.ascontiguousarray(view["pos"], np.int32), np.ascontiguousarray(view["ema"], np.float32),
+                np.ascontiguousarray(view["is16"], np.uint8)]
+        for name, dt in (("k16", np.uint16), ("v16", np.uint16), ("k8", np.int8), ("v8", np.int8),
+                         ("ks", np.uint16), ("vs", np.uint16)):
+            x = view.get(name)
+            if x is None:
+                keep.append(None)
+            else:
+                x = np.ascontiguousarray(x)
+                keep.append(x.view(dt) if x.dtype != dt else x)
+        ptrs = [None if x is None else x.ctypes.data for x in keep]
+        self._check(self.lib.conf_kv_import(self.h, layer, b, kv_head, n, *ptrs), "conf_kv_import")
 
     def counters(self, check: bool = True) -> ConfKVStats:
         st = ConfKVStats()

@@ -410,6 +410,58 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   return CONF_KV_OK;
 }
 
+int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head, int32_t n,
+                   const int32_t *pos, const float *ema, const uint8_t *is_fp16, const uint16_t *k16,
+                   const uint16_t *v16, const int8_t *k8, const int8_t *v8, const uint16_t *k_scale,
+                   const uint16_t *v_scale) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  if (b < 0 || b >= h->cfg.batch || kv_head < 0 || kv_head >= h->cfg.n_kv_heads || n < 0)
+    return CONF_KV_ERR_INVALID_ARG;
+  if (n > h->cfg.capacity - 1) return CONF_KV_ERR_CAPACITY;
+  if (h->appended[layer]) return CONF_KV_ERR_BAD_STATE;
+  if (n > 0 && (!pos || !ema || !is_fp16)) return CONF_KV_ERR_INVALID_ARG;
+  const CacheView &cv = h->cv;
+  int n8 = 0;
+  while (n8 < n && !is_fp16[n8]) ++n8;
+  const int n16 = n - n8;
+  for (int i = n8; i < n; ++i)
+    if (!is_fp16[i]) return CONF_KV_ERR_INVALID_ARG;             // an INT8 slot behind an FP16 one
+  for (int i = 1; i < n; ++i)
+    if (pos[i] <= pos[i - 1]) return CONF_KV_ERR_INVALID_ARG;
+  if (cv.W < 0 ? n8 > 0 : n16 > cv.W) return CONF_KV_ERR_INVALID_ARG;
+  if (n16 > cv.cap16) return CONF_KV_ERR_INVALID_ARG;
+  if (n8 > 0 && (!k8 || !v8 || !k_scale || !v_scale)) return CONF_KV_ERR_INVALID_ARG;
+  if (n16 > 0 && (!k16 || !v16)) return CONF_KV_ERR_INVALID_ARG;
+  const size_t u = ((size_t)layer * cv.B + b) * cv.Hkv + kv_head;
+  const size_t D = cv.D;
+  CK_HIP(h, hipDeviceSynchronize());
+  if (n > 0) {
+    CK_HIP(h, hipMemcpy(cv.pos + u * cv.cap, pos, (size_t)n * 4, hipMemcpyHostToDevice));
+    CK_HIP(h, hipMemcpy(cv.ema + u * cv.cap, ema, (size_t)n * 4, hipMemcpyHostToDevice));
+  }
+  if (n8 > 0) {                                                   // INT8 ring rows 0 .. n8-1
+    CK_HIP(h, hipMemcpy(cv.k8 + u * cv.cap8 * D, k8, (size_t)n8 * D, hipMemcpyHostToDevice));
+    CK_HIP(h, hipMemcpy(cv.v8 + u * cv.cap8 * D, v8, (size_t)n8 * D, hipMemcpyHostToDevice));
+    CK_HIP(h, hipMemcpy(cv.ks + u * cv.cap8, k_scale, (size_t)n8 * 2, hipMemcpyHostToDevice));
+    CK_HIP(h, hipMemcpy(cv.vs + u * cv.cap8, v_scale, (size_t)n8 * 2, hipMemcpyHostToDevice));
+  }
+  if (n16 > 0) {                                                  // FP16 ring rows 0 .. n16-1
+    CK_HIP(h, hipMemcpy(cv.k16 + u * cv.cap16 * D, k16 + (size_t)n8 * D, (size_t)n16 * D * 2,
+                        hipMemcpyHostToDevice));
+    CK_HIP(h, hipMemcpy(cv.v16 + u * cv.cap16 * D, v16 + (size_t)n8 * D, (size_t)n16 * D * 2,
+                        hipMemcpyHostToDevice));
+  }
+  const int32_t zero = 0, len = n, cnt8 = n8;
+  CK_HIP(h, hipMemcpy(cv.len + u, &len, 4, hipMemcpyHostToDevice));
+  CK_HIP(h, hipMemcpy(cv.n8 + u, &cnt8, 4, hipMemcpyHostToDevice));
+  CK_HIP(h, hipMemcpy(cv.head16 + u, &zero, 4, hipMemcpyHostToDevice));
+  CK_HIP(h, hipMemcpy(cv.head8 + u, &zero, 4, hipMemcpyHostToDevice));
+  h->len_ub[layer] = std::max(h->len_ub[layer], n);
+  if (n > 0) h->next_pos[layer] = std::max(h->next_pos[layer], pos[n - 1] + 1);
+  return CONF_KV_OK;
+}
+
 int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *st) {
   if (!h || !st) return CONF_KV_ERR_INVALID_ARG;
   unsigned long long raw[kStatSlots];

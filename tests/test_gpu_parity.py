@@ -351,6 +351,72 @@ def test_lockstep_long_run_wraps_the_int8_ring(lib, torch_cuda, G, D, alpha):
     ls.close()
 
 
+def test_import_round_trip_and_rejections(lib, torch_cuda):
+    """conf_kv_import is the inverse of conf_kv_export: a handle rebuilt from the exported views of
+    another (whose rings have moved) attends, evicts and demotes bit-identically; malformed views
+    are refused and leave the unit as it was."""
+    torch = torch_cuda
+    wl = small(1).scaled(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, vocab=3001, prefill=150, steps=30,
+                         n_tight=(120,), n_loose=(140,), protected=8, fp16_window=12, alpha=0.3,
+                         logit_std=(0.5, 6.0), logit_run=3)
+    say(f"import: capacity={wl.capacity}")
+    a = Lockstep(lib, wl, seed=5)
+    for t in range(wl.steps):                      # moves both ring heads of handle a
+        a.step(check_state=False)
+    b = lib.from_workload(wl)
+    views = {g: a.kv.export(0, 0, g) for g in range(2)}
+    for g in range(2):
+        b.import_unit(0, 0, g, views[g])
+        back = b.export(0, 0, g)
+        for name, x in views[g].items():
+            y = back[name]
+            same = (x == y) if name == "n" else np.array_equal(np.asarray(x).view(np.uint8), np.asarray(y).view(np.uint8))
+            assert same, f"kv-head {g}: {name} differs after import"
+    # the same steps on both handles
+    B, Hq, D = wl.batch, wl.n_q_heads, wl.head_dim
+    out_a = torch.empty((B, Hq, D), dtype=torch.float16, device="cuda")
+    out_b = torch.empty_like(out_a)
+    conf = torch.empty(B, dtype=torch.float32, device="cuda")
+    sel = torch.empty(B, dtype=torch.uint8, device="cuda")
+    for t in range(wl.steps, wl.steps + 12):
+        q, k, v = (torch.from_numpy(x).cuda() for x in gen.step_inputs(wl, 5, 0, t))
+        lg = torch.from_numpy(gen.step_logits(wl, 5, t)).cuda()
+        for kv, out in ((a.kv, out_a), (b, out_b)):
+            kv.attend(0, q, k, v, out)
+            kv.step(lg, conf, sel)
+            kv.evict_compact()
+        assert torch.equal(out_a, out_b), f"step {t}: outputs differ after import"
+    for g in range(2):
+        xa, xb = a.kv.export(0, 0, g), b.export(0, 0, g)
+        for name in xa:
+            same = (xa[name] == xb[name]) if name == "n" else \
+                np.array_equal(np.asarray(xa[name]).view(np.uint8), np.asarray(xb[name]).view(np.uint8))
+            assert same, f"kv-head {g}: {name} differs {12} steps after import"
+    # rejections
+    good = b.export(0, 0, 0)
+    def refused(**change):
+        v = dict(good); v.update(change)
+        with pytest.raises(lib.ConfKVError) as e:
+            b.import_unit(0, 0, 0, v)
+        return e.value.status
+    pos_bad = good["pos"].copy(); pos_bad[3] = pos_bad[2]
+    assert refused(pos=pos_bad) == -1                                   # positions not increasing
+    tags = good["is16"].copy(); tags[0] = True
+    assert refused(is16=tags) == -1                                     # INT8 behind FP16
+    assert refused(is16=np.ones_like(good["is16"])) == -1               # more FP16 slots than the window
+    assert refused(n=wl.capacity) == -4
+    assert refused(k8=None) == -1
+    after = b.export(0, 0, 0)
+    assert all(np.array_equal(np.asarray(good[k]), np.asarray(after[k])) for k in good if k != "n")
+    q, k, v = (torch.from_numpy(x).cuda() for x in gen.step_inputs(wl, 5, 0, 99))
+    b.attend(0, q, k, v, out_b)
+    with pytest.raises(lib.ConfKVError) as e:
+        b.import_unit(0, 0, 0, good)
+    assert e.value.status == -5                                         # an append awaits its commit
+    b.close()
+    a.close()
+
+
 def test_call_order_and_capacity_errors(lib, torch_cuda):
     torch = torch_cuda
     kv = _mk(lib, capacity=64, n_tight=[32], n_loose=[60], protected_window=4)
