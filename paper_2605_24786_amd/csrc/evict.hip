@@ -100,6 +100,32 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Correctly rounded float64 quotients n / d for many numerators and one denominator.
+// The compiler's own division is rcp, two Newton steps on the reciprocal, then
+// q0 = n y, r = fma(-d, q0, n), q = fma(r, y, q0) (plus range scaling that only acts outside
+// the ranges met here: d and n are differences of float32 values or of int32 positions, so
+// d lies in [2^-149, 2^129] and n in {0} or [2^-149, d]).  The reciprocal part depends on d
+// alone and is done once per unit; the three per-numerator operations are the same ones, so
+// the quotient has the same bits as n / d.
+// ---------------------------------------------------------------------------------------
+struct Divisor {
+  double d, y;
+};
+__device__ __forceinline__ Divisor make_divisor(double d) {
+  double y = __builtin_amdgcn_rcp(d);
+  double e = __builtin_fma(-d, y, 1.0);
+  y = __builtin_fma(y, e, y);
+  e = __builtin_fma(-d, y, 1.0);
+  y = __builtin_fma(y, e, y);
+  return Divisor{d, y};
+}
+__device__ __forceinline__ double quotient(double n, const Divisor &dv) {
+  const double q0 = __dmul_rn(n, dv.y);
+  const double r = __builtin_fma(-dv.d, q0, n);
+  return __builtin_fma(r, dv.y, q0);
+}
+
+// ---------------------------------------------------------------------------------------
 // Outcome of one unit's selection.  The INT8 rows are a ring, so the survivors can close the
 // holes from either side: rows behind the first hole shift left (head stays), or rows in
 // front of the last INT8 hole shift right (head advances by the INT8 evictions).  The side
@@ -121,7 +147,7 @@ __device__ __forceinline__ void write_selection(const CacheView &cv, int u, int3
   sel[4] = last_hole8;
   sel[5] = right;
   sel[6] = right ? ring_row(h8, e8, cv.cap8) : h8;
-  sel[7] = 0;
+  sel[7] = 1;                                        // this unit's selection is final
   if (evicted > 0) {
     // traffic of the moves the compaction kernel will make (each row is read and written once)
     const long long rows8 = right ? right_rows : left_rows;
@@ -180,6 +206,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const int n8 = cv.n8[u];
   const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
+  if (sel[7] != 0) return;                            // settled by rank_small_kernel
   const int p_eff = min(cv.P, n);
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
@@ -211,9 +238,10 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
+  const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
   for (int i = tid; i < ncand; i += kRsThreads) {
-    const double ah = (a_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)ema[i], a_lo), a_rng);
-    const double rh = (p_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)pos[i], p_lo), p_rng);
+    const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)ema[i], a_lo), a_div);
+    const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[i], p_lo), p_div);
     score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
   }
   __syncthreads();                                  // orders the score writes before the reads
@@ -327,6 +355,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   const int n8 = cv.n8[u];
   const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
+  if (sel[7] != 0) return;                            // settled by rank_small_kernel
   const int p_eff = min(cv.P, n);
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
@@ -363,6 +392,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
+  const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
   unsigned long long key[E];
   unsigned long long kmin = ~0ull, kmax = 0ull;
 #pragma unroll
@@ -370,8 +400,8 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
     const int i = tid + k * T;
     key[k] = 0ull;
     if (k < Ed && i < ncand) {
-      const double ah = (a_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)av[k], a_lo), a_rng);
-      const double rh = (p_rng == 0.0) ? 0.0 : __ddiv_rn(__dsub_rn((double)pos[i], p_lo), p_rng);
+      const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)av[k], a_lo), a_div);
+      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[i], p_lo), p_div);
       key[k] = (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
       kmin = key[k] < kmin ? key[k] : kmin;
       kmax = key[k] > kmax ? key[k] : kmax;
@@ -532,6 +562,132 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
 #pragma unroll
     for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); l8 = max(l8, s_last8[k]); }
     write_selection(cv, u, sel, tot_keep /* = n - e */, n8, k8, hl, e, l8);
+    cv.unit_evicted[u] += (unsigned)e;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// rank_small: grid (U / 4), one wavefront per unit.  Runs first and settles every unit that
+// evicts nothing or at most kSmallE slots -- the steady state of a decode loop, where a unit
+// is one token over its budget: the e lowest (score, slot) pairs are found by e passes of a
+// running lexicographic minimum, with no histogram, no survivor ranking and a handful of
+// registers, so many wavefronts fit a SIMD.  Same score arithmetic, same decisions as the
+// general kernels, which then skip the settled units (sel[7] = 1) and handle the rest.
+// ---------------------------------------------------------------------------------------
+constexpr int kSmallE = 4;
+
+__global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, LayerMask appended,
+                                                                double alpha,
+                                                                int32_t *__restrict__ src_all,
+                                                                int32_t *__restrict__ sel_all, int U) {
+  const int lane = threadIdx.x & 63;
+  const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6);
+  if (u >= U) return;
+  const int UPL = cv.B * cv.Hkv;
+  const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
+  const int n = cv.len[u] + (appended.get(layer) ? 1 : 0);
+  const int n8 = cv.n8[u];
+  const int N = cv.budget[layer * cv.B + b];
+  int32_t *sel = sel_all + (size_t)u * kSelInts;
+  const int p_eff = min(cv.P, n);
+  const int ncand = n - p_eff;
+  const int e = min(n - N, ncand);
+  if (n <= N || e <= 0) {
+    if (lane == 0) write_selection(cv, u, sel, n, n8, n8, n, 0, -1);
+    return;
+  }
+  if (e > kSmallE) {
+    if (lane == 0) sel[7] = 0;                       // left to the general kernel
+    return;
+  }
+  const float *ema = cv.ema + (size_t)u * cv.cap;
+  const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  // loads go out in batches of kBatch (indices past the end re-read the last candidate), so a
+  // long unit costs a few memory round trips per pass and not one per 64 slots
+  constexpr int kBatch = 8;
+  float fmin_ = INFINITY, fmax_ = -INFINITY;
+  for (int base = 0; base < ncand; base += kBatch * kWave) {
+    float a[kBatch];
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r) a[r] = ema[min(base + r * kWave + lane, ncand - 1)];
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r) {
+      fmin_ = fminf(fmin_, a[r]);
+      fmax_ = fmaxf(fmax_, a[r]);
+    }
+  }
+  const double a_lo = (double)wave_min(fmin_), a_hi = (double)wave_max(fmax_);
+  const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
+  const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
+  const double oma = __dsub_rn(1.0, alpha);
+  const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
+
+  int ev[kSmallE];
+  unsigned long long prev_key = 0ull;
+  int prev_idx = -1;                                 // every (key, slot) pair is above (0, -1)
+#pragma unroll
+  for (int p = 0; p < kSmallE; ++p) {
+    ev[p] = 0x7fffffff;
+    if (p < e) {                                     // uniform over the wavefront
+      unsigned long long best_key = ~0ull;
+      int best_idx = 0x7fffffff;
+      for (int base = 0; base < ncand; base += kBatch * kWave) {
+        float a[kBatch];
+        int ps[kBatch];
+#pragma unroll
+        for (int r = 0; r < kBatch; ++r) {
+          const int i = min(base + r * kWave + lane, ncand - 1);
+          a[r] = ema[i];
+          ps[r] = pos[i];
+        }
+#pragma unroll
+        for (int r = 0; r < kBatch; ++r) {
+          const int i = base + r * kWave + lane;
+          const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)a[r], a_lo), a_div);
+          const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)ps[r], p_lo), p_div);
+          const unsigned long long key =
+              (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
+          const bool above = key > prev_key || (key == prev_key && i > prev_idx);
+          if (i < ncand && above && key < best_key) {  // slots rise within a lane: first one wins a tie
+            best_key = key;
+            best_idx = i;
+          }
+        }
+      }
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) {
+        const unsigned long long ok = __shfl_xor(best_key, m, kWave);
+        const int oi = __shfl_xor(best_idx, m, kWave);
+        if (ok < best_key || (ok == best_key && oi < best_idx)) {
+          best_key = ok;
+          best_idx = oi;
+        }
+      }
+      ev[p] = best_idx;
+      prev_key = best_key;
+      prev_idx = best_idx;
+    }
+  }
+  // evicted slots in slot order
+#pragma unroll
+  for (int x = 1; x < kSmallE; ++x)
+#pragma unroll
+    for (int y = x; y > 0; --y)
+      if (ev[y] < ev[y - 1]) { const int t = ev[y]; ev[y] = ev[y - 1]; ev[y - 1] = t; }
+  const int n_new = n - e;
+  int32_t *src = src_all + (size_t)u * cv.cap;
+  for (int j = lane; j < n_new; j += kWave) {
+    int sidx = j;
+#pragma unroll
+    for (int q = 0; q < kSmallE; ++q) sidx += (ev[q] <= sidx);   // unused entries are INT_MAX
+    src[j] = sidx;
+  }
+  if (lane == 0) {
+    int gone8 = 0, last8 = -1;
+#pragma unroll
+    for (int q = 0; q < kSmallE; ++q)
+      if (ev[q] < n8) { ++gone8; last8 = ev[q]; }
+    write_selection(cv, u, sel, n_new, n8, n8 - gone8, ev[0], e, last8);
     cv.unit_evicted[u] += (unsigned)e;
   }
 }
@@ -753,6 +909,8 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 double *score, int32_t *src, int32_t *sel, int n_max,
                                 hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
+  hipLaunchKernelGGL(rank_small_kernel, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                     src, sel, U);
   // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
   // nothing); with few units the chip is filled by giving each unit four wavefronts.
   if (n_max <= 64 * 33 && U >= 2048)

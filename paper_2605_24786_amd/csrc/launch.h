@@ -48,7 +48,8 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
 // Per unit, written by rank_select: [0] new length, [1] new INT8 count, [2] first evicted slot,
 // [3] evicted slots, [4] last evicted INT8 slot (-1: none), [5] 1 = the INT8 rows in front of
 // that slot shift right (the ring head advances), 0 = the rows behind the first hole shift
-// left, [6] INT8 ring head after the compaction, [7] spare.
+// left, [6] INT8 ring head after the compaction, [7] 1 = the entries above are final for this
+// call (0 after the first ranking kernel: the unit waits for the general one).
 constexpr int kSelInts = 8;
 hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
                                int T0, const float *ema0, hipStream_t stream);
