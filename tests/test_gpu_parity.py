@@ -250,7 +250,10 @@ def _evict_case(lib, torch, n, N, P, W, alpha, ema, D=64, seed=0):
 
 @pytest.mark.parametrize("n,N,P,W", [(300, 100, 20, 30), (300, 100, 20, -1), (1000, 999, 1, 16),
                                      (515, 64, 64, 8), (200, 50, 0, 0), (4000, 512, 128, 64),
-                                     (260, 100, 10, 150), (90, 200, 10, 16)])
+                                     (260, 100, 10, 150), (90, 200, 10, 16),
+                                     # one to five slots over the budget: the one-wavefront ranking kernel
+                                     (700, 699, 16, 32), (700, 698, 16, 32), (1300, 1297, 8, 64),
+                                     (2100, 2096, 128, 64), (640, 635, 16, 700), (3000, 2998, 64, -1)])
 def test_evict_random_ema(lib, torch_cuda, n, N, P, W):
     say(f"evict n={n} N={N} P={P} W={W}")
     rng = np.random.default_rng(n + N)
@@ -274,6 +277,13 @@ def test_evict_ties_and_degenerate(lib, torch_cuda):
     assert list(u.pos) == list(range(350, 400))
     # a single candidate
     _evict_case(lib, torch, 20, 19, 19, 4, 0.65, rng.random(20))
+    # a few slots over the budget with ties at the cut-off: oldest first among equal scores
+    u = _evict_case(lib, torch, n, n - 3, 16, 32, 1.0, np.full(n, 0.5))
+    assert list(u.pos) == list(range(3, 400))
+    lv = rng.integers(0, 3, n) / 2.0
+    for over in (1, 2, 3, 4):
+        _evict_case(lib, torch, n, n - over, 16, 32, 1.0, lv)
+        _evict_case(lib, torch, n, n - over, 16, 500, 0.65, lv)
 
 
 # ------------------------------------------------------------------ whole decode steps
