@@ -184,7 +184,10 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
  * reported an internal error (the counters are still filled in). */
 int conf_kv_counters(conf_kv_handle *h, conf_kv_stats *host_stats);
 
-/* Split count conf_kv_attend would use for `layer` now (diagnostics / benchmarks). */
+/* Split count conf_kv_attend would use for `layer` now (diagnostics / benchmarks); 1000 + the
+ * count when the layer's shape needs the two-launch form (the splits of a unit cannot all be
+ * resident at once, or a split's scores do not fit on chip: partial results and raw scores then
+ * go through the scratch buffer and a second kernel finishes the attention). */
 int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer);
 
 const char *conf_kv_strerror(int status);

@@ -26,7 +26,7 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-  size_t conf_partial, conf_arrive, arrive, part_ml, part_o, score, src, sel, total;
+  size_t conf_partial, conf_arrive, arrive, part_ml, part_o, spill, score, src, sel, total;
   size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
 };
 
@@ -97,6 +97,7 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
   s.part_ml = take(UPL * kAttendMaxSplits * G * 2 * 4);
   s.part_o = take(UPL * kAttendMaxSplits * G * D * 4);
+  s.spill = take(attend_spill_floats((int)UPL, (int)G, c->capacity) * 4);
   s.score = take(U * c->capacity * 8);
   s.src = take(U * c->capacity * 4);
   s.sel = take(U * kSelInts * 4);
@@ -119,7 +120,8 @@ struct conf_kv_handle {
   std::vector<int32_t> next_pos;     // position the next appended token gets
   std::vector<uint8_t> appended;     // an append awaits its commit
   std::vector<uint32_t> epoch;       // attend launches so far, per layer (arrival-flag value)
-  int forced_splits = 0;
+  int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
+  bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
   int last_hip = 0;
 };
 
@@ -168,6 +170,7 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->appended.assign(L, 0);
   h->epoch.assign(L, 0u);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
+  if (const char *tl = getenv("CONF_KV_TWO_LAUNCH")) h->force_two_launch = atoi(tl) != 0;
 
   CacheView &cv = h->cv;
   uint8_t *s = h->state;
@@ -244,7 +247,7 @@ static int plan_for_layer(conf_kv_handle *h, int layer, AttendPlan *plan) {
   const int W = h->cfg.fp16_window;
   const int n16_ub = W < 0 ? n_ub : std::min(n_ub, W + 1);
   if (!attend_plan(h->cfg.head_dim, h->cv.G, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
-                   h->forced_splits, plan))
+                   h->forced_splits, h->force_two_launch, plan))
     return CONF_KV_ERR_BAD_SHAPE;
   return CONF_KV_OK;
 }
@@ -269,6 +272,7 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
   a.out = (__half *)dev_out16;
   a.part_ml = (float *)(h->scratch + h->kl.part_ml);
   a.part_o = (float *)(h->scratch + h->kl.part_o);
+  a.spill = (float *)(h->scratch + h->kl.spill);
   a.arrive = (unsigned *)(h->scratch + h->kl.arrive) + (size_t)layer * UPL * kAttendMaxSplits;
   if (++h->epoch[layer] == 0u) h->epoch[layer] = 1u;     // flags start at 0: skip it on wrap
   a.epoch = h->epoch[layer];
@@ -292,7 +296,8 @@ int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
   if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
   AttendPlan plan;
   int rc = plan_for_layer(h, layer, &plan);
-  return rc != CONF_KV_OK ? rc : plan.splits;
+  if (rc != CONF_KV_OK) return rc;
+  return plan.two_launch ? 1000 + plan.splits : plan.splits;
 }
 
 int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,

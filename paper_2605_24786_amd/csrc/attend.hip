@@ -394,12 +394,41 @@ __device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, fl
   }
 }
 
+// Arrival: every split owns one flag word and stores the launch's epoch into it; nobody does a
+// read-modify-write, so arrivals do not serialise at the memory side.  The first wavefront
+// polls all flags of the unit with one coherent load per round.  The wait is bounded; false
+// means it expired (counted as a device error).  Contains workgroup barriers.
+__device__ __forceinline__ bool arrive_and_wait(const CacheView &cv, const AttendLaunch &a,
+                                                const Slice &sl, int ns, int *s_ok) {
+  const int tid = threadIdx.x;
+  unsigned *flags = a.arrive + (size_t)sl.ul * a.max_splits;
+  if (tid == 0) __hip_atomic_store(&flags[sl.j], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid < kWave) {
+    int ok = 1, spins = 0;
+    for (;;) {
+      const bool here = tid >= ns || __hip_atomic_load(&flags[tid], __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+      if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
+      __builtin_amdgcn_s_sleep(1);
+      if (++spins > kSpinLimit) { ok = 0; break; }
+    }
+    if (!ok && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+    if (tid == 0) *s_ok = ok;
+  }
+  __syncthreads();
+  return *s_ok != 0;
+}
+
 // ---------------------------------------------------------------------------------------
 // Epilogue shared by both bodies.  On entry wm/wl/wo hold NP per-wavefront partials
 // (after a workgroup barrier): partial k is [G][D] floats at
 // wo + (k % kAttWaves) * WSTR + (k / kAttWaves) * G * D; stash holds the slice's raw scores.
+// kPhase 0: the whole epilogue in one kernel (merge, publish, wait for the unit's other splits,
+// gather, EMA, output).  kPhase 1: merge and publish only; kPhase 2: gather, EMA and output in a
+// later launch, which needs no wait (wm/wl are unused and wo is [ns][G][2] floats of LDS) --
+// the pair serves shapes whose splits cannot all be resident at once.
 // ---------------------------------------------------------------------------------------
-template <int D, int G, int NP, int WSTR>
+template <int D, int G, int NP, int WSTR, int kPhase = 0>
 __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const AttendLaunch &a,
                                                 const Slice &sl, int ns, int S, float *stash,
                                                 float *wm, float *wl, float *wo, float *gm,
@@ -409,9 +438,10 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   float *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
   float *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
   // the EMA values this thread will update: requested now, needed after the wait
-  constexpr int kPre = 4;
+  constexpr int kPre = kPhase == 0 ? 4 : 0;
+  const bool exchange = kPhase != 0 || ns > 1;       // partials go through device memory
   float *EMA = cv.ema + (size_t)sl.u * cv.cap;
-  float ema_old[kPre];
+  float ema_old[kPre + 1];
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
     const int t = tid + k * kAttThreads;
@@ -420,6 +450,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   }
   // workgroup merge of the per-wavefront partials; two channels per thread, one 8-byte
   // coherent store each
+  if (kPhase != 2)
   for (int idx = 2 * tid; idx < G * D; idx += 2 * kAttThreads) {
     const int h = idx / D;
     // branch-free, so that all LDS reads are in flight together; an empty partial (m = -inf)
@@ -445,7 +476,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       o1 = fmaf(live ? ok2[k].y : 0.f, f, o1);
       l = fmaf(live ? lk[k] : 0.f, f, l);
     }
-    if (ns == 1) {
+    if (!exchange) {
       // a unit with a single split is complete here: same arithmetic as the general merge
       // below (weight e^0 = 1), without the trip through device memory
       const double inv = 1.0 / (double)l;
@@ -468,33 +499,15 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const bool has_out = tid < per && oidx < G * D;
   float opre[kOutPre] = {};
   TS(19);
-  if (ns > 1) {
-    wait_stores_done();
-    __syncthreads();
-    TS(20);
-    // Arrival: every split owns one flag word and stores the launch's epoch into it; nobody
-    // does a read-modify-write, so arrivals do not serialise at the memory side.  The first
-    // wavefront polls all flags of the unit with one coherent load per round (bounded).
-    unsigned *flags = a.arrive + (size_t)sl.ul * a.max_splits;
-    if (tid == 0) __hip_atomic_store(&flags[sl.j], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid < kWave) {
-      int ok = 1;
-      if (ns > 1) {
-        int spins = 0;
-        for (;;) {
-          const bool here = tid >= ns || __hip_atomic_load(&flags[tid], __ATOMIC_RELAXED,
-                                                           __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
-          if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
-          __builtin_amdgcn_s_sleep(1);
-          if (++spins > kSpinLimit) { ok = 0; break; }
-        }
-        if (!ok && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
-      }
-      if (tid == 0) *s_ok = ok;
+  if (kPhase == 1) return;
+  if (exchange) {
+    if (kPhase == 0) {
+      wait_stores_done();
+      __syncthreads();
+      TS(20);
+      if (!arrive_and_wait(cv, a, sl, ns, s_ok)) return;
+      TS(21);
     }
-    __syncthreads();
-    TS(21);
-    if (!*s_ok) return;
 
     // ---- one round trip: all (m, l) partials of the unit -> LDS, and this split's share of
     // the unit's output partials -> registers ----
@@ -514,7 +527,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       gm[tid] = M;
       ginv[tid] = 1.0 / L;
     }
-  }  // ns > 1
+  }  // exchange
   __syncthreads();
   TS(22);
   // ---- mass + EMA of the slice ----
@@ -539,7 +552,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   }
   TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
-  if (ns > 1) {
+  if (exchange) {
     const int Hq = cv.Hkv * G;
     const int i1 = min(G * D, (sl.j + 1) * per);
     for (int idx = oidx; idx < i1; idx += kAttThreads) {
@@ -569,13 +582,16 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
 // ---------------------------------------------------------------------------------------
 // Kernel 1: vector-ALU body for every slot
 // ---------------------------------------------------------------------------------------
-template <int D, int G>
+// kSpill: the first launch of the two-launch form -- the slice's raw scores go to device
+// scratch instead of LDS and the kernel ends after publishing its partial.
+template <int D, int G, bool kSpill = false>
 __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
                                                              int S) {
   constexpr int NP = kAttWaves;
   extern __shared__ __align__(16) float smem[];
-  float *stash = smem;                          // [G][S] raw scores of the slice
-  float *wo = stash + (size_t)G * S;            // [NP][G][D] per-wave un-normalised output
+  float *stash = kSpill ? a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S
+                        : smem;                 // [G][S] raw scores of the slice
+  float *wo = smem + (kSpill ? 0 : (size_t)G * S);   // [NP][G][D] per-wave un-normalised output
   float *wm = wo + NP * G * D;                  // [NP][G] per-wave maximum
   float *wl = wm + NP * G;                      // [NP][G] per-wave normaliser
   float *gm = wl + NP * G;                      // [G] global maximum
@@ -593,7 +609,22 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   stream_fp16_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
   store_stream_partial<D, G>(st, threadIdx.x >> 6, wm, wl, wo + (threadIdx.x >> 6) * G * D);
   __syncthreads();
-  attend_epilogue<D, G, NP, G * D>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+  attend_epilogue<D, G, NP, G * D, kSpill ? 1 : 0>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+}
+
+// Second launch of the two-launch form: same grid; merges the published partials of the unit,
+// updates the EMA of its slice from the spilled scores and normalises its share of the output.
+template <int D, int G>
+__global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv, AttendLaunch a, int ns,
+                                                                    int S) {
+  extern __shared__ __align__(16) float smem[];
+  float *pml = smem;                            // [ns][G][2]
+  float *gm = pml + (size_t)ns * G * 2;         // [G]
+  double *ginv = (double *)(gm + G + (G & 1));  // [G]
+  __shared__ int s_ok;
+  const Slice sl = make_slice(cv, a, ns, S);
+  float *stash = a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S;
+  attend_epilogue<D, G, 1, 0, 2>(cv, a, sl, ns, S, stash, nullptr, nullptr, pml, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1041,6 +1072,17 @@ static AttendFn attend_fn_valu(int D, int G) {
   return nullptr;
 }
 
+static AttendFn attend_fn_spill(int D, int G, bool finish) {
+#define CONFKV_CASE(d, g) \
+  if (D == d && G == g) return finish ? (AttendFn)attend_finish_kernel<d, g> : (AttendFn)attend_kernel<d, g, true>;
+  CONFKV_CASE(64, 1) CONFKV_CASE(64, 2) CONFKV_CASE(64, 3) CONFKV_CASE(64, 4) CONFKV_CASE(64, 5)
+  CONFKV_CASE(64, 6) CONFKV_CASE(64, 7) CONFKV_CASE(64, 8)
+  CONFKV_CASE(128, 1) CONFKV_CASE(128, 2) CONFKV_CASE(128, 3) CONFKV_CASE(128, 4) CONFKV_CASE(128, 5)
+  CONFKV_CASE(128, 6) CONFKV_CASE(128, 7) CONFKV_CASE(128, 8)
+#undef CONFKV_CASE
+  return nullptr;
+}
+
 static AttendFn attend_fn_mfma(int D, int G) {
   if (D != 128) return nullptr;
   switch (G) {
@@ -1113,7 +1155,7 @@ static int attend_occupancy(AttendFn fn, size_t lds) {
 }
 
 bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
-                 AttendPlan *plan) {
+                 bool force_two_launch, AttendPlan *plan) {
   const DeviceLimits &lim = device_limits();
   if (!lim.ok || !attend_fn_valu(D, G)) return false;
   const bool mfma = wants_mfma(D, G, n16_ub < n_ub);
@@ -1134,7 +1176,8 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   want = std::max(1, std::min(want, kAttendMaxSplits));
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
   // splits shrink the LDS stash when a long unit does not fit otherwise)
-  for (int k = 0; k < kAttendMaxSplits; ++k) {
+  plan->two_launch = false;
+  for (int k = 0; k < kAttendMaxSplits && !force_two_launch; ++k) {
     const int ns = k < want ? want - k : k + 1;
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
     int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
@@ -1153,14 +1196,50 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
     plan->mfma = mfma;
     return true;
   }
-  return false;
+  // No single-kernel plan: the splits of a unit cannot all be resident (many long units), or
+  // the slice's scores do not fit LDS.  Two launches then: the first streams and publishes
+  // partials, keeping the raw scores in device scratch; the second merges and updates the EMA.
+  // Nothing waits inside a kernel, so any split count works.
+  {
+    // about four workgroups per CU, so that the last round of a grid that is not a multiple
+    // of the CU count is short
+    int ns = (4 * lim.cus + units_per_layer - 1) / units_per_layer;
+    ns = (int)std::min<long long>(ns, std::max<long long>(1, unit_bytes / (128 * 1024)));
+    if (forced_splits > 0) ns = want;
+    ns = std::max(1, std::min(ns, kAttendMaxSplits));
+    int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
+    S = (S + 255) / 256 * 256;
+    const size_t lds = attend_lds_bytes(D, G, 0, false);
+    if (lds > lim.max_lds) return false;
+    plan->splits = ns;
+    plan->stash_tokens = S;
+    plan->lds_bytes = lds;
+    plan->mfma = false;
+    plan->two_launch = true;
+    return true;
+  }
+}
+
+size_t attend_spill_floats(int units_per_layer, int G, int cap) {
+  // splits * S <= n + n16 + splits * (2 + 34 + 255) with n, n16 <= cap
+  return (size_t)units_per_layer * G * (2 * (size_t)cap + (size_t)kAttendMaxSplits * 291);
 }
 
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream) {
+  dim3 grid(plan.splits, cv.B * cv.Hkv);
+  if (plan.two_launch) {
+    AttendFn first = attend_fn_spill(cv.D, cv.G, false), second = attend_fn_spill(cv.D, cv.G, true);
+    if (!first || !second || !a.spill) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
+                       plan.stash_tokens);
+    const size_t lds2 = ((size_t)plan.splits * cv.G * 2 + cv.G + 2) * sizeof(float) + cv.G * sizeof(double);
+    hipLaunchKernelGGL(second, grid, dim3(kAttThreads), lds2, stream, cv, a, plan.splits,
+                       plan.stash_tokens);
+    return hipGetLastError();
+  }
   AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, cv.G) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
-  dim3 grid(plan.splits, cv.B * cv.Hkv);
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                      plan.stash_tokens);
   return hipGetLastError();

@@ -21,6 +21,7 @@ struct AttendPlan {
   int stash_tokens;  // score slots per workgroup held in LDS
   size_t lds_bytes;  // dynamic LDS per workgroup
   bool mfma;         // matrix-core body for the INT8 slots
+  bool two_launch;   // stream + publish, then merge + EMA in a second launch (scores in scratch)
 };
 struct AttendLaunch {
   int layer;
@@ -33,14 +34,16 @@ struct AttendLaunch {
   int max_splits;
   float sm_scale, ema_decay;
   int pos_new;
+  float *spill;            // [units per layer][splits][G][stash_tokens] raw scores (two-launch form)
   unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
 };
 constexpr int kAttendMaxSplits = 64;
 bool attend_supported(int D, int G);
+size_t attend_spill_floats(int units_per_layer, int G, int cap);   // scratch the two-launch form needs
 // Largest split count and LDS plan for a unit of at most n_ub tokens (after the append)
 // of which at most n16_ub are FP16.  Returns false when no plan fits the device.
 bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
-                 AttendPlan *plan);
+                 bool force_two_launch, AttendPlan *plan);
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream);
 

@@ -86,3 +86,25 @@ def test_needle_retention_full_size(lib):
     print(f"needles retained: {kept}/{len(slots) * wl.n_kv_heads}", flush=True)
     assert kept == len(slots) * wl.n_kv_heads
     ls.close()
+
+
+def test_many_long_units_take_the_two_launch_form(lib):
+    """A batch of long contexts: 320 units of 11 000 slots in one layer.  No single-kernel plan
+    exists (a unit's scores do not fit on chip in one split, and two splits of 320 units cannot
+    all be resident), so attention runs as two launches through the scratch buffer; results
+    follow the oracle like everywhere else."""
+    wl = workload(1).scaled(name="llama3_8b_b40_t11000", n_layers=1, batch=40, prefill=11000, steps=2,
+                            n_tight=(4096,), n_loose=(8192,))
+    print(f"long batch: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=3, units=3, threads=16)
+    splits = ls.kv.attend_splits(0)
+    print(f"  attend splits: {splits}", flush=True)
+    assert splits >= 1000
+    for t in range(wl.steps):
+        ls.step()
+        _invariants_all_units(ls, wl, t)
+        print(f"  step {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0
+    ls.close()

@@ -127,18 +127,22 @@ def test_prefill_quantiser_bit_exact(lib, torch_cuda, D, W, T0):
 
 # ------------------------------------------------------------------ attention + mass EMA
 
-def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0):
-    say(f"attend D={D} G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits}")
+def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_launch=False):
+    say(f"attend D={D} G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} two_launch={two_launch}")
     if splits:
         os.environ["CONF_KV_SPLITS"] = str(splits)
     else:
         os.environ.pop("CONF_KV_SPLITS", None)
+    if two_launch:
+        os.environ["CONF_KV_TWO_LAUNCH"] = "1"
     try:
         cap = ((T0 + 8 + 63) // 64) * 64
         kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
                  protected_window=4, n_tight=[cap - 2], n_loose=[cap - 1])
     finally:
         os.environ.pop("CONF_KV_SPLITS", None)
+        os.environ.pop("CONF_KV_TWO_LAUNCH", None)
+    assert (kv.attend_splits(0) >= 1000) == two_launch
     rng = np.random.default_rng(seed)
     K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
     V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
@@ -192,6 +196,15 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0):
 ])
 def test_attend_matches_oracle(lib, torch_cuda, D, G, H, B, T0, W, splits):
     _attend_case(lib, torch_cuda, D, G, H, B, T0, W, splits, seed=D + G + T0)
+
+
+@pytest.mark.parametrize("D,G,H,B,T0,W,splits", [
+    (128, 4, 2, 2, 700, 32, 3), (128, 4, 1, 1, 300, 16, 1), (64, 1, 3, 1, 333, -1, 4),
+    (128, 5, 2, 1, 1000, 64, 7), (64, 2, 2, 2, 150, 0, 2), (128, 8, 1, 1, 520, 200, 5)])
+def test_attend_two_launch_form(lib, torch_cuda, D, G, H, B, T0, W, splits):
+    """The form used when the splits of a unit cannot all be resident: scores and partials go
+    through scratch and a second kernel finishes.  Forced here on small shapes."""
+    _attend_case(lib, torch_cuda, D, G, H, B, T0, W, splits, seed=T0 + G, two_launch=True)
 
 
 def test_attend_sharp_softmax(lib, torch_cuda):
