@@ -17,7 +17,8 @@ of the cache, not arithmetic shortcuts.
 
 Readings of the paper taken here (each is listed again where it is used):
   * one importance value and one kept set per (layer, kv-head); the attention
-    mass of a token is the SUM over the query heads that share the kv-head;
+    mass of a token is the SUM over the query heads that share the kv-head
+    (the literal per-layer reading is the ``rank_scope = "layer"`` variant);
   * INT8 scales are per token and per kv-head (absmax over the channels);
   * the new token is appended before its own attention and counts toward the
     cache length and the protected window;
@@ -261,20 +262,25 @@ def append_token(u: UnitCache, k_new: np.ndarray, v_new: np.ndarray, pos_new: in
 
 
 def attend_unit(u: UnitCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, pos_new: int,
-                sm_scale: float, ema_decay: float) -> Tuple[np.ndarray, np.ndarray]:
+                sm_scale: float, ema_decay: float, mass_gain: Optional[float] = None
+                ) -> Tuple[np.ndarray, np.ndarray]:
     """One decode step's attention for one unit, with the EMA importance update.
 
     Appends the new token, attends the G query heads q [G, D] (fp16 values) over all
     stored slots, forms the per-token mass A_i = sum over the G heads of p_{h,i}
     (so sum_i A_i = G), and updates a_i <- lambda a_i + (1 - lambda) A_i for every
     slot including the new one ("Budget and ranker"; Algorithm 1, EMA line).
+    ``mass_gain`` replaces the factor (1 - lambda); (lambda, gain) = (1, 1) is the plain
+    running sum of the mass that the cumulative-attention baselines of the experimental
+    setup rank by.
     Returns (out [G, D] float64, A [n] float64).
     """
     append_token(u, k_new, v_new, pos_new)
     out, p = attention_naive(np.asarray(q).astype(F64), u.stored_k(), u.stored_v(), sm_scale)
     A = np.sum(p, axis=0)
     lam = F64(ema_decay)
-    u.ema = (lam * u.ema.astype(F64) + (1.0 - lam) * A).astype(np.float32)
+    gain = (1.0 - lam) if mass_gain is None else F64(mass_gain)
+    u.ema = (lam * u.ema.astype(F64) + gain * A).astype(np.float32)
     return out, A
 
 
@@ -298,13 +304,51 @@ def rank_scores(ema: np.ndarray, pos: np.ndarray, alpha: float) -> np.ndarray:
     return al * a_hat + (1.0 - al) * r_hat
 
 
-def select_evictions(u: UnitCache, budget: int, protected: int, alpha: float
-                     ) -> Tuple[np.ndarray, np.ndarray]:
+_M64 = (1 << 64) - 1
+
+
+def splitmix64(x: int) -> int:
+    """One output of the SplitMix64 generator (Steele, Lea, Flood 2014) for state x."""
+    z = (x + 0x9E3779B97F4A7C15) & _M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    return z ^ (z >> 31)
+
+
+def random_scores(seed: int, unit_key: int, pos: np.ndarray) -> np.ndarray:
+    """Scores of the random ranker (matched-rate isolation study: which token goes is drawn
+    at random while how many go stays the budget rule's).  A counter-based draw, so both
+    implementations get the same numbers: score = top 53 bits of
+    splitmix64(seed + unit_key * 2^32 + position) scaled to [0, 1)."""
+    out = np.empty(len(pos), dtype=F64)
+    for i, p in enumerate(np.asarray(pos).tolist()):
+        r = splitmix64((int(seed) + (int(unit_key) << 32) + int(p)) & _M64)
+        out[i] = (r >> 11) * 2.0 ** -53
+    return out
+
+
+def shared_importance(units: Sequence["UnitCache"]) -> np.ndarray:
+    """Layer-level importance of the paper's literal reading: the manager keeps one EMA of
+    the head-averaged attention per layer.  With the mass kept per kv-head group this is
+    the sum over the groups (the 1/heads factor drops out of the min-max normalisation),
+    accumulated in kv-head order in float64."""
+    acc = np.zeros(units[0].n, dtype=F64)
+    for u in units:
+        assert u.n == units[0].n and np.array_equal(u.pos, units[0].pos)
+        acc = acc + u.ema.astype(F64)
+    return acc
+
+
+def select_evictions(u: UnitCache, budget: int, protected: int, alpha: float,
+                     importance: Optional[np.ndarray] = None, ranker: str = "composite",
+                     seed: int = 0, unit_key: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Slots to keep and to evict so that the length is at most the budget.
 
     If n <= N nothing happens.  Otherwise the newest P_eff = min(P, n) slots are
     protected, the other n - P_eff are candidates ranked by ``rank_scores``, and the
     e = min(n - N, n - P_eff) lowest are evicted; equal scores go oldest first.
+    ``importance`` [n] replaces the unit's own EMA (layer-shared ranking);
+    ``ranker`` = "random" ranks by ``random_scores`` instead.
     Returns (keep slots increasing, evicted slots increasing).
     """
     n = u.n
@@ -315,7 +359,11 @@ def select_evictions(u: UnitCache, budget: int, protected: int, alpha: float
     e = min(n - budget, n_cand)
     if e <= 0:
         return np.arange(n), np.zeros(0, dtype=np.int64)
-    s = rank_scores(u.ema[:n_cand], u.pos[:n_cand], alpha)
+    if ranker == "random":
+        s = random_scores(seed, unit_key, u.pos[:n_cand])
+    else:
+        a = u.ema if importance is None else importance
+        s = rank_scores(a[:n_cand], u.pos[:n_cand], alpha)
     order = np.lexsort((u.pos[:n_cand], s))        # by score, then older first
     evict = np.sort(order[:e])
     keep = np.setdiff1d(np.arange(n), evict)
@@ -338,13 +386,14 @@ def demote(u: UnitCache, fp16_window: int) -> int:
     return done
 
 
-def evict_compact_unit(u: UnitCache, budget: int, protected: int, alpha: float, fp16_window: int
-                       ) -> np.ndarray:
+def evict_compact_unit(u: UnitCache, budget: int, protected: int, alpha: float, fp16_window: int,
+                       **ranking) -> np.ndarray:
     """Algorithm 1's per-layer tail for one unit: rank, evict, compact, then demote.
 
+    ``ranking`` goes to ``select_evictions`` (importance, ranker, seed, unit_key).
     Returns the original positions that were evicted.
     """
-    keep, evict = select_evictions(u, budget, protected, alpha)
+    keep, evict = select_evictions(u, budget, protected, alpha, **ranking)
     gone = u.pos[evict].copy()
     if evict.size:
         u.take(keep)
@@ -369,6 +418,12 @@ class Policy:
     sm_scale: float = 1.0
     weights: Tuple[float, float, float] = (float(np.float32(0.4)), float(np.float32(0.3)),
                                            float(np.float32(0.3)))
+    mass_gain: Optional[float] = None      # None: 1 - ema_decay
+    ranker: str = "composite"              # or "random"
+    rank_scope: str = "kv_head"            # or "layer": one kept set per (layer, sequence)
+    ranker_seed: int = 0
+    batch: int = 1                         # needed for the random ranker's unit keys
+    n_kv_heads: int = 1
 
 
 class OracleRun:
@@ -392,7 +447,7 @@ class OracleRun:
             if l != layer:
                 continue
             out, _ = attend_unit(u, q[b, g * group:(g + 1) * group], k_new[b, g], v_new[b, g],
-                                 self.next_pos, p.sm_scale, p.ema_decay)
+                                 self.next_pos, p.sm_scale, p.ema_decay, p.mass_gain)
             outs[(l, b, g)] = out
         return outs
 
@@ -406,8 +461,23 @@ class OracleRun:
     def evict_compact(self, tight: np.ndarray) -> Dict[Tuple[int, int, int], np.ndarray]:
         p = self.policy
         gone = {}
-        for (l, b, g), u in self.units.items():
-            N = p.n_tight[l] if tight[b] else p.n_loose[l]
-            gone[(l, b, g)] = evict_compact_unit(u, N, p.protected, p.alpha, p.fp16_window)
+        if p.rank_scope == "layer":
+            # one ranking per (layer, sequence) from the importance shared by its kv-heads;
+            # every kv-head of a followed (layer, sequence) must be followed
+            for (l, b) in sorted({(l, b) for (l, b, _) in self.units}):
+                group = [self.units[(l, b, g)] for g in range(p.n_kv_heads)]
+                N = p.n_tight[l] if tight[b] else p.n_loose[l]
+                shared = shared_importance(group)
+                key = (1 << 40) + l * p.batch + b
+                for g, u in enumerate(group):
+                    gone[(l, b, g)] = evict_compact_unit(u, N, p.protected, p.alpha, p.fp16_window,
+                                                         importance=shared, ranker=p.ranker,
+                                                         seed=p.ranker_seed, unit_key=key)
+        else:
+            for (l, b, g), u in self.units.items():
+                N = p.n_tight[l] if tight[b] else p.n_loose[l]
+                key = (l * p.batch + b) * p.n_kv_heads + g
+                gone[(l, b, g)] = evict_compact_unit(u, N, p.protected, p.alpha, p.fp16_window,
+                                                     ranker=p.ranker, seed=p.ranker_seed, unit_key=key)
         self.next_pos += 1
         return gone

@@ -1,0 +1,121 @@
+"""Pins for the oracle's ranking variants: cumulative mass instead of the EMA, the random
+ranker of the matched-rate isolation study, and the layer-shared kept set of the paper's
+literal reading ("Cache manager": one metadata record per layer; "Budget and ranker":
+head-averaged attention; experimental setup: cumulative-attention and random baselines).
+"""
+import numpy as np
+import pytest
+
+from oracle import confkv_oracle as O
+
+
+def _unit(rng, n, D=8, W=-1, ema=None):
+    return O.load_prefill(rng.standard_normal((n, D)).astype(np.float16),
+                          rng.standard_normal((n, D)).astype(np.float16), W, ema0=ema)
+
+
+def test_splitmix64_published_vector():
+    # first five outputs for the seed 1234567 of the reference implementation
+    want = [6457827717110365317, 3203168211198807973, 9817491932198370423,
+            4593380528125082431, 16408922859458223821]
+    x, got = 1234567, []
+    for _ in range(5):
+        got.append(O.splitmix64(x))
+        x = (x + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+    assert got == want
+
+
+def test_random_scores_are_a_counter_based_uniform_draw():
+    pos = np.arange(20000)
+    s = O.random_scores(7, 3, pos)
+    assert np.all((s >= 0) & (s < 1)) and np.unique(s).size == s.size
+    assert abs(s.mean() - 0.5) < 0.01 and abs(s.var() - 1 / 12) < 0.005
+    hist = np.histogram(s, bins=20, range=(0, 1))[0]
+    assert np.all(np.abs(hist - 1000) < 150)                 # ~4.9 sigma of a binomial(20000, 1/20)
+    assert abs(np.corrcoef(s[:-1], s[1:])[0, 1]) < 0.03      # neighbours are independent
+    # a function of (seed, unit, position) only: any order, any subset
+    assert np.array_equal(O.random_scores(7, 3, pos[::-1])[::-1], s)
+    assert np.array_equal(O.random_scores(7, 3, pos[5:9]), s[5:9])
+    assert not np.array_equal(O.random_scores(8, 3, pos[:50]), s[:50])
+    assert not np.array_equal(O.random_scores(7, 4, pos[:50]), s[:50])
+    # the score is the generator's top 53 bits
+    r = O.splitmix64((7 + (3 << 32) + 11) & ((1 << 64) - 1))
+    assert s[11] == (r >> 11) / 2.0 ** 53
+
+
+def test_random_ranker_keeps_the_rate_and_the_window():
+    rng = np.random.default_rng(1)
+    n, N, P = 300, 120, 25
+    u = _unit(rng, n, ema=rng.random(n).astype(np.float32))
+    keep_c, ev_c = O.select_evictions(u, N, P, 0.65)
+    keep_r, ev_r = O.select_evictions(u, N, P, 0.65, ranker="random", seed=5, unit_key=9)
+    assert ev_r.size == ev_c.size == n - N                       # same rate as the composite ranker
+    assert np.all(ev_r < n - P) and keep_r.size == N             # the window is never touched
+    assert not np.array_equal(ev_r, ev_c)
+    # brute force: the e lowest draws among the candidates
+    s = O.random_scores(5, 9, u.pos[:n - P])
+    assert np.array_equal(ev_r, np.sort(np.argsort(s, kind="stable")[:n - N]))
+    # which token goes does not depend on the mass
+    u2 = _unit(rng, n, ema=rng.random(n).astype(np.float32))
+    assert np.array_equal(O.select_evictions(u2, N, P, 0.65, ranker="random", seed=5, unit_key=9)[1], ev_r)
+    # evictions spread evenly over the candidates: old and new halves lose about the same
+    older = np.count_nonzero(ev_r < (n - P) // 2)
+    assert abs(older - ev_r.size / 2) < 4 * np.sqrt(ev_r.size) / 2
+
+
+def test_cumulative_mass_is_the_running_sum():
+    rng = np.random.default_rng(2)
+    D, G, T0 = 16, 3, 20
+    a = _unit(rng, T0, D=D)
+    b = a.copy()
+    c = a.copy()
+    total = np.zeros(T0, dtype=np.float64)
+    for t in range(6):
+        q = rng.standard_normal((G, D)).astype(np.float16)
+        k, v = rng.standard_normal(D).astype(np.float16), rng.standard_normal(D).astype(np.float16)
+        _, A = O.attend_unit(a, q, k, v, T0 + t, 0.25, 1.0, mass_gain=1.0)
+        total = np.append(total, 0.0) + A
+        O.attend_unit(b, q, k, v, T0 + t, 0.25, np.float32(0.9))
+        O.attend_unit(c, q, k, v, T0 + t, 0.25, np.float32(0.9), mass_gain=1.0 - np.float64(np.float32(0.9)))
+        assert abs(A.sum() - G) < 1e-12
+    assert np.allclose(a.ema, total, rtol=1e-6, atol=0)          # fp32 storage rounds each step
+    assert abs(a.ema.sum() - 6 * G) < 1e-4
+    assert np.array_equal(b.ema, c.ema)                          # the default gain is 1 - decay
+
+
+def test_shared_importance_and_layer_scope():
+    rng = np.random.default_rng(3)
+    n, H = 90, 4
+    units = [_unit(rng, n, ema=rng.random(n).astype(np.float32)) for _ in range(H)]
+    sh = O.shared_importance(units)
+    ref = np.zeros(n)
+    for i in range(n):
+        for u in units:
+            ref[i] += float(u.ema[i])
+    assert np.array_equal(sh, ref)
+    pol = O.Policy(n_layers=1, n_tight=[40], n_loose=[60], protected=10, fp16_window=-1,
+                   rank_scope="layer", batch=1, n_kv_heads=H)
+    run = O.OracleRun(pol, {(0, 0, g): units[g] for g in range(H)}, n)
+    before = [u.copy() for u in units]
+    gone = run.evict_compact(np.array([True]))
+    # one kept set for the layer: every kv-head lost the same positions
+    for g in range(1, H):
+        assert np.array_equal(gone[(0, 0, g)], gone[(0, 0, 0)])
+        assert np.array_equal(units[g].pos, units[0].pos)
+    assert units[0].n == 40 and np.array_equal(units[0].pos[-10:], np.arange(n - 10, n))
+    # it is the plain ranking of the summed importance
+    probe = before[0].copy()
+    probe.ema = sh.astype(np.float64)
+    keep, ev = O.select_evictions(before[0], 40, 10, pol.alpha, importance=sh)
+    s = O.rank_scores(sh[:n - 10], before[0].pos[:n - 10], pol.alpha)
+    assert np.array_equal(ev, np.sort(np.lexsort((before[0].pos[:n - 10], s))[:n - 40]))
+    assert np.array_equal(before[0].pos[ev], gone[(0, 0, 0)])
+    # and differs from what a kv-head would have chosen alone
+    own = [O.select_evictions(before[g], 40, 10, pol.alpha)[1] for g in range(H)]
+    assert any(not np.array_equal(o, ev) for o in own)
+    # with a single kv-head the two scopes coincide
+    u1, u2 = before[1].copy(), before[1].copy()
+    r1 = O.OracleRun(O.Policy(1, [40], [60], 10, -1), {(0, 0, 0): u1}, n)
+    r2 = O.OracleRun(O.Policy(1, [40], [60], 10, -1, rank_scope="layer"), {(0, 0, 0): u2}, n)
+    r1.evict_compact(np.array([True])); r2.evict_compact(np.array([True]))
+    assert np.array_equal(u1.pos, u2.pos)
