@@ -70,7 +70,32 @@ typedef struct conf_kv_config {
   float w_entropy, w_margin, w_top; /* Eq. 1 weights (paper: 0.4, 0.3, 0.3)                    */
   const int32_t *n_tight;    /* host [L]: N_high per layer (budget on confident steps)         */
   const int32_t *n_loose;    /* host [L]: N_low  per layer; n_tight[l] <= n_loose[l]           */
+  /* Variants of the ranker (the paper's experimental setup and its literal per-layer
+   * bookkeeping).  All zeros except mass_gain < 0 give the method as described above. */
+  float mass_gain;           /* weight of a step's mass: a <- ema_decay a + mass_gain A;
+                                negative = 1 - ema_decay (the paper's EMA); (ema_decay,
+                                mass_gain) = (1, 1) is the running sum of the mass         */
+  int32_t ranker;            /* conf_kv_ranker                                                 */
+  int32_t rank_scope;        /* conf_kv_rank_scope                                             */
+  uint64_t ranker_seed;      /* CONF_KV_RANKER_RANDOM: seed of its counter-based draws         */
 } conf_kv_config;
+
+typedef enum conf_kv_ranker {
+  CONF_KV_RANKER_COMPOSITE = 0, /* s = alpha * minmax(mass) + (1 - alpha) * minmax(position)  */
+  CONF_KV_RANKER_RANDOM = 1     /* s = top 53 bits of splitmix64(seed + unit * 2^32 + position)
+                                   as a fraction: which token goes is random, how many go is
+                                   still the budget rule's (matched-rate isolation); unit =
+                                   (layer * B + b) * Hkv + kv_head, or 2^40 + layer * B + b in
+                                   layer scope                                                 */
+} conf_kv_ranker;
+
+typedef enum conf_kv_rank_scope {
+  CONF_KV_SCOPE_KV_HEAD = 0,    /* one importance value and one kept set per (layer, kv-head)  */
+  CONF_KV_SCOPE_LAYER = 1       /* one kept set per (layer, sequence): the importance of a
+                                   token is its mass summed over the kv-heads (the head
+                                   average up to a factor that min-max removes); every kv-head
+                                   of a sequence must hold the same positions                  */
+} conf_kv_rank_scope;
 
 typedef struct conf_kv_stats {
   uint64_t evicted;          /* tokens evicted, summed over units                              */
@@ -92,6 +117,13 @@ size_t conf_kv_scratch_bytes(const conf_kv_config *cfg);
  * loose one.  All units start empty.  On error *out is NULL. */
 int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_state,
                    void *dev_scratch);
+
+/* Pyramidal per-layer budgets ("Layer-wise pyramidal extension": N(l) = max(N_min,
+ * N(0) * beta^(l / L))), floored to integers, for filling n_tight / n_loose: host_out int32
+ * [n_layers].  The paper uses beta = 0.5 and N_min = 96.  Pure host arithmetic in double;
+ * CONF_KV_ERR_INVALID_ARG on n_layers < 1, n0 < 1, n_min < 1 or beta outside (0, 1]. */
+int conf_kv_pyramid_budgets(int32_t n0, int32_t n_layers, double beta, int32_t n_min,
+                            int32_t *host_out);
 
 /* Frees the host-side handle only (device buffers belong to the caller). */
 int conf_kv_destroy(conf_kv_handle *h);

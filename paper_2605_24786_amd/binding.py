@@ -30,7 +30,13 @@ class ConfKVConfig(C.Structure):
         ("tau", C.c_float), ("alpha", C.c_float), ("ema_decay", C.c_float), ("sm_scale", C.c_float),
         ("w_entropy", C.c_float), ("w_margin", C.c_float), ("w_top", C.c_float),
         ("n_tight", C.POINTER(C.c_int32)), ("n_loose", C.POINTER(C.c_int32)),
+        ("mass_gain", C.c_float), ("ranker", C.c_int32), ("rank_scope", C.c_int32),
+        ("ranker_seed", C.c_uint64),
     ]
+
+
+RANKERS = {"composite": 0, "random": 1}
+RANK_SCOPES = {"kv_head": 0, "layer": 1}
 
 
 class ConfKVStats(C.Structure):
@@ -57,6 +63,7 @@ SYMBOLS = {
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
     "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
     "conf_kv_export": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32] + [_P] * 10),
+    "conf_kv_pyramid_budgets": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_int32, _P]),
     "conf_kv_import": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [_P] * 9),
     "conf_kv_counters": (C.c_int, [_P, C.POINTER(ConfKVStats)]),
     "conf_kv_attend_splits": (C.c_int, [_P, C.c_int32]),
@@ -89,7 +96,8 @@ def strerror(status: int) -> str:
 
 def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacity, fp16_window,
                 protected_window, n_tight: Sequence[int], n_loose: Sequence[int], tau=0.7, alpha=0.65,
-                ema_decay=0.9, sm_scale=None, w_entropy=0.4, w_margin=0.3, w_top=0.3):
+                ema_decay=0.9, sm_scale=None, w_entropy=0.4, w_margin=0.3, w_top=0.3, mass_gain=None,
+                ranker="composite", rank_scope="kv_head", ranker_seed=0):
     """A ConfKVConfig plus the two int32 arrays it points to (keep the tuple alive)."""
     nt = (C.c_int32 * len(n_tight))(*[int(x) for x in n_tight])
     nl = (C.c_int32 * len(n_loose))(*[int(x) for x in n_loose])
@@ -97,8 +105,19 @@ def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacit
         sm_scale = 1.0 / float(np.sqrt(head_dim))
     cfg = ConfKVConfig(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacity,
                        fp16_window, protected_window, tau, alpha, ema_decay, sm_scale,
-                       w_entropy, w_margin, w_top, nt, nl)
+                       w_entropy, w_margin, w_top, nt, nl,
+                       -1.0 if mass_gain is None else float(mass_gain), RANKERS[ranker],
+                       RANK_SCOPES[rank_scope], int(ranker_seed))
     return cfg, nt, nl
+
+
+def pyramid_budgets(n0: int, n_layers: int, beta: float = 0.5, n_min: int = 96):
+    """Per-layer budgets of the pyramidal extension (host arithmetic in the library)."""
+    out = (C.c_int32 * n_layers)()
+    rc = load_library().conf_kv_pyramid_budgets(n0, n_layers, beta, n_min, out)
+    if rc != OK:
+        raise ConfKVError(rc, "conf_kv_pyramid_budgets")
+    return list(out)
 
 
 def _ptr(t) -> Optional[int]:
@@ -220,6 +239,8 @@ def from_workload(wl, **override) -> ConfKV:
               head_dim=wl.head_dim, vocab=wl.vocab, capacity=wl.capacity, fp16_window=wl.fp16_window,
               protected_window=wl.protected, n_tight=wl.n_tight, n_loose=wl.n_loose, tau=wl.tau,
               alpha=wl.alpha, ema_decay=wl.ema_decay, w_entropy=wl.w_entropy, w_margin=wl.w_margin,
-              w_top=wl.w_top)
+              w_top=wl.w_top, mass_gain=getattr(wl, "mass_gain", None),
+              ranker=getattr(wl, "ranker", "composite"), rank_scope=getattr(wl, "rank_scope", "kv_head"),
+              ranker_seed=getattr(wl, "ranker_seed", 0))
     kw.update(override)
     return ConfKV(**kw)

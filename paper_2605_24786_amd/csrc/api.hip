@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/conf_kv.h: argument validation, the layout of
 // the caller's device buffers, per-layer host bookkeeping (upper bounds of the lengths,
 // next position, pending appends, arrival-counter bases) and kernel launches.
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -26,7 +27,7 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-  size_t conf_partial, conf_arrive, arrive, part_ml, part_o, spill, score, src, sel, total;
+  size_t conf_partial, conf_arrive, arrive, part_ml, part_o, spill, score, src, sel, shared, total;
   size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
 };
 
@@ -41,6 +42,9 @@ bool config_ok(const conf_kv_config *c) {
   if (!(c->alpha >= 0.f && c->alpha <= 1.f)) return false;
   if (!(c->ema_decay >= 0.f && c->ema_decay <= 1.f)) return false;
   if (!(c->sm_scale > 0.f)) return false;
+  if (!(c->mass_gain < 0.f) && !(c->mass_gain >= 0.f && c->mass_gain <= 1.0e6f)) return false;   // NaN
+  if (c->ranker != CONF_KV_RANKER_COMPOSITE && c->ranker != CONF_KV_RANKER_RANDOM) return false;
+  if (c->rank_scope != CONF_KV_SCOPE_KV_HEAD && c->rank_scope != CONF_KV_SCOPE_LAYER) return false;
   for (int l = 0; l < c->n_layers; ++l) {
     if (c->n_tight[l] < 1 || c->n_tight[l] > c->n_loose[l]) return false;
     if (std::max(c->n_loose[l], c->protected_window) + 1 > c->capacity) return false;
@@ -101,6 +105,7 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   s.score = take(U * c->capacity * 8);
   s.src = take(U * c->capacity * 4);
   s.sel = take(U * kSelInts * 4);
+  s.shared = take(c->rank_scope == CONF_KV_SCOPE_LAYER ? (size_t)c->n_layers * c->batch * c->capacity * 8 : 0);
   s.total = off;
   return s;
 }
@@ -221,6 +226,17 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   return CONF_KV_OK;
 }
 
+int conf_kv_pyramid_budgets(int32_t n0, int32_t n_layers, double beta, int32_t n_min,
+                            int32_t *host_out) {
+  if (!host_out || n_layers < 1 || n0 < 1 || n_min < 1 || !(beta > 0.0 && beta <= 1.0))
+    return CONF_KV_ERR_INVALID_ARG;
+  for (int l = 0; l < n_layers; ++l) {
+    const double v = floor((double)n0 * pow(beta, (double)l / (double)n_layers));
+    host_out[l] = std::max<int32_t>(n_min, (int32_t)v);
+  }
+  return CONF_KV_OK;
+}
+
 int conf_kv_destroy(conf_kv_handle *h) {
   if (!h) return CONF_KV_ERR_INVALID_ARG;
   delete h;
@@ -279,6 +295,7 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
   a.max_splits = kAttendMaxSplits;
   a.sm_scale = h->cfg.sm_scale;
   a.ema_decay = h->cfg.ema_decay;
+  a.mass_gain = h->cfg.mass_gain < 0.f ? 1.0 - (double)h->cfg.ema_decay : (double)h->cfg.mass_gain;
   a.pos_new = h->next_pos[layer];
   a.dbg = nullptr;
 #ifdef CONFKV_TRACE
@@ -319,7 +336,11 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
     if (h->appended[l]) m.set(l);
     n_max = std::max(n_max, h->len_ub[l] + (int)h->appended[l]);
   }
-  CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, (double *)(h->scratch + h->kl.score),
+  RankOptions opt{};
+  opt.random = h->cfg.ranker == CONF_KV_RANKER_RANDOM;
+  opt.seed = h->cfg.ranker_seed;
+  opt.shared = h->cfg.rank_scope == CONF_KV_SCOPE_LAYER ? (double *)(h->scratch + h->kl.shared) : nullptr;
+  CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, opt, (double *)(h->scratch + h->kl.score),
                                  (int32_t *)(h->scratch + h->kl.src),
                                  (int32_t *)(h->scratch + h->kl.sel), n_max, (hipStream_t)stream));
   const int P = h->cfg.protected_window;

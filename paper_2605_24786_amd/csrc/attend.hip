@@ -531,7 +531,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   __syncthreads();
   TS(22);
   // ---- mass + EMA of the slice ----
-  const double lam = (double)a.ema_decay, oml = 1.0 - lam;
+  const double lam = (double)a.ema_decay, oml = a.mass_gain;
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
     const int t = tid + k * kAttThreads;

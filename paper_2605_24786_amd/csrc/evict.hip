@@ -186,16 +186,41 @@ __device__ __forceinline__ int block_scan_excl(int v, int *tmp, int *total) {
   return off + inc - v;
 }
 
+// SplitMix64 (Steele, Lea, Flood 2014): one output for state x.
+__device__ __forceinline__ unsigned long long splitmix64(unsigned long long x) {
+  unsigned long long z = x + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// Layer scope: shared[(layer, b)][slot] = sum over the kv-heads, in kv-head order, of the
+// unit's EMA as float64.  Grid (L * B, ceil(cap / 256)).
+__global__ __launch_bounds__(kEvThreads) void shared_mass_kernel(CacheView cv, LayerMask appended,
+                                                                 double *__restrict__ shared) {
+  const int lb = blockIdx.x, i = blockIdx.y * kEvThreads + threadIdx.x;
+  const int u0 = lb * cv.Hkv;
+  const int n = cv.len[u0] + (appended.get(lb / cv.B) ? 1 : 0);
+  if (i >= n) return;
+  double acc = 0.0;
+  for (int g = 0; g < cv.Hkv; ++g) acc = __dadd_rn(acc, (double)cv.ema[(size_t)(u0 + g) * cv.cap + i]);
+  shared[(size_t)lb * cv.cap + i] = acc;
+}
+
+// The general kernel also serves the ranker variants: importance shared by the kv-heads of a
+// (layer, sequence) -- every unit of the group then ranks the same numbers and reaches the same
+// kept set -- and the random ranker.  check_settled = 0 when rank_small_kernel has not run.
 template <int kRsThreads>
 __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, LayerMask appended,
-                                                                 double alpha,
+                                                                 double alpha, RankOptions opt,
+                                                                 int check_settled,
                                                                  double *__restrict__ score_all,
                                                                  int32_t *__restrict__ src_all,
                                                                  int32_t *__restrict__ sel_all) {
   constexpr int kRsWaves = kRsThreads / kWave;
   __shared__ int hist[256];
   __shared__ int s_tmp[kRsWaves];
-  __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
+  __shared__ double s_fmin[kRsWaves], s_fmax[kRsWaves];
   __shared__ unsigned long long s_prefix;
   __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves], s_last8[kRsWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -206,7 +231,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const int n8 = cv.n8[u];
   const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
-  if (sel[7] != 0) return;                            // settled by rank_small_kernel
+  if (check_settled && sel[7] != 0) return;           // settled by rank_small_kernel
   const int p_eff = min(cv.P, n);
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
@@ -219,30 +244,38 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   double *score = score_all + (size_t)u * cv.cap;
   int32_t *src = src_all + (size_t)u * cv.cap;
 
-  // min / max of the EMA over the candidates
-  float fmin_ = INFINITY, fmax_ = -INFINITY;
+  // importance of slot i: the unit's own EMA, or the sum shared by the (layer, sequence)
+  const double *shared = opt.shared ? opt.shared + (size_t)(u / cv.Hkv) * cv.cap : nullptr;
+  // min / max of the importance over the candidates (float -> double is exact and monotone)
+  double fmin_ = INFINITY, fmax_ = -INFINITY;
   for (int i = tid; i < ncand; i += kRsThreads) {
-    const float a = ema[i];
-    fmin_ = fminf(fmin_, a);
-    fmax_ = fmaxf(fmax_, a);
+    const double a = shared ? shared[i] : (double)ema[i];
+    fmin_ = fmin(fmin_, a);
+    fmax_ = fmax(fmax_, a);
   }
   fmin_ = wave_min(fmin_);
   fmax_ = wave_max(fmax_);
   if (lane == 0) { s_fmin[w] = fmin_; s_fmax[w] = fmax_; }
   if (tid == 0) { s_prefix = 0ull; s_krem = e; s_done = 0; }
   __syncthreads();
-  float lo_f = s_fmin[0], hi_f = s_fmax[0];
+  double a_lo = s_fmin[0], a_hi = s_fmax[0];
 #pragma unroll
-  for (int k = 1; k < kRsWaves; ++k) { lo_f = fminf(lo_f, s_fmin[k]); hi_f = fmaxf(hi_f, s_fmax[k]); }
-  const double a_lo = (double)lo_f, a_hi = (double)hi_f;
+  for (int k = 1; k < kRsWaves; ++k) { a_lo = fmin(a_lo, s_fmin[k]); a_hi = fmax(a_hi, s_fmax[k]); }
   const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
   const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
+  const unsigned long long unit_key = shared ? (1ull << 40) + (unsigned long long)(u / cv.Hkv) : (unsigned long long)u;
   for (int i = tid; i < ncand; i += kRsThreads) {
-    const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)ema[i], a_lo), a_div);
-    const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[i], p_lo), p_div);
-    score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
+    if (opt.random) {
+      const unsigned long long r = splitmix64(opt.seed + (unit_key << 32) + (unsigned long long)(long long)pos[i]);
+      score[i] = (double)(r >> 11) * 0x1.0p-53;     // exact: 53 bits, power-of-two scale
+    } else {
+      const double a = shared ? shared[i] : (double)ema[i];
+      const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn(a, a_lo), a_div);
+      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[i], p_lo), p_div);
+      score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
+    }
   }
   __syncthreads();                                  // orders the score writes before the reads
 
@@ -906,9 +939,17 @@ hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16
 }
 
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
-                                double *score, int32_t *src, int32_t *sel, int n_max,
-                                hipStream_t stream) {
+                                const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
+                                int n_max, hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
+  if (opt.random || opt.shared) {
+    // ranker variants: the general kernel only
+    if (opt.shared)
+      hipLaunchKernelGGL(shared_mass_kernel, dim3(cv.L * cv.B, (cv.cap + kEvThreads - 1) / kEvThreads),
+                         dim3(kEvThreads), 0, stream, cv, appended, opt.shared);
+    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
+                       0, score, src, sel);
+  } else {
   hipLaunchKernelGGL(rank_small_kernel, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
                      src, sel, U);
   // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
@@ -923,8 +964,9 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
     hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33>), dim3(U), dim3(1024), 0, stream, cv, appended,
                        alpha, src, sel);
   else
-    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha,
-                       score, src, sel);
+    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
+                       1, score, src, sel);
+  }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (cv.D == 64) {

@@ -33,6 +33,7 @@ struct AttendLaunch {
   unsigned epoch;          // value a split stores into its flag in this launch (never 0)
   int max_splits;
   float sm_scale, ema_decay;
+  double mass_gain;        // weight of the step's mass in the EMA update
   int pos_new;
   float *spill;            // [units per layer][splits][G][stash_tokens] raw scores (two-launch form)
   unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
@@ -56,8 +57,14 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
 constexpr int kSelInts = 8;
 hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
                                int T0, const float *ema0, hipStream_t stream);
+// Ranker variants; all zero = the composite ranker per (layer, kv-head).
+struct RankOptions {
+  int random;                  // 1: rank by counter-based uniform draws instead of the composite score
+  unsigned long long seed;
+  double *shared;              // non-null: layer scope; [L * B][cap] scratch for the summed mass
+};
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
-                                double *score, int32_t *src, int32_t *sel, int n_max /* longest unit */,
-                                hipStream_t stream);
+                                const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
+                                int n_max /* longest unit */, hipStream_t stream);
 
 }  // namespace confkv

@@ -37,6 +37,11 @@ class Workload:
     w_entropy: float = 0.4
     w_margin: float = 0.3
     w_top: float = 0.3
+    # ranker variants (configuration only; both implementations read them)
+    mass_gain: Optional[float] = None    # None: 1 - ema_decay
+    ranker: str = "composite"            # or "random"
+    rank_scope: str = "kv_head"          # or "layer"
+    ranker_seed: int = 0
     # input recipe
     heavy_hitter_prob: float = 0.02      # fraction of key positions shifted by +3 u
     heavy_hitter_gain: float = 3.0

@@ -34,7 +34,10 @@ def policy_of(wl) -> O.Policy:
     return O.Policy(wl.n_layers, list(wl.n_tight), list(wl.n_loose), wl.protected, wl.fp16_window,
                     tau=f32(wl.tau), alpha=f32(wl.alpha), ema_decay=f32(wl.ema_decay),
                     sm_scale=f32(1.0 / np.sqrt(wl.head_dim)),
-                    weights=(f32(wl.w_entropy), f32(wl.w_margin), f32(wl.w_top)))
+                    weights=(f32(wl.w_entropy), f32(wl.w_margin), f32(wl.w_top)),
+                    mass_gain=None if getattr(wl, "mass_gain", None) is None else f32(wl.mass_gain),
+                    ranker=getattr(wl, "ranker", "composite"), rank_scope=getattr(wl, "rank_scope", "kv_head"),
+                    ranker_seed=getattr(wl, "ranker_seed", 0), batch=wl.batch, n_kv_heads=wl.n_kv_heads)
 
 
 @dataclass

@@ -34,7 +34,7 @@ def test_config_struct_matches_header():
         decl = decl.strip()
         if not decl:
             continue
-        decl = re.sub(r"^(const\s+)?(int32_t|float)\s*\*?", "", decl)
+        decl = re.sub(r"^(const\s+)?(int32_t|uint64_t|float)\s*\*?", "", decl)
         names += [n.strip().lstrip("*") for n in decl.split(",")]
     assert names == [f[0] for f in pkg.ConfKVConfig._fields_]
 
@@ -60,12 +60,16 @@ def test_buffer_sizes(clib):
 @pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=18, n_kv_heads=2), dict(n_q_heads=7),
                                  dict(capacity=100), dict(capacity=128), dict(vocab=1), dict(alpha=1.5),
                                  dict(n_tight=[200, 64]), dict(protected_window=-1), dict(n_layers=0),
-                                 dict(ema_decay=-0.1)])
+                                 dict(ema_decay=-0.1), dict(mass_gain=float("nan")), dict(_ranker=2),
+                                 dict(_rank_scope=-1)])
 def test_bad_configs_are_rejected(clib, bad):
     kw = dict(bad)
     if "n_layers" in kw:
         kw.update(n_tight=[], n_loose=[])
+    raw = {k[1:]: kw.pop(k) for k in list(kw) if k.startswith("_")}    # enum fields set past the binding's names
     cfg, *_ = _cfg(**kw)
+    for k, v in raw.items():
+        setattr(cfg, k, v)
     assert clib.conf_kv_state_bytes(C.byref(cfg)) == 0
     h = C.c_void_p()
     assert clib.conf_kv_create(C.byref(h), C.byref(cfg), 256, 512) == pkg.binding.ERR_BAD_SHAPE
@@ -97,3 +101,15 @@ def test_no_cpu_fallback():
     with pytest.raises(RuntimeError, match="needs a GPU"):
         pkg.ConfKV(n_layers=1, batch=1, n_q_heads=1, n_kv_heads=1, head_dim=64, vocab=10, capacity=64,
                    fp16_window=-1, protected_window=2, n_tight=[8], n_loose=[16])
+
+
+def test_pyramid_budgets_match_the_oracle(clib):
+    """Host arithmetic, no GPU: the library's pyramidal schedule against the oracle's formula."""
+    from oracle import confkv_oracle as O
+    for n0, L, beta, n_min in [(256, 12, 0.5, 96), (128, 12, 0.5, 96), (4096, 64, 0.5, 96),
+                               (2048, 32, 0.5, 96), (1000, 7, 0.3, 10), (512, 1, 0.5, 96), (100, 4, 1.0, 96)]:
+        assert pkg.pyramid_budgets(n0, L, beta, n_min) == O.pyramid_geometric(n0, L, beta, n_min)
+    out = (C.c_int32 * 4)()
+    for bad in [(0, 4, 0.5, 96), (64, 0, 0.5, 96), (64, 4, 0.0, 96), (64, 4, 1.5, 96), (64, 4, 0.5, 0)]:
+        assert clib.conf_kv_pyramid_budgets(*bad, out) == pkg.binding.ERR_INVALID_ARG
+    assert clib.conf_kv_pyramid_budgets(64, 4, 0.5, 96, None) == pkg.binding.ERR_INVALID_ARG

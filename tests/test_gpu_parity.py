@@ -374,6 +374,60 @@ def test_lockstep_long_run_wraps_the_int8_ring(lib, torch_cuda, G, D, alpha):
     ls.close()
 
 
+@pytest.mark.parametrize("idx,variant", [
+    (1, dict(ema_decay=1.0, mass_gain=1.0)),                       # cumulative mass (H2O-shaped importance)
+    (4, dict(mass_gain=0.25)),
+    (1, dict(ranker="random", ranker_seed=12345)),                  # matched-rate random eviction
+    (0, dict(ranker="random", ranker_seed=(1 << 63) + 77)),
+    (1, dict(rank_scope="layer")),                                  # one kept set per (layer, sequence)
+    (4, dict(rank_scope="layer")),
+    (2, dict(rank_scope="layer", ranker="random", ranker_seed=3)),
+    (0, dict(rank_scope="layer", alpha=1.0)),
+])
+def test_lockstep_ranker_variants(lib, torch_cuda, idx, variant):
+    """The ranking variants against the oracle's: cumulative mass instead of the EMA, random
+    eviction at the budget rule's rate, and the paper's literal one-kept-set-per-layer reading."""
+    wl = small(idx).scaled(**variant)
+    if wl.steps < 12:
+        wl = wl.scaled(steps=12)
+    say(f"variant {variant} on workload {idx} (reduced), steps={wl.steps}")
+    ls = Lockstep(lib, wl, seed=20 + idx)
+    for t in range(wl.steps):
+        ls.step()
+        if variant.get("rank_scope") == "layer":
+            for (l, b, g), u in ls.run.units.items():              # kv-heads of a sequence stay aligned
+                assert np.array_equal(u.pos, ls.run.units[(l, b, 0)].pos)
+    rep = ls.report
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"ties={rep.evict_ties} flips={rep.evict_flips}/{rep.budget_flips}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.evictions > 0 and ls.kv.counters().device_errors == 0
+    if variant.get("mass_gain") == 1.0:
+        # the importance is the running sum: it adds up to G per step and unit, minus what left
+        ex = ls.kv.export(0, 0, 0)
+        assert ex["ema"].sum() <= wl.steps * wl.group + 1e-3 and ex["ema"].max() > 1.0
+    ls.close()
+
+
+def test_lockstep_geometric_pyramid(lib, torch_cuda):
+    """Per-layer budgets from the library's pyramidal schedule (beta = 0.5 as in the paper)."""
+    L = 4
+    tight = lib.pyramid_budgets(180, L, 0.5, 60)
+    assert tight == O.pyramid_geometric(180, L, 0.5, 60) and tight[0] == 180 and tight[-1] < tight[0]
+    wl = small(4).scaled(n_layers=L, n_tight=tuple(tight), n_loose=tuple(2 * n for n in tight), steps=24)
+    say(f"pyramid budgets {tight}")
+    ls = Lockstep(lib, wl, seed=8)
+    for t in range(wl.steps):
+        ls.step()
+    ln, _ = ls.kv.lengths()
+    sel = ls.sel.cpu().numpy().astype(bool)
+    for l in range(L):
+        for b in range(wl.batch):
+            assert ln[l, b] <= max(wl.protected, tight[l] if sel[b] else 2 * tight[l])
+    assert ls.report.ok() and ls.report.evictions > 0
+    ls.close()
+
+
 def test_import_round_trip_and_rejections(lib, torch_cuda):
     """conf_kv_import is the inverse of conf_kv_export: a handle rebuilt from the exported views of
     another (whose rings have moved) attends, evicts and demotes bit-identically; malformed views
