@@ -493,11 +493,16 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const float *mlu = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
   const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
   float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
-  constexpr int kOutPre = 8;                         // splits whose partial is prefetched
-  const int per = (G * D + ns - 1) / ns;             // output elements per split (<= 256 threads each
-  const int oidx = sl.j * per + tid;                 //  for ns >= G*D/256)
-  const bool has_out = tid < per && oidx < G * D;
-  float opre[kOutPre] = {};
+  // Output merge: this split normalises `per` elements of the unit's [G][D] output.  The ns
+  // partial values of one element sit in gs consecutive lanes (gs = ns rounded up to a power
+  // of two), so one load per thread fetches them in a single round trip whatever ns is, and a
+  // few lane shuffles add them up.
+  const int per = (G * D + ns - 1) / ns;
+  int gs = 1;
+  while (gs < ns) gs <<= 1;                          // <= 64: groups never straddle a wavefront
+  const int epp = kAttThreads / gs;                  // elements per pass over the workgroup
+  const int os = tid % gs, oe = tid / gs;            // this thread's split and element within a pass
+  float opre = 0.f;
   TS(19);
   if (kPhase == 1) return;
   if (exchange) {
@@ -511,21 +516,18 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
 
     // ---- one round trip: all (m, l) partials of the unit -> LDS, and this split's share of
     // the unit's output partials -> registers ----
-#pragma unroll
-    for (int k = 0; k < kOutPre; ++k)
-      opre[k] = (has_out && k < ns) ? ld_agent(&pou[(size_t)k * G * D + oidx]) : 0.f;
+    if (os < ns && oe < per && sl.j * per + oe < G * D)
+      opre = ld_agent(&pou[(size_t)os * G * D + sl.j * per + oe]);
     for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
     __syncthreads();
-    if (tid < G) {
-      float M = NEG;
-      for (int s = 0; s < ns; ++s) M = fmaxf(M, pml[(s * G + tid) * 2]);
-      double L = 0.0;
-      for (int s = 0; s < ns; ++s) {
-        const float ms = pml[(s * G + tid) * 2];
-        if (ms > NEG) L += exp((double)ms - (double)M) * (double)pml[(s * G + tid) * 2 + 1];
-      }
-      gm[tid] = M;
-      ginv[tid] = 1.0 / L;
+    // global (M, L) of head h by wavefront h: one lane per split
+    for (int h = tid >> 6; h < G; h += kAttWaves) {
+      const int sp = tid & 63;
+      const float ms = sp < ns ? pml[(sp * G + h) * 2] : NEG;
+      const float M = wave_max(ms);
+      const double term = ms > NEG ? exp((double)ms - (double)M) * (double)pml[(sp * G + h) * 2 + 1] : 0.0;
+      const double L = wave_sum(term);
+      if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; }
     }
   }  // exchange
   __syncthreads();
@@ -554,27 +556,17 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
   if (exchange) {
     const int Hq = cv.Hkv * G;
-    const int i1 = min(G * D, (sl.j + 1) * per);
-    for (int idx = oidx; idx < i1; idx += kAttThreads) {
-      const int h = idx / D;
-      const float M = gm[h];
-      float o = 0.f;
-      for (int s0 = 0; s0 < ns; s0 += 8) {
-        float v[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          if (s0 == 0 && idx == oidx && has_out) v[k] = opre[k];        // prefetched above
-          else v[k] = (s0 + k < ns) ? ld_agent(&pou[(size_t)(s0 + k) * G * D + idx]) : 0.f;
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          if (s0 + k < ns) {
-            const float ms = pml[((s0 + k) * G + h) * 2];
-            if (ms > NEG) o = fmaf(v[k], expf(ms - M), o);
-          }
-        }
-      }
-      a.out[((size_t)(sl.b * Hq + sl.g * G)) * D + idx] = __float2half_rn((float)((double)o * ginv[h]));
+    for (int base = 0; base < per; base += epp) {
+      const int e = sl.j * per + base + oe;                          // element of the [G][D] output
+      const bool valid = os < ns && base + oe < per && e < G * D;
+      float v = 0.f;
+      if (valid) v = base == 0 ? opre : ld_agent(&pou[(size_t)os * G * D + e]);
+      const int h = valid ? e / D : 0;
+      const float ms = valid ? pml[(os * G + h) * 2] : NEG;
+      float c = ms > NEG ? v * expf(ms - gm[h]) : 0.f;               // an empty partial weighs nothing
+      for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
+      if (valid && os == 0)
+        a.out[((size_t)(sl.b * Hq + sl.g * G)) * D + e] = __float2half_rn((float)((double)c * ginv[h]));
     }
   }
 }
