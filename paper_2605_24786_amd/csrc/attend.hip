@@ -1160,10 +1160,11 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   int want = lim.cus / units_per_layer;
   if (want < 1) want = 1;
   if (want == 1 && 2 * units_per_layer <= 2 * lim.cus && units_per_layer > lim.cus / 2) want = 2;
-  // a split below about 128 KB of cache costs more in the exchange than it saves in streaming
-  // (measured on 8- and 12-unit layers of 500 to 4096 slots)
+  // Measured on 8- and 12-unit layers of 500 to 32768 slots: a unit below about 192 KB is
+  // fastest on one workgroup (no exchange at all); above, splits down to about 32 KB each
+  // (one 32-slot tile per wavefront) still pay.
   const long long unit_bytes = (long long)(n_ub - n16_ub) * (2 * D + 4) + (long long)n16_ub * 4 * D;
-  want = std::min<long long>(want, std::max<long long>(1, unit_bytes / (128 * 1024)));
+  want = unit_bytes <= 192 * 1024 ? 1 : (int)std::min<long long>(want, unit_bytes / (32 * 1024));
   if (forced_splits > 0) want = std::min<long long>(forced_splits, std::max<long long>(1, nv / 128));
   want = std::max(1, std::min(want, kAttendMaxSplits));
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
@@ -1196,7 +1197,7 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
     // about four workgroups per CU, so that the last round of a grid that is not a multiple
     // of the CU count is short
     int ns = (4 * lim.cus + units_per_layer - 1) / units_per_layer;
-    ns = (int)std::min<long long>(ns, std::max<long long>(1, unit_bytes / (128 * 1024)));
+    ns = (int)std::min<long long>(ns, std::max<long long>(1, unit_bytes / (32 * 1024)));
     if (forced_splits > 0) ns = want;
     ns = std::max(1, std::min(ns, kAttendMaxSplits));
     int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
