@@ -74,9 +74,6 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 // by completion: a publisher waits for its stores to complete before the workgroup
 // barrier that precedes the arrival increment; a consumer only issues its loads after it
 // has observed the arrival count.
-__device__ __forceinline__ void st_agent(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 __device__ __forceinline__ void st_agent2(float *p, float v0, float v1) {   // p 8-byte aligned
   const unsigned long long bits =
       (unsigned long long)__float_as_uint(v0) | ((unsigned long long)__float_as_uint(v1) << 32);

@@ -494,6 +494,26 @@ def test_import_round_trip_and_rejections(lib, torch_cuda):
     a.close()
 
 
+@pytest.mark.parametrize("G,D,W", [(4, 128, 6), (1, 64, -1), (2, 128, 0)])
+def test_lockstep_from_empty_cache_to_full_capacity(lib, torch_cuda, G, D, W):
+    """Degenerate ends of the size range: decoding starts on an empty cache (the first query
+    sees only its own token), the FP16 window fills and the first demotions happen, and the
+    loose budget is capacity - 1, so every slot of the allocation, the last included, is used."""
+    wl = small(1).scaled(n_layers=1, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=D, vocab=2003,
+                         prefill=0, steps=150, n_tight=(40,), n_loose=(63,), protected=5, fp16_window=W,
+                         logit_std=(0.5, 6.0), logit_run=30)
+    assert wl.capacity == 64
+    say(f"empty -> full: G={G} D={D} W={W}")
+    ls = Lockstep(lib, wl, seed=31)
+    seen = set()
+    for t in range(wl.steps):
+        ls.step()
+        seen.add(ls.report.lengths[-1])
+    assert 1 in seen and 63 in seen and 40 in seen
+    assert ls.report.ok() and ls.report.evictions > 0 and ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 def test_call_order_and_capacity_errors(lib, torch_cuda):
     torch = torch_cuda
     kv = _mk(lib, capacity=64, n_tight=[32], n_loose=[60], protected_window=4)
