@@ -391,13 +391,22 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   CK_HIP(h, hipMemcpy(&n8, cv.n8 + u, 4, hipMemcpyDeviceToHost));
   CK_HIP(h, hipMemcpy(&head, cv.head16 + u, 4, hipMemcpyDeviceToHost));
   CK_HIP(h, hipMemcpy(&head8, cv.head8 + u, 4, hipMemcpyDeviceToHost));
-  const int first8 = std::min(n8, cv.cap8 - head8);   // INT8 ring rows before the wrap
+  const int first8 = std::max(0, std::min(n8, cv.cap8 - head8));   // INT8 ring rows before the wrap
   const int n = len + h->appended[layer];
   const int n16 = n - n8;
   if (n_out) *n_out = n;
   if (n == 0) return CONF_KV_OK;
-  if (pos) CK_HIP(h, hipMemcpy(pos, cv.pos + u * cv.cap, (size_t)n * 4, hipMemcpyDeviceToHost));
-  if (ema) CK_HIP(h, hipMemcpy(ema, cv.ema + u * cv.cap, (size_t)n * 4, hipMemcpyDeviceToHost));
+  const int firstm = std::min(n, cv.cap - head8);     // per-slot planes: entries before the wrap
+  if (pos) {
+    CK_HIP(h, hipMemcpy(pos, cv.pos + u * cv.cap + head8, (size_t)firstm * 4, hipMemcpyDeviceToHost));
+    if (n > firstm)
+      CK_HIP(h, hipMemcpy(pos + firstm, cv.pos + u * cv.cap, (size_t)(n - firstm) * 4, hipMemcpyDeviceToHost));
+  }
+  if (ema) {
+    CK_HIP(h, hipMemcpy(ema, cv.ema + u * cv.cap + head8, (size_t)firstm * 4, hipMemcpyDeviceToHost));
+    if (n > firstm)
+      CK_HIP(h, hipMemcpy(ema + firstm, cv.ema + u * cv.cap, (size_t)(n - firstm) * 4, hipMemcpyDeviceToHost));
+  }
   if (is_fp16)
     for (int i = 0; i < n; ++i) is_fp16[i] = i >= n8;
   for (int which = 0; which < 2; ++which) {

@@ -113,7 +113,7 @@ __device__ __forceinline__ void unpack_h16x16(const int4 &r0, const int4 &r1, fl
 struct Slice {
   int u, ul, b, g, j;          // unit, unit within the layer, batch, kv-head, split
   int n, n8, h16, n16;         // length with the append, INT8 slots, FP16 ring head, FP16 slots
-  int h8;                      // INT8 ring head
+  int h8;                      // head of the rings anchored at the oldest slot (EMA, position, INT8 rows)
   int lo8, hi8;                // INT8 slots of this split
   int lo16, hi16;              // FP16 slots of this split (slot numbers, >= n8)
   int cnt8, ntok;              // hi8 - lo8, and cnt8 + (hi16 - lo16)
@@ -166,7 +166,7 @@ __device__ __forceinline__ void append_new_token(const CacheView &cv, const Atte
   } else if (tid < D / 4) {
     ((int4 *)V16)[tid - D / 8] = ((const int4 *)(a.vnew + (size_t)s.ul * D))[tid - D / 8];
   }
-  if (tid == 0) cv.pos[(size_t)s.u * cv.cap + s.n - 1] = a.pos_new;
+  if (tid == 0) cv.pos[(size_t)s.u * cv.cap + ring_row_u(s.h8, s.n - 1, cv.cap)] = a.pos_new;
   __syncthreads();
 }
 
@@ -443,7 +443,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   for (int k = 0; k < kPre; ++k) {
     const int t = tid + k * kAttThreads;
     const int slot = sl.slot_of(min(t, sl.ntok - 1));
-    ema_old[k] = (t < sl.ntok && slot != sl.n - 1) ? EMA[slot] : 0.f;
+    ema_old[k] = (t < sl.ntok && slot != sl.n - 1) ? EMA[ring_row_u(sl.h8, slot, cv.cap)] : 0.f;
   }
   // workgroup merge of the per-wavefront partials; two channels per thread, one 8-byte
   // coherent store each
@@ -538,16 +538,17 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       double A = 0.0;
 #pragma unroll
       for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
-      EMA[sl.slot_of(t)] = (float)(lam * (double)ema_old[k] + oml * A);
+      EMA[ring_row_u(sl.h8, sl.slot_of(t), cv.cap)] = (float)(lam * (double)ema_old[k] + oml * A);
     }
   }
   for (int t = tid + kPre * kAttThreads; t < sl.ntok; t += kAttThreads) {
     const int slot = sl.slot_of(t);
-    const double old = (slot == sl.n - 1) ? 0.0 : (double)EMA[slot];
+    const int row = ring_row_u(sl.h8, slot, cv.cap);
+    const double old = (slot == sl.n - 1) ? 0.0 : (double)EMA[row];
     double A = 0.0;
 #pragma unroll
     for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
-    EMA[slot] = (float)(lam * old + oml * A);
+    EMA[row] = (float)(lam * old + oml * A);
   }
   TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----

@@ -21,9 +21,11 @@ enum StatSlot { kStatEvicted = 0, kStatDemoted = 1, kStatTight = 2, kStatLoose =
 //   ks, vs   fp16  [U][cap8]      per-token scales of those rows (same ring index)
 //   k16, v16 fp16  [U][cap16][D]  FP16 ring; slot i >= n8[u] lives in ring row
 //                                 (head16[u] + i - n8[u]) mod cap16
-//   ema      fp32  [U][cap]       EMA of attention mass, by slot
-//   pos      int32 [U][cap]       original position, by slot (strictly increasing)
-//   len, n8, head16, head8  int32 [U]  committed length, INT8 count, ring heads
+//   ema      fp32  [U][cap]       EMA of attention mass; slot i lives at (head8[u] + i) mod cap
+//   pos      int32 [U][cap]       original position (strictly increasing over the slots), same index
+//   len, n8, head16, head8  int32 [U]  committed length, INT8 count, ring heads.  head8 is the
+//                                 head of every ring anchored at the oldest slot: EMA, position
+//                                 and, in mixed caches (cap8 = cap), the INT8 rows and scales
 //   budget   int32 [L][B]         N selected by the last confidence step
 //   unit_evicted, unit_demoted  uint32 [U]  tokens evicted / demoted so far, per unit
 //   unit_moved  uint64 [U]        bytes read + written by compaction moves so far, per unit

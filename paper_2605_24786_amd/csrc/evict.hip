@@ -126,33 +126,43 @@ __device__ __forceinline__ double quotient(double n, const Divisor &dv) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Outcome of one unit's selection.  The INT8 rows are a ring, so the survivors can close the
-// holes from either side: rows behind the first hole shift left (head stays), or rows in
-// front of the last INT8 hole shift right (head advances by the INT8 evictions).  The side
-// with fewer rows to move is taken; in steady state the evicted slot is old, so the right
-// shift moves next to nothing.
+// Outcome of one unit's selection.  Every plane is a ring, so the survivors can close the
+// holes from either side: slots behind the first hole shift left (heads stay), or slots in
+// front of the last hole shift right (the head of the rings anchored at the oldest slot
+// advances by the number of evictions).  The side with fewer rows to move is taken; in steady
+// state the evicted slot is old, so the right shift moves next to nothing.  The right shift is
+// open when all holes lie in one payload ring: all INT8 in a mixed cache (the FP16 slots, newer
+// than every hole, then keep their rows), any in an FP16-only cache.
+// `last_hole` is the newest evicted slot of that ring (-1: none).
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void write_selection(const CacheView &cv, int u, int32_t *sel, int n_new,
                                                 int n8_old, int n8_new, int first_hole, int evicted,
-                                                int last_hole8) {
-  const int h8 = cv.head8[u];
+                                                int last_hole) {
+  const bool fp16_only = cv.cap8 == 0;
+  const int h0 = cv.head8[u];
   const int e8 = n8_old - n8_new;
-  const int left_rows = n8_new - min(first_hole, n8_new);
-  const int right_rows = last_hole8 + 1 - e8;        // INT8 survivors in front of the last INT8 hole
-  const int right = e8 > 0 && right_rows < left_rows;
+  const int span = fp16_only ? n_new : n8_new;       // survivors of the ring the holes lie in
+  const int left_rows = span - min(first_hole, span);
+  const int right_rows = last_hole + 1 - (fp16_only ? evicted : e8);   // survivors in front of the last hole
+  const int right = (fp16_only ? evicted > 0 : (e8 > 0 && evicted == e8)) && right_rows < left_rows;
   sel[0] = n_new;
   sel[1] = n8_new;
   sel[2] = first_hole;
   sel[3] = evicted;
-  sel[4] = last_hole8;
+  sel[4] = last_hole;
   sel[5] = right;
-  sel[6] = right ? ring_row(h8, e8, cv.cap8) : h8;
+  sel[6] = right ? ring_row(h0, fp16_only ? evicted : e8, cv.cap) : h0;
   sel[7] = 1;                                        // this unit's selection is final
   if (evicted > 0) {
     // traffic of the moves the compaction kernel will make (each row is read and written once)
-    const long long rows8 = right ? right_rows : left_rows;
-    const long long rows16 = (evicted > e8) ? n_new - max(first_hole, n8_new) : 0;
-    const long long meta = n_new - min(first_hole, n_new);
+    const long long meta = right ? right_rows : n_new - min(first_hole, n_new);
+    long long rows8 = 0, rows16 = 0;
+    if (fp16_only) {
+      rows16 = right ? right_rows : left_rows;
+    } else {
+      rows8 = right ? right_rows : left_rows;
+      rows16 = (evicted > e8) ? n_new - max(first_hole, n8_new) : 0;
+    }
     cv.unit_moved[u] += 2ull * (unsigned long long)(rows8 * (2 * cv.D + 4) + rows16 * 4 * cv.D + meta * 8);
   }
 }
@@ -203,7 +213,8 @@ __global__ __launch_bounds__(kEvThreads) void shared_mass_kernel(CacheView cv, L
   const int n = cv.len[u0] + (appended.get(lb / cv.B) ? 1 : 0);
   if (i >= n) return;
   double acc = 0.0;
-  for (int g = 0; g < cv.Hkv; ++g) acc = __dadd_rn(acc, (double)cv.ema[(size_t)(u0 + g) * cv.cap + i]);
+  for (int g = 0; g < cv.Hkv; ++g)
+    acc = __dadd_rn(acc, (double)cv.ema[(size_t)(u0 + g) * cv.cap + ring_row_u(cv.head8[u0 + g], i, cv.cap)]);
   shared[(size_t)lb * cv.cap + i] = acc;
 }
 
@@ -241,6 +252,8 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  const int hm = cv.head8[u], cap = cv.cap;          // slot i of the per-slot planes: ring_row_u(hm, i, cap)
+  const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   double *score = score_all + (size_t)u * cv.cap;
   int32_t *src = src_all + (size_t)u * cv.cap;
 
@@ -249,7 +262,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   // min / max of the importance over the candidates (float -> double is exact and monotone)
   double fmin_ = INFINITY, fmax_ = -INFINITY;
   for (int i = tid; i < ncand; i += kRsThreads) {
-    const double a = shared ? shared[i] : (double)ema[i];
+    const double a = shared ? shared[i] : (double)ema[ring_row_u(hm, i, cap)];
     fmin_ = fmin(fmin_, a);
     fmax_ = fmax(fmax_, a);
   }
@@ -261,19 +274,21 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   double a_lo = s_fmin[0], a_hi = s_fmax[0];
 #pragma unroll
   for (int k = 1; k < kRsWaves; ++k) { a_lo = fmin(a_lo, s_fmin[k]); a_hi = fmax(a_hi, s_fmax[k]); }
-  const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
+  // slots are position-sorted
+  const double p_lo = (double)pos[hm], p_hi = (double)pos[ring_row_u(hm, ncand - 1, cap)];
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
   const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
   const unsigned long long unit_key = shared ? (1ull << 40) + (unsigned long long)(u / cv.Hkv) : (unsigned long long)u;
   for (int i = tid; i < ncand; i += kRsThreads) {
     if (opt.random) {
-      const unsigned long long r = splitmix64(opt.seed + (unit_key << 32) + (unsigned long long)(long long)pos[i]);
+      const unsigned long long r =
+          splitmix64(opt.seed + (unit_key << 32) + (unsigned long long)(long long)pos[ring_row_u(hm, i, cap)]);
       score[i] = (double)(r >> 11) * 0x1.0p-53;     // exact: 53 bits, power-of-two scale
     } else {
-      const double a = shared ? shared[i] : (double)ema[i];
+      const double a = shared ? shared[i] : (double)ema[ring_row_u(hm, i, cap)];
       const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn(a, a_lo), a_div);
-      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[i], p_lo), p_div);
+      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[ring_row_u(hm, i, cap)], p_lo), p_div);
       score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
     }
   }
@@ -337,7 +352,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
     }
     if (evict) {
       hole = min(hole, i);
-      if (i < n8) last8 = max(last8, i);
+      if (i < nx) last8 = max(last8, i);
     }
   }
   kept8 = wave_sum(kept8);
@@ -398,6 +413,8 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  const int hm = cv.head8[u], cap = cv.cap;          // slot i of the per-slot planes: ring_row_u(hm, i, cap)
+  const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   int32_t *src = src_all + (size_t)u * cv.cap;
   const int Ed = (n + T - 1) / T;                   // rounds in use, <= E (checked by the host)
 
@@ -407,7 +424,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
 #pragma unroll
   for (int k = 0; k < E; ++k) {
     const int i = tid + k * T;
-    av[k] = (k < Ed && i < ncand) ? ema[i] : 0.f;
+    av[k] = (k < Ed && i < ncand) ? ema[ring_row_u(hm, i, cap)] : 0.f;
   }
 #pragma unroll
   for (int k = 0; k < E; ++k) {
@@ -422,7 +439,8 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
 #pragma unroll
   for (int k = 1; k < kRsWaves; ++k) { lo_f = fminf(lo_f, s_fmin[k]); hi_f = fmaxf(hi_f, s_fmax[k]); }
   const double a_lo = (double)lo_f, a_hi = (double)hi_f;
-  const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
+  // slots are position-sorted
+  const double p_lo = (double)pos[hm], p_hi = (double)pos[ring_row_u(hm, ncand - 1, cap)];
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
   const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
@@ -434,7 +452,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
     key[k] = 0ull;
     if (k < Ed && i < ncand) {
       const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)av[k], a_lo), a_div);
-      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[i], p_lo), p_div);
+      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[ring_row_u(hm, i, cap)], p_lo), p_div);
       key[k] = (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
       kmin = key[k] < kmin ? key[k] : kmin;
       kmax = key[k] > kmax ? key[k] : kmax;
@@ -562,7 +580,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
       kept8 += keep && i < n8;
       if (ev) {
         hole = min(hole, i);
-        if (i < n8) last8 = max(last8, i);
+        if (i < nx) last8 = max(last8, i);
       }
     }
   }
@@ -635,6 +653,8 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  const int hm = cv.head8[u], cap = cv.cap;          // slot i of the per-slot planes: ring_row_u(hm, i, cap)
+  const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   // loads go out in batches of kBatch (indices past the end re-read the last candidate), so a
   // long unit costs a few memory round trips per pass and not one per 64 slots
   constexpr int kBatch = 8;
@@ -642,7 +662,7 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   for (int base = 0; base < ncand; base += kBatch * kWave) {
     float a[kBatch];
 #pragma unroll
-    for (int r = 0; r < kBatch; ++r) a[r] = ema[min(base + r * kWave + lane, ncand - 1)];
+    for (int r = 0; r < kBatch; ++r) a[r] = ema[ring_row_u(hm, min(base + r * kWave + lane, ncand - 1), cap)];
 #pragma unroll
     for (int r = 0; r < kBatch; ++r) {
       fmin_ = fminf(fmin_, a[r]);
@@ -650,7 +670,8 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
     }
   }
   const double a_lo = (double)wave_min(fmin_), a_hi = (double)wave_max(fmax_);
-  const double p_lo = (double)pos[0], p_hi = (double)pos[ncand - 1];   // slots are position-sorted
+  // slots are position-sorted
+  const double p_lo = (double)pos[hm], p_hi = (double)pos[ring_row_u(hm, ncand - 1, cap)];
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
   const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
@@ -669,7 +690,7 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
         int ps[kBatch];
 #pragma unroll
         for (int r = 0; r < kBatch; ++r) {
-          const int i = min(base + r * kWave + lane, ncand - 1);
+          const int i = ring_row_u(hm, min(base + r * kWave + lane, ncand - 1), cap);
           a[r] = ema[i];
           ps[r] = pos[i];
         }
@@ -718,180 +739,120 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   if (lane == 0) {
     int gone8 = 0, last8 = -1;
 #pragma unroll
-    for (int q = 0; q < kSmallE; ++q)
-      if (ev[q] < n8) { ++gone8; last8 = ev[q]; }
+    for (int q = 0; q < kSmallE; ++q) {
+      if (ev[q] < n8) ++gone8;
+      if (ev[q] < nx) last8 = ev[q];                 // unused entries are INT_MAX
+    }
     write_selection(cv, u, sel, n_new, n8, n8 - gone8, ev[0], e, last8);
     cv.unit_evicted[u] += (unsigned)e;
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// compact: grid (U, 5 planes), 256 threads.  Destination slot j takes source slot src[j]
-// >= j.  Left shift: a workgroup walks its plane front to back in chunks (load a chunk into
-// registers, barrier, store); earlier chunks only wrote below the chunk start and later
-// sources all lie at or above it, so nothing is overwritten before it is read.  Right shift
-// of the INT8 ring (new head = old head + INT8 evictions): survivor j moves from ring offset
-// src[j] to offset e8 + j >= src[j]; the walk goes back to front, the mirror argument holds.
+// compact: grid (U, 5 planes), 256 threads.  Survivor j (new slot number) comes from old slot
+// src[j] >= j.  Left shift (heads stay): a workgroup walks its plane front to back in chunks
+// (load a chunk into registers, barrier, store); earlier chunks only wrote below the chunk
+// start and later sources all lie at or above it, so nothing is overwritten before it is
+// read.  Right shift (the head of the slot-anchored rings advances by the evictions e):
+// survivor j moves from ring offset src[j] to offset e + j >= src[j], only the survivors in
+// front of the last hole move, and the walk goes back to front; the mirror argument holds.
 // planes: 0 = K INT8 rows, 1 = V INT8 rows, 2 = scales + EMA + position, 3 = K FP16 rows,
-// 4 = V FP16 rows.  EMA and position are plain per-slot arrays and always shift left.
+// 4 = V FP16 rows.
 // ---------------------------------------------------------------------------------------
+
+// One plane's rows, ROWB bytes each: destination slots [lo, hi) in walk order `right`.
+// srow(j) / drow(j) give the source and destination ring rows of survivor j.
+template <int ROWB, typename SrcRow, typename DstRow>
+__device__ __forceinline__ void move_rows(uint8_t *base_ptr, int lo, int hi, bool right, SrcRow srow,
+                                          DstRow drow) {
+  constexpr int LPR = ROWB / 16, RPP = kEvThreads / LPR, PASSES = 4;
+  const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
+  for (int done = 0; done < hi - lo; done += RPP * PASSES) {
+    int4 buf[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int k = done + p * RPP + r0;               // k-th slot of the walk
+      const int j = right ? hi - 1 - k : lo + k;
+      if (k < hi - lo) buf[p] = *(const int4 *)(base_ptr + (size_t)srow(j) * ROWB + c * 16);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int k = done + p * RPP + r0;
+      const int j = right ? hi - 1 - k : lo + k;
+      if (k < hi - lo) *(int4 *)(base_ptr + (size_t)drow(j) * ROWB + c * 16) = buf[p];
+    }
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
                                                              const int32_t *__restrict__ src_all,
                                                              const int32_t *__restrict__ sel_all) {
   const int u = blockIdx.x, plane = blockIdx.y, tid = threadIdx.x;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
-  const int n_new = sel[0], n8_new = sel[1], hole = sel[2];
+  const int n_new = sel[0], n8_new = sel[1], hole = sel[2], evicted = sel[3];
   if (hole >= n_new) return;                          // nothing moves
-  const int n8_old = cv.n8[u], h16 = cv.head16[u], h8 = cv.head8[u];
+  const int n8_old = cv.n8[u], h16 = cv.head16[u], h0 = cv.head8[u];
   const int32_t *src = src_all + (size_t)u * cv.cap;
-  const int cap8 = cv.cap8, cap16 = cv.cap16;
+  const int cap = cv.cap, cap8 = cv.cap8, cap16 = cv.cap16;
+  const bool fp16_only = cap8 == 0;
   const bool right = sel[5] != 0;
   const int e8 = n8_old - n8_new;
-  const int jr = sel[4] + 1 - e8;                     // right shift: survivors [0, jr) move
-  const int h8_new = sel[6];
+  const int jr = sel[4] + 1 - (fp16_only ? evicted : e8);   // right shift: survivors [0, jr) move
+  const int h0_new = sel[6];
 
   if (plane <= 1) {
-    constexpr int LPR = D / 16, RPP = kEvThreads / LPR, PASSES = 4;
-    int8_t *base_ptr = (plane == 0 ? cv.k8 : cv.v8) + (size_t)u * cap8 * D;
-    const int c = tid % LPR, r0 = tid / LPR;
-    if (!right) {
-      // destination slots [hole, n8_new), front to back
-      for (int base = hole; base < n8_new; base += RPP * PASSES) {
-        int4 buf[PASSES];
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = base + p * RPP + r0;
-          if (j < n8_new) buf[p] = *(const int4 *)(base_ptr + (size_t)ring_row(h8, src[j], cap8) * D + c * 16);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = base + p * RPP + r0;
-          if (j < n8_new) *(int4 *)(base_ptr + (size_t)ring_row(h8, j, cap8) * D + c * 16) = buf[p];
-        }
-      }
-    } else {
-      // destination slots [0, jr), back to front
-      for (int top = jr; top > 0; top -= RPP * PASSES) {
-        int4 buf[PASSES];
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = top - 1 - (p * RPP + r0);
-          if (j >= 0) buf[p] = *(const int4 *)(base_ptr + (size_t)ring_row(h8, src[j], cap8) * D + c * 16);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = top - 1 - (p * RPP + r0);
-          if (j >= 0) *(int4 *)(base_ptr + (size_t)ring_row(h8_new, j, cap8) * D + c * 16) = buf[p];
-        }
-      }
-    }
+    if (fp16_only) return;
+    uint8_t *base_ptr = (uint8_t *)((plane == 0 ? cv.k8 : cv.v8) + (size_t)u * cap8 * D);
+    move_rows<D>(base_ptr, right ? 0 : hole, right ? jr : n8_new, right,
+                 [&](int j) { return ring_row(h0, src[j], cap8); },
+                 [&](int j) { return ring_row(h0_new, j, cap8); });
   } else if (plane == 2) {
-    // per-slot metadata: EMA and position for [hole, n_new)
-    float *ema = cv.ema + (size_t)u * cv.cap;
-    int32_t *pos = cv.pos + (size_t)u * cv.cap;
+    // per-slot planes: EMA and position for every moving slot, scales for the INT8 ones
+    // (same ring offsets: cap8 = cap in a mixed cache)
+    float *ema = cv.ema + (size_t)u * cap;
+    int32_t *pos = cv.pos + (size_t)u * cap;
+    __half *ks = cv.ks + (size_t)u * cap8, *vs = cv.vs + (size_t)u * cap8;
+    const int lo = right ? 0 : hole, hi = right ? jr : n_new;
     constexpr int PASSES = 4;
-    for (int base = hole; base < n_new; base += kEvThreads * PASSES) {
+    for (int done = 0; done < hi - lo; done += kEvThreads * PASSES) {
       float fa[PASSES];
       int32_t fp[PASSES];
+      __half fk[PASSES], fv[PASSES];
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
-        const int j = base + p * kEvThreads + tid;
-        if (j < n_new) {
-          const int s = src[j];
+        const int k = done + p * kEvThreads + tid;
+        const int j = right ? hi - 1 - k : lo + k;
+        if (k < hi - lo) {
+          const int s = ring_row(h0, src[j], cap);
           fa[p] = ema[s];
           fp[p] = pos[s];
+          if (j < n8_new) { fk[p] = ks[s]; fv[p] = vs[s]; }
         }
       }
       __syncthreads();
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
-        const int j = base + p * kEvThreads + tid;
-        if (j < n_new) {
-          ema[j] = fa[p];
-          pos[j] = fp[p];
-        }
-      }
-    }
-    // scales follow their INT8 rows
-    __half *ks = cv.ks + (size_t)u * cap8, *vs = cv.vs + (size_t)u * cap8;
-    if (!right) {
-      for (int base = hole; base < n8_new; base += kEvThreads * PASSES) {
-        __half fk[PASSES], fv[PASSES];
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = base + p * kEvThreads + tid;
-          if (j < n8_new) {
-            const int s = ring_row(h8, src[j], cap8);
-            fk[p] = ks[s];
-            fv[p] = vs[s];
-          }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = base + p * kEvThreads + tid;
-          if (j < n8_new) {
-            const int d = ring_row(h8, j, cap8);
-            ks[d] = fk[p];
-            vs[d] = fv[p];
-          }
-        }
-      }
-    } else {
-      for (int top = jr; top > 0; top -= kEvThreads * PASSES) {
-        __half fk[PASSES], fv[PASSES];
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = top - 1 - (p * kEvThreads + tid);
-          if (j >= 0) {
-            const int s = ring_row(h8, src[j], cap8);
-            fk[p] = ks[s];
-            fv[p] = vs[s];
-          }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-          const int j = top - 1 - (p * kEvThreads + tid);
-          if (j >= 0) {
-            const int d = ring_row(h8_new, j, cap8);
-            ks[d] = fk[p];
-            vs[d] = fv[p];
-          }
+        const int k = done + p * kEvThreads + tid;
+        const int j = right ? hi - 1 - k : lo + k;
+        if (k < hi - lo) {
+          const int d = ring_row(h0_new, j, cap);
+          ema[d] = fa[p];
+          pos[d] = fp[p];
+          if (j < n8_new) { ks[d] = fk[p]; vs[d] = fv[p]; }
         }
       }
     }
   } else {
-    // FP16 ring rows: destination slots [max(hole, n8_new), n_new).  When every evicted
-    // slot was INT8 the ring rows keep their place and nothing moves.
-    if (sel[3] == n8_old - n8_new) return;
-    constexpr int ROWB = 2 * D, LPR = ROWB / 16, RPP = kEvThreads / LPR, PASSES = 4;
+    // FP16 ring rows.  Mixed cache: they only move (left) when an FP16 slot was evicted.
+    // FP16-only cache: either side.
+    if (!fp16_only && evicted == e8) return;
     uint8_t *base_ptr = (uint8_t *)((plane == 3 ? cv.k16 : cv.v16) + (size_t)u * cap16 * D);
-    const int c = tid % LPR, r0 = tid / LPR;
-    const int j0 = max(hole, n8_new);
-    for (int base = j0; base < n_new; base += RPP * PASSES) {
-      int4 buf[PASSES];
-#pragma unroll
-      for (int p = 0; p < PASSES; ++p) {
-        const int j = base + p * RPP + r0;
-        if (j < n_new) {
-          const int s = ring_row(h16, src[j] - n8_old, cap16);
-          buf[p] = *(const int4 *)(base_ptr + (size_t)s * ROWB + c * 16);
-        }
-      }
-      __syncthreads();
-#pragma unroll
-      for (int p = 0; p < PASSES; ++p) {
-        const int j = base + p * RPP + r0;
-        if (j < n_new) {
-          const int d = ring_row(h16, j - n8_new, cap16);
-          *(int4 *)(base_ptr + (size_t)d * ROWB + c * 16) = buf[p];
-        }
-      }
-    }
+    const int h16_new = (fp16_only && right) ? ring_row(h16, evicted, cap16) : h16;
+    move_rows<2 * D>(base_ptr, right ? 0 : max(hole, n8_new), right ? jr : n_new, right,
+                     [&](int j) { return ring_row(h16, src[j] - n8_old, cap16); },
+                     [&](int j) { return ring_row(h16_new, j - n8_new, cap16); });
   }
 }
 
@@ -905,8 +866,9 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
   const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (u >= U) return;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
-  const int n_new = sel[0], n8_new = sel[1], h8 = sel[6];   // INT8 ring head after the compaction
-  const int h16 = cv.head16[u];
+  const int n_new = sel[0], n8_new = sel[1], h8 = sel[6];   // slot-anchored ring head after the compaction
+  // an FP16-only cache that closed its holes from the front has advanced its FP16 ring too
+  const int h16 = (cv.cap8 == 0 && sel[5]) ? ring_row(cv.head16[u], sel[3], cv.cap16) : cv.head16[u];
   const int n16 = n_new - n8_new;
   const int cnt = (cv.W < 0) ? 0 : max(0, n16 - cv.W);
   for (int t = 0; t < cnt; ++t) {
