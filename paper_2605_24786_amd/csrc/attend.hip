@@ -624,8 +624,15 @@ constexpr int kTile = 32;              // slots per wavefront tile
 constexpr int kKRow = 128 + 16;        // LDS row stride of the INT8 K tile (bytes)
 constexpr int kKRow16 = 256 + 16;      // LDS row stride of the 16-slot FP16 K tile (bytes)
 constexpr int kVRow = 32 + 4;          // LDS row stride of the transposed V tile (bytes)
+// Rows of the transposed V tile come in groups of 16 channels.  A store instruction has its
+// lanes in 8 different groups (16 rows = 144 dwords apart: only two different banks), so group g
+// is shifted by 20 g dwords: the groups then start 164 dwords = 4 banks (mod 32) apart and the
+// lanes of a half wavefront fall into 32 different banks.  A load instruction stays inside
+// one group and is not affected.
+__host__ __device__ constexpr int kVSkew(int group) { return 80 * group; }
+constexpr int kVBytes = 128 * kVRow + kVSkew(7);   // rows plus the largest shift
 constexpr int kPRow = 32 + 8;          // LDS row stride of the probability tile (halfs)
-constexpr int kTileBytes = kTile * kKRow + 128 * kVRow + 16 * kPRow * 2;   // per wavefront
+constexpr int kTileBytes = kTile * kKRow + kVBytes + 16 * kPRow * 2;   // per wavefront
 
 // 4 int8 (one dword) -> 4 fp16 (two dwords), exact: c ^ 0x80 is c + 128 as an unsigned byte,
 // 0x6400 | byte is the fp16 number 1024 + byte, and subtracting 1152 leaves c.
@@ -803,7 +810,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
   // ---------------- INT8 slots on the matrix cores ----------------
   uint8_t *Kt = (uint8_t *)tiles + (size_t)w * kTileBytes;   // [32][kKRow]
   uint8_t *Vt = Kt + kTile * kKRow;                           // [128][kVRow], slots permuted
-  _Float16 *Pb = (_Float16 *)(Vt + 128 * kVRow);              // [16][kPRow], rows >= G stay 0
+  _Float16 *Pb = (_Float16 *)(Vt + kVBytes);                  // [16][kPRow], rows >= G stay 0
   for (int i = lane; i < 16 * kPRow / 2; i += kWave) ((unsigned *)Pb)[i] = 0u;
 
   // A operand of the score contraction: Q padded to 16 rows; k-step s covers channels
@@ -856,7 +863,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
         const unsigned x0 = dword_of(vh[0], q4), x1 = dword_of(vh[1], q4);
         const unsigned x2 = dword_of(vh[2], q4), x3 = dword_of(vh[3], q4);
         // half r of each pair is slot 4r + r4; it lands at column 4*r4 + r
-        unsigned *dst = (unsigned *)(Vt + (8 * c16 + 2 * q4) * kVRow + 8 * r4);
+        unsigned *dst = (unsigned *)(Vt + (8 * c16 + 2 * q4) * kVRow + kVSkew(c16 >> 1) + 8 * r4);
         dst[0] = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
         dst[1] = __builtin_amdgcn_perm(x3, x2, 0x05040100u);
         dst[kVRow / 4] = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
@@ -898,7 +905,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       const half4_t pa = *(const half4_t *)(Pb + t16 * kPRow + 4 * g4);
 #pragma unroll
       for (int nt = 0; nt < 8; ++nt) {
-        const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + 8 * g4);
+        const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + kVSkew(nt) + 8 * g4);
         const uint2 v2 = make_uint2(vb[0], vb[1]);
         O[nt] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, __builtin_bit_cast(half4_t, v2), O[nt], 0, 0, 0);
       }
@@ -923,7 +930,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       const unsigned o0 = __builtin_amdgcn_perm(t2, t0, 0x05040100u), o1 = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
       const unsigned o2 = __builtin_amdgcn_perm(t3, t1, 0x05040100u), o3 = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
       // byte r of o_e is slot 8r + r8 at channel 16*c8 + 4*q4 + e; it lands at column 4*r8 + r
-      uint8_t *dst = Vt + (16 * c8 + 4 * q4) * kVRow + 4 * r8;
+      uint8_t *dst = Vt + (16 * c8 + 4 * q4) * kVRow + kVSkew(c8) + 4 * r8;
       *(unsigned *)(dst) = o0;
       *(unsigned *)(dst + kVRow) = o1;
       *(unsigned *)(dst + 2 * kVRow) = o2;
@@ -1010,7 +1017,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     const half8_t pa = *(const half8_t *)(Pb + t16 * kPRow + 8 * g4);
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) {
-      const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + 8 * g4);   // 4-byte aligned
+      const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + kVSkew(nt) + 8 * g4);   // 4-byte aligned
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, cvt_i8x8_f16x8_biased(vb[0], vb[1]), O[nt], 0, 0, 0);
     }
     wave_lds_sync();
