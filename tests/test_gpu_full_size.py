@@ -21,8 +21,11 @@ from harness import Lockstep  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
-# workload index -> (decode steps run here, oracle-followed units, layers kept)
-PLAN = {0: (6, 12, None), 1: (1, 6, None), 2: (3, 4, 16), 3: (2, 2, 4), 4: (2, 6, 8)}
+# workload index -> (decode steps run here, oracle-followed units, layers kept, logit run length)
+# The logit schedule alternates between uncertain and confident runs of 32 steps; the truncated
+# runs here use runs of 3 steps (same shapes, same values per step kind) so that both budgets,
+# and the large eviction at a loose -> tight switch, occur at full size.
+PLAN = {0: (12, 24, None, 3), 1: (1, 12, None, None), 2: (7, 6, 16, 3), 3: (4, 2, 4, None), 4: (7, 8, 8, 3)}
 
 
 def _invariants_all_units(ls, wl, step):
@@ -49,8 +52,10 @@ def _invariants_all_units(ls, wl, step):
 
 @pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
 def test_full_size_workload(lib, idx):
-    steps, units, layers = PLAN[idx]
+    steps, units, layers, run = PLAN[idx]
     wl = workload(idx)
+    if run is not None:
+        wl = wl.scaled(logit_run=run)
     if layers is not None and layers < wl.n_layers:
         # fewer layers bound the host-side generation time; per-layer shapes stay at full size
         wl = wl.scaled(n_layers=layers, n_tight=wl.n_tight[:layers], n_loose=wl.n_loose[:layers])
