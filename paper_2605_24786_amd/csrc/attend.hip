@@ -441,9 +441,10 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   float ema_old[kPre + 1];
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
-    const int t = tid + k * kAttThreads;
-    const int slot = sl.slot_of(min(t, sl.ntok - 1));
-    ema_old[k] = (t < sl.ntok && slot != sl.n - 1) ? EMA[ring_row_u(sl.h8, slot, cv.cap)] : 0.f;
+    // branch-free (a slot past the slice re-reads its last one; the appended token's slot
+    // holds a stale value): the uses below mask both cases
+    const int slot = sl.slot_of(max(0, min(tid + k * kAttThreads, sl.ntok - 1)));   // an empty slice reads slot lo16 < n
+    ema_old[k] = EMA[ring_row_u(sl.h8, slot, cv.cap)];
   }
   // workgroup merge of the per-wavefront partials; two channels per thread, one 8-byte
   // coherent store each
@@ -538,17 +539,34 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       double A = 0.0;
 #pragma unroll
       for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
-      EMA[ring_row_u(sl.h8, sl.slot_of(t), cv.cap)] = (float)(lam * (double)ema_old[k] + oml * A);
+      const int slot = sl.slot_of(t);
+      const double old = (slot == sl.n - 1) ? 0.0 : (double)ema_old[k];   // the new token starts at 0
+      EMA[ring_row_u(sl.h8, slot, cv.cap)] = (float)(lam * old + oml * A);
     }
   }
-  for (int t = tid + kPre * kAttThreads; t < sl.ntok; t += kAttThreads) {
-    const int slot = sl.slot_of(t);
-    const int row = ring_row_u(sl.h8, slot, cv.cap);
-    const double old = (slot == sl.n - 1) ? 0.0 : (double)EMA[row];
-    double A = 0.0;
+  // the rest of the slice in batches of kBatch slots per thread: branch-free loads first (a
+  // slot past the slice re-reads its last one), so a long slice costs one round trip per
+  // batch, not one per slot
+  constexpr int kBatch = 4;
+  for (int t0 = tid + kPre * kAttThreads; t0 < sl.ntok; t0 += kBatch * kAttThreads) {
+    float old[kBatch];
+    int row[kBatch];
 #pragma unroll
-    for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
-    EMA[row] = (float)(lam * old + oml * A);
+    for (int k = 0; k < kBatch; ++k) {
+      row[k] = ring_row_u(sl.h8, sl.slot_of(min(t0 + k * kAttThreads, sl.ntok - 1)), cv.cap);
+      old[k] = EMA[row[k]];
+    }
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const int t = t0 + k * kAttThreads;
+      if (t < sl.ntok) {
+        double A = 0.0;
+#pragma unroll
+        for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
+        const double prev = (sl.slot_of(t) == sl.n - 1) ? 0.0 : (double)old[k];   // the new token starts at 0
+        EMA[row[k]] = (float)(lam * prev + oml * A);
+      }
+    }
   }
   TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----

@@ -135,16 +135,34 @@ __device__ __forceinline__ double quotient(double n, const Divisor &dv) {
 // than every hole, then keep their rows), any in an FP16-only cache.
 // `last_hole` is the newest evicted slot of that ring (-1: none).
 // ---------------------------------------------------------------------------------------
+struct ShiftPlan {
+  int right;        // 1: slots in front of the last hole shift right
+  int left_rows;    // payload rows a left shift would move
+  int right_rows;   // payload rows (= slots) a right shift would move
+  int lo, hi;       // new slot numbers [lo, hi) that move, i.e. whose source slot the compaction looks up
+};
+__device__ __forceinline__ ShiftPlan shift_plan(const CacheView &cv, int n_new, int n8_old, int n8_new,
+                                                int first_hole, int evicted, int last_hole) {
+  const bool fp16_only = cv.cap8 == 0;
+  const int e8 = n8_old - n8_new;
+  const int span = fp16_only ? n_new : n8_new;       // survivors of the ring the holes lie in
+  ShiftPlan p;
+  p.left_rows = span - min(first_hole, span);
+  p.right_rows = last_hole + 1 - (fp16_only ? evicted : e8);   // survivors in front of the last hole
+  p.right = (fp16_only ? evicted > 0 : (e8 > 0 && evicted == e8)) && p.right_rows < p.left_rows;
+  p.lo = p.right ? 0 : min(first_hole, n_new);
+  p.hi = p.right ? p.right_rows : n_new;
+  return p;
+}
+
 __device__ __forceinline__ void write_selection(const CacheView &cv, int u, int32_t *sel, int n_new,
                                                 int n8_old, int n8_new, int first_hole, int evicted,
                                                 int last_hole) {
   const bool fp16_only = cv.cap8 == 0;
   const int h0 = cv.head8[u];
   const int e8 = n8_old - n8_new;
-  const int span = fp16_only ? n_new : n8_new;       // survivors of the ring the holes lie in
-  const int left_rows = span - min(first_hole, span);
-  const int right_rows = last_hole + 1 - (fp16_only ? evicted : e8);   // survivors in front of the last hole
-  const int right = (fp16_only ? evicted > 0 : (e8 > 0 && evicted == e8)) && right_rows < left_rows;
+  const ShiftPlan sp = shift_plan(cv, n_new, n8_old, n8_new, first_hole, evicted, last_hole);
+  const int right = sp.right, left_rows = sp.left_rows, right_rows = sp.right_rows;
   sel[0] = n_new;
   sel[1] = n8_new;
   sel[2] = first_hole;
@@ -383,7 +401,8 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {   // set bits
 }
 
 template <int T, int E>
-__global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerMask appended,
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T == 256 ? 4 : 1, T == 256 ? 4 : 8)))
+void rank_select_reg_kernel(CacheView cv, LayerMask appended,
                                                             double alpha,
                                                             int32_t *__restrict__ src_all,
                                                             int32_t *__restrict__ sel_all) {
@@ -420,11 +439,17 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
 
   // candidate EMA / position of the owned slots, min / max of the EMA
   float av[E];
+  int pv[E];
+  // slots are position-sorted: first and last candidate position (requested with the rest)
+  const int pos_first = pos[hm], pos_last = pos[ring_row_u(hm, ncand - 1, cap)];
   float fmin_ = INFINITY, fmax_ = -INFINITY;
+  // branch-free loads (indices past the candidates re-read the last one and are masked where
+  // the values are used), so that all loads of the unit are in flight before the first wait
 #pragma unroll
   for (int k = 0; k < E; ++k) {
-    const int i = tid + k * T;
-    av[k] = (k < Ed && i < ncand) ? ema[ring_row_u(hm, i, cap)] : 0.f;
+    const int row = ring_row_u(hm, min(tid + k * T, ncand - 1), cap);
+    av[k] = ema[row];
+    pv[k] = pos[row];
   }
 #pragma unroll
   for (int k = 0; k < E; ++k) {
@@ -439,8 +464,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
 #pragma unroll
   for (int k = 1; k < kRsWaves; ++k) { lo_f = fminf(lo_f, s_fmin[k]); hi_f = fmaxf(hi_f, s_fmax[k]); }
   const double a_lo = (double)lo_f, a_hi = (double)hi_f;
-  // slots are position-sorted
-  const double p_lo = (double)pos[hm], p_hi = (double)pos[ring_row_u(hm, ncand - 1, cap)];
+  const double p_lo = (double)pos_first, p_hi = (double)pos_last;
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
   const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
@@ -452,7 +476,7 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
     key[k] = 0ull;
     if (k < Ed && i < ncand) {
       const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)av[k], a_lo), a_div);
-      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[ring_row_u(hm, i, cap)], p_lo), p_div);
+      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pv[k], p_lo), p_div);
       key[k] = (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
       kmin = key[k] < kmin ? key[k] : kmin;
       kmax = key[k] > kmax ? key[k] : kmax;
@@ -584,35 +608,37 @@ __global__ __launch_bounds__(T) void rank_select_reg_kernel(CacheView cv, LayerM
       }
     }
   }
+  kept8 = wave_sum(kept8);
+  hole = wave_min(hole);
+  last8 = wave_max(last8);
+  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; s_last8[w] = last8; }
   __syncthreads();
+  int k8 = 0, hl = n, l8 = -1;
+#pragma unroll
+  for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); l8 = max(l8, s_last8[k]); }
   int tot_keep = 0;
   {
-    // Ed * waves <= T for both instantiations' limits (20 * 4, 33 * 16): one scan
+    // Ed * waves <= T for every instantiation's limits: one scan
     const int v = tid < Ed * kRsWaves ? s_cnt[tid] : 0;
     const int ex = block_scan_excl<kRsWaves>(v, s_tmp, &tot_keep);
     __syncthreads();
     if (tid < Ed * kRsWaves) s_cnt[tid] = ex;
   }
   __syncthreads();
+  // the compaction only looks up the source of the slots that move
+  const ShiftPlan sp = shift_plan(cv, tot_keep /* = n - e */, n8, k8, hl, e, l8);
 #pragma unroll
   for (int k = 0; k < E; ++k) {
     if (k < Ed) {
       const int i = tid + k * T;
       const bool keep = i < n && !((evbits >> k) & 1ull);
       const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
-      if (keep) src[s_cnt[k * kRsWaves + w] + lanes_below(bm)] = i;
+      const int j = s_cnt[k * kRsWaves + w] + lanes_below(bm);
+      if (keep && j >= sp.lo && j < sp.hi) src[j] = i;
     }
   }
-  kept8 = wave_sum(kept8);
-  hole = wave_min(hole);
-  last8 = wave_max(last8);
-  if (lane == 0) { s_k8[w] = kept8; s_hole[w] = hole; s_last8[w] = last8; }
-  __syncthreads();
   if (tid == 0) {
-    int k8 = 0, hl = n, l8 = -1;
-#pragma unroll
-    for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); l8 = max(l8, s_last8[k]); }
-    write_selection(cv, u, sel, tot_keep /* = n - e */, n8, k8, hl, e, l8);
+    write_selection(cv, u, sel, tot_keep, n8, k8, hl, e, l8);
     cv.unit_evicted[u] += (unsigned)e;
   }
 }
@@ -729,20 +755,22 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
     for (int y = x; y > 0; --y)
       if (ev[y] < ev[y - 1]) { const int t = ev[y]; ev[y] = ev[y - 1]; ev[y - 1] = t; }
   const int n_new = n - e;
+  int gone8 = 0, last8 = -1;
+#pragma unroll
+  for (int q = 0; q < kSmallE; ++q) {
+    if (ev[q] < n8) ++gone8;
+    if (ev[q] < nx) last8 = ev[q];                   // unused entries are INT_MAX
+  }
+  // the compaction only looks up the source of the slots that move
+  const ShiftPlan sp = shift_plan(cv, n_new, n8, n8 - gone8, ev[0], e, last8);
   int32_t *src = src_all + (size_t)u * cv.cap;
-  for (int j = lane; j < n_new; j += kWave) {
+  for (int j = sp.lo + lane; j < sp.hi; j += kWave) {
     int sidx = j;
 #pragma unroll
     for (int q = 0; q < kSmallE; ++q) sidx += (ev[q] <= sidx);   // unused entries are INT_MAX
     src[j] = sidx;
   }
   if (lane == 0) {
-    int gone8 = 0, last8 = -1;
-#pragma unroll
-    for (int q = 0; q < kSmallE; ++q) {
-      if (ev[q] < n8) ++gone8;
-      if (ev[q] < nx) last8 = ev[q];                 // unused entries are INT_MAX
-    }
     write_selection(cv, u, sel, n_new, n8, n8 - gone8, ev[0], e, last8);
     cv.unit_evicted[u] += (unsigned)e;
   }
@@ -761,26 +789,32 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
 // ---------------------------------------------------------------------------------------
 
 // One plane's rows, ROWB bytes each: destination slots [lo, hi) in walk order `right`.
-// srow(j) / drow(j) give the source and destination ring rows of survivor j.
+// srow(s) gives the ring row of old slot s, drow(j) that of new slot j.  Loads are grouped
+// (source slots of all passes, then all rows), so a chunk costs two memory round trips;
+// lanes past the range issue nothing (most units move a handful of rows).
 template <int ROWB, typename SrcRow, typename DstRow>
-__device__ __forceinline__ void move_rows(uint8_t *base_ptr, int lo, int hi, bool right, SrcRow srow,
-                                          DstRow drow) {
+__device__ __forceinline__ void move_rows(uint8_t *base_ptr, const int32_t *__restrict__ src, int lo, int hi,
+                                          bool right, SrcRow srow, DstRow drow) {
   constexpr int LPR = ROWB / 16, RPP = kEvThreads / LPR, PASSES = 4;
   const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
-  for (int done = 0; done < hi - lo; done += RPP * PASSES) {
+  const int cnt = hi - lo;
+  for (int done = 0; done < cnt; done += RPP * PASSES) {
+    int from[PASSES];
     int4 buf[PASSES];
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int k = done + p * RPP + r0;               // k-th slot of the walk
-      const int j = right ? hi - 1 - k : lo + k;
-      if (k < hi - lo) buf[p] = *(const int4 *)(base_ptr + (size_t)srow(j) * ROWB + c * 16);
+      if (k < cnt) from[p] = src[right ? hi - 1 - k : lo + k];
     }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p)
+      if (done + p * RPP + r0 < cnt) buf[p] = *(const int4 *)(base_ptr + (size_t)srow(from[p]) * ROWB + c * 16);
     __syncthreads();
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int k = done + p * RPP + r0;
       const int j = right ? hi - 1 - k : lo + k;
-      if (k < hi - lo) *(int4 *)(base_ptr + (size_t)drow(j) * ROWB + c * 16) = buf[p];
+      if (k < cnt) *(int4 *)(base_ptr + (size_t)drow(j) * ROWB + c * 16) = buf[p];
     }
   }
 }
@@ -805,8 +839,8 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
   if (plane <= 1) {
     if (fp16_only) return;
     uint8_t *base_ptr = (uint8_t *)((plane == 0 ? cv.k8 : cv.v8) + (size_t)u * cap8 * D);
-    move_rows<D>(base_ptr, right ? 0 : hole, right ? jr : n8_new, right,
-                 [&](int j) { return ring_row(h0, src[j], cap8); },
+    move_rows<D>(base_ptr, src, right ? 0 : hole, right ? jr : n8_new, right,
+                 [&](int s) { return ring_row(h0, s, cap8); },
                  [&](int j) { return ring_row(h0_new, j, cap8); });
   } else if (plane == 2) {
     // per-slot planes: EMA and position for every moving slot, scales for the INT8 ones
@@ -816,19 +850,28 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
     __half *ks = cv.ks + (size_t)u * cap8, *vs = cv.vs + (size_t)u * cap8;
     const int lo = right ? 0 : hole, hi = right ? jr : n_new;
     constexpr int PASSES = 4;
-    for (int done = 0; done < hi - lo; done += kEvThreads * PASSES) {
+    const int cnt = hi - lo;
+    for (int done = 0; done < cnt; done += kEvThreads * PASSES) {
+      int from[PASSES];
       float fa[PASSES];
       int32_t fp[PASSES];
-      __half fk[PASSES], fv[PASSES];
+      unsigned short fk[PASSES], fv[PASSES];
+      // grouped loads (see move_rows)
 #pragma unroll
       for (int p = 0; p < PASSES; ++p) {
         const int k = done + p * kEvThreads + tid;
-        const int j = right ? hi - 1 - k : lo + k;
-        if (k < hi - lo) {
-          const int s = ring_row(h0, src[j], cap);
-          fa[p] = ema[s];
-          fp[p] = pos[s];
-          if (j < n8_new) { fk[p] = ks[s]; fv[p] = vs[s]; }
+        if (k < cnt) from[p] = ring_row(h0, src[right ? hi - 1 - k : lo + k], cap);
+      }
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int k = done + p * kEvThreads + tid;
+        if (k < cnt) {
+          fa[p] = ema[from[p]];
+          fp[p] = pos[from[p]];
+          if ((right ? hi - 1 - k : lo + k) < n8_new) {
+            fk[p] = ((const unsigned short *)ks)[from[p]];
+            fv[p] = ((const unsigned short *)vs)[from[p]];
+          }
         }
       }
       __syncthreads();
@@ -836,11 +879,14 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
       for (int p = 0; p < PASSES; ++p) {
         const int k = done + p * kEvThreads + tid;
         const int j = right ? hi - 1 - k : lo + k;
-        if (k < hi - lo) {
+        if (k < cnt) {
           const int d = ring_row(h0_new, j, cap);
           ema[d] = fa[p];
           pos[d] = fp[p];
-          if (j < n8_new) { ks[d] = fk[p]; vs[d] = fv[p]; }
+          if (j < n8_new) {
+            ((unsigned short *)ks)[d] = fk[p];
+            ((unsigned short *)vs)[d] = fv[p];
+          }
         }
       }
     }
@@ -850,8 +896,8 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
     if (!fp16_only && evicted == e8) return;
     uint8_t *base_ptr = (uint8_t *)((plane == 3 ? cv.k16 : cv.v16) + (size_t)u * cap16 * D);
     const int h16_new = (fp16_only && right) ? ring_row(h16, evicted, cap16) : h16;
-    move_rows<2 * D>(base_ptr, right ? 0 : max(hole, n8_new), right ? jr : n_new, right,
-                     [&](int j) { return ring_row(h16, src[j] - n8_old, cap16); },
+    move_rows<2 * D>(base_ptr, src, right ? 0 : max(hole, n8_new), right ? jr : n_new, right,
+                     [&](int s) { return ring_row(h16, s - n8_old, cap16); },
                      [&](int j) { return ring_row(h16_new, j - n8_new, cap16); });
   }
 }
