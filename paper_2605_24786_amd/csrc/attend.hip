@@ -1217,12 +1217,9 @@ bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int fo
   // partials, keeping the raw scores in device scratch; the second merges and updates the EMA.
   // Nothing waits inside a kernel, so any split count works.
   {
-    // about four workgroups per CU, so that the last round of a grid that is not a multiple
-    // of the CU count is short
-    int ns = (4 * lim.cus + units_per_layer - 1) / units_per_layer;
-    ns = (int)std::min<long long>(ns, std::max<long long>(1, unit_bytes / (32 * 1024)));
-    if (forced_splits > 0) ns = want;
-    ns = std::max(1, std::min(ns, kAttendMaxSplits));
+    // same split count as the single-kernel plan would like (measured on 64 units of 4096
+    // slots: 4 splits 40 us, 16 splits 80 us -- the second launch grows with the split count)
+    const int ns = want;
     int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
     S = (S + 255) / 256 * 256;
     const size_t lds = attend_lds_bytes(D, G, 0, false);
