@@ -32,6 +32,7 @@
 //     FP16 slots go through the same contractions in 16-slot tiles, no conversion needed.
 #include <algorithm>
 #include <map>
+#include <mutex>
 #include <tuple>
 
 #include "confkv_dev.h"
@@ -1136,8 +1137,13 @@ struct DeviceLimits {
   bool ok = false;
 };
 
+// The two caches below are shared by every handle of the process; handles may live on
+// different host threads, so both are guarded.
+static std::mutex g_plan_mutex;
+
 static const DeviceLimits &device_limits() {
   static DeviceLimits lim;
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
   if (!lim.ok) {
     int dev = 0;
     hipDeviceProp_t prop;
@@ -1156,6 +1162,7 @@ static const DeviceLimits &device_limits() {
 // Resident workgroups per CU of a kernel with `lds` bytes of dynamic LDS.
 static int attend_occupancy(AttendFn fn, size_t lds) {
   static std::map<std::tuple<const void *, size_t>, int> cache;
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
   auto key = std::make_tuple((const void *)fn, lds);
   auto it = cache.find(key);
   if (it != cache.end()) return it->second;
