@@ -407,8 +407,7 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
                                                             int32_t *__restrict__ src_all,
                                                             int32_t *__restrict__ sel_all) {
   constexpr int kRsWaves = T / kWave;
-  constexpr int BPT = T >= 256 ? 1 : 256 / T;       // histogram bins per thread in the scan
-  __shared__ int hist[256];
+  __shared__ int hist[512];                         // two histograms, used alternately
   __shared__ int s_tmp[kRsWaves];
   __shared__ int s_cnt[E * kRsWaves];               // kept (or tied) lanes per (round, wavefront)
   __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
@@ -504,39 +503,44 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   const unsigned long long span = kmax - kmin;
   const int top = span ? 63 - __clzll((long long)span) : 0;   // highest differing bit
 
-  // radix select of the e-th smallest key, 8 bits (or what is left) per pass
+  // radix select of the e-th smallest key, 8 bits (or what is left) per pass.  Two barriers
+  // per pass: the histogram of the next pass (the other of two buffers) is cleared while this
+  // one is filled, and the first wavefront alone scans the 256 bins (four per lane) and picks
+  // the bin that holds the cut-off.
   unsigned long long mask = 0ull;
-  for (int hi_bit = top + 1; hi_bit > 0;) {
+  for (int bin = tid; bin < 512; bin += T) hist[bin] = 0;
+  __syncthreads();
+  int pass = 0;
+  for (int hi_bit = top + 1; hi_bit > 0; ++pass) {
     const int shift = hi_bit > 8 ? hi_bit - 8 : 0;
     const unsigned dmask = (1u << (hi_bit - shift)) - 1u;
-    for (int bin = tid; bin < 256; bin += T) hist[bin] = 0;
-    __syncthreads();
+    int *hcur = hist + 256 * (pass & 1), *hnext = hist + 256 * ((pass + 1) & 1);
     const unsigned long long prefix = s_prefix;
+    for (int bin = tid; bin < 256; bin += T) hnext[bin] = 0;
 #pragma unroll
     for (int k = 0; k < E; ++k) {
       if (k < Ed && tid + k * T < ncand && (key[k] & mask) == prefix)
-        atomicAdd(&hist[(int)((unsigned)(key[k] >> shift) & dmask)], 1);
+        atomicAdd(&hcur[(int)((unsigned)(key[k] >> shift) & dmask)], 1);
     }
     __syncthreads();
-    // thread t owns the bins [t * BPT, (t + 1) * BPT)
-    int cnt[BPT], mine = 0;
+    if (tid < kWave) {
+      int cnt[4], mine = 0;
 #pragma unroll
-    for (int j = 0; j < BPT; ++j) {
-      cnt[j] = tid * BPT < 256 ? hist[tid * BPT + j] : 0;
-      mine += cnt[j];
-    }
-    int total;
-    int before = block_scan_excl<kRsWaves>(mine, s_tmp, &total);
-    const int krem = s_krem;
-    __syncthreads();                                // every thread has read s_krem
-#pragma unroll
-    for (int j = 0; j < BPT; ++j) {
-      if (before < krem && krem <= before + cnt[j]) {   // exactly one bin holds the cut-off
-        s_prefix = prefix | ((unsigned long long)(tid * BPT + j) << shift);
-        s_krem = krem - before;
-        s_done = (krem - before == cnt[j]);             // the whole bucket goes
+      for (int j = 0; j < 4; ++j) {
+        cnt[j] = hcur[4 * tid + j];
+        mine += cnt[j];
       }
-      before += cnt[j];
+      int before = wave_scan_incl(mine) - mine;
+      const int krem = s_krem;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (before < krem && krem <= before + cnt[j]) {   // exactly one bin holds the cut-off
+          s_prefix = prefix | ((unsigned long long)(4 * tid + j) << shift);
+          s_krem = krem - before;
+          s_done = (krem - before == cnt[j]);             // the whole bucket goes
+        }
+        before += cnt[j];
+      }
     }
     mask = ~0ull << shift;
     hi_bit = shift;
