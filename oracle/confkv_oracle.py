@@ -19,7 +19,9 @@ Readings of the paper taken here (each is listed again where it is used):
   * one importance value and one kept set per (layer, kv-head); the attention
     mass of a token is the SUM over the query heads that share the kv-head
     (the literal per-layer reading is the ``rank_scope = "layer"`` variant);
-  * INT8 scales are per token and per kv-head (absmax over the channels);
+  * INT8 scales are per token and per kv-head (absmax over the channels); the
+    paper's literal "per head and channel" wording is the ``scale_mode =
+    "channel"`` variant: one scale per (kv-head, channel), fixed from the prompt;
   * the new token is appended before its own attention and counts toward the
     cache length and the protected window;
   * the FP16 window holds the W newest *retained* tokens; nothing is promoted.
@@ -113,6 +115,41 @@ def dequantize(codes: np.ndarray, scale) -> np.ndarray:
     return codes.astype(F64) * np.asarray(scale, dtype=F64)[..., None]
 
 
+def channel_scales(x16: np.ndarray) -> np.ndarray:
+    """One fp16 scale per channel of a kv-head from a set of tokens x16 [T, D].
+
+    The paper's literal granularity ("per head and channel", s = max|x| / 127) leaves open
+    which tokens the maximum runs over; here it runs over the tokens given (the prompt) and
+    the scales stay fixed afterwards.  scale_d = fl16(fl32(max_t |x_{t,d}| / 127)); a
+    channel whose scale is zero or not finite gets scale 0 (its codes are all zero).
+    """
+    x16 = np.asarray(x16, dtype=np.float16)
+    D = x16.shape[1]
+    amax = np.max(np.abs(x16), axis=0) if x16.shape[0] else np.zeros(D, np.float16)
+    s = (amax.astype(np.float32) / np.float32(127.0)).astype(np.float16)
+    s[~np.isfinite(s)] = 0
+    return s
+
+
+def quantize_channels(x16: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """INT8 codes of one fp16 vector against fixed per-channel scales.
+
+    code_d = clamp(round_half_even(x_d / scale_d), -127, 127); a value beyond the range the
+    scales were fixed on saturates.  Channels with scale 0 get code 0.
+    """
+    x = np.asarray(x16, dtype=np.float16).astype(F64)
+    s = np.asarray(scales, dtype=np.float16).astype(F64)
+    live = s > 0
+    r = np.zeros(x.shape, dtype=F64)
+    r[live] = np.rint(x[live] / s[live])
+    return np.clip(r, -127, 127).astype(np.int8)
+
+
+def dequantize_channels(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """Stored value under per-channel scales: code_{t,d} * scale_d, float64."""
+    return codes.astype(F64) * np.asarray(scales, dtype=np.float16).astype(F64)[None, :]
+
+
 # --------------------------------------------------------------------------------------
 # Attention over a stored cache  ("Tiled attention and mixed precision")
 # --------------------------------------------------------------------------------------
@@ -180,6 +217,7 @@ class UnitCache:
 
     A slot is either FP16 (k16/v16 rows valid) or INT8 (k8/v8 codes with ks/vs scales).
     INT8 slots always precede FP16 slots because demotion takes the oldest FP16 token.
+    With per-channel scales (``kcs``/``vcs`` [D] set) the per-token ks/vs are unused.
     """
     head_dim: int
     pos: np.ndarray = field(default_factory=lambda: np.zeros(0, dtype=np.int64))
@@ -191,6 +229,8 @@ class UnitCache:
     v8: np.ndarray = None
     ks: np.ndarray = field(default_factory=lambda: np.zeros(0, dtype=np.float16))
     vs: np.ndarray = field(default_factory=lambda: np.zeros(0, dtype=np.float16))
+    kcs: Optional[np.ndarray] = None      # per-channel K scales [D] fp16, or None: per-token scales
+    vcs: Optional[np.ndarray] = None
 
     def __post_init__(self):
         D = self.head_dim
@@ -210,10 +250,12 @@ class UnitCache:
 
     def stored_k(self) -> np.ndarray:
         """Stored key values, float64 [n, D]: the fp16 value, or code * scale."""
-        return np.where(self.is16[:, None], self.k16.astype(F64), dequantize(self.k8, self.ks))
+        k8 = dequantize(self.k8, self.ks) if self.kcs is None else dequantize_channels(self.k8, self.kcs)
+        return np.where(self.is16[:, None], self.k16.astype(F64), k8)
 
     def stored_v(self) -> np.ndarray:
-        return np.where(self.is16[:, None], self.v16.astype(F64), dequantize(self.v8, self.vs))
+        v8 = dequantize(self.v8, self.vs) if self.vcs is None else dequantize_channels(self.v8, self.vcs)
+        return np.where(self.is16[:, None], self.v16.astype(F64), v8)
 
     def take(self, keep: np.ndarray) -> None:
         """Gather the slots ``keep`` (increasing) into contiguous storage: the compaction."""
@@ -224,14 +266,25 @@ class UnitCache:
         c = UnitCache(self.head_dim)
         for name in ("pos", "ema", "is16", "k16", "v16", "k8", "v8", "ks", "vs"):
             setattr(c, name, getattr(self, name).copy())
+        c.kcs = None if self.kcs is None else self.kcs.copy()
+        c.vcs = None if self.vcs is None else self.vcs.copy()
         return c
 
 
 def load_prefill(k16: np.ndarray, v16: np.ndarray, fp16_window: int,
-                 ema0: Optional[np.ndarray] = None) -> UnitCache:
-    """A unit holding T0 prefill tokens at positions 0..T0-1, EMA = ema0 or 0, then demoted."""
+                 ema0: Optional[np.ndarray] = None, scale_mode: str = "token") -> UnitCache:
+    """A unit holding T0 prefill tokens at positions 0..T0-1, EMA = ema0 or 0, then demoted.
+
+    ``scale_mode = "channel"`` fixes the unit's per-channel scales on all T0 prompt tokens
+    (those that stay FP16 included) before the demotion.
+    """
     T, D = k16.shape
     u = UnitCache(D)
+    if scale_mode == "channel":
+        u.kcs = channel_scales(k16)
+        u.vcs = channel_scales(v16)
+    elif scale_mode != "token":
+        raise ValueError(scale_mode)
     u.pos = np.arange(T, dtype=np.int64)
     u.ema = np.zeros(T, dtype=np.float32) if ema0 is None else np.asarray(ema0, np.float32).copy()
     u.is16 = np.ones(T, dtype=bool)
@@ -377,8 +430,12 @@ def demote(u: UnitCache, fp16_window: int) -> int:
     done = 0
     while u.n16 > fp16_window:
         i = int(np.argmax(u.is16))                 # oldest FP16 slot (INT8 slots come first)
-        u.k8[i], u.ks[i] = quantize_vector(u.k16[i])
-        u.v8[i], u.vs[i] = quantize_vector(u.v16[i])
+        if u.kcs is None:
+            u.k8[i], u.ks[i] = quantize_vector(u.k16[i])
+            u.v8[i], u.vs[i] = quantize_vector(u.v16[i])
+        else:
+            u.k8[i] = quantize_channels(u.k16[i], u.kcs)
+            u.v8[i] = quantize_channels(u.v16[i], u.vcs)
         u.k16[i] = 0
         u.v16[i] = 0
         u.is16[i] = False
