@@ -45,7 +45,8 @@ def attend_bytes_per_launch(wl, n8, n16):
     """
     D, G = wl.head_dim, wl.group
     n = n8 + n16
-    per_unit = n8 * (2 * D + 4) + n16 * 4 * D + 8 * n + 4 * G * D + 8 * D + 4
+    chan = getattr(wl, "scale_mode", "token") == "channel"     # then 2 x D fp16 scales per unit instead
+    per_unit = n8 * (2 * D + (0 if chan else 4)) + (4 * D if chan else 0) + n16 * 4 * D + 8 * n + 4 * G * D + 8 * D + 4
     return per_unit * wl.batch * wl.n_kv_heads
 
 
@@ -58,7 +59,7 @@ def step_bytes(wl, n8, n16, moved_bytes):
     logits = 4 * wl.vocab * wl.batch
     n = n8 + n16
     rank = 8 * max(0, n - wl.protected) * wl.units
-    demote = wl.units * (4 * D + 2 * D + 4)
+    demote = wl.units * (4 * D + 2 * D + (0 if getattr(wl, "scale_mode", "token") == "channel" else 4))
     return att + logits + rank + int(moved_bytes) + demote, att
 
 
@@ -82,7 +83,7 @@ def cpu_baseline(wl, seed, budget_s=15.0):
         while t_total < budget_s and done < 64:
             l, b, g = int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch)), int(rng.integers(wl.n_kv_heads))
             K, V = gen.prefill_unit(wl, seed, l, b, g)
-            u = O.load_prefill(K, V, wl.fp16_window)
+            u = O.load_prefill(K, V, wl.fp16_window, scale_mode=getattr(wl, "scale_mode", "token"))
             q, kn, vn = gen.step_inputs(wl, seed, l, 0)
             t0 = time.perf_counter()
             O.attend_unit(u, q[b, g * G:(g + 1) * G], kn[b, g], vn[b, g], wl.prefill, pol.sm_scale, pol.ema_decay)
@@ -172,6 +173,8 @@ def main():
     ap.add_argument("--steady", action="store_true",
                     help="multi-step workloads: load the prompt once and time K consecutive decode steps")
     ap.add_argument("--layers", type=int, default=0, help="keep only the first N layers (0 = all)")
+    ap.add_argument("--scales", choices=["token", "channel"], default="token",
+                    help="granularity of the INT8 scales (channel: the paper's literal per-(head, channel) reading)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device-to-device copy a few times and exit (counter calibration)")
     args = ap.parse_args()
@@ -198,6 +201,8 @@ def main():
     from synth.workloads import workload
 
     wl = workload(args.workload)
+    if args.scales != "token":
+        wl = wl.scaled(name=wl.name + "_" + args.scales + "_scales", scale_mode=args.scales)
     if args.layers and args.layers < wl.n_layers:
         wl = wl.scaled(n_layers=args.layers, n_tight=wl.n_tight[:args.layers], n_loose=wl.n_loose[:args.layers])
     L = wl.n_layers
@@ -273,11 +278,11 @@ def main():
         "config": {"workload": wl.name, "layers": L, "batch": wl.batch, "q_heads": wl.n_q_heads,
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "vocab": wl.vocab,
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
-                   "protected": wl.protected, "kv_storage": "int8+fp16", "attend_splits": kv.attend_splits(0),
+                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "attend_splits": kv.attend_splits(0),
                    "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
         "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel<4>" if wl.group > 1 and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload), "bytes_per_launch": att_bytes,
+                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload) if args.scales == "token" else None, "bytes_per_launch": att_bytes,
                      "launch_ms": att_launch_ms},
         "step_breakdown_ms": {"attend_x_layers": float(np.mean(t_att)), "confidence": float(np.mean(t_conf)),
                               "evict_compact": float(np.mean(t_evict))},

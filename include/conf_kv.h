@@ -78,7 +78,24 @@ typedef struct conf_kv_config {
   int32_t ranker;            /* conf_kv_ranker                                                 */
   int32_t rank_scope;        /* conf_kv_rank_scope                                             */
   uint64_t ranker_seed;      /* CONF_KV_RANKER_RANDOM: seed of its counter-based draws         */
+  int32_t scale_mode;        /* conf_kv_scale_mode: granularity of the INT8 scales             */
+  int32_t reserved0;         /* must be 0                                                      */
 } conf_kv_config;
+
+typedef enum conf_kv_scale_mode {
+  CONF_KV_SCALES_TOKEN = 0,     /* one scale per token and kv-head (absmax over the channels),
+                                   separately for K and V                                      */
+  CONF_KV_SCALES_CHANNEL = 1    /* the granularity "Tiled attention and mixed precision" names:
+                                   one scale per (kv-head, channel), separately for K and V,
+                                   s_d = fl16(fl32(max_t |x_{t,d}| / 127)) over ALL T0 prompt
+                                   tokens of conf_kv_load_prefill (those that stay FP16
+                                   included), fixed from then on; later tokens saturate at
+                                   +-127.  Attention folds the K scales into the query and the
+                                   V scales into the output.  Needs D = 128 and a mixed cache
+                                   (fp16_window >= 0); a layer must be given its scales
+                                   (conf_kv_load_prefill or conf_kv_import) before its first
+                                   conf_kv_evict_compact, else CONF_KV_ERR_BAD_STATE           */
+} conf_kv_scale_mode;
 
 typedef enum conf_kv_ranker {
   CONF_KV_RANKER_COMPOSITE = 0, /* s = alpha * minmax(mass) + (1 - alpha) * minmax(position)  */
@@ -132,7 +149,8 @@ int conf_kv_destroy(conf_kv_handle *h);
  * (Algorithm 1's input cache).  dev_k16 / dev_v16: fp16 [B][Hkv][T0][D].
  * dev_ema0: fp32 [B][Hkv][T0] initial EMA importance, or NULL for zeros.
  * All but the newest W tokens are quantised to INT8 ("Tiled attention and mixed
- * precision": symmetric, scale = max|x|/127, here per token and kv-head).
+ * precision": symmetric, scale = max|x|/127, per token and kv-head, or per kv-head and
+ * channel over the T0 prompt tokens: conf_kv_scale_mode).
  * 0 <= T0 <= capacity - 1, else CONF_KV_ERR_CAPACITY.  Enqueues on `stream`. */
 int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16,
                          const void *dev_v16, int32_t T0, const float *dev_ema0,
@@ -191,7 +209,8 @@ int conf_kv_lengths(conf_kv_handle *h, int32_t *host_len, int32_t *host_n16);
 /* Position-sorted view of one unit into host buffers sized for `capacity` slots; any
  * output pointer may be NULL.  pos int32 [n]; ema fp32 [n]; is_fp16 uint8 [n];
  * k16 / v16: fp16 bits [n][D] (zeros on INT8 slots); k8 / v8: int8 [n][D] (zeros on FP16
- * slots); k_scale / v_scale: fp16 bits [n] (zero on FP16 slots); *n_out = n. */
+ * slots); k_scale / v_scale: fp16 bits [n] (zero on FP16 slots), or the unit's channel scales
+ * [D] under CONF_KV_SCALES_CHANNEL (give room for max(capacity, D) values); *n_out = n. */
 int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head, int32_t *pos,
                    float *ema, uint8_t *is_fp16, uint16_t *k16, uint16_t *v16, int8_t *k8,
                    int8_t *v8, uint16_t *k_scale, uint16_t *v_scale, int32_t *n_out);
@@ -201,7 +220,8 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
  * pos int32 [n] strictly increasing; ema fp32 [n]; is_fp16 uint8 [n]: zeros (INT8 slots) then
  * ones (FP16 slots), at most fp16_window ones, all ones for an FP16-only cache; k16 / v16 fp16
  * bits [n][D], read on FP16 slots; k8 / v8 int8 [n][D] and k_scale / v_scale fp16 bits [n], read
- * on INT8 slots (a plane no slot reads may be NULL).  0 <= n <= capacity - 1
+ * on INT8 slots (a plane no slot reads may be NULL); under CONF_KV_SCALES_CHANNEL k_scale /
+ * v_scale are the unit's channel scales [D], always read, finite and >= 0.  0 <= n <= capacity - 1
  * (CONF_KV_ERR_CAPACITY); malformed views give CONF_KV_ERR_INVALID_ARG and leave the unit
  * unchanged.  Not allowed between conf_kv_attend of that layer and the next
  * conf_kv_evict_compact (CONF_KV_ERR_BAD_STATE).  The next token appended to the layer gets a

@@ -31,12 +31,13 @@ class ConfKVConfig(C.Structure):
         ("w_entropy", C.c_float), ("w_margin", C.c_float), ("w_top", C.c_float),
         ("n_tight", C.POINTER(C.c_int32)), ("n_loose", C.POINTER(C.c_int32)),
         ("mass_gain", C.c_float), ("ranker", C.c_int32), ("rank_scope", C.c_int32),
-        ("ranker_seed", C.c_uint64),
+        ("ranker_seed", C.c_uint64), ("scale_mode", C.c_int32), ("reserved0", C.c_int32),
     ]
 
 
 RANKERS = {"composite": 0, "random": 1}
 RANK_SCOPES = {"kv_head": 0, "layer": 1}
+SCALE_MODES = {"token": 0, "channel": 1}
 
 
 class ConfKVStats(C.Structure):
@@ -97,7 +98,7 @@ def strerror(status: int) -> str:
 def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacity, fp16_window,
                 protected_window, n_tight: Sequence[int], n_loose: Sequence[int], tau=0.7, alpha=0.65,
                 ema_decay=0.9, sm_scale=None, w_entropy=0.4, w_margin=0.3, w_top=0.3, mass_gain=None,
-                ranker="composite", rank_scope="kv_head", ranker_seed=0):
+                ranker="composite", rank_scope="kv_head", ranker_seed=0, scale_mode="token"):
     """A ConfKVConfig plus the two int32 arrays it points to (keep the tuple alive)."""
     nt = (C.c_int32 * len(n_tight))(*[int(x) for x in n_tight])
     nl = (C.c_int32 * len(n_loose))(*[int(x) for x in n_loose])
@@ -107,7 +108,7 @@ def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacit
                        fp16_window, protected_window, tau, alpha, ema_decay, sm_scale,
                        w_entropy, w_margin, w_top, nt, nl,
                        -1.0 if mass_gain is None else float(mass_gain), RANKERS[ranker],
-                       RANK_SCOPES[rank_scope], int(ranker_seed))
+                       RANK_SCOPES[rank_scope], int(ranker_seed), SCALE_MODES[scale_mode], 0)
     return cfg, nt, nl
 
 
@@ -195,7 +196,8 @@ class ConfKV:
         pos = np.zeros(cap, np.int32); ema = np.zeros(cap, np.float32); is16 = np.zeros(cap, np.uint8)
         k16 = np.zeros((cap, D), np.uint16); v16 = np.zeros((cap, D), np.uint16)
         k8 = np.zeros((cap, D), np.int8); v8 = np.zeros((cap, D), np.int8)
-        ks = np.zeros(cap, np.uint16); vs = np.zeros(cap, np.uint16)
+        chan = c.scale_mode == SCALE_MODES["channel"]       # then ks / vs are the channel scales [D]
+        ks = np.zeros(max(cap, D), np.uint16); vs = np.zeros(max(cap, D), np.uint16)
         n = C.c_int32(0)
         self._check(self.lib.conf_kv_export(self.h, layer, b, kv_head, pos.ctypes.data, ema.ctypes.data,
                                             is16.ctypes.data, k16.ctypes.data, v16.ctypes.data,
@@ -204,7 +206,7 @@ class ConfKV:
         m = n.value
         return dict(n=m, pos=pos[:m], ema=ema[:m], is16=is16[:m].astype(bool),
                     k16=k16[:m].view(np.float16), v16=v16[:m].view(np.float16), k8=k8[:m], v8=v8[:m],
-                    ks=ks[:m].view(np.float16), vs=vs[:m].view(np.float16))
+                    ks=ks[:D if chan else m].view(np.float16), vs=vs[:D if chan else m].view(np.float16))
 
     def import_unit(self, layer: int, b: int, kv_head: int, view: dict):
         """`view` is what export() returns (n, pos, ema, is16, k16, v16, k8, v8, ks, vs)."""
@@ -241,6 +243,6 @@ def from_workload(wl, **override) -> ConfKV:
               alpha=wl.alpha, ema_decay=wl.ema_decay, w_entropy=wl.w_entropy, w_margin=wl.w_margin,
               w_top=wl.w_top, mass_gain=getattr(wl, "mass_gain", None),
               ranker=getattr(wl, "ranker", "composite"), rank_scope=getattr(wl, "rank_scope", "kv_head"),
-              ranker_seed=getattr(wl, "ranker_seed", 0))
+              ranker_seed=getattr(wl, "ranker_seed", 0), scale_mode=getattr(wl, "scale_mode", "token"))
     kw.update(override)
     return ConfKV(**kw)

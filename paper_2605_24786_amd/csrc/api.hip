@@ -45,6 +45,9 @@ bool config_ok(const conf_kv_config *c) {
   if (!(c->mass_gain < 0.f) && !(c->mass_gain >= 0.f && c->mass_gain <= 1.0e6f)) return false;   // NaN
   if (c->ranker != CONF_KV_RANKER_COMPOSITE && c->ranker != CONF_KV_RANKER_RANDOM) return false;
   if (c->rank_scope != CONF_KV_SCOPE_KV_HEAD && c->rank_scope != CONF_KV_SCOPE_LAYER) return false;
+  if (c->scale_mode != CONF_KV_SCALES_TOKEN && c->scale_mode != CONF_KV_SCALES_CHANNEL) return false;
+  if (c->scale_mode == CONF_KV_SCALES_CHANNEL && (c->head_dim != 128 || c->fp16_window < 0)) return false;
+  if (c->reserved0 != 0) return false;
   for (int l = 0; l < c->n_layers; ++l) {
     if (c->n_tight[l] < 1 || c->n_tight[l] > c->n_loose[l]) return false;
     if (std::max(c->n_loose[l], c->protected_window) + 1 > c->capacity) return false;
@@ -79,8 +82,10 @@ StateLayout state_layout(const conf_kv_config *c) {
   s.n_loose = take((size_t)c->n_layers * 4);
   s.ema = take(U * cap * 4);
   s.pos = take(U * cap * 4);
-  s.ks = take(U * s.cap8 * 2);
-  s.vs = take(U * s.cap8 * 2);
+  // per-token scales [U][cap8], or per-channel scales [U][D]
+  const size_t scales = c->scale_mode == CONF_KV_SCALES_CHANNEL ? D : (size_t)s.cap8;
+  s.ks = take(U * scales * 2);
+  s.vs = take(U * scales * 2);
   s.k8 = take(U * s.cap8 * D);
   s.v8 = take(U * s.cap8 * D);
   s.k16 = take(U * s.cap16 * D * 2);
@@ -124,6 +129,7 @@ struct conf_kv_handle {
   std::vector<int32_t> len_ub;       // upper bound of the committed length
   std::vector<int32_t> next_pos;     // position the next appended token gets
   std::vector<uint8_t> appended;     // an append awaits its commit
+  std::vector<uint8_t> scaled;       // per unit: channel scales were given (channel mode)
   std::vector<uint32_t> epoch;       // attend launches so far, per layer (arrival-flag value)
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
@@ -174,6 +180,7 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->next_pos.assign(L, 0);
   h->appended.assign(L, 0);
   h->epoch.assign(L, 0u);
+  h->scaled.assign((size_t)L * cfg->batch * cfg->n_kv_heads, 0);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
   if (const char *tl = getenv("CONF_KV_TWO_LAUNCH")) h->force_two_launch = atoi(tl) != 0;
 
@@ -208,12 +215,15 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   cv.cap16 = h->sl.cap16;
   cv.W = cfg->fp16_window;
   cv.P = cfg->protected_window;
+  cv.chan = cfg->scale_mode == CONF_KV_SCALES_CHANNEL;
 
   std::vector<int32_t> budget((size_t)L * cfg->batch);
   for (int l = 0; l < L; ++l)
     for (int b = 0; b < cfg->batch; ++b) budget[(size_t)l * cfg->batch + b] = h->n_loose[l];
   hipError_t e = hipMemset(h->state, 0, h->sl.header_bytes);
   if (e == hipSuccess) e = hipMemset(h->scratch, 0, h->kl.zero_bytes);
+  if (e == hipSuccess && cv.chan)      // attention reads the channel scales even before any slot is INT8
+    e = hipMemset(cv.ks, 0, (size_t)((uint8_t *)cv.k8 - (uint8_t *)cv.ks));
   if (e == hipSuccess) e = hipMemcpy(cv.budget, budget.data(), budget.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy((void *)cv.n_tight, h->n_tight.data(), (size_t)L * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy((void *)cv.n_loose, h->n_loose.data(), (size_t)L * 4, hipMemcpyHostToDevice);
@@ -255,6 +265,8 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   h->len_ub[layer] = T0;
   h->next_pos[layer] = T0;
   h->appended[layer] = 0;
+  const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
+  std::fill(h->scaled.begin() + layer * UPL, h->scaled.begin() + (layer + 1) * UPL, (uint8_t)1);
   return CONF_KV_OK;
 }
 
@@ -262,7 +274,7 @@ static int plan_for_layer(conf_kv_handle *h, int layer, AttendPlan *plan) {
   const int n_ub = h->len_ub[layer] + 1;
   const int W = h->cfg.fp16_window;
   const int n16_ub = W < 0 ? n_ub : std::min(n_ub, W + 1);
-  if (!attend_plan(h->cfg.head_dim, h->cv.G, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
+  if (!attend_plan(h->cfg.head_dim, h->cv.G, h->cv.chan != 0, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
                    h->forced_splits, h->force_two_launch, plan))
     return CONF_KV_ERR_BAD_SHAPE;
   return CONF_KV_OK;
@@ -332,9 +344,13 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   if (!h) return CONF_KV_ERR_INVALID_ARG;
   LayerMask m{};
   int n_max = 0;
+  const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     if (h->appended[l]) m.set(l);
     n_max = std::max(n_max, h->len_ub[l] + (int)h->appended[l]);
+    if (h->cv.chan && h->len_ub[l] + (int)h->appended[l] > 0)     // a demotion needs the scales
+      for (size_t u = l * UPL; u < (l + 1) * UPL; ++u)
+        if (!h->scaled[u]) return CONF_KV_ERR_BAD_STATE;
   }
   RankOptions opt{};
   opt.random = h->cfg.ranker == CONF_KV_RANKER_RANDOM;
@@ -395,6 +411,10 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   const int n = len + h->appended[layer];
   const int n16 = n - n8;
   if (n_out) *n_out = n;
+  if (cv.chan) {                                      // the unit's channel scales, whatever its length
+    if (k_scale) CK_HIP(h, hipMemcpy(k_scale, cv.ks + u * D, D * 2, hipMemcpyDeviceToHost));
+    if (v_scale) CK_HIP(h, hipMemcpy(v_scale, cv.vs + u * D, D * 2, hipMemcpyDeviceToHost));
+  }
   if (n == 0) return CONF_KV_OK;
   const int firstm = std::min(n, cv.cap - head8);     // per-slot planes: entries before the wrap
   if (pos) {
@@ -434,7 +454,7 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
         CK_HIP(h, hipMemcpy(d8 + (size_t)first8 * D, p8, (size_t)(n8 - first8) * D, hipMemcpyDeviceToHost));
       memset(d8 + (size_t)n8 * D, 0, (size_t)n16 * D);
     }
-    if (dsc) {
+    if (dsc && !cv.chan) {
       if (first8 > 0)
         CK_HIP(h, hipMemcpy(dsc, psc + head8, (size_t)first8 * 2, hipMemcpyDeviceToHost));
       if (n8 > first8)
@@ -467,6 +487,13 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   if (cv.W < 0 ? n8 > 0 : n16 > cv.W) return CONF_KV_ERR_INVALID_ARG;
   if (n16 > cv.cap16) return CONF_KV_ERR_INVALID_ARG;
   if (n8 > 0 && (!k8 || !v8 || !k_scale || !v_scale)) return CONF_KV_ERR_INVALID_ARG;
+  if (cv.chan) {
+    if (!k_scale || !v_scale) return CONF_KV_ERR_INVALID_ARG;
+    for (int d = 0; d < cv.D; ++d)                                // fp16 bits: finite and >= 0
+      if ((k_scale[d] & 0x8000u) || (k_scale[d] & 0x7c00u) == 0x7c00u || (v_scale[d] & 0x8000u) ||
+          (v_scale[d] & 0x7c00u) == 0x7c00u)
+        return CONF_KV_ERR_INVALID_ARG;
+  }
   if (n16 > 0 && (!k16 || !v16)) return CONF_KV_ERR_INVALID_ARG;
   const size_t u = ((size_t)layer * cv.B + b) * cv.Hkv + kv_head;
   const size_t D = cv.D;
@@ -478,8 +505,15 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   if (n8 > 0) {                                                   // INT8 ring rows 0 .. n8-1
     CK_HIP(h, hipMemcpy(cv.k8 + u * cv.cap8 * D, k8, (size_t)n8 * D, hipMemcpyHostToDevice));
     CK_HIP(h, hipMemcpy(cv.v8 + u * cv.cap8 * D, v8, (size_t)n8 * D, hipMemcpyHostToDevice));
-    CK_HIP(h, hipMemcpy(cv.ks + u * cv.cap8, k_scale, (size_t)n8 * 2, hipMemcpyHostToDevice));
-    CK_HIP(h, hipMemcpy(cv.vs + u * cv.cap8, v_scale, (size_t)n8 * 2, hipMemcpyHostToDevice));
+    if (!cv.chan) {
+      CK_HIP(h, hipMemcpy(cv.ks + u * cv.cap8, k_scale, (size_t)n8 * 2, hipMemcpyHostToDevice));
+      CK_HIP(h, hipMemcpy(cv.vs + u * cv.cap8, v_scale, (size_t)n8 * 2, hipMemcpyHostToDevice));
+    }
+  }
+  if (cv.chan) {
+    CK_HIP(h, hipMemcpy(cv.ks + u * D, k_scale, D * 2, hipMemcpyHostToDevice));
+    CK_HIP(h, hipMemcpy(cv.vs + u * D, v_scale, D * 2, hipMemcpyHostToDevice));
+    h->scaled[u] = 1;
   }
   if (n16 > 0) {                                                  // FP16 ring rows 0 .. n16-1
     CK_HIP(h, hipMemcpy(cv.k16 + u * cv.cap16 * D, k16 + (size_t)n8 * D, (size_t)n16 * D * 2,

@@ -247,8 +247,12 @@ __device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slic
   const int c = lane % LPT, ts = lane / LPT;
   const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
   const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
-  const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
-  const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
+  // per-channel scales: the caller folded the K scales into qf and applies the V scales to the
+  // accumulator afterwards; every slot then has the factors (sm, 1).  The per-token loads stay
+  // branch-free on element 0 of the unit's scale plane.
+  const bool chan = cv.chan != 0;
+  const __half *KS = cv.ks + (size_t)sl.u * (chan ? D : cv.cap8);
+  const __half *VS = cv.vs + (size_t)sl.u * (chan ? D : cv.cap8);
   for (int base = sl.lo8; base < sl.hi8; base += TB * R8) {
     int4 kr[R8], vr[R8];
     unsigned short ksh[R8], vsh[R8];
@@ -263,8 +267,8 @@ __device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slic
       const int ic = ring_row_u(sl.h8, ok[r] ? i : sl.hi8 - 1, cv.cap8);
       kr[r] = *(const int4 *)(K8 + (size_t)ic * D + c * 16);
       vr[r] = *(const int4 *)(V8 + (size_t)ic * D + c * 16);
-      ksh[r] = ((const unsigned short *)KS)[ic];
-      vsh[r] = ((const unsigned short *)VS)[ic];
+      ksh[r] = ((const unsigned short *)KS)[chan ? 0 : ic];
+      vsh[r] = ((const unsigned short *)VS)[chan ? 0 : ic];
     }
     float s[R8][G], vf[R8][16];
 #pragma unroll
@@ -289,8 +293,8 @@ __device__ __forceinline__ void stream_int8_valu(const CacheView &cv, const Slic
 #pragma unroll
     for (int r = 0; r < R8; ++r) {
       const int i = base + r * TB + w * TW + ts;
-      const float f = __half2float(__ushort_as_half(ksh[r])) * sm;
-      vsc[r] = __half2float(__ushort_as_half(vsh[r]));
+      const float f = chan ? sm : __half2float(__ushort_as_half(ksh[r])) * sm;
+      vsc[r] = chan ? 1.f : __half2float(__ushort_as_half(vsh[r]));
 #pragma unroll
       for (int h = 0; h < G; ++h) {
         s[r][h] *= f;
@@ -614,7 +618,29 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   st.reset();
   float qf[G][16];
   load_q_slices<D, G>(cv, a, sl, qf);
-  stream_int8_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
+  if (cv.chan) {
+    // per-channel scales: fold the K scales of this lane's 16 channels into the query for the
+    // INT8 slots, scale the accumulated INT8 output by the V scales, reload the plain query
+    constexpr int LPT = D / 16;
+    const int c = (threadIdx.x & 63) % LPT;
+    float sc[16];
+    const int4 *kp = (const int4 *)(cv.ks + (size_t)sl.u * D + c * 16);
+    unpack_h16x16(kp[0], kp[1], sc);
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) qf[h][e] *= sc[e];
+    stream_int8_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
+    const int4 *vp = (const int4 *)(cv.vs + (size_t)sl.u * D + c * 16);
+    unpack_h16x16(vp[0], vp[1], sc);
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) st.acc[h][e] *= sc[e];
+    load_q_slices<D, G>(cv, a, sl, qf);
+  } else {
+    stream_int8_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
+  }
   stream_fp16_valu<D, G>(cv, sl, a.sm_scale, qf, st, stash, S);
   store_stream_partial<D, G>(st, threadIdx.x >> 6, wm, wl, wo + (threadIdx.x >> 6) * G * D);
   __syncthreads();
@@ -755,9 +781,12 @@ __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], i
   }
 }
 
-template <int G>
-__global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void attend_mfma_kernel(CacheView cv, AttendLaunch a,
-                                                                  int ns, int S) {
+// kChan: the INT8 scales are per (unit, channel).  The K scales are folded into the query (a
+// second A operand, split into an fp16 head and tail so the fold costs no accuracy), the V
+// scales multiply the output once, after the last INT8 tile; the FP16 slots then come last.
+template <int G, bool kChan = false>
+__global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(kChan ? 2 : 3, kChan ? 2 : 3)))
+void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   constexpr int D = 128;
   constexpr int NP = kAttWaves;                 // one partial per wavefront
   constexpr int kTileFloats =
@@ -779,8 +808,8 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
   const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
   const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
   const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
-  const __half *KS = cv.ks + (size_t)sl.u * cv.cap8;
-  const __half *VS = cv.vs + (size_t)sl.u * cv.cap8;
+  const __half *KS = cv.ks + (size_t)sl.u * (kChan ? D : cv.cap8);
+  const __half *VS = cv.vs + (size_t)sl.u * (kChan ? D : cv.cap8);
 
   const int ntiles = (sl.cnt8 + kTile - 1) / kTile;            // 0 when the split has no INT8 slot
   // One INT8 tile in flight: four 128-bit K pieces, four V pieces and the raw scale bits.
@@ -809,12 +838,16 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     t.v2 = *(const int4 *)(V8 + o2);
     t.k3 = *(const int4 *)(K8 + o3);
     t.v3 = *(const int4 *)(V8 + o3);
-    const unsigned j0 = (unsigned)ring_row_u(h8, min(base + t16, last), cap8);
-    const unsigned j1 = (unsigned)ring_row_u(h8, min(base + 16 + t16, last), cap8);
-    t.ks0 = ((const unsigned short *)KS)[j0];
-    t.vs0 = ((const unsigned short *)VS)[j0];
-    t.ks1 = ((const unsigned short *)KS)[j1];
-    t.vs1 = ((const unsigned short *)VS)[j1];
+    if constexpr (!kChan) {
+      const unsigned j0 = (unsigned)ring_row_u(h8, min(base + t16, last), cap8);
+      const unsigned j1 = (unsigned)ring_row_u(h8, min(base + 16 + t16, last), cap8);
+      t.ks0 = ((const unsigned short *)KS)[j0];
+      t.vs0 = ((const unsigned short *)VS)[j0];
+      t.ks1 = ((const unsigned short *)KS)[j1];
+      t.vs1 = ((const unsigned short *)VS)[j1];
+    } else {
+      t.ks0 = t.ks1 = t.vs0 = t.vs1 = 0;
+    }
     return t;
   };
   TileRegs tr = {};
@@ -845,6 +878,27 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       qa[s] = __builtin_bit_cast(half8_t, raw);
     }
   }
+  // Per-channel scales: A operand of the INT8 scores = q * s_k * 2^8 as head + tail in fp16
+  // (the power of two keeps the tail of every term that matters a normal number; it is taken
+  // back in the score factor), and this lane's eight V scales (channels 16 nt + t16).
+  constexpr float kFoldUp = 256.0f;
+  half8_t qh[kChan ? 4 : 1], ql[kChan ? 4 : 1];
+  float vch[kChan ? 8 : 1];
+  if constexpr (kChan) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const half8_t ksv = __builtin_bit_cast(half8_t, *(const int4 *)(KS + g4 * 32 + 8 * s));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float prod = (float)qa[s][e] * (float)ksv[e] * kFoldUp;
+        const _Float16 hi = (_Float16)prod;
+        qh[s][e] = hi;
+        ql[s][e] = (_Float16)(prod - (float)hi);
+      }
+    }
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) vch[nt] = __half2float(VS[16 * nt + t16]);
+  }
   floatx4_t O[8];
 #pragma unroll
   for (int nt = 0; nt < 8; ++nt) O[nt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
@@ -858,9 +912,12 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
 
   // ---------------- FP16 slots: 16-slot tiles on the matrix cores, taken first ----------------
   // (tiles go to the wavefronts from the back, which hold the fewest INT8 tiles; the first
-  // INT8 tile's loads are in flight meanwhile)
+  // INT8 tile's loads are in flight meanwhile).  With per-channel scales they come second.
   const int ntiles16 = (sl.hi16 - sl.lo16 + 15) / 16;
-  {
+  int tix = 0;
+#pragma unroll
+  for (int phase = 0; phase < 2; ++phase) {
+  if ((phase == 0) != kChan) {
     const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
     const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
     const int c16 = lane & 15, r4 = lane >> 4;   // load coordinates: 16-byte piece, row
@@ -930,8 +987,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       }
       wave_lds_sync();
     }
-  }
-  int tix = 0;
+  } else {
   for (int tile = w; tile < ntiles; tile += kAttWaves) {
     const int base = sl.lo8 + tile * kTile;
     if (tix < 6) TS(4 + 2 * tix);
@@ -955,10 +1011,10 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       *(unsigned *)(dst + 2 * kVRow) = o2;
       *(unsigned *)(dst + 3 * kVRow) = o3;
     }
-    const float kscale[2] = {__half2float(__ushort_as_half(tr.ks0)) * sm,
-                             __half2float(__ushort_as_half(tr.ks1)) * sm};
-    const float vscale[2] = {__half2float(__ushort_as_half(tr.vs0)),
-                             __half2float(__ushort_as_half(tr.vs1))};
+    const float kscale[2] = {kChan ? sm * (1.0f / kFoldUp) : __half2float(__ushort_as_half(tr.ks0)) * sm,
+                             kChan ? sm * (1.0f / kFoldUp) : __half2float(__ushort_as_half(tr.ks1)) * sm};
+    const float vscale[2] = {kChan ? 1.0f : __half2float(__ushort_as_half(tr.vs0)),
+                             kChan ? 1.0f : __half2float(__ushort_as_half(tr.vs1))};
     wave_lds_sync();
     if (tix < 6) TS(5 + 2 * tix);
     ++tix;
@@ -972,10 +1028,20 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
       const uint8_t *krow = Kt + (16 * sb + t16) * kKRow + g4 * 32;
       const int4 b0 = *(const int4 *)(krow), b1 = *(const int4 *)(krow + 16);
       floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (kChan) {
+        const half8_t kb[4] = {cvt_i8x8_f16x8(b0.x, b0.y), cvt_i8x8_f16x8(b0.z, b0.w),
+                               cvt_i8x8_f16x8(b1.x, b1.y), cvt_i8x8_f16x8(b1.z, b1.w)};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ql[s], kb[s], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qh[s], kb[s], acc, 0, 0, 0);
+        }
+      } else {
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[0], cvt_i8x8_f16x8(b0.x, b0.y), acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[1], cvt_i8x8_f16x8(b0.z, b0.w), acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[2], cvt_i8x8_f16x8(b1.x, b1.y), acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[3], cvt_i8x8_f16x8(b1.z, b1.w), acc, 0, 0, 0);
+      }
       const bool valid = base + 16 * sb + t16 < sl.hi8;
       float z[NV];
       regroup_rows<G>(acc, z);
@@ -1041,6 +1107,20 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(3, 
     }
     wave_lds_sync();
   }
+  if constexpr (kChan) {
+    // the INT8 part is complete: take the code bias out and go from code units to values
+    float pb[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) { pb[j] = row16_sum(pbias[j]) * kCodeBias; pbias[j] = 0.f; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float bias = rows_to_tile<G>(pb, i, g4);
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) O[nt][i] = (O[nt][i] - bias) * vch[nt];
+    }
+  }
+  }  // INT8 phase
+  }  // phases
   TS(16);
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
@@ -1099,23 +1179,20 @@ static AttendFn attend_fn_spill(int D, int G, bool finish) {
   return nullptr;
 }
 
-static AttendFn attend_fn_mfma(int D, int G) {
+static AttendFn attend_fn_mfma(int D, int G, bool chan) {
   if (D != 128) return nullptr;
+#define CONFKV_CASE(g) \
+  case g: return chan ? (AttendFn)attend_mfma_kernel<g, true> : (AttendFn)attend_mfma_kernel<g, false>;
   switch (G) {
-    case 2: return attend_mfma_kernel<2>;
-    case 3: return attend_mfma_kernel<3>;
-    case 4: return attend_mfma_kernel<4>;
-    case 5: return attend_mfma_kernel<5>;
-    case 6: return attend_mfma_kernel<6>;
-    case 7: return attend_mfma_kernel<7>;
-    case 8: return attend_mfma_kernel<8>;
+    CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
     default: return nullptr;
   }
+#undef CONFKV_CASE
 }
 
 // The matrix-core kernel serves grouped-query shapes whose units hold INT8 slots.
 static bool wants_mfma(int D, int G, bool has_int8) {
-  return g_use_mfma && has_int8 && attend_fn_mfma(D, G) != nullptr;
+  return g_use_mfma && has_int8 && attend_fn_mfma(D, G, false) != nullptr;
 }
 
 bool attend_supported(int D, int G) { return attend_fn_valu(D, G) != nullptr; }
@@ -1176,12 +1253,12 @@ static int attend_occupancy(AttendFn fn, size_t lds) {
   return nb;
 }
 
-bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
+bool attend_plan(int D, int G, bool chan, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
                  bool force_two_launch, AttendPlan *plan) {
   const DeviceLimits &lim = device_limits();
   if (!lim.ok || !attend_fn_valu(D, G)) return false;
   const bool mfma = wants_mfma(D, G, n16_ub < n_ub);
-  AttendFn fn = mfma ? attend_fn_mfma(D, G) : attend_fn_valu(D, G);
+  AttendFn fn = mfma ? attend_fn_mfma(D, G, chan) : attend_fn_valu(D, G);
   const long long nv = (long long)n_ub + n16_ub;
   // One workgroup per CU measured best: the exchange between the splits of a unit (arrival
   // counter, partial gather) gets slower with more participants, and a grid that is not a
@@ -1258,7 +1335,7 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                        plan.stash_tokens);
     return hipGetLastError();
   }
-  AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, cv.G) : attend_fn_valu(cv.D, cv.G);
+  AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, cv.G, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                      plan.stash_tokens);

@@ -18,7 +18,8 @@ enum StatSlot { kStatEvicted = 0, kStatDemoted = 1, kStatTight = 2, kStatLoose =
 // All planes of the cache, for every unit u = (layer * B + b) * Hkv + kv_head.
 //   k8, v8   int8  [U][cap8][D]   INT8 ring; slot i < n8[u] lives in ring row
 //                                 (head8[u] + i) mod cap8
-//   ks, vs   fp16  [U][cap8]      per-token scales of those rows (same ring index)
+//   ks, vs   fp16  [U][cap8]      per-token scales of those rows (same ring index); with
+//                                 per-channel scales (chan != 0): [U][D], one scale per channel
 //   k16, v16 fp16  [U][cap16][D]  FP16 ring; slot i >= n8[u] lives in ring row
 //                                 (head16[u] + i - n8[u]) mod cap16
 //   ema      fp32  [U][cap]       EMA of attention mass; slot i lives at (head8[u] + i) mod cap
@@ -41,6 +42,7 @@ struct CacheView {
   unsigned *unit_evicted, *unit_demoted;   // [U] per-unit event counts
   unsigned long long *unit_moved;          // [U] per-unit compaction traffic
   int32_t L, B, Hkv, G, D, cap, cap8, cap16, W, P;
+  int32_t chan;                            // INT8 scales are per (unit, channel), not per token
 };
 
 // One bit per layer: did conf_kv_attend append a token since the last commit?

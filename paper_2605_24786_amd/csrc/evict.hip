@@ -58,6 +58,68 @@ __device__ __forceinline__ void quantize_row_wave(const __half *__restrict__ src
   if (lane == 0) *dst_scale = dead ? __float2half_rn(0.f) : hs;
 }
 
+// The same with fixed per-channel scales ("Tiled attention and mixed precision": per head and
+// channel): code_d = clamp(rint(x_d / s_d), -127, 127); a channel whose scale is 0 gets code 0.
+template <int D>
+__device__ __forceinline__ void quantize_row_channels(const __half *__restrict__ src,
+                                                      int8_t *__restrict__ dst_codes,
+                                                      const __half *__restrict__ scales, int lane) {
+  constexpr int EPL = D / kWave;
+  static_assert(EPL == 2, "per-channel scales are built for D = 128");
+  const __half2 v = ((const __half2 *)src)[lane];
+  const __half2 sc = ((const __half2 *)scales)[lane];
+  const float x[2] = {__low2float(v), __high2float(v)};
+  const float sf[2] = {__low2float(sc), __high2float(sc)};
+  int code[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    float r = (sf[e] > 0.f) ? rintf(__fdiv_rn(x[e], sf[e])) : 0.f;
+    r = fminf(fmaxf(r, -127.f), 127.f);
+    code[e] = (int)r;
+  }
+  ((unsigned short *)dst_codes)[lane] = (unsigned short)((code[0] & 0xff) | ((code[1] & 0xff) << 8));
+}
+
+// ---------------------------------------------------------------------------------------
+// Channel scales of a prompt: grid (B * Hkv, 2), plane 0 = K, 1 = V; 1024 threads.  Thread t
+// owns the 8 channels of 16-byte piece t % 16 on the rows t / 16, t / 16 + 64, ...;
+// scale_d = fl16(fl32(max_t |x_{t,d}| / 127)), 0 when that is not finite.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void channel_scales_kernel(CacheView cv, int layer,
+                                                              const __half *__restrict__ k16,
+                                                              const __half *__restrict__ v16, int T0) {
+  constexpr int D = 128, PIECES = D / 8, ROWS = 1024 / PIECES;
+  __shared__ unsigned short part[ROWS][D];
+  const int ul = blockIdx.x, tid = threadIdx.x;
+  const int u = layer * cv.B * cv.Hkv + ul;
+  const int c = tid % PIECES, r0 = tid / PIECES;
+  const __half *src = (blockIdx.y ? v16 : k16) + (size_t)ul * T0 * D;
+  // |x| as fp16 bits with the sign cleared: for finite values and infinities the bit patterns
+  // order like the magnitudes, so the maximum is taken on 16-bit integers
+  unsigned short m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int t = r0; t < T0; t += ROWS) {
+    const int4 raw = *(const int4 *)(src + (size_t)t * D + c * 8);
+    const unsigned w[4] = {(unsigned)raw.x, (unsigned)raw.y, (unsigned)raw.z, (unsigned)raw.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      m[2 * e] = max(m[2 * e], (unsigned short)(w[e] & 0x7fffu));
+      m[2 * e + 1] = max(m[2 * e + 1], (unsigned short)((w[e] >> 16) & 0x7fffu));
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[r0][c * 8 + e] = m[e];
+  __syncthreads();
+  if (tid < D) {
+    unsigned short best = 0;
+    for (int r = 0; r < ROWS; ++r) best = max(best, part[r][tid]);
+    const float amax = __half2float(__ushort_as_half(best));      // NaN patterns stay NaN
+    const __half hs = __float2half_rn(__fdiv_rn(amax, 127.0f));
+    const float sf = __half2float(hs);
+    const bool dead = !(sf > 0.f) || isinf(sf);
+    ((blockIdx.y ? cv.vs : cv.ks) + (size_t)u * D)[tid] = dead ? __float2half_rn(0.f) : hs;
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Prompt loader: grid (ceil(T0 / 4), B * Hkv), one wavefront per token.
 // ---------------------------------------------------------------------------------------
@@ -84,6 +146,13 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
     cv.ema[(size_t)u * cv.cap + t] = ema0 ? ema0[(size_t)ul * T0 + t] : 0.f;
   }
   if (t < n8) {
+    if constexpr (D == 128) {
+      if (cv.chan) {                              // scales were fixed by channel_scales_kernel
+        quantize_row_channels<D>(ksrc, cv.k8 + ((size_t)u * cv.cap8 + t) * D, cv.ks + (size_t)u * D, lane);
+        quantize_row_channels<D>(vsrc, cv.v8 + ((size_t)u * cv.cap8 + t) * D, cv.vs + (size_t)u * D, lane);
+        return;
+      }
+    }
     quantize_row_wave<D>(ksrc, cv.k8 + ((size_t)u * cv.cap8 + t) * D, cv.ks + (size_t)u * cv.cap8 + t, lane);
     quantize_row_wave<D>(vsrc, cv.v8 + ((size_t)u * cv.cap8 + t) * D, cv.vs + (size_t)u * cv.cap8 + t, lane);
   } else {
@@ -181,7 +250,8 @@ __device__ __forceinline__ void write_selection(const CacheView &cv, int u, int3
       rows8 = right ? right_rows : left_rows;
       rows16 = (evicted > e8) ? n_new - max(first_hole, n8_new) : 0;
     }
-    cv.unit_moved[u] += 2ull * (unsigned long long)(rows8 * (2 * cv.D + 4) + rows16 * 4 * cv.D + meta * 8);
+    const int scale_bytes = cv.chan ? 0 : 4;           // per-token scales travel with their rows
+    cv.unit_moved[u] += 2ull * (unsigned long long)(rows8 * (2 * cv.D + scale_bytes) + rows16 * 4 * cv.D + meta * 8);
   }
 }
 
@@ -872,7 +942,7 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
         if (k < cnt) {
           fa[p] = ema[from[p]];
           fp[p] = pos[from[p]];
-          if ((right ? hi - 1 - k : lo + k) < n8_new) {
+          if (!cv.chan && (right ? hi - 1 - k : lo + k) < n8_new) {
             fk[p] = ((const unsigned short *)ks)[from[p]];
             fv[p] = ((const unsigned short *)vs)[from[p]];
           }
@@ -887,7 +957,7 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
           const int d = ring_row(h0_new, j, cap);
           ema[d] = fa[p];
           pos[d] = fp[p];
-          if (j < n8_new) {
+          if (!cv.chan && j < n8_new) {
             ((unsigned short *)ks)[d] = fk[p];
             ((unsigned short *)vs)[d] = fv[p];
           }
@@ -924,6 +994,13 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
   for (int t = 0; t < cnt; ++t) {
     const int row = ring_row(h16, t, cv.cap16);
     const size_t dst = (size_t)u * cv.cap8 + ring_row(h8, n8_new + t, cv.cap8);
+    if constexpr (D == 128) {
+      if (cv.chan) {
+        quantize_row_channels<D>(cv.k16 + ((size_t)u * cv.cap16 + row) * D, cv.k8 + dst * D, cv.ks + (size_t)u * D, lane);
+        quantize_row_channels<D>(cv.v16 + ((size_t)u * cv.cap16 + row) * D, cv.v8 + dst * D, cv.vs + (size_t)u * D, lane);
+        continue;
+      }
+    }
     quantize_row_wave<D>(cv.k16 + ((size_t)u * cv.cap16 + row) * D, cv.k8 + dst * D, cv.ks + dst, lane);
     quantize_row_wave<D>(cv.v16 + ((size_t)u * cv.cap16 + row) * D, cv.v8 + dst * D, cv.vs + dst, lane);
   }
@@ -943,6 +1020,8 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
 hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
                                int T0, const float *ema0, hipStream_t stream) {
   dim3 grid((T0 + 3) / 4 > 0 ? (T0 + 3) / 4 : 1, cv.B * cv.Hkv);
+  if (cv.chan)      // D = 128 by construction of the handle
+    hipLaunchKernelGGL(channel_scales_kernel, dim3(cv.B * cv.Hkv, 2), dim3(1024), 0, stream, cv, layer, k16, v16, T0);
   if (cv.D == 64)
     hipLaunchKernelGGL(load_prefill_kernel<64>, grid, dim3(kEvThreads), 0, stream, cv, layer, k16, v16, T0, ema0);
   else

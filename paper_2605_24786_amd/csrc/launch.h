@@ -43,7 +43,7 @@ bool attend_supported(int D, int G);
 size_t attend_spill_floats(int units_per_layer, int G, int cap);   // scratch the two-launch form needs
 // Largest split count and LDS plan for a unit of at most n_ub tokens (after the append)
 // of which at most n16_ub are FP16.  Returns false when no plan fits the device.
-bool attend_plan(int D, int G, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
+bool attend_plan(int D, int G, bool chan, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
                  bool force_two_launch, AttendPlan *plan);
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream);

@@ -42,6 +42,7 @@ class Workload:
     ranker: str = "composite"            # or "random"
     rank_scope: str = "kv_head"          # or "layer"
     ranker_seed: int = 0
+    scale_mode: str = "token"            # or "channel": INT8 scales per (kv-head, channel)
     # input recipe
     heavy_hitter_prob: float = 0.02      # fraction of key positions shifted by +3 u
     heavy_hitter_gain: float = 3.0

@@ -91,7 +91,8 @@ class Lockstep:
                 for (ul, b, g) in self.units:
                     if ul == l:
                         ounits[(l, b, g)] = O.load_prefill(K[b, g], V[b, g], wl.fp16_window,
-                                                           None if e0 is None else e0[b, g])
+                                                           None if e0 is None else e0[b, g],
+                                                           scale_mode=getattr(wl, "scale_mode", "token"))
         torch.cuda.synchronize()
         self.run = O.OracleRun(policy_of(wl), ounits, wl.prefill)
         self.t = 0
@@ -115,9 +116,13 @@ class Lockstep:
                     f"{tag}: {name} payload bits differ"
             for name in ("k8", "v8"):
                 assert np.array_equal(ex[name][m8], getattr(u, name)[m8]), f"{tag}: {name} codes differ"
-            for name in ("ks", "vs"):
-                assert np.array_equal(ex[name][m8].view(np.uint16), getattr(u, name)[m8].view(np.uint16)), \
-                    f"{tag}: {name} scales differ"
+            if u.kcs is not None:
+                assert np.array_equal(ex["ks"].view(np.uint16), u.kcs.view(np.uint16)), f"{tag}: K channel scales differ"
+                assert np.array_equal(ex["vs"].view(np.uint16), u.vcs.view(np.uint16)), f"{tag}: V channel scales differ"
+            else:
+                for name in ("ks", "vs"):
+                    assert np.array_equal(ex[name][m8].view(np.uint16), getattr(u, name)[m8].view(np.uint16)), \
+                        f"{tag}: {name} scales differ"
             ref = u.ema.astype(np.float64)
             err = np.abs(ex["ema"].astype(np.float64) - ref)
             bound = EMA_ATOL + EMA_RTOL * np.abs(ref)

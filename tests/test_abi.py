@@ -52,6 +52,9 @@ def test_buffer_sizes(clib):
     U, cap, D = 4, 256, 128
     payload = U * (cap * (2 * D + 4 + 8) + 32 * 2 * D * 2)      # INT8 rows + scales + meta + FP16 ring
     assert payload <= sb <= payload + 64 * 1024 and sb % 256 == 0 and kb > 0
+    cfgc, *_ = _cfg(scale_mode="channel")                        # per-channel scales: [U][D], not [U][cap]
+    sbc = clib.conf_kv_state_bytes(C.byref(cfgc))
+    assert 0 < sbc < sb and sb - sbc >= U * (cap - D) * 4 - 4 * 256
     cfg16, *_ = _cfg(fp16_window=-1)                             # FP16-only: no INT8 planes
     sb16 = clib.conf_kv_state_bytes(C.byref(cfg16))
     assert U * cap * (4 * D + 8) <= sb16 <= U * cap * (4 * D + 8) + 64 * 1024
@@ -61,7 +64,9 @@ def test_buffer_sizes(clib):
                                  dict(capacity=100), dict(capacity=128), dict(vocab=1), dict(alpha=1.5),
                                  dict(n_tight=[200, 64]), dict(protected_window=-1), dict(n_layers=0),
                                  dict(ema_decay=-0.1), dict(mass_gain=float("nan")), dict(_ranker=2),
-                                 dict(_rank_scope=-1)])
+                                 dict(_rank_scope=-1), dict(_scale_mode=2), dict(_reserved0=1),
+                                 dict(scale_mode="channel", head_dim=64),
+                                 dict(scale_mode="channel", fp16_window=-1)])
 def test_bad_configs_are_rejected(clib, bad):
     kw = dict(bad)
     if "n_layers" in kw:

@@ -76,6 +76,24 @@ def test_full_size_workload(lib, idx):
     ls.close()
 
 
+def test_full_size_channel_scales(lib):
+    """The roofline workload's shape with INT8 scales per (kv-head, channel): 4 of its layers,
+    the prompt calibration over 4096 tokens, the first step's large eviction and demotion."""
+    wl = workload(1).scaled(name="llama3_8b_b8_t4096_channel_scales", n_layers=4, n_tight=(1024,) * 4,
+                            n_loose=(2048,) * 4, steps=3, scale_mode="channel", logit_std=(0.5, 6.0), logit_run=1)
+    print(f"channel scales at full size: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=0, units=6, threads=16)
+    for t in range(wl.steps):
+        ls.step()
+        _invariants_all_units(ls, wl, t)
+        print(f"  step {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    print(f"  ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} flips={rep.evict_flips}/{rep.budget_flips}", flush=True)
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 def test_needle_retention_full_size(lib):
     """Retrieval stress at full cache length (one layer): every planted needle survives the
     32769 -> 4096 eviction after the first probe step, on every unit of the layer."""

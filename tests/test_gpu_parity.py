@@ -127,8 +127,10 @@ def test_prefill_quantiser_bit_exact(lib, torch_cuda, D, W, T0):
 
 # ------------------------------------------------------------------ attention + mass EMA
 
-def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_launch=False):
-    say(f"attend D={D} G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} two_launch={two_launch}")
+def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_launch=False,
+                 scale_mode="token", late_gain=1.0):
+    say(f"attend D={D} G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} two_launch={two_launch} "
+        f"scales={scale_mode}")
     if splits:
         os.environ["CONF_KV_SPLITS"] = str(splits)
     else:
@@ -138,7 +140,7 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_l
     try:
         cap = ((T0 + 8 + 63) // 64) * 64
         kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
-                 protected_window=4, n_tight=[cap - 2], n_loose=[cap - 1])
+                 protected_window=4, n_tight=[cap - 2], n_loose=[cap - 1], scale_mode=scale_mode)
     finally:
         os.environ.pop("CONF_KV_SPLITS", None)
         os.environ.pop("CONF_KV_TWO_LAUNCH", None)
@@ -146,15 +148,22 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_l
     rng = np.random.default_rng(seed)
     K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
     V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    if scale_mode == "channel":
+        # channels of very different ranges (what per-channel scales are for), one dead channel
+        K = (K * rng.choice([0.05, 0.3, 1.0, 4.0], size=(B, H, 1, D))).astype(np.float16)
+        V = (V * rng.choice([0.05, 0.3, 1.0, 4.0], size=(B, H, 1, D))).astype(np.float16)
+        K[..., 5] = 0
+        V[..., 17] = 0
     e0 = rng.random((B, H, T0)).astype(np.float32)
     kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(), torch.from_numpy(e0).cuda())
-    units = {(b, g): O.load_prefill(K[b, g], V[b, g], W, e0[b, g]) for b in range(B) for g in range(H)}
+    units = {(b, g): O.load_prefill(K[b, g], V[b, g], W, e0[b, g], scale_mode=scale_mode)
+             for b in range(B) for g in range(H)}
     out = torch.zeros((B, G * H, D), dtype=torch.float16, device="cuda")
     sm, lam = f32(1 / math.sqrt(D)), f32(0.9)
     for t in range(3):
         q = (rng.standard_normal((B, G * H, D)) * scale_q).astype(np.float16)
-        kn = rng.standard_normal((B, H, D)).astype(np.float16)
-        vn = rng.standard_normal((B, H, D)).astype(np.float16)
+        kn = (rng.standard_normal((B, H, D)) * late_gain).astype(np.float16)   # late_gain > 1: codes saturate
+        vn = (rng.standard_normal((B, H, D)) * late_gain).astype(np.float16)
         kv.attend(0, torch.from_numpy(q).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda(), out)
         got = out.cpu().numpy().astype(np.float64)
         for (b, g), u in units.items():
@@ -169,8 +178,14 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_l
             e_err = np.abs(ex["ema"].astype(np.float64) - e_ref)
             assert np.all(e_err <= 1e-7 + 2e-5 * e_ref), f"step {t} unit {(b, g)}: EMA off, max rel {np.max(e_err / (e_ref + 1e-30)):.3g}"
         kv.evict_compact()                          # budgets above the length: commit + demotion only
-        for u in units.values():
+        for (b, g), u in units.items():
             O.demote(u, W)
+            if scale_mode == "channel":
+                ex = kv.export(0, b, g)
+                m8 = ~u.is16
+                assert np.array_equal(ex["k8"][m8], u.k8[m8]) and np.array_equal(ex["v8"][m8], u.v8[m8])
+                assert np.array_equal(ex["ks"].view(np.uint16), u.kcs.view(np.uint16))
+                assert np.array_equal(ex["vs"].view(np.uint16), u.vcs.view(np.uint16))
     assert kv.counters().evicted == 0
     kv.close()
 
@@ -205,6 +220,27 @@ def test_attend_two_launch_form(lib, torch_cuda, D, G, H, B, T0, W, splits):
     """The form used when the splits of a unit cannot all be resident: scores and partials go
     through scratch and a second kernel finishes.  Forced here on small shapes."""
     _attend_case(lib, torch_cuda, D, G, H, B, T0, W, splits, seed=T0 + G, two_launch=True)
+
+
+@pytest.mark.parametrize("G,H,B,T0,W,splits,two_launch", [
+    (4, 2, 2, 777, 40, 0, False),      # matrix-core body, default plan
+    (4, 1, 1, 1500, 128, 7, False),    # ragged splits across the INT8 / FP16 boundary
+    (5, 2, 1, 600, 24, 3, False), (8, 1, 1, 260, 16, 2, False), (2, 1, 1, 300, 0, 2, False),
+    (3, 2, 1, 333, 20, 1, False), (7, 1, 2, 411, 48, 2, False), (6, 1, 1, 190, 8, 0, False),
+    (1, 2, 1, 500, 16, 3, False),      # G = 1: vector-ALU body
+    (4, 2, 2, 700, 32, 3, True), (1, 1, 1, 300, 8, 2, True), (5, 1, 1, 900, 64, 5, True),
+    (4, 1, 1, 5, 2, 0, False),         # a tiny cache
+])
+def test_attend_channel_scales(lib, torch_cuda, G, H, B, T0, W, splits, two_launch):
+    """INT8 scales per (kv-head, channel), fixed on the prompt and folded into the query and the
+    output ("Tiled attention and mixed precision"); late tokens three times the prompt's range
+    saturate when they are demoted."""
+    _attend_case(lib, torch_cuda, 128, G, H, B, T0, W, splits, seed=7 * G + T0, two_launch=two_launch,
+                 scale_mode="channel", late_gain=3.0)
+
+
+def test_attend_channel_scales_sharp_softmax(lib, torch_cuda):
+    _attend_case(lib, torch_cuda, 128, 4, 1, 1, 900, 32, 6, seed=5, scale_q=6.0, scale_mode="channel")
 
 
 def test_attend_sharp_softmax(lib, torch_cuda):
@@ -320,7 +356,7 @@ def test_lockstep_small_workloads(lib, torch_cuda, idx):
     ls.close()
 
 
-def _expected_moves(pre, gone_pos, D, fp16_only):
+def _expected_moves(pre, gone_pos, D, fp16_only, scale_bytes=4):
     """What the compaction has to move for one unit: (right shift?, head advance, bytes read +
     written).  Holes close from the side with fewer rows; the head-side shift is open when all
     holes lie in one payload ring (all INT8 in a mixed cache, any in an FP16-only one)."""
@@ -342,7 +378,7 @@ def _expected_moves(pre, gone_pos, D, fp16_only):
     else:
         rows8 = right_rows if right else left_rows
         rows16 = n_new - max(first, n8_new) if e > e8 else 0
-    return right, (adv if right else 0), 2 * (rows8 * (2 * D + 4) + rows16 * 4 * D + meta * 8)
+    return right, (adv if right else 0), 2 * (rows8 * (2 * D + scale_bytes) + rows16 * 4 * D + meta * 8)
 
 
 @pytest.mark.parametrize("G,D,W,alpha", [(4, 128, 8, 0.1), (1, 64, 8, 0.65), (5, 128, 8, 0.9), (1, 128, 8, 0.9),
@@ -386,6 +422,80 @@ def test_lockstep_long_run_wraps_the_rings(lib, torch_cuda, G, D, W, alpha):
     assert st.device_errors == 0 and (W < 0 or st.demoted > 2 * wl.capacity)
     assert st.compact_bytes == moved_bytes, (st.compact_bytes, moved_bytes)
     ls.close()
+
+
+@pytest.mark.parametrize("G,W,alpha,steps", [(4, 8, 0.1, 400), (1, 8, 0.9, 300), (5, 30, 0.65, 300)])
+def test_lockstep_channel_scales(lib, torch_cuda, G, W, alpha, steps):
+    """Whole decode steps with per-(kv-head, channel) INT8 scales: prompt calibration, eviction,
+    ring compaction in both directions (the scales do not travel with the rows) and demotion
+    against the fixed scales, bit-exact against the oracle."""
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=128, vocab=3001,
+                         prefill=100, steps=steps, n_tight=(97, 80), n_loose=(104, 100), protected=8,
+                         fp16_window=W, logit_std=(0.5, 6.0), logit_run=7, alpha=alpha, scale_mode="channel")
+    say(f"channel scales lockstep: G={G} W={W} alpha={alpha}")
+    ls = Lockstep(lib, wl, seed=23)
+    moved_bytes = 0
+    for t in range(wl.steps):
+        ls.step(check_state=(t % 3 == 0 or t > wl.steps - 10))
+        for key, gone_pos in ls.last_gone.items():
+            if gone_pos.size:
+                moved_bytes += _expected_moves(ls.last_before[key], gone_pos, 128, False, scale_bytes=0)[2]
+    rep = ls.report
+    st = ls.kv.counters()
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"flips={rep.evict_flips}/{rep.budget_flips} demoted={st.demoted}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.evictions > 0 and st.demoted > 0 and st.device_errors == 0
+    assert st.compact_bytes == moved_bytes, (st.compact_bytes, moved_bytes)
+    ls.close()
+
+
+def test_channel_scales_need_calibration_and_round_trip(lib, torch_cuda):
+    torch = torch_cuda
+    D, G, H = 128, 4, 2
+    kw = dict(n_q_heads=G * H, n_kv_heads=H, fp16_window=4, capacity=64, protected_window=4,
+              n_tight=[40], n_loose=[50], scale_mode="channel")
+    a = _mk(lib, **kw)
+    rng = np.random.default_rng(9)
+    out = torch.zeros((1, G * H, D), dtype=torch.float16, device="cuda")
+    q = torch.from_numpy(rng.standard_normal((1, G * H, D)).astype(np.float16)).cuda()
+    kn = torch.from_numpy(rng.standard_normal((1, H, D)).astype(np.float16)).cuda()
+    a.attend(0, q, kn, kn, out)                     # an empty cache: the query sees only itself
+    assert np.allclose(out.cpu().numpy()[0, :G].astype(np.float64), kn.cpu().numpy()[0, 0].astype(np.float64))
+    with pytest.raises(lib.ConfKVError) as ei:      # no scales were ever given to this layer
+        a.evict_compact()
+    assert ei.value.status == lib.binding.ERR_BAD_STATE
+    a.close()
+    # hand a calibrated cache over to a second handle and keep decoding on both
+    a = _mk(lib, **kw)
+    b = _mk(lib, **kw)
+    K = (rng.standard_normal((1, H, 30, D)) * rng.choice([0.1, 1.0, 5.0], size=(1, H, 1, D))).astype(np.float16)
+    a.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(K[:, :, ::-1].copy()).cuda())
+    for g in range(H):
+        view = a.export(0, 0, g)
+        assert view["ks"].shape == (D,) and view["n"] == 30
+        b.import_unit(0, 0, g, view)
+        bad = dict(view)
+        bad["ks"] = view["ks"].copy()
+        bad["ks"][3] = np.float16(-1.0)
+        with pytest.raises(lib.ConfKVError):
+            b.import_unit(0, 0, g, bad)
+    oa, ob = torch.zeros_like(out), torch.zeros_like(out)
+    for t in range(12):
+        q = torch.from_numpy(rng.standard_normal((1, G * H, D)).astype(np.float16)).cuda()
+        kn = torch.from_numpy((2 * rng.standard_normal((1, H, D))).astype(np.float16)).cuda()
+        a.attend(0, q, kn, kn, oa)
+        b.attend(0, q, kn, kn, ob)
+        assert torch.equal(oa, ob)
+        a.evict_compact()
+        b.evict_compact()
+    for g in range(H):
+        va, vb = a.export(0, 0, g), b.export(0, 0, g)
+        for name in va:
+            assert np.array_equal(np.asarray(va[name]).view(np.uint8) if hasattr(va[name], "view") else va[name],
+                                  np.asarray(vb[name]).view(np.uint8) if hasattr(vb[name], "view") else vb[name]), name
+    a.close()
+    b.close()
 
 
 @pytest.mark.parametrize("G,D,W", [(4, 128, 6), (1, 64, -1), (2, 128, 0)])
