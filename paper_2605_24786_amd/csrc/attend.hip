@@ -910,34 +910,73 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
 #pragma unroll
   for (int j = 0; j < NV; ++j) { mrun[j] = NEG; lrun[j] = 0.f; pbias[j] = 0.f; hd[j] = RowMap<G>::head(j, g4); }
 
-  // ---------------- FP16 slots: 16-slot tiles on the matrix cores, taken first ----------------
-  // (tiles go to the wavefronts from the back, which hold the fewest INT8 tiles; the first
-  // INT8 tile's loads are in flight meanwhile).  With per-channel scales they come second.
+  // ---------------- the slice as a list of work items ----------------
+  // Items 0 .. ntiles-1 are the 32-slot INT8 tiles, the rest the 16-slot FP16 tiles (the same
+  // 8 KB of rows each).  Wavefront w takes items w, w + 8, ..; the rows of its next item are
+  // requested as soon as the current ones have left the registers for LDS, so one item per
+  // wavefront is always in flight.
+  const int base16 = sl.lo16;
   const int ntiles16 = (sl.hi16 - sl.lo16 + 15) / 16;
+  const int nitems = ntiles + ntiles16;
+  const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
+  const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
+  const int c16 = lane & 15, r4 = lane >> 4;     // FP16 load coordinates: 16-byte piece, row
+  auto load_tile16 = [&](int f) -> TileRegs {
+    TileRegs t;
+    const int base = base16 + 16 * f, last = sl.hi16 - 1;
+    const int h16 = sl.h16, cap16 = cv.cap16, n8 = sl.n8;
+    const unsigned col = (unsigned)c16 * 8u;
+    const unsigned o0 = (unsigned)ring_row(h16, min(base + r4, last) - n8, cap16) * D + col;
+    const unsigned o1 = (unsigned)ring_row(h16, min(base + 4 + r4, last) - n8, cap16) * D + col;
+    const unsigned o2 = (unsigned)ring_row(h16, min(base + 8 + r4, last) - n8, cap16) * D + col;
+    const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * D + col;
+    t.k0 = *(const int4 *)(K16 + o0);
+    t.v0 = *(const int4 *)(V16 + o0);
+    t.k1 = *(const int4 *)(K16 + o1);
+    t.v1 = *(const int4 *)(V16 + o1);
+    t.k2 = *(const int4 *)(K16 + o2);
+    t.v2 = *(const int4 *)(V16 + o2);
+    t.k3 = *(const int4 *)(K16 + o3);
+    t.v3 = *(const int4 *)(V16 + o3);
+    t.ks0 = t.ks1 = t.vs0 = t.vs1 = 0;
+    return t;
+  };
+  auto load_item = [&](int it) -> TileRegs { return it < ntiles ? load_tile(it) : load_tile16(it - ntiles); };
+  // a wavefront whose first item is an FP16 tile requests it only now: the appended row is in it
+  if (w >= ntiles && w < nitems) tr = load_tile16(w - ntiles);
+  // with per-channel scales the accumulator leaves code units once, after the wavefront's last
+  // INT8 item (its FP16 items, if any, come after that)
+  bool in_code_units = kChan;
+  auto leave_code_units = [&]() {
+    // the INT8 part is complete: take the code bias out and go from code units to values
+    float pb[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) { pb[j] = row16_sum(pbias[j]) * kCodeBias; pbias[j] = 0.f; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float bias = rows_to_tile<G>(pb, i, g4);
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) O[nt][i] = (O[nt][i] - bias) * vch[nt];
+    }
+    in_code_units = false;
+  };
   int tix = 0;
-#pragma unroll
-  for (int phase = 0; phase < 2; ++phase) {
-  if ((phase == 0) != kChan) {
-    const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
-    const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
-    const int c16 = lane & 15, r4 = lane >> 4;   // load coordinates: 16-byte piece, row
-    for (int f = kAttWaves - 1 - w; f < ntiles16; f += kAttWaves) {
-      const int base = sl.lo16 + 16 * f;
-      int4 kh[4], vh[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int slot = min(base + 4 * r + r4, sl.hi16 - 1);
-        const size_t off = (size_t)ring_row(sl.h16, slot - sl.n8, cv.cap16) * D + c16 * 8;
-        kh[r] = *(const int4 *)(K16 + off);
-        vh[r] = *(const int4 *)(V16 + off);
+  for (int item = w; item < nitems; item += kAttWaves) {
+    if (item >= ntiles) {
+      // ---- an FP16 tile ----
+      if constexpr (kChan) {
+        if (in_code_units) leave_code_units();
       }
+      const int base = base16 + 16 * (item - ntiles);
       // K rows as they are (row stride kKRow16 bytes), V transposed to [channel][slot]
-#pragma unroll
-      for (int r = 0; r < 4; ++r) *(int4 *)(Kt + (4 * r + r4) * kKRow16 + c16 * 16) = kh[r];
+      *(int4 *)(Kt + (r4)*kKRow16 + c16 * 16) = tr.k0;
+      *(int4 *)(Kt + (4 + r4) * kKRow16 + c16 * 16) = tr.k1;
+      *(int4 *)(Kt + (8 + r4) * kKRow16 + c16 * 16) = tr.k2;
+      *(int4 *)(Kt + (12 + r4) * kKRow16 + c16 * 16) = tr.k3;
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const unsigned x0 = dword_of(vh[0], q4), x1 = dword_of(vh[1], q4);
-        const unsigned x2 = dword_of(vh[2], q4), x3 = dword_of(vh[3], q4);
+        const unsigned x0 = dword_of(tr.v0, q4), x1 = dword_of(tr.v1, q4);
+        const unsigned x2 = dword_of(tr.v2, q4), x3 = dword_of(tr.v3, q4);
         // half r of each pair is slot 4r + r4; it lands at column 4*r4 + r
         unsigned *dst = (unsigned *)(Vt + (8 * c16 + 2 * q4) * kVRow + kVSkew(c16 >> 1) + 8 * r4);
         dst[0] = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
@@ -946,6 +985,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
         dst[kVRow / 4 + 1] = __builtin_amdgcn_perm(x3, x2, 0x07060302u);
       }
       wave_lds_sync();
+      if (item + kAttWaves < nitems) tr = load_item(item + kAttWaves);
       const uint8_t *krow = Kt + t16 * kKRow16 + g4 * 64;
       floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -986,10 +1026,9 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
         O[nt] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, __builtin_bit_cast(half4_t, v2), O[nt], 0, 0, 0);
       }
       wave_lds_sync();
+      continue;
     }
-  } else {
-  for (int tile = w; tile < ntiles; tile += kAttWaves) {
-    const int base = sl.lo8 + tile * kTile;
+    const int base = sl.lo8 + item * kTile;
     if (tix < 6) TS(4 + 2 * tix);
     // ---- registers -> LDS: K rows as they are, V transposed to [channel][slot] ----
     *(int4 *)(Kt + (r8)*kKRow + c8 * 16) = tr.k0;
@@ -1019,7 +1058,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     if (tix < 6) TS(5 + 2 * tix);
     ++tix;
     // the registers are free again: fetch this wavefront's next tile while computing
-    if (tile + kAttWaves < ntiles) tr = load_tile(tile + kAttWaves);
+    if (item + kAttWaves < nitems) tr = load_item(item + kAttWaves);
 
     // ---- scores: S[head][slot] for the two 16-slot halves of the tile ----
     float sc[2][NV];
@@ -1108,19 +1147,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     wave_lds_sync();
   }
   if constexpr (kChan) {
-    // the INT8 part is complete: take the code bias out and go from code units to values
-    float pb[NV];
-#pragma unroll
-    for (int j = 0; j < NV; ++j) { pb[j] = row16_sum(pbias[j]) * kCodeBias; pbias[j] = 0.f; }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float bias = rows_to_tile<G>(pb, i, g4);
-#pragma unroll
-      for (int nt = 0; nt < 8; ++nt) O[nt][i] = (O[nt][i] - bias) * vch[nt];
-    }
+    if (in_code_units) leave_code_units();
   }
-  }  // INT8 phase
-  }  // phases
   TS(16);
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
