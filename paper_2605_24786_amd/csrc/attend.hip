@@ -154,7 +154,9 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
 }
 
 // The workgroup that owns the tail writes the new token into the FP16 ring.
-template <int D>
+// kSync = false: the caller never reads the appended row back in this launch (it takes the new
+// token from the call's arguments), so nothing has to wait for the stores.
+template <int D, bool kSync = true>
 __device__ __forceinline__ void append_new_token(const CacheView &cv, const AttendLaunch &a,
                                                  const Slice &s, int ns) {
   if (s.j != ns - 1) return;
@@ -168,7 +170,7 @@ __device__ __forceinline__ void append_new_token(const CacheView &cv, const Atte
     ((int4 *)V16)[tid - D / 8] = ((const int4 *)(a.vnew + (size_t)s.ul * D))[tid - D / 8];
   }
   if (tid == 0) cv.pos[(size_t)s.u * cv.cap + ring_row_u(s.h8, s.n - 1, cv.cap)] = a.pos_new;
-  __syncthreads();
+  if constexpr (kSync) __syncthreads();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -851,10 +853,10 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     return t;
   };
   TileRegs tr = {};
-  // the first INT8 tile is requested before anything else: its latency covers the append,
-  // the query loads and the FP16 tiles
+  // the first INT8 tile is requested before anything else: its latency covers the append and
+  // the query loads
   if (w < ntiles) tr = load_tile(w);
-  append_new_token<D>(cv, a, sl, ns);
+  append_new_token<D, false>(cv, a, sl, ns);
   const float NEG = -INFINITY;
   const float sm = a.sm_scale;
   TS(1);
@@ -930,19 +932,24 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     const unsigned o1 = (unsigned)ring_row(h16, min(base + 4 + r4, last) - n8, cap16) * D + col;
     const unsigned o2 = (unsigned)ring_row(h16, min(base + 8 + r4, last) - n8, cap16) * D + col;
     const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * D + col;
-    t.k0 = *(const int4 *)(K16 + o0);
-    t.v0 = *(const int4 *)(V16 + o0);
-    t.k1 = *(const int4 *)(K16 + o1);
-    t.v1 = *(const int4 *)(V16 + o1);
-    t.k2 = *(const int4 *)(K16 + o2);
-    t.v2 = *(const int4 *)(V16 + o2);
-    t.k3 = *(const int4 *)(K16 + o3);
-    t.v3 = *(const int4 *)(V16 + o3);
+    // the appended token (slot n - 1, the last slot of the unit's last split) is taken from the
+    // call's arguments, not read back from the ring: no wait on the append's stores
+    const int newest = sl.n - 1;
+    const __half *kn = a.knew + (size_t)sl.ul * D + col, *vn = a.vnew + (size_t)sl.ul * D + col;
+    const bool f0 = min(base + r4, last) == newest, f1 = min(base + 4 + r4, last) == newest;
+    const bool f2 = min(base + 8 + r4, last) == newest, f3 = min(base + 12 + r4, last) == newest;
+    t.k0 = *(const int4 *)(f0 ? kn : K16 + o0);
+    t.v0 = *(const int4 *)(f0 ? vn : V16 + o0);
+    t.k1 = *(const int4 *)(f1 ? kn : K16 + o1);
+    t.v1 = *(const int4 *)(f1 ? vn : V16 + o1);
+    t.k2 = *(const int4 *)(f2 ? kn : K16 + o2);
+    t.v2 = *(const int4 *)(f2 ? vn : V16 + o2);
+    t.k3 = *(const int4 *)(f3 ? kn : K16 + o3);
+    t.v3 = *(const int4 *)(f3 ? vn : V16 + o3);
     t.ks0 = t.ks1 = t.vs0 = t.vs1 = 0;
     return t;
   };
   auto load_item = [&](int it) -> TileRegs { return it < ntiles ? load_tile(it) : load_tile16(it - ntiles); };
-  // a wavefront whose first item is an FP16 tile requests it only now: the appended row is in it
   if (w >= ntiles && w < nitems) tr = load_tile16(w - ntiles);
   // with per-channel scales the accumulator leaves code units once, after the wavefront's last
   // INT8 item (its FP16 items, if any, come after that)
