@@ -337,6 +337,40 @@ def attend_unit(u: UnitCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarra
     return out, A
 
 
+def attend_chunk_unit(u: UnitCache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, pos0: int,
+                      sm_scale: float, ema_decay: float, mass_gain: Optional[float] = None
+                      ) -> Tuple[np.ndarray, np.ndarray]:
+    """Tq consecutive tokens of one sequence in one call (a chunk of a prompt, or several
+    decode tokens that are all kept): q [Tq, G, D], k_new / v_new [Tq, D], positions
+    pos0 .. pos0 + Tq - 1.  Defined as what Tq single-token steps without eviction in
+    between compute: query t attends the cache and the chunk's tokens 0 .. t (causal), and
+    the importance follows a <- lambda a + gain A_t once per query, which telescopes to
+
+        a_i <- lambda^Tq a_i + gain * sum_t lambda^(Tq-1-t) A_{t,i}
+
+    (a token of the chunk starts at 0 and receives no mass from the queries before it).
+    The stored fp32 importance is written once, at the end of the call.
+    Returns (out [Tq, G, D] float64, W [n] float64 = the weighted mass sum above).
+    """
+    q = np.asarray(q)
+    Tq = q.shape[0]
+    lam = F64(ema_decay)
+    gain = (1.0 - lam) if mass_gain is None else F64(mass_gain)
+    n_old = u.n
+    a = np.concatenate([u.ema.astype(F64), np.zeros(Tq)])
+    outs = []
+    for t in range(Tq):
+        append_token(u, k_new[t], v_new[t], pos0 + t)
+        out, p = attention_naive(q[t].astype(F64), u.stored_k(), u.stored_v(), sm_scale)
+        A = np.sum(p, axis=0)                       # over the n_old + t + 1 visible slots
+        a[:n_old + t + 1] = lam * a[:n_old + t + 1] + gain * A
+        a[n_old + t + 1:] = 0.0                     # tokens not yet appended hold nothing
+        outs.append(out)
+    W = a - (lam ** Tq) * np.concatenate([u.ema[:n_old].astype(F64), np.zeros(Tq)])
+    u.ema = a.astype(np.float32)
+    return np.stack(outs), W
+
+
 # --------------------------------------------------------------------------------------
 # Ranking, eviction, compaction, demotion  ("Budget and ranker"; Algorithm 1)
 # --------------------------------------------------------------------------------------
@@ -494,17 +528,33 @@ class OracleRun:
         self.policy = policy
         self.units = units
         self.next_pos = next_pos
+        self.pending = 1          # tokens appended per layer since the last evict_compact
 
     def attend(self, layer: int, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, group: int
                ) -> Dict[Tuple[int, int, int], np.ndarray]:
         """q [B, Hq, D], k_new/v_new [B, Hkv, D] fp16 -> {unit: out [G, D]} for followed units."""
         outs = {}
         p = self.policy
+        self.pending = 1
         for (l, b, g), u in self.units.items():
             if l != layer:
                 continue
             out, _ = attend_unit(u, q[b, g * group:(g + 1) * group], k_new[b, g], v_new[b, g],
                                  self.next_pos, p.sm_scale, p.ema_decay, p.mass_gain)
+            outs[(l, b, g)] = out
+        return outs
+
+    def attend_chunk(self, layer: int, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, group: int
+                     ) -> Dict[Tuple[int, int, int], np.ndarray]:
+        """q [B, Tq, Hq, D], k_new/v_new [B, Tq, Hkv, D] fp16 -> {unit: out [Tq, G, D]}."""
+        outs = {}
+        p = self.policy
+        self.pending = int(q.shape[1])
+        for (l, b, g), u in self.units.items():
+            if l != layer:
+                continue
+            out, _ = attend_chunk_unit(u, q[b, :, g * group:(g + 1) * group], k_new[b, :, g], v_new[b, :, g],
+                                       self.next_pos, p.sm_scale, p.ema_decay, p.mass_gain)
             outs[(l, b, g)] = out
         return outs
 
@@ -536,5 +586,6 @@ class OracleRun:
                 key = (l * p.batch + b) * p.n_kv_heads + g
                 gone[(l, b, g)] = evict_compact_unit(u, N, p.protected, p.alpha, p.fp16_window,
                                                      ranker=p.ranker, seed=p.ranker_seed, unit_key=key)
-        self.next_pos += 1
+        self.next_pos += self.pending
+        self.pending = 1
         return gone

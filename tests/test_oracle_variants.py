@@ -119,3 +119,55 @@ def test_shared_importance_and_layer_scope():
     r2 = O.OracleRun(O.Policy(1, [40], [60], 10, -1, rank_scope="layer"), {(0, 0, 0): u2}, n)
     r1.evict_compact(np.array([True])); r2.evict_compact(np.array([True]))
     assert np.array_equal(u1.pos, u2.pos)
+
+
+# ---- several tokens per call ("Compatibility with serving systems": chunked / multi-token steps)
+
+def test_chunk_is_the_sequence_of_single_steps_up_to_fp32_storage():
+    rng = np.random.default_rng(21)
+    n, D, G, Tq, W = 30, 8, 3, 5, 4
+    ema0 = rng.random(n).astype(np.float32)
+    a = _unit(rng, n, D, W, ema0)
+    b = a.copy()
+    q = rng.standard_normal((Tq, G, D)).astype(np.float16)
+    kn = rng.standard_normal((Tq, D)).astype(np.float16)
+    vn = rng.standard_normal((Tq, D)).astype(np.float16)
+    out_c, _ = O.attend_chunk_unit(a, q, kn, vn, n, 0.35, 0.9)
+    outs = [O.attend_unit(b, q[t], kn[t], vn[t], n + t, 0.35, 0.9)[0] for t in range(Tq)]
+    assert np.allclose(out_c, np.stack(outs), rtol=1e-13, atol=1e-15)     # same arithmetic
+    assert np.array_equal(a.pos, b.pos) and np.array_equal(a.k16.view(np.uint16), b.k16.view(np.uint16))
+    # the sequence rounds the stored importance to fp32 after every step, the chunk once
+    assert np.allclose(a.ema, b.ema, rtol=4e-7, atol=1e-9)
+
+
+def test_chunk_closed_form_causal_mask_and_mass():
+    # dense causal attention of the Tq queries over [cache, chunk], written out directly
+    rng = np.random.default_rng(22)
+    n, D, G, Tq = 12, 4, 2, 4
+    ema0 = rng.random(n).astype(np.float32)
+    u = _unit(rng, n, D, -1, ema0)
+    K = np.vstack([u.k16.astype(np.float64), np.zeros((Tq, D))])
+    V = np.vstack([u.v16.astype(np.float64), np.zeros((Tq, D))])
+    q = rng.standard_normal((Tq, G, D)).astype(np.float16)
+    kn = rng.standard_normal((Tq, D)).astype(np.float16)
+    vn = rng.standard_normal((Tq, D)).astype(np.float16)
+    K[n:], V[n:] = kn, vn
+    lam, gain, sm = 0.8, 0.25, 0.5
+    out, Wm = O.attend_chunk_unit(u, q, kn, vn, 100, sm, lam, mass_gain=gain)
+    want_out = np.zeros((Tq, G, D))
+    want_W = np.zeros(n + Tq)
+    for t in range(Tq):
+        vis = n + t + 1
+        for h in range(G):
+            s = sm * (K[:vis] @ q[t, h].astype(np.float64))
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            want_out[t, h] = p @ V[:vis]
+            want_W[:vis] += gain * lam ** (Tq - 1 - t) * p
+    assert np.allclose(out, want_out, rtol=1e-12, atol=1e-14)
+    assert np.allclose(Wm, want_W, rtol=1e-12, atol=1e-14)
+    want_ema = lam ** Tq * np.concatenate([ema0.astype(np.float64), np.zeros(Tq)]) + want_W
+    assert np.allclose(u.ema, want_ema.astype(np.float32), rtol=2e-7, atol=1e-12)
+    assert np.array_equal(u.pos[-Tq:], 100 + np.arange(Tq))
+    # total mass handed out by query t is G, weighted lambda^(Tq-1-t)
+    assert abs(Wm.sum() - gain * G * sum(lam ** (Tq - 1 - t) for t in range(Tq))) < 1e-12
