@@ -46,7 +46,9 @@ def attend_bytes_per_launch(wl, n8, n16):
     D, G = wl.head_dim, wl.group
     n = n8 + n16
     chan = getattr(wl, "scale_mode", "token") == "channel"     # then 2 x D fp16 scales per unit instead
-    per_unit = n8 * (2 * D + (0 if chan else 4)) + (4 * D if chan else 0) + n16 * 4 * D + 8 * n + 4 * G * D + 8 * D + 4
+    tq = max(1, getattr(wl, "max_chunk", 0))                    # tokens per call here: q, out and new rows scale with it
+    per_unit = (n8 * (2 * D + (0 if chan else 4)) + (4 * D if chan else 0) + n16 * 4 * D + 8 * n
+                + tq * (4 * G * D + 8 * D + 4))
     return per_unit * wl.batch * wl.n_kv_heads
 
 
@@ -175,6 +177,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="keep only the first N layers (0 = all)")
     ap.add_argument("--scales", choices=["token", "channel"], default="token",
                     help="granularity of the INT8 scales (channel: the paper's literal per-(head, channel) reading)")
+    ap.add_argument("--chunk", type=int, default=1,
+                    help="tokens per attention call (conf_kv_attend_chunk when above 1; at most 16 / group size)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device-to-device copy a few times and exit (counter calibration)")
     args = ap.parse_args()
@@ -203,6 +207,8 @@ def main():
     wl = workload(args.workload)
     if args.scales != "token":
         wl = wl.scaled(name=wl.name + "_" + args.scales + "_scales", scale_mode=args.scales)
+    if args.chunk > 1:
+        wl = wl.scaled(name=wl.name + f"_chunk{args.chunk}", max_chunk=args.chunk)
     if args.layers and args.layers < wl.n_layers:
         wl = wl.scaled(n_layers=args.layers, n_tight=wl.n_tight[:args.layers], n_loose=wl.n_loose[:args.layers])
     L = wl.n_layers
@@ -213,11 +219,16 @@ def main():
         K, V = gen.prefill_layer(wl, args.seed, l, threads=16)
         prompts.append((torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()))
     qs, ks, vs = [], [], []
+    tq = args.chunk
     for l in range(L):
-        q, k, v = gen.step_inputs(wl, args.seed, l, 0)
+        if tq == 1:
+            q, k, v = gen.step_inputs(wl, args.seed, l, 0)
+        else:    # [B][tq][heads][D]: the inputs of tq consecutive steps
+            parts = [gen.step_inputs(wl, args.seed, l, t) for t in range(tq)]
+            q, k, v = (np.ascontiguousarray(np.stack([p[j] for p in parts], axis=1)) for j in range(3))
         qs.append(torch.from_numpy(q).cuda()); ks.append(torch.from_numpy(k).cuda()); vs.append(torch.from_numpy(v).cuda())
-    logits = torch.from_numpy(gen.step_logits(wl, args.seed, 0)).cuda()
-    out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float16, device="cuda")
+    logits = torch.from_numpy(gen.step_logits(wl, args.seed, tq - 1)).cuda()
+    out = torch.empty(tuple(qs[0].shape), dtype=torch.float16, device="cuda")
     conf = torch.empty(wl.batch, dtype=torch.float32, device="cuda")
     sel = torch.empty(wl.batch, dtype=torch.uint8, device="cuda")
     print(f"# setup {time.time() - t_setup:.1f}s: {wl.name}, state {kv.state.numel() / 2**30:.2f} GiB", file=sys.stderr, flush=True)
@@ -230,7 +241,10 @@ def main():
         # returns per-phase events when ev is given: [start, after attends, after step, end]
         if ev: ev[0].record()
         for l in range(L):
-            kv.attend(l, qs[l], ks[l], vs[l], out)
+            if tq == 1:
+                kv.attend(l, qs[l], ks[l], vs[l], out)
+            else:
+                kv.attend_chunk(l, qs[l], ks[l], vs[l], out)
         if ev: ev[1].record()
         kv.step(logits, conf, sel)
         if ev: ev[2].record()
@@ -238,13 +252,14 @@ def main():
         if ev: ev[3].record()
 
     if args.steady:
+        assert tq == 1, "--steady times single-token steps"
         steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel)
         return
     for _ in range(args.warmup):
         reload(); torch.cuda.synchronize()
         one_step(); torch.cuda.synchronize()
 
-    len_before = wl.prefill + 1
+    len_before = wl.prefill + tq
     n8_b = max(0, wl.prefill - wl.fp16_window) if wl.fp16_window >= 0 else 0
     n16_b = len_before - n8_b
     t_step, t_att, t_conf, t_evict = [], [], [], []
@@ -278,11 +293,11 @@ def main():
         "config": {"workload": wl.name, "layers": L, "batch": wl.batch, "q_heads": wl.n_q_heads,
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "vocab": wl.vocab,
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
-                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "attend_splits": kv.attend_splits(0),
+                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "attend_splits": kv.attend_splits(0),
                    "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
-        "roofline": {"bound": "hbm", "kernel": "attend_mfma_kernel<4>" if wl.group > 1 and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("attend_mfma_kernel<16>" if tq > 1 else f"attend_mfma_kernel<{wl.group}>") if (tq > 1 or wl.group > 1) and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload) if args.scales == "token" else None, "bytes_per_launch": att_bytes,
+                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload) if args.scales == "token" and tq == 1 else None, "bytes_per_launch": att_bytes,
                      "launch_ms": att_launch_ms},
         "step_breakdown_ms": {"attend_x_layers": float(np.mean(t_att)), "confidence": float(np.mean(t_conf)),
                               "evict_compact": float(np.mean(t_evict))},

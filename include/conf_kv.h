@@ -79,7 +79,9 @@ typedef struct conf_kv_config {
   int32_t rank_scope;        /* conf_kv_rank_scope                                             */
   uint64_t ranker_seed;      /* CONF_KV_RANKER_RANDOM: seed of its counter-based draws         */
   int32_t scale_mode;        /* conf_kv_scale_mode: granularity of the INT8 scales             */
-  int32_t reserved0;         /* must be 0                                                      */
+  int32_t max_chunk;         /* most tokens one conf_kv_attend_chunk call may append; 0 or 1 =
+                                single-token calls only.  Above 1: head_dim 128 and
+                                max_chunk * (n_q_heads / n_kv_heads) <= 16                     */
 } conf_kv_config;
 
 typedef enum conf_kv_scale_mode {
@@ -174,6 +176,21 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16,
  */
 int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const void *dev_knew16,
                    const void *dev_vnew16, void *dev_out16, conf_kv_stream stream);
+
+/* Several consecutive tokens of every sequence in one call (a chunk of a prompt, or decode
+ * tokens that are all kept; "Compatibility with serving systems" names such multi-token
+ * steps): 1 <= tq <= max_chunk.  Defined as tq conf_kv_attend calls without eviction in
+ * between: token t gets position p0 + t, query t attends the cache and the chunk's tokens
+ * 0 .. t (causal), and the importance follows a <- lambda a + gain A_t once per query, i.e.
+ * a_i <- lambda^tq a_i + gain * sum_t lambda^(tq-1-t) A_{t,i}, stored once.  The keys and
+ * values of the cache are read once for all tq queries.
+ * dev_q16 / dev_out16: fp16 [B][tq][Hq][D]; dev_knew16 / dev_vnew16: fp16 [B][tq][Hkv][D].
+ * The following conf_kv_evict_compact commits all tq appends.  Same errors as conf_kv_attend;
+ * tq outside 1 .. max(1, max_chunk) is CONF_KV_ERR_INVALID_ARG; CONF_KV_ERR_BAD_SHAPE when
+ * tq > 1 and the layer's caches are too long for a single-launch plan. */
+int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const void *dev_q16,
+                         const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
+                         conf_kv_stream stream);
 
 /*
  * Confidence estimator and budget selector (Eq. 1; "Budget and ranker"; Algorithm 1,

@@ -31,7 +31,7 @@ class ConfKVConfig(C.Structure):
         ("w_entropy", C.c_float), ("w_margin", C.c_float), ("w_top", C.c_float),
         ("n_tight", C.POINTER(C.c_int32)), ("n_loose", C.POINTER(C.c_int32)),
         ("mass_gain", C.c_float), ("ranker", C.c_int32), ("rank_scope", C.c_int32),
-        ("ranker_seed", C.c_uint64), ("scale_mode", C.c_int32), ("reserved0", C.c_int32),
+        ("ranker_seed", C.c_uint64), ("scale_mode", C.c_int32), ("max_chunk", C.c_int32),
     ]
 
 
@@ -60,6 +60,7 @@ SYMBOLS = {
     "conf_kv_destroy": (C.c_int, [_P]),
     "conf_kv_load_prefill": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, _P]),
     "conf_kv_attend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P]),
+    "conf_kv_attend_chunk": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, _P, _P, _P]),
     "conf_kv_step": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
     "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
@@ -98,7 +99,7 @@ def strerror(status: int) -> str:
 def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacity, fp16_window,
                 protected_window, n_tight: Sequence[int], n_loose: Sequence[int], tau=0.7, alpha=0.65,
                 ema_decay=0.9, sm_scale=None, w_entropy=0.4, w_margin=0.3, w_top=0.3, mass_gain=None,
-                ranker="composite", rank_scope="kv_head", ranker_seed=0, scale_mode="token"):
+                ranker="composite", rank_scope="kv_head", ranker_seed=0, scale_mode="token", max_chunk=0):
     """A ConfKVConfig plus the two int32 arrays it points to (keep the tuple alive)."""
     nt = (C.c_int32 * len(n_tight))(*[int(x) for x in n_tight])
     nl = (C.c_int32 * len(n_loose))(*[int(x) for x in n_loose])
@@ -108,7 +109,7 @@ def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacit
                        fp16_window, protected_window, tau, alpha, ema_decay, sm_scale,
                        w_entropy, w_margin, w_top, nt, nl,
                        -1.0 if mass_gain is None else float(mass_gain), RANKERS[ranker],
-                       RANK_SCOPES[rank_scope], int(ranker_seed), SCALE_MODES[scale_mode], 0)
+                       RANK_SCOPES[rank_scope], int(ranker_seed), SCALE_MODES[scale_mode], int(max_chunk))
     return cfg, nt, nl
 
 
@@ -175,6 +176,12 @@ class ConfKV:
     def attend(self, layer: int, q16, knew16, vnew16, out16):
         return self._check(self.lib.conf_kv_attend(self.h, layer, _ptr(q16), _ptr(knew16), _ptr(vnew16),
                                                    _ptr(out16), self._stream()), "conf_kv_attend")
+
+    def attend_chunk(self, layer: int, q16, knew16, vnew16, out16):
+        """q16 / out16 [B][tq][Hq][D], knew16 / vnew16 [B][tq][Hkv][D]; tq = q16.shape[1]."""
+        tq = int(q16.shape[1])
+        return self._check(self.lib.conf_kv_attend_chunk(self.h, layer, tq, _ptr(q16), _ptr(knew16), _ptr(vnew16),
+                                                         _ptr(out16), self._stream()), "conf_kv_attend_chunk")
 
     def step(self, logits, conf=None, sel=None):
         return self._check(self.lib.conf_kv_step(self.h, _ptr(logits), _ptr(conf), _ptr(sel),
@@ -243,6 +250,7 @@ def from_workload(wl, **override) -> ConfKV:
               alpha=wl.alpha, ema_decay=wl.ema_decay, w_entropy=wl.w_entropy, w_margin=wl.w_margin,
               w_top=wl.w_top, mass_gain=getattr(wl, "mass_gain", None),
               ranker=getattr(wl, "ranker", "composite"), rank_scope=getattr(wl, "rank_scope", "kv_head"),
-              ranker_seed=getattr(wl, "ranker_seed", 0), scale_mode=getattr(wl, "scale_mode", "token"))
+              ranker_seed=getattr(wl, "ranker_seed", 0), scale_mode=getattr(wl, "scale_mode", "token"),
+              max_chunk=getattr(wl, "max_chunk", 0))
     kw.update(override)
     return ConfKV(**kw)

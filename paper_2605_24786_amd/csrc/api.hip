@@ -47,10 +47,12 @@ bool config_ok(const conf_kv_config *c) {
   if (c->rank_scope != CONF_KV_SCOPE_KV_HEAD && c->rank_scope != CONF_KV_SCOPE_LAYER) return false;
   if (c->scale_mode != CONF_KV_SCALES_TOKEN && c->scale_mode != CONF_KV_SCALES_CHANNEL) return false;
   if (c->scale_mode == CONF_KV_SCALES_CHANNEL && (c->head_dim != 128 || c->fp16_window < 0)) return false;
-  if (c->reserved0 != 0) return false;
+  if (c->max_chunk < 0) return false;
+  if (c->max_chunk > 1 && (c->head_dim != 128 || c->max_chunk * (c->n_q_heads / c->n_kv_heads) > kChunkRows))
+    return false;
   for (int l = 0; l < c->n_layers; ++l) {
     if (c->n_tight[l] < 1 || c->n_tight[l] > c->n_loose[l]) return false;
-    if (std::max(c->n_loose[l], c->protected_window) + 1 > c->capacity) return false;
+    if (std::max(c->n_loose[l], c->protected_window) + std::max(1, c->max_chunk) > c->capacity) return false;
   }
   return true;
 }
@@ -63,7 +65,7 @@ StateLayout state_layout(const conf_kv_config *c) {
   if (c->fp16_window < 0) {
     s.cap16 = c->capacity;
   } else {
-    long long want = ((long long)c->fp16_window + 1 + 15) / 16 * 16;
+    long long want = ((long long)c->fp16_window + std::max(1, c->max_chunk) + 15) / 16 * 16;
     s.cap16 = (int)std::min<long long>(want, c->capacity);
   }
   size_t off = 0;
@@ -98,14 +100,15 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   ScratchLayout s{};
   const size_t UPL = (size_t)c->batch * c->n_kv_heads, U = UPL * c->n_layers;
   const size_t G = c->n_q_heads / c->n_kv_heads, D = c->head_dim;
+  const size_t R = c->max_chunk > 1 ? (size_t)kChunkRows : G;   // query rows per unit in the exchange buffers
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   s.conf_arrive = take((size_t)c->batch * 4);
   s.arrive = take(U * kAttendMaxSplits * 4);
   s.zero_bytes = off;
   s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
-  s.part_ml = take(UPL * kAttendMaxSplits * G * 2 * 4);
-  s.part_o = take(UPL * kAttendMaxSplits * G * D * 4);
+  s.part_ml = take(UPL * kAttendMaxSplits * R * 2 * 4);
+  s.part_o = take(UPL * kAttendMaxSplits * R * D * 4);
   s.spill = take(attend_spill_floats((int)UPL, (int)G, c->capacity) * 4);
   s.score = take(U * c->capacity * 8);
   s.src = take(U * c->capacity * 4);
@@ -270,26 +273,30 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   return CONF_KV_OK;
 }
 
-static int plan_for_layer(conf_kv_handle *h, int layer, AttendPlan *plan) {
-  const int n_ub = h->len_ub[layer] + 1;
+static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan) {
+  const int n_ub = h->len_ub[layer] + tq;
   const int W = h->cfg.fp16_window;
-  const int n16_ub = W < 0 ? n_ub : std::min(n_ub, W + 1);
-  if (!attend_plan(h->cfg.head_dim, h->cv.G, h->cv.chan != 0, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
+  const int n16_ub = W < 0 ? n_ub : std::min(n_ub, W + tq);
+  // a chunk runs on the matrix-core body with all 16 tile rows as query rows
+  const int rows = tq > 1 ? kChunkRows : h->cv.G;
+  if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, tq > 1, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
                    h->forced_splits, h->force_two_launch, plan))
     return CONF_KV_ERR_BAD_SHAPE;
   return CONF_KV_OK;
 }
 
-int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const void *dev_knew16,
-                   const void *dev_vnew16, void *dev_out16, conf_kv_stream stream) {
+static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const void *dev_q16,
+                         const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
+                         conf_kv_stream stream) {
   if (!h || !dev_q16 || !dev_knew16 || !dev_vnew16 || !dev_out16) return CONF_KV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  if (tq < 1 || tq > std::max(1, h->cfg.max_chunk)) return CONF_KV_ERR_INVALID_ARG;
   if (((uintptr_t)dev_q16 | (uintptr_t)dev_knew16 | (uintptr_t)dev_vnew16 | (uintptr_t)dev_out16) & 15)
     return CONF_KV_ERR_INVALID_ARG;
   if (h->appended[layer]) return CONF_KV_ERR_BAD_STATE;
-  if (h->len_ub[layer] + 1 > h->cfg.capacity) return CONF_KV_ERR_CAPACITY;
+  if (h->len_ub[layer] + tq > h->cfg.capacity) return CONF_KV_ERR_CAPACITY;
   AttendPlan plan;
-  int rc = plan_for_layer(h, layer, &plan);
+  int rc = plan_for_layer(h, layer, tq, &plan);
   if (rc != CONF_KV_OK) return rc;
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   AttendLaunch a{};
@@ -309,6 +316,8 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
   a.ema_decay = h->cfg.ema_decay;
   a.mass_gain = h->cfg.mass_gain < 0.f ? 1.0 - (double)h->cfg.ema_decay : (double)h->cfg.mass_gain;
   a.pos_new = h->next_pos[layer];
+  a.tq = tq;
+  a.gq = h->cv.G;
   a.dbg = nullptr;
 #ifdef CONFKV_TRACE
   // the ranking work arrays at the end of the scratch buffer are idle during conf_kv_attend
@@ -316,15 +325,26 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
     a.dbg = (unsigned long long *)(h->scratch + h->kl.total - (size_t)8 * 32 * 4 * 4096);
 #endif
   CK_HIP(h, launch_attend(h->cv, a, plan, (hipStream_t)stream));
-  h->appended[layer] = 1;
+  h->appended[layer] = (uint8_t)tq;
   return CONF_KV_OK;
+}
+
+int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const void *dev_knew16,
+                   const void *dev_vnew16, void *dev_out16, conf_kv_stream stream) {
+  return attend_tokens(h, layer, 1, dev_q16, dev_knew16, dev_vnew16, dev_out16, stream);
+}
+
+int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const void *dev_q16,
+                         const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
+                         conf_kv_stream stream) {
+  return attend_tokens(h, layer, tq, dev_q16, dev_knew16, dev_vnew16, dev_out16, stream);
 }
 
 int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
   if (!h) return CONF_KV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
   AttendPlan plan;
-  int rc = plan_for_layer(h, layer, &plan);
+  int rc = plan_for_layer(h, layer, 1, &plan);
   if (rc != CONF_KV_OK) return rc;
   return plan.two_launch ? 1000 + plan.splits : plan.splits;
 }
@@ -346,7 +366,7 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   int n_max = 0;
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
-    if (h->appended[l]) m.set(l);
+    m.set(l, h->appended[l]);
     n_max = std::max(n_max, h->len_ub[l] + (int)h->appended[l]);
     if (h->cv.chan && h->len_ub[l] + (int)h->appended[l] > 0)     // a demotion needs the scales
       for (size_t u = l * UPL; u < (l + 1) * UPL; ++u)
@@ -361,11 +381,9 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
                                  (int32_t *)(h->scratch + h->kl.sel), n_max, (hipStream_t)stream));
   const int P = h->cfg.protected_window;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
-    if (h->appended[l]) {
-      h->len_ub[l] += 1;
-      h->next_pos[l] += 1;
-      h->appended[l] = 0;
-    }
+    h->len_ub[l] += h->appended[l];
+    h->next_pos[l] += h->appended[l];
+    h->appended[l] = 0;
     // any budget the step may have chosen is at most the loose one
     const int n = h->len_ub[l], NL = h->n_loose[l];
     if (n > NL) h->len_ub[l] = std::max(NL, std::min(P, n));

@@ -133,7 +133,7 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
   s.b = s.ul / cv.Hkv;
   s.g = s.ul % cv.Hkv;
   s.n8 = cv.n8[s.u];
-  s.n = cv.len[s.u] + 1;                  // the appended token included
+  s.n = cv.len[s.u] + a.tq;               // the appended tokens included
   s.h16 = cv.head16[s.u];
   s.h8 = cv.head8[s.u];
   s.n16 = s.n - s.n8;
@@ -161,15 +161,17 @@ __device__ __forceinline__ void append_new_token(const CacheView &cv, const Atte
                                                  const Slice &s, int ns) {
   if (s.j != ns - 1) return;
   const int tid = threadIdx.x;
-  const int row = ring_row(s.h16, s.n16 - 1, cv.cap16);
-  __half *K16 = cv.k16 + ((size_t)s.u * cv.cap16 + row) * D;
-  __half *V16 = cv.v16 + ((size_t)s.u * cv.cap16 + row) * D;
-  if (tid < D / 8) {
-    ((int4 *)K16)[tid] = ((const int4 *)(a.knew + (size_t)s.ul * D))[tid];
-  } else if (tid < D / 4) {
-    ((int4 *)V16)[tid - D / 8] = ((const int4 *)(a.vnew + (size_t)s.ul * D))[tid - D / 8];
+  constexpr int PPR = D / 8;                        // 16-byte pieces per row
+  // token t of the call: K/V rows [B][tq][Hkv][D] -> FP16 ring row of slot n - tq + t
+  for (int i = tid; i < 2 * a.tq * PPR; i += kAttThreads) {
+    const int which = i / (a.tq * PPR), r = i % (a.tq * PPR), t = r / PPR, c = r % PPR;
+    const int row = ring_row(s.h16, s.n16 - a.tq + t, cv.cap16);
+    const __half *src = (which ? a.vnew : a.knew) + (((size_t)s.b * a.tq + t) * cv.Hkv + s.g) * D;
+    __half *dst = (which ? cv.v16 : cv.k16) + ((size_t)s.u * cv.cap16 + row) * D;
+    ((int4 *)dst)[c] = ((const int4 *)src)[c];
   }
-  if (tid == 0) cv.pos[(size_t)s.u * cv.cap + ring_row_u(s.h8, s.n - 1, cv.cap)] = a.pos_new;
+  if (tid < a.tq)
+    cv.pos[(size_t)s.u * cv.cap + ring_row_u(s.h8, s.n - a.tq + tid, cv.cap)] = a.pos_new + tid;
   if constexpr (kSync) __syncthreads();
 }
 
@@ -423,6 +425,25 @@ __device__ __forceinline__ bool arrive_and_wait(const CacheView &cv, const Atten
   return *s_ok != 0;
 }
 
+// Query row r of a unit is (token r / gq of the call, head r % gq of the group); rows past
+// tq * gq are padding.  Element e = r * D + d of the unit's [rows][D] output lives at
+// out[b][token][g * gq + head][d].
+__device__ __forceinline__ size_t out_index(const CacheView &cv, const AttendLaunch &a, const Slice &sl,
+                                            int e, int D) {
+  const int r = e / D, d = e - r * D;
+  const int t = r / a.gq, hq = r - t * a.gq;
+  return ((((size_t)sl.b * a.tq + t) * cv.Hkv + sl.g) * a.gq + hq) * D + d;
+}
+// Weight of row r's mass in the importance update of a call with tq tokens:
+// lambda^(tq - 1 - token), 0 for padding rows; for tq = 1 it is exactly 1.
+__device__ __forceinline__ double row_weight(const AttendLaunch &a, int r) {
+  const int t = r / a.gq;
+  if (t >= a.tq) return 0.0;
+  double w = 1.0;
+  for (int k = t + 1; k < a.tq; ++k) w *= (double)a.ema_decay;
+  return w;
+}
+
 // ---------------------------------------------------------------------------------------
 // Epilogue shared by both bodies.  On entry wm/wl/wo hold NP per-wavefront partials
 // (after a workgroup barrier): partial k is [G][D] floats at
@@ -488,8 +509,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       __half2 o2;
       o2.x = __float2half_rn((float)((double)o0 * inv));
       o2.y = __float2half_rn((float)((double)o1 * inv));
-      *(__half2 *)&a.out[((size_t)(sl.b * cv.Hkv * G + sl.g * G)) * D + idx] = o2;
-      if (idx % D == 0) { gm[h] = M; ginv[h] = inv; }
+      if (h < a.tq * a.gq) *(__half2 *)&a.out[out_index(cv, a, sl, idx, D)] = o2;
+      if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, h); }
     } else {
       st_agent2(&po[idx], o0, o1);
       if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
@@ -532,22 +553,28 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       const float M = wave_max(ms);
       const double term = ms > NEG ? exp((double)ms - (double)M) * (double)pml[(sp * G + h) * 2 + 1] : 0.0;
       const double L = wave_sum(term);
-      if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; }
+      if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; ginv[G + h] = (1.0 / L) * row_weight(a, h); }
     }
   }  // exchange
   __syncthreads();
   TS(22);
   // ---- mass + EMA of the slice ----
-  const double lam = (double)a.ema_decay, oml = a.mass_gain;
+  // a <- lambda^tq a + gain * sum over the rows of lambda^(tq-1-token) p; ginv[G + h] holds
+  // row h's weight over its normaliser.  Slots appended by this call start at 0.
+  double lam = 1.0;
+  for (int k = 0; k < a.tq; ++k) lam *= (double)a.ema_decay;
+  const double oml = a.mass_gain;
+  const double *gw = ginv + G;
+  const int first_new = sl.n - a.tq;
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
     const int t = tid + k * kAttThreads;
     if (t < sl.ntok) {
       double A = 0.0;
 #pragma unroll
-      for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
+      for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * gw[h];
       const int slot = sl.slot_of(t);
-      const double old = (slot == sl.n - 1) ? 0.0 : (double)ema_old[k];   // the new token starts at 0
+      const double old = (slot >= first_new) ? 0.0 : (double)ema_old[k];   // a new token starts at 0
       EMA[ring_row_u(sl.h8, slot, cv.cap)] = (float)(lam * old + oml * A);
     }
   }
@@ -569,8 +596,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       if (t < sl.ntok) {
         double A = 0.0;
 #pragma unroll
-        for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * ginv[h];
-        const double prev = (sl.slot_of(t) == sl.n - 1) ? 0.0 : (double)old[k];   // the new token starts at 0
+        for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * gw[h];
+        const double prev = (sl.slot_of(t) >= first_new) ? 0.0 : (double)old[k];   // a new token starts at 0
         EMA[row[k]] = (float)(lam * prev + oml * A);
       }
     }
@@ -578,7 +605,6 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   TS(23);
   // ---- this split normalises its share of the unit's output (online-softmax merge) ----
   if (exchange) {
-    const int Hq = cv.Hkv * G;
     for (int base = 0; base < per; base += epp) {
       const int e = sl.j * per + base + oe;                          // element of the [G][D] output
       const bool valid = os < ns && base + oe < per && e < G * D;
@@ -588,8 +614,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       const float ms = valid ? pml[(os * G + h) * 2] : NEG;
       float c = ms > NEG ? v * expf(ms - gm[h]) : 0.f;               // an empty partial weighs nothing
       for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
-      if (valid && os == 0)
-        a.out[((size_t)(sl.b * Hq + sl.g * G)) * D + e] = __float2half_rn((float)((double)c * ginv[h]));
+      if (valid && os == 0 && h < a.tq * a.gq)
+        a.out[out_index(cv, a, sl, e, D)] = __float2half_rn((float)((double)c * ginv[h]));
     }
   }
 }
@@ -610,7 +636,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
   float *wm = wo + NP * G * D;                  // [NP][G] per-wave maximum
   float *wl = wm + NP * G;                      // [NP][G] per-wave normaliser
   float *gm = wl + NP * G;                      // [G] global maximum
-  double *ginv = (double *)(gm + G + (G & 1));  // [G] 1 / global normaliser
+  double *ginv = (double *)(gm + G + (G & 1));  // [2 G]: 1 / global normaliser, the same times the row's mass weight
   __shared__ int s_ok;
 
   const Slice sl = make_slice(cv, a, ns, S);
@@ -657,7 +683,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv
   extern __shared__ __align__(16) float smem[];
   float *pml = smem;                            // [ns][G][2]
   float *gm = pml + (size_t)ns * G * 2;         // [G]
-  double *ginv = (double *)(gm + G + (G & 1));  // [G]
+  double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
   __shared__ int s_ok;
   const Slice sl = make_slice(cv, a, ns, S);
   float *stash = a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S;
@@ -740,12 +766,13 @@ __device__ __forceinline__ float row16_sum(float v) {
 // three quarters of padding.  Two lane-row swaps regroup the real rows over the whole wavefront:
 //   G <= 4: one value per lane; lane row r = lane / 16 holds head r
 //   G  > 4: two values per lane; value j of lane row r holds head 2j + (r >> 1) + 4 (r & 1)
+//   G  > 8: all 16 rows are real; the matrix-core layout is kept (four values per lane)
 // The slot (tile column lane % 16) stays where it is.
 template <int G>
 struct RowMap {
-  static constexpr int NV = G <= 4 ? 1 : 2;
+  static constexpr int NV = G <= 4 ? 1 : G <= 8 ? 2 : 4;
   static __device__ __forceinline__ int head(int j, int r) {
-    return G <= 4 ? r : 2 * j + (r >> 1) + 4 * (r & 1);
+    return G <= 4 ? r : G <= 8 ? 2 * j + (r >> 1) + 4 * (r & 1) : 4 * r + j;
   }
 };
 // rows (a0, b0, a2, b2) of the two operands
@@ -764,16 +791,21 @@ template <int G>
 __device__ __forceinline__ void regroup_rows(const floatx4_t &acc, float (&z)[RowMap<G>::NV]) {
   if constexpr (G <= 4) {
     z[0] = swap32_low(swap16_even(acc[0], acc[1]), swap16_even(acc[2], acc[3]));
-  } else {
+  } else if constexpr (G <= 8) {
     z[0] = swap32_low(acc[0], acc[1]);
     z[1] = swap32_low(acc[2], acc[3]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) z[j] = acc[j];
   }
 }
 // A quantity that is uniform over each lane row of the regrouped layout, read back in the
 // matrix-core layout: the value of head 4 * g4 + i (rows that hold no head get anything).
 template <int G>
 __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], int i, int g4) {
-  if constexpr (G <= 4) {
+  if constexpr (G > 8) {
+    return x[i];
+  } else if constexpr (G <= 4) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[0]), 16 * i));
   } else {
     const int v = __builtin_bit_cast(int, x[i >> 1]);
@@ -786,10 +818,15 @@ __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], i
 // kChan: the INT8 scales are per (unit, channel).  The K scales are folded into the query (a
 // second A operand, split into an fp16 head and tail so the fold costs no accuracy), the V
 // scales multiply the output once, after the last INT8 tile; the FP16 slots then come last.
+// G is the number of query rows per unit: the group size for single-token calls (row = head),
+// or kChunkRows for multi-token calls, where row r is (token r / gq, head r % gq), padding rows
+// carry a zero query, and a row sees the call's own tokens causally.
 template <int G, bool kChan = false>
-__global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(kChan ? 2 : 3, kChan ? 2 : 3)))
+__global__ __launch_bounds__(kAttThreads)
+__attribute__((amdgpu_waves_per_eu((kChan || G > 8) ? 2 : 3, (kChan || G > 8) ? 2 : 3)))
 void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   constexpr int D = 128;
+  static_assert(G * D * 4 <= kTileBytes, "a wavefront's output partial must fit its tile buffer");
   constexpr int NP = kAttWaves;                 // one partial per wavefront
   constexpr int kTileFloats =
       (kAttWaves * kTileBytes > NP * G * D * 4 ? kAttWaves * kTileBytes : NP * G * D * 4) / 4;
@@ -797,8 +834,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   float *tiles = smem;                          // per-wave tile buffers, later [NP][G][D] partials
   float *stash = smem + kTileFloats;            // [G][S]
   float *gm = stash + (size_t)G * S;            // [G]
-  double *ginv = (double *)(gm + G + (G & 1));  // [G]
-  float *wm = (float *)(ginv + G);              // [NP][G]
+  double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
+  float *wm = (float *)(ginv + 2 * G);          // [NP][G]
   float *wl = wm + NP * G;                      // [NP][G]
   float *wo = tiles;
   __shared__ int s_ok;
@@ -871,12 +908,13 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   // g4*32 + 8s + [0,8), matching the K bytes this lane reads from the tile below.
   half8_t qa[4];
   {
-    const int Hq = cv.Hkv * G;
+    // row t16 = (token, head) of the call's [B][tq][Hq][D] queries
+    const int q_tok = t16 / a.gq, q_head = t16 - q_tok * a.gq;
+    const __half *qrow = a.q + ((((size_t)sl.b * a.tq + q_tok) * cv.Hkv + sl.g) * a.gq + q_head) * D;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       int4 raw = make_int4(0, 0, 0, 0);
-      if (t16 < G)
-        raw = *(const int4 *)(a.q + ((size_t)(sl.b * Hq + sl.g * G + t16)) * D + g4 * 32 + 8 * s);
+      if (t16 < G && q_tok < a.tq) raw = *(const int4 *)(qrow + g4 * 32 + 8 * s);
       qa[s] = __builtin_bit_cast(half8_t, raw);
     }
   }
@@ -911,6 +949,11 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   int hd[NV];                                    // head of value j of this lane
 #pragma unroll
   for (int j = 0; j < NV; ++j) { mrun[j] = NEG; lrun[j] = 0.f; pbias[j] = 0.f; hd[j] = RowMap<G>::head(j, g4); }
+  // causal order inside the call: the row of token t sees slots below n - tq + t + 1 (every
+  // slot of the unit when the call has one token)
+  int seen[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) seen[j] = sl.n - a.tq + hd[j] / a.gq + 1;
 
   // ---------------- the slice as a list of work items ----------------
   // Items 0 .. ntiles-1 are the 32-slot INT8 tiles, the rest the 16-slot FP16 tiles (the same
@@ -932,20 +975,22 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     const unsigned o1 = (unsigned)ring_row(h16, min(base + 4 + r4, last) - n8, cap16) * D + col;
     const unsigned o2 = (unsigned)ring_row(h16, min(base + 8 + r4, last) - n8, cap16) * D + col;
     const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * D + col;
-    // the appended token (slot n - 1, the last slot of the unit's last split) is taken from the
-    // call's arguments, not read back from the ring: no wait on the append's stores
-    const int newest = sl.n - 1;
-    const __half *kn = a.knew + (size_t)sl.ul * D + col, *vn = a.vnew + (size_t)sl.ul * D + col;
-    const bool f0 = min(base + r4, last) == newest, f1 = min(base + 4 + r4, last) == newest;
-    const bool f2 = min(base + 8 + r4, last) == newest, f3 = min(base + 12 + r4, last) == newest;
-    t.k0 = *(const int4 *)(f0 ? kn : K16 + o0);
-    t.v0 = *(const int4 *)(f0 ? vn : V16 + o0);
-    t.k1 = *(const int4 *)(f1 ? kn : K16 + o1);
-    t.v1 = *(const int4 *)(f1 ? vn : V16 + o1);
-    t.k2 = *(const int4 *)(f2 ? kn : K16 + o2);
-    t.v2 = *(const int4 *)(f2 ? vn : V16 + o2);
-    t.k3 = *(const int4 *)(f3 ? kn : K16 + o3);
-    t.v3 = *(const int4 *)(f3 ? vn : V16 + o3);
+    // the call's own tokens (slots n - tq .. n - 1, at the end of the unit's last split) are
+    // taken from the call's arguments, not read back from the ring: no wait on the append's stores
+    const int first_new = sl.n - a.tq;
+    const size_t tok = (size_t)cv.Hkv * D;                      // [B][tq][Hkv][D]: stride of a token
+    const __half *kn = a.knew + ((size_t)sl.b * a.tq * cv.Hkv + sl.g) * D + col;
+    const __half *vn = a.vnew + ((size_t)sl.b * a.tq * cv.Hkv + sl.g) * D + col;
+    const int s0 = min(base + r4, last) - first_new, s1 = min(base + 4 + r4, last) - first_new;
+    const int s2 = min(base + 8 + r4, last) - first_new, s3 = min(base + 12 + r4, last) - first_new;
+    t.k0 = *(const int4 *)(s0 >= 0 ? kn + s0 * tok : K16 + o0);
+    t.v0 = *(const int4 *)(s0 >= 0 ? vn + s0 * tok : V16 + o0);
+    t.k1 = *(const int4 *)(s1 >= 0 ? kn + s1 * tok : K16 + o1);
+    t.v1 = *(const int4 *)(s1 >= 0 ? vn + s1 * tok : V16 + o1);
+    t.k2 = *(const int4 *)(s2 >= 0 ? kn + s2 * tok : K16 + o2);
+    t.v2 = *(const int4 *)(s2 >= 0 ? vn + s2 * tok : V16 + o2);
+    t.k3 = *(const int4 *)(s3 >= 0 ? kn + s3 * tok : K16 + o3);
+    t.v3 = *(const int4 *)(s3 >= 0 ? vn + s3 * tok : V16 + o3);
     t.ks0 = t.ks1 = t.vs0 = t.vs1 = 0;
     return t;
   };
@@ -1004,9 +1049,9 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
       bool changed = false;
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
-        const bool real = valid && hd[j] < G;
+        const bool real = valid && hd[j] < G && base + t16 < seen[j];
         const float sv = real ? z[j] * sm : NEG;
-        if (real) stash[hd[j] * S + sl.cnt8 + (base + t16 - sl.lo16)] = sv;
+        if (valid && hd[j] < G) stash[hd[j] * S + sl.cnt8 + (base + t16 - sl.lo16)] = sv;
         const float mn = fmaxf(mrun[j], row16_max(sv));
         corr[j] = (mn == NEG) ? 1.f : __expf(mrun[j] - mn);
         changed |= (mn != mrun[j]);
@@ -1220,6 +1265,7 @@ static AttendFn attend_fn_mfma(int D, int G, bool chan) {
   case g: return chan ? (AttendFn)attend_mfma_kernel<g, true> : (AttendFn)attend_mfma_kernel<g, false>;
   switch (G) {
     CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
+    CONFKV_CASE(kChunkRows)
     default: return nullptr;
   }
 #undef CONFKV_CASE
@@ -1237,10 +1283,10 @@ static size_t attend_lds_bytes(int D, int G, int S, bool mfma) {
     const int NP = kAttWaves;
     size_t floats = (size_t)G * S + G + 2 + 2 * NP * G;
     size_t tiles = std::max<size_t>((size_t)kAttWaves * kTileBytes, (size_t)NP * G * D * sizeof(float));
-    return floats * sizeof(float) + (size_t)G * sizeof(double) + tiles + 32;
+    return floats * sizeof(float) + (size_t)2 * G * sizeof(double) + tiles + 32;
   }
   size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + 2 * kAttWaves * G + G + 2;
-  return floats * sizeof(float) + (size_t)G * sizeof(double) + 16;
+  return floats * sizeof(float) + (size_t)2 * G * sizeof(double) + 16;
 }
 
 struct DeviceLimits {
@@ -1288,11 +1334,12 @@ static int attend_occupancy(AttendFn fn, size_t lds) {
   return nb;
 }
 
-bool attend_plan(int D, int G, bool chan, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
+bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
                  bool force_two_launch, AttendPlan *plan) {
   const DeviceLimits &lim = device_limits();
-  if (!lim.ok || !attend_fn_valu(D, G)) return false;
-  const bool mfma = wants_mfma(D, G, n16_ub < n_ub);
+  if (!lim.ok) return false;
+  if (chunk ? attend_fn_mfma(D, G, chan) == nullptr : attend_fn_valu(D, G) == nullptr) return false;
+  const bool mfma = chunk || wants_mfma(D, G, n16_ub < n_ub);
   AttendFn fn = mfma ? attend_fn_mfma(D, G, chan) : attend_fn_valu(D, G);
   const long long nv = (long long)n_ub + n16_ub;
   // One workgroup per CU measured best: the exchange between the splits of a unit (arrival
@@ -1312,12 +1359,16 @@ bool attend_plan(int D, int G, bool chan, int units_per_layer, int n_ub, int n16
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
   // splits shrink the LDS stash when a long unit does not fit otherwise)
   plan->two_launch = false;
-  for (int k = 0; k < kAttendMaxSplits && !force_two_launch; ++k) {
+  for (int k = 0; k < kAttendMaxSplits && (chunk || !force_two_launch); ++k) {
     const int ns = k < want ? want - k : k + 1;
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
-    int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
-    S = (S + 255) / 256 * 256;
+    const int need = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
+    int S = (need + 255) / 256 * 256;
     size_t lds = attend_lds_bytes(D, G, S, mfma);
+    if (lds > lim.max_lds) {                    // a tight fit: give the rounding up
+      S = (need + 31) / 32 * 32;
+      lds = attend_lds_bytes(D, G, S, mfma);
+    }
     if (lds > lim.max_lds) continue;
     if (ns > 1) {
       int occ = attend_occupancy(fn, lds);
@@ -1335,6 +1386,7 @@ bool attend_plan(int D, int G, bool chan, int units_per_layer, int n_ub, int n16
   // the slice's scores do not fit LDS.  Two launches then: the first streams and publishes
   // partials, keeping the raw scores in device scratch; the second merges and updates the EMA.
   // Nothing waits inside a kernel, so any split count works.
+  if (chunk) return false;                         // multi-token calls have the single-launch form only
   {
     // same split count as the single-kernel plan would like (measured on 64 units of 4096
     // slots: 4 splits 40 us, 16 splits 80 us -- the second launch grows with the split count)
@@ -1365,12 +1417,14 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
     if (!first || !second || !a.spill) return hipErrorInvalidValue;
     hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                        plan.stash_tokens);
-    const size_t lds2 = ((size_t)plan.splits * cv.G * 2 + cv.G + 2) * sizeof(float) + cv.G * sizeof(double);
+    const size_t lds2 = ((size_t)plan.splits * cv.G * 2 + cv.G + 2) * sizeof(float) + 2 * cv.G * sizeof(double);
     hipLaunchKernelGGL(second, grid, dim3(kAttThreads), lds2, stream, cv, a, plan.splits,
                        plan.stash_tokens);
     return hipGetLastError();
   }
-  AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, cv.G, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);
+  const int rows = a.tq > 1 ? kChunkRows : cv.G;
+  if (a.tq > 1 && (!plan.mfma || plan.two_launch)) return hipErrorInvalidValue;
+  AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, rows, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                      plan.stash_tokens);

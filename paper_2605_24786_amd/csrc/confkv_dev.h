@@ -45,11 +45,11 @@ struct CacheView {
   int32_t chan;                            // INT8 scales are per (unit, channel), not per token
 };
 
-// One bit per layer: did conf_kv_attend append a token since the last commit?
+// Per layer: tokens appended by conf_kv_attend / conf_kv_attend_chunk since the last commit.
 struct LayerMask {
-  unsigned long long w[kMaxLayers / 64];
-  __host__ __device__ bool get(int l) const { return (w[l >> 6] >> (l & 63)) & 1ull; }
-  __host__ __device__ void set(int l) { w[l >> 6] |= 1ull << (l & 63); }
+  unsigned char c[kMaxLayers];
+  __host__ __device__ int get(int l) const { return c[l]; }
+  __host__ __device__ void set(int l, int count) { c[l] = (unsigned char)count; }
 };
 
 __device__ __forceinline__ int ring_row(int head, int idx, int cap16) {

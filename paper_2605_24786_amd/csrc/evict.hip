@@ -298,7 +298,7 @@ __global__ __launch_bounds__(kEvThreads) void shared_mass_kernel(CacheView cv, L
                                                                  double *__restrict__ shared) {
   const int lb = blockIdx.x, i = blockIdx.y * kEvThreads + threadIdx.x;
   const int u0 = lb * cv.Hkv;
-  const int n = cv.len[u0] + (appended.get(lb / cv.B) ? 1 : 0);
+  const int n = cv.len[u0] + appended.get(lb / cv.B);
   if (i >= n) return;
   double acc = 0.0;
   for (int g = 0; g < cv.Hkv; ++g)
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const int u = blockIdx.x;
   const int UPL = cv.B * cv.Hkv;
   const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
-  const int n = cv.len[u] + (appended.get(layer) ? 1 : 0);
+  const int n = cv.len[u] + appended.get(layer);
   const int n8 = cv.n8[u];
   const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
@@ -487,7 +487,7 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   const int u = blockIdx.x;
   const int UPL = cv.B * cv.Hkv;
   const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
-  const int n = cv.len[u] + (appended.get(layer) ? 1 : 0);
+  const int n = cv.len[u] + appended.get(layer);
   const int n8 = cv.n8[u];
   const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
@@ -736,7 +736,7 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   if (u >= U) return;
   const int UPL = cv.B * cv.Hkv;
   const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
-  const int n = cv.len[u] + (appended.get(layer) ? 1 : 0);
+  const int n = cv.len[u] + appended.get(layer);
   const int n8 = cv.n8[u];
   const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;

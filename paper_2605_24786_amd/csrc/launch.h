@@ -34,16 +34,20 @@ struct AttendLaunch {
   int max_splits;
   float sm_scale, ema_decay;
   double mass_gain;        // weight of the step's mass in the EMA update
-  int pos_new;
+  int pos_new;             // position of the first appended token
+  int tq;                  // tokens appended (and queries per head) in this call
+  int gq;                  // query heads per kv-head; the kernels' row r is (token r / gq, head r % gq)
   float *spill;            // [units per layer][splits][G][stash_tokens] raw scores (two-launch form)
   unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
 };
 constexpr int kAttendMaxSplits = 64;
+constexpr int kChunkRows = 16;     // query rows per unit of a multi-token call (one matrix-core tile)
 bool attend_supported(int D, int G);
 size_t attend_spill_floats(int units_per_layer, int G, int cap);   // scratch the two-launch form needs
 // Largest split count and LDS plan for a unit of at most n_ub tokens (after the append)
-// of which at most n16_ub are FP16.  Returns false when no plan fits the device.
-bool attend_plan(int D, int G, bool chan, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
+// of which at most n16_ub are FP16.  G = query rows per unit (the group size, or kChunkRows for
+// a multi-token call, which only has the single-launch matrix-core form).  Returns false when no plan fits the device.
+bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
                  bool force_two_launch, AttendPlan *plan);
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream);

@@ -43,6 +43,7 @@ class Workload:
     rank_scope: str = "kv_head"          # or "layer"
     ranker_seed: int = 0
     scale_mode: str = "token"            # or "channel": INT8 scales per (kv-head, channel)
+    max_chunk: int = 0                   # most tokens per multi-token attend call (0: single-token only)
     # input recipe
     heavy_hitter_prob: float = 0.02      # fraction of key positions shifted by +3 u
     heavy_hitter_gain: float = 3.0
@@ -67,7 +68,7 @@ class Workload:
     @property
     def capacity(self) -> int:
         """Slots a unit needs: the longest cache it can ever hold, plus the append."""
-        longest = max(self.prefill, max(self.n_loose), self.protected) + 1
+        longest = max(self.prefill, max(self.n_loose), self.protected) + max(1, self.max_chunk)
         return ((longest + 63) // 64) * 64
 
     def scaled(self, **kw) -> "Workload":

@@ -132,22 +132,35 @@ class Lockstep:
                 rep.max_ema_rel = max(rep.max_ema_rel, float(np.max(err[nz] / ref[nz])))
 
     # ---- one decode step ----
-    def step(self, check_state: bool = True):
+    def step(self, check_state: bool = True, tq: int = 1):
+        """One decode step; tq > 1 feeds tq tokens through one conf_kv_attend_chunk call per
+        layer (the inputs of steps t .. t + tq - 1, the logits of the last one)."""
         torch, wl, kv, rep = self.torch, self.wl, self.kv, self.report
         G = wl.group
         for l in range(wl.n_layers):
-            q, k, v = gen.step_inputs(wl, self.seed, l, self.t)
-            kv.attend(l, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(),
-                      torch.from_numpy(v).cuda(), self.out)
-            ref = self.run.attend(l, q, k, v, G)
+            if tq == 1:
+                q, k, v = gen.step_inputs(wl, self.seed, l, self.t)
+                kv.attend(l, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(),
+                          torch.from_numpy(v).cuda(), self.out)
+                ref = self.run.attend(l, q, k, v, G)
+                got = self.out.cpu().numpy().astype(np.float64) if ref else None
+            else:
+                parts = [gen.step_inputs(wl, self.seed, l, self.t + i) for i in range(tq)]
+                q, k, v = (np.ascontiguousarray(np.stack([p[j] for p in parts], axis=1)) for j in range(3))
+                out = torch.empty((wl.batch, tq, wl.n_q_heads, wl.head_dim), dtype=torch.float16, device="cuda")
+                kv.attend_chunk(l, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(),
+                                torch.from_numpy(v).cuda(), out)
+                ref = self.run.attend_chunk(l, q, k, v, G)
+                # [B][tq][Hq][D] -> per unit [tq][G][D], compared like the single-token case
+                got = out.cpu().numpy().astype(np.float64).transpose(0, 2, 1, 3) if ref else None
+                ref = {key: r.transpose(1, 0, 2) for key, r in ref.items()}      # [G][tq][D]
             if ref:
-                got = self.out.cpu().numpy().astype(np.float64)
                 for (ul, b, g), r in ref.items():
                     o = got[b, g * G:(g + 1) * G]
                     err = np.max(np.abs(o - r) / (OUT_ATOL + OUT_RTOL * np.abs(r)))
                     rep.max_out_err = max(rep.max_out_err, float(err))
                     assert err <= 1.0, f"step {self.t} unit {(ul, b, g)}: attention output off by {err:.3g} x tolerance"
-        logits = gen.step_logits(wl, self.seed, self.t)
+        logits = gen.step_logits(wl, self.seed, self.t + tq - 1)
         kv.step(torch.from_numpy(logits).cuda(), self.conf, self.sel)
         c_ref, tight_ref = self.run.step(logits)
         c_gpu = self.conf.cpu().numpy().astype(np.float64)
@@ -177,7 +190,7 @@ class Lockstep:
             self._adopt(key, before[key], ex_pos, sel_gpu[key[1]])
         if check_state:
             self.compare_state("after evict")
-        self.t += 1
+        self.t += tq
         rep.steps += 1
         rep.unit_steps += len(self.run.units)
         first = next(iter(self.run.units.values()))

@@ -243,6 +243,129 @@ def test_attend_channel_scales_sharp_softmax(lib, torch_cuda):
     _attend_case(lib, torch_cuda, 128, 4, 1, 1, 900, 32, 6, seed=5, scale_q=6.0, scale_mode="channel")
 
 
+def _chunk_case(lib, torch, G, H, B, T0, W, splits, tqs, seed, scale_mode="token"):
+    say(f"chunks G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} tq={tqs} scales={scale_mode}")
+    D = 128
+    if splits:
+        os.environ["CONF_KV_SPLITS"] = str(splits)
+    try:
+        cap = ((T0 + sum(tqs) + 8 + 63) // 64) * 64
+        kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
+                 protected_window=4, n_tight=[cap - 17], n_loose=[cap - 16], scale_mode=scale_mode,
+                 max_chunk=max(tqs))
+    finally:
+        os.environ.pop("CONF_KV_SPLITS", None)
+    rng = np.random.default_rng(seed)
+    K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    e0 = rng.random((B, H, T0)).astype(np.float32)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(), torch.from_numpy(e0).cuda())
+    units = {(b, g): O.load_prefill(K[b, g], V[b, g], W, e0[b, g], scale_mode=scale_mode)
+             for b in range(B) for g in range(H)}
+    sm, lam = f32(1 / math.sqrt(D)), f32(0.9)
+    pos = T0
+    for tq in tqs:
+        q = rng.standard_normal((B, tq, G * H, D)).astype(np.float16)
+        kn = rng.standard_normal((B, tq, H, D)).astype(np.float16)
+        vn = rng.standard_normal((B, tq, H, D)).astype(np.float16)
+        # keys of the chunk that attract the chunk's own later queries: the causal part matters
+        kn[:, 0] = (kn[:, 0].astype(np.float32) + 0.5 * q[:, -1, ::G][:, :H].astype(np.float32)).astype(np.float16)
+        out = torch.zeros((B, tq, G * H, D), dtype=torch.float16, device="cuda")
+        if tq == 1:
+            kv.attend(0, torch.from_numpy(q[:, 0].copy()).cuda(), torch.from_numpy(kn[:, 0].copy()).cuda(),
+                      torch.from_numpy(vn[:, 0].copy()).cuda(), out[:, 0])
+        else:
+            kv.attend_chunk(0, torch.from_numpy(q).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda(), out)
+        got = out.cpu().numpy().astype(np.float64)
+        for (b, g), u in units.items():
+            ref, _ = O.attend_chunk_unit(u, q[b, :, g * G:(g + 1) * G], kn[b, :, g], vn[b, :, g], pos, sm, lam)
+            o = got[b, :, g * G:(g + 1) * G]
+            err = np.max(np.abs(o - ref) / (1e-3 + 2e-3 * np.abs(ref)))
+            assert err <= 1.0, f"tq {tq} unit {(b, g)}: out off by {err:.3g} x tol"
+            ex = kv.export(0, b, g)
+            assert ex["n"] == u.n and np.array_equal(ex["pos"], u.pos.astype(np.int32)) and ex["is16"][-tq:].all()
+            assert np.array_equal(ex["k16"][-tq:].view(np.uint16), kn[b, :, g].view(np.uint16))
+            assert np.array_equal(ex["v16"][-tq:].view(np.uint16), vn[b, :, g].view(np.uint16))
+            e_ref = u.ema.astype(np.float64)
+            e_err = np.abs(ex["ema"].astype(np.float64) - e_ref)
+            assert np.all(e_err <= 1e-7 + 2e-5 * e_ref), f"tq {tq} unit {(b, g)}: EMA off, max rel {np.max(e_err / (e_ref + 1e-30)):.3g}"
+        pos += tq
+        kv.evict_compact()                          # budgets above the length: commit + demotion only
+        for u in units.values():
+            O.demote(u, W)
+    for (b, g), u in units.items():
+        ex = kv.export(0, b, g)
+        assert np.array_equal(ex["is16"], u.is16)
+        m8 = ~u.is16
+        assert np.array_equal(ex["k8"][m8], u.k8[m8]) and np.array_equal(ex["v8"][m8], u.v8[m8])
+    assert kv.counters().evicted == 0
+    kv.close()
+
+
+@pytest.mark.parametrize("G,H,B,T0,W,splits,tqs,scales", [
+    (4, 2, 2, 777, 40, 0, (4, 1, 3, 4), "token"),        # Llama-like group: up to 4 tokens a call
+    (4, 1, 1, 1500, 128, 7, (4, 4), "token"),            # ragged splits, the chunk crosses tile borders
+    (1, 2, 1, 300, 16, 2, (16, 5, 16), "token"),         # MHA: 16 tokens a call
+    (2, 1, 1, 300, 0, 2, (8, 8), "token"),               # W = 0: everything but the chunk is INT8
+    (5, 2, 1, 600, 24, 3, (3, 2, 3), "token"),           # 15 of 16 rows in use
+    (8, 1, 1, 260, 16, 2, (2, 2), "token"),
+    (3, 1, 2, 200, -1, 2, (5, 5, 1, 5), "token"),        # FP16-only cache at D = 128
+    (4, 1, 1, 0, 6, 0, (4, 4, 4), "token"),              # from an empty cache: the chunk sees only itself
+    (4, 2, 1, 700, 32, 3, (4, 2, 4), "channel"),         # per-channel scales
+    (1, 1, 1, 500, 20, 1, (16, 16), "channel"),
+    (4, 1, 1, 3000, 64, 0, (4, 4), "token"),             # default plan of a long unit (several splits)
+])
+def test_attend_chunk_matches_oracle(lib, torch_cuda, G, H, B, T0, W, splits, tqs, scales):
+    """Several tokens per call: one read of the cache serves all their queries; outputs, the
+    telescoped importance update, the appended rows and the later demotions follow the oracle."""
+    _chunk_case(lib, torch_cuda, G, H, B, T0, W, splits, tqs, seed=11 * G + T0, scale_mode=scales)
+
+
+@pytest.mark.parametrize("G,W,scales", [(4, 8, "token"), (1, 8, "token"), (2, -1, "token"), (4, 30, "channel")])
+def test_lockstep_chunks_with_eviction(lib, torch_cuda, G, W, scales):
+    """Whole steps whose attention appends 1 .. 16/G tokens at a time, with the budget rule
+    evicting in between (several tokens leave per step) on wrapping rings."""
+    mc = 16 // G
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=128, vocab=3001,
+                         prefill=100, steps=150, n_tight=(90, 70), n_loose=(100, 96), protected=max(8, mc),
+                         fp16_window=W, logit_std=(0.5, 6.0), logit_run=5, alpha=0.5, scale_mode=scales,
+                         max_chunk=mc)
+    say(f"chunk lockstep: G={G} W={W} scales={scales} max_chunk={mc}")
+    ls = Lockstep(lib, wl, seed=29)
+    rng = np.random.default_rng(4)
+    for t in range(wl.steps):
+        ls.step(tq=int(rng.integers(1, mc + 1)))
+    rep = ls.report
+    st = ls.kv.counters()
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"ties={rep.evict_ties} flips={rep.evict_flips}/{rep.budget_flips} demoted={st.demoted}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.evictions > wl.steps and st.device_errors == 0
+    ls.close()
+
+
+def test_chunk_call_errors(lib, torch_cuda):
+    torch = torch_cuda
+    kv = _mk(lib, max_chunk=3, capacity=64, n_tight=[40], n_loose=[50])
+    D = 128
+    z = lambda *shape: torch.zeros(shape, dtype=torch.float16, device="cuda")
+    with pytest.raises(lib.ConfKVError) as ei:
+        kv.attend_chunk(0, z(1, 4, 4, D), z(1, 4, 1, D), z(1, 4, 1, D), z(1, 4, 4, D))     # tq > max_chunk
+    assert ei.value.status == lib.binding.ERR_INVALID_ARG
+    kv.attend_chunk(0, z(1, 3, 4, D), z(1, 3, 1, D), z(1, 3, 1, D), z(1, 3, 4, D))
+    with pytest.raises(lib.ConfKVError) as ei:
+        kv.attend(0, z(1, 4, D), z(1, 1, D), z(1, 1, D), z(1, 4, D))                       # second append before the commit
+    assert ei.value.status == lib.binding.ERR_BAD_STATE
+    assert kv.lengths()[0][0, 0] == 3
+    kv.evict_compact()
+    assert kv.lengths()[0][0, 0] == 3 and np.array_equal(kv.export(0, 0, 0)["pos"], [0, 1, 2])
+    kv.close()
+    plain = _mk(lib)                                                                        # max_chunk = 0
+    with pytest.raises(lib.ConfKVError):
+        plain.attend_chunk(0, z(1, 2, 4, D), z(1, 2, 1, D), z(1, 2, 1, D), z(1, 2, 4, D))
+    plain.close()
+
+
 def test_attend_sharp_softmax(lib, torch_cuda):
     # large-magnitude queries: a few slots take nearly all the mass, the rest underflow
     _attend_case(lib, torch_cuda, 128, 4, 1, 1, 900, 32, 6, seed=5, scale_q=6.0)
