@@ -428,19 +428,19 @@ __device__ __forceinline__ bool arrive_and_wait(const CacheView &cv, const Atten
 // Query row r of a unit is (token r / gq of the call, head r % gq of the group); rows past
 // tq * gq are padding.  Element e = r * D + d of the unit's [rows][D] output lives at
 // out[b][token][g * gq + head][d].
-__device__ __forceinline__ size_t out_index(const CacheView &cv, const AttendLaunch &a, const Slice &sl,
+__device__ __forceinline__ size_t out_index(const CacheView &cv, const Slice &sl, int tq, int gq,
                                             int e, int D) {
   const int r = e / D, d = e - r * D;
-  const int t = r / a.gq, hq = r - t * a.gq;
-  return ((((size_t)sl.b * a.tq + t) * cv.Hkv + sl.g) * a.gq + hq) * D + d;
+  const int t = r / gq, hq = r - t * gq;
+  return ((((size_t)sl.b * tq + t) * cv.Hkv + sl.g) * gq + hq) * D + d;
 }
 // Weight of row r's mass in the importance update of a call with tq tokens:
 // lambda^(tq - 1 - token), 0 for padding rows; for tq = 1 it is exactly 1.
-__device__ __forceinline__ double row_weight(const AttendLaunch &a, int r) {
-  const int t = r / a.gq;
-  if (t >= a.tq) return 0.0;
+__device__ __forceinline__ double row_weight(const AttendLaunch &a, int tq, int gq, int r) {
+  const int t = r / gq;
+  if (t >= tq) return 0.0;
   double w = 1.0;
-  for (int k = t + 1; k < a.tq; ++k) w *= (double)a.ema_decay;
+  for (int k = t + 1; k < tq; ++k) w *= (double)a.ema_decay;
   return w;
 }
 
@@ -460,6 +460,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
                                                 double *ginv, int *s_ok) {
   const int tid = threadIdx.x;
   const float NEG = -INFINITY;
+  // more than 8 rows only occur in multi-token calls; otherwise rows are the heads of one token
+  const int tq = G > 8 ? a.tq : 1, gq = G > 8 ? a.gq : G;
   float *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
   float *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
   // the EMA values this thread will update: requested now, needed after the wait
@@ -509,8 +511,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       __half2 o2;
       o2.x = __float2half_rn((float)((double)o0 * inv));
       o2.y = __float2half_rn((float)((double)o1 * inv));
-      if (h < a.tq * a.gq) *(__half2 *)&a.out[out_index(cv, a, sl, idx, D)] = o2;
-      if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, h); }
+      if (h < tq * gq) *(__half2 *)&a.out[out_index(cv, sl, tq, gq, idx, D)] = o2;
+      if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
     } else {
       st_agent2(&po[idx], o0, o1);
       if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
@@ -553,7 +555,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       const float M = wave_max(ms);
       const double term = ms > NEG ? exp((double)ms - (double)M) * (double)pml[(sp * G + h) * 2 + 1] : 0.0;
       const double L = wave_sum(term);
-      if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; ginv[G + h] = (1.0 / L) * row_weight(a, h); }
+      if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; ginv[G + h] = (1.0 / L) * row_weight(a, tq, gq, h); }
     }
   }  // exchange
   __syncthreads();
@@ -562,10 +564,10 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   // a <- lambda^tq a + gain * sum over the rows of lambda^(tq-1-token) p; ginv[G + h] holds
   // row h's weight over its normaliser.  Slots appended by this call start at 0.
   double lam = 1.0;
-  for (int k = 0; k < a.tq; ++k) lam *= (double)a.ema_decay;
+  for (int k = 0; k < tq; ++k) lam *= (double)a.ema_decay;
   const double oml = a.mass_gain;
   const double *gw = ginv + G;
-  const int first_new = sl.n - a.tq;
+  const int first_new = sl.n - tq;
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
     const int t = tid + k * kAttThreads;
@@ -614,8 +616,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       const float ms = valid ? pml[(os * G + h) * 2] : NEG;
       float c = ms > NEG ? v * expf(ms - gm[h]) : 0.f;               // an empty partial weighs nothing
       for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
-      if (valid && os == 0 && h < a.tq * a.gq)
-        a.out[out_index(cv, a, sl, e, D)] = __float2half_rn((float)((double)c * ginv[h]));
+      if (valid && os == 0 && h < tq * gq)
+        a.out[out_index(cv, sl, tq, gq, e, D)] = __float2half_rn((float)((double)c * ginv[h]));
     }
   }
 }
@@ -841,6 +843,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   __shared__ int s_ok;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tq = G > 8 ? a.tq : 1, gq = G > 8 ? a.gq : G;   // tokens of the call, heads per token
   TS(0);
   const Slice sl = make_slice(cv, a, ns, S);
   const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
@@ -909,12 +912,12 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   half8_t qa[4];
   {
     // row t16 = (token, head) of the call's [B][tq][Hq][D] queries
-    const int q_tok = t16 / a.gq, q_head = t16 - q_tok * a.gq;
-    const __half *qrow = a.q + ((((size_t)sl.b * a.tq + q_tok) * cv.Hkv + sl.g) * a.gq + q_head) * D;
+    const int q_tok = t16 / gq, q_head = t16 - q_tok * gq;
+    const __half *qrow = a.q + ((((size_t)sl.b * tq + q_tok) * cv.Hkv + sl.g) * gq + q_head) * D;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       int4 raw = make_int4(0, 0, 0, 0);
-      if (t16 < G && q_tok < a.tq) raw = *(const int4 *)(qrow + g4 * 32 + 8 * s);
+      if (t16 < G && q_tok < tq) raw = *(const int4 *)(qrow + g4 * 32 + 8 * s);
       qa[s] = __builtin_bit_cast(half8_t, raw);
     }
   }
@@ -953,7 +956,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   // slot of the unit when the call has one token)
   int seen[NV];
 #pragma unroll
-  for (int j = 0; j < NV; ++j) seen[j] = sl.n - a.tq + hd[j] / a.gq + 1;
+  for (int j = 0; j < NV; ++j) seen[j] = sl.n - tq + hd[j] / gq + 1;
 
   // ---------------- the slice as a list of work items ----------------
   // Items 0 .. ntiles-1 are the 32-slot INT8 tiles, the rest the 16-slot FP16 tiles (the same
@@ -977,10 +980,10 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * D + col;
     // the call's own tokens (slots n - tq .. n - 1, at the end of the unit's last split) are
     // taken from the call's arguments, not read back from the ring: no wait on the append's stores
-    const int first_new = sl.n - a.tq;
+    const int first_new = sl.n - tq;
     const size_t tok = (size_t)cv.Hkv * D;                      // [B][tq][Hkv][D]: stride of a token
-    const __half *kn = a.knew + ((size_t)sl.b * a.tq * cv.Hkv + sl.g) * D + col;
-    const __half *vn = a.vnew + ((size_t)sl.b * a.tq * cv.Hkv + sl.g) * D + col;
+    const __half *kn = a.knew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * D + col;
+    const __half *vn = a.vnew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * D + col;
     const int s0 = min(base + r4, last) - first_new, s1 = min(base + 4 + r4, last) - first_new;
     const int s2 = min(base + 8 + r4, last) - first_new, s3 = min(base + 12 + r4, last) - first_new;
     t.k0 = *(const int4 *)(s0 >= 0 ? kn + s0 * tok : K16 + o0);
