@@ -823,7 +823,9 @@ __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], i
 // G is the number of query rows per unit: the group size for single-token calls (row = head),
 // or kChunkRows for multi-token calls, where row r is (token r / gq, head r % gq), padding rows
 // carry a zero query, and a row sees the call's own tokens causally.
-template <int G, bool kChan = false>
+// kSpill: the first launch of the two-launch form (raw scores to device scratch, ends after
+// publishing its partial).
+template <int G, bool kChan = false, bool kSpill = false>
 __global__ __launch_bounds__(kAttThreads)
 __attribute__((amdgpu_waves_per_eu((kChan || G > 8) ? 2 : 3, (kChan || G > 8) ? 2 : 3)))
 void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
@@ -834,8 +836,9 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
       (kAttWaves * kTileBytes > NP * G * D * 4 ? kAttWaves * kTileBytes : NP * G * D * 4) / 4;
   extern __shared__ __align__(16) float smem[];
   float *tiles = smem;                          // per-wave tile buffers, later [NP][G][D] partials
-  float *stash = smem + kTileFloats;            // [G][S]
-  float *gm = stash + (size_t)G * S;            // [G]
+  float *stash = kSpill ? a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S
+                        : smem + kTileFloats;   // [G][S]
+  float *gm = smem + kTileFloats + (kSpill ? 0 : (size_t)G * S);   // [G]
   double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
   float *wm = (float *)(ginv + 2 * G);          // [NP][G]
   float *wl = wm + NP * G;                      // [NP][G]
@@ -1229,7 +1232,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   TS(17);
   __syncthreads();
   TS(18);
-  attend_epilogue<D, G, NP, kTileBytes / 4>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+  attend_epilogue<D, G, NP, kTileBytes / 4, kSpill ? 1 : 0>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1269,6 +1272,17 @@ static AttendFn attend_fn_mfma(int D, int G, bool chan) {
   switch (G) {
     CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
     CONFKV_CASE(kChunkRows)
+    default: return nullptr;
+  }
+#undef CONFKV_CASE
+}
+
+static AttendFn attend_fn_mfma_spill(int D, int G, bool chan) {
+  if (D != 128) return nullptr;
+#define CONFKV_CASE(g) \
+  case g: return chan ? (AttendFn)attend_mfma_kernel<g, true, true> : (AttendFn)attend_mfma_kernel<g, false, true>;
+  switch (G) {
+    CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
     default: return nullptr;
   }
 #undef CONFKV_CASE
@@ -1396,12 +1410,13 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
     const int ns = want;
     int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
     S = (S + 255) / 256 * 256;
-    const size_t lds = attend_lds_bytes(D, G, 0, false);
+    const size_t lds = attend_lds_bytes(D, G, 0, mfma);
     if (lds > lim.max_lds) return false;
+    if (lds > 64 * 1024) (void)attend_occupancy(attend_fn_mfma_spill(D, G, chan), lds);   // raises the dynamic-LDS limit
     plan->splits = ns;
     plan->stash_tokens = S;
     plan->lds_bytes = lds;
-    plan->mfma = false;
+    plan->mfma = mfma;
     plan->two_launch = true;
     return true;
   }
@@ -1416,7 +1431,8 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                          hipStream_t stream) {
   dim3 grid(plan.splits, cv.B * cv.Hkv);
   if (plan.two_launch) {
-    AttendFn first = attend_fn_spill(cv.D, cv.G, false), second = attend_fn_spill(cv.D, cv.G, true);
+    AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, cv.G, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
+    AttendFn second = attend_fn_spill(cv.D, cv.G, true);
     if (!first || !second || !a.spill) return hipErrorInvalidValue;
     hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                        plan.stash_tokens);
