@@ -94,6 +94,25 @@ def test_full_size_channel_scales(lib):
     ls.close()
 
 
+def test_full_size_chunks(lib):
+    """Four tokens per attention call at the roofline workload's shape (4 of its layers): the
+    16-row score stash only just fits next to the tile buffers, the chunk straddles the splits'
+    FP16 shares, and the first step's eviction takes 2052 tokens per unit."""
+    wl = workload(1).scaled(name="llama3_8b_b8_t4096_chunk4", n_layers=4, n_tight=(1024,) * 4,
+                            n_loose=(2048,) * 4, steps=3, max_chunk=4, logit_std=(0.5, 6.0), logit_run=1)
+    print(f"chunks at full size: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=0, units=6, threads=16)
+    for t, tq in enumerate((4, 3, 4)):
+        ls.step(tq=tq)
+        _invariants_all_units(ls, wl, ls.t - 1)
+        print(f"  step {t} (tq={tq}): len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    print(f"  ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} flips={rep.evict_flips}/{rep.budget_flips}", flush=True)
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 def test_needle_retention_full_size(lib):
     """Retrieval stress at full cache length (one layer): every planted needle survives the
     32769 -> 4096 eviction after the first probe step, on every unit of the layer."""
