@@ -173,6 +173,11 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16,
  * Exactly one conf_kv_attend per layer between two conf_kv_evict_compact calls
  * (CONF_KV_ERR_BAD_STATE otherwise); CONF_KV_ERR_CAPACITY, before anything is launched,
  * if the unit could already hold `capacity` tokens.
+ * The workgroups that share a unit exchange partial results inside the launch, so the launch
+ * is sized to be resident on the device all at once.  Other kernels running at the same time
+ * only delay it (its waits are bounded at several hundred milliseconds); a wait that does
+ * expire leaves the call's outputs undefined and is reported by conf_kv_counters
+ * (device_errors, CONF_KV_ERR_DEVICE).
  */
 int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const void *dev_knew16,
                    const void *dev_vnew16, void *dev_out16, conf_kv_stream stream);
