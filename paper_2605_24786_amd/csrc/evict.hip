@@ -479,7 +479,8 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   constexpr int kRsWaves = T / kWave;
   __shared__ int hist[512];                         // two histograms, used alternately
   __shared__ int s_tmp[kRsWaves];
-  __shared__ int s_cnt[E * kRsWaves];               // kept (or tied) lanes per (round, wavefront)
+  __shared__ int s_cnt[E * kRsWaves];               // tied lanes per (round, wavefront)
+  __shared__ int s_keep[E * kRsWaves + 1];          // kept lanes per (round, wavefront), then their prefix sums
   __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
   __shared__ unsigned long long s_prefix, s_kmin[kRsWaves], s_kmax[kRsWaves];
   __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves], s_last8[kRsWaves];
@@ -643,8 +644,10 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
     }
     __syncthreads();
   }
-  // eviction flags as a bit per round
+  // eviction flags as a bit per round, and in the same walk the survivors per (round,
+  // wavefront), the INT8 survivors, the first hole and the last hole of the shiftable ring
   unsigned long long evbits = 0ull;                 // E <= 64
+  int kept8 = 0, hole = n, last8 = -1;
 #pragma unroll
   for (int k = 0; k < E; ++k) {
     if (k < Ed) {
@@ -663,18 +666,9 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
         if (tie) ev = s_cnt[k * kRsWaves + w] + lanes_below(bm) < krem;
       }
       if (ev) evbits |= 1ull << k;
-    }
-  }
-  __syncthreads();                                  // s_cnt is reused for the keep counts
-  int kept8 = 0, hole = n, last8 = -1;
-#pragma unroll
-  for (int k = 0; k < E; ++k) {
-    if (k < Ed) {
-      const int i = tid + k * T;
-      const bool ev = (evbits >> k) & 1ull;
       const bool keep = i < n && !ev;
-      const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
-      if (lane == 0) s_cnt[k * kRsWaves + w] = __builtin_popcountll(bm);
+      const unsigned long long kb = __builtin_amdgcn_ballot_w64(keep);
+      if (lane == 0) s_keep[k * kRsWaves + w] = __builtin_popcountll(kb);
       kept8 += keep && i < n8;
       if (ev) {
         hole = min(hole, i);
@@ -693,10 +687,11 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   int tot_keep = 0;
   {
     // Ed * waves <= T for every instantiation's limits: one scan
-    const int v = tid < Ed * kRsWaves ? s_cnt[tid] : 0;
+    const int v = tid < Ed * kRsWaves ? s_keep[tid] : 0;
     const int ex = block_scan_excl<kRsWaves>(v, s_tmp, &tot_keep);
     __syncthreads();
-    if (tid < Ed * kRsWaves) s_cnt[tid] = ex;
+    if (tid < Ed * kRsWaves) s_keep[tid] = ex;
+    if (tid == 0) s_keep[Ed * kRsWaves] = tot_keep;
   }
   __syncthreads();
   // the compaction only looks up the source of the slots that move
@@ -704,11 +699,16 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
 #pragma unroll
   for (int k = 0; k < E; ++k) {
     if (k < Ed) {
-      const int i = tid + k * T;
-      const bool keep = i < n && !((evbits >> k) & 1ull);
-      const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
-      const int j = s_cnt[k * kRsWaves + w] + lanes_below(bm);
-      if (keep && j >= sp.lo && j < sp.hi) src[j] = i;
+      // new slots [first, next) come from this wavefront's lanes of round k; most rounds lie
+      // wholly outside the moving range and are skipped
+      const int first = s_keep[k * kRsWaves + w], next = s_keep[k * kRsWaves + w + 1];
+      if (first < sp.hi && next > sp.lo) {
+        const int i = tid + k * T;
+        const bool keep = i < n && !((evbits >> k) & 1ull);
+        const unsigned long long bm = __builtin_amdgcn_ballot_w64(keep);
+        const int j = first + lanes_below(bm);
+        if (keep && j >= sp.lo && j < sp.hi) src[j] = i;
+      }
     }
   }
   if (tid == 0) {
