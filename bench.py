@@ -65,6 +65,42 @@ def step_bytes(wl, n8, n16, moved_bytes):
     return att + logits + rank + int(moved_bytes) + demote, att
 
 
+def read_probe(torch, pkg, launch_bytes):
+    """What a plain read-only pass reaches on this machine (context for the roofline fraction, which
+    is quoted against the published 8 TB/s): the library's probe kernel (16-byte loads, 8 in
+    flight per thread, 4096 workgroups) over 2 GiB in one launch, and over different regions of
+    `launch_bytes` each, one launch per region -- the shape of a decode step, where every layer's
+    cache is read once and nothing is reused between launches.  torch's sum is timed the same way
+    as a cross-check."""
+    x = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_()
+    per = max(4, launch_bytes // 16 * 4)                 # floats per region, a multiple of 16 bytes
+    regions = [x[i * per:(i + 1) * per] for i in range(min(28, x.numel() // per))]
+    wgs = 4096                                           # best of a sweep from 256 to 16384
+    out = torch.zeros(wgs, dtype=torch.int32, device="cuda")
+
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(reps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / reps
+
+    big = timed(lambda: pkg.probe_read(x, out, wgs), 5)
+    reg = timed(lambda: [pkg.probe_read(r, out, wgs) for r in regions], 3) / len(regions)
+    big_t = timed(lambda: x.sum(), 5)
+    reg_t = timed(lambda: [r.sum() for r in regions], 3) / len(regions)
+    gb = lambda nbytes, ms: nbytes / ms / 1e6
+    return {"kind": "conf_kv_probe_read (torch.sum as cross-check)",
+            "stream_2GiB_GBps": gb(x.numel() * 4, big), "per_launch_GBps": gb(per * 4, reg),
+            "per_launch_bytes": per * 4, "per_launch_us": reg * 1e3,
+            "torch_sum_stream_GBps": gb(x.numel() * 4, big_t), "torch_sum_per_launch_GBps": gb(per * 4, reg_t)}
+
+
 def cpu_baseline(wl, seed, budget_s=15.0):
     """The oracle, as it stands, on a bounded sample of units of the same workload."""
     from threadpoolctl import threadpool_limits
@@ -308,6 +344,9 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.seed)
     kv.close()
+    del kv, prompts
+    torch.cuda.empty_cache()
+    result["roofline"]["read_probe"] = read_probe(torch, pkg, att_bytes)
     print(json.dumps(result))
 
 

@@ -268,6 +268,15 @@ const char *conf_kv_strerror(int status);
 /* The hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int conf_kv_last_hip_error(conf_kv_handle *h);
 
+/* Measurement aid, not part of the decode path: one launch that reads dev_src[0 .. bytes) once
+ * (plain 16-byte loads, `workgroups` workgroups of 256 threads over equal contiguous shares)
+ * and folds it into dev_out, uint32 [workgroups], which the caller has zeroed.  What this
+ * reaches is the practical ceiling of a streaming read on the device, to set next to the
+ * published peak.  bytes a positive multiple of 16, dev_src 16-byte aligned, 1 <= workgroups
+ * <= 65536; CONF_KV_ERR_INVALID_ARG otherwise, CONF_KV_ERR_HIP if the launch fails. */
+int conf_kv_probe_read(const void *dev_src, size_t bytes, uint32_t *dev_out, int32_t workgroups,
+                       conf_kv_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,6 +71,7 @@ SYMBOLS = {
     "conf_kv_attend_splits": (C.c_int, [_P, C.c_int32]),
     "conf_kv_strerror": (C.c_char_p, [C.c_int]),
     "conf_kv_last_hip_error": (C.c_int, [_P]),
+    "conf_kv_probe_read": (C.c_int, [_P, C.c_size_t, _P, C.c_int32, _P]),
 }
 
 _lib = None
@@ -120,6 +121,17 @@ def pyramid_budgets(n0: int, n_layers: int, beta: float = 0.5, n_min: int = 96):
     if rc != OK:
         raise ConfKVError(rc, "conf_kv_pyramid_budgets")
     return list(out)
+
+
+def probe_read(src, out, workgroups: int, stream=None) -> None:
+    """One read-only pass over the torch tensor `src` (see conf_kv_probe_read); `out` is a zeroed
+    uint32/int32 tensor of `workgroups` elements."""
+    import torch
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    rc = load_library().conf_kv_probe_read(src.data_ptr(), src.numel() * src.element_size(), out.data_ptr(),
+                                           workgroups, st)
+    if rc != OK:
+        raise ConfKVError(rc, "conf_kv_probe_read")
 
 
 def _ptr(t) -> Optional[int]:

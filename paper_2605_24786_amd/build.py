@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libconfkv.so")
-SOURCES = ["api.hip", "conf_reduce.hip", "attend.hip", "evict.hip"]
+SOURCES = ["api.hip", "conf_reduce.hip", "attend.hip", "evict.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -584,4 +584,14 @@ const char *conf_kv_strerror(int status) {
 
 int conf_kv_last_hip_error(conf_kv_handle *h) { return h ? h->last_hip : 0; }
 
+int conf_kv_probe_read(const void *dev_src, size_t bytes, uint32_t *dev_out, int32_t workgroups,
+                       conf_kv_stream stream) {
+  if (!dev_src || !dev_out || bytes == 0 || bytes % 16 || ((uintptr_t)dev_src & 15) || workgroups < 1 ||
+      workgroups > 65536)
+    return CONF_KV_ERR_INVALID_ARG;
+  return launch_probe_read(dev_src, bytes, dev_out, workgroups, (hipStream_t)stream) == hipSuccess
+             ? CONF_KV_OK
+             : CONF_KV_ERR_HIP;
+}
+
 }  // extern "C"

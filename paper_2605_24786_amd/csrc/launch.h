@@ -15,6 +15,9 @@ hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, f
                               unsigned *arrive, float *conf, uint8_t *sel, double tau, double wH,
                               double wm, double wp, hipStream_t stream);
 
+// ---- probe.hip ----
+hipError_t launch_probe_read(const void *src, size_t bytes, unsigned *out, int workgroups, hipStream_t stream);
+
 // ---- attend.hip ----
 struct AttendPlan {
   int splits;        // workgroups per unit

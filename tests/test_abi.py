@@ -95,6 +95,12 @@ def test_null_and_misaligned_arguments(clib):
     assert clib.conf_kv_evict_compact(None, None) == E
     assert clib.conf_kv_lengths(None, None, None) == E
     assert clib.conf_kv_last_hip_error(None) == 0
+    # the bandwidth probe validates its arguments before anything is launched
+    bad = pkg.binding.ERR_INVALID_ARG
+    assert clib.conf_kv_probe_read(None, 1024, 256, 4, None) == bad
+    assert clib.conf_kv_probe_read(256, 1000, 256, 4, None) == bad       # not a multiple of 16
+    assert clib.conf_kv_probe_read(264, 1024, 256, 4, None) == bad       # misaligned source
+    assert clib.conf_kv_probe_read(256, 1024, 256, 0, None) == bad
     for s in range(-7, 1):
         assert pkg.strerror(s) and pkg.strerror(s) != "unknown status"
     assert pkg.strerror(-99) == "unknown status"

@@ -660,3 +660,16 @@ def test_call_order_and_capacity_errors(lib, torch_cuda):
     ln, n16 = kv.lengths()
     assert ln.tolist() == [[1]] and n16.tolist() == [[[1]]]
     kv.close()
+
+
+def test_probe_read_reads_every_byte_once(lib, torch_cuda):
+    """The bandwidth probe of the benchmark: its fold is the XOR of every 32-bit word, so a
+    skipped or doubly read range would show."""
+    torch = torch_cuda
+    rng = np.random.default_rng(12)
+    for n16, wgs in ((1, 1), (1000, 7), (70001, 256), (1 << 20, 2048)):
+        x = rng.integers(-2**31, 2**31 - 1, size=n16 * 4, dtype=np.int64).astype(np.int32)
+        out = torch.zeros(wgs, dtype=torch.int32, device="cuda")
+        lib.probe_read(torch.from_numpy(x).cuda(), out, wgs)
+        got = np.bitwise_xor.reduce(out.cpu().numpy().view(np.uint32))
+        assert got == np.bitwise_xor.reduce(x.view(np.uint32)), (n16, wgs)
