@@ -873,23 +873,24 @@ __device__ __forceinline__ void move_rows(uint8_t *base_ptr, const int32_t *__re
   const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
   const int cnt = hi - lo;
   for (int done = 0; done < cnt; done += RPP * PASSES) {
-    int from[PASSES];
-    int4 buf[PASSES];
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-      const int k = done + p * RPP + r0;               // k-th slot of the walk
-      if (k < cnt) from[p] = src[right ? hi - 1 - k : lo + k];
-    }
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p)
-      if (done + p * RPP + r0 < cnt) buf[p] = *(const int4 *)(base_ptr + (size_t)srow(from[p]) * ROWB + c * 16);
+    // four passes written out with scalar variables: as arrays the rows took a detour
+    // through scratch memory
+    const int k0 = done + r0, k1 = k0 + RPP, k2 = k1 + RPP, k3 = k2 + RPP;   // k-th slots of the walk
+    int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
+    int4 b0, b1, b2, b3;
+    if (k0 < cnt) f0 = src[right ? hi - 1 - k0 : lo + k0];
+    if (k1 < cnt) f1 = src[right ? hi - 1 - k1 : lo + k1];
+    if (k2 < cnt) f2 = src[right ? hi - 1 - k2 : lo + k2];
+    if (k3 < cnt) f3 = src[right ? hi - 1 - k3 : lo + k3];
+    if (k0 < cnt) b0 = *(const int4 *)(base_ptr + (size_t)srow(f0) * ROWB + c * 16);
+    if (k1 < cnt) b1 = *(const int4 *)(base_ptr + (size_t)srow(f1) * ROWB + c * 16);
+    if (k2 < cnt) b2 = *(const int4 *)(base_ptr + (size_t)srow(f2) * ROWB + c * 16);
+    if (k3 < cnt) b3 = *(const int4 *)(base_ptr + (size_t)srow(f3) * ROWB + c * 16);
     __syncthreads();
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-      const int k = done + p * RPP + r0;
-      const int j = right ? hi - 1 - k : lo + k;
-      if (k < cnt) *(int4 *)(base_ptr + (size_t)drow(j) * ROWB + c * 16) = buf[p];
-    }
+    if (k0 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k0 : lo + k0) * ROWB + c * 16) = b0;
+    if (k1 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k1 : lo + k1) * ROWB + c * 16) = b1;
+    if (k2 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k2 : lo + k2) * ROWB + c * 16) = b2;
+    if (k3 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k3 : lo + k3) * ROWB + c * 16) = b3;
   }
 }
 
