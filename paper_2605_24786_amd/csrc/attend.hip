@@ -1288,9 +1288,10 @@ static AttendFn attend_fn_mfma_spill(int D, int G, bool chan) {
 #undef CONFKV_CASE
 }
 
-// The matrix-core kernel serves grouped-query shapes whose units hold INT8 slots.
-static bool wants_mfma(int D, int G, bool has_int8) {
-  return g_use_mfma && has_int8 && attend_fn_mfma(D, G, false) != nullptr;
+// The matrix-core kernel serves every grouped-query shape at D = 128, FP16-only caches included
+// (at G >= 4 the vector-ALU body runs out of registers).
+static bool wants_mfma(int D, int G, bool /*has_int8*/) {
+  return g_use_mfma && attend_fn_mfma(D, G, false) != nullptr;
 }
 
 bool attend_supported(int D, int G) { return attend_fn_valu(D, G) != nullptr; }
