@@ -3,7 +3,7 @@
 // normaliser, dequantisation fused into the read; "Budget and ranker" -- EMA of attention
 // mass; Algorithm 1 -- append in FP16, update EMA metadata).
 //
-// One launch per layer, grid (splits, B * Hkv), 256 threads.  The `splits` workgroups of a
+// One launch per layer, grid (splits, B * Hkv), 512 threads.  The `splits` workgroups of a
 // unit (b, kv-head) each stream a contiguous, byte-balanced slice of the unit's slots once
 // and serve all G query heads of the group from that single read:
 //
@@ -30,6 +30,12 @@
 //     padded to 16.  The vector ALU then only converts int8 -> fp16 and keeps the softmax
 //     state, which is what lets the kernel stay memory-bound for grouped-query shapes.
 //     FP16 slots go through the same contractions in 16-slot tiles, no conversion needed.
+//     The same body with all 16 tile rows as query rows serves calls that carry several
+//     tokens per sequence (conf_kv_attend_chunk), and a variant of it folds per-channel INT8
+//     scales into the query and the output.
+// When the splits of a unit cannot all be resident, or a slice's scores do not fit LDS, the
+// launch is replaced by two (stream + publish with the scores in device scratch; merge + mass),
+// which need no wait inside a kernel.
 #include <algorithm>
 #include <map>
 #include <mutex>
