@@ -621,6 +621,134 @@ def test_channel_scales_need_calibration_and_round_trip(lib, torch_cuda):
     b.close()
 
 
+@pytest.mark.parametrize("idx,variant", [
+    (1, dict(ema_decay=1.0, mass_gain=1.0)),                       # cumulative mass (H2O-shaped importance)
+    (4, dict(mass_gain=0.25)),
+    (1, dict(ranker="random", ranker_seed=12345)),                  # matched-rate random eviction
+    (0, dict(ranker="random", ranker_seed=(1 << 63) + 77)),
+    (1, dict(rank_scope="layer")),                                  # one kept set per (layer, sequence)
+    (4, dict(rank_scope="layer")),
+    (2, dict(rank_scope="layer", ranker="random", ranker_seed=3)),
+    (0, dict(rank_scope="layer", alpha=1.0)),
+    # the variants together: the paper's literal reading (layer-shared kept set, per-channel
+    # scales), and several tokens per call under the random and the cumulative-mass rankers
+    (1, dict(rank_scope="layer", scale_mode="channel")),
+    (4, dict(rank_scope="layer", scale_mode="channel", max_chunk=4, tq=3)),
+    (1, dict(ranker="random", ranker_seed=9, max_chunk=4, tq=4)),
+    (2, dict(ema_decay=1.0, mass_gain=1.0, max_chunk=3, tq=2)),
+])
+def test_lockstep_ranker_variants(lib, torch_cuda, idx, variant):
+    """The ranking variants against the oracle's: cumulative mass instead of the EMA, random
+    eviction at the budget rule's rate, and the paper's literal one-kept-set-per-layer reading."""
+    variant = dict(variant)
+    tq = variant.pop("tq", 1)
+    wl = small(idx).scaled(**variant)
+    if wl.steps < 12:
+        wl = wl.scaled(steps=12)
+    say(f"variant {variant} tq={tq} on workload {idx} (reduced), steps={wl.steps}")
+    ls = Lockstep(lib, wl, seed=20 + idx)
+    for t in range(wl.steps):
+        ls.step(tq=tq)
+        if variant.get("rank_scope") == "layer":
+            for (l, b, g), u in ls.run.units.items():              # kv-heads of a sequence stay aligned
+                assert np.array_equal(u.pos, ls.run.units[(l, b, 0)].pos)
+    rep = ls.report
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"ties={rep.evict_ties} flips={rep.evict_flips}/{rep.budget_flips}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.evictions > 0 and ls.kv.counters().device_errors == 0
+    if variant.get("mass_gain") == 1.0:
+        # the importance is the running sum: it adds up to G per step and unit, minus what left
+        ex = ls.kv.export(0, 0, 0)
+        assert ex["ema"].sum() <= wl.steps * tq * wl.group + 1e-3 and ex["ema"].max() > 1.0
+    ls.close()
+
+
+def test_lockstep_geometric_pyramid(lib, torch_cuda):
+    """Per-layer budgets from the library's pyramidal schedule (beta = 0.5 as in the paper)."""
+    L = 4
+    tight = lib.pyramid_budgets(180, L, 0.5, 60)
+    assert tight == O.pyramid_geometric(180, L, 0.5, 60) and tight[0] == 180 and tight[-1] < tight[0]
+    wl = small(4).scaled(n_layers=L, n_tight=tuple(tight), n_loose=tuple(2 * n for n in tight), steps=24)
+    say(f"pyramid budgets {tight}")
+    ls = Lockstep(lib, wl, seed=8)
+    for t in range(wl.steps):
+        ls.step()
+    ln, _ = ls.kv.lengths()
+    sel = ls.sel.cpu().numpy().astype(bool)
+    for l in range(L):
+        for b in range(wl.batch):
+            assert ln[l, b] <= max(wl.protected, tight[l] if sel[b] else 2 * tight[l])
+    assert ls.report.ok() and ls.report.evictions > 0
+    ls.close()
+
+
+def test_import_round_trip_and_rejections(lib, torch_cuda):
+    """conf_kv_import is the inverse of conf_kv_export: a handle rebuilt from the exported views of
+    another (whose rings have moved) attends, evicts and demotes bit-identically; malformed views
+    are refused and leave the unit as it was."""
+    torch = torch_cuda
+    wl = small(1).scaled(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, vocab=3001, prefill=150, steps=30,
+                         n_tight=(120,), n_loose=(140,), protected=8, fp16_window=12, alpha=0.3,
+                         logit_std=(0.5, 6.0), logit_run=3)
+    say(f"import: capacity={wl.capacity}")
+    a = Lockstep(lib, wl, seed=5)
+    for t in range(wl.steps):                      # moves both ring heads of handle a
+        a.step(check_state=False)
+    b = lib.from_workload(wl)
+    views = {g: a.kv.export(0, 0, g) for g in range(2)}
+    for g in range(2):
+        b.import_unit(0, 0, g, views[g])
+        back = b.export(0, 0, g)
+        for name, x in views[g].items():
+            y = back[name]
+            same = (x == y) if name == "n" else np.array_equal(np.asarray(x).view(np.uint8), np.asarray(y).view(np.uint8))
+            assert same, f"kv-head {g}: {name} differs after import"
+    # the same steps on both handles
+    B, Hq, D = wl.batch, wl.n_q_heads, wl.head_dim
+    out_a = torch.empty((B, Hq, D), dtype=torch.float16, device="cuda")
+    out_b = torch.empty_like(out_a)
+    conf = torch.empty(B, dtype=torch.float32, device="cuda")
+    sel = torch.empty(B, dtype=torch.uint8, device="cuda")
+    for t in range(wl.steps, wl.steps + 12):
+        q, k, v = (torch.from_numpy(x).cuda() for x in gen.step_inputs(wl, 5, 0, t))
+        lg = torch.from_numpy(gen.step_logits(wl, 5, t)).cuda()
+        for kv, out in ((a.kv, out_a), (b, out_b)):
+            kv.attend(0, q, k, v, out)
+            kv.step(lg, conf, sel)
+            kv.evict_compact()
+        assert torch.equal(out_a, out_b), f"step {t}: outputs differ after import"
+    for g in range(2):
+        xa, xb = a.kv.export(0, 0, g), b.export(0, 0, g)
+        for name in xa:
+            same = (xa[name] == xb[name]) if name == "n" else \
+                np.array_equal(np.asarray(xa[name]).view(np.uint8), np.asarray(xb[name]).view(np.uint8))
+            assert same, f"kv-head {g}: {name} differs {12} steps after import"
+    # rejections
+    good = b.export(0, 0, 0)
+    def refused(**change):
+        v = dict(good); v.update(change)
+        with pytest.raises(lib.ConfKVError) as e:
+            b.import_unit(0, 0, 0, v)
+        return e.value.status
+    pos_bad = good["pos"].copy(); pos_bad[3] = pos_bad[2]
+    assert refused(pos=pos_bad) == -1                                   # positions not increasing
+    tags = good["is16"].copy(); tags[0] = True
+    assert refused(is16=tags) == -1                                     # INT8 behind FP16
+    assert refused(is16=np.ones_like(good["is16"])) == -1               # more FP16 slots than the window
+    assert refused(n=wl.capacity) == -4
+    assert refused(k8=None) == -1
+    after = b.export(0, 0, 0)
+    assert all(np.array_equal(np.asarray(good[k]), np.asarray(after[k])) for k in good if k != "n")
+    q, k, v = (torch.from_numpy(x).cuda() for x in gen.step_inputs(wl, 5, 0, 99))
+    b.attend(0, q, k, v, out_b)
+    with pytest.raises(lib.ConfKVError) as e:
+        b.import_unit(0, 0, 0, good)
+    assert e.value.status == -5                                         # an append awaits its commit
+    b.close()
+    a.close()
+
+
 @pytest.mark.parametrize("G,D,W", [(4, 128, 6), (1, 64, -1), (2, 128, 0)])
 def test_lockstep_from_empty_cache_to_full_capacity(lib, torch_cuda, G, D, W):
     """Degenerate ends of the size range: decoding starts on an empty cache (the first query
