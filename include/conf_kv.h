@@ -20,6 +20,9 @@
  *   - The three hot calls only enqueue kernels on the given stream; they never
  *     synchronise.  Lengths and budgets live on the device; the host keeps upper bounds.
  *   - A handle is driven from one host thread, on one stream at a time.
+ *   - The hot calls are not meant for HIP graph capture: each one bakes host-side state of the
+ *     step (positions, a launch counter the in-kernel waits compare against, the launch plan
+ *     for the current lengths) into its kernel arguments, so a replayed launch would be wrong.
  *   - Every function returns CONF_KV_OK (0) or a negative conf_kv_status; nothing throws.
  *   - Tensors are dense, row-major, in the index order written next to each argument.
  *   - fp16 data is IEEE binary16; "int8" codes are two's complement in [-127, 127].
