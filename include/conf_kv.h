@@ -194,8 +194,7 @@ int conf_kv_attend(conf_kv_handle *h, int32_t layer, const void *dev_q16, const 
  * values of the cache are read once for all tq queries.
  * dev_q16 / dev_out16: fp16 [B][tq][Hq][D]; dev_knew16 / dev_vnew16: fp16 [B][tq][Hkv][D].
  * The following conf_kv_evict_compact commits all tq appends.  Same errors as conf_kv_attend;
- * tq outside 1 .. max(1, max_chunk) is CONF_KV_ERR_INVALID_ARG; CONF_KV_ERR_BAD_SHAPE when
- * tq > 1 and the layer's caches are too long for a single-launch plan. */
+ * tq outside 1 .. max(1, max_chunk) is CONF_KV_ERR_INVALID_ARG. */
 int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const void *dev_q16,
                          const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
                          conf_kv_stream stream);

@@ -1268,6 +1268,8 @@ static AttendFn attend_fn_spill(int D, int G, bool finish) {
   CONFKV_CASE(128, 1) CONFKV_CASE(128, 2) CONFKV_CASE(128, 3) CONFKV_CASE(128, 4) CONFKV_CASE(128, 5)
   CONFKV_CASE(128, 6) CONFKV_CASE(128, 7) CONFKV_CASE(128, 8)
 #undef CONFKV_CASE
+  // multi-token calls: only the second launch exists for 16 rows (the first is the matrix-core body)
+  if (D == 128 && G == kChunkRows && finish) return (AttendFn)attend_finish_kernel<128, kChunkRows>;
   return nullptr;
 }
 
@@ -1289,6 +1291,7 @@ static AttendFn attend_fn_mfma_spill(int D, int G, bool chan) {
   case g: return chan ? (AttendFn)attend_mfma_kernel<g, true, true> : (AttendFn)attend_mfma_kernel<g, false, true>;
   switch (G) {
     CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
+    CONFKV_CASE(kChunkRows)
     default: return nullptr;
   }
 #undef CONFKV_CASE
@@ -1383,7 +1386,7 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
   // splits shrink the LDS stash when a long unit does not fit otherwise)
   plan->two_launch = false;
-  for (int k = 0; k < kAttendMaxSplits && (chunk || !force_two_launch); ++k) {
+  for (int k = 0; k < kAttendMaxSplits && !force_two_launch; ++k) {
     const int ns = k < want ? want - k : k + 1;
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
     const int need = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
@@ -1410,7 +1413,6 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
   // the slice's scores do not fit LDS.  Two launches then: the first streams and publishes
   // partials, keeping the raw scores in device scratch; the second merges and updates the EMA.
   // Nothing waits inside a kernel, so any split count works.
-  if (chunk) return false;                         // multi-token calls have the single-launch form only
   {
     // same split count as the single-kernel plan would like (measured on 64 units of 4096
     // slots: 4 splits 40 us, 16 splits 80 us -- the second launch grows with the split count)
@@ -1438,18 +1440,20 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                          hipStream_t stream) {
   dim3 grid(plan.splits, cv.B * cv.Hkv);
   if (plan.two_launch) {
-    AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, cv.G, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
-    AttendFn second = attend_fn_spill(cv.D, cv.G, true);
+    const int rows2 = a.tq > 1 ? kChunkRows : cv.G;                 // query rows per unit
+    if (a.tq > 1 && !plan.mfma) return hipErrorInvalidValue;
+    AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, rows2, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
+    AttendFn second = attend_fn_spill(cv.D, rows2, true);
     if (!first || !second || !a.spill) return hipErrorInvalidValue;
     hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                        plan.stash_tokens);
-    const size_t lds2 = ((size_t)plan.splits * cv.G * 2 + cv.G + 2) * sizeof(float) + 2 * cv.G * sizeof(double);
+    const size_t lds2 = ((size_t)plan.splits * rows2 * 2 + rows2 + 2) * sizeof(float) + 2 * rows2 * sizeof(double);
     hipLaunchKernelGGL(second, grid, dim3(kAttThreads), lds2, stream, cv, a, plan.splits,
                        plan.stash_tokens);
     return hipGetLastError();
   }
   const int rows = a.tq > 1 ? kChunkRows : cv.G;
-  if (a.tq > 1 && (!plan.mfma || plan.two_launch)) return hipErrorInvalidValue;
+  if (a.tq > 1 && !plan.mfma) return hipErrorInvalidValue;
   AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, rows, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,

@@ -113,6 +113,25 @@ def test_full_size_chunks(lib):
     ls.close()
 
 
+def test_chunks_on_long_units_take_the_two_launch_form(lib):
+    """Four tokens per call on 64 units of 9000 slots: sixteen rows of scores for a slice of such
+    a unit do not fit on chip next to the tile buffers at any resident split count, so the call
+    goes through scratch in two launches."""
+    wl = workload(1).scaled(name="llama3_8b_b8_t9000_chunk4", n_layers=2, prefill=9000, steps=2,
+                            n_tight=(4096,) * 2, n_loose=(8192,) * 2, max_chunk=4)
+    print(f"long units, chunks: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=4, units=3, threads=16)
+    for t, tq in enumerate((4, 2)):
+        ls.step(tq=tq)
+        _invariants_all_units(ls, wl, ls.t - 1)
+        print(f"  step {t} (tq={tq}): len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    st = ls.kv.counters()
+    assert st.device_errors == 0 and rep.evictions > 0
+    ls.close()
+
+
 def test_needle_retention_full_size(lib):
     """Retrieval stress at full cache length (one layer): every planted needle survives the
     32769 -> 4096 eviction after the first probe step, on every unit of the layer."""

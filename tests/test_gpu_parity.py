@@ -243,11 +243,13 @@ def test_attend_channel_scales_sharp_softmax(lib, torch_cuda):
     _attend_case(lib, torch_cuda, 128, 4, 1, 1, 900, 32, 6, seed=5, scale_q=6.0, scale_mode="channel")
 
 
-def _chunk_case(lib, torch, G, H, B, T0, W, splits, tqs, seed, scale_mode="token"):
-    say(f"chunks G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} tq={tqs} scales={scale_mode}")
+def _chunk_case(lib, torch, G, H, B, T0, W, splits, tqs, seed, scale_mode="token", two_launch=False):
+    say(f"chunks G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} tq={tqs} scales={scale_mode} two_launch={two_launch}")
     D = 128
     if splits:
         os.environ["CONF_KV_SPLITS"] = str(splits)
+    if two_launch:
+        os.environ["CONF_KV_TWO_LAUNCH"] = "1"
     try:
         cap = ((T0 + sum(tqs) + 8 + 63) // 64) * 64
         kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
@@ -255,6 +257,7 @@ def _chunk_case(lib, torch, G, H, B, T0, W, splits, tqs, seed, scale_mode="token
                  max_chunk=max(tqs))
     finally:
         os.environ.pop("CONF_KV_SPLITS", None)
+        os.environ.pop("CONF_KV_TWO_LAUNCH", None)
     rng = np.random.default_rng(seed)
     K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
     V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
@@ -319,6 +322,15 @@ def test_attend_chunk_matches_oracle(lib, torch_cuda, G, H, B, T0, W, splits, tq
     """Several tokens per call: one read of the cache serves all their queries; outputs, the
     telescoped importance update, the appended rows and the later demotions follow the oracle."""
     _chunk_case(lib, torch_cuda, G, H, B, T0, W, splits, tqs, seed=11 * G + T0, scale_mode=scales)
+
+
+@pytest.mark.parametrize("G,H,B,T0,W,splits,tqs,scales", [
+    (4, 2, 2, 700, 32, 3, (4, 3), "token"), (1, 1, 1, 500, 16, 5, (16, 7), "token"),
+    (5, 1, 1, 900, 64, 7, (3, 3), "channel"), (2, 1, 1, 300, -1, 2, (8, 8), "token")])
+def test_attend_chunk_two_launch_form(lib, torch_cuda, G, H, B, T0, W, splits, tqs, scales):
+    """Multi-token calls on caches too long for a single launch go through scratch like the
+    single-token ones; forced here on small shapes."""
+    _chunk_case(lib, torch_cuda, G, H, B, T0, W, splits, tqs, seed=13 * G + T0, scale_mode=scales, two_launch=True)
 
 
 @pytest.mark.parametrize("G,W,scales", [(4, 8, "token"), (1, 8, "token"), (2, -1, "token"), (4, 30, "channel")])
