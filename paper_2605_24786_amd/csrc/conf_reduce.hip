@@ -44,11 +44,12 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
 
   float x[kConfPerThread];
   const int base = c * kConfChunk + tid;
+  // branch-free loads (an index past the row re-reads its last logit and is masked afterwards),
+  // so that all sixteen are in flight before the first one is waited for
 #pragma unroll
-  for (int r = 0; r < kConfPerThread; ++r) {
-    int idx = base + r * kConfThreads;
-    x[r] = idx < V ? row[idx] : NEG;
-  }
+  for (int r = 0; r < kConfPerThread; ++r) x[r] = row[min(base + r * kConfThreads, V - 1)];
+#pragma unroll
+  for (int r = 0; r < kConfPerThread; ++r) x[r] = base + r * kConfThreads < V ? x[r] : NEG;
   float v1 = NEG, v2 = NEG;
 #pragma unroll
   for (int r = 0; r < kConfPerThread; ++r) {
