@@ -813,3 +813,56 @@ def test_probe_read_reads_every_byte_once(lib, torch_cuda):
         lib.probe_read(torch.from_numpy(x).cuda(), out, wgs)
         got = np.bitwise_xor.reduce(out.cpu().numpy().view(np.uint32))
         assert got == np.bitwise_xor.reduce(x.view(np.uint32)), (n16, wgs)
+
+
+def _random_config(seed):
+    """A seeded draw from the space of supported configurations (shapes, windows, budgets,
+    ranker and scale variants, tokens per call), small enough for the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    D = int(rng.choice([64, 128], p=[0.3, 0.7]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    H = int(rng.choice([1, 2, 3]))
+    B = int(rng.choice([1, 2, 3]))
+    W = int(rng.choice([-1, 0, 3, 12, 40]))
+    P = int(rng.choice([0, 1, 7, 20]))
+    prefill = int(rng.choice([0, 5, 60, 130, 333]))
+    loose = int(rng.integers(max(P, 8) + 4, max(prefill, 24) + 16))     # most runs have to evict
+    tight = int(rng.integers(max(1, loose // 3), loose + 1))
+    L = int(rng.choice([1, 2]))
+    kw = dict(n_layers=L, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, vocab=int(rng.choice([257, 1000, 5003])),
+              prefill=prefill, steps=int(rng.integers(12, 30)), n_tight=(tight,) * L, n_loose=(loose,) * L,
+              protected=P, fp16_window=W, logit_std=(0.5, 6.0), logit_run=int(rng.integers(1, 6)),
+              alpha=float(rng.choice([0.0, 0.3, 0.65, 1.0])), ema_decay=float(rng.choice([0.5, 0.9, 1.0])))
+    if rng.random() < 0.3:
+        kw["mass_gain"] = float(rng.choice([0.25, 1.0]))
+    if rng.random() < 0.25:
+        kw.update(ranker="random", ranker_seed=int(rng.integers(0, 2**62)))
+    if rng.random() < 0.3:
+        kw["rank_scope"] = "layer"
+    if D == 128 and W >= 0 and rng.random() < 0.4:
+        kw["scale_mode"] = "channel"
+    tq_max = 1
+    if D == 128 and rng.random() < 0.5:
+        tq_max = int(rng.integers(2, 16 // G + 1)) if 16 // G >= 2 else 1
+        if tq_max > 1:
+            kw["max_chunk"] = tq_max
+    return kw, tq_max
+
+
+@pytest.mark.parametrize("seed", list(range(32)))
+def test_lockstep_random_configurations(lib, torch_cuda, seed):
+    """Seeded random configurations across the whole option space, a few dozen steps each, in
+    lock-step with the oracle: combinations no hand-written case covers."""
+    kw, tq_max = _random_config(seed)
+    wl = small(1).scaled(name=f"random{seed}", **kw)
+    say(f"random config {seed}: {kw} capacity={wl.capacity}")
+    ls = Lockstep(lib, wl, seed=seed)
+    rng = np.random.default_rng(seed)
+    for t in range(wl.steps):
+        ls.step(tq=int(rng.integers(1, tq_max + 1)))
+    rep = ls.report
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"ties={rep.evict_ties} flips={rep.evict_flips}/{rep.budget_flips}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0
+    ls.close()
