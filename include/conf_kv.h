@@ -128,6 +128,12 @@ typedef struct conf_kv_stats {
   uint64_t compact_bytes;    /* bytes read + written by the compaction's in-place row moves    */
 } conf_kv_stats;
 
+/* Environment variables read once by conf_kv_create (test and measurement hooks; none is
+ * needed in normal use): CONF_KV_SPLITS=n asks for n workgroups per unit in conf_kv_attend
+ * instead of the planned number (clamped to what the unit's length allows);
+ * CONF_KV_TWO_LAUNCH=1 forces the two-launch form of conf_kv_attend; CONF_KV_NO_MFMA=1 (read
+ * at the first plan of the process) keeps every shape on the vector-ALU streaming body. */
+
 /* Bytes of device memory the caller must provide for the cache state and for scratch
  * (split partials, arrival counters, ranking work arrays).  0 on an invalid config. */
 size_t conf_kv_state_bytes(const conf_kv_config *cfg);
