@@ -171,3 +171,19 @@ def test_chunk_closed_form_causal_mask_and_mass():
     assert np.array_equal(u.pos[-Tq:], 100 + np.arange(Tq))
     # total mass handed out by query t is G, weighted lambda^(Tq-1-t)
     assert abs(Wm.sum() - gain * G * sum(lam ** (Tq - 1 - t) for t in range(Tq))) < 1e-12
+
+
+def test_oracle_reproduces_its_stored_regression_values():
+    """tests/golden/oracle_regression.json is written by tests/golden/make_oracle_regression.py from
+    the oracle alone; the oracle as it stands must still produce it (a deliberate change to the
+    oracle's arithmetic regenerates the file and says why in its commit)."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_regression",
+                                                  os.path.join(here, "golden", "make_oracle_regression.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = json.load(open(os.path.join(here, "golden", "oracle_regression.json")))
+    assert json.loads(json.dumps(mod.compute(), sort_keys=True)) == stored
