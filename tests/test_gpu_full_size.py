@@ -132,6 +132,44 @@ def test_chunks_on_long_units_take_the_two_launch_form(lib):
     ls.close()
 
 
+def test_page_fragmentation_of_token_level_eviction(lib):
+    """What token-level eviction would cost a paged layout ("Compatibility with serving systems",
+    "Limitations": partially dead blocks): after a steady-state run at workload 4's shape (4 of
+    its layers), group the ORIGINAL positions into pages of 16 and 32 tokens and count, per unit,
+    the pages that still hold a live token against the pages the live tokens would fill if packed.
+    No kernel is involved beyond the ordinary decode path; the numbers are printed for the
+    design notes and only sanity-checked here."""
+    import torch
+    wl = workload(4).scaled(n_layers=4, n_tight=workload(4).n_tight[:4], n_loose=workload(4).n_loose[:4],
+                            steps=120, logit_run=3)
+    kv = lib.from_workload(wl)
+    for l in range(wl.n_layers):
+        K, V = gen.prefill_layer(wl, 0, l, threads=16)
+        kv.load_prefill(l, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float16, device="cuda")
+    for t in range(wl.steps):
+        for l in range(wl.n_layers):
+            q, k, v = gen.step_inputs(wl, 0, l, t)
+            kv.attend(l, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), out)
+        kv.step(torch.from_numpy(gen.step_logits(wl, 0, t)).cuda())
+        kv.evict_compact()
+    rng = np.random.default_rng(0)
+    for page in (16, 32):
+        live_pages = packed_pages = partial = 0
+        for _ in range(48):
+            l, b, g = int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch)), int(rng.integers(wl.n_kv_heads))
+            pos = kv.export(l, b, g)["pos"]
+            ids, counts = np.unique(pos // page, return_counts=True)
+            live_pages += ids.size
+            packed_pages += -(-pos.size // page)
+            partial += int((counts < page).sum())
+        print(f"page size {page}: live pages {live_pages}, packed {packed_pages} "
+              f"(overhead {live_pages / packed_pages:.2f}x), partially dead {partial / live_pages:.0%}", flush=True)
+        assert live_pages >= packed_pages
+    assert kv.counters().device_errors == 0 and kv.counters().evicted > 0
+    kv.close()
+
+
 def test_needle_retention_full_size(lib):
     """Retrieval stress at full cache length (one layer): every planted needle survives the
     32769 -> 4096 eviction after the first probe step, on every unit of the layer."""
