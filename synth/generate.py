@@ -69,6 +69,18 @@ def prefill_unit(wl: Workload, seed: int, layer: int, b: int, kv_head: int
     return k.astype(np.float16), v.astype(np.float16)
 
 
+def prefill_heavy_hitters(wl: Workload, seed: int, layer: int, b: int, kv_head: int) -> np.ndarray:
+    """Prompt positions of one unit whose keys got the heavy-hitter offset (same draws as
+    ``prefill_unit``), sorted."""
+    if wl.heavy_hitter_prob <= 0.0:
+        return np.zeros(0, dtype=np.int64)
+    g = _rng(seed, _T_PREFILL, layer, b, kv_head)
+    T, D = wl.prefill, wl.head_dim
+    g.standard_normal((T, D), dtype=np.float32)
+    g.standard_normal((T, D), dtype=np.float32)
+    return np.flatnonzero(g.random(T) < wl.heavy_hitter_prob).astype(np.int64)
+
+
 def prefill_layer(wl: Workload, seed: int, layer: int, threads: int = 8
                   ) -> Tuple[np.ndarray, np.ndarray]:
     """Prefill K and V of one layer: fp16 [B, Hkv, T0, D] each."""

@@ -866,3 +866,45 @@ def test_lockstep_random_configurations(lib, torch_cuda, seed):
     assert rep.ok(), (rep.evict_flips, rep.budget_flips)
     assert ls.kv.counters().device_errors == 0
     ls.close()
+
+
+def test_heavy_hitter_recall_by_ranker_mode(lib, torch_cuda):
+    """The structure of the matched-rate isolation study on synthetic data: every ranker evicts the
+    same number of tokens (the budget rule decides how many), and what differs is which heavy-hitter
+    keys of the prompt survive.  Ranking by attention alone keeps nearly all of them; the composite
+    score gives a third of its weight to recency and keeps fewer, still well above recency alone
+    (which keeps those that happen to be recent: about the kept fraction) and random."""
+    torch = torch_cuda
+    base = small(1).scaled(n_layers=1, batch=2, n_q_heads=8, n_kv_heads=2, prefill=1500, steps=24,
+                           n_tight=(300,), n_loose=(300,), protected=32, fp16_window=32, logit_run=4)
+    modes = {"composite": dict(alpha=0.65), "attention only": dict(alpha=1.0), "recency only": dict(alpha=0.0),
+             "cumulative mass": dict(alpha=0.65, ema_decay=1.0, mass_gain=1.0),
+             "random": dict(ranker="random", ranker_seed=5)}
+    recall, kept_n = {}, {}
+    for name, variant in modes.items():
+        wl = base.scaled(**variant)
+        kv = lib.from_workload(wl)
+        K, V = gen.prefill_layer(wl, 0, 0)
+        kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+        out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float16, device="cuda")
+        for t in range(wl.steps):
+            q, k, v = gen.step_inputs(wl, 0, 0, t)
+            kv.attend(0, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), out)
+            kv.step(torch.from_numpy(gen.step_logits(wl, 0, t)).cuda())
+            kv.evict_compact()
+        hit = tot = 0
+        for b in range(wl.batch):
+            for g in range(wl.n_kv_heads):
+                pos = kv.export(0, b, g)["pos"]
+                hh = gen.prefill_heavy_hitters(wl, 0, 0, b, g)
+                hit += int(np.isin(hh, pos).sum())
+                tot += hh.size
+                kept_n[name] = pos.size
+        recall[name] = hit / tot
+        kv.close()
+    say("heavy-hitter recall after 1500 -> 300 slots: " + ", ".join(f"{k} {v:.2f}" for k, v in recall.items()))
+    assert len(set(kept_n.values())) == 1                       # matched rate
+    assert recall["attention only"] > 0.8
+    assert recall["composite"] > recall["recency only"] + 0.1 and recall["composite"] > recall["random"] + 0.15
+    assert recall["cumulative mass"] > recall["recency only"] + 0.1
+    assert 0.1 <= recall["recency only"] <= 0.3 and recall["random"] <= 0.3     # the kept fraction is 0.2
