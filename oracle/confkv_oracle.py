@@ -371,6 +371,42 @@ def attend_chunk_unit(u: UnitCache, q: np.ndarray, k_new: np.ndarray, v_new: np.
     return np.stack(outs), W
 
 
+def observe_unit(u: UnitCache, q: np.ndarray, first: int, sm_scale: float, ema_decay: float,
+                 mass_gain: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Importance from queries of tokens that are ALREADY in the cache (the prompt's own
+    attention, taken over an observation window at its end): q [Tq, G, D] are the queries of
+    the cached slots first .. first + Tq - 1.  Nothing is appended.  Defined like
+    ``attend_chunk_unit`` on the stored values: query t sees slots 0 .. first + t, the
+    importance of every slot below first + Tq follows a <- lambda a + gain A_t once per query
+    (a window slot counts from 0 at its own query, whatever it held before), and slots at or
+    above first + Tq are neither seen nor changed.  Calling it for consecutive windows
+    first = s, s + Tq, .. is the same as one call over their union.
+    Returns (out [Tq, G, D] float64, W [first + Tq] float64 = the weighted mass received).
+    """
+    q = np.asarray(q)
+    Tq = q.shape[0]
+    if first < 0 or first + Tq > u.n:
+        raise ValueError("window outside the cache")
+    lam = F64(ema_decay)
+    gain = (1.0 - lam) if mass_gain is None else F64(mass_gain)
+    K, V = u.stored_k(), u.stored_v()
+    a = u.ema.astype(F64).copy()
+    a[first:first + Tq] = 0.0
+    base = a.copy()
+    outs = []
+    for t in range(Tq):
+        vis = first + t + 1
+        out, p = attention_naive(q[t].astype(F64), K[:vis], V[:vis], sm_scale)
+        a[:vis] = lam * a[:vis] + gain * np.sum(p, axis=0)
+        outs.append(out)
+    n_eff = first + Tq
+    W = a[:n_eff] - (lam ** Tq) * base[:n_eff]
+    new = u.ema.astype(F64)
+    new[:n_eff] = a[:n_eff]
+    u.ema = new.astype(np.float32)
+    return np.stack(outs), W
+
+
 # --------------------------------------------------------------------------------------
 # Ranking, eviction, compaction, demotion  ("Budget and ranker"; Algorithm 1)
 # --------------------------------------------------------------------------------------
@@ -555,6 +591,20 @@ class OracleRun:
                 continue
             out, _ = attend_chunk_unit(u, q[b, :, g * group:(g + 1) * group], k_new[b, :, g], v_new[b, :, g],
                                        self.next_pos, p.sm_scale, p.ema_decay, p.mass_gain)
+            outs[(l, b, g)] = out
+        return outs
+
+    def observe(self, layer: int, q: np.ndarray, first: int, group: int
+                ) -> Dict[Tuple[int, int, int], np.ndarray]:
+        """q [B, Tq, Hq, D]: queries of the cached slots first .. first + Tq - 1 of every followed
+        unit of the layer -> {unit: out [Tq, G, D]}; importance updated, nothing appended."""
+        outs = {}
+        p = self.policy
+        for (l, b, g), u in self.units.items():
+            if l != layer:
+                continue
+            out, _ = observe_unit(u, q[b, :, g * group:(g + 1) * group], first, p.sm_scale, p.ema_decay,
+                                  p.mass_gain)
             outs[(l, b, g)] = out
         return outs
 

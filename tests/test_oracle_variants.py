@@ -187,3 +187,53 @@ def test_oracle_reproduces_its_stored_regression_values():
     spec.loader.exec_module(mod)
     stored = json.load(open(os.path.join(here, "golden", "oracle_regression.json")))
     assert json.loads(json.dumps(mod.compute(), sort_keys=True)) == stored
+
+
+# ---- importance from the prompt's own attention (an observation window at its end)
+
+def test_observe_equals_decoding_the_window_on_an_fp16_cache():
+    # on an FP16-only cache the stored values are the tokens themselves, so observing the last
+    # Tq slots is the same as loading the prompt without them and decoding them as a chunk
+    rng = np.random.default_rng(31)
+    n, D, G, Tq = 40, 8, 2, 6
+    k = rng.standard_normal((n, D)).astype(np.float16)
+    v = rng.standard_normal((n, D)).astype(np.float16)
+    e0 = rng.random(n).astype(np.float32)
+    q = rng.standard_normal((Tq, G, D)).astype(np.float16)
+    a = O.load_prefill(k, v, -1, ema0=e0)
+    out_a, _ = O.observe_unit(a, q, n - Tq, 0.3, 0.9)
+    b = O.load_prefill(k[:n - Tq], v[:n - Tq], -1, ema0=e0[:n - Tq])
+    out_b, _ = O.attend_chunk_unit(b, q, k[n - Tq:], v[n - Tq:], n - Tq, 0.3, 0.9)
+    assert np.allclose(out_a, out_b, rtol=1e-13, atol=1e-15)
+    assert np.array_equal(a.ema, b.ema) and np.array_equal(a.pos, b.pos)
+
+
+def test_observe_in_pieces_leaves_later_slots_alone_and_composes():
+    rng = np.random.default_rng(32)
+    n, D, G, W = 50, 8, 3, 5
+    k = rng.standard_normal((n, D)).astype(np.float16)
+    v = rng.standard_normal((n, D)).astype(np.float16)
+    e0 = rng.random(n).astype(np.float32)
+    q = rng.standard_normal((12, G, D)).astype(np.float16)
+    whole = O.load_prefill(k, v, W, ema0=e0)               # mixed cache: most window slots are INT8
+    O.observe_unit(whole, q, 30, 0.3, 0.8, mass_gain=0.5)
+    parts = O.load_prefill(k, v, W, ema0=e0)
+    O.observe_unit(parts, q[:5], 30, 0.3, 0.8, mass_gain=0.5)
+    assert np.array_equal(parts.ema[35:], e0[35:])          # not seen yet, not touched
+    O.observe_unit(parts, q[5:], 35, 0.3, 0.8, mass_gain=0.5)
+    assert np.allclose(parts.ema, whole.ema, rtol=3e-7, atol=1e-9)      # fp32 storage between the pieces
+    assert np.array_equal(whole.ema[42:], e0[42:])
+    assert whole.n == n and np.array_equal(whole.is16, parts.is16)      # nothing appended or demoted
+    with pytest.raises(ValueError):
+        O.observe_unit(whole, q, 45, 0.3, 0.8)
+
+
+def test_observe_mass_totals():
+    # query t hands out mass G over the slots it sees, weighted lambda^(Tq-1-t)
+    rng = np.random.default_rng(33)
+    n, D, G, Tq = 25, 4, 2, 4
+    u = _unit(rng, n, D, 3)
+    q = rng.standard_normal((Tq, G, D)).astype(np.float16)
+    _, Wm = O.observe_unit(u, q, n - Tq, 0.5, 0.9, mass_gain=0.25)
+    assert abs(Wm.sum() - 0.25 * G * sum(0.9 ** (Tq - 1 - t) for t in range(Tq))) < 1e-12
+    assert Wm[-1] > 0 and np.all(Wm >= 0)
