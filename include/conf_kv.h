@@ -205,6 +205,21 @@ int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
                          const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
                          conf_kv_stream stream);
 
+/* Importance from the prompt's own attention (the step before the decode loop: the cache's
+ * initial importance comes from an observation window of queries at the end of the prompt
+ * instead of starting at zero).  dev_q16: fp16 [B][tq][Hq][D], the queries of the cached slots
+ * first .. first + tq - 1 of every unit of the layer; nothing is appended.  Defined like
+ * conf_kv_attend_chunk on the stored values: query t sees slots 0 .. first + t, the importance
+ * of every slot below first + tq follows a <- lambda a + gain A_t once per query (a window
+ * slot counts from 0 at its own query, whatever it held before), slots from first + tq on are
+ * neither seen nor changed.  Calls for consecutive windows first = s, s + tq, .. compose.
+ * dev_out16: fp16 [B][tq][Hq][D] attention outputs of those queries, or NULL.
+ * Allowed between conf_kv_load_prefill of the layer and its first conf_kv_attend
+ * (CONF_KV_ERR_BAD_STATE otherwise), with max_chunk >= 2, 1 <= tq <= max_chunk and
+ * 0 <= first, first + tq <= T0 (CONF_KV_ERR_INVALID_ARG). */
+int conf_kv_observe(conf_kv_handle *h, int32_t layer, int32_t first, int32_t tq, const void *dev_q16,
+                    void *dev_out16, conf_kv_stream stream);
+
 /*
  * Confidence estimator and budget selector (Eq. 1; "Budget and ranker"; Algorithm 1,
  * lines softmax / c / N).  For every sequence b: p = softmax(logits[b]),

@@ -61,6 +61,7 @@ SYMBOLS = {
     "conf_kv_load_prefill": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, _P]),
     "conf_kv_attend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P]),
     "conf_kv_attend_chunk": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, _P, _P, _P]),
+    "conf_kv_observe": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]),
     "conf_kv_step": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
     "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
@@ -194,6 +195,12 @@ class ConfKV:
         tq = int(q16.shape[1])
         return self._check(self.lib.conf_kv_attend_chunk(self.h, layer, tq, _ptr(q16), _ptr(knew16), _ptr(vnew16),
                                                          _ptr(out16), self._stream()), "conf_kv_attend_chunk")
+
+    def observe(self, layer: int, first: int, q16, out16=None):
+        """q16 / out16 [B][tq][Hq][D]: queries of the cached slots first .. first + tq - 1; out16 optional."""
+        tq = int(q16.shape[1])
+        return self._check(self.lib.conf_kv_observe(self.h, layer, first, tq, _ptr(q16), _ptr(out16),
+                                                    self._stream()), "conf_kv_observe")
 
     def step(self, logits, conf=None, sel=None):
         return self._check(self.lib.conf_kv_step(self.h, _ptr(logits), _ptr(conf), _ptr(sel),

@@ -133,6 +133,7 @@ struct conf_kv_handle {
   std::vector<int32_t> next_pos;     // position the next appended token gets
   std::vector<uint8_t> appended;     // an append awaits its commit
   std::vector<uint8_t> scaled;       // per unit: channel scales were given (channel mode)
+  std::vector<int32_t> fresh_len;    // per layer: T0 of a prompt no decode step has touched yet, else -1
   std::vector<uint32_t> epoch;       // attend launches so far, per layer (arrival-flag value)
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
@@ -184,6 +185,7 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->appended.assign(L, 0);
   h->epoch.assign(L, 0u);
   h->scaled.assign((size_t)L * cfg->batch * cfg->n_kv_heads, 0);
+  h->fresh_len.assign(L, -1);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
   if (const char *tl = getenv("CONF_KV_TWO_LAUNCH")) h->force_two_launch = atoi(tl) != 0;
 
@@ -270,33 +272,43 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   h->appended[layer] = 0;
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   std::fill(h->scaled.begin() + layer * UPL, h->scaled.begin() + (layer + 1) * UPL, (uint8_t)1);
+  h->fresh_len[layer] = T0;
   return CONF_KV_OK;
 }
 
-static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan) {
-  const int n_ub = h->len_ub[layer] + tq;
+static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan, int observe_first = -1) {
+  const bool observe = observe_first >= 0;
+  const int n_ub = observe ? observe_first + tq : h->len_ub[layer] + tq;     // slots the call sees
   const int W = h->cfg.fp16_window;
-  const int n16_ub = W < 0 ? n_ub : std::min(n_ub, W + tq);
+  const int n16_ub = W < 0 ? n_ub : std::min(n_ub, observe ? W : W + tq);
   // a chunk runs on the matrix-core body with all 16 tile rows as query rows
-  const int rows = tq > 1 ? kChunkRows : h->cv.G;
-  if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, tq > 1, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
+  const int rows = (tq > 1 || observe) ? kChunkRows : h->cv.G;
+  if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, tq > 1 || observe, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
                    h->forced_splits, h->force_two_launch, plan))
     return CONF_KV_ERR_BAD_SHAPE;
   return CONF_KV_OK;
 }
 
+// observe_first < 0: append tq tokens and attend; >= 0: conf_kv_observe
 static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const void *dev_q16,
                          const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
-                         conf_kv_stream stream) {
-  if (!h || !dev_q16 || !dev_knew16 || !dev_vnew16 || !dev_out16) return CONF_KV_ERR_INVALID_ARG;
+                         conf_kv_stream stream, int32_t observe_first = -1) {
+  const bool observe = observe_first >= 0;
+  if (!h || !dev_q16) return CONF_KV_ERR_INVALID_ARG;
+  if (!observe && (!dev_knew16 || !dev_vnew16 || !dev_out16)) return CONF_KV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
   if (tq < 1 || tq > std::max(1, h->cfg.max_chunk)) return CONF_KV_ERR_INVALID_ARG;
+  if (observe) {
+    if (h->cfg.max_chunk < 2) return CONF_KV_ERR_INVALID_ARG;
+    if (h->appended[layer] || h->fresh_len[layer] < 0) return CONF_KV_ERR_BAD_STATE;
+    if ((long long)observe_first + tq > h->fresh_len[layer]) return CONF_KV_ERR_INVALID_ARG;
+  }
   if (((uintptr_t)dev_q16 | (uintptr_t)dev_knew16 | (uintptr_t)dev_vnew16 | (uintptr_t)dev_out16) & 15)
     return CONF_KV_ERR_INVALID_ARG;
   if (h->appended[layer]) return CONF_KV_ERR_BAD_STATE;
-  if (h->len_ub[layer] + tq > h->cfg.capacity) return CONF_KV_ERR_CAPACITY;
+  if (!observe && h->len_ub[layer] + tq > h->cfg.capacity) return CONF_KV_ERR_CAPACITY;
   AttendPlan plan;
-  int rc = plan_for_layer(h, layer, tq, &plan);
+  int rc = plan_for_layer(h, layer, tq, &plan, observe_first);
   if (rc != CONF_KV_OK) return rc;
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   AttendLaunch a{};
@@ -318,6 +330,7 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.pos_new = h->next_pos[layer];
   a.tq = tq;
   a.gq = h->cv.G;
+  a.observe_first = observe_first;
   a.dbg = nullptr;
 #ifdef CONFKV_TRACE
   // the ranking work arrays at the end of the scratch buffer are idle during conf_kv_attend
@@ -325,7 +338,10 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
     a.dbg = (unsigned long long *)(h->scratch + h->kl.total - (size_t)8 * 32 * 4 * 4096);
 #endif
   CK_HIP(h, launch_attend(h->cv, a, plan, (hipStream_t)stream));
-  h->appended[layer] = (uint8_t)tq;
+  if (!observe) {
+    h->appended[layer] = (uint8_t)tq;
+    h->fresh_len[layer] = -1;
+  }
   return CONF_KV_OK;
 }
 
@@ -338,6 +354,12 @@ int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
                          const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
                          conf_kv_stream stream) {
   return attend_tokens(h, layer, tq, dev_q16, dev_knew16, dev_vnew16, dev_out16, stream);
+}
+
+int conf_kv_observe(conf_kv_handle *h, int32_t layer, int32_t first, int32_t tq, const void *dev_q16,
+                    void *dev_out16, conf_kv_stream stream) {
+  if (first < 0) return CONF_KV_ERR_INVALID_ARG;
+  return attend_tokens(h, layer, tq, dev_q16, nullptr, nullptr, dev_out16, stream, first);
 }
 
 int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
@@ -384,6 +406,7 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
     h->len_ub[l] += h->appended[l];
     h->next_pos[l] += h->appended[l];
     h->appended[l] = 0;
+    h->fresh_len[l] = -1;
     // any budget the step may have chosen is at most the loose one
     const int n = h->len_ub[l], NL = h->n_loose[l];
     if (n > NL) h->len_ub[l] = std::max(NL, std::min(P, n));
@@ -545,6 +568,7 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   CK_HIP(h, hipMemcpy(cv.head16 + u, &zero, 4, hipMemcpyHostToDevice));
   CK_HIP(h, hipMemcpy(cv.head8 + u, &zero, 4, hipMemcpyHostToDevice));
   h->len_ub[layer] = std::max(h->len_ub[layer], n);
+  h->fresh_len[layer] = -1;
   if (n > 0) h->next_pos[layer] = std::max(h->next_pos[layer], pos[n - 1] + 1);
   return CONF_KV_OK;
 }

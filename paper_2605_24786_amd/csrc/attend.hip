@@ -138,14 +138,17 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
   s.u = a.layer * cv.B * cv.Hkv + s.ul;
   s.b = s.ul / cv.Hkv;
   s.g = s.ul % cv.Hkv;
-  s.n8 = cv.n8[s.u];
-  s.n = cv.len[s.u] + a.tq;               // the appended tokens included
+  // an observation call sees the unit as it was when its last query was the newest token
+  const bool observe = a.observe_first >= 0;
+  s.n = observe ? a.observe_first + a.tq : cv.len[s.u] + a.tq;     // the appended tokens included
+  s.n8 = observe ? min(cv.n8[s.u], s.n) : cv.n8[s.u];
   s.h16 = cv.head16[s.u];
   s.h8 = cv.head8[s.u];
   s.n16 = s.n - s.n8;
   s.lo8 = (int)((long long)s.n8 * s.j / ns) & ~31;
   s.hi8 = s.j == ns - 1 ? s.n8 : (int)((long long)s.n8 * (s.j + 1) / ns) & ~31;
-  // the tail split's FP16 share is never empty (n16 >= 1), so its owner holds slot n-1
+  // outside observation calls the tail split's FP16 share is never empty (n16 >= 1), so its
+  // owner holds slot n-1
   s.lo16 = s.n8 + (int)((long long)s.n16 * s.j / ns);
   s.hi16 = s.n8 + (int)((long long)s.n16 * (s.j + 1) / ns);
   s.cnt8 = s.hi8 - s.lo8;
@@ -165,7 +168,7 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
 template <int D, bool kSync = true>
 __device__ __forceinline__ void append_new_token(const CacheView &cv, const AttendLaunch &a,
                                                  const Slice &s, int ns) {
-  if (s.j != ns - 1) return;
+  if (s.j != ns - 1 || a.observe_first >= 0) return;
   const int tid = threadIdx.x;
   constexpr int PPR = D / 8;                        // 16-byte pieces per row
   // token t of the call: K/V rows [B][tq][Hkv][D] -> FP16 ring row of slot n - tq + t
@@ -517,7 +520,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       __half2 o2;
       o2.x = __float2half_rn((float)((double)o0 * inv));
       o2.y = __float2half_rn((float)((double)o1 * inv));
-      if (h < tq * gq) *(__half2 *)&a.out[out_index(cv, sl, tq, gq, idx, D)] = o2;
+      if (h < tq * gq && a.out) *(__half2 *)&a.out[out_index(cv, sl, tq, gq, idx, D)] = o2;
       if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
     } else {
       st_agent2(&po[idx], o0, o1);
@@ -622,7 +625,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       const float ms = valid ? pml[(os * G + h) * 2] : NEG;
       float c = ms > NEG ? v * expf(ms - gm[h]) : 0.f;               // an empty partial weighs nothing
       for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
-      if (valid && os == 0 && h < tq * gq)
+      if (valid && os == 0 && h < tq * gq && a.out)
         a.out[out_index(cv, sl, tq, gq, e, D)] = __float2half_rn((float)((double)c * ginv[h]));
     }
   }
@@ -989,7 +992,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * D + col;
     // the call's own tokens (slots n - tq .. n - 1, at the end of the unit's last split) are
     // taken from the call's arguments, not read back from the ring: no wait on the append's stores
-    const int first_new = sl.n - tq;
+    // (an observation call appends nothing: every row comes from the ring)
+    const int first_new = a.observe_first >= 0 ? 0x3fffffff : sl.n - tq;
     const size_t tok = (size_t)cv.Hkv * D;                      // [B][tq][Hkv][D]: stride of a token
     const __half *kn = a.knew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * D + col;
     const __half *vn = a.vnew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * D + col;
@@ -1150,8 +1154,10 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
       regroup_rows<G>(acc, z);
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
-        const float sv = z[j] * kscale[sb];
         const bool real = valid && hd[j] < G;
+        // an INT8 slot is ahead of a query only in an observation call (appended tokens are FP16)
+        const bool ahead = G > 8 && base + 16 * sb + t16 >= seen[j];
+        const float sv = ahead ? NEG : z[j] * kscale[sb];
         sc[sb][j] = real ? sv : NEG;
         if (real) stash[hd[j] * S + (base + 16 * sb + t16 - sl.lo8)] = sv;
       }
@@ -1440,8 +1446,9 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                          hipStream_t stream) {
   dim3 grid(plan.splits, cv.B * cv.Hkv);
   if (plan.two_launch) {
-    const int rows2 = a.tq > 1 ? kChunkRows : cv.G;                 // query rows per unit
-    if (a.tq > 1 && !plan.mfma) return hipErrorInvalidValue;
+    const bool rows16 = a.tq > 1 || a.observe_first >= 0;
+    const int rows2 = rows16 ? kChunkRows : cv.G;                   // query rows per unit
+    if (rows16 && !plan.mfma) return hipErrorInvalidValue;
     AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, rows2, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
     AttendFn second = attend_fn_spill(cv.D, rows2, true);
     if (!first || !second || !a.spill) return hipErrorInvalidValue;
@@ -1452,8 +1459,9 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                        plan.stash_tokens);
     return hipGetLastError();
   }
-  const int rows = a.tq > 1 ? kChunkRows : cv.G;
-  if (a.tq > 1 && !plan.mfma) return hipErrorInvalidValue;
+  const bool rows16 = a.tq > 1 || a.observe_first >= 0;
+  const int rows = rows16 ? kChunkRows : cv.G;
+  if (rows16 && !plan.mfma) return hipErrorInvalidValue;
   AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, rows, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,

@@ -40,6 +40,8 @@ struct AttendLaunch {
   int pos_new;             // position of the first appended token
   int tq;                  // tokens appended (and queries per head) in this call
   int gq;                  // query heads per kv-head; the kernels' row r is (token r / gq, head r % gq)
+  int observe_first;       // >= 0: the queries belong to the cached slots observe_first .. observe_first + tq - 1;
+                           // nothing is appended and slots from observe_first + tq on are left alone
   float *spill;            // [units per layer][splits][G][stash_tokens] raw scores (two-launch form)
   unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
 };

@@ -131,6 +131,29 @@ class Lockstep:
             if nz.any():
                 rep.max_ema_rel = max(rep.max_ema_rel, float(np.max(err[nz] / ref[nz])))
 
+    # ---- the prompt's own attention, before the decode loop ----
+    def observe(self, first: int, tq: int, want_out: bool = True):
+        """One conf_kv_observe call per layer over the cached slots first .. first + tq - 1 with
+        seeded queries (drawn like decode queries, from a step index of their own); outputs and
+        state of the followed units are compared with the oracle's."""
+        torch, wl, kv, rep = self.torch, self.wl, self.kv, self.report
+        G = wl.group
+        for l in range(wl.n_layers):
+            parts = [gen.step_inputs(wl, self.seed + 7919, l, first + i)[0] for i in range(tq)]
+            q = np.ascontiguousarray(np.stack(parts, axis=1))                      # [B][tq][Hq][D]
+            out = torch.empty((wl.batch, tq, wl.n_q_heads, wl.head_dim), dtype=torch.float16,
+                              device="cuda") if want_out else None
+            kv.observe(l, first, torch.from_numpy(q).cuda(), out)
+            ref = self.run.observe(l, q, first, G)
+            if ref and want_out:
+                got = out.cpu().numpy().astype(np.float64)
+                for (ul, b, g), r in ref.items():
+                    o = got[b, :, g * G:(g + 1) * G]
+                    err = np.max(np.abs(o - r) / (OUT_ATOL + OUT_RTOL * np.abs(r)))
+                    rep.max_out_err = max(rep.max_out_err, float(err))
+                    assert err <= 1.0, f"observe {first}+{tq} unit {(ul, b, g)}: out off by {err:.3g} x tolerance"
+        self.compare_state(f"after observe {first}+{tq}")
+
     # ---- one decode step ----
     def step(self, check_state: bool = True, tq: int = 1):
         """One decode step; tq > 1 feeds tq tokens through one conf_kv_attend_chunk call per

@@ -113,6 +113,33 @@ def test_full_size_chunks(lib):
     ls.close()
 
 
+def test_full_size_observation_window(lib):
+    """Importance from the prompt's own attention at the roofline workload's shape (4 of its
+    layers): the last 32 prompt tokens observe the prompt in windows of 4 (the window ends inside
+    the FP16 tail and starts in INT8 slots when the tail is shorter than 32), then decode steps
+    evict by what the observation left."""
+    wl = workload(1).scaled(name="llama3_8b_b8_t4096_observe", n_layers=4, n_tight=(1024,) * 4,
+                            n_loose=(2048,) * 4, steps=3, max_chunk=4, fp16_window=24,
+                            logit_std=(0.5, 6.0), logit_run=1)
+    print(f"observation window at full size: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=2, units=6, threads=16)
+    for k, first in enumerate(range(wl.prefill - 32, wl.prefill, 4)):
+        ls.observe(first, 4, want_out=k % 2 == 0)
+    print(f"  observed: out_err={ls.report.max_out_err:.3f}xtol ema_rel={ls.report.max_ema_rel:.2e}", flush=True)
+    # the observation gave every followed unit a non-trivial importance profile
+    for u in ls.run.units.values():
+        assert np.count_nonzero(u.ema) > 0.99 * u.n
+    for t in range(3):
+        ls.step()
+        _invariants_all_units(ls, wl, t)
+        print(f"  step {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    print(f"  ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} flips={rep.evict_flips}/{rep.budget_flips}", flush=True)
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0 and rep.evictions > 0
+    ls.close()
+
+
 def test_chunks_on_long_units_take_the_two_launch_form(lib):
     """Four tokens per call on 64 units of 9000 slots: sixteen rows of scores for a slice of such
     a unit do not fit on chip next to the tile buffers at any resident split count, so the call

@@ -305,6 +305,134 @@ def _chunk_case(lib, torch, G, H, B, T0, W, splits, tqs, seed, scale_mode="token
     kv.close()
 
 
+def _observe_case(lib, torch, G, H, B, T0, W, splits, windows, seed, scale_mode="token", two_launch=False,
+                  decode_after=3):
+    """The prompt's own attention over an observation window: conf_kv_observe against the oracle's
+    observe_unit on the same cache, window by window, then decode steps with evictions ranked by
+    the importance it left."""
+    say(f"observe G={G} Hkv={H} B={B} T0={T0} W={W} splits={splits} windows={windows} scales={scale_mode} "
+        f"two_launch={two_launch}")
+    D = 128
+    if splits:
+        os.environ["CONF_KV_SPLITS"] = str(splits)
+    if two_launch:
+        os.environ["CONF_KV_TWO_LAUNCH"] = "1"
+    try:
+        cap = ((T0 + 8 + 63) // 64) * 64
+        kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
+                 protected_window=4, n_tight=[T0 - 20], n_loose=[T0 - 20], scale_mode=scale_mode,
+                 max_chunk=max(2, max(tq for _, tq in windows)))
+    finally:
+        os.environ.pop("CONF_KV_SPLITS", None)
+        os.environ.pop("CONF_KV_TWO_LAUNCH", None)
+    rng = np.random.default_rng(seed)
+    K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    e0 = rng.random((B, H, T0)).astype(np.float32)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(), torch.from_numpy(e0).cuda())
+    units = {(b, g): O.load_prefill(K[b, g], V[b, g], W, e0[b, g], scale_mode=scale_mode)
+             for b in range(B) for g in range(H)}
+    sm, lam = f32(1 / math.sqrt(D)), f32(0.9)
+    for k, (first, tq) in enumerate(windows):
+        q = rng.standard_normal((B, tq, G * H, D)).astype(np.float16)
+        # sharpen: each query leans on a few keys it may see and on one it may not (ahead of it)
+        for b in range(B):
+            for g in range(H):
+                near = K[b, g, rng.integers(0, first + 1)].astype(np.float32)
+                ahead = K[b, g, min(T0 - 1, first + tq)].astype(np.float32)
+                q[b, :, g * G:(g + 1) * G] = (q[b, :, g * G:(g + 1) * G].astype(np.float32) + 0.4 * near
+                                              + 0.4 * ahead).astype(np.float16)
+        want_out = k % 2 == 0                        # the output is optional
+        out = torch.zeros((B, tq, G * H, D), dtype=torch.float16, device="cuda") if want_out else None
+        kv.observe(0, first, torch.from_numpy(q).cuda(), out)
+        got = out.cpu().numpy().astype(np.float64) if want_out else None
+        for (b, g), u in units.items():
+            before = u.ema.copy()
+            ref, _ = O.observe_unit(u, q[b, :, g * G:(g + 1) * G], first, sm, lam)
+            if want_out:
+                o = got[b, :, g * G:(g + 1) * G]
+                err = np.max(np.abs(o - ref) / (1e-3 + 2e-3 * np.abs(ref)))
+                assert err <= 1.0, f"window {(first, tq)} unit {(b, g)}: out off by {err:.3g} x tol"
+            ex = kv.export(0, b, g)
+            assert ex["n"] == u.n == T0 and np.array_equal(ex["is16"], u.is16)
+            e_ref = u.ema.astype(np.float64)
+            e_err = np.abs(ex["ema"].astype(np.float64) - e_ref)
+            assert np.all(e_err <= 1e-7 + 2e-5 * e_ref), \
+                f"window {(first, tq)} unit {(b, g)}: EMA off, max rel {np.max(e_err / (e_ref + 1e-30)):.3g}"
+            # slots past the window keep their bits
+            assert np.array_equal(ex["ema"][first + tq:].view(np.uint32), before[first + tq:].view(np.uint32))
+    # decode: the ranking now runs on what the observation left
+    pos = T0
+    for step in range(decode_after):
+        q = rng.standard_normal((B, G * H, D)).astype(np.float16)
+        kn = rng.standard_normal((B, H, D)).astype(np.float16)
+        vn = rng.standard_normal((B, H, D)).astype(np.float16)
+        out = torch.zeros((B, G * H, D), dtype=torch.float16, device="cuda")
+        kv.attend(0, torch.from_numpy(q).cuda(), torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda(), out)
+        got = out.cpu().numpy().astype(np.float64)
+        kv.evict_compact()
+        for (b, g), u in units.items():
+            ref, _ = O.attend_unit(u, q[b, g * G:(g + 1) * G], kn[b, g], vn[b, g], pos, sm, lam)
+            err = np.max(np.abs(got[b, g * G:(g + 1) * G] - ref) / (1e-3 + 2e-3 * np.abs(ref)))
+            assert err <= 1.0, f"decode {step} unit {(b, g)}: out off by {err:.3g} x tol"
+            O.evict_compact_unit(u, T0 - 20, 4, f32(0.65), W)
+            ex = kv.export(0, b, g)
+            assert ex["n"] == u.n
+            # (seeded inputs: no score pair at the cut is closer than the EMA tolerance)
+            assert np.array_equal(ex["pos"], u.pos.astype(np.int32)), f"decode {step} unit {(b, g)}: kept set differs"
+        pos += 1
+    kv.close()
+
+
+@pytest.mark.parametrize("G,H,B,T0,W,splits,windows,scales", [
+    (4, 2, 2, 600, 64, 0, ((568, 4), (572, 4), (576, 4), (596, 4)), "token"),   # windows inside the FP16 tail
+    (4, 1, 1, 900, 32, 3, ((100, 4), (104, 3), (860, 4), (864, 4), (896, 4)), "token"),  # INT8 slots as window
+    (1, 2, 1, 400, 16, 2, ((368, 16), (384, 16)), "token"),                     # MHA, window crosses INT8 -> FP16
+    (2, 1, 1, 300, 0, 2, ((292, 8),), "token"),                                 # W = 0: the whole cache is INT8
+    (3, 1, 2, 260, -1, 2, ((0, 5), (5, 5), (255, 5)), "token"),                 # FP16-only cache, from slot 0
+    (4, 1, 1, 700, 48, 3, ((690, 2), (692, 4), (696, 4)), "channel"),           # per-channel scales
+    (8, 1, 1, 3000, 128, 0, ((2996, 2), (2998, 2)), "token"),                   # default plan of a long unit
+    (4, 1, 1, 500, 40, 1, ((499, 1),), "token"),                                # a single query
+])
+def test_observe_matches_oracle(lib, torch_cuda, G, H, B, T0, W, splits, windows, scales):
+    _observe_case(lib, torch_cuda, G, H, B, T0, W, splits, windows, seed=G * 100 + T0, scale_mode=scales)
+
+
+def test_observe_two_launch_form(lib, torch_cuda):
+    _observe_case(lib, torch_cuda, 4, 2, 1, 1200, 64, 4, ((1190, 4), (1194, 4)), seed=5, two_launch=True)
+
+
+def test_observe_call_errors(lib, torch_cuda):
+    torch = torch_cuda
+
+    def _raises(status, call):
+        with pytest.raises(lib.ConfKVError) as ei:
+            call()
+        assert ei.value.status == status
+    B, H, G, D, T0 = 1, 1, 4, 128, 100
+    K = torch.zeros((B, H, T0, D), dtype=torch.float16, device="cuda")
+    q = torch.zeros((B, 4, G * H, D), dtype=torch.float16, device="cuda")
+    # needs the 16-row kernel: max_chunk >= 2
+    kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=16, capacity=128,
+             protected_window=4, n_tight=[80], n_loose=[90])
+    kv.load_prefill(0, K, K, None)
+    _raises(lib.binding.ERR_INVALID_ARG, lambda: kv.observe(0, 90, q[:, :1]))
+    kv.close()
+    kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=16, capacity=128,
+             protected_window=4, n_tight=[80], n_loose=[90], max_chunk=4)
+    _raises(lib.binding.ERR_BAD_STATE, lambda: kv.observe(0, 0, q))        # nothing loaded yet
+    kv.load_prefill(0, K, K, None)
+    _raises(lib.binding.ERR_INVALID_ARG, lambda: kv.observe(0, 97, q))      # window past the prompt
+    _raises(lib.binding.ERR_INVALID_ARG, lambda: kv.observe(0, -1, q))
+    kv.observe(0, 96, q)
+    out = torch.zeros((B, G * H, D), dtype=torch.float16, device="cuda")
+    kv.attend(0, q[:, 0].contiguous(), K[:, :, 0].contiguous(), K[:, :, 0].contiguous(), out)
+    _raises(lib.binding.ERR_BAD_STATE, lambda: kv.observe(0, 96, q))        # the decode loop has begun
+    kv.evict_compact()
+    _raises(lib.binding.ERR_BAD_STATE, lambda: kv.observe(0, 96, q))
+    kv.close()
+
+
 @pytest.mark.parametrize("G,H,B,T0,W,splits,tqs,scales", [
     (4, 2, 2, 777, 40, 0, (4, 1, 3, 4), "token"),        # Llama-like group: up to 4 tokens a call
     (4, 1, 1, 1500, 128, 7, (4, 4), "token"),            # ragged splits, the chunk crosses tile borders
