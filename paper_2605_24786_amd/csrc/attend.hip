@@ -67,7 +67,7 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 #define TS(k)                                                                                   \
   do {                                                                                          \
     if (a.dbg && (threadIdx.x & 63) == 0)                                                       \
-      a.dbg[((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * kAttWaves + (threadIdx.x >> 6)) * 32 + (k)] = \
+      a.dbg[((size_t)(unit_in_layer(cv) * gridDim.x + blockIdx.x) * kAttWaves + (threadIdx.x >> 6)) * 32 + (k)] = \
           wall_clock64();                                                                       \
   } while (0)
 #else
@@ -128,29 +128,47 @@ struct Slice {
   __device__ __forceinline__ int slot_of(int t) const { return t < cnt8 ? lo8 + t : lo16 + (t - cnt8); }
 };
 
+// floor(x * j / ns) for x = q * ns + r (0 <= r < ns <= 64, j <= ns) without 64-bit division:
+// q * j + floor(r * j / ns), the small quotient through one reciprocal (exact: the argument is
+// below 4096 and (r j + 1/2) / ns is at least 1/128 away from every integer).
+__device__ __forceinline__ int share_cut(unsigned q, unsigned r, int j, float inv_ns) {
+  return (int)(q * (unsigned)j + (unsigned)(((float)(r * (unsigned)j) + 0.5f) * inv_ns));
+}
+// The launch grid is (splits, kv-heads, sequences).
+__device__ __forceinline__ int unit_in_layer(const CacheView &cv) { return blockIdx.z * cv.Hkv + blockIdx.y; }
+
 // Every split takes an equal share of the INT8 slots (cut at multiples of 32, the tile of
 // the matrix-core body) and an equal share of the FP16 slots, so all splits of a unit carry
 // the same mix of work and reach the arrival point together.
 __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLaunch &a, int ns, int S) {
   Slice s;
-  s.ul = blockIdx.y;
+  s.g = blockIdx.y;
+  s.b = blockIdx.z;
+  s.ul = unit_in_layer(cv);
   s.j = blockIdx.x;
   s.u = a.layer * cv.B * cv.Hkv + s.ul;
-  s.b = s.ul / cv.Hkv;
-  s.g = s.ul % cv.Hkv;
+  // The unit's four counters in ONE round trip: lanes 0..3 of every wavefront read one array
+  // each with a single load instruction (four scalar loads get spread over the prologue by the
+  // compiler, each waiting for the one before).
+  const int k4 = threadIdx.x & 3;
+  const int32_t *arr = k4 == 0 ? cv.len : k4 == 1 ? cv.n8 : k4 == 2 ? cv.head16 : cv.head8;
+  const int mv = arr[s.u];
+  const int len = __builtin_amdgcn_readlane(mv, 0), n8 = __builtin_amdgcn_readlane(mv, 1);
+  s.h16 = __builtin_amdgcn_readlane(mv, 2);
+  s.h8 = __builtin_amdgcn_readlane(mv, 3);
   // an observation call sees the unit as it was when its last query was the newest token
-  const bool observe = a.observe_first >= 0;
-  s.n = observe ? a.observe_first + a.tq : cv.len[s.u] + a.tq;     // the appended tokens included
-  s.n8 = observe ? min(cv.n8[s.u], s.n) : cv.n8[s.u];
-  s.h16 = cv.head16[s.u];
-  s.h8 = cv.head8[s.u];
+  s.n = (a.observe_first >= 0 ? a.observe_first : len) + a.tq;     // the appended tokens included
+  s.n8 = min(n8, s.n);                                             // n8 <= len outside observation calls
   s.n16 = s.n - s.n8;
-  s.lo8 = (int)((long long)s.n8 * s.j / ns) & ~31;
-  s.hi8 = s.j == ns - 1 ? s.n8 : (int)((long long)s.n8 * (s.j + 1) / ns) & ~31;
+  const float inv_ns = __builtin_amdgcn_rcpf((float)ns);
+  const unsigned q8 = (unsigned)s.n8 / (unsigned)ns, r8 = (unsigned)s.n8 - q8 * (unsigned)ns;
+  const unsigned q16 = (unsigned)s.n16 / (unsigned)ns, r16 = (unsigned)s.n16 - q16 * (unsigned)ns;
+  s.lo8 = share_cut(q8, r8, s.j, inv_ns) & ~31;
+  s.hi8 = s.j == ns - 1 ? s.n8 : share_cut(q8, r8, s.j + 1, inv_ns) & ~31;
   // outside observation calls the tail split's FP16 share is never empty (n16 >= 1), so its
   // owner holds slot n-1
-  s.lo16 = s.n8 + (int)((long long)s.n16 * s.j / ns);
-  s.hi16 = s.n8 + (int)((long long)s.n16 * (s.j + 1) / ns);
+  s.lo16 = s.n8 + share_cut(q16, r16, s.j, inv_ns);
+  s.hi16 = s.n8 + share_cut(q16, r16, s.j + 1, inv_ns);
   s.cnt8 = s.hi8 - s.lo8;
   s.ntok = s.cnt8 + (s.hi16 - s.lo16);
   if (s.ntok > S) {                       // cannot happen when the host plan is right
@@ -641,7 +659,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
                                                              int S) {
   constexpr int NP = kAttWaves;
   extern __shared__ __align__(16) float smem[];
-  float *stash = kSpill ? a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S
+  float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S
                         : smem;                 // [G][S] raw scores of the slice
   float *wo = smem + (kSpill ? 0 : (size_t)G * S);   // [NP][G][D] per-wave un-normalised output
   float *wm = wo + NP * G * D;                  // [NP][G] per-wave maximum
@@ -697,7 +715,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv
   double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
   __shared__ int s_ok;
   const Slice sl = make_slice(cv, a, ns, S);
-  float *stash = a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S;
+  float *stash = a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S;
   attend_epilogue<D, G, 1, 0, 2>(cv, a, sl, ns, S, stash, nullptr, nullptr, pml, gm, ginv, &s_ok);
 }
 
@@ -845,7 +863,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
       (kAttWaves * kTileBytes > NP * G * D * 4 ? kAttWaves * kTileBytes : NP * G * D * 4) / 4;
   extern __shared__ __align__(16) float smem[];
   float *tiles = smem;                          // per-wave tile buffers, later [NP][G][D] partials
-  float *stash = kSpill ? a.spill + ((size_t)blockIdx.y * ns + blockIdx.x) * G * S
+  float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S
                         : smem + kTileFloats;   // [G][S]
   float *gm = smem + kTileFloats + (kSpill ? 0 : (size_t)G * S);   // [G]
   double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
@@ -857,7 +875,13 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int tq = G > 8 ? a.tq : 1, gq = G > 8 ? a.gq : G;   // tokens of the call, heads per token
   TS(0);
+  // every kernel argument the streaming prologue needs, fetched now (one round trip) rather
+  // than piecemeal between the dependent loads below
+  asm volatile("" ::"s"(cv.k8), "s"(cv.v8), "s"(cv.ks), "s"(cv.vs), "s"(cv.k16), "s"(cv.v16), "s"(cv.len),
+               "s"(cv.n8), "s"(cv.head16), "s"(cv.head8), "s"(cv.cap8), "s"(cv.cap16), "s"(cv.Hkv), "s"(cv.B),
+               "s"(a.layer), "s"(a.tq), "s"(a.observe_first), "s"(a.q), "s"(a.knew), "s"(a.vnew));
   const Slice sl = make_slice(cv, a, ns, S);
+  TS(2);
   const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
   const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
   const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
@@ -908,6 +932,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   // the first INT8 tile is requested before anything else: its latency covers the append and
   // the query loads
   if (w < ntiles) tr = load_tile(w);
+  TS(3);
   append_new_token<D, false>(cv, a, sl, ns);
   const float NEG = -INFINITY;
   const float sm = a.sm_scale;
@@ -1444,7 +1469,7 @@ size_t attend_spill_floats(int units_per_layer, int G, int cap) {
 
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream) {
-  dim3 grid(plan.splits, cv.B * cv.Hkv);
+  dim3 grid(plan.splits, cv.Hkv, cv.B);
   if (plan.two_launch) {
     const bool rows16 = a.tq > 1 || a.observe_first >= 0;
     const int rows2 = rows16 ? kChunkRows : cv.G;                   // query rows per unit
