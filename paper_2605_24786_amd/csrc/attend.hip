@@ -579,9 +579,11 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     for (int h = tid >> 6; h < G; h += kAttWaves) {
       const int sp = tid & 63;
       const float ms = sp < ns ? pml[(sp * G + h) * 2] : NEG;
-      const float M = wave_max(ms);
-      const double term = ms > NEG ? exp((double)ms - (double)M) * (double)pml[(sp * G + h) * 2 + 1] : 0.0;
-      const double L = wave_sum(term);
+      // only the first gs lanes hold partials: log2(gs) exchange steps instead of six
+      float M = ms;
+      for (int m = gs >> 1; m >= 1; m >>= 1) M = fmaxf(M, __shfl_xor(M, m, kWave));
+      double L = ms > NEG ? (double)expf(ms - M) * (double)pml[(sp * G + h) * 2 + 1] : 0.0;
+      for (int m = gs >> 1; m >= 1; m >>= 1) L += __shfl_xor(L, m, kWave);
       if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; ginv[G + h] = (1.0 / L) * row_weight(a, tq, gq, h); }
     }
   }  // exchange
