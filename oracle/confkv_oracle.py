@@ -464,8 +464,11 @@ def shared_importance(units: Sequence["UnitCache"]) -> np.ndarray:
 
 def select_evictions(u: UnitCache, budget: int, protected: int, alpha: float,
                      importance: Optional[np.ndarray] = None, ranker: str = "composite",
-                     seed: int = 0, unit_key: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+                     seed: int = 0, unit_key: int = 0, page: int = 0
+                     ) -> Tuple[np.ndarray, np.ndarray]:
     """Slots to keep and to evict so that the length is at most the budget.
+
+    ``page`` > 1 coarsens the eviction to whole pages (``select_page_evictions``).
 
     If n <= N nothing happens.  Otherwise the newest P_eff = min(P, n) slots are
     protected, the other n - P_eff are candidates ranked by ``rank_scores``, and the
@@ -487,10 +490,51 @@ def select_evictions(u: UnitCache, budget: int, protected: int, alpha: float,
     else:
         a = u.ema if importance is None else importance
         s = rank_scores(a[:n_cand], u.pos[:n_cand], alpha)
-    order = np.lexsort((u.pos[:n_cand], s))        # by score, then older first
-    evict = np.sort(order[:e])
+    if page and page > 1:
+        evict = select_page_evictions(s, u.pos[:n], n_cand, e, page)
+    else:
+        order = np.lexsort((u.pos[:n_cand], s))    # by score, then older first
+        evict = np.sort(order[:e])
     keep = np.setdiff1d(np.arange(n), evict)
     return keep, evict
+
+
+def select_page_evictions(s: np.ndarray, pos: np.ndarray, n_cand: int, e: int, page: int) -> np.ndarray:
+    """Coarsened eviction ("Compatibility with serving systems" and "Limitations": token-level
+    eviction leaves partially dead blocks in a paged layout unless eviction is coarsened).
+
+    A page is the set of live slots whose original positions share floor(pos / page); slots
+    are position-sorted, so a page is a run of consecutive slots.  ``s`` [n_cand] are the
+    token scores of the candidates, exactly those the token-level rule ranks.  A page can go
+    only when every live slot of it is a candidate (none lies in the protected window).  Its
+    score is the mean of its slots' scores: their sum in slot order, in float64, divided by
+    their number.  Pages go whole, lowest score first and older first among equal scores,
+    until at least ``e`` slots are gone (so the length is at most the budget; it may fall
+    short of it by up to page - 1 slots) or no page that can go is left.
+    Returns the evicted slots, increasing.
+    """
+    pid = np.asarray(pos).astype(np.int64) // int(page)
+    n = len(pid)
+    pages = []                                      # (score, first slot, slot count)
+    i0 = 0
+    while i0 < n:
+        i1 = i0
+        while i1 < n and pid[i1] == pid[i0]:
+            i1 += 1
+        if i1 <= n_cand:
+            tot = F64(0.0)
+            for i in range(i0, i1):
+                tot = F64(tot + F64(s[i]))
+            pages.append((F64(tot / F64(i1 - i0)), i0, i1 - i0))
+        i0 = i1
+    pages.sort(key=lambda t: (t[0], t[1]))
+    gone, out = 0, []
+    for _, first, cnt in pages:
+        if gone >= e:
+            break
+        out.extend(range(first, first + cnt))
+        gone += cnt
+    return np.array(sorted(out), dtype=np.int64)
 
 
 def demote(u: UnitCache, fp16_window: int) -> int:
@@ -517,7 +561,7 @@ def evict_compact_unit(u: UnitCache, budget: int, protected: int, alpha: float, 
                        **ranking) -> np.ndarray:
     """Algorithm 1's per-layer tail for one unit: rank, evict, compact, then demote.
 
-    ``ranking`` goes to ``select_evictions`` (importance, ranker, seed, unit_key).
+    ``ranking`` goes to ``select_evictions`` (importance, ranker, seed, unit_key, page).
     Returns the original positions that were evicted.
     """
     keep, evict = select_evictions(u, budget, protected, alpha, **ranking)
@@ -549,6 +593,7 @@ class Policy:
     ranker: str = "composite"              # or "random"
     rank_scope: str = "kv_head"            # or "layer": one kept set per (layer, sequence)
     ranker_seed: int = 0
+    evict_page: int = 0                    # > 1: whole pages of that many positions are evicted
     batch: int = 1                         # needed for the random ranker's unit keys
     n_kv_heads: int = 1
 
@@ -629,13 +674,15 @@ class OracleRun:
                 for g, u in enumerate(group):
                     gone[(l, b, g)] = evict_compact_unit(u, N, p.protected, p.alpha, p.fp16_window,
                                                          importance=shared, ranker=p.ranker,
-                                                         seed=p.ranker_seed, unit_key=key)
+                                                         seed=p.ranker_seed, unit_key=key,
+                                                         page=p.evict_page)
         else:
             for (l, b, g), u in self.units.items():
                 N = p.n_tight[l] if tight[b] else p.n_loose[l]
                 key = (l * p.batch + b) * p.n_kv_heads + g
                 gone[(l, b, g)] = evict_compact_unit(u, N, p.protected, p.alpha, p.fp16_window,
-                                                     ranker=p.ranker, seed=p.ranker_seed, unit_key=key)
+                                                     ranker=p.ranker, seed=p.ranker_seed, unit_key=key,
+                                                     page=p.evict_page)
         self.next_pos += self.pending
         self.pending = 1
         return gone

@@ -334,8 +334,14 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.dbg = nullptr;
 #ifdef CONFKV_TRACE
   // the ranking work arrays at the end of the scratch buffer are idle during conf_kv_attend
-  if (getenv("CONF_KV_TRACE") && h->kl.total - h->kl.score >= (size_t)8 * 32 * 4 * 4096)
-    a.dbg = (unsigned long long *)(h->scratch + h->kl.total - (size_t)8 * 32 * 4 * 4096);
+  // (4 MB when they are that large, else 256 KB: enough for 128 workgroups)
+  if (getenv("CONF_KV_TRACE")) {
+    const size_t big = (size_t)8 * 32 * 4 * 4096, small = (size_t)8 * 32 * 8 * 128;
+    const size_t have = h->kl.total - h->kl.score;
+    const size_t need = (size_t)8 * 32 * 8 * plan.splits * UPL;
+    const size_t region = have >= big ? big : small;
+    if (have >= region && need <= region) a.dbg = (unsigned long long *)(h->scratch + h->kl.total - region);
+  }
 #endif
   CK_HIP(h, launch_attend(h->cv, a, plan, (hipStream_t)stream));
   if (!observe) {
