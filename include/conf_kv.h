@@ -85,6 +85,17 @@ typedef struct conf_kv_config {
   int32_t max_chunk;         /* most tokens one conf_kv_attend_chunk call may append; 0 or 1 =
                                 single-token calls only.  Above 1: head_dim 128 and
                                 max_chunk * (n_q_heads / n_kv_heads) <= 16                     */
+  int32_t evict_page;        /* 0 or 1: tokens are evicted one by one.  g > 1 (at most 1024):
+                                coarsened eviction for paged layouts -- a page is the live slots
+                                whose original positions share floor(position / g); a page
+                                goes whole or not at all, and only when none of its slots lies
+                                in the protected window; pages are ranked by the mean of their
+                                slots' scores and go lowest first, older first among equal
+                                means, until the length is at most the budget (it may end up to
+                                g - 1 below it) or no page that can go is left (up to g - 1
+                                slots over max(budget, protected_window) then remain).
+                                capacity must hold max(n_loose, protected_window + g - 1) plus
+                                the appended tokens                                            */
 } conf_kv_config;
 
 typedef enum conf_kv_scale_mode {

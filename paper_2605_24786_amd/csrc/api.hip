@@ -50,9 +50,13 @@ bool config_ok(const conf_kv_config *c) {
   if (c->max_chunk < 0) return false;
   if (c->max_chunk > 1 && (c->head_dim != 128 || c->max_chunk * (c->n_q_heads / c->n_kv_heads) > kChunkRows))
     return false;
+  if (c->evict_page < 0 || c->evict_page > 1024) return false;
+  const int page_slack = c->evict_page > 1 ? c->evict_page - 1 : 0;   // slots a page in the window can hold back
   for (int l = 0; l < c->n_layers; ++l) {
     if (c->n_tight[l] < 1 || c->n_tight[l] > c->n_loose[l]) return false;
-    if (std::max(c->n_loose[l], c->protected_window) + std::max(1, c->max_chunk) > c->capacity) return false;
+    if (std::max((long long)c->n_loose[l], (long long)c->protected_window + page_slack) + std::max(1, c->max_chunk) >
+        c->capacity)
+      return false;
   }
   return true;
 }
@@ -404,6 +408,7 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   opt.random = h->cfg.ranker == CONF_KV_RANKER_RANDOM;
   opt.seed = h->cfg.ranker_seed;
   opt.shared = h->cfg.rank_scope == CONF_KV_SCOPE_LAYER ? (double *)(h->scratch + h->kl.shared) : nullptr;
+  opt.page = h->cfg.evict_page > 1 ? h->cfg.evict_page : 0;
   CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, opt, (double *)(h->scratch + h->kl.score),
                                  (int32_t *)(h->scratch + h->kl.src),
                                  (int32_t *)(h->scratch + h->kl.sel), n_max, (hipStream_t)stream));
@@ -415,7 +420,8 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
     h->fresh_len[l] = -1;
     // any budget the step may have chosen is at most the loose one
     const int n = h->len_ub[l], NL = h->n_loose[l];
-    if (n > NL) h->len_ub[l] = std::max(NL, std::min(P, n));
+    // (a page that reaches into the protected window holds back up to evict_page - 1 more)
+    if (n > NL) h->len_ub[l] = std::max(NL, std::min(P + (opt.page > 1 ? opt.page - 1 : 0), n));
   }
   return CONF_KV_OK;
 }

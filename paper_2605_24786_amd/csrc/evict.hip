@@ -382,15 +382,58 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   }
   __syncthreads();                                  // orders the score writes before the reads
 
-  // radix select of the e-th smallest score
+  // Coarsened eviction: whole pages of opt.page original positions go.  Slots are
+  // position-sorted, so a page is a run of consecutive slots; the thread of its first slot
+  // adds up the token scores in slot order, and the page's mean replaces that slot's score.
+  // src[] holds, until the survivor list is written into it, the slot count of every page
+  // that can go at its first slot (a page with a slot in the protected window cannot),
+  // later -1 at every slot that goes, 0 elsewhere.
+  const int pg = opt.page;
+  bool all_go = false;                              // every page that can go goes: no select
+  if (pg > 1) {
+    for (int i = tid; i < n; i += kRsThreads) src[i] = 0;
+    __syncthreads();
+    int can = 0;
+    for (int i = tid; i < ncand; i += kRsThreads) {
+      const int pid = pos[ring_row_u(hm, i, cap)] / pg;
+      if (i == 0 || pos[ring_row_u(hm, i - 1, cap)] / pg != pid) {
+        double tot = 0.0;
+        int m = i;
+        while (m < n && pos[ring_row_u(hm, m, cap)] / pg == pid) {
+          if (m < ncand) tot = __dadd_rn(tot, score[m]);
+          ++m;
+        }
+        if (m <= ncand) {
+          score[i] = __ddiv_rn(tot, (double)(m - i));
+          src[i] = m - i;
+          can += m - i;
+        }
+      }
+    }
+    can = wave_sum(can);
+    if (lane == 0) s_tmp[w] = can;
+    __syncthreads();
+    can = 0;
+#pragma unroll
+    for (int k = 0; k < kRsWaves; ++k) can += s_tmp[k];
+    __syncthreads();                                // s_tmp is reused by the scans below
+    if (can == 0) {
+      if (tid == 0) write_selection(cv, u, sel, n, n8, n8, n, 0, -1);
+      return;
+    }
+    all_go = can <= e;
+  }
+
+  // radix select of the e-th smallest score (of the page whose slots take the count to e)
   unsigned long long mask = 0ull;
-  for (int shift = 56; shift >= 0; shift -= 8) {
+  for (int shift = 56; shift >= 0 && !all_go; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
     const unsigned long long prefix = s_prefix;
     for (int i = tid; i < ncand; i += kRsThreads) {
+      const int wgt = pg > 1 ? src[i] : 1;
       const unsigned long long key = (unsigned long long)__double_as_longlong(score[i]);
-      if ((key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255ull)], 1);
+      if (wgt > 0 && (key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255ull)], wgt);
     }
     __syncthreads();
     const int cnt = tid < 256 ? hist[tid] : 0;
@@ -411,18 +454,48 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   const int krem = s_krem;
   const bool whole_bucket = s_done != 0;            // no tie ranking needed
 
-  // survivor list in slot order; ties with the cut-off are evicted oldest first
   int carry_keep = 0, carry_tie = 0, kept8 = 0, hole = n, last8 = -1;
+  if (pg > 1) {
+    // page decisions, in slot order (pages that tie with the cut-off go oldest first until the
+    // count is reached); the thread of a page's first slot marks all its slots
+    for (int base = 0; base < ncand; base += kRsThreads) {
+      const int i = base + tid;
+      const int wgt = i < ncand ? max(src[i], 0) : 0;
+      int tie = 0, below = 0;
+      if (wgt > 0) {
+        const unsigned long long km = (unsigned long long)__double_as_longlong(score[i]) & mask;
+        below = km < prefix;
+        tie = km == prefix;
+      }
+      int go;
+      if (all_go) {
+        go = wgt > 0;
+      } else if (whole_bucket) {
+        go = below | tie;
+      } else {
+        int tot_tie;
+        const int before = carry_tie + block_scan_excl<kRsWaves>(tie ? wgt : 0, s_tmp, &tot_tie);
+        carry_tie += tot_tie;
+        go = below | (tie & (before < krem));
+      }
+      if (wgt > 0)
+        for (int m = i; m < i + wgt; ++m) src[m] = go ? -1 : 0;
+      __syncthreads();                              // marks may land in the next chunk's slots
+    }
+  }
+  // survivor list in slot order; ties with the cut-off are evicted oldest first
   for (int base = 0; base < n; base += kRsThreads) {
     const int i = base + tid;
     int tie = 0, below = 0;
-    if (i < ncand) {
+    if (pg <= 1 && i < ncand) {
       const unsigned long long km = (unsigned long long)__double_as_longlong(score[i]) & mask;
       below = km < prefix;
       tie = km == prefix;
     }
     int evict;
-    if (whole_bucket) {
+    if (pg > 1) {
+      evict = i < ncand && src[i] < 0;              // read before the scan's barriers, overwritten after
+    } else if (whole_bucket) {
       evict = below | tie;
     } else {
       int tot_tie;
@@ -452,8 +525,9 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
     int k8 = 0, hl = n, l8 = -1;
 #pragma unroll
     for (int k = 0; k < kRsWaves; ++k) { k8 += s_k8[k]; hl = min(hl, s_hole[k]); l8 = max(l8, s_last8[k]); }
-    write_selection(cv, u, sel, carry_keep /* = n - e */, n8, k8, hl, e, l8);
-    cv.unit_evicted[u] += (unsigned)e;              // per-unit counter: no contended atomic
+    // (n - carry_keep = e, or up to a page more under coarsened eviction)
+    write_selection(cv, u, sel, carry_keep, n8, k8, hl, n - carry_keep, l8);
+    cv.unit_evicted[u] += (unsigned)(n - carry_keep);   // per-unit counter: no contended atomic
   }
 }
 
@@ -1034,7 +1108,7 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
                                 int n_max, hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
-  if (opt.random || opt.shared) {
+  if (opt.random || opt.shared || opt.page > 1) {
     // ranker variants: the general kernel only
     if (opt.shared)
       hipLaunchKernelGGL(shared_mass_kernel, dim3(cv.L * cv.B, (cv.cap + kEvThreads - 1) / kEvThreads),

@@ -71,6 +71,7 @@ struct RankOptions {
   int random;                  // 1: rank by counter-based uniform draws instead of the composite score
   unsigned long long seed;
   double *shared;              // non-null: layer scope; [L * B][cap] scratch for the summed mass
+  int page;                    // > 1: whole pages of that many original positions are evicted
 };
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
                                 const RankOptions &opt, double *score, int32_t *src, int32_t *sel,

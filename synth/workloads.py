@@ -44,6 +44,7 @@ class Workload:
     ranker_seed: int = 0
     scale_mode: str = "token"            # or "channel": INT8 scales per (kv-head, channel)
     max_chunk: int = 0                   # most tokens per multi-token attend call (0: single-token only)
+    evict_page: int = 0                  # > 1: whole pages of that many original positions are evicted
     # input recipe
     heavy_hitter_prob: float = 0.02      # fraction of key positions shifted by +3 u
     heavy_hitter_gain: float = 3.0
@@ -68,7 +69,8 @@ class Workload:
     @property
     def capacity(self) -> int:
         """Slots a unit needs: the longest cache it can ever hold, plus the append."""
-        longest = max(self.prefill, max(self.n_loose), self.protected) + max(1, self.max_chunk)
+        slack = self.evict_page - 1 if self.evict_page > 1 else 0     # a page reaching into the window stays
+        longest = max(self.prefill, max(self.n_loose), self.protected + slack) + max(1, self.max_chunk)
         return ((longest + 63) // 64) * 64
 
     def scaled(self, **kw) -> "Workload":

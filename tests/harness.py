@@ -37,7 +37,8 @@ def policy_of(wl) -> O.Policy:
                     weights=(f32(wl.w_entropy), f32(wl.w_margin), f32(wl.w_top)),
                     mass_gain=None if getattr(wl, "mass_gain", None) is None else f32(wl.mass_gain),
                     ranker=getattr(wl, "ranker", "composite"), rank_scope=getattr(wl, "rank_scope", "kv_head"),
-                    ranker_seed=getattr(wl, "ranker_seed", 0), batch=wl.batch, n_kv_heads=wl.n_kv_heads)
+                    ranker_seed=getattr(wl, "ranker_seed", 0), evict_page=getattr(wl, "evict_page", 0),
+                    batch=wl.batch, n_kv_heads=wl.n_kv_heads)
 
 
 @dataclass
@@ -226,6 +227,14 @@ class Lockstep:
         l = key[0]
         N = p.n_tight[l] if tight else p.n_loose[l]
         n = pre.n
+        if p.evict_page > 1 or p.ranker != "composite" or p.rank_scope != "kv_head":
+            # no near-tie analysis for the variants: any difference counts as a flip
+            rep.evict_flips.append(1.0)
+            u = pre.copy()
+            u.take(np.flatnonzero(np.isin(pre.pos, gpu_pos)))
+            O.demote(u, p.fp16_window)
+            self.run.units[key] = u
+            return
         p_eff = min(p.protected, n)
         ncand = n - p_eff
         s = O.rank_scores(pre.ema[:ncand], pre.pos[:ncand], p.alpha)

@@ -66,7 +66,8 @@ def test_buffer_sizes(clib):
                                  dict(ema_decay=-0.1), dict(mass_gain=float("nan")), dict(_ranker=2),
                                  dict(_rank_scope=-1), dict(_scale_mode=2), dict(max_chunk=-1), dict(max_chunk=5),
                                  dict(max_chunk=2, head_dim=64), dict(max_chunk=70, n_tight=[64, 64], n_loose=[200, 200]),
-                                 dict(scale_mode="channel", head_dim=64),
+                                 dict(scale_mode="channel", head_dim=64), dict(evict_page=-1), dict(evict_page=1025),
+                                 dict(evict_page=64, protected_window=200, capacity=256),
                                  dict(scale_mode="channel", fp16_window=-1)])
 def test_bad_configs_are_rejected(clib, bad):
     kw = dict(bad)

@@ -159,8 +159,10 @@ def test_chunks_on_long_units_take_the_two_launch_form(lib):
     ls.close()
 
 
-def test_page_fragmentation_of_token_level_eviction(lib):
-    """What token-level eviction would cost a paged layout ("Compatibility with serving systems",
+@pytest.mark.parametrize("evict_page", [0, 16])
+def test_page_fragmentation_of_token_level_eviction(lib, evict_page):
+    """With evict_page = 16 the same run under coarsened eviction: no page of 16 is partially dead
+    (the newest one aside).  With 0: what token-level eviction would cost a paged layout ("Compatibility with serving systems",
     "Limitations": partially dead blocks): after a steady-state run at workload 4's shape (4 of
     its layers), group the ORIGINAL positions into pages of 16 and 32 tokens and count, per unit,
     the pages that still hold a live token against the pages the live tokens would fill if packed.
@@ -168,7 +170,7 @@ def test_page_fragmentation_of_token_level_eviction(lib):
     design notes and only sanity-checked here."""
     import torch
     wl = workload(4).scaled(n_layers=4, n_tight=workload(4).n_tight[:4], n_loose=workload(4).n_loose[:4],
-                            steps=120, logit_run=3)
+                            steps=120, logit_run=3, evict_page=evict_page)
     kv = lib.from_workload(wl)
     for l in range(wl.n_layers):
         K, V = gen.prefill_layer(wl, 0, l, threads=16)
@@ -190,7 +192,9 @@ def test_page_fragmentation_of_token_level_eviction(lib):
             live_pages += ids.size
             packed_pages += -(-pos.size // page)
             partial += int((counts < page).sum())
-        print(f"page size {page}: live pages {live_pages}, packed {packed_pages} "
+            if evict_page == page:                      # only the newest page may be short
+                assert not (counts[:-1] < page).any()
+        print(f"evict_page {evict_page}, page size {page}: live pages {live_pages}, packed {packed_pages} "
               f"(overhead {live_pages / packed_pages:.2f}x), partially dead {partial / live_pages:.0%}", flush=True)
         assert live_pages >= packed_pages
     assert kv.counters().device_errors == 0 and kv.counters().evicted > 0

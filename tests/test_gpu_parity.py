@@ -560,6 +560,111 @@ def _evict_case(lib, torch, n, N, P, W, alpha, ema, D=64, seed=0):
     return u
 
 
+def _page_case(lib, torch, n, N, P, W, page, alpha, ema, thin=None, D=64, seed=0):
+    """Coarsened eviction of one unit against the oracle; thin = keep every slot with that
+    probability first (positions with gaps, brought in through conf_kv_import)."""
+    rng = np.random.default_rng(seed)
+    cap = ((max(n, N, P + page) + 1 + 63) // 64) * 64
+    cfg = dict(n_q_heads=1, n_kv_heads=1, head_dim=D, fp16_window=W, protected_window=P, capacity=cap,
+               n_tight=[N], n_loose=[N], alpha=alpha, evict_page=page)
+    kv = _mk(lib, **cfg)
+    K = rng.standard_normal((1, 1, n, D)).astype(np.float16)
+    V = rng.standard_normal((1, 1, n, D)).astype(np.float16)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(),
+                    torch.from_numpy(ema.reshape(1, 1, n).astype(np.float32)).cuda())
+    u = O.load_prefill(K[0, 0], V[0, 0], W, ema.astype(np.float32))
+    if thin is not None:
+        idx = np.flatnonzero(rng.random(n) < thin)
+        view = kv.export(0, 0, 0)
+        view = {k: (int(idx.size) if k == "n" else np.ascontiguousarray(np.asarray(x)[idx])) for k, x in view.items()}
+        kv.close()
+        kv = _mk(lib, **cfg)
+        kv.import_unit(0, 0, 0, view)
+        u.take(idx)
+    n0 = u.n
+    kv.evict_compact()
+    gone = O.evict_compact_unit(u, N, P, f32(alpha), W, page=page)
+    ex = kv.export(0, 0, 0)
+    assert ex["n"] == u.n, (ex["n"], u.n)
+    assert np.array_equal(ex["pos"], u.pos.astype(np.int32))
+    assert np.array_equal(ex["is16"], u.is16) and np.array_equal(ex["ema"], u.ema)
+    m8 = ~u.is16
+    assert np.array_equal(ex["k8"][m8], u.k8[m8]) and np.array_equal(ex["v8"][m8], u.v8[m8])
+    assert np.array_equal(ex["k16"][u.is16].view(np.uint16), u.k16[u.is16].view(np.uint16))
+    assert kv.counters().evicted == gone.size == n0 - u.n
+    kv.close()
+    return u, gone
+
+
+@pytest.mark.parametrize("n,N,P,W,page,thin", [
+    (300, 100, 20, 30, 16, None), (300, 100, 20, -1, 16, None), (1000, 999, 1, 16, 32, None),
+    (515, 64, 64, 8, 16, None), (200, 50, 0, 0, 4, None), (4000, 512, 128, 64, 16, None),
+    (260, 100, 10, 150, 8, None), (90, 200, 10, 16, 16, None), (700, 699, 16, 32, 16, None),
+    (3000, 2998, 64, -1, 32, None), (2500, 1024, 128, 64, 16, 0.7), (900, 300, 16, 32, 32, 0.4),
+    (1200, 600, 40, -1, 16, 0.5), (400, 399, 8, 16, 2, 0.9), (5000, 4000, 128, 128, 1024, None),
+])
+def test_evict_pages_random_ema(lib, torch_cuda, n, N, P, W, page, thin):
+    say(f"evict pages n={n} N={N} P={P} W={W} page={page} thin={thin}")
+    rng = np.random.default_rng(n + N + page)
+    u, gone = _page_case(lib, torch_cuda, n, N, P, W, page, 0.65, rng.random(n), thin=thin, seed=n)
+    # pages go whole
+    left = set((u.pos // page).tolist())
+    assert not left & set((gone // page).tolist())
+
+
+def test_evict_pages_ties_and_degenerate(lib, torch_cuda):
+    say("evict pages: ties, degenerate cases")
+    # every score equal (alpha = 1, equal mass): the oldest pages go, the last one whole
+    u, gone = _page_case(lib, torch_cuda, 300, 250, 10, 16, 16, 1.0, np.full(300, 0.25))
+    assert gone.tolist() == list(range(64)) and u.n == 236
+    # recency only: a sliding window in whole pages
+    u, gone = _page_case(lib, torch_cuda, 300, 251, 10, 16, 16, 0.0, np.random.default_rng(0).random(300))
+    assert gone.tolist() == list(range(64))
+    # two values: pages of equal mean tie exactly, older first
+    ema = np.where((np.arange(512) // 16) % 2 == 0, 0.125, 0.875)
+    u, gone = _page_case(lib, torch_cuda, 512, 400, 16, 32, 16, 1.0, ema)
+    assert sorted(set((gone // 16).tolist())) == [0, 2, 4, 6, 8, 10, 12]
+    # nothing can go: every candidate shares its page with a protected slot
+    u, gone = _page_case(lib, torch_cuda, 60, 10, 40, 8, 64, 0.65, np.random.default_rng(1).random(60))
+    assert gone.size == 0 and u.n == 60
+    # fewer evictable slots than asked for: all of them go
+    u, gone = _page_case(lib, torch_cuda, 100, 10, 30, 8, 32, 0.65, np.random.default_rng(2).random(100))
+    assert gone.tolist() == list(range(64)) and u.n == 36
+    # page of one = the token rule
+    rng = np.random.default_rng(3)
+    ema = rng.random(400)
+    a, _ = _page_case(lib, torch_cuda, 400, 200, 16, 32, 1, 0.65, ema, seed=3)
+    b = _evict_case(lib, torch_cuda, 400, 200, 16, 32, 0.65, ema, seed=3)
+    assert np.array_equal(a.pos, b.pos)
+
+
+@pytest.mark.parametrize("G,D,W,page,scope,tq", [(4, 128, 16, 16, "kv_head", 1), (1, 64, -1, 8, "kv_head", 1),
+                                                 (4, 128, 24, 32, "layer", 1), (2, 128, 16, 16, "kv_head", 4)])
+def test_lockstep_page_eviction(lib, torch_cuda, G, D, W, page, scope, tq):
+    """Decode loops with coarsened eviction: state bit-identical to the oracle's at every step, and
+    no page of original positions is ever partially dead (the newest, still filling one aside)."""
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=D, vocab=2003, prefill=260,
+                         steps=40, n_tight=(150, 120), n_loose=(230, 200), protected=20, fp16_window=W,
+                         alpha=0.5, logit_std=(0.5, 6.0), logit_run=5, evict_page=page, rank_scope=scope,
+                         max_chunk=tq if tq > 1 else 0)
+    say(f"lockstep pages G={G} D={D} W={W} page={page} scope={scope} tq={tq} capacity={wl.capacity}")
+    ls = Lockstep(lib, wl, seed=11)
+    t = 0
+    while t < wl.steps:
+        ls.step(tq=tq)
+        t += tq
+        for key, u in ls.run.units.items():
+            live = np.bincount((u.pos // page).astype(np.int64))
+            newest = int(u.pos[-1]) // page
+            bad = [k for k, c in enumerate(live) if c not in (0, page) and k != newest]
+            assert not bad, (t, key, bad)
+    rep = ls.report
+    assert rep.ok(), rep.evict_flips
+    assert rep.evictions > 0 and rep.tight_steps > 0
+    assert ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 @pytest.mark.parametrize("n,N,P,W", [(300, 100, 20, 30), (300, 100, 20, -1), (1000, 999, 1, 16),
                                      (515, 64, 64, 8), (200, 50, 0, 0), (4000, 512, 128, 64),
                                      (260, 100, 10, 150), (90, 200, 10, 16),
@@ -969,6 +1074,8 @@ def _random_config(seed):
         kw["rank_scope"] = "layer"
     if D == 128 and W >= 0 and rng.random() < 0.4:
         kw["scale_mode"] = "channel"
+    if rng.random() < 0.3:
+        kw["evict_page"] = int(rng.choice([2, 4, 16]))
     tq_max = 1
     if D == 128 and rng.random() < 0.5:
         tq_max = int(rng.integers(2, 16 // G + 1)) if 16 // G >= 2 else 1
