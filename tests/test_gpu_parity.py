@@ -1114,7 +1114,10 @@ def test_heavy_hitter_recall_by_ranker_mode(lib, torch_cuda):
                            n_tight=(300,), n_loose=(300,), protected=32, fp16_window=32, logit_run=4)
     modes = {"composite": dict(alpha=0.65), "attention only": dict(alpha=1.0), "recency only": dict(alpha=0.0),
              "cumulative mass": dict(alpha=0.65, ema_decay=1.0, mass_gain=1.0),
-             "random": dict(ranker="random", ranker_seed=5)}
+             "random": dict(ranker="random", ranker_seed=5),
+             # coarsened eviction: a heavy hitter survives only with its whole page
+             "attention only, pages of 4": dict(alpha=1.0, evict_page=4),
+             "attention only, pages of 16": dict(alpha=1.0, evict_page=16)}
     recall, kept_n = {}, {}
     for name, variant in modes.items():
         wl = base.scaled(**variant)
@@ -1138,7 +1141,12 @@ def test_heavy_hitter_recall_by_ranker_mode(lib, torch_cuda):
         recall[name] = hit / tot
         kv.close()
     say("heavy-hitter recall after 1500 -> 300 slots: " + ", ".join(f"{k} {v:.2f}" for k, v in recall.items()))
-    assert len(set(kept_n.values())) == 1                       # matched rate
+    token_level = [k for k in modes if "pages" not in k]
+    assert len({kept_n[k] for k in token_level}) == 1          # matched rate
+    assert all(kept_n["composite"] - 16 < kept_n[k] <= kept_n["composite"] for k in modes)
+    # whole pages dilute a single important token: recall falls with the page size
+    assert recall["attention only"] >= recall["attention only, pages of 4"] >= recall["attention only, pages of 16"]
+    assert recall["attention only, pages of 16"] > recall["random"]
     assert recall["attention only"] > 0.8
     assert recall["composite"] > recall["recency only"] + 0.1 and recall["composite"] > recall["random"] + 0.15
     assert recall["cumulative mass"] > recall["recency only"] + 0.1
