@@ -664,8 +664,15 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
     for (int bin = tid; bin < 256; bin += T) hnext[bin] = 0;
 #pragma unroll
     for (int k = 0; k < E; ++k) {
-      if (k < Ed && tid + k * T < ncand && (key[k] & mask) == prefix)
-        atomicAdd(&hcur[(int)((unsigned)(key[k] >> shift) & dmask)], 1);
+      if (k < Ed && tid + k * T < ncand && (key[k] & mask) == prefix) {
+        // scores in (0, 1] share their leading exponent bits, so in the first pass most lanes of
+        // a wavefront hit one bin: the lanes that share the first active lane's bin add once
+        const int bin = (int)((unsigned)(key[k] >> shift) & dmask);
+        const int b0 = __builtin_amdgcn_readfirstlane(bin);
+        const unsigned long long same = __builtin_amdgcn_ballot_w64(bin == b0);
+        if (bin != b0) atomicAdd(&hcur[bin], 1);
+        else if (lanes_below(same) == 0) atomicAdd(&hcur[b0], __builtin_popcountll(same));
+      }
     }
     __syncthreads();
     if (tid < kWave) {
