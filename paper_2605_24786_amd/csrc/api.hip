@@ -112,7 +112,8 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   s.zero_bytes = off;
   s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
   s.part_ml = take(UPL * kAttendMaxSplits * R * 2 * 4);
-  s.part_o = take(UPL * kAttendMaxSplits * R * D * 4);
+  // (the matrix-core body exchanges 128-channel partials whatever the head dimension)
+  s.part_o = take(UPL * kAttendMaxSplits * R * std::max<size_t>(D, 128) * 4);
   s.spill = take(attend_spill_floats((int)UPL, (int)R, c->capacity) * 4);
   s.score = take(U * c->capacity * 8);
   s.src = take(U * c->capacity * 4);

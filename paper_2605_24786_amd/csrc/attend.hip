@@ -480,7 +480,7 @@ __device__ __forceinline__ double row_weight(const AttendLaunch &a, int tq, int 
 // later launch, which needs no wait (wm/wl are unused and wo is [ns][G][2] floats of LDS) --
 // the pair serves shapes whose splits cannot all be resident at once.
 // ---------------------------------------------------------------------------------------
-template <int D, int G, int NP, int WSTR, int kPhase = 0>
+template <int D, int G, int NP, int WSTR, int kPhase = 0, int DR = D>
 __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const AttendLaunch &a,
                                                 const Slice &sl, int ns, int S, float *stash,
                                                 float *wm, float *wl, float *wo, float *gm,
@@ -538,7 +538,9 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       __half2 o2;
       o2.x = __float2half_rn((float)((double)o0 * inv));
       o2.y = __float2half_rn((float)((double)o1 * inv));
-      if (h < tq * gq && a.out) *(__half2 *)&a.out[out_index(cv, sl, tq, gq, idx, D)] = o2;
+      // (DR < D: the matrix-core body pads a 64-channel head to its 128-channel tiles)
+      if (h < tq * gq && a.out && idx - h * D < DR)
+        *(__half2 *)&a.out[out_index(cv, sl, tq, gq, h * DR + (idx - h * D), DR)] = o2;
       if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
     } else {
       st_agent2(&po[idx], o0, o1);
@@ -645,8 +647,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       const float ms = valid ? pml[(os * G + h) * 2] : NEG;
       float c = ms > NEG ? v * expf(ms - gm[h]) : 0.f;               // an empty partial weighs nothing
       for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
-      if (valid && os == 0 && h < tq * gq && a.out)
-        a.out[out_index(cv, sl, tq, gq, e, D)] = __float2half_rn((float)((double)c * ginv[h]));
+      if (valid && os == 0 && h < tq * gq && a.out && e - h * D < DR)
+        a.out[out_index(cv, sl, tq, gq, h * DR + (e - h * D), DR)] = __float2half_rn((float)((double)c * ginv[h]));
     }
   }
 }
@@ -708,7 +710,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 
 // Second launch of the two-launch form: same grid; merges the published partials of the unit,
 // updates the EMA of its slice from the spilled scores and normalises its share of the output.
-template <int D, int G>
+template <int D, int G, int DR = D>
 __global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv, AttendLaunch a, int ns,
                                                                     int S) {
   extern __shared__ __align__(16) float smem[];
@@ -718,11 +720,11 @@ __global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv
   __shared__ int s_ok;
   const Slice sl = make_slice(cv, a, ns, S);
   float *stash = a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S;
-  attend_epilogue<D, G, 1, 0, 2>(cv, a, sl, ns, S, stash, nullptr, nullptr, pml, gm, ginv, &s_ok);
+  attend_epilogue<D, G, 1, 0, 2, DR>(cv, a, sl, ns, S, stash, nullptr, nullptr, pml, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
-// Kernel 2: matrix-core body for the INT8 slots (D = 128), vector ALU for the FP16 slots
+// Kernel 2: matrix-core body (D = 128, or D = 64 padded to the same tiles)
 // ---------------------------------------------------------------------------------------
 constexpr int kTile = 32;              // slots per wavefront tile
 constexpr int kKRow = 128 + 16;        // LDS row stride of the INT8 K tile (bytes)
@@ -854,11 +856,16 @@ __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], i
 // carry a zero query, and a row sees the call's own tokens causally.
 // kSpill: the first launch of the two-launch form (raw scores to device scratch, ends after
 // publishing its partial).
-template <int G, bool kChan = false, bool kSpill = false>
+template <int G, bool kChan = false, bool kSpill = false, int DR = 128>
 __global__ __launch_bounds__(kAttThreads)
 __attribute__((amdgpu_waves_per_eu((kChan || G > 8) ? 2 : 3, (kChan || G > 8) ? 2 : 3)))
 void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
+  // D: channels of the tiles and partials on chip.  DR: the head dimension in memory; a 64-channel
+  // head runs on the same tiles with channels 64..127 holding a second copy of its rows against
+  // zero query channels (their products are 0, their outputs are dropped).
   constexpr int D = 128;
+  static_assert(DR == 64 || DR == 128, "head dimension");
+  static_assert(!(kChan && DR != 128), "per-channel scales need 128 channels");
   static_assert(G * D * 4 <= kTileBytes, "a wavefront's output partial must fit its tile buffer");
   constexpr int NP = kAttWaves;                 // one partial per wavefront
   constexpr int kTileFloats =
@@ -886,8 +893,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   TS(2);
   const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
   const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
-  const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * D;
-  const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * D;
+  const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * DR;
+  const int8_t *V8 = cv.v8 + (size_t)sl.u * cv.cap8 * DR;
   const __half *KS = cv.ks + (size_t)sl.u * (kChan ? D : cv.cap8);
   const __half *VS = cv.vs + (size_t)sl.u * (kChan ? D : cv.cap8);
 
@@ -904,12 +911,12 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     const int base = sl.lo8 + tile * kTile;
     const int last = sl.hi8 - 1;
     // 32-bit byte offsets from the unit's (wavefront-uniform) plane bases
-    const unsigned col = (unsigned)c8 * 16u;
+    const unsigned col = (unsigned)(c8 & (DR / 16 - 1)) * 16u;
     const int h8 = sl.h8, cap8 = cv.cap8;
-    const unsigned o0 = (unsigned)ring_row_u(h8, min(base + r8, last), cap8) * D + col;
-    const unsigned o1 = (unsigned)ring_row_u(h8, min(base + 8 + r8, last), cap8) * D + col;
-    const unsigned o2 = (unsigned)ring_row_u(h8, min(base + 16 + r8, last), cap8) * D + col;
-    const unsigned o3 = (unsigned)ring_row_u(h8, min(base + 24 + r8, last), cap8) * D + col;
+    const unsigned o0 = (unsigned)ring_row_u(h8, min(base + r8, last), cap8) * DR + col;
+    const unsigned o1 = (unsigned)ring_row_u(h8, min(base + 8 + r8, last), cap8) * DR + col;
+    const unsigned o2 = (unsigned)ring_row_u(h8, min(base + 16 + r8, last), cap8) * DR + col;
+    const unsigned o3 = (unsigned)ring_row_u(h8, min(base + 24 + r8, last), cap8) * DR + col;
     t.k0 = *(const int4 *)(K8 + o0);
     t.v0 = *(const int4 *)(V8 + o0);
     t.k1 = *(const int4 *)(K8 + o1);
@@ -935,7 +942,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   // the query loads
   if (w < ntiles) tr = load_tile(w);
   TS(3);
-  append_new_token<D, false>(cv, a, sl, ns);
+  append_new_token<DR, false>(cv, a, sl, ns);
   const float NEG = -INFINITY;
   const float sm = a.sm_scale;
   TS(1);
@@ -952,11 +959,11 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   {
     // row t16 = (token, head) of the call's [B][tq][Hq][D] queries
     const int q_tok = t16 / gq, q_head = t16 - q_tok * gq;
-    const __half *qrow = a.q + ((((size_t)sl.b * tq + q_tok) * cv.Hkv + sl.g) * gq + q_head) * D;
+    const __half *qrow = a.q + ((((size_t)sl.b * tq + q_tok) * cv.Hkv + sl.g) * gq + q_head) * DR;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       int4 raw = make_int4(0, 0, 0, 0);
-      if (t16 < G && q_tok < tq) raw = *(const int4 *)(qrow + g4 * 32 + 8 * s);
+      if (t16 < G && q_tok < tq && g4 * 32 + 8 * s < DR) raw = *(const int4 *)(qrow + g4 * 32 + 8 * s);
       qa[s] = __builtin_bit_cast(half8_t, raw);
     }
   }
@@ -1005,25 +1012,25 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   const int base16 = sl.lo16;
   const int ntiles16 = (sl.hi16 - sl.lo16 + 15) / 16;
   const int nitems = ntiles + ntiles16;
-  const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * D;
-  const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * D;
+  const __half *K16 = cv.k16 + (size_t)sl.u * cv.cap16 * DR;
+  const __half *V16 = cv.v16 + (size_t)sl.u * cv.cap16 * DR;
   const int c16 = lane & 15, r4 = lane >> 4;     // FP16 load coordinates: 16-byte piece, row
   auto load_tile16 = [&](int f) -> TileRegs {
     TileRegs t;
     const int base = base16 + 16 * f, last = sl.hi16 - 1;
     const int h16 = sl.h16, cap16 = cv.cap16, n8 = sl.n8;
-    const unsigned col = (unsigned)c16 * 8u;
-    const unsigned o0 = (unsigned)ring_row(h16, min(base + r4, last) - n8, cap16) * D + col;
-    const unsigned o1 = (unsigned)ring_row(h16, min(base + 4 + r4, last) - n8, cap16) * D + col;
-    const unsigned o2 = (unsigned)ring_row(h16, min(base + 8 + r4, last) - n8, cap16) * D + col;
-    const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * D + col;
+    const unsigned col = (unsigned)(c16 & (DR / 8 - 1)) * 8u;
+    const unsigned o0 = (unsigned)ring_row(h16, min(base + r4, last) - n8, cap16) * DR + col;
+    const unsigned o1 = (unsigned)ring_row(h16, min(base + 4 + r4, last) - n8, cap16) * DR + col;
+    const unsigned o2 = (unsigned)ring_row(h16, min(base + 8 + r4, last) - n8, cap16) * DR + col;
+    const unsigned o3 = (unsigned)ring_row(h16, min(base + 12 + r4, last) - n8, cap16) * DR + col;
     // the call's own tokens (slots n - tq .. n - 1, at the end of the unit's last split) are
     // taken from the call's arguments, not read back from the ring: no wait on the append's stores
     // (an observation call appends nothing: every row comes from the ring)
     const int first_new = a.observe_first >= 0 ? 0x3fffffff : sl.n - tq;
-    const size_t tok = (size_t)cv.Hkv * D;                      // [B][tq][Hkv][D]: stride of a token
-    const __half *kn = a.knew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * D + col;
-    const __half *vn = a.vnew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * D + col;
+    const size_t tok = (size_t)cv.Hkv * DR;                     // [B][tq][Hkv][D]: stride of a token
+    const __half *kn = a.knew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * DR + col;
+    const __half *vn = a.vnew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * DR + col;
     const int s0 = min(base + r4, last) - first_new, s1 = min(base + 4 + r4, last) - first_new;
     const int s2 = min(base + 8 + r4, last) - first_new, s3 = min(base + 12 + r4, last) - first_new;
     t.k0 = *(const int4 *)(s0 >= 0 ? kn + s0 * tok : K16 + o0);
@@ -1271,7 +1278,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   TS(17);
   __syncthreads();
   TS(18);
-  attend_epilogue<D, G, NP, kTileBytes / 4, kSpill ? 1 : 0>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+  attend_epilogue<D, G, NP, kTileBytes / 4, kSpill ? 1 : 0, DR>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1306,7 +1313,27 @@ static AttendFn attend_fn_spill(int D, int G, bool finish) {
   return nullptr;
 }
 
+// Second launch behind the matrix-core body at D = 64: the partials are 128 channels wide.
+static AttendFn attend_fn_finish_padded(int G) {
+#define CONFKV_CASE(g) \
+  case g: return (AttendFn)attend_finish_kernel<128, g, 64>;
+  switch (G) {
+    CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
+    default: return nullptr;
+  }
+#undef CONFKV_CASE
+}
+
 static AttendFn attend_fn_mfma(int D, int G, bool chan) {
+  if (D == 64 && !chan) {
+#define CONFKV_CASE(g) \
+  case g: return (AttendFn)attend_mfma_kernel<g, false, false, 64>;
+    switch (G) {
+      CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
+      default: return nullptr;
+    }
+#undef CONFKV_CASE
+  }
   if (D != 128) return nullptr;
 #define CONFKV_CASE(g) \
   case g: return chan ? (AttendFn)attend_mfma_kernel<g, true> : (AttendFn)attend_mfma_kernel<g, false>;
@@ -1319,6 +1346,15 @@ static AttendFn attend_fn_mfma(int D, int G, bool chan) {
 }
 
 static AttendFn attend_fn_mfma_spill(int D, int G, bool chan) {
+  if (D == 64 && !chan) {
+#define CONFKV_CASE(g) \
+  case g: return (AttendFn)attend_mfma_kernel<g, false, true, 64>;
+    switch (G) {
+      CONFKV_CASE(2) CONFKV_CASE(3) CONFKV_CASE(4) CONFKV_CASE(5) CONFKV_CASE(6) CONFKV_CASE(7) CONFKV_CASE(8)
+      default: return nullptr;
+    }
+#undef CONFKV_CASE
+  }
   if (D != 128) return nullptr;
 #define CONFKV_CASE(g) \
   case g: return chan ? (AttendFn)attend_mfma_kernel<g, true, true> : (AttendFn)attend_mfma_kernel<g, false, true>;
@@ -1330,8 +1366,8 @@ static AttendFn attend_fn_mfma_spill(int D, int G, bool chan) {
 #undef CONFKV_CASE
 }
 
-// The matrix-core kernel serves every grouped-query shape at D = 128, FP16-only caches included
-// (at G >= 4 the vector-ALU body runs out of registers).
+// The matrix-core kernel serves every grouped-query shape, FP16-only caches included (at G >= 4
+// the vector-ALU body runs out of registers); at D = 64 it pads the head to its 128-channel tiles.
 static bool wants_mfma(int D, int G, bool /*has_int8*/) {
   return g_use_mfma && attend_fn_mfma(D, G, false) != nullptr;
 }
@@ -1342,7 +1378,7 @@ static size_t attend_lds_bytes(int D, int G, int S, bool mfma) {
   if (mfma) {
     const int NP = kAttWaves;
     size_t floats = (size_t)G * S + G + 2 + 2 * NP * G;
-    size_t tiles = std::max<size_t>((size_t)kAttWaves * kTileBytes, (size_t)NP * G * D * sizeof(float));
+    size_t tiles = std::max<size_t>((size_t)kAttWaves * kTileBytes, (size_t)NP * G * 128 * sizeof(float));
     return floats * sizeof(float) + (size_t)2 * G * sizeof(double) + tiles + 32;
   }
   size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + 2 * kAttWaves * G + G + 2;
@@ -1477,7 +1513,7 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
     const int rows2 = rows16 ? kChunkRows : cv.G;                   // query rows per unit
     if (rows16 && !plan.mfma) return hipErrorInvalidValue;
     AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, rows2, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
-    AttendFn second = attend_fn_spill(cv.D, rows2, true);
+    AttendFn second = plan.mfma && cv.D == 64 ? attend_fn_finish_padded(rows2) : attend_fn_spill(cv.D, rows2, true);
     if (!first || !second || !a.spill) return hipErrorInvalidValue;
     hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                        plan.stash_tokens);

@@ -113,6 +113,24 @@ def test_full_size_chunks(lib):
     ls.close()
 
 
+def test_full_size_grouped_heads_of_64_channels(lib):
+    """Eight query heads of 64 channels per kv-head (the shape of the 20B mixture-of-experts model
+    the paper evaluates) at the roofline workload's batch and length, 4 layers: the matrix-core
+    body with the head padded to its 128-channel tiles."""
+    wl = workload(1).scaled(name="b8_t4096_hq64_hkv8_d64", n_layers=4, n_q_heads=64, n_kv_heads=8, head_dim=64,
+                            n_tight=(1024,) * 4, n_loose=(2048,) * 4, steps=3, logit_std=(0.5, 6.0), logit_run=1)
+    print(f"64-channel grouped heads at full size: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=1, units=6, threads=16)
+    for t in range(wl.steps):
+        ls.step()
+        _invariants_all_units(ls, wl, t)
+        print(f"  step {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0 and rep.evictions > 0
+    ls.close()
+
+
 def test_full_size_observation_window(lib):
     """Importance from the prompt's own attention at the roofline workload's shape (4 of its
     layers): the last 32 prompt tokens observe the prompt in windows of 4 (the window ends inside

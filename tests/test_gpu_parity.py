@@ -206,6 +206,11 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_l
     (64, 3, 1, 1, 150, 10, 2),
     (64, 7, 1, 1, 97, -1, 0),
     (64, 4, 2, 1, 130, 100, 4),
+    (64, 8, 2, 2, 900, 48, 3),        # 64-channel heads in groups of eight (mixed INT8 / FP16), ragged splits
+    (64, 8, 1, 1, 2100, 128, 0),      # the same at the default plan of a longer unit
+    (64, 4, 2, 1, 777, -1, 5),        # 64-channel grouped heads, FP16-only
+    (64, 2, 1, 1, 300, 0, 2),
+    (64, 5, 1, 2, 411, 33, 1),
     (128, 4, 1, 1, 5, 2, 0),          # a tiny cache
     (128, 1, 1, 1, 0, 4, 0),          # empty cache: the query sees only itself
 ])
@@ -215,7 +220,8 @@ def test_attend_matches_oracle(lib, torch_cuda, D, G, H, B, T0, W, splits):
 
 @pytest.mark.parametrize("D,G,H,B,T0,W,splits", [
     (128, 4, 2, 2, 700, 32, 3), (128, 4, 1, 1, 300, 16, 1), (64, 1, 3, 1, 333, -1, 4),
-    (128, 5, 2, 1, 1000, 64, 7), (64, 2, 2, 2, 150, 0, 2), (128, 8, 1, 1, 520, 200, 5)])
+    (128, 5, 2, 1, 1000, 64, 7), (64, 2, 2, 2, 150, 0, 2), (128, 8, 1, 1, 520, 200, 5),
+    (64, 8, 2, 1, 800, 40, 4), (64, 4, 1, 2, 500, -1, 3)])
 def test_attend_two_launch_form(lib, torch_cuda, D, G, H, B, T0, W, splits):
     """The form used when the splits of a unit cannot all be resident: scores and partials go
     through scratch and a second kernel finishes.  Forced here on small shapes."""
