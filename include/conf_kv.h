@@ -59,7 +59,8 @@ typedef enum conf_kv_status {
 typedef struct conf_kv_config {
   int32_t n_layers;          /* L  >= 1                                                        */
   int32_t batch;             /* B  >= 1 sequences, all at the same decode position             */
-  int32_t n_q_heads;         /* Hq, a multiple of n_kv_heads; group G = Hq / Hkv in 1..8       */
+  int32_t n_q_heads;         /* Hq, a multiple of n_kv_heads; group G = Hq / Hkv in 1..8
+                                (1..16 at head_dim 128)                                        */
   int32_t n_kv_heads;        /* Hkv                                                            */
   int32_t head_dim;          /* D in {64, 128}                                                 */
   int32_t vocab;             /* V >= 2                                                         */
@@ -226,7 +227,8 @@ int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
  * neither seen nor changed.  Calls for consecutive windows first = s, s + tq, .. compose.
  * dev_out16: fp16 [B][tq][Hq][D] attention outputs of those queries, or NULL.
  * Allowed between conf_kv_load_prefill of the layer and its first conf_kv_attend
- * (CONF_KV_ERR_BAD_STATE otherwise), with max_chunk >= 2, 1 <= tq <= max_chunk and
+ * (CONF_KV_ERR_BAD_STATE otherwise), with max_chunk >= 2 (or a group of more than 8 heads, then
+ * tq = 1), 1 <= tq <= max(1, max_chunk) and
  * 0 <= first, first + tq <= T0 (CONF_KV_ERR_INVALID_ARG). */
 int conf_kv_observe(conf_kv_handle *h, int32_t layer, int32_t first, int32_t tq, const void *dev_q16,
                     void *dev_out16, conf_kv_stream stream);

@@ -104,7 +104,7 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   ScratchLayout s{};
   const size_t UPL = (size_t)c->batch * c->n_kv_heads, U = UPL * c->n_layers;
   const size_t G = c->n_q_heads / c->n_kv_heads, D = c->head_dim;
-  const size_t R = c->max_chunk > 1 ? (size_t)kChunkRows : G;   // query rows per unit in the exchange buffers
+  const size_t R = (c->max_chunk > 1 || G > 8) ? (size_t)kChunkRows : G;   // query rows per unit in the exchange buffers
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   s.conf_arrive = take((size_t)c->batch * 4);
@@ -287,8 +287,9 @@ static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan
   const int W = h->cfg.fp16_window;
   const int n16_ub = W < 0 ? n_ub : std::min(n_ub, observe ? W : W + tq);
   // a chunk runs on the matrix-core body with all 16 tile rows as query rows
-  const int rows = (tq > 1 || observe) ? kChunkRows : h->cv.G;
-  if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, tq > 1 || observe, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
+  const bool rows16 = tq > 1 || observe || h->cv.G > 8;
+  const int rows = rows16 ? kChunkRows : h->cv.G;
+  if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, rows16, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
                    h->forced_splits, h->force_two_launch, plan))
     return CONF_KV_ERR_BAD_SHAPE;
   return CONF_KV_OK;
@@ -304,7 +305,8 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
   if (tq < 1 || tq > std::max(1, h->cfg.max_chunk)) return CONF_KV_ERR_INVALID_ARG;
   if (observe) {
-    if (h->cfg.max_chunk < 2) return CONF_KV_ERR_INVALID_ARG;
+    // (the call runs on the 16-row kernel: the exchange buffers must have been sized for it)
+    if (h->cfg.max_chunk < 2 && h->cv.G <= 8) return CONF_KV_ERR_INVALID_ARG;
     if (h->appended[layer] || h->fresh_len[layer] < 0) return CONF_KV_ERR_BAD_STATE;
     if ((long long)observe_first + tq > h->fresh_len[layer]) return CONF_KV_ERR_INVALID_ARG;
   }

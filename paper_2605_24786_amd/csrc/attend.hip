@@ -1372,7 +1372,10 @@ static bool wants_mfma(int D, int G, bool /*has_int8*/) {
   return g_use_mfma && attend_fn_mfma(D, G, false) != nullptr;
 }
 
-bool attend_supported(int D, int G) { return attend_fn_valu(D, G) != nullptr; }
+// Groups of 9 to 16 query heads run as a one-token call of the 16-row matrix-core kernel (D = 128).
+bool attend_supported(int D, int G) {
+  return attend_fn_valu(D, G) != nullptr || (D == 128 && G > 8 && G <= kChunkRows);
+}
 
 static size_t attend_lds_bytes(int D, int G, int S, bool mfma) {
   if (mfma) {
@@ -1509,7 +1512,7 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                          hipStream_t stream) {
   dim3 grid(plan.splits, cv.Hkv, cv.B);
   if (plan.two_launch) {
-    const bool rows16 = a.tq > 1 || a.observe_first >= 0;
+    const bool rows16 = a.tq > 1 || a.observe_first >= 0 || cv.G > 8;
     const int rows2 = rows16 ? kChunkRows : cv.G;                   // query rows per unit
     if (rows16 && !plan.mfma) return hipErrorInvalidValue;
     AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, rows2, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
@@ -1522,7 +1525,7 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
                        plan.stash_tokens);
     return hipGetLastError();
   }
-  const bool rows16 = a.tq > 1 || a.observe_first >= 0;
+  const bool rows16 = a.tq > 1 || a.observe_first >= 0 || cv.G > 8;
   const int rows = rows16 ? kChunkRows : cv.G;
   if (rows16 && !plan.mfma) return hipErrorInvalidValue;
   AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, rows, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);

@@ -60,7 +60,7 @@ def test_buffer_sizes(clib):
     assert U * cap * (4 * D + 8) <= sb16 <= U * cap * (4 * D + 8) + 64 * 1024
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=18, n_kv_heads=2), dict(n_q_heads=7),
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(n_q_heads=34, n_kv_heads=2), dict(n_q_heads=18, n_kv_heads=2, head_dim=64), dict(n_q_heads=7),
                                  dict(capacity=100), dict(capacity=128), dict(vocab=1), dict(alpha=1.5),
                                  dict(n_tight=[200, 64]), dict(protected_window=-1), dict(n_layers=0),
                                  dict(ema_decay=-0.1), dict(mass_gain=float("nan")), dict(_ranker=2),

@@ -211,6 +211,9 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_l
     (64, 4, 2, 1, 777, -1, 5),        # 64-channel grouped heads, FP16-only
     (64, 2, 1, 1, 300, 0, 2),
     (64, 5, 1, 2, 411, 33, 1),
+    (128, 16, 1, 2, 900, 64, 3),      # sixteen query heads per kv-head: the 16-row kernel with one token
+    (128, 12, 2, 1, 500, 32, 0),      # twelve: four padding rows
+    (128, 9, 1, 1, 300, -1, 2),
     (128, 4, 1, 1, 5, 2, 0),          # a tiny cache
     (128, 1, 1, 1, 0, 4, 0),          # empty cache: the query sees only itself
 ])
@@ -221,7 +224,7 @@ def test_attend_matches_oracle(lib, torch_cuda, D, G, H, B, T0, W, splits):
 @pytest.mark.parametrize("D,G,H,B,T0,W,splits", [
     (128, 4, 2, 2, 700, 32, 3), (128, 4, 1, 1, 300, 16, 1), (64, 1, 3, 1, 333, -1, 4),
     (128, 5, 2, 1, 1000, 64, 7), (64, 2, 2, 2, 150, 0, 2), (128, 8, 1, 1, 520, 200, 5),
-    (64, 8, 2, 1, 800, 40, 4), (64, 4, 1, 2, 500, -1, 3)])
+    (64, 8, 2, 1, 800, 40, 4), (64, 4, 1, 2, 500, -1, 3), (128, 12, 1, 1, 700, 48, 3)])
 def test_attend_two_launch_form(lib, torch_cuda, D, G, H, B, T0, W, splits):
     """The form used when the splits of a unit cannot all be resident: scores and partials go
     through scratch and a second kernel finishes.  Forced here on small shapes."""
@@ -642,6 +645,24 @@ def test_evict_pages_ties_and_degenerate(lib, torch_cuda):
     a, _ = _page_case(lib, torch_cuda, 400, 200, 16, 32, 1, 0.65, ema, seed=3)
     b = _evict_case(lib, torch_cuda, 400, 200, 16, 32, 0.65, ema, seed=3)
     assert np.array_equal(a.pos, b.pos)
+
+
+def test_lockstep_wide_groups(lib, torch_cuda):
+    """Groups of twelve query heads per kv-head through decode steps with evictions and demotions,
+    and an observation window first (one query per call at this group size)."""
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=24, n_kv_heads=2, head_dim=128, vocab=2003, prefill=300,
+                         steps=16, n_tight=(150, 120), n_loose=(230, 200), protected=20, fp16_window=24,
+                         logit_std=(0.5, 6.0), logit_run=3)
+    say(f"lockstep G=12 capacity={wl.capacity}")
+    ls = Lockstep(lib, wl, seed=12)
+    for first in range(296, 300):
+        ls.observe(first, 1)
+    for t in range(wl.steps):
+        ls.step()
+    rep = ls.report
+    assert rep.ok(), rep.evict_flips
+    assert rep.evictions > 0 and ls.kv.counters().device_errors == 0
+    ls.close()
 
 
 @pytest.mark.parametrize("G,D,W,page,scope,tq", [(4, 128, 16, 16, "kv_head", 1), (1, 64, -1, 8, "kv_head", 1),
