@@ -214,6 +214,7 @@ def _attend_case(lib, torch, D, G, H, B, T0, W, splits, seed, scale_q=1.0, two_l
     (128, 16, 1, 2, 900, 64, 3),      # sixteen query heads per kv-head: the 16-row kernel with one token
     (128, 12, 2, 1, 500, 32, 0),      # twelve: four padding rows
     (128, 9, 1, 1, 300, -1, 2),
+    (128, 4, 1, 1, 36000, -1, 0),     # longer than any register-resident path assumes
     (128, 4, 1, 1, 5, 2, 0),          # a tiny cache
     (128, 1, 1, 1, 0, 4, 0),          # empty cache: the query sees only itself
 ])
@@ -697,7 +698,9 @@ def test_lockstep_page_eviction(lib, torch_cuda, G, D, W, page, scope, tq):
                                      (260, 100, 10, 150), (90, 200, 10, 16),
                                      # one to five slots over the budget: the one-wavefront ranking kernel
                                      (700, 699, 16, 32), (700, 698, 16, 32), (1300, 1297, 8, 64),
-                                     (2100, 2096, 128, 64), (640, 635, 16, 700), (3000, 2998, 64, -1)])
+                                     (2100, 2096, 128, 64), (640, 635, 16, 700), (3000, 2998, 64, -1),
+                                     # above 33 792 slots the scores live in scratch, not in registers
+                                     (36000, 20000, 128, -1), (34000, 33990, 64, -1)])
 def test_evict_random_ema(lib, torch_cuda, n, N, P, W):
     say(f"evict n={n} N={N} P={P} W={W}")
     rng = np.random.default_rng(n + N)
