@@ -27,7 +27,7 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-  size_t conf_partial, conf_arrive, arrive, part_ml, part_o, spill, score, src, sel, shared, total;
+  size_t conf_partial, conf_arrive, part_ml, part_o, spill, score, src, sel, shared, total;
   size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
 };
 
@@ -108,10 +108,10 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   s.conf_arrive = take((size_t)c->batch * 4);
-  s.arrive = take(U * kAttendMaxSplits * 4);
+  // epoch-tagged (m, l) words of the splits: tags start at 0, which no launch uses
+  s.part_ml = take(UPL * kAttendMaxSplits * R * 2 * 8);
   s.zero_bytes = off;
   s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
-  s.part_ml = take(UPL * kAttendMaxSplits * R * 2 * 4);
   // (the matrix-core body exchanges 128-channel partials whatever the head dimension)
   s.part_o = take(UPL * kAttendMaxSplits * R * std::max<size_t>(D, 128) * 4);
   s.spill = take(attend_spill_floats((int)UPL, (int)R, c->capacity) * 4);
@@ -139,7 +139,7 @@ struct conf_kv_handle {
   std::vector<uint8_t> appended;     // an append awaits its commit
   std::vector<uint8_t> scaled;       // per unit: channel scales were given (channel mode)
   std::vector<int32_t> fresh_len;    // per layer: T0 of a prompt no decode step has touched yet, else -1
-  std::vector<uint32_t> epoch;       // attend launches so far, per layer (arrival-flag value)
+  uint32_t epoch = 0;                // attend launches so far: the tag of the words a launch publishes
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
   int last_hip = 0;
@@ -188,7 +188,6 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->len_ub.assign(L, 0);
   h->next_pos.assign(L, 0);
   h->appended.assign(L, 0);
-  h->epoch.assign(L, 0u);
   h->scaled.assign((size_t)L * cfg->batch * cfg->n_kv_heads, 0);
   h->fresh_len.assign(L, -1);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
@@ -317,19 +316,21 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   AttendPlan plan;
   int rc = plan_for_layer(h, layer, tq, &plan, observe_first);
   if (rc != CONF_KV_OK) return rc;
-  const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
+  [[maybe_unused]] const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;   // phase-trace builds
   AttendLaunch a{};
   a.layer = layer;
   a.q = (const __half *)dev_q16;
   a.knew = (const __half *)dev_knew16;
   a.vnew = (const __half *)dev_vnew16;
   a.out = (__half *)dev_out16;
-  a.part_ml = (float *)(h->scratch + h->kl.part_ml);
+  a.part_ml = (unsigned long long *)(h->scratch + h->kl.part_ml);
   a.part_o = (float *)(h->scratch + h->kl.part_o);
   a.spill = (float *)(h->scratch + h->kl.spill);
-  a.arrive = (unsigned *)(h->scratch + h->kl.arrive) + (size_t)layer * UPL * kAttendMaxSplits;
-  if (++h->epoch[layer] == 0u) h->epoch[layer] = 1u;     // flags start at 0: skip it on wrap
-  a.epoch = h->epoch[layer];
+  // One counter for the handle: the tagged words are shared by the layers, so a launch must not
+  // meet a tag a launch on another layer left.  (A wrap after 2^32 launches would need a word
+  // untouched for exactly that long to be misread; 0 is skipped because the words start at 0.)
+  if (++h->epoch == 0u) h->epoch = 1u;
+  a.epoch = h->epoch;
   a.max_splits = kAttendMaxSplits;
   a.sm_scale = h->cfg.sm_scale;
   a.ema_decay = h->cfg.ema_decay;

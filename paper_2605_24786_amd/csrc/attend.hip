@@ -90,6 +90,15 @@ __device__ __forceinline__ float ld_agent(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0); }
+// A float that travels with the epoch of the launch that wrote it: one 8-byte word, so a
+// reader sees value and tag together or neither.
+__device__ __forceinline__ void st_tagged(unsigned long long *p, unsigned epoch, float v) {
+  __hip_atomic_store(p, ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(v),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_tagged(const unsigned long long *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // LDS traffic between lanes of one wavefront: LDS operations of a wavefront execute in
 // program order, so a compiler-level barrier is all that is needed between a write phase
@@ -427,28 +436,41 @@ __device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, fl
   }
 }
 
-// Arrival: every split owns one flag word and stores the launch's epoch into it; nobody does a
-// read-modify-write, so arrivals do not serialise at the memory side.  The first wavefront
-// polls all flags of the unit with one coherent load per round.  The wait is bounded; false
-// means it expired (counted as a device error).  Contains workgroup barriers.
-__device__ __forceinline__ bool arrive_and_wait(const CacheView &cv, const AttendLaunch &a,
-                                                const Slice &sl, int ns, int *s_ok) {
+// Arrival and the gather of the softmax statistics in one: every split publishes its (m, l)
+// per head as words tagged with the launch's epoch -- after its output partial is complete in
+// memory -- and thread k polls word k of the unit until the tag is this launch's, then drops
+// the value into LDS.  Seeing a split's words therefore means its output partial may be read.
+// Nobody does a read-modify-write, so arrivals do not serialise at the memory side.  The wait
+// is bounded; false means it expired (counted as a device error).  Contains a workgroup
+// barrier; *s_ok must have been set to 1 before the barrier that precedes the call.
+template <int G>
+__device__ __forceinline__ bool collect_ml(const CacheView &cv, const AttendLaunch &a, const Slice &sl,
+                                           int ns, float *pml, int *s_ok) {
   const int tid = threadIdx.x;
-  unsigned *flags = a.arrive + (size_t)sl.ul * a.max_splits;
-  if (tid == 0) __hip_atomic_store(&flags[sl.j], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (tid < kWave) {
-    int ok = 1, spins = 0;
+  const unsigned long long *words = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
+  for (int base = 0; base < ns * G * 2; base += kAttThreads) {
+    const int idx = base + tid;
+    const bool mine = idx < ns * G * 2;
+    bool here = !mine;
+    int spins = 0;
     for (;;) {
-      const bool here = tid >= ns || __hip_atomic_load(&flags[tid], __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+      if (!here) {
+        const unsigned long long wv = ld_tagged(&words[idx]);
+        if ((unsigned)(wv >> 32) == a.epoch) {
+          pml[idx] = __uint_as_float((unsigned)wv);
+          here = true;
+        }
+      }
       if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
       __builtin_amdgcn_s_sleep(1);
-      if (++spins > kSpinLimit) { ok = 0; break; }
+      if (++spins > kSpinLimit) {
+        if (!here) *s_ok = 0;
+        break;
+      }
     }
-    if (!ok && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
-    if (tid == 0) *s_ok = ok;
   }
   __syncthreads();
+  if (*s_ok == 0 && tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
   return *s_ok != 0;
 }
 
@@ -489,7 +511,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const float NEG = -INFINITY;
   // more than 8 rows only occur in multi-token calls; otherwise rows are the heads of one token
   const int tq = G > 8 ? a.tq : 1, gq = G > 8 ? a.gq : G;
-  float *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
+  unsigned long long *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
   float *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
   // the EMA values this thread will update: requested now, needed after the wait
   constexpr int kPre = kPhase == 0 ? 4 : 0;
@@ -544,10 +566,10 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
     } else {
       st_agent2(&po[idx], o0, o1);
-      if (idx % D == 0) st_agent2(&ml[h * 2], M, l);
+      // (m, l) wait in LDS: they go out after the output partial has landed
+      if (idx % D == 0) { gm[h] = M; ((float *)ginv)[h] = l; }
     }
   }
-  const float *mlu = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
   const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
   float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
   // Output merge: this split normalises `per` elements of the unit's [G][D] output.  The ns
@@ -561,22 +583,32 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const int os = tid % gs, oe = tid / gs;            // this thread's split and element within a pass
   float opre = 0.f;
   TS(19);
+  if (exchange && kPhase != 2) {
+    // the output partial is complete in memory before the tagged (m, l) can be seen
+    if (tid == 0) *s_ok = 1;
+    wait_stores_done();
+    __syncthreads();
+    TS(20);
+    if (tid < G) {
+      st_tagged(&ml[tid * 2], a.epoch, gm[tid]);
+      st_tagged(&ml[tid * 2 + 1], a.epoch, ((const float *)ginv)[tid]);
+    }
+  }
   if (kPhase == 1) return;
   if (exchange) {
     if (kPhase == 0) {
-      wait_stores_done();
-      __syncthreads();
-      TS(20);
-      if (!arrive_and_wait(cv, a, sl, ns, s_ok)) return;
+      if (!collect_ml<G>(cv, a, sl, ns, pml, s_ok)) return;
       TS(21);
+    } else {
+      // second launch: every word of the unit was written by the first one
+      const unsigned long long *words = a.part_ml + (size_t)sl.ul * a.max_splits * G * 2;
+      for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = __uint_as_float((unsigned)ld_tagged(&words[idx]));
+      __syncthreads();
     }
-
-    // ---- one round trip: all (m, l) partials of the unit -> LDS, and this split's share of
-    // the unit's output partials -> registers ----
+    // this split's share of the unit's output partials -> registers, needed only after the
+    // importance update: the round trip runs behind it
     if (os < ns && oe < per && sl.j * per + oe < G * D)
       opre = ld_agent(&pou[(size_t)os * G * D + sl.j * per + oe]);
-    for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = ld_agent(&mlu[idx]);
-    __syncthreads();
     // global (M, L) of head h by wavefront h: one lane per split
     for (int h = tid >> 6; h < G; h += kAttWaves) {
       const int sp = tid & 63;

@@ -30,10 +30,9 @@ struct AttendLaunch {
   int layer;
   const __half *q, *knew, *vnew;
   __half *out;
-  float *part_ml;          // [units per layer][max splits][G][2]
+  unsigned long long *part_ml;   // [units per layer][max splits][G][2] words: (epoch << 32) | float bits of m, of l
   float *part_o;           // [units per layer][max splits][G][D]
-  unsigned *arrive;        // [units per layer][max splits] arrival flags of this layer
-  unsigned epoch;          // value a split stores into its flag in this launch (never 0)
+  unsigned epoch;          // tag of the words published in this launch (never 0, never reused by a later one)
   int max_splits;
   float sm_scale, ema_decay;
   double mass_gain;        // weight of the step's mass in the EMA update
