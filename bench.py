@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per conf_kv_attend launch on the default workload from hardware counters
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scale factors from a plain 1 GiB copy); the runs and
 # readings are in profiles/bench_llama3_8b_b8_t4096_hbm_counters.txt.  None for other workloads.
-COUNTER_TRAFFIC_BYTES = {1: int((35435.0 * 2.0 + 1676.0) * 1024)}
+COUNTER_TRAFFIC_BYTES = {1: int((35433.8 * 2.0 + 1668.0) * 1024)}
 
 
 def attend_bytes_per_launch(wl, n8, n16):
