@@ -144,7 +144,9 @@ typedef struct conf_kv_stats {
  * needed in normal use): CONF_KV_SPLITS=n asks for n workgroups per unit in conf_kv_attend
  * instead of the planned number (clamped to what the unit's length allows);
  * CONF_KV_TWO_LAUNCH=1 forces the two-launch form of conf_kv_attend; CONF_KV_NO_MFMA=1 (read
- * at the first plan of the process) keeps every shape on the vector-ALU streaming body. */
+ * at the first plan of the process) keeps every shape on the vector-ALU streaming body;
+ * CONF_KV_COMPACT_PAIRED=0/1 (read at every conf_kv_evict_compact) forces one of the two grid
+ * shapes of the compaction kernel, which is otherwise chosen by the number of units. */
 
 /* Bytes of device memory the caller must provide for the cache state and for scratch
  * (split partials, arrival counters, ranking work arrays).  0 on an invalid config. */

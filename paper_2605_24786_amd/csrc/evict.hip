@@ -932,24 +932,30 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
 }
 
 // ---------------------------------------------------------------------------------------
-// compact: grid (U, 5 planes), 256 threads.  Survivor j (new slot number) comes from old slot
+// compact: grid (U, 2) or (U, 5), 256 threads.  Survivor j (new slot number) comes from old slot
 // src[j] >= j.  Left shift (heads stay): a workgroup walks its plane front to back in chunks
 // (load a chunk into registers, barrier, store); earlier chunks only wrote below the chunk
 // start and later sources all lie at or above it, so nothing is overwritten before it is
 // read.  Right shift (the head of the slot-anchored rings advances by the evictions e):
 // survivor j moves from ring offset src[j] to offset e + j >= src[j], only the survivors in
 // front of the last hole move, and the walk goes back to front; the mirror argument holds.
-// planes: 0 = K INT8 rows, 1 = V INT8 rows, 2 = scales + EMA + position, 3 = K FP16 rows,
-// 4 = V FP16 rows.
+// Paired form, grid (U, 2), for thousands of units: workgroup 0 of a unit moves the K and V
+// rows of the ring the holes lie in, together (one look-up of the sources serves both);
+// workgroup 1 moves scales, EMA and position, and then, in a mixed cache, the FP16 rows in the
+// rare case that an FP16 slot was evicted.  Most units move a handful of rows there, so the
+// kernel's time is workgroups times round trips.  With fewer units every plane gets a workgroup
+// of its own, grid (U, 5): 0 = K INT8 rows, 1 = V INT8 rows, 2 = scales + EMA + position,
+// 3 = K FP16 rows, 4 = V FP16 rows.
 // ---------------------------------------------------------------------------------------
 
-// One plane's rows, ROWB bytes each: destination slots [lo, hi) in walk order `right`.
-// srow(s) gives the ring row of old slot s, drow(j) that of new slot j.  Loads are grouped
-// (source slots of all passes, then all rows), so a chunk costs two memory round trips;
-// lanes past the range issue nothing (most units move a handful of rows).
+// The rows of one plane, or of two with the same row size and ring (K and V; base2 = null:
+// one), ROWB bytes each:
+// destination slots [lo, hi) in walk order `right`.  srow(s) gives the ring row of old slot s,
+// drow(j) that of new slot j.  Loads are grouped (source slots of all passes, then all rows of
+// both planes), so a chunk costs two memory round trips; lanes past the range issue nothing.
 template <int ROWB, typename SrcRow, typename DstRow>
-__device__ __forceinline__ void move_rows(uint8_t *base_ptr, const int32_t *__restrict__ src, int lo, int hi,
-                                          bool right, SrcRow srow, DstRow drow) {
+__device__ __forceinline__ void move_rows(uint8_t *base_ptr, uint8_t *base2, const int32_t *__restrict__ src,
+                                          int lo, int hi, bool right, SrcRow srow, DstRow drow) {
   constexpr int LPR = ROWB / 16, RPP = kEvThreads / LPR, PASSES = 4;
   const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
   const int cnt = hi - lo;
@@ -958,7 +964,7 @@ __device__ __forceinline__ void move_rows(uint8_t *base_ptr, const int32_t *__re
     // through scratch memory
     const int k0 = done + r0, k1 = k0 + RPP, k2 = k1 + RPP, k3 = k2 + RPP;   // k-th slots of the walk
     int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
-    int4 b0, b1, b2, b3;
+    int4 b0, b1, b2, b3, c0, c1, c2, c3;
     if (k0 < cnt) f0 = src[right ? hi - 1 - k0 : lo + k0];
     if (k1 < cnt) f1 = src[right ? hi - 1 - k1 : lo + k1];
     if (k2 < cnt) f2 = src[right ? hi - 1 - k2 : lo + k2];
@@ -967,19 +973,34 @@ __device__ __forceinline__ void move_rows(uint8_t *base_ptr, const int32_t *__re
     if (k1 < cnt) b1 = *(const int4 *)(base_ptr + (size_t)srow(f1) * ROWB + c * 16);
     if (k2 < cnt) b2 = *(const int4 *)(base_ptr + (size_t)srow(f2) * ROWB + c * 16);
     if (k3 < cnt) b3 = *(const int4 *)(base_ptr + (size_t)srow(f3) * ROWB + c * 16);
+    if (base2 && k0 < cnt) c0 = *(const int4 *)(base2 + (size_t)srow(f0) * ROWB + c * 16);
+    if (base2 && k1 < cnt) c1 = *(const int4 *)(base2 + (size_t)srow(f1) * ROWB + c * 16);
+    if (base2 && k2 < cnt) c2 = *(const int4 *)(base2 + (size_t)srow(f2) * ROWB + c * 16);
+    if (base2 && k3 < cnt) c3 = *(const int4 *)(base2 + (size_t)srow(f3) * ROWB + c * 16);
     __syncthreads();
     if (k0 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k0 : lo + k0) * ROWB + c * 16) = b0;
     if (k1 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k1 : lo + k1) * ROWB + c * 16) = b1;
     if (k2 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k2 : lo + k2) * ROWB + c * 16) = b2;
     if (k3 < cnt) *(int4 *)(base_ptr + (size_t)drow(right ? hi - 1 - k3 : lo + k3) * ROWB + c * 16) = b3;
+    if (base2 && k0 < cnt) *(int4 *)(base2 + (size_t)drow(right ? hi - 1 - k0 : lo + k0) * ROWB + c * 16) = c0;
+    if (base2 && k1 < cnt) *(int4 *)(base2 + (size_t)drow(right ? hi - 1 - k1 : lo + k1) * ROWB + c * 16) = c1;
+    if (base2 && k2 < cnt) *(int4 *)(base2 + (size_t)drow(right ? hi - 1 - k2 : lo + k2) * ROWB + c * 16) = c2;
+    if (base2 && k3 < cnt) *(int4 *)(base2 + (size_t)drow(right ? hi - 1 - k3 : lo + k3) * ROWB + c * 16) = c3;
   }
 }
 
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
                                                              const int32_t *__restrict__ src_all,
-                                                             const int32_t *__restrict__ sel_all) {
-  const int u = blockIdx.x, plane = blockIdx.y, tid = threadIdx.x;
+                                                             const int32_t *__restrict__ sel_all, int paired) {
+  const int u = blockIdx.x, tid = threadIdx.x;
+  // what this workgroup moves: the payload rows of the ring the holes lie in (K, V or both),
+  // the per-slot planes, the FP16 rows of a mixed cache (K, V or both)
+  const int y = blockIdx.y;
+  const bool do_k = paired ? y == 0 : (y == 0 || y == 3), do_v = paired ? y == 0 : (y == 1 || y == 4);
+  const bool do_meta = paired ? y == 1 : y == 2;
+  const bool late16 = paired ? y == 1 : y >= 3;     // FP16 rows of a mixed cache
+  const bool main_rows = paired ? y == 0 : y <= 1;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
   const int n_new = sel[0], n8_new = sel[1], hole = sel[2], evicted = sel[3];
   if (hole >= n_new) return;                          // nothing moves
@@ -992,13 +1013,28 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
   const int jr = sel[4] + 1 - (fp16_only ? evicted : e8);   // right shift: survivors [0, jr) move
   const int h0_new = sel[6];
 
-  if (plane <= 1) {
-    if (fp16_only) return;
-    uint8_t *base_ptr = (uint8_t *)((plane == 0 ? cv.k8 : cv.v8) + (size_t)u * cap8 * D);
-    move_rows<D>(base_ptr, src, right ? 0 : hole, right ? jr : n8_new, right,
+  // FP16 ring rows.  Mixed cache: they only move (left) when an FP16 slot was evicted.
+  // FP16-only cache: either side.
+  auto move_fp16_rows = [&](bool k, bool v) {
+    const int h16_new = (fp16_only && right) ? ring_row(h16, evicted, cap16) : h16;
+    uint8_t *pk = (uint8_t *)(cv.k16 + (size_t)u * cap16 * D), *pv = (uint8_t *)(cv.v16 + (size_t)u * cap16 * D);
+    move_rows<2 * D>(k ? pk : pv, (k && v) ? pv : nullptr, src,
+                     right ? 0 : max(hole, n8_new), right ? jr : n_new, right,
+                     [&](int s) { return ring_row(h16, s - n8_old, cap16); },
+                     [&](int j) { return ring_row(h16_new, j - n8_new, cap16); });
+  };
+  if (fp16_only) {
+    // the FP16 ring is the ring the holes lie in: its rows are the main rows (planes 3 and 4
+    // of the unpaired form)
+    if (paired ? y == 0 : y >= 3) move_fp16_rows(paired || y == 3, paired || y == 4);
+  } else if (main_rows) {
+    uint8_t *pk = (uint8_t *)(cv.k8 + (size_t)u * cap8 * D), *pv = (uint8_t *)(cv.v8 + (size_t)u * cap8 * D);
+    move_rows<D>(do_k ? pk : pv, (do_k && do_v) ? pv : nullptr, src,
+                 right ? 0 : hole, right ? jr : n8_new, right,
                  [&](int s) { return ring_row(h0, s, cap8); },
                  [&](int j) { return ring_row(h0_new, j, cap8); });
-  } else if (plane == 2) {
+  }
+  if (do_meta) {
     // per-slot planes: EMA and position for every moving slot, scales for the INT8 ones
     // (same ring offsets: cap8 = cap in a mixed cache)
     float *ema = cv.ema + (size_t)u * cap;
@@ -1046,16 +1082,8 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
         }
       }
     }
-  } else {
-    // FP16 ring rows.  Mixed cache: they only move (left) when an FP16 slot was evicted.
-    // FP16-only cache: either side.
-    if (!fp16_only && evicted == e8) return;
-    uint8_t *base_ptr = (uint8_t *)((plane == 3 ? cv.k16 : cv.v16) + (size_t)u * cap16 * D);
-    const int h16_new = (fp16_only && right) ? ring_row(h16, evicted, cap16) : h16;
-    move_rows<2 * D>(base_ptr, src, right ? 0 : max(hole, n8_new), right ? jr : n_new, right,
-                     [&](int s) { return ring_row(h16, s - n8_old, cap16); },
-                     [&](int j) { return ring_row(h16_new, j - n8_new, cap16); });
   }
+  if (!fp16_only && late16 && evicted != e8) move_fp16_rows(paired || y == 3, paired || y == 4);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1142,11 +1170,15 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
   }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
+  // measured: with 8192 units the paired form saves 6 us per step, with 2048 and fewer the
+  // workgroup per plane is 3 to 4 us faster
+  int paired = U >= 4096;
+  if (const char *e = getenv("CONF_KV_COMPACT_PAIRED")) paired = atoi(e) != 0;   // test hook: force a form
   if (cv.D == 64) {
-    hipLaunchKernelGGL(compact_kernel<64>, dim3(U, 5), dim3(kEvThreads), 0, stream, cv, src, sel);
+    hipLaunchKernelGGL(compact_kernel<64>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
   } else {
-    hipLaunchKernelGGL(compact_kernel<128>, dim3(U, 5), dim3(kEvThreads), 0, stream, cv, src, sel);
+    hipLaunchKernelGGL(compact_kernel<128>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
   }
   return hipGetLastError();

@@ -648,6 +648,29 @@ def test_evict_pages_ties_and_degenerate(lib, torch_cuda):
     assert np.array_equal(a.pos, b.pos)
 
 
+@pytest.mark.parametrize("paired", [0, 1])
+@pytest.mark.parametrize("G,D,W,N", [(4, 128, 16, (150, 230)), (1, 64, -1, (150, 230)), (2, 128, 120, (60, 100))])
+def test_lockstep_both_compaction_forms(lib, torch_cuda, paired, G, D, W, N):
+    """The compaction kernel has a form with one workgroup per plane and one that pairs K with V
+    (chosen by the unit count); both are forced here on the same runs, the third of which evicts
+    FP16 slots (the FP16 window is wider than the budgets)."""
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=D, vocab=2003, prefill=260,
+                         steps=24, n_tight=(N[0],) * 2, n_loose=(N[1],) * 2, protected=20, fp16_window=W,
+                         alpha=0.5, logit_std=(0.5, 6.0), logit_run=4)
+    say(f"lockstep compaction form paired={paired} G={G} D={D} W={W} N={N}")
+    os.environ["CONF_KV_COMPACT_PAIRED"] = str(paired)
+    try:
+        ls = Lockstep(lib, wl, seed=21)
+        for t in range(wl.steps):
+            ls.step()
+        rep = ls.report
+        assert rep.ok(), rep.evict_flips
+        assert rep.evictions > 0 and rep.tight_steps > 0 and ls.kv.counters().device_errors == 0
+        ls.close()
+    finally:
+        os.environ.pop("CONF_KV_COMPACT_PAIRED", None)
+
+
 def test_lockstep_wide_groups(lib, torch_cuda):
     """Groups of twelve query heads per kv-head through decode steps with evictions and demotions,
     and an observation window first (one query per call at this group size)."""
