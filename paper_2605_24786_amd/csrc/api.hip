@@ -27,7 +27,7 @@ struct StateLayout {
 };
 
 struct ScratchLayout {
-  size_t conf_partial, conf_arrive, part_ml, part_o, spill, score, src, sel, shared, total;
+  size_t conf_partial, part_ml, part_o, spill, score, src, sel, shared, total;
   size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
 };
 
@@ -107,11 +107,10 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   const size_t R = (c->max_chunk > 1 || G > 8) ? (size_t)kChunkRows : G;   // query rows per unit in the exchange buffers
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-  s.conf_arrive = take((size_t)c->batch * 4);
+  s.conf_partial = take(conf_reduce_scratch_bytes(c->batch, c->vocab));
   // epoch-tagged (m, l) words of the splits: tags start at 0, which no launch uses
   s.part_ml = take(UPL * kAttendMaxSplits * R * 2 * 8);
   s.zero_bytes = off;
-  s.conf_partial = take(conf_reduce_scratch_floats(c->batch, c->vocab) * 4);
   // (the matrix-core body exchanges 128-channel partials whatever the head dimension)
   s.part_o = take(UPL * kAttendMaxSplits * R * std::max<size_t>(D, 128) * 4);
   s.spill = take(attend_spill_floats((int)UPL, (int)R, c->capacity) * 4);
@@ -140,6 +139,7 @@ struct conf_kv_handle {
   std::vector<uint8_t> scaled;       // per unit: channel scales were given (channel mode)
   std::vector<int32_t> fresh_len;    // per layer: T0 of a prompt no decode step has touched yet, else -1
   uint32_t epoch = 0;                // attend launches so far: the tag of the words a launch publishes
+  uint32_t conf_epoch = 0;           // the same for conf_kv_step
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
   int last_hip = 0;
@@ -388,9 +388,10 @@ int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
 int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
                  conf_kv_stream stream) {
   if (!h || !dev_logits) return CONF_KV_ERR_INVALID_ARG;
+  if (++h->conf_epoch == 0u) h->conf_epoch = 1u;         // the partial words start at tag 0
   CK_HIP(h, launch_conf_reduce(h->cv, dev_logits, h->cfg.vocab,
-                               (float *)(h->scratch + h->kl.conf_partial),
-                               (unsigned *)(h->scratch + h->kl.conf_arrive), dev_conf, dev_sel,
+                               (unsigned long long *)(h->scratch + h->kl.conf_partial),
+                               h->conf_epoch, dev_conf, dev_sel,
                                (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
                                (double)h->cfg.w_top, (hipStream_t)stream));
   return CONF_KV_OK;

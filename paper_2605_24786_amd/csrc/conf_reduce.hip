@@ -3,9 +3,12 @@
 //
 // One launch: grid (chunks, B).  A workgroup reduces one 4096-logit chunk of one sequence
 // to (max, sum e^{x-max}, sum (x-max) e^{x-max}, top-1, top-2) with the chunk held in
-// registers, publishes it, and the last workgroup to arrive for a sequence merges the
+// registers and publishes it as words tagged with the call's epoch; the workgroup of the
+// sequence's last chunk waits (bounded) until every chunk's words carry that tag, merges the
 // chunk partials in float64, evaluates Eq. 1 and writes c, the tight/loose flag and the
-// per-layer budgets.  HBM traffic is one read of the logits (4 B per logit).
+// per-layer budgets.  Nobody does a read-modify-write: a ticket counter per sequence made the
+// 32 arrivals of a row queue up at one address.  HBM traffic is one read of the logits
+// (4 B per logit).
 #include "confkv_dev.h"
 #include "launch.h"
 
@@ -14,13 +17,21 @@ namespace confkv {
 constexpr int kConfThreads = 256;
 constexpr int kConfPerThread = 16;
 constexpr int kConfChunk = kConfThreads * kConfPerThread;   // 4096 logits per workgroup
-constexpr int kPartialStride = 8;                           // floats per chunk partial
+constexpr int kPartialStride = 8;                           // 8-byte words per chunk partial (5 in use)
+constexpr int kConfSpinLimit = 400000;                      // polls before the merger gives up (about 0.4 s)
 
-__device__ __forceinline__ void st_coherent(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// A float with the epoch of the call that wrote it in one 8-byte word: value and tag are seen
+// together or not at all.  Agent-scope relaxed atomics are coherent across the XCDs by
+// themselves, so no cache-wide fence is needed.
+__device__ __forceinline__ void st_tagged(unsigned long long *p, unsigned epoch, float v) {
+  __hip_atomic_store(p, ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(v),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float ld_coherent(const float *p) {
+__device__ __forceinline__ unsigned long long ld_word(const unsigned long long *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const unsigned long long *p) {   // the value half
+  return __uint_as_float((unsigned)ld_word(p));
 }
 
 __device__ __forceinline__ void top2_merge(float &a1, float &a2, float b1, float b2) {
@@ -31,12 +42,12 @@ __device__ __forceinline__ void top2_merge(float &a1, float &a2, float b1, float
 }
 
 __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
-    const float *__restrict__ logits, int V, int nchunk, float *__restrict__ partial,
-    unsigned *__restrict__ arrive, float *__restrict__ conf, uint8_t *__restrict__ sel,
+    const float *__restrict__ logits, int V, int nchunk, unsigned long long *__restrict__ partial,
+    unsigned epoch, float *__restrict__ conf, uint8_t *__restrict__ sel,
     CacheView cv, double tau, double wH, double wm, double wp) {
   __shared__ float s_f[4 * 4];
   __shared__ double s_d[4 * 2];
-  __shared__ int s_last;
+  __shared__ int s_ok;
   const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const float *row = logits + (size_t)b * V;
@@ -84,27 +95,44 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   if (lane == 0) { s_f[8 + w] = S; s_f[12 + w] = T; }
   __syncthreads();
   if (tid == 0) {
-    float *p = partial + ((size_t)b * nchunk + c) * kPartialStride;
-    // agent-scope relaxed atomics are coherent across the XCDs by themselves; the stores
-    // are complete before the ticket is taken, and the last arrival loads them the same
-    // way, so no cache-wide fence is needed
-    st_coherent(&p[0], mx);
-    st_coherent(&p[1], (s_f[8] + s_f[9]) + (s_f[10] + s_f[11]));
-    st_coherent(&p[2], (s_f[12] + s_f[13]) + (s_f[14] + s_f[15]));
-    st_coherent(&p[3], v1);
-    st_coherent(&p[4], v2);
-    __builtin_amdgcn_s_waitcnt(0);
-    unsigned ticket = __hip_atomic_fetch_add(&arrive[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (ticket == (unsigned)(nchunk - 1));
+    unsigned long long *p = partial + ((size_t)b * nchunk + c) * kPartialStride;
+    st_tagged(&p[0], epoch, mx);
+    st_tagged(&p[1], epoch, (s_f[8] + s_f[9]) + (s_f[10] + s_f[11]));
+    st_tagged(&p[2], epoch, (s_f[12] + s_f[13]) + (s_f[14] + s_f[15]));
+    st_tagged(&p[3], epoch, v1);
+    st_tagged(&p[4], epoch, v2);
+    s_ok = 1;
+  }
+  if (c != nchunk - 1) return;
+
+  // ---- workgroup of the sequence's last chunk (every other chunk was dispatched before it):
+  // wait for the words of all chunks, then merge the chunk partials in float64 ----
+  const unsigned long long *pb = partial + (size_t)b * nchunk * kPartialStride;
+  __syncthreads();                                  // s_ok is set
+  for (int base = 0; base < nchunk * 5; base += kConfThreads) {
+    const int i = base + tid;
+    const bool mine = i < nchunk * 5;
+    const unsigned long long *wp_ = pb + (size_t)(mine ? i / 5 : 0) * kPartialStride + (mine ? i % 5 : 0);
+    bool here = !mine;
+    int spins = 0;
+    for (;;) {
+      if (!here) here = (unsigned)(ld_word(wp_) >> 32) == epoch;
+      if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
+      __builtin_amdgcn_s_sleep(1);
+      if (++spins > kConfSpinLimit) {
+        if (!here) s_ok = 0;
+        break;
+      }
+    }
   }
   __syncthreads();
-  if (!s_last) return;
-
-  // ---- last workgroup of this sequence: merge the chunk partials in float64 ----
-  const float *pb = partial + (size_t)b * nchunk * kPartialStride;
+  if (!s_ok) {                                      // a chunk never arrived: no budgets are written
+    if (tid == 0) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+    return;
+  }
   float M = NEG, t1 = NEG, t2 = NEG;
   for (int k = tid; k < nchunk; k += kConfThreads) {
-    const float *p = pb + (size_t)k * kPartialStride;
+    const unsigned long long *p = pb + (size_t)k * kPartialStride;
     M = fmaxf(M, ld_coherent(&p[0]));
     top2_merge(t1, t2, ld_coherent(&p[3]), ld_coherent(&p[4]));
   }
@@ -124,7 +152,7 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
 
   double Sd = 0.0, Td = 0.0;
   for (int k = tid; k < nchunk; k += kConfThreads) {
-    const float *p = pb + (size_t)k * kPartialStride;
+    const unsigned long long *p = pb + (size_t)k * kPartialStride;
     const float mk = ld_coherent(&p[0]), sk = ld_coherent(&p[1]), tk = ld_coherent(&p[2]);
     if (mk > NEG) {
       double shift = (double)mk - (double)M;       // <= 0
@@ -153,7 +181,6 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     if (sel) sel[b] = (uint8_t)tight;
     s_tight = tight;
     atomicAdd(&cv.stats[tight ? kStatTight : kStatLoose], 1ull);
-    __hip_atomic_store(&arrive[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
   const int tight = s_tight;
@@ -161,18 +188,18 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     cv.budget[l * cv.B + b] = tight ? cv.n_tight[l] : cv.n_loose[l];
 }
 
-size_t conf_reduce_scratch_floats(int B, int V) {
+size_t conf_reduce_scratch_bytes(int B, int V) {
   int nchunk = (V + kConfChunk - 1) / kConfChunk;
-  return (size_t)B * nchunk * kPartialStride;
+  return (size_t)B * nchunk * kPartialStride * 8;
 }
 
-hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, float *partial,
-                              unsigned *arrive, float *conf, uint8_t *sel, double tau, double wH,
+hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
+                              unsigned epoch, float *conf, uint8_t *sel, double tau, double wH,
                               double wm, double wp, hipStream_t stream) {
   int nchunk = (V + kConfChunk - 1) / kConfChunk;
   dim3 grid(nchunk, cv.B);
   hipLaunchKernelGGL(conf_reduce_kernel, grid, dim3(kConfThreads), 0, stream, logits, V, nchunk,
-                     partial, arrive, conf, sel, cv, tau, wH, wm, wp);
+                     partial, epoch, conf, sel, cv, tau, wH, wm, wp);
   return hipGetLastError();
 }
 

@@ -10,9 +10,9 @@
 namespace confkv {
 
 // ---- conf_reduce.hip ----
-size_t conf_reduce_scratch_floats(int B, int V);
-hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, float *partial,
-                              unsigned *arrive, float *conf, uint8_t *sel, double tau, double wH,
+size_t conf_reduce_scratch_bytes(int B, int V);   // epoch-tagged chunk partials: zero before the first call
+hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
+                              unsigned epoch /* never 0, never reused */, float *conf, uint8_t *sel, double tau, double wH,
                               double wm, double wp, hipStream_t stream);
 
 // ---- probe.hip ----
