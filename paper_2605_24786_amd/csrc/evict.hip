@@ -540,6 +540,25 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
 // kept slot lands at base(round, wavefront) + its rank inside the ballot.  Same arithmetic
 // and same decisions as rank_select_kernel; used whenever the longest unit fits (n <= T * E).
 // ---------------------------------------------------------------------------------------
+// The per-unit words a ranking kernel starts from -- length, INT8 count, ring head, budget and
+// the unit's "settled" mark -- in ONE memory round trip: lanes 0..4 of a wavefront read one
+// word each with a single load (as separate scalar loads the compiler strings them out between
+// the kernel-argument fetches, each waiting for the one before).
+struct UnitWords { int len, n8, head, budget, settled; };
+__device__ __forceinline__ UnitWords load_unit_words(const CacheView &cv, const int32_t *sel, int u, int layer, int b) {
+  const int k = threadIdx.x & 7;
+  const int32_t *p = k == 0 ? cv.len + u : k == 1 ? cv.n8 + u : k == 2 ? cv.head8 + u
+                   : k == 3 ? cv.budget + (layer * cv.B + b) : sel + 7;
+  const int v = *p;
+  UnitWords w;
+  w.len = __builtin_amdgcn_readlane(v, 0);
+  w.n8 = __builtin_amdgcn_readlane(v, 1);
+  w.head = __builtin_amdgcn_readlane(v, 2);
+  w.budget = __builtin_amdgcn_readlane(v, 3);
+  w.settled = __builtin_amdgcn_readlane(v, 4);
+  return w;
+}
+
 __device__ __forceinline__ int lanes_below(unsigned long long m) {   // set bits of m below this lane
   return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0));
 }
@@ -560,13 +579,18 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves], s_last8[kRsWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int u = blockIdx.x;
+  // the kernel arguments of the prologue in one fetch
+  asm volatile("" ::"s"(cv.len), "s"(cv.n8), "s"(cv.head8), "s"(cv.budget), "s"(cv.ema), "s"(cv.pos), "s"(cv.B),
+               "s"(cv.Hkv), "s"(cv.P), "s"(cv.cap), "s"(cv.cap8), "s"(sel_all), "s"(src_all));
   const int UPL = cv.B * cv.Hkv;
   const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
-  const int n = cv.len[u] + appended.get(layer);
-  const int n8 = cv.n8[u];
-  const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
-  if (sel[7] != 0) return;                            // settled by rank_small_kernel
+  const int app = appended.get(layer);
+  const UnitWords uw = load_unit_words(cv, sel, u, layer, b);
+  if (uw.settled != 0) return;                        // settled by rank_small_kernel
+  const int n = uw.len + app;
+  const int n8 = uw.n8;
+  const int N = uw.budget;
   const int p_eff = min(cv.P, n);
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
@@ -576,7 +600,7 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
-  const int hm = cv.head8[u], cap = cv.cap;          // slot i of the per-slot planes: ring_row_u(hm, i, cap)
+  const int hm = uw.head, cap = cv.cap;              // slot i of the per-slot planes: ring_row_u(hm, i, cap)
   const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   int32_t *src = src_all + (size_t)u * cv.cap;
   const int Ed = (n + T - 1) / T;                   // rounds in use, <= E (checked by the host)
@@ -815,12 +839,16 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6);
   if (u >= U) return;
+  asm volatile("" ::"s"(cv.len), "s"(cv.n8), "s"(cv.head8), "s"(cv.budget), "s"(cv.ema), "s"(cv.pos), "s"(cv.B),
+               "s"(cv.Hkv), "s"(cv.P), "s"(cv.cap), "s"(cv.cap8), "s"(sel_all), "s"(src_all));
   const int UPL = cv.B * cv.Hkv;
   const int layer = u / UPL, b = (u % UPL) / cv.Hkv;
-  const int n = cv.len[u] + appended.get(layer);
-  const int n8 = cv.n8[u];
-  const int N = cv.budget[layer * cv.B + b];
   int32_t *sel = sel_all + (size_t)u * kSelInts;
+  const int app = appended.get(layer);
+  const UnitWords uw = load_unit_words(cv, sel, u, layer, b);   // (its "settled" word is not used here)
+  const int n = uw.len + app;
+  const int n8 = uw.n8;
+  const int N = uw.budget;
   const int p_eff = min(cv.P, n);
   const int ncand = n - p_eff;
   const int e = min(n - N, ncand);
@@ -834,7 +862,7 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
-  const int hm = cv.head8[u], cap = cv.cap;          // slot i of the per-slot planes: ring_row_u(hm, i, cap)
+  const int hm = uw.head, cap = cv.cap;                // slot i of the per-slot planes: ring_row_u(hm, i, cap)
   const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   // loads go out in batches of kBatch (indices past the end re-read the last candidate), so a
   // long unit costs a few memory round trips per pass and not one per 64 slots
