@@ -145,6 +145,8 @@ typedef struct conf_kv_stats {
  * instead of the planned number (clamped to what the unit's length allows);
  * CONF_KV_TWO_LAUNCH=1 forces the two-launch form of conf_kv_attend; CONF_KV_NO_MFMA=1 (read
  * at the first plan of the process) keeps every shape on the vector-ALU streaming body;
+ * CONF_KV_SPIN_LIMIT=n bounds the in-kernel waits for other workgroups to n polls (default
+ * 400000, about 0.4 s; an expired wait ends the kernel early and counts a device error);
  * CONF_KV_COMPACT_PAIRED=0/1 (read at every conf_kv_evict_compact) forces one of the two grid
  * shapes of the compaction kernel, which is otherwise chosen by the number of units. */
 

@@ -142,6 +142,7 @@ struct conf_kv_handle {
   uint32_t conf_epoch = 0;           // the same for conf_kv_step
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
+  int spin_limit = kSpinLimitDefault;   // CONF_KV_SPIN_LIMIT at create (tests of the expiry path)
   int last_hip = 0;
 };
 
@@ -192,6 +193,7 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->fresh_len.assign(L, -1);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
   if (const char *tl = getenv("CONF_KV_TWO_LAUNCH")) h->force_two_launch = atoi(tl) != 0;
+  if (const char *sp = getenv("CONF_KV_SPIN_LIMIT")) h->spin_limit = std::max(0, atoi(sp));
 
   CacheView &cv = h->cv;
   uint8_t *s = h->state;
@@ -331,6 +333,7 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   // untouched for exactly that long to be misread; 0 is skipped because the words start at 0.)
   if (++h->epoch == 0u) h->epoch = 1u;
   a.epoch = h->epoch;
+  a.spin_limit = h->spin_limit;
   a.max_splits = kAttendMaxSplits;
   a.sm_scale = h->cfg.sm_scale;
   a.ema_decay = h->cfg.ema_decay;
@@ -391,7 +394,7 @@ int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, ui
   if (++h->conf_epoch == 0u) h->conf_epoch = 1u;         // the partial words start at tag 0
   CK_HIP(h, launch_conf_reduce(h->cv, dev_logits, h->cfg.vocab,
                                (unsigned long long *)(h->scratch + h->kl.conf_partial),
-                               h->conf_epoch, dev_conf, dev_sel,
+                               h->conf_epoch, h->spin_limit, dev_conf, dev_sel,
                                (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
                                (double)h->cfg.w_top, (hipStream_t)stream));
   return CONF_KV_OK;

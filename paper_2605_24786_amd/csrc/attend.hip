@@ -48,7 +48,6 @@ namespace confkv {
 
 constexpr int kAttThreads = 512;
 constexpr int kAttWaves = 8;
-constexpr int kSpinLimit = 400000;   // polls (about a microsecond each) before a wait gives up
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -463,7 +462,7 @@ __device__ __forceinline__ bool collect_ml(const CacheView &cv, const AttendLaun
       }
       if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
       __builtin_amdgcn_s_sleep(1);
-      if (++spins > kSpinLimit) {
+      if (++spins > a.spin_limit) {
         if (!here) *s_ok = 0;
         break;
       }

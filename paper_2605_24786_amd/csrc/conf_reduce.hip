@@ -18,7 +18,6 @@ constexpr int kConfThreads = 256;
 constexpr int kConfPerThread = 16;
 constexpr int kConfChunk = kConfThreads * kConfPerThread;   // 4096 logits per workgroup
 constexpr int kPartialStride = 8;                           // 8-byte words per chunk partial (5 in use)
-constexpr int kConfSpinLimit = 400000;                      // polls before the merger gives up (about 0.4 s)
 
 // A float with the epoch of the call that wrote it in one 8-byte word: value and tag are seen
 // together or not at all.  Agent-scope relaxed atomics are coherent across the XCDs by
@@ -43,7 +42,7 @@ __device__ __forceinline__ void top2_merge(float &a1, float &a2, float b1, float
 
 __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     const float *__restrict__ logits, int V, int nchunk, unsigned long long *__restrict__ partial,
-    unsigned epoch, float *__restrict__ conf, uint8_t *__restrict__ sel,
+    unsigned epoch, int spin_limit, float *__restrict__ conf, uint8_t *__restrict__ sel,
     CacheView cv, double tau, double wH, double wm, double wp) {
   __shared__ float s_f[4 * 4];
   __shared__ double s_d[4 * 2];
@@ -119,7 +118,7 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
       if (!here) here = (unsigned)(ld_word(wp_) >> 32) == epoch;
       if (__builtin_amdgcn_ballot_w64(!here) == 0ull) break;
       __builtin_amdgcn_s_sleep(1);
-      if (++spins > kConfSpinLimit) {
+      if (++spins > spin_limit) {
         if (!here) s_ok = 0;
         break;
       }
@@ -194,12 +193,12 @@ size_t conf_reduce_scratch_bytes(int B, int V) {
 }
 
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
-                              unsigned epoch, float *conf, uint8_t *sel, double tau, double wH,
+                              unsigned epoch, int spin_limit, float *conf, uint8_t *sel, double tau, double wH,
                               double wm, double wp, hipStream_t stream) {
   int nchunk = (V + kConfChunk - 1) / kConfChunk;
   dim3 grid(nchunk, cv.B);
   hipLaunchKernelGGL(conf_reduce_kernel, grid, dim3(kConfThreads), 0, stream, logits, V, nchunk,
-                     partial, epoch, conf, sel, cv, tau, wH, wm, wp);
+                     partial, epoch, spin_limit, conf, sel, cv, tau, wH, wm, wp);
   return hipGetLastError();
 }
 

@@ -12,8 +12,9 @@ namespace confkv {
 // ---- conf_reduce.hip ----
 size_t conf_reduce_scratch_bytes(int B, int V);   // epoch-tagged chunk partials: zero before the first call
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
-                              unsigned epoch /* never 0, never reused */, float *conf, uint8_t *sel, double tau, double wH,
-                              double wm, double wp, hipStream_t stream);
+                              unsigned epoch /* never 0, never reused */, int spin_limit, float *conf, uint8_t *sel,
+                              double tau, double wH, double wm, double wp, hipStream_t stream);
+constexpr int kSpinLimitDefault = 400000;   // polls (about a microsecond each) before a bounded wait gives up
 
 // ---- probe.hip ----
 hipError_t launch_probe_read(const void *src, size_t bytes, unsigned *out, int workgroups, hipStream_t stream);
@@ -33,6 +34,7 @@ struct AttendLaunch {
   unsigned long long *part_ml;   // [units per layer][max splits][G][2] words: (epoch << 32) | float bits of m, of l
   float *part_o;           // [units per layer][max splits][G][D]
   unsigned epoch;          // tag of the words published in this launch (never 0, never reused by a later one)
+  int spin_limit;          // polls before a wait for the other splits gives up (device error)
   int max_splits;
   float sm_scale, ema_decay;
   double mass_gain;        // weight of the step's mass in the EMA update

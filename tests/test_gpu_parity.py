@@ -671,6 +671,51 @@ def test_lockstep_both_compaction_forms(lib, torch_cuda, paired, G, D, W, N):
         os.environ.pop("CONF_KV_COMPACT_PAIRED", None)
 
 
+def test_expired_waits_end_the_kernels_and_are_reported(lib, torch_cuda):
+    """The bounded in-kernel waits (splits of a unit waiting for each other's statistics, the
+    confidence merger waiting for the chunks of its row) with the bound forced to zero polls from
+    the host: every kernel still runs to its end, the expiry is counted and conf_kv_counters
+    reports CONF_KV_ERR_DEVICE; a handle with the normal bound is unaffected."""
+    torch = torch_cuda
+    say("expired waits")
+    B, H, G, D, T0, V = 1, 2, 4, 128, 3000, 50000
+    rng = np.random.default_rng(0)
+    K = torch.from_numpy(rng.standard_normal((B, H, T0, D)).astype(np.float16)).cuda()
+    q = torch.from_numpy(rng.standard_normal((B, G * H, D)).astype(np.float16)).cuda()
+    kn = torch.from_numpy(rng.standard_normal((B, H, D)).astype(np.float16)).cuda()
+    lg = torch.from_numpy(rng.standard_normal((B, V)).astype(np.float32)).cuda()
+    out = torch.empty_like(q)
+    cfg = dict(batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, vocab=V, fp16_window=32, capacity=3072,
+               protected_window=8, n_tight=[2000], n_loose=[2500])
+    os.environ["CONF_KV_SPIN_LIMIT"] = "0"
+    os.environ["CONF_KV_SPLITS"] = "8"
+    try:
+        bad = _mk(lib, **cfg)
+    finally:
+        os.environ.pop("CONF_KV_SPIN_LIMIT", None)
+        os.environ.pop("CONF_KV_SPLITS", None)
+    bad.load_prefill(0, K, K)
+    assert bad.attend_splits(0) == 8
+    for _ in range(4):                       # with no poll allowed, some split misses a peer's words
+        bad.attend(0, q, kn, kn, out)
+        bad.step(lg)
+        bad.evict_compact()
+    torch.cuda.synchronize()
+    st = bad.counters(check=False)
+    assert st.device_errors > 0
+    with pytest.raises(lib.ConfKVError) as ei:
+        bad.counters()
+    assert ei.value.status == lib.binding.ERR_DEVICE
+    bad.close()
+    good = _mk(lib, **cfg)
+    good.load_prefill(0, K, K)
+    good.attend(0, q, kn, kn, out)
+    good.step(lg)
+    good.evict_compact()
+    assert good.counters().device_errors == 0
+    good.close()
+
+
 def test_lockstep_wide_groups(lib, torch_cuda):
     """Groups of twelve query heads per kv-head through decode steps with evictions and demotions,
     and an observation window first (one query per call at this group size)."""
