@@ -53,6 +53,15 @@ def compute() -> dict:
     out["chunk"] = {"out": digest(np.round(o, 12)), "mass": digest(np.round(Wm, 12)), "ema": digest(u.ema)}
     # the random ranker's draws
     out["random_scores"] = [repr(float(x)) for x in O.random_scores(12345, 7, np.arange(4))]
+    # importance from an observation window at the end of the prompt (nothing appended)
+    u = O.load_prefill(K, V, W)
+    q = rng.standard_normal((5, G, D)).astype(np.float16)
+    o, Wm = O.observe_unit(u, q, T - 5, 0.25, float(np.float32(0.9)))
+    out["observe"] = {"out": digest(np.round(o, 12)), "mass": digest(np.round(Wm, 12)), "ema": digest(u.ema)}
+    # coarsened eviction: whole pages of 8 original positions, twice (the second on gapped positions)
+    u = O.load_prefill(K, V, W, ema0=rng.random(T).astype(np.float32))
+    gone = [[int(x) for x in O.evict_compact_unit(u, N, P, float(np.float32(0.65)), W, page=8)] for N in (70, 41)]
+    out["pages"] = {"evicted": gone, "n": u.n, "ema": digest(u.ema)}
     return out
 
 
