@@ -217,6 +217,8 @@ def main():
                     help="tokens per attention call (conf_kv_attend_chunk when above 1; at most 16 / group size)")
     ap.add_argument("--evict-page", type=int, default=0,
                     help="coarsened eviction: whole pages of this many original positions go (0 = token level)")
+    ap.add_argument("--rank-scope", choices=["kv_head", "layer"], default="kv_head",
+                    help="layer: one kept set per (layer, sequence) from the importance summed over its kv-heads")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device-to-device copy a few times and exit (counter calibration)")
     args = ap.parse_args()
@@ -249,6 +251,8 @@ def main():
         wl = wl.scaled(name=wl.name + f"_chunk{args.chunk}", max_chunk=args.chunk)
     if args.evict_page > 1:
         wl = wl.scaled(name=wl.name + f"_page{args.evict_page}", evict_page=args.evict_page)
+    if args.rank_scope != "kv_head":
+        wl = wl.scaled(name=wl.name + "_layer_scope", rank_scope=args.rank_scope)
     if args.layers and args.layers < wl.n_layers:
         wl = wl.scaled(n_layers=args.layers, n_tight=wl.n_tight[:args.layers], n_loose=wl.n_loose[:args.layers])
     L = wl.n_layers
@@ -333,7 +337,7 @@ def main():
         "config": {"workload": wl.name, "layers": L, "batch": wl.batch, "q_heads": wl.n_q_heads,
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "vocab": wl.vocab,
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
-                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "evict_page": args.evict_page, "attend_splits": kv.attend_splits(0),
+                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "evict_page": args.evict_page, "rank_scope": args.rank_scope, "attend_splits": kv.attend_splits(0),
                    "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
         "roofline": {"bound": "hbm", "kernel": ("attend_mfma_kernel<16>" if tq > 1 else f"attend_mfma_kernel<{wl.group}>") if (tq > 1 or wl.group > 1) and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

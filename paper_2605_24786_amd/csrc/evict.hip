@@ -563,18 +563,21 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {   // set bits
   return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0));
 }
 
-template <int T, int E>
-__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T == 256 ? 4 : 1, T == 256 ? 4 : 8)))
+// kShared: the importance is the layer-shared float64 sum in shared_all (see rank_small_kernel).
+template <int T, int E, bool kShared = false>
+__global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T == 256 && !kShared ? 4 : 1, T == 256 && !kShared ? 4 : 8)))
 void rank_select_reg_kernel(CacheView cv, LayerMask appended,
                                                             double alpha,
                                                             int32_t *__restrict__ src_all,
-                                                            int32_t *__restrict__ sel_all) {
+                                                            int32_t *__restrict__ sel_all,
+                                                            const double *__restrict__ shared_all = nullptr) {
+  typedef typename std::conditional<kShared, double, float>::type Imp;   // importance as stored
   constexpr int kRsWaves = T / kWave;
   __shared__ int hist[512];                         // two histograms, used alternately
   __shared__ int s_tmp[kRsWaves];
   __shared__ int s_cnt[E * kRsWaves];               // tied lanes per (round, wavefront)
   __shared__ int s_keep[E * kRsWaves + 1];          // kept lanes per (round, wavefront), then their prefix sums
-  __shared__ float s_fmin[kRsWaves], s_fmax[kRsWaves];
+  __shared__ Imp s_fmin[kRsWaves], s_fmax[kRsWaves];
   __shared__ unsigned long long s_prefix, s_kmin[kRsWaves], s_kmax[kRsWaves];
   __shared__ int s_krem, s_done, s_hole[kRsWaves], s_k8[kRsWaves], s_last8[kRsWaves];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -606,31 +609,40 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   const int Ed = (n + T - 1) / T;                   // rounds in use, <= E (checked by the host)
 
   // candidate EMA / position of the owned slots, min / max of the EMA
-  float av[E];
+  const double *shared = kShared ? shared_all + (size_t)(u / cv.Hkv) * cv.cap : nullptr;
+  Imp av[E];
   int pv[E];
   // slots are position-sorted: first and last candidate position (requested with the rest)
   const int pos_first = pos[hm], pos_last = pos[ring_row_u(hm, ncand - 1, cap)];
-  float fmin_ = INFINITY, fmax_ = -INFINITY;
+  Imp fmin_ = INFINITY, fmax_ = -INFINITY;
   // branch-free loads (indices past the candidates re-read the last one and are masked where
   // the values are used), so that all loads of the unit are in flight before the first wait
 #pragma unroll
   for (int k = 0; k < E; ++k) {
-    const int row = ring_row_u(hm, min(tid + k * T, ncand - 1), cap);
-    av[k] = ema[row];
+    const int slot = min(tid + k * T, ncand - 1);
+    const int row = ring_row_u(hm, slot, cap);
+    if constexpr (kShared) av[k] = shared[slot];
+    else av[k] = ema[row];
     pv[k] = pos[row];
   }
 #pragma unroll
   for (int k = 0; k < E; ++k) {
-    if (k < Ed && tid + k * T < ncand) { fmin_ = fminf(fmin_, av[k]); fmax_ = fmaxf(fmax_, av[k]); }
+    if (k < Ed && tid + k * T < ncand) {              // (no NaN in an importance: plain compares)
+      fmin_ = av[k] < fmin_ ? av[k] : fmin_;
+      fmax_ = av[k] > fmax_ ? av[k] : fmax_;
+    }
   }
   fmin_ = wave_min(fmin_);
   fmax_ = wave_max(fmax_);
   if (lane == 0) { s_fmin[w] = fmin_; s_fmax[w] = fmax_; }
   if (tid == 0) { s_prefix = 0ull; s_krem = e; s_done = 0; }
   __syncthreads();
-  float lo_f = s_fmin[0], hi_f = s_fmax[0];
+  Imp lo_f = s_fmin[0], hi_f = s_fmax[0];
 #pragma unroll
-  for (int k = 1; k < kRsWaves; ++k) { lo_f = fminf(lo_f, s_fmin[k]); hi_f = fmaxf(hi_f, s_fmax[k]); }
+  for (int k = 1; k < kRsWaves; ++k) {
+    lo_f = s_fmin[k] < lo_f ? s_fmin[k] : lo_f;
+    hi_f = s_fmax[k] > hi_f ? s_fmax[k] : hi_f;
+  }
   const double a_lo = (double)lo_f, a_hi = (double)hi_f;
   const double p_lo = (double)pos_first, p_hi = (double)pos_last;
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
@@ -832,8 +844,12 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
 // ---------------------------------------------------------------------------------------
 constexpr int kSmallE = 4;
 
+// kShared: the importance is the float64 sum over the kv-heads of the (layer, sequence), which
+// shared_mass_kernel left in shared_all (indexed by slot, not by ring row).
+template <bool kShared>
 __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, LayerMask appended,
                                                                 double alpha,
+                                                                const double *__restrict__ shared_all,
                                                                 int32_t *__restrict__ src_all,
                                                                 int32_t *__restrict__ sel_all, int U) {
   const int lane = threadIdx.x & 63;
@@ -862,20 +878,26 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
+  const double *shared = kShared ? shared_all + (size_t)(u / cv.Hkv) * cv.cap : nullptr;
   const int hm = uw.head, cap = cv.cap;                // slot i of the per-slot planes: ring_row_u(hm, i, cap)
   const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   // loads go out in batches of kBatch (indices past the end re-read the last candidate), so a
   // long unit costs a few memory round trips per pass and not one per 64 slots
   constexpr int kBatch = 8;
-  float fmin_ = INFINITY, fmax_ = -INFINITY;
+  typedef typename std::conditional<kShared, double, float>::type Imp;   // importance as stored
+  Imp fmin_ = INFINITY, fmax_ = -INFINITY;
   for (int base = 0; base < ncand; base += kBatch * kWave) {
-    float a[kBatch];
-#pragma unroll
-    for (int r = 0; r < kBatch; ++r) a[r] = ema[ring_row_u(hm, min(base + r * kWave + lane, ncand - 1), cap)];
+    Imp a[kBatch];
 #pragma unroll
     for (int r = 0; r < kBatch; ++r) {
-      fmin_ = fminf(fmin_, a[r]);
-      fmax_ = fmaxf(fmax_, a[r]);
+      const int i = min(base + r * kWave + lane, ncand - 1);
+      if constexpr (kShared) a[r] = shared[i];
+      else a[r] = ema[ring_row_u(hm, i, cap)];
+    }
+#pragma unroll
+    for (int r = 0; r < kBatch; ++r) {
+      fmin_ = a[r] < fmin_ ? a[r] : fmin_;             // (no NaN in an importance: plain compares)
+      fmax_ = a[r] > fmax_ ? a[r] : fmax_;
     }
   }
   const double a_lo = (double)wave_min(fmin_), a_hi = (double)wave_max(fmax_);
@@ -895,12 +917,14 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
       unsigned long long best_key = ~0ull;
       int best_idx = 0x7fffffff;
       for (int base = 0; base < ncand; base += kBatch * kWave) {
-        float a[kBatch];
+        Imp a[kBatch];
         int ps[kBatch];
 #pragma unroll
         for (int r = 0; r < kBatch; ++r) {
-          const int i = ring_row_u(hm, min(base + r * kWave + lane, ncand - 1), cap);
-          a[r] = ema[i];
+          const int slot = min(base + r * kWave + lane, ncand - 1);
+          const int i = ring_row_u(hm, slot, cap);
+          if constexpr (kShared) a[r] = shared[slot];
+          else a[r] = ema[i];
           ps[r] = pos[i];
         }
 #pragma unroll
@@ -1172,15 +1196,27 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 int n_max, hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
   if (opt.random || opt.shared || opt.page > 1) {
-    // ranker variants: the general kernel only
+    // ranker variants: the general kernel; with the layer-shared importance alone, the
+    // one-wavefront kernel first settles the units that evict a few slots (the steady state)
     if (opt.shared)
       hipLaunchKernelGGL(shared_mass_kernel, dim3(cv.L * cv.B, (cv.cap + kEvThreads - 1) / kEvThreads),
                          dim3(kEvThreads), 0, stream, cv, appended, opt.shared);
-    hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
-                       0, score, src, sel);
+    const int pre = opt.shared && !opt.random && opt.page <= 1;
+    if (pre)
+      hipLaunchKernelGGL(rank_small_kernel<true>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                         (const double *)opt.shared, src, sel, U);
+    if (pre && n_max <= 256 * 20)
+      hipLaunchKernelGGL((rank_select_reg_kernel<256, 20, true>), dim3(U), dim3(256), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)opt.shared);
+    else if (pre && n_max <= 1024 * 33)
+      hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33, true>), dim3(U), dim3(1024), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)opt.shared);
+    else
+      hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
+                         pre, score, src, sel);
   } else {
-  hipLaunchKernelGGL(rank_small_kernel, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                     src, sel, U);
+  hipLaunchKernelGGL(rank_small_kernel<false>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                     (const double *)nullptr, src, sel, U);
   // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
   // nothing); with few units the chip is filled by giving each unit four wavefronts.
   if (n_max <= 64 * 33 && U >= 2048)

@@ -671,6 +671,25 @@ def test_lockstep_both_compaction_forms(lib, torch_cuda, paired, G, D, W, N):
         os.environ.pop("CONF_KV_COMPACT_PAIRED", None)
 
 
+@pytest.mark.parametrize("prefill,D,W", [(6000, 128, 64), (1200, 64, -1), (40000, 128, 32)])
+def test_lockstep_layer_scope_on_every_ranking_kernel(lib, torch_cuda, prefill, D, W):
+    """One kept set per (layer, sequence) from the importance summed over the kv-heads, at unit
+    lengths that take each ranking kernel in turn: the first step evicts thousands of slots (the
+    register-resident kernels up to 33 792 slots, the scratch one above), the following ones one
+    or two (the one-wavefront kernel)."""
+    wl = small(1).scaled(n_layers=1, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=D, vocab=1009, prefill=prefill,
+                         steps=4, n_tight=(prefill // 3,), n_loose=(prefill // 2,), protected=16, fp16_window=W,
+                         rank_scope="layer", logit_std=(0.5, 6.0), logit_run=2)
+    say(f"lockstep layer scope prefill={prefill} D={D} W={W} capacity={wl.capacity}")
+    ls = Lockstep(lib, wl, seed=31)
+    for t in range(wl.steps):
+        ls.step()
+    rep = ls.report
+    assert rep.ok(), rep.evict_flips
+    assert rep.evictions > prefill // 3 and ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 def test_expired_waits_end_the_kernels_and_are_reported(lib, torch_cuda):
     """The bounded in-kernel waits (splits of a unit waiting for each other's statistics, the
     confidence merger waiting for the chunks of its row) with the bound forced to zero polls from
