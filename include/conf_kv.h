@@ -87,7 +87,9 @@ typedef struct conf_kv_config {
                                 single-token calls only.  Above 1: head_dim 128 and
                                 max_chunk * (n_q_heads / n_kv_heads) <= 16                     */
   int32_t evict_page;        /* 0 or 1: tokens are evicted one by one.  g > 1 (at most 1024):
-                                coarsened eviction for paged layouts -- a page is the live slots
+                                coarsened eviction for paged layouts (the remedy the paper names
+                                in "Compatibility with serving systems" and "Limitations" for
+                                partially dead blocks; it defines no rule) -- a page is the live slots
                                 whose original positions share floor(position / g); a page
                                 goes whole or not at all, and only when none of its slots lies
                                 in the protected window; pages are ranked by the mean of their
