@@ -79,13 +79,35 @@ SYMBOLS = {
 _lib = None
 
 
+def stale_sources() -> list:
+    """Sources of the library that were modified after libconfkv.so was built (empty: up to date)."""
+    if not os.path.exists(LIB_PATH):
+        return []
+    built = os.path.getmtime(LIB_PATH)
+    dirs = [os.path.join(_HERE, "csrc"), os.path.join(os.path.dirname(_HERE), "include")]
+    out = []
+    for d in dirs:
+        for name in sorted(os.listdir(d)) if os.path.isdir(d) else []:
+            if name.endswith((".hip", ".h")) and os.path.getmtime(os.path.join(d, name)) > built:
+                out.append(name)
+    return out
+
+
 def load_library() -> C.CDLL:
-    """Loads libconfkv.so (building it first only if it has never been built)."""
+    """Loads libconfkv.so, building it first if it has never been built.  A library older than
+    its sources is rebuilt when CONF_KV_REBUILD=1 and otherwise loaded with a loud warning (the
+    GPU machines run what was built beforehand; they do not compile)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        stale = stale_sources()
+        if not os.path.exists(LIB_PATH) or (stale and os.environ.get("CONF_KV_REBUILD") == "1"):
             from . import build as _build
             _build.build()
+        elif stale:
+            import warnings
+            warnings.warn(f"libconfkv.so is older than {', '.join(stale)}: the loaded library does not contain "
+                          f"those edits (run `python -m paper_2605_24786_amd.build`, or set CONF_KV_REBUILD=1)",
+                          RuntimeWarning, stacklevel=2)
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SYMBOLS.items():
             fn = getattr(lib, name)

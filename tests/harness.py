@@ -23,7 +23,7 @@ from synth import generate as gen
 OUT_RTOL, OUT_ATOL = 2e-3, 1e-3
 CONF_ATOL = 1e-5
 TIE_REL = 1e-6
-EMA_RTOL, EMA_ATOL = 2e-4, 1e-7
+EMA_RTOL, EMA_ATOL = 1e-5, 1e-8
 
 
 def f32(x) -> float:
