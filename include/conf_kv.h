@@ -252,6 +252,21 @@ int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, ui
                  conf_kv_stream stream);
 
 /*
+ * conf_kv_step for callers that cannot allocate or hand over a workspace at the time of the call
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid allocation): same
+ * arguments, same results, but the per-chunk partial sums of the reduction live in a device
+ * array of the library itself (1 MiB per GPU, resident from the library's load until the
+ * process ends) instead of the handle's dev_scratch.  The call allocates and frees nothing.
+ * Limit: batch * ceil(vocab / 4096) * 64 bytes must fit that array, i.e. batch * ceil(vocab /
+ * 4096) <= 16384 (CONF_KV_ERR_CAPACITY otherwise, before anything is launched).  Every call on
+ * one GPU, from any handle, uses that GPU's one array: calls that overlap in time on one GPU
+ * (different streams or host threads) race and give undefined results; calls in stream order
+ * are safe, whatever their sizes.
+ */
+int conf_kv_step_static(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
+                        conf_kv_stream stream);
+
+/*
  * Ranker, eviction, in-place compaction and demotion for every layer (Algorithm 1's
  * per-layer tail; "Budget and ranker"; "Cache manager").  For each unit with
  * n > N[l][b]: the newest min(P, n) slots are protected; over the other slots

@@ -64,6 +64,7 @@ SYMBOLS = {
     "conf_kv_attend_chunk": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, _P, _P, _P]),
     "conf_kv_observe": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]),
     "conf_kv_step": (C.c_int, [_P, _P, _P, _P, _P]),
+    "conf_kv_step_static": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
     "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
     "conf_kv_export": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32] + [_P] * 10),
@@ -230,6 +231,10 @@ class ConfKV:
     def step(self, logits, conf=None, sel=None):
         return self._check(self.lib.conf_kv_step(self.h, _ptr(logits), _ptr(conf), _ptr(sel),
                                                  self._stream()), "conf_kv_step")
+
+    def step_static(self, logits, conf=None, sel=None):
+        return self._check(self.lib.conf_kv_step_static(self.h, _ptr(logits), _ptr(conf), _ptr(sel),
+                                                        self._stream()), "conf_kv_step_static")
 
     def evict_compact(self):
         return self._check(self.lib.conf_kv_evict_compact(self.h, self._stream()), "conf_kv_evict_compact")

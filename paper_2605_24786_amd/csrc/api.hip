@@ -231,7 +231,9 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   std::vector<int32_t> budget((size_t)L * cfg->batch);
   for (int l = 0; l < L; ++l)
     for (int b = 0; b < cfg->batch; ++b) budget[(size_t)l * cfg->batch + b] = h->n_loose[l];
-  hipError_t e = hipMemset(h->state, 0, h->sl.header_bytes);
+  // the library's own device array (conf_kv_step_static): resolve its address on this device now
+  hipError_t e = conf_reduce_static_setup();
+  if (e == hipSuccess) e = hipMemset(h->state, 0, h->sl.header_bytes);
   if (e == hipSuccess) e = hipMemset(h->scratch, 0, h->kl.zero_bytes);
   if (e == hipSuccess && cv.chan)      // attention reads the channel scales even before any slot is INT8
     e = hipMemset(cv.ks, 0, (size_t)((uint8_t *)cv.k8 - (uint8_t *)cv.ks));
@@ -397,6 +399,16 @@ int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, ui
                                h->conf_epoch, h->spin_limit, dev_conf, dev_sel,
                                (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
                                (double)h->cfg.w_top, (hipStream_t)stream));
+  return CONF_KV_OK;
+}
+
+int conf_kv_step_static(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
+                        conf_kv_stream stream) {
+  if (!h || !dev_logits) return CONF_KV_ERR_INVALID_ARG;
+  if (conf_reduce_scratch_bytes(h->cfg.batch, h->cfg.vocab) > kConfStaticBytes) return CONF_KV_ERR_CAPACITY;
+  CK_HIP(h, launch_conf_reduce_static(h->cv, dev_logits, h->cfg.vocab, h->spin_limit, dev_conf, dev_sel,
+                                      (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
+                                      (double)h->cfg.w_top, (hipStream_t)stream));
   return CONF_KV_OK;
 }
 

@@ -9,6 +9,8 @@
 // per-layer budgets.  Nobody does a read-modify-write: a ticket counter per sequence made the
 // 32 arrivals of a row queue up at one address.  HBM traffic is one read of the logits
 // (4 B per logit).
+#include <mutex>
+
 #include "confkv_dev.h"
 #include "launch.h"
 
@@ -185,6 +187,67 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   const int tight = s_tight;
   for (int l = tid; l < cv.L; l += kConfThreads)
     cv.budget[l * cv.B + b] = tight ? cv.n_tight[l] : cv.n_loose[l];
+}
+
+// ---------------------------------------------------------------------------------------
+// The same reduction with the chunk partials in memory the library owns: for callers that
+// cannot provide (or allocate) a workspace.  `scratch` is a host-side stand-in for the
+// array: host code only ever uses the device address hipGetSymbolAddress returns for the
+// current device (every device holds its own copy).  The array starts zeroed when the code
+// object is loaded, and tag 0 is never used by a launch.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned long long scratch[kConfStaticBytes / 8];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  unsigned long long *ptr = nullptr;   // device address of `scratch` on this device
+  unsigned epoch = 0;                  // tag of the last launch that used it
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// words [0, n) <- 0 (a kernel, not a memset node: the call may sit in a captured stream)
+__global__ void conf_static_clear_kernel(unsigned long long *p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+}  // namespace
+
+hipError_t conf_reduce_static_setup() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static[dev].ptr) return hipSuccess;
+  unsigned long long *ptr = nullptr;
+  e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!ptr) return hipErrorInvalidSymbol;
+  g_static[dev].ptr = ptr;
+  return hipSuccess;
+}
+
+hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, int V, int spin_limit, float *conf,
+                                     uint8_t *sel, double tau, double wH, double wm, double wp, hipStream_t stream) {
+  if (conf_reduce_scratch_bytes(cv.B, V) > kConfStaticBytes) return hipErrorInvalidValue;   // the caller checks first
+  hipError_t e = conf_reduce_static_setup();
+  if (e != hipSuccess) return e;
+  int dev = -1;
+  e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  unsigned long long *ptr;
+  unsigned epoch;
+  bool wrapped = false;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    ptr = g_static[dev].ptr;
+    if (++g_static[dev].epoch == 0u) { g_static[dev].epoch = 1u; wrapped = true; }
+    epoch = g_static[dev].epoch;
+  }
+  // after 2^32 launches the tags start over: no word may still carry one of the new round
+  if (wrapped) hipLaunchKernelGGL(conf_static_clear_kernel, dim3(64), dim3(256), 0, stream, ptr, kConfStaticBytes / 8);
+  return launch_conf_reduce(cv, logits, V, ptr, epoch, spin_limit, conf, sel, tau, wH, wm, wp, stream);
 }
 
 size_t conf_reduce_scratch_bytes(int B, int V) {

@@ -14,6 +14,13 @@ size_t conf_reduce_scratch_bytes(int B, int V);   // epoch-tagged chunk partials
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
                               unsigned epoch /* never 0, never reused */, int spin_limit, float *conf, uint8_t *sel,
                               double tau, double wH, double wm, double wp, hipStream_t stream);
+// The same launch with the chunk partials in a file-scope device array of the library (one copy
+// per device, shared by every call on that device; kConfStaticBytes of it).  setup resolves the
+// array's address on the current device once; the launch does it too if nobody has.
+constexpr size_t kConfStaticBytes = (size_t)1 << 20;
+hipError_t conf_reduce_static_setup();
+hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, int V, int spin_limit, float *conf,
+                                     uint8_t *sel, double tau, double wH, double wm, double wp, hipStream_t stream);
 constexpr int kSpinLimitDefault = 400000;   // polls (about a microsecond each) before a bounded wait gives up
 
 // ---- probe.hip ----
