@@ -149,6 +149,11 @@ typedef struct conf_kv_stats {
  * at the first plan of the process) keeps every shape on the vector-ALU streaming body;
  * CONF_KV_SPIN_LIMIT=n bounds the in-kernel waits for other workgroups to n polls (default
  * 400000, about 0.4 s; an expired wait ends the kernel early and counts a device error);
+ * CONF_KV_TEST_WITHHOLD=1 makes split 0 of every unit (conf_kv_attend) and chunk 0 of every
+ * logit row (conf_kv_step) keep their published words to themselves, so that the waits of the
+ * others expire (the kernels still end normally; tests of the expiry path);
+ * CONF_KV_GRID_KV_MAJOR=0/1 overrides the order of the attention grid (kv-heads first puts all
+ * splits of a unit on one XCD and is the default when the number of kv-heads is a multiple of 8);
  * CONF_KV_COMPACT_PAIRED=0/1 (read at every conf_kv_evict_compact) forces one of the two grid
  * shapes of the compaction kernel, which is otherwise chosen by the number of units. */
 
@@ -164,7 +169,7 @@ size_t conf_kv_scratch_bytes(const conf_kv_config *cfg);
 int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_state,
                    void *dev_scratch);
 
-/* Pyramidal per-layer budgets ("Layer-wise pyramidal extension": N(l) = max(N_min,
+/* Pyramidal per-layer budgets ("Pyramidal layer budgets": N(l) = max(N_min,
  * N(0) * beta^(l / L))), floored to integers, for filling n_tight / n_loose: host_out int32
  * [n_layers].  The paper uses beta = 0.5 and N_min = 96.  Pure host arithmetic in double;
  * CONF_KV_ERR_INVALID_ARG on n_layers < 1, n0 < 1, n_min < 1 or beta outside (0, 1]. */

@@ -110,9 +110,9 @@ ScratchLayout scratch_layout(const conf_kv_config *c) {
   s.conf_partial = take(conf_reduce_scratch_bytes(c->batch, c->vocab));
   // epoch-tagged (m, l) words of the splits: tags start at 0, which no launch uses
   s.part_ml = take(UPL * kAttendMaxSplits * R * 2 * 8);
-  s.zero_bytes = off;
   // (the matrix-core body exchanges 128-channel partials whatever the head dimension)
-  s.part_o = take(UPL * kAttendMaxSplits * R * std::max<size_t>(D, 128) * 4);
+  s.part_o = take(UPL * kAttendMaxSplits * R * std::max<size_t>(D, 128) * 8);
+  s.zero_bytes = off;
   s.spill = take(attend_spill_floats((int)UPL, (int)R, c->capacity) * 4);
   s.score = take(U * c->capacity * 8);
   s.src = take(U * c->capacity * 4);
@@ -142,6 +142,8 @@ struct conf_kv_handle {
   uint32_t conf_epoch = 0;           // the same for conf_kv_step
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
+  int withhold = 0;                 // CONF_KV_TEST_WITHHOLD at create (tests of the expiry path)
+  int kv_major = 0;                 // splits of a unit on one XCD (eight kv-heads or a multiple; CONF_KV_GRID_KV_MAJOR overrides)
   int spin_limit = kSpinLimitDefault;   // CONF_KV_SPIN_LIMIT at create (tests of the expiry path)
   int last_hip = 0;
 };
@@ -193,6 +195,9 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->fresh_len.assign(L, -1);
   if (const char *fs = getenv("CONF_KV_SPLITS")) h->forced_splits = atoi(fs);
   if (const char *tl = getenv("CONF_KV_TWO_LAUNCH")) h->force_two_launch = atoi(tl) != 0;
+  if (const char *wh = getenv("CONF_KV_TEST_WITHHOLD")) h->withhold = atoi(wh) != 0;
+  h->kv_major = cfg->n_kv_heads % 8 == 0;
+  if (const char *km = getenv("CONF_KV_GRID_KV_MAJOR")) h->kv_major = atoi(km) != 0;
   if (const char *sp = getenv("CONF_KV_SPIN_LIMIT")) h->spin_limit = std::max(0, atoi(sp));
 
   CacheView &cv = h->cv;
@@ -328,12 +333,16 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.vnew = (const __half *)dev_vnew16;
   a.out = (__half *)dev_out16;
   a.part_ml = (unsigned long long *)(h->scratch + h->kl.part_ml);
-  a.part_o = (float *)(h->scratch + h->kl.part_o);
+  a.part_o = (unsigned long long *)(h->scratch + h->kl.part_o);
   a.spill = (float *)(h->scratch + h->kl.spill);
   // One counter for the handle: the tagged words are shared by the layers, so a launch must not
-  // meet a tag a launch on another layer left.  (A wrap after 2^32 launches would need a word
-  // untouched for exactly that long to be misread; 0 is skipped because the words start at 0.)
-  if (++h->epoch == 0u) h->epoch = 1u;
+  // meet a tag a launch on another layer left.  0 is skipped because the words start at 0, and
+  // when the counter wraps (2^32 launches) the words are cleared first, so that no word of the
+  // round before can carry a tag of the new one.
+  if (++h->epoch == 0u) {
+    h->epoch = 1u;
+    CK_HIP(h, launch_zero_words(h->scratch + h->kl.part_ml, h->kl.zero_bytes - h->kl.part_ml, (hipStream_t)stream));
+  }
   a.epoch = h->epoch;
   a.spin_limit = h->spin_limit;
   a.max_splits = kAttendMaxSplits;
@@ -344,6 +353,8 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.tq = tq;
   a.gq = h->cv.G;
   a.observe_first = observe_first;
+  a.kv_major = h->kv_major;
+  a.withhold = h->withhold;
   a.dbg = nullptr;
 #ifdef CONFKV_TRACE
   // the ranking work arrays at the end of the scratch buffer are idle during conf_kv_attend
@@ -393,10 +404,13 @@ int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
 int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
                  conf_kv_stream stream) {
   if (!h || !dev_logits) return CONF_KV_ERR_INVALID_ARG;
-  if (++h->conf_epoch == 0u) h->conf_epoch = 1u;         // the partial words start at tag 0
+  if (++h->conf_epoch == 0u) {                           // the partial words start at tag 0: see conf_kv_attend
+    h->conf_epoch = 1u;
+    CK_HIP(h, launch_zero_words(h->scratch + h->kl.conf_partial, h->kl.part_ml - h->kl.conf_partial, (hipStream_t)stream));
+  }
   CK_HIP(h, launch_conf_reduce(h->cv, dev_logits, h->cfg.vocab,
                                (unsigned long long *)(h->scratch + h->kl.conf_partial),
-                               h->conf_epoch, h->spin_limit, dev_conf, dev_sel,
+                               h->conf_epoch, h->spin_limit, h->withhold, dev_conf, dev_sel,
                                (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
                                (double)h->cfg.w_top, (hipStream_t)stream));
   return CONF_KV_OK;
@@ -406,7 +420,7 @@ int conf_kv_step_static(conf_kv_handle *h, const float *dev_logits, float *dev_c
                         conf_kv_stream stream) {
   if (!h || !dev_logits) return CONF_KV_ERR_INVALID_ARG;
   if (conf_reduce_scratch_bytes(h->cfg.batch, h->cfg.vocab) > kConfStaticBytes) return CONF_KV_ERR_CAPACITY;
-  CK_HIP(h, launch_conf_reduce_static(h->cv, dev_logits, h->cfg.vocab, h->spin_limit, dev_conf, dev_sel,
+  CK_HIP(h, launch_conf_reduce_static(h->cv, dev_logits, h->cfg.vocab, h->spin_limit, h->withhold, dev_conf, dev_sel,
                                       (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
                                       (double)h->cfg.w_top, (hipStream_t)stream));
   return CONF_KV_OK;

@@ -3,20 +3,24 @@
 // normaliser, dequantisation fused into the read; "Budget and ranker" -- EMA of attention
 // mass; Algorithm 1 -- append in FP16, update EMA metadata).
 //
-// One launch per layer, grid (splits, B * Hkv), 512 threads.  The `splits` workgroups of a
-// unit (b, kv-head) each stream a contiguous, byte-balanced slice of the unit's slots once
-// and serve all G query heads of the group from that single read:
+// One launch per layer, grid (splits, kv-heads, sequences) -- or (kv-heads, splits, sequences)
+// when the number of kv-heads is a multiple of eight, which puts all splits of a unit on one
+// XCD -- of 512 threads.  The `splits` workgroups of a unit (b, kv-head) each stream a
+// contiguous, byte-balanced slice of the unit's slots once and serve all G query heads of
+// the group from that single read:
 //
 //   stream   running (max, normaliser, output) per head (online softmax); the raw scores
 //            s[h][i] of the slice stay in LDS
-//   publish  workgroup merge; (m, l, o) -> global, arrive
-//   mass     wait until every split of the unit has arrived (they all publish at about the
-//            same time), form the exact global (M, L), then per slot
-//            A_i = sum_h e^{s[h][i]-M[h]} / L[h] and ema_i <- lambda ema_i + (1-lambda) A_i;
-//            every split also normalises its share of the unit's output row.
+//   publish  the workgroup's (m, l) per head go out first, then its merged output partial;
+//            every published 8-byte word carries the epoch of the launch, so nothing waits for
+//            stores to land and no counter is shared
+//   mass     gather the (m, l) words of every split of the unit (a bounded poll on their
+//            tags: they all publish at about the same time), form the exact global (M, L),
+//            then per slot A_i = sum_h e^{s[h][i]-M[h]} / L[h] and
+//            ema_i <- lambda ema_i + (1-lambda) A_i; every split also normalises its share of
+//            the unit's output row from the splits' tagged output partials.
 //
-// Every K/V byte is read once; the scores never leave the chip.  The wait (on per-split
-// arrival flags carrying the launch's epoch) is between
+// Every K/V byte is read once; the scores never leave the chip.  The wait is between
 // workgroups of one launch, so the host only launches grids that are co-resident
 // (splits * units <= occupancy * CUs) and the wait itself is bounded.
 //
@@ -37,7 +41,9 @@
 // launch is replaced by two (stream + publish with the scores in device scratch; merge + mass),
 // which need no wait inside a kernel.
 #include <algorithm>
+#include <atomic>
 #include <map>
+#include <set>
 #include <mutex>
 #include <tuple>
 
@@ -60,35 +66,42 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 }
 
 // Optional in-kernel phase trace (build with -DCONFKV_TRACE): lane 0 of every wavefront
-// stores the 100 MHz wall clock at numbered points into a debug buffer, 32 slots per
-// wavefront.  Compiled out otherwise.
+// notes the 100 MHz wall clock at numbered points, 32 slots per wavefront, in 2 KB of LDS behind
+// the kernel's own dynamic LDS (so a time stamp costs no trip to memory and no address
+// translation while the kernel runs); the workgroup copies them to the debug buffer as its last
+// act.  Compiled out otherwise.
 #ifdef CONFKV_TRACE
-#define TS(k)                                                                                   \
-  do {                                                                                          \
-    if (a.dbg && (threadIdx.x & 63) == 0)                                                       \
-      a.dbg[((size_t)(unit_in_layer(cv) * gridDim.x + blockIdx.x) * kAttWaves + (threadIdx.x >> 6)) * 32 + (k)] = \
-          wall_clock64();                                                                       \
+#define TS_SLOT(k) ts_lds_[a.trace_off / 8 + (threadIdx.x >> 6) * 32 + (k)]
+#define TS_INIT()                                                              \
+  do {                                                                         \
+    extern __shared__ unsigned long long ts_lds_[];                            \
+    if (a.dbg && (threadIdx.x & 63) < 32) TS_SLOT(threadIdx.x & 63) = 0ull;     \
+  } while (0)
+#define TS(k)                                                                  \
+  do {                                                                         \
+    extern __shared__ unsigned long long ts_lds_[];                            \
+    if (a.dbg && (threadIdx.x & 63) == 0) TS_SLOT(k) = wall_clock64();         \
+  } while (0)
+#define TS_DUMP()                                                              \
+  do {                                                                         \
+    extern __shared__ unsigned long long ts_lds_[];                            \
+    __syncthreads();                                                           \
+    if (a.dbg && threadIdx.x < kAttWaves * 32)                                 \
+      a.dbg[(size_t)(unit_in_layer(cv, a) * ns + split_index(a)) * kAttWaves * 32 + threadIdx.x] = \
+          ts_lds_[a.trace_off / 8 + threadIdx.x];                              \
   } while (0)
 #else
+#define TS_INIT() do { } while (0)
 #define TS(k) do { } while (0)
+#define TS_DUMP() do { } while (0)
 #endif
 
 // Partials travel between workgroups (possibly on different XCDs, whose L2s are not
 // coherent for ordinary accesses) through agent-scope relaxed atomics: such loads and
 // stores are coherent across the device by themselves, so no cache-wide release/acquire
-// fence (an L2 write-back plus invalidate on this hardware) is ever issued.  Ordering is
-// by completion: a publisher waits for its stores to complete before the workgroup
-// barrier that precedes the arrival increment; a consumer only issues its loads after it
-// has observed the arrival count.
-__device__ __forceinline__ void st_agent2(float *p, float v0, float v1) {   // p 8-byte aligned
-  const unsigned long long bits =
-      (unsigned long long)__float_as_uint(v0) | ((unsigned long long)__float_as_uint(v1) << 32);
-  __hip_atomic_store((unsigned long long *)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0); }
+// fence (an L2 write-back plus invalidate on this hardware) is ever issued.  No ordering
+// between different words is needed either: every published word carries the epoch of the
+// launch that wrote it, so a reader can tell on its own whether the word it got is current.
 // A float that travels with the epoch of the launch that wrote it: one 8-byte word, so a
 // reader sees value and tag together or neither.
 __device__ __forceinline__ void st_tagged(unsigned long long *p, unsigned epoch, float v) {
@@ -106,6 +119,10 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
 }
+
+// Workgroup barrier that orders LDS traffic only: global loads and stores issued before it
+// stay in flight across it (__syncthreads waits for them as well).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 __device__ __forceinline__ void unpack_i8x16(const int4 &r, float (&f)[16]) {
   const int wds[4] = {r.x, r.y, r.z, r.w};
@@ -142,18 +159,24 @@ struct Slice {
 __device__ __forceinline__ int share_cut(unsigned q, unsigned r, int j, float inv_ns) {
   return (int)(q * (unsigned)j + (unsigned)(((float)(r * (unsigned)j) + 0.5f) * inv_ns));
 }
-// The launch grid is (splits, kv-heads, sequences).
-__device__ __forceinline__ int unit_in_layer(const CacheView &cv) { return blockIdx.z * cv.Hkv + blockIdx.y; }
+// The launch grid is (splits, kv-heads, sequences), or (kv-heads, splits, sequences) when
+// a.kv_major is set: workgroups go to the XCDs round-robin in linear order, so with eight
+// kv-heads (or a multiple) in front all splits of a unit then run on one XCD.
+__device__ __forceinline__ int kv_head_index(const AttendLaunch &a) { return a.kv_major ? blockIdx.x : blockIdx.y; }
+__device__ __forceinline__ int split_index(const AttendLaunch &a) { return a.kv_major ? blockIdx.y : blockIdx.x; }
+__device__ __forceinline__ int unit_in_layer(const CacheView &cv, const AttendLaunch &a) {
+  return blockIdx.z * cv.Hkv + kv_head_index(a);
+}
 
 // Every split takes an equal share of the INT8 slots (cut at multiples of 32, the tile of
 // the matrix-core body) and an equal share of the FP16 slots, so all splits of a unit carry
 // the same mix of work and reach the arrival point together.
 __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLaunch &a, int ns, int S) {
   Slice s;
-  s.g = blockIdx.y;
+  s.g = kv_head_index(a);
   s.b = blockIdx.z;
-  s.ul = unit_in_layer(cv);
-  s.j = blockIdx.x;
+  s.ul = unit_in_layer(cv, a);
+  s.j = split_index(a);
   s.u = a.layer * cv.B * cv.Hkv + s.ul;
   // The unit's four counters in ONE round trip: lanes 0..3 of every wavefront read one array
   // each with a single load instruction (four scalar loads get spread over the prologue by the
@@ -473,14 +496,35 @@ __device__ __forceinline__ bool collect_ml(const CacheView &cv, const AttendLaun
   return *s_ok != 0;
 }
 
+// e^x for x <= 0 (-inf included, which gives 0) to about one ulp: 2^(x log2 e) with the product
+// carried in two floats, so the hardware exponential sees an argument without rounding error.
+// No range checks: the result cannot overflow, and below 2^-126 it may flush to zero.
+__device__ __forceinline__ float exp_nonpos(float x) {
+  x = fmaxf(x, -100.0f);
+  const float kHi = 1.44269502e+00f, kLo = 1.92596299e-08f;          // log2(e) = kHi + kLo
+  const float ph = x * kHi;
+  const float pl = fmaf(x, kLo, fmaf(x, kHi, -ph));
+  const float r = __builtin_amdgcn_exp2f(ph);
+  return fmaf(r, pl * 0.693147181f, r);
+}
+// 1 / x for a positive, finite double to about 1e-15 relative: the fp32 reciprocal estimate and two
+// Newton steps (a correctly rounded division costs ten times the instructions and nothing
+// downstream is that exact).
+__device__ __forceinline__ double recip_pos(double x) {
+  double r = (double)__builtin_amdgcn_rcpf((float)x);
+  r = r * (2.0 - x * r);
+  return r * (2.0 - x * r);
+}
+
 // Query row r of a unit is (token r / gq of the call, head r % gq of the group); rows past
 // tq * gq are padding.  Element e = r * D + d of the unit's [rows][D] output lives at
 // out[b][token][g * gq + head][d].
 __device__ __forceinline__ size_t out_index(const CacheView &cv, const Slice &sl, int tq, int gq,
                                             int e, int D) {
-  const int r = e / D, d = e - r * D;
-  const int t = r / gq, hq = r - t * gq;
-  return ((((size_t)sl.b * tq + t) * cv.Hkv + sl.g) * gq + hq) * D + d;
+  // (32-bit arithmetic: the output of one call stays far below 2^31 elements)
+  const unsigned r = (unsigned)e / (unsigned)D, d = (unsigned)e - r * (unsigned)D;
+  const unsigned t = r / (unsigned)gq, hq = r - t * (unsigned)gq;
+  return (size_t)(((((unsigned)sl.b * (unsigned)tq + t) * (unsigned)cv.Hkv + (unsigned)sl.g) * (unsigned)gq + hq) * (unsigned)D + d);
 }
 // Weight of row r's mass in the importance update of a call with tq tokens:
 // lambda^(tq - 1 - token), 0 for padding rows; for tq = 1 it is exactly 1.
@@ -511,7 +555,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   // more than 8 rows only occur in multi-token calls; otherwise rows are the heads of one token
   const int tq = G > 8 ? a.tq : 1, gq = G > 8 ? a.gq : G;
   unsigned long long *ml = a.part_ml + ((size_t)sl.ul * a.max_splits + sl.j) * G * 2;
-  float *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
+  unsigned long long *po = a.part_o + ((size_t)sl.ul * a.max_splits + sl.j) * G * D;
   // the EMA values this thread will update: requested now, needed after the wait
   constexpr int kPre = kPhase == 0 ? 4 : 0;
   const bool exchange = kPhase != 0 || ns > 1;       // partials go through device memory
@@ -524,52 +568,80 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     const int slot = sl.slot_of(max(0, min(tid + k * kAttThreads, sl.ntok - 1)));   // an empty slice reads slot lo16 < n
     ema_old[k] = EMA[ring_row_u(sl.h8, slot, cv.cap)];
   }
-  // workgroup merge of the per-wavefront partials; two channels per thread, one 8-byte
-  // coherent store each
+  // The softmax statistics go out first: thread h merges row h's (m, l) over the wavefront
+  // partials (the same operations, in the same order, as the output merge below) and publishes
+  // them at once, so their trip to the unit's other splits runs behind the output merge.
+  if (kPhase != 2 && exchange && tid < G) {
+    float M = NEG;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) M = fmaxf(M, wm[k * G + tid]);
+    float l = 0.f;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+      const float mk = wm[k * G + tid];
+      const bool live = mk > NEG;
+      l = fmaf(live ? wl[k * G + tid] : 0.f, live ? __expf(mk - M) : 0.f, l);
+    }
+    if (!a.withhold || sl.j != 0) {                   // (test hook: split 0 keeps its words to itself)
+      st_tagged(&ml[tid * 2], a.epoch, M);
+      st_tagged(&ml[tid * 2 + 1], a.epoch, l);
+    }
+  }
+  // workgroup merge of the per-wavefront output partials: kEPT channels per thread, each
+  // published as a word that carries the launch's epoch, so that nobody has to wait for the
+  // stores to land before announcing them
+  constexpr int kEPT = G * D > kAttThreads ? 2 : 1;
   if (kPhase != 2)
-  for (int idx = 2 * tid; idx < G * D; idx += 2 * kAttThreads) {
+  for (int idx = kEPT * tid; idx < G * D; idx += kEPT * kAttThreads) {
     const int h = idx / D;
     // branch-free, so that all LDS reads are in flight together; an empty partial (m = -inf)
     // may hold anything and enters with weight zero through the selects
-    float mk[NP], lk[NP];
-    float2 ok2[NP];
+    float mk[NP], lk[NP], ok2[NP][kEPT];
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
       mk[k] = wm[k * G + h];
       lk[k] = wl[k * G + h];
       // partial k belongs to wavefront k % kAttWaves
-      ok2[k] = *(const float2 *)&wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx];
+      const float *src = &wo[(k % kAttWaves) * WSTR + (k / kAttWaves) * G * D + idx];
+      if constexpr (kEPT == 2) {
+        const float2 t2 = *(const float2 *)src;
+        ok2[k][0] = t2.x;
+        ok2[k][kEPT - 1] = t2.y;
+      } else {
+        ok2[k][0] = *src;
+      }
     }
     float M = NEG;
 #pragma unroll
     for (int k = 0; k < NP; ++k) M = fmaxf(M, mk[k]);
-    float o0 = 0.f, o1 = 0.f, l = 0.f;
+    float o[kEPT] = {}, l = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
       const bool live = mk[k] > NEG;
       const float f = live ? __expf(mk[k] - M) : 0.f;
-      o0 = fmaf(live ? ok2[k].x : 0.f, f, o0);
-      o1 = fmaf(live ? ok2[k].y : 0.f, f, o1);
+#pragma unroll
+      for (int e = 0; e < kEPT; ++e) o[e] = fmaf(live ? ok2[k][e] : 0.f, f, o[e]);
       l = fmaf(live ? lk[k] : 0.f, f, l);
     }
     if (!exchange) {
       // a unit with a single split is complete here: same arithmetic as the general merge
       // below (weight e^0 = 1), without the trip through device memory
-      const double inv = 1.0 / (double)l;
-      __half2 o2;
-      o2.x = __float2half_rn((float)((double)o0 * inv));
-      o2.y = __float2half_rn((float)((double)o1 * inv));
-      // (DR < D: the matrix-core body pads a 64-channel head to its 128-channel tiles)
-      if (h < tq * gq && a.out && idx - h * D < DR)
-        *(__half2 *)&a.out[out_index(cv, sl, tq, gq, h * DR + (idx - h * D), DR)] = o2;
+      const double inv = recip_pos((double)l);
+#pragma unroll
+      for (int e = 0; e < kEPT; ++e) {
+        // (DR < D: the matrix-core body pads a 64-channel head to its 128-channel tiles)
+        if (h < tq * gq && a.out && idx + e - h * D < DR)
+          a.out[out_index(cv, sl, tq, gq, h * DR + (idx + e - h * D), DR)] = __float2half_rn((float)((double)o[e] * inv));
+      }
       if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
     } else {
-      st_agent2(&po[idx], o0, o1);
-      // (m, l) wait in LDS: they go out after the output partial has landed
-      if (idx % D == 0) { gm[h] = M; ((float *)ginv)[h] = l; }
+#pragma unroll
+      for (int e = 0; e < kEPT; ++e) st_tagged(&po[idx + e], a.epoch, o[e]);
     }
   }
-  const float *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
+  TS(19);
+  if (kPhase == 1) return;
+  const unsigned long long *pou = a.part_o + (size_t)sl.ul * a.max_splits * G * D;
   float *pml = wo;                                   // [ns][G][2], reuses the merge buffer
   // Output merge: this split normalises `per` elements of the unit's [G][D] output.  The ns
   // partial values of one element sit in gs consecutive lanes (gs = ns rounded up to a power
@@ -580,22 +652,12 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   while (gs < ns) gs <<= 1;                          // <= 64: groups never straddle a wavefront
   const int epp = kAttThreads / gs;                  // elements per pass over the workgroup
   const int os = tid % gs, oe = tid / gs;            // this thread's split and element within a pass
-  float opre = 0.f;
-  TS(19);
-  if (exchange && kPhase != 2) {
-    // the output partial is complete in memory before the tagged (m, l) can be seen
-    if (tid == 0) *s_ok = 1;
-    wait_stores_done();
-    __syncthreads();
-    TS(20);
-    if (tid < G) {
-      st_tagged(&ml[tid * 2], a.epoch, gm[tid]);
-      st_tagged(&ml[tid * 2 + 1], a.epoch, ((const float *)ginv)[tid]);
-    }
-  }
-  if (kPhase == 1) return;
+  unsigned long long opre = 0ull, opre2 = 0ull;
   if (exchange) {
     if (kPhase == 0) {
+      if (tid == 0) *s_ok = 1;
+      lds_barrier();                                 // the merge has read the buffer the statistics land in
+      TS(20);
       if (!collect_ml<G>(cv, a, sl, ns, pml, s_ok)) return;
       TS(21);
     } else {
@@ -604,24 +666,85 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       for (int idx = tid; idx < ns * G * 2; idx += kAttThreads) pml[idx] = __uint_as_float((unsigned)ld_tagged(&words[idx]));
       __syncthreads();
     }
-    // this split's share of the unit's output partials -> registers, needed only after the
-    // importance update: the round trip runs behind it
+    // this split's share of the unit's output partials: a first look now, checked (and asked for
+    // again if the word is not this launch's yet) only after the importance update
     if (os < ns && oe < per && sl.j * per + oe < G * D)
-      opre = ld_agent(&pou[(size_t)os * G * D + sl.j * per + oe]);
+      opre = ld_tagged(&pou[(size_t)os * G * D + sl.j * per + oe]);
     // global (M, L) of head h by wavefront h: one lane per split
     for (int h = tid >> 6; h < G; h += kAttWaves) {
       const int sp = tid & 63;
       const float ms = sp < ns ? pml[(sp * G + h) * 2] : NEG;
       // only the first gs lanes hold partials: log2(gs) exchange steps instead of six
+      const float ls = sp < ns ? pml[(sp * G + h) * 2 + 1] : 0.f;
       float M = ms;
-      for (int m = gs >> 1; m >= 1; m >>= 1) M = fmaxf(M, __shfl_xor(M, m, kWave));
-      double L = ms > NEG ? (double)expf(ms - M) * (double)pml[(sp * G + h) * 2 + 1] : 0.0;
-      for (int m = gs >> 1; m >= 1; m >>= 1) L += __shfl_xor(L, m, kWave);
-      if (sp == 0) { gm[h] = M; ginv[h] = 1.0 / L; ginv[G + h] = (1.0 / L) * row_weight(a, tq, gq, h); }
+      // (fixed lane distances up to four splits, so the exchanges need no index registers)
+      if (gs <= 4) {
+        if (gs > 2) M = fmaxf(M, __shfl_xor(M, 2, kWave));
+        if (gs > 1) M = fmaxf(M, __shfl_xor(M, 1, kWave));
+      } else {
+        for (int m = gs >> 1; m >= 1; m >>= 1) M = fmaxf(M, __shfl_xor(M, m, kWave));
+      }
+      const float es = ms > NEG ? exp_nonpos(ms - M) : 0.f;        // an empty partial weighs nothing
+      double L = (double)es * (double)ls;
+      if (gs <= 4) {
+        if (gs > 2) L += __shfl_xor(L, 2, kWave);
+        if (gs > 1) L += __shfl_xor(L, 1, kWave);
+      } else {
+        for (int m = gs >> 1; m >= 1; m >>= 1) L += __shfl_xor(L, m, kWave);
+      }
+      const double inv = recip_pos(L);
+      if (sp == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
+      // what split sp's output partial of this row is multiplied by, in place of its maximum
+      if (sp < ns) pml[(sp * G + h) * 2] = es * (float)inv;
     }
-  }  // exchange
-  __syncthreads();
+    lds_barrier();                                   // (the look at the output partials stays in flight)
+    // a second look, half a round trip later: by now the slowest split's words have landed, and
+    // this one too travels behind the importance update
+    if (os < ns && oe < per && sl.j * per + oe < G * D)
+      opre2 = ld_tagged(&pou[(size_t)os * G * D + sl.j * per + oe]);
+  } else {
+    __syncthreads();
+  }
   TS(22);
+  // ---- this split normalises its share of the unit's output (online-softmax merge) ----
+  auto finish_output = [&]() {
+  if (exchange) {
+      for (int base = 0; base < per; base += epp) {
+        const int e = sl.j * per + base + oe;                          // element of the [G][D] output
+        const bool valid = os < ns && base + oe < per && e < G * D;
+        const unsigned long long *src = &pou[(size_t)os * G * D + (valid ? e : 0)];
+        unsigned long long wv = base == 0 ? ((unsigned)(opre >> 32) == a.epoch ? opre : opre2) : (valid ? ld_tagged(src) : 0ull);
+        // a word that is not this launch's yet is asked for again (bounded); in a second launch
+        // every word is there
+        bool here = !valid || (unsigned)(wv >> 32) == a.epoch;
+        for (int spins = 0; __builtin_amdgcn_ballot_w64(!here) != 0ull; ++spins) {
+          if (spins > a.spin_limit) break;
+          __builtin_amdgcn_s_sleep(1);
+          if (!here) {
+            wv = ld_tagged(src);
+            here = (unsigned)(wv >> 32) == a.epoch;
+          }
+        }
+        const unsigned long long missing = __builtin_amdgcn_ballot_w64(!here);
+        if (missing) {                                                 // the wait expired: no output from this wavefront
+          if ((tid & 63) == __builtin_ctzll(missing)) atomicAdd(&cv.stats[kStatDeviceErr], 1ull);
+          continue;
+        }
+        const float v = __uint_as_float((unsigned)wv);
+        const int h = valid ? e / D : 0;
+        const float wgt = valid ? pml[(os * G + h) * 2] : 0.f;         // e^{m_s - M} / L of that split and row
+        float c = wgt > 0.f ? v * wgt : 0.f;                           // (an empty partial may hold anything)
+        if (gs <= 4) {                                                 // the usual case: two fixed exchanges
+          if (gs > 2) c += __shfl_xor(c, 2, kWave);
+          if (gs > 1) c += __shfl_xor(c, 1, kWave);
+        } else {
+          for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
+        }
+        if (valid && os == 0 && h < tq * gq && a.out && e - h * D < DR)
+          a.out[out_index(cv, sl, tq, gq, h * DR + (e - h * D), DR)] = __float2half_rn(c);
+      }
+    }
+  };
   // ---- mass + EMA of the slice ----
   // a <- lambda^tq a + gain * sum over the rows of lambda^(tq-1-token) p; ginv[G + h] holds
   // row h's weight over its normaliser.  Slots appended by this call start at 0.
@@ -630,18 +753,22 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
   const double oml = a.mass_gain;
   const double *gw = ginv + G;
   const int first_new = sl.n - tq;
+  // The new values of the first kPre slots per thread stay in registers until the output is
+  // out: a store between the look at the output partials and its use would make that use wait
+  // for the store's acknowledgement as well (loads and stores share one in-order counter).
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
     const int t = tid + k * kAttThreads;
     if (t < sl.ntok) {
       double A = 0.0;
 #pragma unroll
-      for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * gw[h];
+      for (int h = 0; h < G; ++h) A += (double)exp_nonpos(stash[h * S + t] - gm[h]) * gw[h];
       const int slot = sl.slot_of(t);
       const double old = (slot >= first_new) ? 0.0 : (double)ema_old[k];   // a new token starts at 0
       EMA[ring_row_u(sl.h8, slot, cv.cap)] = (float)(lam * old + oml * A);
     }
   }
+  TS(30);
   // the rest of the slice in batches of kBatch slots per thread: branch-free loads first (a
   // slot past the slice re-reads its last one), so a long slice costs one round trip per
   // batch, not one per slot
@@ -660,28 +787,15 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       if (t < sl.ntok) {
         double A = 0.0;
 #pragma unroll
-        for (int h = 0; h < G; ++h) A += (double)expf(stash[h * S + t] - gm[h]) * gw[h];
+        for (int h = 0; h < G; ++h) A += (double)exp_nonpos(stash[h * S + t] - gm[h]) * gw[h];
         const double prev = (sl.slot_of(t) >= first_new) ? 0.0 : (double)old[k];   // a new token starts at 0
         EMA[row[k]] = (float)(lam * prev + oml * A);
       }
     }
   }
   TS(23);
-  // ---- this split normalises its share of the unit's output (online-softmax merge) ----
-  if (exchange) {
-    for (int base = 0; base < per; base += epp) {
-      const int e = sl.j * per + base + oe;                          // element of the [G][D] output
-      const bool valid = os < ns && base + oe < per && e < G * D;
-      float v = 0.f;
-      if (valid) v = base == 0 ? opre : ld_agent(&pou[(size_t)os * G * D + e]);
-      const int h = valid ? e / D : 0;
-      const float ms = valid ? pml[(os * G + h) * 2] : NEG;
-      float c = ms > NEG ? v * expf(ms - gm[h]) : 0.f;               // an empty partial weighs nothing
-      for (int m = gs >> 1; m >= 1; m >>= 1) c += __shfl_xor(c, m, kWave);
-      if (valid && os == 0 && h < tq * gq && a.out && e - h * D < DR)
-        a.out[out_index(cv, sl, tq, gq, h * DR + (e - h * D), DR)] = __float2half_rn((float)((double)c * ginv[h]));
-    }
-  }
+  finish_output();
+  TS(31);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -694,7 +808,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
                                                              int S) {
   constexpr int NP = kAttWaves;
   extern __shared__ __align__(16) float smem[];
-  float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S
+  float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv, a) * ns + split_index(a)) * G * S
                         : smem;                 // [G][S] raw scores of the slice
   float *wo = smem + (kSpill ? 0 : (size_t)G * S);   // [NP][G][D] per-wave un-normalised output
   float *wm = wo + NP * G * D;                  // [NP][G] per-wave maximum
@@ -750,7 +864,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv
   double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
   __shared__ int s_ok;
   const Slice sl = make_slice(cv, a, ns, S);
-  float *stash = a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S;
+  float *stash = a.spill + ((size_t)unit_in_layer(cv, a) * ns + split_index(a)) * G * S;
   attend_epilogue<D, G, 1, 0, 2, DR>(cv, a, sl, ns, S, stash, nullptr, nullptr, pml, gm, ginv, &s_ok);
 }
 
@@ -903,7 +1017,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
       (kAttWaves * kTileBytes > NP * G * D * 4 ? kAttWaves * kTileBytes : NP * G * D * 4) / 4;
   extern __shared__ __align__(16) float smem[];
   float *tiles = smem;                          // per-wave tile buffers, later [NP][G][D] partials
-  float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv) * ns + blockIdx.x) * G * S
+  float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv, a) * ns + split_index(a)) * G * S
                         : smem + kTileFloats;   // [G][S]
   float *gm = smem + kTileFloats + (kSpill ? 0 : (size_t)G * S);   // [G]
   double *ginv = (double *)(gm + G + (G & 1));  // [2 G]
@@ -914,6 +1028,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int tq = G > 8 ? a.tq : 1, gq = G > 8 ? a.gq : G;   // tokens of the call, heads per token
+  TS_INIT();
   TS(0);
   // every kernel argument the streaming prologue needs, fetched now (one round trip) rather
   // than piecemeal between the dependent loads below
@@ -1310,6 +1425,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   __syncthreads();
   TS(18);
   attend_epilogue<D, G, NP, kTileBytes / 4, kSpill ? 1 : 0, DR>(cv, a, sl, ns, S, stash, wm, wl, wo, gm, ginv, &s_ok);
+  TS_DUMP();
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1318,7 +1434,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
 
 typedef void (*AttendFn)(CacheView, AttendLaunch, int, int);
 
-static bool g_use_mfma = true;
+static std::atomic<bool> g_use_mfma{true};
 
 static AttendFn attend_fn_valu(int D, int G) {
 #define CONFKV_CASE(d, g) \
@@ -1455,8 +1571,16 @@ static int attend_occupancy(AttendFn fn, size_t lds) {
   auto it = cache.find(key);
   if (it != cache.end()) return it->second;
   int nb = 0;
-  if (lds > 64 * 1024)
-    (void)hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  // The dynamic-LDS ceiling of a kernel is raised once, to the most any plan can ask for: a
+  // ceiling set per plan would be lowered again by a later, smaller plan of the same kernel.
+  static std::set<const void *> raised;
+  if (lds > 64 * 1024 && raised.insert((const void *)fn).second) {
+    hipFuncAttributes fa;
+    size_t fixed = 0;                            // LDS the kernel declares itself counts against the same limit
+    if (hipFuncGetAttributes(&fa, (const void *)fn) == hipSuccess) fixed = fa.sharedSizeBytes;
+    (void)hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(160 * 1024 - std::min<size_t>(fixed, 64 * 1024)));
+  }
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void *)fn, kAttThreads, lds) !=
       hipSuccess)
     nb = 0;
@@ -1539,9 +1663,11 @@ size_t attend_spill_floats(int units_per_layer, int G, int cap) {
   return (size_t)units_per_layer * G * (2 * (size_t)cap + (size_t)kAttendMaxSplits * 291);
 }
 
-hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
+hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a_in, const AttendPlan &plan,
                          hipStream_t stream) {
-  dim3 grid(plan.splits, cv.Hkv, cv.B);
+  AttendLaunch a = a_in;
+  if (plan.two_launch || !plan.mfma) a.dbg = nullptr;      // only the single matrix-core kernel is traced
+  const dim3 grid = a.kv_major ? dim3(cv.Hkv, plan.splits, cv.B) : dim3(plan.splits, cv.Hkv, cv.B);
   if (plan.two_launch) {
     const bool rows16 = a.tq > 1 || a.observe_first >= 0 || cv.G > 8;
     const int rows2 = rows16 ? kChunkRows : cv.G;                   // query rows per unit
@@ -1561,6 +1687,16 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const Atten
   if (rows16 && !plan.mfma) return hipErrorInvalidValue;
   AttendFn fn = plan.mfma ? attend_fn_mfma(cv.D, rows, cv.chan != 0) : attend_fn_valu(cv.D, cv.G);
   if (!fn) return hipErrorInvalidValue;
+#ifdef CONFKV_TRACE
+  if (a.dbg && plan.mfma) {             // time stamps live in LDS behind the kernel's own
+    AttendLaunch at = a;
+    at.trace_off = (int)((plan.lds_bytes + 15) / 16 * 16);
+    const size_t lds = at.trace_off + kAttWaves * 32 * 8;
+    (void)hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), lds, stream, cv, at, plan.splits, plan.stash_tokens);
+    return hipGetLastError();
+  }
+#endif
   hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
                      plan.stash_tokens);
   return hipGetLastError();

@@ -44,7 +44,7 @@ __device__ __forceinline__ void top2_merge(float &a1, float &a2, float b1, float
 
 __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     const float *__restrict__ logits, int V, int nchunk, unsigned long long *__restrict__ partial,
-    unsigned epoch, int spin_limit, float *__restrict__ conf, uint8_t *__restrict__ sel,
+    unsigned epoch, int spin_limit, int withhold, float *__restrict__ conf, uint8_t *__restrict__ sel,
     CacheView cv, double tau, double wH, double wm, double wp) {
   __shared__ float s_f[4 * 4];
   __shared__ double s_d[4 * 2];
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   T = wave_sum(T);
   if (lane == 0) { s_f[8 + w] = S; s_f[12 + w] = T; }
   __syncthreads();
-  if (tid == 0) {
+  if (tid == 0 && withhold && c == 0) s_ok = 1;       // (test hook: chunk 0 keeps its words to itself)
+  if (tid == 0 && !(withhold && c == 0)) {
     unsigned long long *p = partial + ((size_t)b * nchunk + c) * kPartialStride;
     st_tagged(&p[0], epoch, mx);
     st_tagged(&p[1], epoch, (s_f[8] + s_f[9]) + (s_f[10] + s_f[11]));
@@ -228,8 +229,9 @@ hipError_t conf_reduce_static_setup() {
   return hipSuccess;
 }
 
-hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, int V, int spin_limit, float *conf,
-                                     uint8_t *sel, double tau, double wH, double wm, double wp, hipStream_t stream) {
+hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, int V, int spin_limit, int withhold,
+                                     float *conf, uint8_t *sel, double tau, double wH, double wm, double wp,
+                                     hipStream_t stream) {
   if (conf_reduce_scratch_bytes(cv.B, V) > kConfStaticBytes) return hipErrorInvalidValue;   // the caller checks first
   hipError_t e = conf_reduce_static_setup();
   if (e != hipSuccess) return e;
@@ -246,8 +248,13 @@ hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, i
     epoch = g_static[dev].epoch;
   }
   // after 2^32 launches the tags start over: no word may still carry one of the new round
-  if (wrapped) hipLaunchKernelGGL(conf_static_clear_kernel, dim3(64), dim3(256), 0, stream, ptr, kConfStaticBytes / 8);
-  return launch_conf_reduce(cv, logits, V, ptr, epoch, spin_limit, conf, sel, tau, wH, wm, wp, stream);
+  if (wrapped) (void)launch_zero_words(ptr, kConfStaticBytes, stream);
+  return launch_conf_reduce(cv, logits, V, ptr, epoch, spin_limit, withhold, conf, sel, tau, wH, wm, wp, stream);
+}
+
+hipError_t launch_zero_words(void *p, size_t bytes, hipStream_t stream) {
+  hipLaunchKernelGGL(conf_static_clear_kernel, dim3(256), dim3(256), 0, stream, (unsigned long long *)p, bytes / 8);
+  return hipGetLastError();
 }
 
 size_t conf_reduce_scratch_bytes(int B, int V) {
@@ -256,12 +263,12 @@ size_t conf_reduce_scratch_bytes(int B, int V) {
 }
 
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
-                              unsigned epoch, int spin_limit, float *conf, uint8_t *sel, double tau, double wH,
-                              double wm, double wp, hipStream_t stream) {
+                              unsigned epoch, int spin_limit, int withhold, float *conf, uint8_t *sel, double tau,
+                              double wH, double wm, double wp, hipStream_t stream) {
   int nchunk = (V + kConfChunk - 1) / kConfChunk;
   dim3 grid(nchunk, cv.B);
   hipLaunchKernelGGL(conf_reduce_kernel, grid, dim3(kConfThreads), 0, stream, logits, V, nchunk,
-                     partial, epoch, spin_limit, conf, sel, cv, tau, wH, wm, wp);
+                     partial, epoch, spin_limit, withhold, conf, sel, cv, tau, wH, wm, wp);
   return hipGetLastError();
 }
 

@@ -12,15 +12,20 @@ namespace confkv {
 // ---- conf_reduce.hip ----
 size_t conf_reduce_scratch_bytes(int B, int V);   // epoch-tagged chunk partials: zero before the first call
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
-                              unsigned epoch /* never 0, never reused */, int spin_limit, float *conf, uint8_t *sel,
-                              double tau, double wH, double wm, double wp, hipStream_t stream);
+                              unsigned epoch /* never 0, never reused */, int spin_limit,
+                              int withhold /* test hook: chunk 0 does not publish, so the bounded wait expires */,
+                              float *conf, uint8_t *sel, double tau, double wH, double wm, double wp,
+                              hipStream_t stream);
+// words [0, bytes / 8) <- 0 on the stream (a kernel, not a memset node)
+hipError_t launch_zero_words(void *p, size_t bytes, hipStream_t stream);
 // The same launch with the chunk partials in a file-scope device array of the library (one copy
 // per device, shared by every call on that device; kConfStaticBytes of it).  setup resolves the
 // array's address on the current device once; the launch does it too if nobody has.
 constexpr size_t kConfStaticBytes = (size_t)1 << 20;
 hipError_t conf_reduce_static_setup();
-hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, int V, int spin_limit, float *conf,
-                                     uint8_t *sel, double tau, double wH, double wm, double wp, hipStream_t stream);
+hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, int V, int spin_limit, int withhold,
+                                     float *conf, uint8_t *sel, double tau, double wH, double wm, double wp,
+                                     hipStream_t stream);
 constexpr int kSpinLimitDefault = 400000;   // polls (about a microsecond each) before a bounded wait gives up
 
 // ---- probe.hip ----
@@ -39,7 +44,7 @@ struct AttendLaunch {
   const __half *q, *knew, *vnew;
   __half *out;
   unsigned long long *part_ml;   // [units per layer][max splits][G][2] words: (epoch << 32) | float bits of m, of l
-  float *part_o;           // [units per layer][max splits][G][D]
+  unsigned long long *part_o;    // [units per layer][max splits][G][D] words: (epoch << 32) | float bits of a partial output
   unsigned epoch;          // tag of the words published in this launch (never 0, never reused by a later one)
   int spin_limit;          // polls before a wait for the other splits gives up (device error)
   int max_splits;
@@ -50,8 +55,12 @@ struct AttendLaunch {
   int gq;                  // query heads per kv-head; the kernels' row r is (token r / gq, head r % gq)
   int observe_first;       // >= 0: the queries belong to the cached slots observe_first .. observe_first + tq - 1;
                            // nothing is appended and slots from observe_first + tq on are left alone
+  int withhold;            // test hook: split 0 of every unit does not publish its statistics, so the
+                           // other splits' bounded waits expire (the kernel still ends normally)
+  int kv_major;            // grid is (kv-heads, splits, sequences) instead of (splits, kv-heads, sequences)
   float *spill;            // [units per layer][splits][G][stash_tokens] raw scores (two-launch form)
   unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
+  int trace_off;           // byte offset of the time stamps in dynamic LDS (CONFKV_TRACE builds)
 };
 constexpr int kAttendMaxSplits = 64;
 constexpr int kChunkRows = 16;     // query rows per unit of a multi-token call (one matrix-core tile)

@@ -70,6 +70,69 @@ def pick_units(wl, count: Optional[int], seed: int = 0) -> List[Tuple[int, int, 
     return [allu[i] for i in idx]
 
 
+def compare_unit_state(ex: dict, u: O.UnitCache, tag: str, rep: Report) -> None:
+    """One exported unit (the dict ConfKV.export returns) against the oracle's unit: length, kept
+    positions, precision tags, FP16 payload bits, INT8 codes and scales bit for bit; the EMA
+    within EMA_RTOL / EMA_ATOL."""
+    assert ex["n"] == u.n, f"{tag}: length gpu {ex['n']} oracle {u.n}"
+    assert np.array_equal(ex["pos"], u.pos.astype(np.int32)), f"{tag}: kept positions differ"
+    assert np.array_equal(ex["is16"], u.is16), f"{tag}: precision tags differ"
+    m16, m8 = u.is16, ~u.is16
+    for name in ("k16", "v16"):
+        assert np.array_equal(ex[name][m16].view(np.uint16), getattr(u, name)[m16].view(np.uint16)), \
+            f"{tag}: {name} payload bits differ"
+    for name in ("k8", "v8"):
+        assert np.array_equal(ex[name][m8], getattr(u, name)[m8]), f"{tag}: {name} codes differ"
+    if u.kcs is not None:
+        assert np.array_equal(ex["ks"].view(np.uint16), u.kcs.view(np.uint16)), f"{tag}: K channel scales differ"
+        assert np.array_equal(ex["vs"].view(np.uint16), u.vcs.view(np.uint16)), f"{tag}: V channel scales differ"
+    else:
+        for name in ("ks", "vs"):
+            assert np.array_equal(ex[name][m8].view(np.uint16), getattr(u, name)[m8].view(np.uint16)), \
+                f"{tag}: {name} scales differ"
+    ref = u.ema.astype(np.float64)
+    err = np.abs(ex["ema"].astype(np.float64) - ref)
+    bound = EMA_ATOL + EMA_RTOL * np.abs(ref)
+    assert np.all(err <= bound), f"{tag}: EMA off by {np.max(err / bound):.3g} x tolerance"
+    nz = ref > 1e-12
+    if nz.any():
+        rep.max_ema_rel = max(rep.max_ema_rel, float(np.max(err[nz] / ref[nz])))
+
+
+def adopt_gpu_choice(p: O.Policy, layer: int, key, pre: O.UnitCache, gpu_pos: np.ndarray, tight: bool,
+                     rep: Report) -> O.UnitCache:
+    """Kept sets differ: measure, in the oracle's float64 scores, how close the disputed slots were
+    to the cut-off (within TIE_REL: a counted tie, else a flip that fails the run), then replay the
+    oracle's compaction with the GPU's kept set so later steps stay comparable."""
+    N = p.n_tight[layer] if tight else p.n_loose[layer]
+    n = pre.n
+    if p.evict_page > 1 or p.ranker != "composite" or p.rank_scope != "kv_head":
+        # no near-tie analysis for the variants: any difference counts as a flip
+        rep.evict_flips.append(1.0)
+        u = pre.copy()
+        u.take(np.flatnonzero(np.isin(pre.pos, gpu_pos)))
+        O.demote(u, p.fp16_window)
+        return u
+    p_eff = min(p.protected, n)
+    ncand = n - p_eff
+    s = O.rank_scores(pre.ema[:ncand], pre.pos[:ncand], p.alpha)
+    keep_o, evict_o = O.select_evictions(pre, N, p.protected, p.alpha)
+    keep_g = np.flatnonzero(np.isin(pre.pos, gpu_pos))
+    assert keep_g.size == gpu_pos.size == keep_o.size, f"unit {key}: kept-set sizes differ"
+    disputed = np.setxor1d(keep_o, keep_g)
+    assert np.all(disputed < ncand), f"unit {key}: a protected slot is disputed"
+    cut = np.max(s[evict_o])                       # highest evicted score = the cut-off
+    rel = float(np.max(np.abs(s[disputed] - cut)) / max(abs(cut), 1e-300))
+    if rel <= TIE_REL:
+        rep.evict_ties += 1
+    else:
+        rep.evict_flips.append(rel)
+    u = pre.copy()
+    u.take(keep_g)
+    O.demote(u, p.fp16_window)
+    return u
+
+
 class Lockstep:
     def __init__(self, pkg, wl, seed: int = 0, units: Optional[int] = None, threads: int = 8,
                  ema0: bool = False, **override):
@@ -104,33 +167,8 @@ class Lockstep:
 
     # ---- comparisons ----
     def compare_state(self, when: str):
-        rep = self.report
         for key, u in self.run.units.items():
-            ex = self.kv.export(*key)
-            tag = f"{when} step {self.t} unit {key}"
-            assert ex["n"] == u.n, f"{tag}: length gpu {ex['n']} oracle {u.n}"
-            assert np.array_equal(ex["pos"], u.pos.astype(np.int32)), f"{tag}: kept positions differ"
-            assert np.array_equal(ex["is16"], u.is16), f"{tag}: precision tags differ"
-            m16, m8 = u.is16, ~u.is16
-            for name in ("k16", "v16"):
-                assert np.array_equal(ex[name][m16].view(np.uint16), getattr(u, name)[m16].view(np.uint16)), \
-                    f"{tag}: {name} payload bits differ"
-            for name in ("k8", "v8"):
-                assert np.array_equal(ex[name][m8], getattr(u, name)[m8]), f"{tag}: {name} codes differ"
-            if u.kcs is not None:
-                assert np.array_equal(ex["ks"].view(np.uint16), u.kcs.view(np.uint16)), f"{tag}: K channel scales differ"
-                assert np.array_equal(ex["vs"].view(np.uint16), u.vcs.view(np.uint16)), f"{tag}: V channel scales differ"
-            else:
-                for name in ("ks", "vs"):
-                    assert np.array_equal(ex[name][m8].view(np.uint16), getattr(u, name)[m8].view(np.uint16)), \
-                        f"{tag}: {name} scales differ"
-            ref = u.ema.astype(np.float64)
-            err = np.abs(ex["ema"].astype(np.float64) - ref)
-            bound = EMA_ATOL + EMA_RTOL * np.abs(ref)
-            assert np.all(err <= bound), f"{tag}: EMA off by {np.max(err / bound):.3g} x tolerance"
-            nz = ref > 1e-12
-            if nz.any():
-                rep.max_ema_rel = max(rep.max_ema_rel, float(np.max(err[nz] / ref[nz])))
+            compare_unit_state(self.kv.export(*key), u, f"{when} step {self.t} unit {key}", self.report)
 
     # ---- the prompt's own attention, before the decode loop ----
     def observe(self, first: int, tq: int, want_out: bool = True):
@@ -221,38 +259,7 @@ class Lockstep:
         rep.lengths.append(first.n)
 
     def _adopt(self, key, pre: O.UnitCache, gpu_pos: np.ndarray, tight: bool):
-        """Kept sets differ: measure how close the disputed slots were to the cut-off, then
-        replay the oracle's compaction with the GPU's kept set."""
-        rep, p = self.report, self.run.policy
-        l = key[0]
-        N = p.n_tight[l] if tight else p.n_loose[l]
-        n = pre.n
-        if p.evict_page > 1 or p.ranker != "composite" or p.rank_scope != "kv_head":
-            # no near-tie analysis for the variants: any difference counts as a flip
-            rep.evict_flips.append(1.0)
-            u = pre.copy()
-            u.take(np.flatnonzero(np.isin(pre.pos, gpu_pos)))
-            O.demote(u, p.fp16_window)
-            self.run.units[key] = u
-            return
-        p_eff = min(p.protected, n)
-        ncand = n - p_eff
-        s = O.rank_scores(pre.ema[:ncand], pre.pos[:ncand], p.alpha)
-        keep_o, evict_o = O.select_evictions(pre, N, p.protected, p.alpha)
-        keep_g = np.flatnonzero(np.isin(pre.pos, gpu_pos))
-        assert keep_g.size == gpu_pos.size == keep_o.size, f"unit {key}: kept-set sizes differ"
-        disputed = np.setxor1d(keep_o, keep_g)
-        assert np.all(disputed < ncand), f"unit {key}: a protected slot is disputed"
-        cut = np.max(s[evict_o])                       # highest evicted score = the cut-off
-        rel = float(np.max(np.abs(s[disputed] - cut)) / max(abs(cut), 1e-300))
-        if rel <= TIE_REL:
-            rep.evict_ties += 1
-        else:
-            rep.evict_flips.append(rel)
-        u = pre.copy()
-        u.take(keep_g)
-        O.demote(u, p.fp16_window)
-        self.run.units[key] = u
+        self.run.units[key] = adopt_gpu_choice(self.run.policy, key[0], key, pre, gpu_pos, tight, self.report)
 
     def close(self):
         self.kv.close()

@@ -692,9 +692,10 @@ def test_lockstep_layer_scope_on_every_ranking_kernel(lib, torch_cuda, prefill, 
 
 def test_expired_waits_end_the_kernels_and_are_reported(lib, torch_cuda):
     """The bounded in-kernel waits (splits of a unit waiting for each other's statistics, the
-    confidence merger waiting for the chunks of its row) with the bound forced to zero polls from
-    the host: every kernel still runs to its end, the expiry is counted and conf_kv_counters
-    reports CONF_KV_ERR_DEVICE; a handle with the normal bound is unaffected."""
+    confidence merger waiting for the chunks of its row) expire deterministically: a test hook
+    makes split 0 of every unit and chunk 0 of every logit row keep their words to themselves, and
+    the bound is a few polls.  Every kernel still runs to its end, each expired wait is counted
+    and conf_kv_counters reports CONF_KV_ERR_DEVICE; a handle without the hook is unaffected."""
     torch = torch_cuda
     say("expired waits")
     B, H, G, D, T0, V = 1, 2, 4, 128, 3000, 50000
@@ -706,22 +707,32 @@ def test_expired_waits_end_the_kernels_and_are_reported(lib, torch_cuda):
     out = torch.empty_like(q)
     cfg = dict(batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, vocab=V, fp16_window=32, capacity=3072,
                protected_window=8, n_tight=[2000], n_loose=[2500])
-    os.environ["CONF_KV_SPIN_LIMIT"] = "0"
+    os.environ["CONF_KV_SPIN_LIMIT"] = "200"
+    os.environ["CONF_KV_TEST_WITHHOLD"] = "1"
     os.environ["CONF_KV_SPLITS"] = "8"
     try:
         bad = _mk(lib, **cfg)
     finally:
         os.environ.pop("CONF_KV_SPIN_LIMIT", None)
+        os.environ.pop("CONF_KV_TEST_WITHHOLD", None)
         os.environ.pop("CONF_KV_SPLITS", None)
     bad.load_prefill(0, K, K)
     assert bad.attend_splits(0) == 8
-    for _ in range(4):                       # with no poll allowed, some split misses a peer's words
+    bad.attend(0, q, kn, kn, out)
+    torch.cuda.synchronize()
+    # no split of either unit ever sees split 0's words (every split gathers all eight sets)
+    assert bad.counters(check=False).device_errors == H * 8
+    bad.step(lg)
+    torch.cuda.synchronize()
+    assert bad.counters(check=False).device_errors == H * 8 + B         # the row's merger never sees chunk 0
+    bad.evict_compact()
+    for _ in range(3):
         bad.attend(0, q, kn, kn, out)
         bad.step(lg)
         bad.evict_compact()
     torch.cuda.synchronize()
     st = bad.counters(check=False)
-    assert st.device_errors > 0
+    assert st.device_errors == 4 * (H * 8 + B)
     with pytest.raises(lib.ConfKVError) as ei:
         bad.counters()
     assert ei.value.status == lib.binding.ERR_DEVICE
