@@ -246,23 +246,35 @@ class ConfKV:
         self._check(self.lib.conf_kv_lengths(self.h, ln.ctypes.data, n16.ctypes.data), "conf_kv_lengths")
         return ln, n16
 
-    def export(self, layer: int, b: int, kv_head: int):
+    def export(self, layer: int, b: int, kv_head: int, planes=None):
+        """Position-sorted view of one unit.  `planes` limits the copy to some of "pos", "ema",
+        "is16", "k16", "v16", "k8", "v8", "ks", "vs" (the others get NULL pointers and are absent
+        from the result); None fetches everything."""
         c = self.cfg
         cap, D = c.capacity, c.head_dim
-        pos = np.zeros(cap, np.int32); ema = np.zeros(cap, np.float32); is16 = np.zeros(cap, np.uint8)
-        k16 = np.zeros((cap, D), np.uint16); v16 = np.zeros((cap, D), np.uint16)
-        k8 = np.zeros((cap, D), np.int8); v8 = np.zeros((cap, D), np.int8)
         chan = c.scale_mode == SCALE_MODES["channel"]       # then ks / vs are the channel scales [D]
-        ks = np.zeros(max(cap, D), np.uint16); vs = np.zeros(max(cap, D), np.uint16)
+        want = (lambda name: planes is None or name in planes)
+        shapes = dict(pos=(cap, np.int32), ema=(cap, np.float32), is16=(cap, np.uint8), k16=((cap, D), np.uint16),
+                      v16=((cap, D), np.uint16), k8=((cap, D), np.int8), v8=((cap, D), np.int8),
+                      ks=(max(cap, D), np.uint16), vs=(max(cap, D), np.uint16))
+        buf = {name: np.zeros(shape, dt) for name, (shape, dt) in shapes.items() if want(name)}
+        ptr = lambda name: buf[name].ctypes.data if name in buf else None
         n = C.c_int32(0)
-        self._check(self.lib.conf_kv_export(self.h, layer, b, kv_head, pos.ctypes.data, ema.ctypes.data,
-                                            is16.ctypes.data, k16.ctypes.data, v16.ctypes.data,
-                                            k8.ctypes.data, v8.ctypes.data, ks.ctypes.data, vs.ctypes.data,
+        self._check(self.lib.conf_kv_export(self.h, layer, b, kv_head, ptr("pos"), ptr("ema"), ptr("is16"),
+                                            ptr("k16"), ptr("v16"), ptr("k8"), ptr("v8"), ptr("ks"), ptr("vs"),
                                             C.addressof(n)), "conf_kv_export")
         m = n.value
-        return dict(n=m, pos=pos[:m], ema=ema[:m], is16=is16[:m].astype(bool),
-                    k16=k16[:m].view(np.float16), v16=v16[:m].view(np.float16), k8=k8[:m], v8=v8[:m],
-                    ks=ks[:D if chan else m].view(np.float16), vs=vs[:D if chan else m].view(np.float16))
+        out = dict(n=m)
+        for name, x in buf.items():
+            if name in ("ks", "vs"):
+                out[name] = x[:D if chan else m].view(np.float16)
+            elif name in ("k16", "v16"):
+                out[name] = x[:m].view(np.float16)
+            elif name == "is16":
+                out[name] = x[:m].astype(bool)
+            else:
+                out[name] = x[:m]
+        return out
 
     def import_unit(self, layer: int, b: int, kv_head: int, view: dict):
         """`view` is what export() returns (n, pos, ema, is16, k16, v16, k8, v8, ks, vs)."""

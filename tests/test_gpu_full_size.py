@@ -1,11 +1,11 @@
-"""Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+"""Variants and edge shapes at full size (the five workloads themselves, at their full step
+counts, are in test_gpu_configs.py).
 
 The GPU runs every unit; the float64 oracle follows a seeded sample of units (units evolve
-independently given their inputs and their sequence's budget).  Long runs are truncated to
-a few decode steps here so the suite stays within minutes; the first step is always the
-heaviest one (full prompt length, largest eviction).  Properties that hold at any size are
-checked on ALL units from the GPU state: lengths within budget, FP16 window respected,
-positions strictly increasing with the protected window intact, EMA mass conservation.
+independently given their inputs and their sequence's budget) for a few decode steps; the
+first step is always the heaviest one (full prompt length, largest eviction).  Properties that
+hold at any size are checked on ALL units from the GPU state: lengths within budget, FP16
+window respected, positions strictly increasing with the protected window intact.
 """
 import os
 import sys
@@ -20,13 +20,6 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from harness import Lockstep  # noqa: E402
 
 pytestmark = pytest.mark.gpu
-
-# workload index -> (decode steps run here, oracle-followed units, layers kept, logit run length)
-# The logit schedule alternates between uncertain and confident runs of 32 steps; the truncated
-# runs here use runs of 3 steps (same shapes, same values per step kind) so that both budgets,
-# and the large eviction at a loose -> tight switch, occur at full size.
-PLAN = {0: (12, 24, None, 3), 1: (1, 12, None, None), 2: (7, 6, 16, 3), 3: (4, 2, 4, None), 4: (7, 8, 8, 3)}
-
 
 def _invariants_all_units(ls, wl, step):
     kv = ls.kv
@@ -48,32 +41,6 @@ def _invariants_all_units(ls, wl, step):
         newest = wl.prefill + step
         assert np.array_equal(pos[-P:], np.arange(newest - P + 1, newest + 1))  # protected window kept
         assert not ex["is16"][:ex["n"] - n16[l, b, g]].any() and ex["is16"][ex["n"] - n16[l, b, g]:].all()
-
-
-@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
-def test_full_size_workload(lib, idx):
-    steps, units, layers, run = PLAN[idx]
-    wl = workload(idx)
-    if run is not None:
-        wl = wl.scaled(logit_run=run)
-    if layers is not None and layers < wl.n_layers:
-        # fewer layers bound the host-side generation time; per-layer shapes stay at full size
-        wl = wl.scaled(n_layers=layers, n_tight=wl.n_tight[:layers], n_loose=wl.n_loose[:layers])
-    print(f"full-size workload {idx}: {wl.name} layers={wl.n_layers} units={wl.units} steps={steps} "
-          f"oracle units={units}", flush=True)
-    ls = Lockstep(lib, wl, seed=0, units=units, threads=16)
-    print(f"  attend splits: {ls.kv.attend_splits(0)}", flush=True)
-    for t in range(steps):
-        ls.step()
-        _invariants_all_units(ls, wl, t)
-        print(f"  step {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
-    rep = ls.report
-    st = ls.kv.counters()
-    print(f"  conf_err={rep.max_conf_err:.2e} ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
-          f"ties(evict/budget)={rep.evict_ties}/{rep.budget_ties} flips={rep.evict_flips}/{rep.budget_flips}", flush=True)
-    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
-    assert st.device_errors == 0
-    ls.close()
 
 
 def test_full_size_channel_scales(lib):
