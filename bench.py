@@ -30,10 +30,36 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per conf_kv_attend launch on the default workload from hardware counters
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scale factors from a plain 1 GiB copy); the runs and
-# readings are in profiles/bench_llama3_8b_b8_t4096_hbm_counters.txt.  None for other workloads.
-COUNTER_TRAFFIC_BYTES = {1: int((35433.8 * 2.0 + 1668.0) * 1024)}
+DTYPE = "int8+fp16 storage, fp16 mfma, fp32 accumulate"
+# HBM bytes per conf_kv_attend launch on the default workload come from the tracked counter
+# summary (two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by
+# what the same counter reads for a plain 1 GiB device copy): parsed at run time, so the figure
+# cannot outlive the file it came from.
+COUNTER_FILE = {1: os.path.join(ROOT, "profiles", "bench_llama3_8b_b8_t4096_hbm_counters.txt")}
+
+
+def counter_traffic(workload_index, kernel="attend_mfma_kernel"):
+    """(bytes per launch, file name) from the tracked FETCH_SIZE / WRITE_SIZE summary, or (None, None)."""
+    path = COUNTER_FILE.get(workload_index)
+    if not path or not os.path.exists(path):
+        return None, None
+    mean = {}
+    for line in open(path):
+        if line.startswith("#") or "mean=" not in line:
+            continue
+        for ctr in ("FETCH_SIZE", "WRITE_SIZE"):
+            if f" {ctr} " in line:
+                who = "copy" if "copyBuffer" in line else kernel if kernel in line else None
+                if who:
+                    mean[(who, ctr)] = float(line.split("mean=")[1])
+    try:
+        copy_kib = float(1 << 20)                       # the calibration copy reads and writes 1 GiB
+        scale_f = copy_kib / mean[("copy", "FETCH_SIZE")]
+        scale_w = copy_kib / mean[("copy", "WRITE_SIZE")]
+        kib = mean[(kernel, "FETCH_SIZE")] * scale_f + mean[(kernel, "WRITE_SIZE")] * scale_w
+    except (KeyError, ZeroDivisionError):
+        return None, None
+    return int(kib * 1024), os.path.relpath(path, ROOT)
 
 
 def attend_bytes_per_launch(wl, n8, n16):
@@ -101,8 +127,9 @@ def read_probe(torch, pkg, launch_bytes):
             "torch_sum_stream_GBps": gb(x.numel() * 4, big_t), "torch_sum_per_launch_GBps": gb(per * 4, reg_t)}
 
 
-def cpu_baseline(wl, seed, budget_s=15.0):
-    """The oracle, as it stands, on a bounded sample of units of the same workload."""
+def _cpu_worker(job):
+    """One oracle worker: `count` seeded units of the workload, timing attend + evict/compact/demote."""
+    wl, seed, worker, count, tight = job
     from threadpoolctl import threadpool_limits
     from oracle import confkv_oracle as O
     from synth import generate as gen
@@ -110,15 +137,10 @@ def cpu_baseline(wl, seed, budget_s=15.0):
     from harness import policy_of
     pol = policy_of(wl)
     G = wl.group
-    rng = np.random.default_rng(seed)
-    done, t_total = 0, 0.0
-    logits = gen.step_logits(wl, seed, 0)
+    rng = np.random.default_rng([seed, worker])
+    times = []
     with threadpool_limits(limits=1):
-        t0 = time.perf_counter()
-        c = O.confidence(logits[0], pol.weights)
-        t_conf = time.perf_counter() - t0
-        tight = c >= pol.tau
-        while t_total < budget_s and done < 64:
+        for _ in range(count):
             l, b, g = int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch)), int(rng.integers(wl.n_kv_heads))
             K, V = gen.prefill_unit(wl, seed, l, b, g)
             u = O.load_prefill(K, V, wl.fp16_window, scale_mode=getattr(wl, "scale_mode", "token"))
@@ -127,14 +149,39 @@ def cpu_baseline(wl, seed, budget_s=15.0):
             O.attend_unit(u, q[b, g * G:(g + 1) * G], kn[b, g], vn[b, g], wl.prefill, pol.sm_scale, pol.ema_decay)
             N = pol.n_tight[l] if tight else pol.n_loose[l]
             O.evict_compact_unit(u, N, pol.protected, pol.alpha, pol.fp16_window)
-            t_total += time.perf_counter() - t0
-            done += 1
-    per_unit = t_total / done
-    step_s = per_unit * wl.units + t_conf * wl.batch
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
-            "sample": f"{done} of {wl.units} units of workload {wl.name} (attend + evict/compact/demote, "
-                      f"{per_unit * 1e3:.2f} ms per unit) plus 1 of {wl.batch} confidence rows "
-                      f"({t_conf * 1e3:.2f} ms), single thread, extrapolated to all units"}
+            times.append(time.perf_counter() - t0)
+    return times
+
+
+def cpu_baseline(wl, seed, units_per_core=8):
+    """The oracle, as it stands, on a bounded sample of units of the same workload, one process
+    per host core this process may run on (at most 16, the machine's CPU share).  Must run before the
+    GPU is initialised: the workers are forked."""
+    import multiprocessing as mp
+    from oracle import confkv_oracle as O
+    from synth import generate as gen
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import policy_of
+    pol = policy_of(wl)
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    logits = gen.step_logits(wl, seed, 0)
+    t0 = time.perf_counter()
+    c = O.confidence(logits[0], pol.weights)
+    t_conf = time.perf_counter() - t0
+    tight = bool(c >= pol.tau)
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(cores) as pool:
+        per = pool.map(_cpu_worker, [(wl, seed, w, units_per_core, tight) for w in range(cores)])
+    wall = time.perf_counter() - t0
+    times = np.concatenate([np.asarray(p) for p in per])
+    per_unit = float(times.mean())                      # with all cores busy at once
+    step_s = (per_unit * wl.units + t_conf * wl.batch) / cores
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{times.size} of {wl.units} units of workload {wl.name} (attend + evict/compact/demote, "
+                      f"{per_unit * 1e3:.2f} ms per unit with {cores} processes busy) plus 1 of {wl.batch} confidence "
+                      f"rows ({t_conf * 1e3:.2f} ms); extrapolated to all units spread over the {cores} cores "
+                      f"(os.cpu_count() = {os.cpu_count()}, affinity = {len(os.sched_getaffinity(0))}; "
+                      f"sample took {wall:.1f} s)"}
 
 
 def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
@@ -184,8 +231,9 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
     print(json.dumps({
         "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "mode": "steady-state", "layers": L, "batch": wl.batch,
+        "scaling": "weak", "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
+        "config": {"workload": wl.name, "mode": "steady-state", "layers": L, "batch": wl.batch, "layout": args.layout,
+                   "evict_page": args.evict_page,
                    "mean_cache_len": float(r[:, 5].mean()), "attend_splits": kv.attend_splits(0)},
         "roofline": {"bound": "hbm", "kernel": "attend", "achieved": att_gbps, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": att_gbps / HBM_PEAK_GBS, "traffic": None,
@@ -217,6 +265,8 @@ def main():
                     help="tokens per attention call (conf_kv_attend_chunk when above 1; at most 16 / group size)")
     ap.add_argument("--evict-page", type=int, default=0,
                     help="coarsened eviction: whole pages of this many original positions go (0 = token level)")
+    ap.add_argument("--layout", choices=["contiguous", "paged"], default="contiguous",
+                    help="paged: INT8 slots in pages of --evict-page slots behind a block table (no row moves)")
     ap.add_argument("--rank-scope", choices=["kv_head", "layer"], default="kv_head",
                     help="layer: one kept set per (layer, sequence) from the importance summed over its kv-heads")
     ap.add_argument("--copy-probe", action="store_true",
@@ -227,6 +277,11 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    cpu = None
+    if not (args.no_cpu_baseline or args.copy_probe or args.steady):
+        # (before anything touches the GPU: the oracle's workers are forked)
+        from synth.workloads import workload as _workload
+        cpu = cpu_baseline(_workload(args.workload), args.seed)
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -251,6 +306,8 @@ def main():
         wl = wl.scaled(name=wl.name + f"_chunk{args.chunk}", max_chunk=args.chunk)
     if args.evict_page > 1:
         wl = wl.scaled(name=wl.name + f"_page{args.evict_page}", evict_page=args.evict_page)
+    if args.layout != "contiguous":
+        wl = wl.scaled(name=wl.name + "_" + args.layout, layout=args.layout)
     if args.rank_scope != "kv_head":
         wl = wl.scaled(name=wl.name + "_layer_scope", rank_scope=args.rank_scope)
     if args.layers and args.layers < wl.n_layers:
@@ -329,19 +386,22 @@ def main():
     moved = (st.compact_bytes - moved0) / args.steps
     total_bytes, att_total = step_bytes(wl, n8_b, n16_b, moved)
     achieved = att_bytes / (att_launch_ms * 1e-3) / 1e9
+    plain = (args.scales == "token" and tq == 1 and not args.layers and args.evict_page <= 1
+             and args.rank_scope == "kv_head" and args.layout == "contiguous")
+    traffic, traffic_file = counter_traffic(args.workload) if plain else (None, None)
     result = {
         "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": wl.name, "layers": L, "batch": wl.batch, "q_heads": wl.n_q_heads,
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "vocab": wl.vocab,
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
-                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "evict_page": args.evict_page, "rank_scope": args.rank_scope, "attend_splits": kv.attend_splits(0),
+                   "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "evict_page": args.evict_page, "layout": args.layout, "rank_scope": args.rank_scope, "attend_splits": kv.attend_splits(0),
                    "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
         "roofline": {"bound": "hbm", "kernel": ("attend_mfma_kernel<16>" if tq > 1 else f"attend_mfma_kernel<{wl.group}>") if (tq > 1 or wl.group > 1) and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload) if args.scales == "token" and tq == 1 else None, "bytes_per_launch": att_bytes,
+                     "traffic": traffic, "traffic_source": traffic_file, "bytes_per_launch": att_bytes,
                      "launch_ms": att_launch_ms},
         "step_breakdown_ms": {"attend_x_layers": float(np.mean(t_att)), "confidence": float(np.mean(t_conf)),
                               "evict_compact": float(np.mean(t_evict))},
@@ -349,8 +409,8 @@ def main():
                      "frac_of_peak": total_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "attend_GBps": att_total / (float(np.mean(t_att)) * 1e-3) / 1e9},
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, args.seed)
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     kv.close()
     del kv, prompts
     torch.cuda.empty_cache()

@@ -99,7 +99,28 @@ typedef struct conf_kv_config {
                                 slots over max(budget, protected_window) then remain).
                                 capacity must hold max(n_loose, protected_window + g - 1) plus
                                 the appended tokens                                            */
+  int32_t layout;            /* conf_kv_layout: where the INT8 slots of a unit live              */
 } conf_kv_config;
+
+typedef enum conf_kv_layout {
+  CONF_KV_LAYOUT_CONTIGUOUS = 0, /* the paper's layout ("Cache manager": gather survivors into
+                                    contiguous storage): slots in position order in one ring per
+                                    plane; an eviction moves the rows on the cheaper side of
+                                    the holes                                                    */
+  CONF_KV_LAYOUT_PAGED = 1       /* the alternative "Compatibility with serving systems" and
+                                    "Limitations" name for paged serving stacks: the INT8 slots
+                                    of a unit live in pages of evict_page slots reached through a
+                                    per-unit block table; a page holds the tokens whose original
+                                    positions share floor(position / evict_page); attention reads
+                                    rows through the table; evicting a page edits the table and
+                                    moves no row.  Needs coarsened eviction (evict_page a power
+                                    of two, 8 .. 1024), a mixed cache with fp16_window <=
+                                    protected_window (so that only whole INT8 pages can go),
+                                    per-token scales, the per-kv-head ranking scope, a group of
+                                    2 .. 8 query heads and single-token attention calls;
+                                    conf_kv_import is not available.  conf_kv_export returns the
+                                    same position-sorted view as under the contiguous layout     */
+} conf_kv_layout;
 
 typedef enum conf_kv_scale_mode {
   CONF_KV_SCALES_TOKEN = 0,     /* one scale per token and kv-head (absmax over the channels),

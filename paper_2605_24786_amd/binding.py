@@ -32,13 +32,14 @@ class ConfKVConfig(C.Structure):
         ("n_tight", C.POINTER(C.c_int32)), ("n_loose", C.POINTER(C.c_int32)),
         ("mass_gain", C.c_float), ("ranker", C.c_int32), ("rank_scope", C.c_int32),
         ("ranker_seed", C.c_uint64), ("scale_mode", C.c_int32), ("max_chunk", C.c_int32),
-        ("evict_page", C.c_int32),
+        ("evict_page", C.c_int32), ("layout", C.c_int32),
     ]
 
 
 RANKERS = {"composite": 0, "random": 1}
 RANK_SCOPES = {"kv_head": 0, "layer": 1}
 SCALE_MODES = {"token": 0, "channel": 1}
+LAYOUTS = {"contiguous": 0, "paged": 1}
 
 
 class ConfKVStats(C.Structure):
@@ -126,7 +127,7 @@ def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacit
                 protected_window, n_tight: Sequence[int], n_loose: Sequence[int], tau=0.7, alpha=0.65,
                 ema_decay=0.9, sm_scale=None, w_entropy=0.4, w_margin=0.3, w_top=0.3, mass_gain=None,
                 ranker="composite", rank_scope="kv_head", ranker_seed=0, scale_mode="token", max_chunk=0,
-                evict_page=0):
+                evict_page=0, layout="contiguous"):
     """A ConfKVConfig plus the two int32 arrays it points to (keep the tuple alive)."""
     nt = (C.c_int32 * len(n_tight))(*[int(x) for x in n_tight])
     nl = (C.c_int32 * len(n_loose))(*[int(x) for x in n_loose])
@@ -137,7 +138,7 @@ def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, vocab, capacit
                        w_entropy, w_margin, w_top, nt, nl,
                        -1.0 if mass_gain is None else float(mass_gain), RANKERS[ranker],
                        RANK_SCOPES[rank_scope], int(ranker_seed), SCALE_MODES[scale_mode], int(max_chunk),
-                       int(evict_page))
+                       int(evict_page), LAYOUTS[layout])
     return cfg, nt, nl
 
 
@@ -312,6 +313,7 @@ def from_workload(wl, **override) -> ConfKV:
               w_top=wl.w_top, mass_gain=getattr(wl, "mass_gain", None),
               ranker=getattr(wl, "ranker", "composite"), rank_scope=getattr(wl, "rank_scope", "kv_head"),
               ranker_seed=getattr(wl, "ranker_seed", 0), scale_mode=getattr(wl, "scale_mode", "token"),
-              max_chunk=getattr(wl, "max_chunk", 0), evict_page=getattr(wl, "evict_page", 0))
+              max_chunk=getattr(wl, "max_chunk", 0), evict_page=getattr(wl, "evict_page", 0),
+              layout=getattr(wl, "layout", "contiguous"))
     kw.update(override)
     return ConfKV(**kw)

@@ -21,7 +21,8 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct StateLayout {
-  size_t len, n8, head16, head8, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, unit_moved, ema, pos, ks, vs, k8, v8, k16, v16, total;
+  size_t len, n8, head16, head8, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, unit_moved, pt, ema, pos, ks, vs, k8, v8, k16, v16, total;
+  int npages;            // paged layout: physical pages per unit (0 otherwise)
   size_t header_bytes;   // [0, header_bytes) is zeroed at create
   int cap8, cap16;
 };
@@ -30,6 +31,16 @@ struct ScratchLayout {
   size_t conf_partial, part_ml, part_o, spill, score, src, sel, shared, total;
   size_t zero_bytes;     // [0, zero_bytes) holds the counters and is zeroed at create
 };
+
+// FP16 ring rows of a mixed cache: the window plus the appended tokens, in whole 16-row tiles.
+int fp16_ring_rows(const conf_kv_config *c) {
+  const long long want = ((long long)c->fp16_window + std::max(1, c->max_chunk) + 15) / 16 * 16;
+  return (int)std::min<long long>(want, c->capacity);
+}
+// Paged layout: INT8 rows in whole pages below the rows that hold the FP16 slots' metadata.
+int paged_rows(const conf_kv_config *c) {
+  return (c->capacity - fp16_ring_rows(c)) / c->evict_page * c->evict_page;
+}
 
 bool config_ok(const conf_kv_config *c) {
   if (!c || !c->n_tight || !c->n_loose) return false;
@@ -51,11 +62,24 @@ bool config_ok(const conf_kv_config *c) {
   if (c->max_chunk > 1 && (c->head_dim != 128 || c->max_chunk * (c->n_q_heads / c->n_kv_heads) > kChunkRows))
     return false;
   if (c->evict_page < 0 || c->evict_page > 1024) return false;
+  if (c->layout != CONF_KV_LAYOUT_CONTIGUOUS && c->layout != CONF_KV_LAYOUT_PAGED) return false;
+  if (c->layout == CONF_KV_LAYOUT_PAGED) {
+    const int g = c->evict_page, G = c->n_q_heads / c->n_kv_heads;
+    if (g < 8 || (g & (g - 1))) return false;                      // a power of two, 8 .. 1024
+    if (c->fp16_window < 0 || c->fp16_window > c->protected_window) return false;
+    if (c->scale_mode != CONF_KV_SCALES_TOKEN || c->rank_scope != CONF_KV_SCOPE_KV_HEAD) return false;
+    if (c->max_chunk > 1 || G < 2 || G > 8) return false;
+  }
   const int page_slack = c->evict_page > 1 ? c->evict_page - 1 : 0;   // slots a page in the window can hold back
   for (int l = 0; l < c->n_layers; ++l) {
     if (c->n_tight[l] < 1 || c->n_tight[l] > c->n_loose[l]) return false;
     if (std::max((long long)c->n_loose[l], (long long)c->protected_window + page_slack) + std::max(1, c->max_chunk) >
         c->capacity)
+      return false;
+    // paged: the whole pages below the FP16 slots' metadata rows must hold the longest INT8 part
+    if (c->layout == CONF_KV_LAYOUT_PAGED &&
+        std::max((long long)c->n_loose[l], (long long)c->protected_window + page_slack) + 1 >
+            (long long)paged_rows(c))
       return false;
   }
   return true;
@@ -66,12 +90,7 @@ StateLayout state_layout(const conf_kv_config *c) {
   const size_t U = (size_t)c->n_layers * c->batch * c->n_kv_heads;
   const size_t cap = c->capacity, D = c->head_dim;
   s.cap8 = c->fp16_window < 0 ? 0 : c->capacity;
-  if (c->fp16_window < 0) {
-    s.cap16 = c->capacity;
-  } else {
-    long long want = ((long long)c->fp16_window + std::max(1, c->max_chunk) + 15) / 16 * 16;
-    s.cap16 = (int)std::min<long long>(want, c->capacity);
-  }
+  s.cap16 = c->fp16_window < 0 ? c->capacity : fp16_ring_rows(c);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   s.len = take(U * 4);
@@ -86,6 +105,8 @@ StateLayout state_layout(const conf_kv_config *c) {
   s.budget = take((size_t)c->n_layers * c->batch * 4);
   s.n_tight = take((size_t)c->n_layers * 4);
   s.n_loose = take((size_t)c->n_layers * 4);
+  s.npages = c->layout == CONF_KV_LAYOUT_PAGED ? paged_rows(c) / c->evict_page : 0;
+  s.pt = take(U * (size_t)s.npages * 4);
   s.ema = take(U * cap * 4);
   s.pos = take(U * cap * 4);
   // per-token scales [U][cap8], or per-channel scales [U][D]
@@ -232,6 +253,11 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   cv.W = cfg->fp16_window;
   cv.P = cfg->protected_window;
   cv.chan = cfg->scale_mode == CONF_KV_SCALES_CHANNEL;
+  cv.pt = (int32_t *)(s + h->sl.pt);
+  cv.npages = h->sl.npages;
+  cv.page_lg = 0;
+  if (cfg->layout == CONF_KV_LAYOUT_PAGED)
+    while ((1 << cv.page_lg) < cfg->evict_page) ++cv.page_lg;
 
   std::vector<int32_t> budget((size_t)L * cfg->batch);
   for (int l = 0; l < L; ++l)
@@ -242,6 +268,12 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   if (e == hipSuccess) e = hipMemset(h->scratch, 0, h->kl.zero_bytes);
   if (e == hipSuccess && cv.chan)      // attention reads the channel scales even before any slot is INT8
     e = hipMemset(cv.ks, 0, (size_t)((uint8_t *)cv.k8 - (uint8_t *)cv.ks));
+  if (e == hipSuccess && cv.npages > 0) {              // every unit's block table starts as the identity
+    const size_t U = (size_t)L * cfg->batch * cfg->n_kv_heads;
+    std::vector<int32_t> ident(U * cv.npages);
+    for (size_t i = 0; i < ident.size(); ++i) ident[i] = (int32_t)(i % cv.npages);
+    e = hipMemcpy(cv.pt, ident.data(), ident.size() * 4, hipMemcpyHostToDevice);
+  }
   if (e == hipSuccess) e = hipMemcpy(cv.budget, budget.data(), budget.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy((void *)cv.n_tight, h->n_tight.data(), (size_t)L * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy((void *)cv.n_loose, h->n_loose.data(), (size_t)L * 4, hipMemcpyHostToDevice);
@@ -278,6 +310,7 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   if (T0 < 0) return CONF_KV_ERR_INVALID_ARG;
   if (T0 > 0 && (!dev_k16 || !dev_v16)) return CONF_KV_ERR_INVALID_ARG;
   if (T0 > h->cfg.capacity - 1) return CONF_KV_ERR_CAPACITY;
+  if (h->cv.page_lg && T0 - h->cfg.fp16_window > (h->cv.npages << h->cv.page_lg)) return CONF_KV_ERR_CAPACITY;
   CK_HIP(h, launch_load_prefill(h->cv, layer, (const __half *)dev_k16, (const __half *)dev_v16, T0,
                                 dev_ema0, (hipStream_t)stream));
   h->len_ub[layer] = T0;
@@ -289,6 +322,11 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   return CONF_KV_OK;
 }
 
+// LDS the attention kernel needs for the unit's block table (paged layout), in whole 16 bytes.
+static size_t table_lds(const conf_kv_handle *h) {
+  return h->cv.page_lg ? ((size_t)h->cv.npages * 4 + 15) / 16 * 16 : 0;
+}
+
 static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan, int observe_first = -1) {
   const bool observe = observe_first >= 0;
   const int n_ub = observe ? observe_first + tq : h->len_ub[layer] + tq;     // slots the call sees
@@ -298,8 +336,10 @@ static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan
   const bool rows16 = tq > 1 || observe || h->cv.G > 8;
   const int rows = rows16 ? kChunkRows : h->cv.G;
   if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, rows16, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
-                   h->forced_splits, h->force_two_launch, plan))
+                   h->forced_splits, h->force_two_launch, table_lds(h), plan))
     return CONF_KV_ERR_BAD_SHAPE;
+  // the paged layout is read by the single-launch matrix-core kernel only
+  if (h->cv.page_lg && (plan->two_launch || !plan->mfma)) return CONF_KV_ERR_BAD_SHAPE;
   return CONF_KV_OK;
 }
 
@@ -354,6 +394,8 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.gq = h->cv.G;
   a.observe_first = observe_first;
   a.kv_major = h->kv_major;
+  a.tab_off = (int)(plan.lds_bytes - table_lds(h));
+  a.trace_off = 0;
   a.withhold = h->withhold;
   a.dbg = nullptr;
 #ifdef CONFKV_TRACE
@@ -503,6 +545,48 @@ int conf_kv_export(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
     if (v_scale) CK_HIP(h, hipMemcpy(v_scale, cv.vs + u * D, D * 2, hipMemcpyDeviceToHost));
   }
   if (n == 0) return CONF_KV_OK;
+  if (cv.page_lg) {
+    // Paged layout: the unit's planes come to the host whole and the view is gathered there
+    // through the block table (INT8 slots) and the FP16 ring (metadata of the FP16 slots).
+    std::vector<int32_t> tab(cv.npages);
+    CK_HIP(h, hipMemcpy(tab.data(), cv.pt + u * cv.npages, (size_t)cv.npages * 4, hipMemcpyDeviceToHost));
+    const int g = 1 << cv.page_lg;
+    auto row_of = [&](int i) {
+      if (i < n8) return tab[i >> cv.page_lg] * g + (i & (g - 1));
+      int r = head + (i - n8);
+      if (r >= cv.cap16) r -= cv.cap16;
+      return cv.cap - cv.cap16 + r;
+    };
+    std::vector<uint8_t> tmp;
+    auto gather = [&](const void *dev_plane, size_t row_bytes, void *out, int count) -> hipError_t {
+      tmp.resize((size_t)cv.cap * row_bytes);
+      hipError_t e = hipMemcpy(tmp.data(), dev_plane, tmp.size(), hipMemcpyDeviceToHost);
+      if (e != hipSuccess) return e;
+      for (int i = 0; i < count; ++i) memcpy((uint8_t *)out + (size_t)i * row_bytes, tmp.data() + (size_t)row_of(i) * row_bytes, row_bytes);
+      return hipSuccess;
+    };
+    if (pos) CK_HIP(h, gather(cv.pos + u * cv.cap, 4, pos, n));
+    if (ema) CK_HIP(h, gather(cv.ema + u * cv.cap, 4, ema, n));
+    if (is_fp16)
+      for (int i = 0; i < n; ++i) is_fp16[i] = i >= n8;
+    if (k8) { CK_HIP(h, gather(cv.k8 + u * cv.cap8 * D, D, k8, n8)); memset(k8 + (size_t)n8 * D, 0, (size_t)n16 * D); }
+    if (v8) { CK_HIP(h, gather(cv.v8 + u * cv.cap8 * D, D, v8, n8)); memset(v8 + (size_t)n8 * D, 0, (size_t)n16 * D); }
+    if (k_scale) { CK_HIP(h, gather(cv.ks + u * cv.cap8, 2, k_scale, n8)); memset(k_scale + n8, 0, (size_t)n16 * 2); }
+    if (v_scale) { CK_HIP(h, gather(cv.vs + u * cv.cap8, 2, v_scale, n8)); memset(v_scale + n8, 0, (size_t)n16 * 2); }
+    for (int which = 0; which < 2; ++which) {
+      uint16_t *d16 = which ? v16 : k16;
+      if (!d16) continue;
+      const __half *p16 = (which ? cv.v16 : cv.k16) + u * cv.cap16 * D;
+      memset(d16, 0, (size_t)n8 * D * 2);
+      if (n16 > 0) {
+        const int first = std::min(n16, cv.cap16 - head);
+        CK_HIP(h, hipMemcpy(d16 + (size_t)n8 * D, p16 + (size_t)head * D, (size_t)first * D * 2, hipMemcpyDeviceToHost));
+        if (n16 > first)
+          CK_HIP(h, hipMemcpy(d16 + (size_t)(n8 + first) * D, p16, (size_t)(n16 - first) * D * 2, hipMemcpyDeviceToHost));
+      }
+    }
+    return CONF_KV_OK;
+  }
   const int firstm = std::min(n, cv.cap - head8);     // per-slot planes: entries before the wrap
   if (pos) {
     CK_HIP(h, hipMemcpy(pos, cv.pos + u * cv.cap + head8, (size_t)firstm * 4, hipMemcpyDeviceToHost));
@@ -561,7 +645,7 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   if (b < 0 || b >= h->cfg.batch || kv_head < 0 || kv_head >= h->cfg.n_kv_heads || n < 0)
     return CONF_KV_ERR_INVALID_ARG;
   if (n > h->cfg.capacity - 1) return CONF_KV_ERR_CAPACITY;
-  if (h->appended[layer]) return CONF_KV_ERR_BAD_STATE;
+  if (h->appended[layer] || h->cv.page_lg) return CONF_KV_ERR_BAD_STATE;   // (no import into the paged layout)
   if (n > 0 && (!pos || !ema || !is_fp16)) return CONF_KV_ERR_INVALID_ARG;
   const CacheView &cv = h->cv;
   int n8 = 0;

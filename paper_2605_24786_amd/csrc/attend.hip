@@ -149,6 +149,7 @@ struct Slice {
   int lo8, hi8;                // INT8 slots of this split
   int lo16, hi16;              // FP16 slots of this split (slot numbers, >= n8)
   int cnt8, ntok;              // hi8 - lo8, and cnt8 + (hi16 - lo16)
+  const int32_t *tab;          // paged layout: the unit's block table (device memory, or a copy in LDS)
   // stash index t in [0, ntok) <-> slot
   __device__ __forceinline__ int slot_of(int t) const { return t < cnt8 ? lo8 + t : lo16 + (t - cnt8); }
 };
@@ -178,6 +179,7 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
   s.ul = unit_in_layer(cv, a);
   s.j = split_index(a);
   s.u = a.layer * cv.B * cv.Hkv + s.ul;
+  s.tab = cv.pt + (size_t)s.u * cv.npages;
   // The unit's four counters in ONE round trip: lanes 0..3 of every wavefront read one array
   // each with a single load instruction (four scalar loads get spread over the prologue by the
   // compiler, each waiting for the one before).
@@ -229,7 +231,7 @@ __device__ __forceinline__ void append_new_token(const CacheView &cv, const Atte
     ((int4 *)dst)[c] = ((const int4 *)src)[c];
   }
   if (tid < a.tq)
-    cv.pos[(size_t)s.u * cv.cap + ring_row_u(s.h8, s.n - a.tq + tid, cv.cap)] = a.pos_new + tid;
+    cv.pos[(size_t)s.u * cv.cap + slot_row(cv, s.tab, s.h8, s.n8, s.h16, s.n - a.tq + tid)] = a.pos_new + tid;
   if constexpr (kSync) __syncthreads();
 }
 
@@ -566,7 +568,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     // branch-free (a slot past the slice re-reads its last one; the appended token's slot
     // holds a stale value): the uses below mask both cases
     const int slot = sl.slot_of(max(0, min(tid + k * kAttThreads, sl.ntok - 1)));   // an empty slice reads slot lo16 < n
-    ema_old[k] = EMA[ring_row_u(sl.h8, slot, cv.cap)];
+    ema_old[k] = EMA[slot_row(cv, sl.tab, sl.h8, sl.n8, sl.h16, slot)];
   }
   // The softmax statistics go out first: thread h merges row h's (m, l) over the wavefront
   // partials (the same operations, in the same order, as the output merge below) and publishes
@@ -765,7 +767,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       for (int h = 0; h < G; ++h) A += (double)exp_nonpos(stash[h * S + t] - gm[h]) * gw[h];
       const int slot = sl.slot_of(t);
       const double old = (slot >= first_new) ? 0.0 : (double)ema_old[k];   // a new token starts at 0
-      EMA[ring_row_u(sl.h8, slot, cv.cap)] = (float)(lam * old + oml * A);
+      EMA[slot_row(cv, sl.tab, sl.h8, sl.n8, sl.h16, slot)] = (float)(lam * old + oml * A);
     }
   }
   TS(30);
@@ -778,7 +780,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
     int row[kBatch];
 #pragma unroll
     for (int k = 0; k < kBatch; ++k) {
-      row[k] = ring_row_u(sl.h8, sl.slot_of(min(t0 + k * kAttThreads, sl.ntok - 1)), cv.cap);
+      row[k] = slot_row(cv, sl.tab, sl.h8, sl.n8, sl.h16, sl.slot_of(min(t0 + k * kAttThreads, sl.ntok - 1)));
       old[k] = EMA[row[k]];
     }
 #pragma unroll
@@ -1035,8 +1037,24 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   asm volatile("" ::"s"(cv.k8), "s"(cv.v8), "s"(cv.ks), "s"(cv.vs), "s"(cv.k16), "s"(cv.v16), "s"(cv.len),
                "s"(cv.n8), "s"(cv.head16), "s"(cv.head8), "s"(cv.cap8), "s"(cv.cap16), "s"(cv.Hkv), "s"(cv.B),
                "s"(a.layer), "s"(a.tq), "s"(a.observe_first), "s"(a.q), "s"(a.knew), "s"(a.vnew));
-  const Slice sl = make_slice(cv, a, ns, S);
+  // Paged layout: the unit's block table comes into LDS (requested before the counters, so both
+  // trips overlap); every INT8 row address below goes through it.
+  int32_t *tab = (int32_t *)((char *)smem + a.tab_off);
+  if (cv.page_lg) {
+    const int32_t *gt = cv.pt + (size_t)(a.layer * cv.B * cv.Hkv + unit_in_layer(cv, a)) * cv.npages;
+    for (int i = tid; i < cv.npages; i += kAttThreads) tab[i] = gt[i];
+  }
+  Slice sl = make_slice(cv, a, ns, S);
+  if (cv.page_lg) {
+    sl.tab = tab;
+    __syncthreads();
+  }
   TS(2);
+  const int page_lg = cv.page_lg, page_mask = (1 << cv.page_lg) - 1;
+  // row of INT8 slot i in the INT8 planes
+  auto row8 = [&](int i) -> unsigned {
+    return page_lg ? (unsigned)((tab[i >> page_lg] << page_lg) | (i & page_mask)) : (unsigned)ring_row_u(sl.h8, i, cv.cap8);
+  };
   const int t16 = lane & 15, g4 = lane >> 4;    // MFMA operand coordinates of this lane
   const int c8 = lane & 7, r8 = lane >> 3;      // global-load coordinates: 16-byte piece, row
   const int8_t *K8 = cv.k8 + (size_t)sl.u * cv.cap8 * DR;
@@ -1058,11 +1076,10 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     const int last = sl.hi8 - 1;
     // 32-bit byte offsets from the unit's (wavefront-uniform) plane bases
     const unsigned col = (unsigned)(c8 & (DR / 16 - 1)) * 16u;
-    const int h8 = sl.h8, cap8 = cv.cap8;
-    const unsigned o0 = (unsigned)ring_row_u(h8, min(base + r8, last), cap8) * DR + col;
-    const unsigned o1 = (unsigned)ring_row_u(h8, min(base + 8 + r8, last), cap8) * DR + col;
-    const unsigned o2 = (unsigned)ring_row_u(h8, min(base + 16 + r8, last), cap8) * DR + col;
-    const unsigned o3 = (unsigned)ring_row_u(h8, min(base + 24 + r8, last), cap8) * DR + col;
+    const unsigned o0 = row8(min(base + r8, last)) * DR + col;
+    const unsigned o1 = row8(min(base + 8 + r8, last)) * DR + col;
+    const unsigned o2 = row8(min(base + 16 + r8, last)) * DR + col;
+    const unsigned o3 = row8(min(base + 24 + r8, last)) * DR + col;
     t.k0 = *(const int4 *)(K8 + o0);
     t.v0 = *(const int4 *)(V8 + o0);
     t.k1 = *(const int4 *)(K8 + o1);
@@ -1072,8 +1089,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
     t.k3 = *(const int4 *)(K8 + o3);
     t.v3 = *(const int4 *)(V8 + o3);
     if constexpr (!kChan) {
-      const unsigned j0 = (unsigned)ring_row_u(h8, min(base + t16, last), cap8);
-      const unsigned j1 = (unsigned)ring_row_u(h8, min(base + 16 + t16, last), cap8);
+      const unsigned j0 = row8(min(base + t16, last));
+      const unsigned j1 = row8(min(base + 16 + t16, last));
       t.ks0 = ((const unsigned short *)KS)[j0];
       t.vs0 = ((const unsigned short *)VS)[j0];
       t.ks1 = ((const unsigned short *)KS)[j1];
@@ -1529,7 +1546,7 @@ static size_t attend_lds_bytes(int D, int G, int S, bool mfma) {
     const int NP = kAttWaves;
     size_t floats = (size_t)G * S + G + 2 + 2 * NP * G;
     size_t tiles = std::max<size_t>((size_t)kAttWaves * kTileBytes, (size_t)NP * G * 128 * sizeof(float));
-    return floats * sizeof(float) + (size_t)2 * G * sizeof(double) + tiles + 32;
+    return (floats * sizeof(float) + (size_t)2 * G * sizeof(double) + tiles + 32 + 15) / 16 * 16;
   }
   size_t floats = (size_t)G * S + (size_t)kAttWaves * G * D + 2 * kAttWaves * G + G + 2;
   return floats * sizeof(float) + (size_t)2 * G * sizeof(double) + 16;
@@ -1589,7 +1606,7 @@ static int attend_occupancy(AttendFn fn, size_t lds) {
 }
 
 bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
-                 bool force_two_launch, AttendPlan *plan) {
+                 bool force_two_launch, size_t extra_lds, AttendPlan *plan) {
   const DeviceLimits &lim = device_limits();
   if (!lim.ok) return false;
   if (chunk ? attend_fn_mfma(D, G, chan) == nullptr : attend_fn_valu(D, G) == nullptr) return false;
@@ -1618,10 +1635,10 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
     const int need = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
     int S = (need + 255) / 256 * 256;
-    size_t lds = attend_lds_bytes(D, G, S, mfma);
+    size_t lds = attend_lds_bytes(D, G, S, mfma) + extra_lds;
     if (lds > lim.max_lds) {                    // a tight fit: give the rounding up
       S = (need + 31) / 32 * 32;
-      lds = attend_lds_bytes(D, G, S, mfma);
+      lds = attend_lds_bytes(D, G, S, mfma) + extra_lds;
     }
     if (lds > lim.max_lds) continue;
     if (ns > 1) {
@@ -1646,7 +1663,7 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
     const int ns = want;
     int S = (n_ub + ns - 1) / ns + (n16_ub + ns - 1) / ns + 34;
     S = (S + 255) / 256 * 256;
-    const size_t lds = attend_lds_bytes(D, G, 0, mfma);
+    const size_t lds = attend_lds_bytes(D, G, 0, mfma) + extra_lds;
     if (lds > lim.max_lds) return false;
     if (lds > 64 * 1024) (void)attend_occupancy(attend_fn_mfma_spill(D, G, chan), lds);   // raises the dynamic-LDS limit
     plan->splits = ns;

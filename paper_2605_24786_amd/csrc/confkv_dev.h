@@ -43,7 +43,28 @@ struct CacheView {
   unsigned long long *unit_moved;          // [U] per-unit compaction traffic
   int32_t L, B, Hkv, G, D, cap, cap8, cap16, W, P;
   int32_t chan;                            // INT8 scales are per (unit, channel), not per token
+  // Paged layout (page_lg > 0): the INT8 slots of a unit live in pages of 2^page_lg rows of the
+  // INT8 planes, reached through the unit's block table pt[u][0 .. npages): entries
+  // [0, ceil(n8 / page)) are the live pages in slot order, the rest the free ones, so the table
+  // is always a permutation of the physical pages.  Slot i < n8 (codes, scales, EMA, position)
+  // lives in row pt[u][i >> page_lg] * page + (i & (page - 1)); the EMA and position of an FP16
+  // slot i >= n8 live in row cap - cap16 + (its FP16 ring row); head8 stays 0.
+  int32_t *pt;
+  int32_t page_lg, npages;
 };
+
+// Row of slot i in the planes anchored at the oldest slot (EMA, position; for i < n8 also the
+// INT8 codes and per-token scales), in either layout.  tab: the unit's block table.
+__device__ __forceinline__ int slot_row(const CacheView &cv, const int32_t *tab, int h8, int n8, int h16, int i) {
+  if (cv.page_lg == 0) {
+    const unsigned r = (unsigned)(h8 + i);
+    return (int)min(r, r - (unsigned)cv.cap);
+  }
+  if (i < n8) return (tab[i >> cv.page_lg] << cv.page_lg) | (i & ((1 << cv.page_lg) - 1));
+  int r = h16 + (i - n8);
+  r = r >= cv.cap16 ? r - cv.cap16 : r;
+  return cv.cap - cv.cap16 + r;
+}
 
 // Per layer: tokens appended by conf_kv_attend / conf_kv_attend_chunk since the last commit.
 struct LayerMask {

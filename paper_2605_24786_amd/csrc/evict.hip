@@ -138,12 +138,16 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
     cv.head16[u] = 0;
     cv.head8[u] = 0;
   }
+  if (cv.page_lg && blockIdx.x == 0)                // paged layout: the block table starts over as the identity
+    for (int i = threadIdx.x; i < cv.npages; i += kEvThreads) cv.pt[(size_t)u * cv.npages + i] = i;
   if (t >= T0) return;
   const __half *ksrc = k16 + ((size_t)ul * T0 + t) * D;
   const __half *vsrc = v16 + ((size_t)ul * T0 + t) * D;
   if (lane == 0) {
-    cv.pos[(size_t)u * cv.cap + t] = t;
-    cv.ema[(size_t)u * cv.cap + t] = ema0 ? ema0[(size_t)ul * T0 + t] : 0.f;
+    // (identity table, ring heads 0: INT8 slot t sits in row t, FP16 slot t in metadata row t - n8)
+    const int mrow = (cv.page_lg && t >= n8) ? cv.cap - cv.cap16 + (t - n8) : t;
+    cv.pos[(size_t)u * cv.cap + mrow] = t;
+    cv.ema[(size_t)u * cv.cap + mrow] = ema0 ? ema0[(size_t)ul * T0 + t] : 0.f;
   }
   if (t < n8) {
     if constexpr (D == 128) {
@@ -237,10 +241,13 @@ __device__ __forceinline__ void write_selection(const CacheView &cv, int u, int3
   sel[2] = first_hole;
   sel[3] = evicted;
   sel[4] = last_hole;
-  sel[5] = right;
-  sel[6] = right ? ring_row(h0, fp16_only ? evicted : e8, cv.cap) : h0;
+  sel[5] = cv.page_lg ? 0 : right;
+  sel[6] = cv.page_lg ? 0 : (right ? ring_row(h0, fp16_only ? evicted : e8, cv.cap) : h0);
   sel[7] = 1;                                        // this unit's selection is final
-  if (evicted > 0) {
+  if (evicted > 0 && cv.page_lg) {
+    // paged layout: whole pages leave, the block table is rewritten, no row moves
+    cv.unit_moved[u] += 2ull * 4ull * (unsigned long long)((n8_old + (1 << cv.page_lg) - 1) >> cv.page_lg);
+  } else if (evicted > 0) {
     // traffic of the moves the compaction kernel will make (each row is read and written once)
     const long long meta = right ? right_rows : n_new - min(first_hole, n_new);
     long long rows8 = 0, rows16 = 0;
@@ -340,7 +347,10 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   }
   const float *ema = cv.ema + (size_t)u * cv.cap;
   const int32_t *pos = cv.pos + (size_t)u * cv.cap;
-  const int hm = cv.head8[u], cap = cv.cap;          // slot i of the per-slot planes: ring_row_u(hm, i, cap)
+  const int hm = cv.head8[u];                        // slot i of the per-slot planes: row_of(i)
+  const int h16 = cv.head16[u];
+  const int32_t *tab = cv.pt + (size_t)u * cv.npages;   // paged layout: the unit's block table
+  auto row_of = [&](int i) { return slot_row(cv, tab, hm, n8, h16, i); };
   const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   double *score = score_all + (size_t)u * cv.cap;
   int32_t *src = src_all + (size_t)u * cv.cap;
@@ -350,7 +360,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   // min / max of the importance over the candidates (float -> double is exact and monotone)
   double fmin_ = INFINITY, fmax_ = -INFINITY;
   for (int i = tid; i < ncand; i += kRsThreads) {
-    const double a = shared ? shared[i] : (double)ema[ring_row_u(hm, i, cap)];
+    const double a = shared ? shared[i] : (double)ema[row_of(i)];
     fmin_ = fmin(fmin_, a);
     fmax_ = fmax(fmax_, a);
   }
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
 #pragma unroll
   for (int k = 1; k < kRsWaves; ++k) { a_lo = fmin(a_lo, s_fmin[k]); a_hi = fmax(a_hi, s_fmax[k]); }
   // slots are position-sorted
-  const double p_lo = (double)pos[hm], p_hi = (double)pos[ring_row_u(hm, ncand - 1, cap)];
+  const double p_lo = (double)pos[row_of(0)], p_hi = (double)pos[row_of(ncand - 1)];
   const double a_rng = __dsub_rn(a_hi, a_lo), p_rng = __dsub_rn(p_hi, p_lo);
   const double oma = __dsub_rn(1.0, alpha);
   const Divisor a_div = make_divisor(a_rng == 0.0 ? 1.0 : a_rng), p_div = make_divisor(p_rng == 0.0 ? 1.0 : p_rng);
@@ -371,12 +381,12 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
   for (int i = tid; i < ncand; i += kRsThreads) {
     if (opt.random) {
       const unsigned long long r =
-          splitmix64(opt.seed + (unit_key << 32) + (unsigned long long)(long long)pos[ring_row_u(hm, i, cap)]);
+          splitmix64(opt.seed + (unit_key << 32) + (unsigned long long)(long long)pos[row_of(i)]);
       score[i] = (double)(r >> 11) * 0x1.0p-53;     // exact: 53 bits, power-of-two scale
     } else {
-      const double a = shared ? shared[i] : (double)ema[ring_row_u(hm, i, cap)];
+      const double a = shared ? shared[i] : (double)ema[row_of(i)];
       const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn(a, a_lo), a_div);
-      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[ring_row_u(hm, i, cap)], p_lo), p_div);
+      const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pos[row_of(i)], p_lo), p_div);
       score[i] = __dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh));
     }
   }
@@ -395,11 +405,11 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
     __syncthreads();
     int can = 0;
     for (int i = tid; i < ncand; i += kRsThreads) {
-      const int pid = pos[ring_row_u(hm, i, cap)] / pg;
-      if (i == 0 || pos[ring_row_u(hm, i - 1, cap)] / pg != pid) {
+      const int pid = pos[row_of(i)] / pg;
+      if (i == 0 || pos[row_of(i - 1)] / pg != pid) {
         double tot = 0.0;
         int m = i;
-        while (m < n && pos[ring_row_u(hm, m, cap)] / pg == pid) {
+        while (m < n && pos[row_of(m)] / pg == pid) {
           if (m < ncand) tot = __dadd_rn(tot, score[m]);
           ++m;
         }
@@ -1139,6 +1149,48 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
 }
 
 // ---------------------------------------------------------------------------------------
+// Paged layout: the compaction is an edit of the unit's block table ("Compatibility with
+// serving systems": evicting whole blocks frees them without a gather).  Grid (U / 4), one
+// wavefront per unit, 2 * npages ints of LDS per wavefront.  Under the layout's rules only
+// whole INT8 pages leave, so new page q is the old page that held the source slot of new slot
+// q * page; the pages that left follow the live ones (in their old order), the free ones
+// keep their places behind them.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kEvThreads) void compact_paged_kernel(CacheView cv, const int32_t *__restrict__ src_all,
+                                                                   const int32_t *__restrict__ sel_all, int U) {
+  extern __shared__ int32_t pg_lds[];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int u = blockIdx.x * (kEvThreads / kWave) + w;
+  if (u >= U) return;
+  const int32_t *sel = sel_all + (size_t)u * kSelInts;
+  if (sel[3] == 0) return;                                   // nothing left the unit
+  const int lg = cv.page_lg, g = 1 << lg;
+  const int live_old = (cv.n8[u] + g - 1) >> lg, live_new = (sel[1] + g - 1) >> lg;
+  if (live_old == live_new) return;
+  int32_t *tab = cv.pt + (size_t)u * cv.npages;
+  const int32_t *src = src_all + (size_t)u * cv.cap;
+  int32_t *old = pg_lds + (size_t)w * 2 * cv.npages, *used = old + cv.npages;
+  for (int p = lane; p < live_old; p += kWave) { old[p] = tab[p]; used[p] = 0; }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  for (int q = lane; q < live_new; q += kWave) {
+    const int op = src[q << lg] >> lg;                       // old page of the new page's first slot
+    tab[q] = old[op];
+    used[op] = 1;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  int carry = live_new;
+  for (int base = 0; base < live_old; base += kWave) {
+    const int p = base + lane;
+    const int gone = p < live_old && !used[p];
+    const int rank = wave_scan_incl(gone) - gone;
+    if (gone) tab[carry + rank] = old[p];
+    carry += wave_sum(gone);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // demote: grid (U / 4), one wavefront per unit.  Quantises the oldest FP16 slots until at most W stay
 // FP16, appends them at the INT8 ring tail, and commits (len, n8, head16, head8).
 // ---------------------------------------------------------------------------------------
@@ -1153,9 +1205,17 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
   const int h16 = (cv.cap8 == 0 && sel[5]) ? ring_row(cv.head16[u], sel[3], cv.cap16) : cv.head16[u];
   const int n16 = n_new - n8_new;
   const int cnt = (cv.W < 0) ? 0 : max(0, n16 - cv.W);
+  const int32_t *tab = cv.pt + (size_t)u * cv.npages;          // paged layout (already edited by the compaction)
   for (int t = 0; t < cnt; ++t) {
     const int row = ring_row(h16, t, cv.cap16);
-    const size_t dst = (size_t)u * cv.cap8 + ring_row(h8, n8_new + t, cv.cap8);
+    const int drow = cv.page_lg ? slot_row(cv, tab, 0, n8_new + t + 1, 0, n8_new + t) : ring_row(h8, n8_new + t, cv.cap8);
+    const size_t dst = (size_t)u * cv.cap8 + drow;
+    if (cv.page_lg && lane == 0) {
+      // the slot's EMA and position move from the FP16 slots' metadata rows to its INT8 row
+      const size_t from = (size_t)u * cv.cap + cv.cap - cv.cap16 + row;
+      cv.ema[(size_t)u * cv.cap + drow] = cv.ema[from];
+      cv.pos[(size_t)u * cv.cap + drow] = cv.pos[from];
+    }
     if constexpr (D == 128) {
       if (cv.chan) {
         quantize_row_channels<D>(cv.k16 + ((size_t)u * cv.cap16 + row) * D, cv.k8 + dst * D, cv.ks + (size_t)u * D, lane);
@@ -1238,6 +1298,16 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
   // workgroup per plane is 3 to 4 us faster
   int paired = U >= 4096;
   if (const char *e = getenv("CONF_KV_COMPACT_PAIRED")) paired = atoi(e) != 0;   // test hook: force a form
+  if (cv.page_lg) {
+    // paged layout: a table edit instead of row moves (the ranking above was the general kernel)
+    const size_t lds = (size_t)(kEvThreads / kWave) * 2 * cv.npages * sizeof(int32_t);
+    hipLaunchKernelGGL(compact_paged_kernel, dim3((U + 3) / 4), dim3(kEvThreads), lds, stream, cv, src, sel, U);
+    if (cv.D == 64)
+      hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
+    else
+      hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
+    return hipGetLastError();
+  }
   if (cv.D == 64) {
     hipLaunchKernelGGL(compact_kernel<64>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);

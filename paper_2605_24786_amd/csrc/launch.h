@@ -60,6 +60,7 @@ struct AttendLaunch {
   int kv_major;            // grid is (kv-heads, splits, sequences) instead of (splits, kv-heads, sequences)
   float *spill;            // [units per layer][splits][G][stash_tokens] raw scores (two-launch form)
   unsigned long long *dbg; // phase-trace buffer (CONFKV_TRACE builds), else null
+  int tab_off;             // paged layout: byte offset of the unit's block table in dynamic LDS
   int trace_off;           // byte offset of the time stamps in dynamic LDS (CONFKV_TRACE builds)
 };
 constexpr int kAttendMaxSplits = 64;
@@ -69,8 +70,9 @@ size_t attend_spill_floats(int units_per_layer, int G, int cap);   // scratch th
 // Largest split count and LDS plan for a unit of at most n_ub tokens (after the append)
 // of which at most n16_ub are FP16.  G = query rows per unit (the group size, or kChunkRows for
 // a multi-token call, which only has the single-launch matrix-core form).  Returns false when no plan fits the device.
+// extra_lds: bytes the launch needs behind the kernel's own dynamic LDS (the block table of the paged layout).
 bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
-                 bool force_two_launch, AttendPlan *plan);
+                 bool force_two_launch, size_t extra_lds, AttendPlan *plan);
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream);
 

@@ -45,6 +45,7 @@ class Workload:
     scale_mode: str = "token"            # or "channel": INT8 scales per (kv-head, channel)
     max_chunk: int = 0                   # most tokens per multi-token attend call (0: single-token only)
     evict_page: int = 0                  # > 1: whole pages of that many original positions are evicted
+    layout: str = "contiguous"           # or "paged": INT8 slots in pages of evict_page reached through a block table
     # input recipe
     heavy_hitter_prob: float = 0.02      # fraction of key positions shifted by +3 u
     heavy_hitter_gain: float = 3.0
@@ -71,6 +72,8 @@ class Workload:
         """Slots a unit needs: the longest cache it can ever hold, plus the append."""
         slack = self.evict_page - 1 if self.evict_page > 1 else 0     # a page reaching into the window stays
         longest = max(self.prefill, max(self.n_loose), self.protected + slack) + max(1, self.max_chunk)
+        if self.layout == "paged":           # the FP16 slots' metadata rows and a partly filled page come on top
+            longest += self.fp16_window + 16 + self.evict_page
         return ((longest + 63) // 64) * 64
 
     def scaled(self, **kw) -> "Workload":

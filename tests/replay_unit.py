@@ -53,7 +53,8 @@ def main(path: str) -> None:
             tight = bool(sel[t])
             N = pol.n_tight[l] if tight else pol.n_loose[l]
             gpu_pos = pos_all[off[t]:off[t + 1]].astype(np.int64)
-            keep, evict = O.select_evictions(u, N, pol.protected, pol.alpha)
+            keep, evict = O.select_evictions(u, N, pol.protected, pol.alpha, ranker=pol.ranker, seed=pol.ranker_seed,
+                                             unit_key=(l * pol.batch + b) * pol.n_kv_heads + g, page=pol.evict_page)
             rep.evictions += int(evict.size)
             if np.array_equal(u.pos[keep], gpu_pos):
                 if evict.size:

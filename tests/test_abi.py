@@ -68,7 +68,15 @@ def test_buffer_sizes(clib):
                                  dict(max_chunk=2, head_dim=64), dict(max_chunk=70, n_tight=[64, 64], n_loose=[200, 200]),
                                  dict(scale_mode="channel", head_dim=64), dict(evict_page=-1), dict(evict_page=1025),
                                  dict(evict_page=64, protected_window=200, capacity=256),
-                                 dict(scale_mode="channel", fp16_window=-1)])
+                                 dict(scale_mode="channel", fp16_window=-1),
+                                 # the paged layout: pages a power of two, only whole INT8 pages evictable, ...
+                                 dict(layout="paged"), dict(layout="paged", evict_page=24),
+                                 dict(layout="paged", evict_page=16, fp16_window=32, protected_window=16),
+                                 dict(layout="paged", evict_page=16, fp16_window=-1),
+                                 dict(layout="paged", evict_page=16, protected_window=16, n_q_heads=2),
+                                 dict(layout="paged", evict_page=16, protected_window=16, rank_scope="layer"),
+                                 dict(layout="paged", evict_page=16, protected_window=16, capacity=144),
+                                 dict(_layout=2)])
 def test_bad_configs_are_rejected(clib, bad):
     kw = dict(bad)
     if "n_layers" in kw:
