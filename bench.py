@@ -262,7 +262,7 @@ def main():
     ap.add_argument("--scales", choices=["token", "channel"], default="token",
                     help="granularity of the INT8 scales (channel: the paper's literal per-(head, channel) reading)")
     ap.add_argument("--chunk", type=int, default=1,
-                    help="tokens per attention call (conf_kv_attend_chunk when above 1; at most 16 / group size)")
+                    help="tokens per attention call (conf_kv_attend_chunk when above 1; at most 128 / group size)")
     ap.add_argument("--evict-page", type=int, default=0,
                     help="coarsened eviction: whole pages of this many original positions go (0 = token level)")
     ap.add_argument("--layout", choices=["contiguous", "paged"], default="contiguous",
@@ -399,7 +399,7 @@ def main():
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
                    "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "evict_page": args.evict_page, "layout": args.layout, "rank_scope": args.rank_scope, "attend_splits": kv.attend_splits(0),
                    "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
-        "roofline": {"bound": "hbm", "kernel": ("attend_mfma_kernel<16>" if tq > 1 else f"attend_mfma_kernel<{wl.group}>") if (tq > 1 or wl.group > 1) and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("attend_wide_kernel" if tq * wl.group > 16 else "attend_mfma_kernel<16>" if tq > 1 else f"attend_mfma_kernel<{wl.group}>") if (tq > 1 or wl.group > 1) and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_file, "bytes_per_launch": att_bytes,
                      "launch_ms": att_launch_ms},

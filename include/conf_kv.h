@@ -83,9 +83,10 @@ typedef struct conf_kv_config {
   int32_t rank_scope;        /* conf_kv_rank_scope                                             */
   uint64_t ranker_seed;      /* CONF_KV_RANKER_RANDOM: seed of its counter-based draws         */
   int32_t scale_mode;        /* conf_kv_scale_mode: granularity of the INT8 scales             */
-  int32_t max_chunk;         /* most tokens one conf_kv_attend_chunk call may append; 0 or 1 =
-                                single-token calls only.  Above 1: head_dim 128 and
-                                max_chunk * (n_q_heads / n_kv_heads) <= 16                     */
+  int32_t max_chunk;         /* most tokens one conf_kv_attend_chunk / conf_kv_observe call may
+                                carry; 0 or 1 = single-token calls only.  Above 1: head_dim 128
+                                and max_chunk * (n_q_heads / n_kv_heads) <= 128 query rows per
+                                kv-head; beyond 16 rows per-token scales only                  */
   int32_t evict_page;        /* 0 or 1: tokens are evicted one by one.  g > 1 (at most 1024):
                                 coarsened eviction for paged layouts (the remedy the paper names
                                 in "Compatibility with serving systems" and "Limitations" for
@@ -260,10 +261,21 @@ int conf_kv_attend_chunk(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
  * dev_out16: fp16 [B][tq][Hq][D] attention outputs of those queries, or NULL.
  * Allowed between conf_kv_load_prefill of the layer and its first conf_kv_attend
  * (CONF_KV_ERR_BAD_STATE otherwise), with max_chunk >= 2 (or a group of more than 8 heads, then
- * tq = 1), 1 <= tq <= max(1, max_chunk) and
+ * tq = 1), 1 <= tq <= max(1, max_chunk) (calls of more than 16 / G tokens run on a kernel that
+ * reads the keys twice instead of keeping 16 x slots scores on chip) and
  * 0 <= first, first + tq <= T0 (CONF_KV_ERR_INVALID_ARG). */
 int conf_kv_observe(conf_kv_handle *h, int32_t layer, int32_t first, int32_t tq, const void *dev_q16,
                     void *dev_out16, conf_kv_stream stream);
+
+/* The prompt-phase importance in full (the step before the decode loop; "Related work" names
+ * prompt-phase observation as the neighbouring idea, the paper's own update is "using A" per
+ * decode step): every prompt query observes the prompt causally, as conf_kv_observe over the
+ * consecutive windows first = 0, max_chunk, 2 max_chunk, .. covering all T0 cached tokens, in one
+ * launch sequence.  dev_q16: fp16 [B][T0][Hq][D], the queries of all prompt tokens.  The result is
+ * what T0 single-token decode steps over the stored prompt would have left (see
+ * conf_kv_attend_chunk for the telescoped update).  Same call order rules and errors as
+ * conf_kv_observe; needs max_chunk >= 2. */
+int conf_kv_observe_prompt(conf_kv_handle *h, int32_t layer, const void *dev_q16, conf_kv_stream stream);
 
 /*
  * Confidence estimator and budget selector (Eq. 1; "Budget and ranker"; Algorithm 1,

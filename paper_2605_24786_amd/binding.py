@@ -64,6 +64,7 @@ SYMBOLS = {
     "conf_kv_attend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P]),
     "conf_kv_attend_chunk": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, _P, _P, _P]),
     "conf_kv_observe": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P]),
+    "conf_kv_observe_prompt": (C.c_int, [_P, C.c_int32, _P, _P]),
     "conf_kv_step": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_step_static": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
@@ -228,6 +229,11 @@ class ConfKV:
         tq = int(q16.shape[1])
         return self._check(self.lib.conf_kv_observe(self.h, layer, first, tq, _ptr(q16), _ptr(out16),
                                                     self._stream()), "conf_kv_observe")
+
+    def observe_prompt(self, layer: int, q16):
+        """q16 [B][T0][Hq][D]: the queries of every prompt token of the layer's freshly loaded cache."""
+        return self._check(self.lib.conf_kv_observe_prompt(self.h, layer, _ptr(q16), self._stream()),
+                           "conf_kv_observe_prompt")
 
     def step(self, logits, conf=None, sel=None):
         return self._check(self.lib.conf_kv_step(self.h, _ptr(logits), _ptr(conf), _ptr(sel),

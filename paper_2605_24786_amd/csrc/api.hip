@@ -59,8 +59,13 @@ bool config_ok(const conf_kv_config *c) {
   if (c->scale_mode != CONF_KV_SCALES_TOKEN && c->scale_mode != CONF_KV_SCALES_CHANNEL) return false;
   if (c->scale_mode == CONF_KV_SCALES_CHANNEL && (c->head_dim != 128 || c->fp16_window < 0)) return false;
   if (c->max_chunk < 0) return false;
-  if (c->max_chunk > 1 && (c->head_dim != 128 || c->max_chunk * (c->n_q_heads / c->n_kv_heads) > kChunkRows))
-    return false;
+  // multi-token calls: one tile of 16 query rows per unit, or up to kWideRowsMax rows on the
+  // many-rows kernel (per-token scales only)
+  if (c->max_chunk > 1) {
+    const int rows = c->max_chunk * (c->n_q_heads / c->n_kv_heads);
+    if (c->head_dim != 128 || rows > kWideRowsMax) return false;
+    if (rows > kChunkRows && c->scale_mode != CONF_KV_SCALES_TOKEN) return false;
+  }
   if (c->evict_page < 0 || c->evict_page > 1024) return false;
   if (c->layout != CONF_KV_LAYOUT_CONTIGUOUS && c->layout != CONF_KV_LAYOUT_PAGED) return false;
   if (c->layout == CONF_KV_LAYOUT_PAGED) {
@@ -333,6 +338,11 @@ static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan
   const int W = h->cfg.fp16_window;
   const int n16_ub = W < 0 ? n_ub : std::min(n_ub, observe ? W : W + tq);
   // a chunk runs on the matrix-core body with all 16 tile rows as query rows
+  if (tq * h->cv.G > kChunkRows) {                         // more rows than one tile: the many-rows kernel
+    if (!attend_wide_plan(tq * h->cv.G, h->cfg.batch * h->cfg.n_kv_heads, n_ub, h->forced_splits, plan))
+      return CONF_KV_ERR_BAD_SHAPE;
+    return CONF_KV_OK;
+  }
   const bool rows16 = tq > 1 || observe || h->cv.G > 8;
   const int rows = rows16 ? kChunkRows : h->cv.G;
   if (!attend_plan(h->cfg.head_dim, rows, h->cv.chan != 0, rows16, h->cfg.batch * h->cfg.n_kv_heads, n_ub, n16_ub,
@@ -346,7 +356,7 @@ static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan
 // observe_first < 0: append tq tokens and attend; >= 0: conf_kv_observe
 static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const void *dev_q16,
                          const void *dev_knew16, const void *dev_vnew16, void *dev_out16,
-                         conf_kv_stream stream, int32_t observe_first = -1) {
+                         conf_kv_stream stream, int32_t observe_first = -1, int32_t q_tokens = 0) {
   const bool observe = observe_first >= 0;
   if (!h || !dev_q16) return CONF_KV_ERR_INVALID_ARG;
   if (!observe && (!dev_knew16 || !dev_vnew16 || !dev_out16)) return CONF_KV_ERR_INVALID_ARG;
@@ -391,6 +401,7 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.mass_gain = h->cfg.mass_gain < 0.f ? 1.0 - (double)h->cfg.ema_decay : (double)h->cfg.mass_gain;
   a.pos_new = h->next_pos[layer];
   a.tq = tq;
+  a.q_tokens = q_tokens > 0 ? q_tokens : tq;
   a.gq = h->cv.G;
   a.observe_first = observe_first;
   a.kv_major = h->kv_major;
@@ -432,6 +443,21 @@ int conf_kv_observe(conf_kv_handle *h, int32_t layer, int32_t first, int32_t tq,
                     void *dev_out16, conf_kv_stream stream) {
   if (first < 0) return CONF_KV_ERR_INVALID_ARG;
   return attend_tokens(h, layer, tq, dev_q16, nullptr, nullptr, dev_out16, stream, first);
+}
+
+int conf_kv_observe_prompt(conf_kv_handle *h, int32_t layer, const void *dev_q16, conf_kv_stream stream) {
+  if (!h || !dev_q16) return CONF_KV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
+  if (h->appended[layer] || h->fresh_len[layer] < 0) return CONF_KV_ERR_BAD_STATE;
+  const int T0 = h->fresh_len[layer], step = std::max(1, h->cfg.max_chunk);
+  const size_t tok = (size_t)h->cfg.n_q_heads * h->cfg.head_dim;          // elements of one token's queries
+  for (int first = 0; first < T0; first += step) {
+    const int tq = std::min(step, T0 - first);
+    int rc = attend_tokens(h, layer, tq, (const __half *)dev_q16 + (size_t)first * tok, nullptr, nullptr, nullptr,
+                           stream, first, T0);
+    if (rc != CONF_KV_OK) return rc;
+  }
+  return CONF_KV_OK;
 }
 
 int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {

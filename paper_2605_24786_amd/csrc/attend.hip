@@ -1122,7 +1122,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   {
     // row t16 = (token, head) of the call's [B][tq][Hq][D] queries
     const int q_tok = t16 / gq, q_head = t16 - q_tok * gq;
-    const __half *qrow = a.q + ((((size_t)sl.b * tq + q_tok) * cv.Hkv + sl.g) * gq + q_head) * DR;
+    const __half *qrow = a.q + ((((size_t)sl.b * a.q_tokens + q_tok) * cv.Hkv + sl.g) * gq + q_head) * DR;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       int4 raw = make_int4(0, 0, 0, 0);
@@ -1445,6 +1445,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
   TS_DUMP();
 }
 
+#include "attend_wide.h"
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -1630,6 +1632,7 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
   // preference order: want, want-1, .., 1 (fewer, always co-resident), then want+1, .. (more
   // splits shrink the LDS stash when a long unit does not fit otherwise)
   plan->two_launch = false;
+  plan->wide_rb = 0;
   for (int k = 0; k < kAttendMaxSplits && !force_two_launch; ++k) {
     const int ns = k < want ? want - k : k + 1;
     // LDS is sized in steps of 256 slots so the occupancy query is cached across calls
@@ -1675,6 +1678,32 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
   }
 }
 
+// Calls with more than 16 query rows per unit: row blocks (a power of two) and split count.  The
+// splits of a unit exchange partials inside the launch, so with more than one split the whole grid
+// must be resident (one workgroup per CU: the tile buffers take most of the LDS).
+bool attend_wide_plan(int rows, int units_per_layer, int n_ub, int forced_splits, AttendPlan *plan) {
+  const DeviceLimits &lim = device_limits();
+  if (!lim.ok || rows <= kChunkRows || rows > kWideMaxRows) return false;
+  int rb = 2;
+  while (rb * 16 < rows) rb *= 2;
+  int ns = 1;
+  while (ns * 2 <= kWideMaxSplits && ns * 2 * units_per_layer <= lim.cus && n_ub / (ns * 2) >= 256) ns *= 2;
+  if (forced_splits > 0) {
+    ns = 1;
+    while (ns * 2 <= std::min(forced_splits, kWideMaxSplits) && ns * 2 * units_per_layer <= lim.cus && n_ub / (ns * 2) >= 64) ns *= 2;
+  }
+  AttendFn fn = rb == 2 ? (AttendFn)attend_wide_kernel<2> : rb == 4 ? (AttendFn)attend_wide_kernel<4> : (AttendFn)attend_wide_kernel<8>;
+  const size_t lds = attend_wide_lds_bytes(rb * 16, ns);
+  if (lds > lim.max_lds || attend_occupancy(fn, lds) < 1) return false;
+  plan->splits = ns;
+  plan->stash_tokens = 0;
+  plan->lds_bytes = lds;
+  plan->mfma = true;
+  plan->two_launch = false;
+  plan->wide_rb = rb;
+  return true;
+}
+
 size_t attend_spill_floats(int units_per_layer, int G, int cap) {
   // splits * S <= n + n16 + splits * (2 + 34 + 255) with n, n16 <= cap
   return (size_t)units_per_layer * G * (2 * (size_t)cap + (size_t)kAttendMaxSplits * 291);
@@ -1697,6 +1726,14 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a_in, const At
     const size_t lds2 = ((size_t)plan.splits * rows2 * 2 + rows2 + 2) * sizeof(float) + 2 * rows2 * sizeof(double);
     hipLaunchKernelGGL(second, grid, dim3(kAttThreads), lds2, stream, cv, a, plan.splits,
                        plan.stash_tokens);
+    return hipGetLastError();
+  }
+  if (plan.wide_rb) {
+    AttendFn wide = plan.wide_rb == 2 ? (AttendFn)attend_wide_kernel<2>
+                    : plan.wide_rb == 4 ? (AttendFn)attend_wide_kernel<4> : (AttendFn)attend_wide_kernel<8>;
+    a.dbg = nullptr;
+    a.max_splits = kWideMaxSplits;
+    hipLaunchKernelGGL(wide, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits, 0);
     return hipGetLastError();
   }
   const bool rows16 = a.tq > 1 || a.observe_first >= 0 || cv.G > 8;

@@ -38,6 +38,7 @@ struct AttendPlan {
   size_t lds_bytes;  // dynamic LDS per workgroup
   bool mfma;         // matrix-core body for the INT8 slots
   bool two_launch;   // stream + publish, then merge + EMA in a second launch (scores in scratch)
+  int wide_rb;       // > 0: the many-rows kernel with that many blocks of 16 query rows per unit
 };
 struct AttendLaunch {
   int layer;
@@ -52,6 +53,8 @@ struct AttendLaunch {
   double mass_gain;        // weight of the step's mass in the EMA update
   int pos_new;             // position of the first appended token
   int tq;                  // tokens appended (and queries per head) in this call
+  int q_tokens;            // tokens per sequence in the q tensor: q is [B][q_tokens][Hq][D] and the call's
+                           // queries are its first tq tokens (tq, unless the call is a window of a longer tensor)
   int gq;                  // query heads per kv-head; the kernels' row r is (token r / gq, head r % gq)
   int observe_first;       // >= 0: the queries belong to the cached slots observe_first .. observe_first + tq - 1;
                            // nothing is appended and slots from observe_first + tq on are left alone
@@ -73,6 +76,10 @@ size_t attend_spill_floats(int units_per_layer, int G, int cap);   // scratch th
 // extra_lds: bytes the launch needs behind the kernel's own dynamic LDS (the block table of the paged layout).
 bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n_ub, int n16_ub, int forced_splits,
                  bool force_two_launch, size_t extra_lds, AttendPlan *plan);
+// Plan of a call with more than kChunkRows query rows per unit (at most kWideRowsMax); false when
+// the shape cannot be served.
+constexpr int kWideRowsMax = 128;
+bool attend_wide_plan(int rows, int units_per_layer, int n_ub, int forced_splits, AttendPlan *plan);
 hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a, const AttendPlan &plan,
                          hipStream_t stream);
 

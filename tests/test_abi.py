@@ -64,7 +64,8 @@ def test_buffer_sizes(clib):
                                  dict(capacity=100), dict(capacity=128), dict(vocab=1), dict(alpha=1.5),
                                  dict(n_tight=[200, 64]), dict(protected_window=-1), dict(n_layers=0),
                                  dict(ema_decay=-0.1), dict(mass_gain=float("nan")), dict(_ranker=2),
-                                 dict(_rank_scope=-1), dict(_scale_mode=2), dict(max_chunk=-1), dict(max_chunk=5),
+                                 dict(_rank_scope=-1), dict(_scale_mode=2), dict(max_chunk=-1), dict(max_chunk=33),
+                                 dict(max_chunk=5, scale_mode="channel"),
                                  dict(max_chunk=2, head_dim=64), dict(max_chunk=70, n_tight=[64, 64], n_loose=[200, 200]),
                                  dict(scale_mode="channel", head_dim=64), dict(evict_page=-1), dict(evict_page=1025),
                                  dict(evict_page=64, protected_window=200, capacity=256),

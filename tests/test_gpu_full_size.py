@@ -80,6 +80,26 @@ def test_full_size_chunks(lib):
     ls.close()
 
 
+def test_full_size_many_row_chunks(lib):
+    """Sixteen tokens per attention call at the roofline workload's shape (4 of its layers): 64
+    query rows per kv-head on the many-rows kernel (four row blocks per K/V tile, four splits per
+    unit exchanging 64 rows of partials, importance from the second pass over the keys), then an
+    eviction of more than two thousand tokens per unit."""
+    wl = workload(1).scaled(name="llama3_8b_b8_t4096_chunk16", n_layers=4, n_tight=(1024,) * 4,
+                            n_loose=(2048,) * 4, steps=3, max_chunk=16, logit_std=(0.5, 6.0), logit_run=1)
+    print(f"many-row chunks at full size: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=0, units=6, threads=16)
+    for t, tq in enumerate((16, 11, 16)):
+        ls.step(tq=tq)
+        _invariants_all_units(ls, wl, ls.t - 1)
+        print(f"  step {t} (tq={tq}): len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    print(f"  ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} flips={rep.evict_flips}/{rep.budget_flips}", flush=True)
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 def test_full_size_grouped_heads_of_64_channels(lib):
     """Eight query heads of 64 channels per kv-head (the shape of the 20B mixture-of-experts model
     the paper evaluates) at the roofline workload's batch and length, 4 layers: the matrix-core

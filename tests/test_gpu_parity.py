@@ -261,9 +261,10 @@ def _chunk_case(lib, torch, G, H, B, T0, W, splits, tqs, seed, scale_mode="token
     if two_launch:
         os.environ["CONF_KV_TWO_LAUNCH"] = "1"
     try:
-        cap = ((T0 + sum(tqs) + 8 + 63) // 64) * 64
+        room = max(16, max(tqs))                    # the budgets stay above every length the case reaches
+        cap = ((T0 + sum(tqs) + room + 8 + 63) // 64) * 64
         kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=cap,
-                 protected_window=4, n_tight=[cap - 17], n_loose=[cap - 16], scale_mode=scale_mode,
+                 protected_window=4, n_tight=[cap - room - 1], n_loose=[cap - room], scale_mode=scale_mode,
                  max_chunk=max(tqs))
     finally:
         os.environ.pop("CONF_KV_SPLITS", None)
@@ -408,6 +409,48 @@ def test_observe_matches_oracle(lib, torch_cuda, G, H, B, T0, W, splits, windows
     _observe_case(lib, torch_cuda, G, H, B, T0, W, splits, windows, seed=G * 100 + T0, scale_mode=scales)
 
 
+@pytest.mark.parametrize("G,H,B,T0,W,splits,windows", [
+    (4, 2, 1, 1200, 64, 0, ((1100, 16), (1116, 16), (1132, 12), (1190, 10))),   # 64-row windows, INT8 then FP16 slots
+    (5, 1, 2, 700, 32, 2, ((0, 12), (12, 12), (600, 16))),                       # from slot 0; 80 rows
+    (8, 1, 1, 640, 16, 4, ((500, 16), (624, 16))),                               # 128 rows, the last window ends the prompt
+    (2, 1, 1, 300, -1, 0, ((100, 20), (120, 16))),                               # FP16-only cache
+])
+def test_observe_many_rows(lib, torch_cuda, G, H, B, T0, W, splits, windows):
+    """Observation windows of more than 16 query rows per kv-head."""
+    _observe_case(lib, torch_cuda, G, H, B, T0, W, splits, windows, seed=G * 10 + T0)
+
+
+@pytest.mark.parametrize("G,T0,W,mc", [(4, 300, 32, 16), (5, 150, 16, 12), (1, 200, 8, 3)])
+def test_observe_prompt_covers_every_query(lib, torch_cuda, G, T0, W, mc):
+    """conf_kv_observe_prompt: every prompt query observes the prompt, in one call; equal to the
+    oracle's observe_unit over the same consecutive windows, i.e. to T0 single-token decode steps
+    over the stored prompt."""
+    torch = torch_cuda
+    H, B, D = 2, 2, 128
+    say(f"observe_prompt G={G} T0={T0} W={W} max_chunk={mc}")
+    kv = _mk(lib, batch=B, n_q_heads=G * H, n_kv_heads=H, head_dim=D, fp16_window=W, capacity=((T0 + 71) // 64) * 64,
+             protected_window=4, n_tight=[T0 - 20], n_loose=[T0 - 20], max_chunk=mc)
+    rng = np.random.default_rng(T0 + G)
+    K = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    V = rng.standard_normal((B, H, T0, D)).astype(np.float16)
+    q = (rng.standard_normal((B, T0, G * H, D)) * 1.5).astype(np.float16)
+    kv.load_prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    kv.observe_prompt(0, torch.from_numpy(q).cuda())
+    sm, lam = f32(1 / math.sqrt(D)), f32(0.9)
+    for b in range(B):
+        for g in range(H):
+            u = O.load_prefill(K[b, g], V[b, g], W)
+            for first in range(0, T0, mc):
+                O.observe_unit(u, q[b, first:first + mc, g * G:(g + 1) * G], first, sm, lam)
+            ex = kv.export(0, b, g)
+            e_ref = u.ema.astype(np.float64)
+            e_err = np.abs(ex["ema"].astype(np.float64) - e_ref)
+            assert np.all(e_err <= 1e-8 + 1e-5 * e_ref), f"unit {(b, g)}: EMA off, max rel {np.max(e_err / (e_ref + 1e-30)):.3g}"
+            assert abs(float(e_ref.sum()) - G * (1 - lam ** T0) ) < 1e-3 * G     # all the mass of T0 steps is there
+    assert kv.counters().device_errors == 0
+    kv.close()
+
+
 def test_observe_two_launch_form(lib, torch_cuda):
     _observe_case(lib, torch_cuda, 4, 2, 1, 1200, 64, 4, ((1190, 4), (1194, 4)), seed=5, two_launch=True)
 
@@ -462,6 +505,23 @@ def test_attend_chunk_matches_oracle(lib, torch_cuda, G, H, B, T0, W, splits, tq
     _chunk_case(lib, torch_cuda, G, H, B, T0, W, splits, tqs, seed=11 * G + T0, scale_mode=scales)
 
 
+@pytest.mark.parametrize("G,H,B,T0,W,splits,tqs", [
+    (4, 2, 1, 777, 40, 0, (16, 8, 12)),          # 64, 32 and 48 query rows per kv-head
+    (5, 1, 2, 600, 24, 2, (12, 16)),             # 60 rows (4 blocks), 80 rows (8 blocks, 3 of padding)
+    (8, 1, 1, 500, 16, 0, (16,)),                # 128 rows: every block real
+    (4, 1, 1, 3000, 64, 0, (16, 16)),            # default plan of a long unit (several splits)
+    (4, 1, 1, 3000, 64, 8, (16, 5)),             # eight splits, the chunk straddles their FP16 shares
+    (2, 1, 1, 300, 0, 2, (32,)),                 # W = 0: everything but the chunk is INT8
+    (3, 1, 2, 200, -1, 2, (20, 7)),              # FP16-only cache
+    (4, 1, 1, 0, 6, 0, (16, 16)),                # from an empty cache
+    (1, 2, 1, 400, 16, 0, (64, 100)),            # MHA: 64 and 100 tokens a call
+])
+def test_attend_chunk_many_rows(lib, torch_cuda, G, H, B, T0, W, splits, tqs):
+    """Calls with more query rows per kv-head than one matrix-core tile (up to 128): several row
+    blocks per K/V tile, no score stash, the importance from a second pass over the keys."""
+    _chunk_case(lib, torch_cuda, G, H, B, T0, W, splits, tqs, seed=17 * G + T0)
+
+
 @pytest.mark.parametrize("G,H,B,T0,W,splits,tqs,scales", [
     (4, 2, 2, 700, 32, 3, (4, 3), "token"), (1, 1, 1, 500, 16, 5, (16, 7), "token"),
     (5, 1, 1, 900, 64, 7, (3, 3), "channel"), (2, 1, 1, 300, -1, 2, (8, 8), "token")])
@@ -483,6 +543,27 @@ def test_lockstep_chunks_with_eviction(lib, torch_cuda, G, W, scales):
     say(f"chunk lockstep: G={G} W={W} scales={scales} max_chunk={mc}")
     ls = Lockstep(lib, wl, seed=29)
     rng = np.random.default_rng(4)
+    for t in range(wl.steps):
+        ls.step(tq=int(rng.integers(1, mc + 1)))
+    rep = ls.report
+    st = ls.kv.counters()
+    say(f"  out_err={rep.max_out_err:.3f}xtol ema_rel={rep.max_ema_rel:.2e} evictions={rep.evictions} "
+        f"ties={rep.evict_ties} flips={rep.evict_flips}/{rep.budget_flips} demoted={st.demoted}")
+    assert rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert rep.evictions > wl.steps and st.device_errors == 0
+    ls.close()
+
+
+@pytest.mark.parametrize("G,W,mc", [(4, 8, 16), (5, 24, 12), (1, 8, 40)])
+def test_lockstep_many_row_chunks_with_eviction(lib, torch_cuda, G, W, mc):
+    """Whole steps whose attention appends up to `mc` tokens at a time (up to 64 query rows per
+    kv-head), with the budget rule evicting in between."""
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=128, vocab=3001,
+                         prefill=300, steps=60, n_tight=(220, 180), n_loose=(330, 300), protected=max(8, mc),
+                         fp16_window=W, logit_std=(0.5, 6.0), logit_run=5, alpha=0.5, max_chunk=mc)
+    say(f"many-row chunk lockstep: G={G} W={W} max_chunk={mc}")
+    ls = Lockstep(lib, wl, seed=31)
+    rng = np.random.default_rng(6)
     for t in range(wl.steps):
         ls.step(tq=int(rng.integers(1, mc + 1)))
     rep = ls.report
