@@ -197,9 +197,25 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
     reload(); torch.cuda.synchronize()
     rows = []
     moved0 = 0
+    graph = None
+    if args.static_plan:
+        kv.static_plan(True)
+    if args.graph:
+        # the timed steps are replays of one recorded step: launch shapes from the budgets, the
+        # step's logits copied into the recorded tensor before each replay (outside the interval)
+        kv.static_plan(True)
+        glogits = torch.empty_like(logits_for(0))
+        assert args.warmup >= 1, "--graph records after at least one step outside the graph"
     for t in range(args.warmup + args.steps):
         if t == args.warmup:
             moved0 = kv.counters().compact_bytes
+            if args.graph:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for l in range(L):
+                        kv.attend(l, qs[l], ks[l], vs[l], out)
+                    kv.step(glogits, conf, sel)
+                    kv.evict_compact()
         lg = logits_for(t)
         ln, n16 = kv.lengths()
         n = ln.astype(np.int64) + 1
@@ -210,6 +226,16 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
         other_bytes = int(4 * wl.vocab * wl.batch + 8 * np.maximum(0, n - wl.protected).sum() * wl.n_kv_heads
                           + wl.units * (6 * D + 4))                      # logits, ranking inputs, demotion
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        if graph is not None:
+            glogits.copy_(lg)
+            ev[0].record()
+            graph.replay()
+            for e in ev[1:]:
+                e.record()
+            torch.cuda.synchronize()
+            rows.append((ev[0].elapsed_time(ev[3]), float("nan"), float("nan"), float("nan"), att_bytes,
+                         float(n.mean()), other_bytes))
+            continue
         ev[0].record()
         for l in range(L):
             kv.attend(l, qs[l], ks[l], vs[l], out)
@@ -228,6 +254,22 @@ def steady_state(args, wl, kv, torch, gen, reload, qs, ks, vs, out, conf, sel):
     moved = (st.compact_bytes - moved0) / args.steps
     total_bytes = float(r[:, 4].mean() + r[:, 6].mean() + moved)
     att_gbps = float((r[:, 4] / (r[:, 1] * 1e-3)).mean() / 1e9)
+    if graph is not None:
+        # no events inside a replay: the attention share of the step is not measured in this mode
+        print(json.dumps({
+            "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
+            "config": {"workload": wl.name, "mode": "steady-state, every timed step a replay of one recorded HIP graph",
+                       "layers": L, "batch": wl.batch, "layout": args.layout, "evict_page": args.evict_page,
+                       "mean_cache_len": float(r[:, 5].mean()), "attend_splits": kv.attend_splits(0)},
+            "step_hbm": {"algorithmic_bytes": total_bytes, "compaction_bytes": moved,
+                         "achieved_GBps": total_bytes / (ms_step * 1e-3) / 1e9,
+                         "frac_of_peak": total_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "counters": {"evicted": int(st.evicted), "demoted": int(st.demoted), "tight": int(st.tight_steps),
+                         "loose": int(st.loose_steps)},
+        }))
+        return
     print(json.dumps({
         "metric": "decode_steps_per_s", "value": 1000.0 / ms_step, "unit": "steps/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
@@ -258,6 +300,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--steady", action="store_true",
                     help="multi-step workloads: load the prompt once and time K consecutive decode steps")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --steady: record one decode step into a HIP graph after the warm-up and time replays of it")
+    ap.add_argument("--static-plan", action="store_true",
+                    help="with --steady: launch shapes from the budgets (what --graph uses), without the graph")
     ap.add_argument("--layers", type=int, default=0, help="keep only the first N layers (0 = all)")
     ap.add_argument("--scales", choices=["token", "channel"], default="token",
                     help="granularity of the INT8 scales (channel: the paper's literal per-(head, channel) reading)")

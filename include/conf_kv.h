@@ -20,9 +20,18 @@
  *   - The three hot calls only enqueue kernels on the given stream; they never
  *     synchronise.  Lengths and budgets live on the device; the host keeps upper bounds.
  *   - A handle is driven from one host thread, on one stream at a time.
- *   - The hot calls are not meant for HIP graph capture: each one bakes host-side state of the
- *     step (positions, a launch counter the in-kernel waits compare against, the launch plan
- *     for the current lengths) into its kernel arguments, so a replayed launch would be wrong.
+ *   - A whole decode step (the calls above, on one stream) may be recorded into a HIP graph
+ *     and replayed: the calls enqueue kernels only (no copies, no memset nodes), and what
+ *     changes from step to step (lengths, ring heads, budgets, the positions appended tokens
+ *     get, the tags the in-kernel waits compare) lives on the device and is advanced by the
+ *     kernels themselves.  The kernel arguments do hold the launch shapes, which the host
+ *     derives from upper bounds of the lengths: call conf_kv_static_plan(h, 1) before
+ *     recording, so that the shapes cover every later step, and record only after one step has
+ *     run outside the graph (first launches set kernel attributes).  The tensors the recorded
+ *     calls read and write are the ones given at recording time.  conf_kv_step_static keeps its
+ *     tag on the host and is not replayable.
+ *   - At most 2^23 attention or confidence launches may lie between two
+ *     conf_kv_evict_compact calls (CONF_KV_ERR_BAD_STATE beyond that).
  *   - Every function returns CONF_KV_OK (0) or a negative conf_kv_status; nothing throws.
  *   - Tensors are dense, row-major, in the index order written next to each argument.
  *   - fp16 data is IEEE binary16; "int8" codes are two's complement in [-127, 127].
@@ -177,7 +186,9 @@ typedef struct conf_kv_stats {
  * CONF_KV_GRID_KV_MAJOR=0/1 overrides the order of the attention grid (kv-heads first puts all
  * splits of a unit on one XCD and is the default when the number of kv-heads is a multiple of 8);
  * CONF_KV_COMPACT_PAIRED=0/1 (read at every conf_kv_evict_compact) forces one of the two grid
- * shapes of the compaction kernel, which is otherwise chosen by the number of units. */
+ * shapes of the compaction kernel, which is otherwise chosen by the number of units;
+ * CONF_KV_TEST_TAG_BASE=n starts the device-side tag bases (see conf_kv_tag_state) at n instead
+ * of 0, so that a test reaches the clearing of the exchange words in a few steps. */
 
 /* Bytes of device memory the caller must provide for the cache state and for scratch
  * (split partials, arrival counters, ranking work arrays).  0 on an invalid config. */
@@ -317,6 +328,17 @@ int conf_kv_step_static(conf_kv_handle *h, const float *dev_logits, float *dev_c
  */
 int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream);
 
+/*
+ * Launch shapes for replayed steps (for callers that record a decode step into a HIP graph).
+ * on != 0: from now on the split counts and kernel variants of conf_kv_attend* and
+ * conf_kv_evict_compact are derived from the loose budgets n_loose[l] (the longest a committed
+ * unit can be once the first conf_kv_evict_compact has run) instead of the lengths seen so far,
+ * so a step recorded now stays valid however the caches grow or shrink later.  A prompt longer
+ * than n_loose[l] is still covered while it lasts.  Results do not depend on the setting; short
+ * caches run a little slower with it.  on == 0: back to the default.  Host-side only.
+ */
+int conf_kv_static_plan(conf_kv_handle *h, int32_t on);
+
 /* ---- inspection: these synchronise the device; meant for tests and monitoring ---- */
 
 /* host_len: int32 [L][B] current cache length (appends included); host_n16: int32
@@ -348,6 +370,14 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
                    const int32_t *pos, const float *ema, const uint8_t *is_fp16, const uint16_t *k16,
                    const uint16_t *v16, const int8_t *k8, const int8_t *v8, const uint16_t *k_scale,
                    const uint16_t *v_scale);
+
+/* The tags of the words through which the workgroups of a launch exchange partial results:
+ * a launch's tag is a device-side base plus the launch's number since the last
+ * conf_kv_evict_compact, which moves the base past them.  Once a base exceeds 0xFF000000 the
+ * next conf_kv_evict_compact first clears every exchange word and then starts both bases over
+ * at 0 (*clear_pending is 1 in between), so no word ever carries a tag a later launch uses.
+ * Outputs (host, each may be NULL): the attention and confidence bases and the pending flag. */
+int conf_kv_tag_state(conf_kv_handle *h, uint32_t *attend_base, uint32_t *conf_base, int32_t *clear_pending);
 
 /* Device-side counters since conf_kv_create.  Returns CONF_KV_ERR_DEVICE if any kernel
  * reported an internal error (the counters are still filled in). */

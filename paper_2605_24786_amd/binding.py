@@ -68,6 +68,8 @@ SYMBOLS = {
     "conf_kv_step": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_step_static": (C.c_int, [_P, _P, _P, _P, _P]),
     "conf_kv_evict_compact": (C.c_int, [_P, _P]),
+    "conf_kv_static_plan": (C.c_int, [_P, C.c_int32]),
+    "conf_kv_tag_state": (C.c_int, [_P, _P, _P, _P]),
     "conf_kv_lengths": (C.c_int, [_P, _P, _P]),
     "conf_kv_export": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32] + [_P] * 10),
     "conf_kv_pyramid_budgets": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_int32, _P]),
@@ -238,6 +240,16 @@ class ConfKV:
     def step(self, logits, conf=None, sel=None):
         return self._check(self.lib.conf_kv_step(self.h, _ptr(logits), _ptr(conf), _ptr(sel),
                                                  self._stream()), "conf_kv_step")
+
+    def static_plan(self, on: bool = True):
+        """Launch shapes from the budgets instead of the lengths so far: call before recording a step into a graph."""
+        return self._check(self.lib.conf_kv_static_plan(self.h, int(bool(on))), "conf_kv_static_plan")
+
+    def tag_state(self):
+        """(attention tag base, confidence tag base, clearing pending) from the device; synchronises."""
+        a, c, p = C.c_uint32(0), C.c_uint32(0), C.c_int32(0)
+        self._check(self.lib.conf_kv_tag_state(self.h, C.byref(a), C.byref(c), C.byref(p)), "conf_kv_tag_state")
+        return a.value, c.value, p.value
 
     def step_static(self, logits, conf=None, sel=None):
         return self._check(self.lib.conf_kv_step_static(self.h, _ptr(logits), _ptr(conf), _ptr(sel),

@@ -21,7 +21,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct StateLayout {
-  size_t len, n8, head16, head8, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, unit_moved, pt, ema, pos, ks, vs, k8, v8, k16, v16, total;
+  size_t len, n8, head16, head8, budget, n_tight, n_loose, stats, unit_evicted, unit_demoted, unit_moved, ctl, pt, ema, pos, ks, vs, k8, v8, k16, v16, total;
   int npages;            // paged layout: physical pages per unit (0 otherwise)
   size_t header_bytes;   // [0, header_bytes) is zeroed at create
   int cap8, cap16;
@@ -106,6 +106,7 @@ StateLayout state_layout(const conf_kv_config *c) {
   s.unit_evicted = take(U * 4);
   s.unit_demoted = take(U * 4);
   s.unit_moved = take(U * 8);
+  s.ctl = take((size_t)(kCtlPos + c->n_layers) * 4);
   s.header_bytes = off;
   s.budget = take((size_t)c->n_layers * c->batch * 4);
   s.n_tight = take((size_t)c->n_layers * 4);
@@ -160,12 +161,16 @@ struct conf_kv_handle {
   CacheView cv{};
   // per layer
   std::vector<int32_t> len_ub;       // upper bound of the committed length
-  std::vector<int32_t> next_pos;     // position the next appended token gets
   std::vector<uint8_t> appended;     // an append awaits its commit
   std::vector<uint8_t> scaled;       // per unit: channel scales were given (channel mode)
   std::vector<int32_t> fresh_len;    // per layer: T0 of a prompt no decode step has touched yet, else -1
-  uint32_t epoch = 0;                // attend launches so far: the tag of the words a launch publishes
-  uint32_t conf_epoch = 0;           // the same for conf_kv_step
+  // Launches since the last commit (conf_kv_evict_compact).  The tag of the words a launch
+  // publishes is this number plus a base on the device that the commit advances, and the
+  // position of the next appended token lives on the device too: no launch argument changes
+  // from one decode step to the next, so a recorded step can be replayed.
+  uint32_t attend_launches = 0;
+  uint32_t conf_launches = 0;
+  bool static_plan = false;          // conf_kv_static_plan: launch shapes from the budgets, not the lengths so far
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
   int withhold = 0;                 // CONF_KV_TEST_WITHHOLD at create (tests of the expiry path)
@@ -215,7 +220,6 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   h->scratch = (uint8_t *)dev_scratch;
   const int L = cfg->n_layers;
   h->len_ub.assign(L, 0);
-  h->next_pos.assign(L, 0);
   h->appended.assign(L, 0);
   h->scaled.assign((size_t)L * cfg->batch * cfg->n_kv_heads, 0);
   h->fresh_len.assign(L, -1);
@@ -258,6 +262,9 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
   cv.W = cfg->fp16_window;
   cv.P = cfg->protected_window;
   cv.chan = cfg->scale_mode == CONF_KV_SCALES_CHANNEL;
+  cv.ctl = (unsigned *)(s + h->sl.ctl);
+  cv.tagged = (unsigned long long *)(h->scratch + h->kl.conf_partial);
+  cv.n_tagged = (h->kl.zero_bytes - h->kl.conf_partial) / 8;
   cv.pt = (int32_t *)(s + h->sl.pt);
   cv.npages = h->sl.npages;
   cv.page_lg = 0;
@@ -278,6 +285,10 @@ int conf_kv_create(conf_kv_handle **out, const conf_kv_config *cfg, void *dev_st
     std::vector<int32_t> ident(U * cv.npages);
     for (size_t i = 0; i < ident.size(); ++i) ident[i] = (int32_t)(i % cv.npages);
     e = hipMemcpy(cv.pt, ident.data(), ident.size() * 4, hipMemcpyHostToDevice);
+  }
+  if (const char *tb = getenv("CONF_KV_TEST_TAG_BASE")) {   // test hook: start the tag bases near their restart
+    const unsigned base[2] = {(unsigned)strtoul(tb, nullptr, 0), (unsigned)strtoul(tb, nullptr, 0)};
+    if (e == hipSuccess) e = hipMemcpy(cv.ctl + kCtlTag, base, sizeof base, hipMemcpyHostToDevice);
   }
   if (e == hipSuccess) e = hipMemcpy(cv.budget, budget.data(), budget.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy((void *)cv.n_tight, h->n_tight.data(), (size_t)L * 4, hipMemcpyHostToDevice);
@@ -319,12 +330,17 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   CK_HIP(h, launch_load_prefill(h->cv, layer, (const __half *)dev_k16, (const __half *)dev_v16, T0,
                                 dev_ema0, (hipStream_t)stream));
   h->len_ub[layer] = T0;
-  h->next_pos[layer] = T0;
   h->appended[layer] = 0;
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   std::fill(h->scaled.begin() + layer * UPL, h->scaled.begin() + (layer + 1) * UPL, (uint8_t)1);
   h->fresh_len[layer] = T0;
   return CONF_KV_OK;
+}
+
+// Upper bound of a layer's committed length that the launch shapes are derived from: what the
+// host has seen so far, or (conf_kv_static_plan) what the budgets allow at any later step too.
+static int length_bound(const conf_kv_handle *h, int layer) {
+  return h->static_plan ? std::max(h->len_ub[layer], h->n_loose[layer]) : h->len_ub[layer];
 }
 
 // LDS the attention kernel needs for the unit's block table (paged layout), in whole 16 bytes.
@@ -334,7 +350,7 @@ static size_t table_lds(const conf_kv_handle *h) {
 
 static int plan_for_layer(conf_kv_handle *h, int layer, int tq, AttendPlan *plan, int observe_first = -1) {
   const bool observe = observe_first >= 0;
-  const int n_ub = observe ? observe_first + tq : h->len_ub[layer] + tq;     // slots the call sees
+  const int n_ub = observe ? observe_first + tq : length_bound(h, layer) + tq;     // slots the call sees
   const int W = h->cfg.fp16_window;
   const int n16_ub = W < 0 ? n_ub : std::min(n_ub, observe ? W : W + tq);
   // a chunk runs on the matrix-core body with all 16 tile rows as query rows
@@ -385,21 +401,18 @@ static int attend_tokens(conf_kv_handle *h, int32_t layer, int32_t tq, const voi
   a.part_ml = (unsigned long long *)(h->scratch + h->kl.part_ml);
   a.part_o = (unsigned long long *)(h->scratch + h->kl.part_o);
   a.spill = (float *)(h->scratch + h->kl.spill);
-  // One counter for the handle: the tagged words are shared by the layers, so a launch must not
-  // meet a tag a launch on another layer left.  0 is skipped because the words start at 0, and
-  // when the counter wraps (2^32 launches) the words are cleared first, so that no word of the
-  // round before can carry a tag of the new one.
-  if (++h->epoch == 0u) {
-    h->epoch = 1u;
-    CK_HIP(h, launch_zero_words(h->scratch + h->kl.part_ml, h->kl.zero_bytes - h->kl.part_ml, (hipStream_t)stream));
-  }
-  a.epoch = h->epoch;
+  // One numbering for the handle: the tagged words are shared by the layers, so a launch must not
+  // meet a tag a launch on another layer left.  The words start at 0 and numbers start at 1, so
+  // tag 0 is never used; before the device-side base nears the end of its range the commit has
+  // the words cleared and starts over (evict.hip).
+  if (h->attend_launches >= kTagLaunchesMax) return CONF_KV_ERR_BAD_STATE;
+  a.epoch = ++h->attend_launches;
   a.spin_limit = h->spin_limit;
   a.max_splits = kAttendMaxSplits;
   a.sm_scale = h->cfg.sm_scale;
   a.ema_decay = h->cfg.ema_decay;
   a.mass_gain = h->cfg.mass_gain < 0.f ? 1.0 - (double)h->cfg.ema_decay : (double)h->cfg.mass_gain;
-  a.pos_new = h->next_pos[layer];
+  a.pos_new = 0;                                   // read on the device
   a.tq = tq;
   a.q_tokens = q_tokens > 0 ? q_tokens : tq;
   a.gq = h->cv.G;
@@ -472,13 +485,10 @@ int conf_kv_attend_splits(conf_kv_handle *h, int32_t layer) {
 int conf_kv_step(conf_kv_handle *h, const float *dev_logits, float *dev_conf, uint8_t *dev_sel,
                  conf_kv_stream stream) {
   if (!h || !dev_logits) return CONF_KV_ERR_INVALID_ARG;
-  if (++h->conf_epoch == 0u) {                           // the partial words start at tag 0: see conf_kv_attend
-    h->conf_epoch = 1u;
-    CK_HIP(h, launch_zero_words(h->scratch + h->kl.conf_partial, h->kl.part_ml - h->kl.conf_partial, (hipStream_t)stream));
-  }
+  if (h->conf_launches >= kTagLaunchesMax) return CONF_KV_ERR_BAD_STATE;    // (numbered like the attention launches)
   CK_HIP(h, launch_conf_reduce(h->cv, dev_logits, h->cfg.vocab,
                                (unsigned long long *)(h->scratch + h->kl.conf_partial),
-                               h->conf_epoch, h->spin_limit, h->withhold, dev_conf, dev_sel,
+                               ++h->conf_launches, 1, h->spin_limit, h->withhold, dev_conf, dev_sel,
                                (double)h->cfg.tau, (double)h->cfg.w_entropy, (double)h->cfg.w_margin,
                                (double)h->cfg.w_top, (hipStream_t)stream));
   return CONF_KV_OK;
@@ -501,7 +511,7 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     m.set(l, h->appended[l]);
-    n_max = std::max(n_max, h->len_ub[l] + (int)h->appended[l]);
+    n_max = std::max(n_max, length_bound(h, l) + (int)h->appended[l]);
     if (h->cv.chan && h->len_ub[l] + (int)h->appended[l] > 0)     // a demotion needs the scales
       for (size_t u = l * UPL; u < (l + 1) * UPL; ++u)
         if (!h->scaled[u]) return CONF_KV_ERR_BAD_STATE;
@@ -513,11 +523,12 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   opt.page = h->cfg.evict_page > 1 ? h->cfg.evict_page : 0;
   CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, opt, (double *)(h->scratch + h->kl.score),
                                  (int32_t *)(h->scratch + h->kl.src),
-                                 (int32_t *)(h->scratch + h->kl.sel), n_max, (hipStream_t)stream));
+                                 (int32_t *)(h->scratch + h->kl.sel), n_max, h->attend_launches, h->conf_launches,
+                                 (hipStream_t)stream));
+  h->attend_launches = h->conf_launches = 0;
   const int P = h->cfg.protected_window;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     h->len_ub[l] += h->appended[l];
-    h->next_pos[l] += h->appended[l];
     h->appended[l] = 0;
     h->fresh_len[l] = -1;
     // any budget the step may have chosen is at most the loose one
@@ -525,6 +536,23 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
     // (a page that reaches into the protected window holds back up to evict_page - 1 more)
     if (n > NL) h->len_ub[l] = std::max(NL, std::min(P + (opt.page > 1 ? opt.page - 1 : 0), n));
   }
+  return CONF_KV_OK;
+}
+
+int conf_kv_static_plan(conf_kv_handle *h, int32_t on) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  h->static_plan = on != 0;
+  return CONF_KV_OK;
+}
+
+int conf_kv_tag_state(conf_kv_handle *h, uint32_t *attend_base, uint32_t *conf_base, int32_t *clear_pending) {
+  if (!h) return CONF_KV_ERR_INVALID_ARG;
+  unsigned ctl[kCtlPos] = {};
+  CK_HIP(h, hipDeviceSynchronize());
+  CK_HIP(h, hipMemcpy(ctl, h->cv.ctl, sizeof ctl, hipMemcpyDeviceToHost));
+  if (attend_base) *attend_base = ctl[kCtlTag];
+  if (conf_base) *conf_base = ctl[kCtlConfTag];
+  if (clear_pending) *clear_pending = (int32_t)ctl[kCtlClear];
   return CONF_KV_OK;
 }
 
@@ -725,7 +753,12 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   CK_HIP(h, hipMemcpy(cv.head8 + u, &zero, 4, hipMemcpyHostToDevice));
   h->len_ub[layer] = std::max(h->len_ub[layer], n);
   h->fresh_len[layer] = -1;
-  if (n > 0) h->next_pos[layer] = std::max(h->next_pos[layer], pos[n - 1] + 1);
+  if (n > 0) {                       // later tokens get positions behind the imported ones
+    unsigned next = 0;
+    CK_HIP(h, hipMemcpy(&next, h->cv.ctl + kCtlPos + layer, 4, hipMemcpyDeviceToHost));
+    next = std::max(next, (unsigned)(pos[n - 1] + 1));
+    CK_HIP(h, hipMemcpy(h->cv.ctl + kCtlPos + layer, &next, 4, hipMemcpyHostToDevice));
+  }
   return CONF_KV_OK;
 }
 

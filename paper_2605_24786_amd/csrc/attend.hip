@@ -104,6 +104,16 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 // launch that wrote it, so a reader can tell on its own whether the word it got is current.
 // A float that travels with the epoch of the launch that wrote it: one 8-byte word, so a
 // reader sees value and tag together or neither.
+// The host passes a launch's number since the last commit and the device completes it: the
+// tag base and the position of the next appended token live in cv.ctl, where the commit at the
+// end of conf_kv_evict_compact advances them.  A recorded sequence of launches can therefore be
+// replayed: nothing that changes from step to step is a launch argument.
+__device__ __forceinline__ AttendLaunch resolve_launch(const CacheView &cv, AttendLaunch a) {
+  a.epoch += __builtin_amdgcn_readfirstlane(cv.ctl[kCtlTag]);
+  a.pos_new = __builtin_amdgcn_readfirstlane(cv.ctl[kCtlPos + a.layer]);
+  return a;
+}
+
 __device__ __forceinline__ void st_tagged(unsigned long long *p, unsigned epoch, float v) {
   __hip_atomic_store(p, ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(v),
                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -806,8 +816,9 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
 // kSpill: the first launch of the two-launch form -- the slice's raw scores go to device
 // scratch instead of LDS and the kernel ends after publishing its partial.
 template <int D, int G, bool kSpill = false>
-__global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a, int ns,
+__global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a_in, int ns,
                                                              int S) {
+  const AttendLaunch a = resolve_launch(cv, a_in);
   constexpr int NP = kAttWaves;
   extern __shared__ __align__(16) float smem[];
   float *stash = kSpill ? a.spill + ((size_t)unit_in_layer(cv, a) * ns + split_index(a)) * G * S
@@ -858,8 +869,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 // Second launch of the two-launch form: same grid; merges the published partials of the unit,
 // updates the EMA of its slice from the spilled scores and normalises its share of the output.
 template <int D, int G, int DR = D>
-__global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv, AttendLaunch a, int ns,
+__global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv, AttendLaunch a_in, int ns,
                                                                     int S) {
+  const AttendLaunch a = resolve_launch(cv, a_in);
   extern __shared__ __align__(16) float smem[];
   float *pml = smem;                            // [ns][G][2]
   float *gm = pml + (size_t)ns * G * 2;         // [G]
@@ -1006,7 +1018,8 @@ __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], i
 template <int G, bool kChan = false, bool kSpill = false, int DR = 128>
 __global__ __launch_bounds__(kAttThreads)
 __attribute__((amdgpu_waves_per_eu((kChan || G > 8) ? 2 : 3, (kChan || G > 8) ? 2 : 3)))
-void attend_mfma_kernel(CacheView cv, AttendLaunch a, int ns, int S) {
+void attend_mfma_kernel(CacheView cv, AttendLaunch a_in, int ns, int S) {
+  const AttendLaunch a = resolve_launch(cv, a_in);
   // D: channels of the tiles and partials on chip.  DR: the head dimension in memory; a 64-channel
   // head runs on the same tiles with channels 64..127 holding a second copy of its rows against
   // zero query channels (their products are 0, their outputs are dropped).

@@ -44,8 +44,11 @@ __device__ __forceinline__ void top2_merge(float &a1, float &a2, float b1, float
 
 __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     const float *__restrict__ logits, int V, int nchunk, unsigned long long *__restrict__ partial,
-    unsigned epoch, int spin_limit, int withhold, float *__restrict__ conf, uint8_t *__restrict__ sel,
-    CacheView cv, double tau, double wH, double wm, double wp) {
+    unsigned launch_no, int device_base, int spin_limit, int withhold, float *__restrict__ conf,
+    uint8_t *__restrict__ sel, CacheView cv, double tau, double wH, double wm, double wp) {
+  // the words' tag: the launch's number plus, for the handle's own words, the base the commit
+  // at the end of conf_kv_evict_compact advances (so that a recorded launch can be replayed)
+  const unsigned epoch = launch_no + (device_base ? __builtin_amdgcn_readfirstlane(cv.ctl[kCtlConfTag]) : 0u);
   __shared__ float s_f[4 * 4];
   __shared__ double s_d[4 * 2];
   __shared__ int s_ok;
@@ -55,13 +58,30 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   const float NEG = -INFINITY;
 
   float x[kConfPerThread];
-  const int base = c * kConfChunk + tid;
-  // branch-free loads (an index past the row re-reads its last logit and is masked afterwards),
-  // so that all sixteen are in flight before the first one is waited for
+  if ((V & 3) == 0) {
+    // rows start on 16-byte boundaries: four 128-bit loads per thread, all in flight together
+    // (a quad past the row re-reads its last quad and is masked afterwards)
+    const int q0 = c * (kConfChunk / 4) + tid, nq = V / 4;
+    float4 v[kConfPerThread / 4];
 #pragma unroll
-  for (int r = 0; r < kConfPerThread; ++r) x[r] = row[min(base + r * kConfThreads, V - 1)];
+    for (int r = 0; r < kConfPerThread / 4; ++r) v[r] = ((const float4 *)row)[min(q0 + r * kConfThreads, nq - 1)];
 #pragma unroll
-  for (int r = 0; r < kConfPerThread; ++r) x[r] = base + r * kConfThreads < V ? x[r] : NEG;
+    for (int r = 0; r < kConfPerThread / 4; ++r) {
+      const bool in = q0 + r * kConfThreads < nq;
+      x[4 * r] = in ? v[r].x : NEG;
+      x[4 * r + 1] = in ? v[r].y : NEG;
+      x[4 * r + 2] = in ? v[r].z : NEG;
+      x[4 * r + 3] = in ? v[r].w : NEG;
+    }
+  } else {
+    const int base = c * kConfChunk + tid;
+    // branch-free loads (an index past the row re-reads its last logit and is masked afterwards),
+    // so that all sixteen are in flight before the first one is waited for
+#pragma unroll
+    for (int r = 0; r < kConfPerThread; ++r) x[r] = row[min(base + r * kConfThreads, V - 1)];
+#pragma unroll
+    for (int r = 0; r < kConfPerThread; ++r) x[r] = base + r * kConfThreads < V ? x[r] : NEG;
+  }
   float v1 = NEG, v2 = NEG;
 #pragma unroll
   for (int r = 0; r < kConfPerThread; ++r) {
@@ -249,7 +269,7 @@ hipError_t launch_conf_reduce_static(const CacheView &cv, const float *logits, i
   }
   // after 2^32 launches the tags start over: no word may still carry one of the new round
   if (wrapped) (void)launch_zero_words(ptr, kConfStaticBytes, stream);
-  return launch_conf_reduce(cv, logits, V, ptr, epoch, spin_limit, withhold, conf, sel, tau, wH, wm, wp, stream);
+  return launch_conf_reduce(cv, logits, V, ptr, epoch, 0, spin_limit, withhold, conf, sel, tau, wH, wm, wp, stream);
 }
 
 hipError_t launch_zero_words(void *p, size_t bytes, hipStream_t stream) {
@@ -263,12 +283,12 @@ size_t conf_reduce_scratch_bytes(int B, int V) {
 }
 
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
-                              unsigned epoch, int spin_limit, int withhold, float *conf, uint8_t *sel, double tau,
-                              double wH, double wm, double wp, hipStream_t stream) {
+                              unsigned launch_no, int device_base, int spin_limit, int withhold, float *conf,
+                              uint8_t *sel, double tau, double wH, double wm, double wp, hipStream_t stream) {
   int nchunk = (V + kConfChunk - 1) / kConfChunk;
   dim3 grid(nchunk, cv.B);
   hipLaunchKernelGGL(conf_reduce_kernel, grid, dim3(kConfThreads), 0, stream, logits, V, nchunk,
-                     partial, epoch, spin_limit, withhold, conf, sel, cv, tau, wH, wm, wp);
+                     partial, launch_no, device_base, spin_limit, withhold, conf, sel, cv, tau, wH, wm, wp);
   return hipGetLastError();
 }
 

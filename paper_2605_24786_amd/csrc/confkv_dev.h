@@ -51,7 +51,21 @@ struct CacheView {
   // slot i >= n8 live in row cap - cap16 + (its FP16 ring row); head8 stays 0.
   int32_t *pt;
   int32_t page_lg, npages;
+  // Step state the kernels advance themselves, so that no launch argument changes from one
+  // decode step to the next (see CtlSlot), and the epoch-tagged exchange words of the attention
+  // and confidence kernels (all of them, for the clearing before the tags start over).
+  unsigned *ctl;
+  unsigned long long *tagged;
+  unsigned long long n_tagged;
 };
+
+// cv.ctl: [kCtlTag] tags handed out to attention launches up to the last commit (a launch's tag
+// is this plus its number since then, so never 0), [kCtlConfTag] the same for the confidence
+// kernel, [kCtlClear] 1 = the bases are near the end of their range: the next commit clears the
+// tagged words and starts both over, [kCtlPos + l] position the next token appended to layer l gets.
+enum CtlSlot { kCtlTag = 0, kCtlConfTag = 1, kCtlClear = 2, kCtlPos = 4 };
+constexpr unsigned kTagRestart = 0xFF000000u;      // a base above this asks for the clearing
+constexpr unsigned kTagLaunchesMax = 1u << 23;     // launches between two commits (host-enforced)
 
 // Row of slot i in the planes anchored at the oldest slot (EMA, position; for i < n8 also the
 // INT8 codes and per-token scales), in either layout.  tab: the unit's block table.

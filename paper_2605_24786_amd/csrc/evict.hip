@@ -137,6 +137,7 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
     cv.n8[u] = n8;
     cv.head16[u] = 0;
     cv.head8[u] = 0;
+    if (ul == 0) cv.ctl[kCtlPos + layer] = (unsigned)T0;      // the first decode token's position
   }
   if (cv.page_lg && blockIdx.x == 0)                // paged layout: the block table starts over as the identity
     for (int i = threadIdx.x; i < cv.npages; i += kEvThreads) cv.pt[(size_t)u * cv.npages + i] = i;
@@ -1051,11 +1052,20 @@ __device__ __forceinline__ void move_rows(uint8_t *base_ptr, uint8_t *base2, con
   }
 }
 
+// Before the tags of the exchange words start over (the commit of the call before asked for it;
+// the flag does not change while this kernel runs), every workgroup clears its share of them.
+__device__ __forceinline__ void clear_tagged_if_asked(const CacheView &cv) {
+  if (__builtin_amdgcn_readfirstlane(cv.ctl[kCtlClear]) == 0u) return;
+  const size_t nwg = (size_t)gridDim.x * gridDim.y, wg = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+  for (size_t i = wg * blockDim.x + threadIdx.x; i < cv.n_tagged; i += nwg * blockDim.x) cv.tagged[i] = 0ull;
+}
+
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
                                                              const int32_t *__restrict__ src_all,
                                                              const int32_t *__restrict__ sel_all, int paired) {
   const int u = blockIdx.x, tid = threadIdx.x;
+  clear_tagged_if_asked(cv);
   // what this workgroup moves: the payload rows of the ring the holes lie in (K, V or both),
   // the per-slot planes, the FP16 rows of a mixed cache (K, V or both)
   const int y = blockIdx.y;
@@ -1161,6 +1171,7 @@ __global__ __launch_bounds__(kEvThreads) void compact_paged_kernel(CacheView cv,
   extern __shared__ int32_t pg_lds[];
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int u = blockIdx.x * (kEvThreads / kWave) + w;
+  clear_tagged_if_asked(cv);
   if (u >= U) return;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
   if (sel[3] == 0) return;                                   // nothing left the unit
@@ -1192,11 +1203,31 @@ __global__ __launch_bounds__(kEvThreads) void compact_paged_kernel(CacheView cv,
 
 // ---------------------------------------------------------------------------------------
 // demote: grid (U / 4), one wavefront per unit.  Quantises the oldest FP16 slots until at most W stay
-// FP16, appends them at the INT8 ring tail, and commits (len, n8, head16, head8).
+// FP16, appends them at the INT8 ring tail, and commits (len, n8, head16, head8).  The first
+// wavefront also commits the step state in cv.ctl: the layers' next positions move past the
+// appended tokens and the tag bases past the launches since the last commit; a base near the
+// end of its range asks the next call's compaction kernel to clear the tagged words, after
+// which both bases start over at 0.
 // ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
-                                                            const int32_t *__restrict__ sel_all, int U) {
+                                                            const int32_t *__restrict__ sel_all, int U,
+                                                            LayerMask appended, unsigned attend_launches,
+                                                            unsigned conf_launches) {
+  if (blockIdx.x == 0 && threadIdx.x < kWave) {
+    for (int l = threadIdx.x; l < cv.L; l += kWave)
+      if (const int c = appended.get(l)) cv.ctl[kCtlPos + l] += (unsigned)c;
+    if (threadIdx.x == 0) {
+      if (cv.ctl[kCtlClear]) {
+        cv.ctl[kCtlTag] = cv.ctl[kCtlConfTag] = cv.ctl[kCtlClear] = 0u;
+      } else {
+        const unsigned t = cv.ctl[kCtlTag] + attend_launches, c = cv.ctl[kCtlConfTag] + conf_launches;
+        cv.ctl[kCtlTag] = t;
+        cv.ctl[kCtlConfTag] = c;
+        if (t > kTagRestart || c > kTagRestart) cv.ctl[kCtlClear] = 1u;
+      }
+    }
+  }
   const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (u >= U) return;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
@@ -1253,7 +1284,8 @@ hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16
 
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
                                 const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
-                                int n_max, hipStream_t stream) {
+                                int n_max, unsigned attend_launches, unsigned conf_launches,
+                                hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
   if (opt.random || opt.shared || opt.page > 1) {
     // ranker variants: the general kernel; with the layer-shared importance alone, the
@@ -1303,17 +1335,21 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
     const size_t lds = (size_t)(kEvThreads / kWave) * 2 * cv.npages * sizeof(int32_t);
     hipLaunchKernelGGL(compact_paged_kernel, dim3((U + 3) / 4), dim3(kEvThreads), lds, stream, cv, src, sel, U);
     if (cv.D == 64)
-      hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
+      hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
+                         attend_launches, conf_launches);
     else
-      hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
+      hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
+                         attend_launches, conf_launches);
     return hipGetLastError();
   }
   if (cv.D == 64) {
     hipLaunchKernelGGL(compact_kernel<64>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
-    hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
+    hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
+                         attend_launches, conf_launches);
   } else {
     hipLaunchKernelGGL(compact_kernel<128>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
-    hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U);
+    hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
+                         attend_launches, conf_launches);
   }
   return hipGetLastError();
 }

@@ -12,7 +12,8 @@ namespace confkv {
 // ---- conf_reduce.hip ----
 size_t conf_reduce_scratch_bytes(int B, int V);   // epoch-tagged chunk partials: zero before the first call
 hipError_t launch_conf_reduce(const CacheView &cv, const float *logits, int V, unsigned long long *partial,
-                              unsigned epoch /* never 0, never reused */, int spin_limit,
+                              unsigned launch_no /* the words' tag; never 0, never reused */,
+                              int device_base /* 1: the tag is launch_no + cv.ctl[kCtlConfTag] */, int spin_limit,
                               int withhold /* test hook: chunk 0 does not publish, so the bounded wait expires */,
                               float *conf, uint8_t *sel, double tau, double wH, double wm, double wp,
                               hipStream_t stream);
@@ -46,12 +47,13 @@ struct AttendLaunch {
   __half *out;
   unsigned long long *part_ml;   // [units per layer][max splits][G][2] words: (epoch << 32) | float bits of m, of l
   unsigned long long *part_o;    // [units per layer][max splits][G][D] words: (epoch << 32) | float bits of a partial output
-  unsigned epoch;          // tag of the words published in this launch (never 0, never reused by a later one)
+  unsigned epoch;          // number of the launch since the last commit, from 1; the kernels add the base in
+                           // cv.ctl: the sum tags the words the launch publishes (never 0, never reused)
   int spin_limit;          // polls before a wait for the other splits gives up (device error)
   int max_splits;
   float sm_scale, ema_decay;
   double mass_gain;        // weight of the step's mass in the EMA update
-  int pos_new;             // position of the first appended token
+  int pos_new;             // position of the first appended token (the kernels read it from cv.ctl)
   int tq;                  // tokens appended (and queries per head) in this call
   int q_tokens;            // tokens per sequence in the q tensor: q is [B][q_tokens][Hq][D] and the call's
                            // queries are its first tq tokens (tq, unless the call is a window of a longer tensor)
@@ -101,6 +103,8 @@ struct RankOptions {
 };
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
                                 const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
-                                int n_max /* longest unit */, hipStream_t stream);
+                                int n_max /* longest unit */,
+                                unsigned attend_launches, unsigned conf_launches /* since the last commit */,
+                                hipStream_t stream);
 
 }  // namespace confkv

@@ -193,14 +193,54 @@ class Lockstep:
                     assert err <= 1.0, f"observe {first}+{tq} unit {(ul, b, g)}: out off by {err:.3g} x tolerance"
         self.compare_state(f"after observe {first}+{tq}")
 
+    # ---- a decode step recorded once into a HIP graph and replayed ----
+    def record_step(self):
+        """Record the calls of one decode step (one conf_kv_attend per layer, conf_kv_step,
+        conf_kv_evict_compact) into a graph over fixed input / output tensors.  Nothing runs
+        while recording; every later ``step`` fills the tensors and replays the graph."""
+        torch, wl, kv = self.torch, self.wl, self.kv
+        L, B, Hq, Hkv, D = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+        self.gq = torch.zeros((L, B, Hq, D), dtype=torch.float16, device="cuda")
+        self.gk = torch.zeros((L, B, Hkv, D), dtype=torch.float16, device="cuda")
+        self.gv = torch.zeros((L, B, Hkv, D), dtype=torch.float16, device="cuda")
+        self.gout = torch.zeros((L, B, Hq, D), dtype=torch.float16, device="cuda")
+        self.glogits = torch.zeros((B, wl.vocab), dtype=torch.float32, device="cuda")
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            for l in range(L):
+                kv.attend(l, self.gq[l], self.gk[l], self.gv[l], self.gout[l])
+            kv.step(self.glogits, self.conf, self.sel)
+            kv.evict_compact()
+        self.replays = 0
+
+    def _replay(self):
+        torch, wl = self.torch, self.wl
+        ins = [gen.step_inputs(wl, self.seed, l, self.t) for l in range(wl.n_layers)]
+        for j, dst in enumerate((self.gq, self.gk, self.gv)):
+            dst.copy_(torch.from_numpy(np.stack([x[j] for x in ins])))
+        self.glogits.copy_(torch.from_numpy(gen.step_logits(wl, self.seed, self.t)))
+        self.gout.zero_()
+        self.graph.replay()
+        self.replays += 1
+        return ins, self.gout.cpu().numpy().astype(np.float64)
+
     # ---- one decode step ----
     def step(self, check_state: bool = True, tq: int = 1):
         """One decode step; tq > 1 feeds tq tokens through one conf_kv_attend_chunk call per
-        layer (the inputs of steps t .. t + tq - 1, the logits of the last one)."""
+        layer (the inputs of steps t .. t + tq - 1, the logits of the last one).  After
+        ``record_step`` the GPU side of the step is a replay of the recorded graph."""
         torch, wl, kv, rep = self.torch, self.wl, self.kv, self.report
         G = wl.group
+        replayed = None
+        if getattr(self, "graph", None) is not None:
+            assert tq == 1
+            replayed = self._replay()
         for l in range(wl.n_layers):
-            if tq == 1:
+            if replayed is not None:
+                q, k, v = replayed[0][l]
+                ref = self.run.attend(l, q, k, v, G)
+                got = replayed[1][l]
+            elif tq == 1:
                 q, k, v = gen.step_inputs(wl, self.seed, l, self.t)
                 kv.attend(l, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(),
                           torch.from_numpy(v).cuda(), self.out)
@@ -223,7 +263,8 @@ class Lockstep:
                     rep.max_out_err = max(rep.max_out_err, float(err))
                     assert err <= 1.0, f"step {self.t} unit {(ul, b, g)}: attention output off by {err:.3g} x tolerance"
         logits = gen.step_logits(wl, self.seed, self.t + tq - 1)
-        kv.step(torch.from_numpy(logits).cuda(), self.conf, self.sel)
+        if replayed is None:
+            kv.step(torch.from_numpy(logits).cuda(), self.conf, self.sel)
         c_ref, tight_ref = self.run.step(logits)
         c_gpu = self.conf.cpu().numpy().astype(np.float64)
         sel_gpu = self.sel.cpu().numpy().astype(bool)
@@ -241,7 +282,8 @@ class Lockstep:
         rep.tight_steps += int(sel_gpu.sum())
         # eviction: keep pre-evict copies so the oracle can adopt a GPU tie-break
         before = {key: u.copy() for key, u in self.run.units.items()}
-        kv.evict_compact()
+        if replayed is None:
+            kv.evict_compact()
         gone = self.run.evict_compact(sel_gpu)      # the oracle follows the GPU's budget choice
         self.last_before, self.last_gone = before, gone
         for key, u in self.run.units.items():
