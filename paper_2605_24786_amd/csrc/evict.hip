@@ -862,7 +862,8 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
                                                                 double alpha,
                                                                 const double *__restrict__ shared_all,
                                                                 int32_t *__restrict__ src_all,
-                                                                int32_t *__restrict__ sel_all, int U) {
+                                                                int32_t *__restrict__ sel_all, int U,
+                                                                int idle_only) {
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6);
   if (u >= U) return;
@@ -883,7 +884,9 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
     if (lane == 0) write_selection(cv, u, sel, n, n8, n8, n, 0, -1);
     return;
   }
-  if (e > kSmallE) {
+  // (idle_only: the ranker variants -- random draws, whole pages -- are the general kernel's; this
+  // one then only settles the units that evict nothing, most of them in a decode loop)
+  if (e > kSmallE || idle_only) {
     if (lane == 0) sel[7] = 0;                       // left to the general kernel
     return;
   }
@@ -1288,27 +1291,34 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
   if (opt.random || opt.shared || opt.page > 1) {
-    // ranker variants: the general kernel; with the layer-shared importance alone, the
-    // one-wavefront kernel first settles the units that evict a few slots (the steady state)
+    // ranker variants: the one-wavefront kernel first settles the units that evict nothing (with
+    // the layer-shared importance alone, also those that evict a few slots: the steady state),
+    // the general kernel serves the rest
     if (opt.shared)
       hipLaunchKernelGGL(shared_mass_kernel, dim3(cv.L * cv.B, (cv.cap + kEvThreads - 1) / kEvThreads),
                          dim3(kEvThreads), 0, stream, cv, appended, opt.shared);
     const int pre = opt.shared && !opt.random && opt.page <= 1;
-    if (pre)
+    if (opt.shared)
       hipLaunchKernelGGL(rank_small_kernel<true>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                         (const double *)opt.shared, src, sel, U);
+                         (const double *)opt.shared, src, sel, U, !pre);
+    else
+      hipLaunchKernelGGL(rank_small_kernel<false>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                         (const double *)nullptr, src, sel, U, 1);
     if (pre && n_max <= 256 * 20)
       hipLaunchKernelGGL((rank_select_reg_kernel<256, 20, true>), dim3(U), dim3(256), 0, stream, cv, appended,
                          alpha, src, sel, (const double *)opt.shared);
     else if (pre && n_max <= 1024 * 33)
       hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33, true>), dim3(U), dim3(1024), 0, stream, cv, appended,
                          alpha, src, sel, (const double *)opt.shared);
+    else if (n_max <= 256 * 16)    // (a short unit does not fill 1024 threads, and most units return at once)
+      hipLaunchKernelGGL(rank_select_kernel<256>, dim3(U), dim3(256), 0, stream, cv, appended, alpha, opt,
+                         1, score, src, sel);
     else
       hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
-                         pre, score, src, sel);
+                         1, score, src, sel);
   } else {
   hipLaunchKernelGGL(rank_small_kernel<false>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                     (const double *)nullptr, src, sel, U);
+                     (const double *)nullptr, src, sel, U, 0);
   // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
   // nothing); with few units the chip is filled by giving each unit four wavefronts.
   if (n_max <= 64 * 33 && U >= 2048)
