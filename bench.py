@@ -128,7 +128,7 @@ def read_probe(torch, pkg, launch_bytes):
 
 
 def _cpu_worker(job):
-    """One oracle worker: `count` seeded units of the workload, timing attend + evict/compact/demote."""
+    """One oracle worker: the units `count` (ids) of the workload, timing attend + evict/compact/demote."""
     wl, seed, worker, count, tight = job
     from threadpoolctl import threadpool_limits
     from oracle import confkv_oracle as O
@@ -137,11 +137,10 @@ def _cpu_worker(job):
     from harness import policy_of
     pol = policy_of(wl)
     G = wl.group
-    rng = np.random.default_rng([seed, worker])
     times = []
     with threadpool_limits(limits=1):
-        for _ in range(count):
-            l, b, g = int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch)), int(rng.integers(wl.n_kv_heads))
+        for uid in count:                      # unit ids (layer * B + b) * Hkv + kv-head
+            l, b, g = uid // (wl.batch * wl.n_kv_heads), uid // wl.n_kv_heads % wl.batch, uid % wl.n_kv_heads
             K, V = gen.prefill_unit(wl, seed, l, b, g)
             u = O.load_prefill(K, V, wl.fp16_window, scale_mode=getattr(wl, "scale_mode", "token"))
             q, kn, vn = gen.step_inputs(wl, seed, l, 0)
@@ -153,7 +152,7 @@ def _cpu_worker(job):
     return times
 
 
-def cpu_baseline(wl, seed, units_per_core=8):
+def cpu_baseline(wl, seed, units_per_core=128):
     """The oracle, as it stands, on a bounded sample of units of the same workload, one process
     per host core this process may run on (at most 16, the machine's CPU share).  Must run before the
     GPU is initialised: the workers are forked."""
@@ -171,13 +170,16 @@ def cpu_baseline(wl, seed, units_per_core=8):
     tight = bool(c >= pol.tau)
     t0 = time.perf_counter()
     with mp.get_context("fork").Pool(cores) as pool:
-        per = pool.map(_cpu_worker, [(wl, seed, w, units_per_core, tight) for w in range(cores)])
+        # every units-th unit of the workload, at most units_per_core per worker (all of them when they fit)
+        take = min(wl.units, cores * units_per_core)
+        ids = [int(i) for i in np.linspace(0, wl.units - 1, take).round()] if take < wl.units else list(range(wl.units))
+        per = pool.map(_cpu_worker, [(wl, seed, w, ids[w::cores], tight) for w in range(cores)])
     wall = time.perf_counter() - t0
     times = np.concatenate([np.asarray(p) for p in per])
     per_unit = float(times.mean())                      # with all cores busy at once
     step_s = (per_unit * wl.units + t_conf * wl.batch) / cores
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
-            "sample": f"{times.size} of {wl.units} units of workload {wl.name} (attend + evict/compact/demote, "
+            "sample": f"{'all ' if times.size == wl.units else ''}{times.size} of {wl.units} units of workload {wl.name} (attend + evict/compact/demote, "
                       f"{per_unit * 1e3:.2f} ms per unit with {cores} processes busy) plus 1 of {wl.batch} confidence "
                       f"rows ({t_conf * 1e3:.2f} ms); extrapolated to all units spread over the {cores} cores "
                       f"(os.cpu_count() = {os.cpu_count()}, affinity = {len(os.sched_getaffinity(0))}; "

@@ -108,11 +108,15 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 // tag base and the position of the next appended token live in cv.ctl, where the commit at the
 // end of conf_kv_evict_compact advances them.  A recorded sequence of launches can therefore be
 // replayed: nothing that changes from step to step is a launch argument.
+// The two words are only requested here: the first instruction that needs one of them (the
+// append, the publish at the end of the stream) is where the kernel waits, long after the tile
+// requests have gone out.
 __device__ __forceinline__ AttendLaunch resolve_launch(const CacheView &cv, AttendLaunch a) {
-  a.epoch += __builtin_amdgcn_readfirstlane(cv.ctl[kCtlTag]);
-  a.pos_new = __builtin_amdgcn_readfirstlane(cv.ctl[kCtlPos + a.layer]);
+  a.tag_base = cv.ctl[kCtlTag];
+  a.pos_new = (int)cv.ctl[kCtlPos + a.layer];
   return a;
 }
+__device__ __forceinline__ unsigned tag_of(const AttendLaunch &a) { return a.tag_base + a.epoch; }
 
 __device__ __forceinline__ void st_tagged(unsigned long long *p, unsigned epoch, float v) {
   __hip_atomic_store(p, ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(v),
@@ -490,7 +494,7 @@ __device__ __forceinline__ bool collect_ml(const CacheView &cv, const AttendLaun
     for (;;) {
       if (!here) {
         const unsigned long long wv = ld_tagged(&words[idx]);
-        if ((unsigned)(wv >> 32) == a.epoch) {
+        if ((unsigned)(wv >> 32) == tag_of(a)) {
           pml[idx] = __uint_as_float((unsigned)wv);
           here = true;
         }
@@ -595,8 +599,8 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       l = fmaf(live ? wl[k * G + tid] : 0.f, live ? __expf(mk - M) : 0.f, l);
     }
     if (!a.withhold || sl.j != 0) {                   // (test hook: split 0 keeps its words to itself)
-      st_tagged(&ml[tid * 2], a.epoch, M);
-      st_tagged(&ml[tid * 2 + 1], a.epoch, l);
+      st_tagged(&ml[tid * 2], tag_of(a), M);
+      st_tagged(&ml[tid * 2 + 1], tag_of(a), l);
     }
   }
   // workgroup merge of the per-wavefront output partials: kEPT channels per thread, each
@@ -648,7 +652,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
       if (idx % D == 0) { gm[h] = M; ginv[h] = inv; ginv[G + h] = inv * row_weight(a, tq, gq, h); }
     } else {
 #pragma unroll
-      for (int e = 0; e < kEPT; ++e) st_tagged(&po[idx + e], a.epoch, o[e]);
+      for (int e = 0; e < kEPT; ++e) st_tagged(&po[idx + e], tag_of(a), o[e]);
     }
   }
   TS(19);
@@ -725,16 +729,16 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
         const int e = sl.j * per + base + oe;                          // element of the [G][D] output
         const bool valid = os < ns && base + oe < per && e < G * D;
         const unsigned long long *src = &pou[(size_t)os * G * D + (valid ? e : 0)];
-        unsigned long long wv = base == 0 ? ((unsigned)(opre >> 32) == a.epoch ? opre : opre2) : (valid ? ld_tagged(src) : 0ull);
+        unsigned long long wv = base == 0 ? ((unsigned)(opre >> 32) == tag_of(a) ? opre : opre2) : (valid ? ld_tagged(src) : 0ull);
         // a word that is not this launch's yet is asked for again (bounded); in a second launch
         // every word is there
-        bool here = !valid || (unsigned)(wv >> 32) == a.epoch;
+        bool here = !valid || (unsigned)(wv >> 32) == tag_of(a);
         for (int spins = 0; __builtin_amdgcn_ballot_w64(!here) != 0ull; ++spins) {
           if (spins > a.spin_limit) break;
           __builtin_amdgcn_s_sleep(1);
           if (!here) {
             wv = ld_tagged(src);
-            here = (unsigned)(wv >> 32) == a.epoch;
+            here = (unsigned)(wv >> 32) == tag_of(a);
           }
         }
         const unsigned long long missing = __builtin_amdgcn_ballot_w64(!here);

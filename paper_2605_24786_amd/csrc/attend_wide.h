@@ -380,11 +380,11 @@ void attend_wide_kernel(CacheView cv, AttendLaunch a_in, int ns, int /*unused*/)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (t16 == 0) {
-          st_tagged(&a.part_ml[(row0 + rowc[i]) * 2], a.epoch, mrun[i]);
-          st_tagged(&a.part_ml[(row0 + rowc[i]) * 2 + 1], a.epoch, lrun[i]);
+          st_tagged(&a.part_ml[(row0 + rowc[i]) * 2], tag_of(a), mrun[i]);
+          st_tagged(&a.part_ml[(row0 + rowc[i]) * 2 + 1], tag_of(a), lrun[i]);
         }
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) st_tagged(&a.part_o[(row0 + rowc[i]) * D + 16 * nt + t16], a.epoch, O[nt][i]);
+        for (int nt = 0; nt < 8; ++nt) st_tagged(&a.part_o[(row0 + rowc[i]) * D + 16 * nt + t16], tag_of(a), O[nt][i]);
       }
     }
     // every thread gathers some of the ns * R * 2 statistics words of the unit (bounded poll)
@@ -396,7 +396,7 @@ void attend_wide_kernel(CacheView cv, AttendLaunch a_in, int ns, int /*unused*/)
       for (int spins = 0;; ++spins) {
         if (!here) {
           const unsigned long long wv = ld_tagged(&words[idx]);
-          if ((unsigned)(wv >> 32) == a.epoch) {
+          if ((unsigned)(wv >> 32) == tag_of(a)) {
             pml[idx] = __uint_as_float((unsigned)wv);
             here = true;
           }
@@ -446,7 +446,7 @@ void attend_wide_kernel(CacheView cv, AttendLaunch a_in, int ns, int /*unused*/)
           for (int i = 0; i < 4; ++i) wv[i] = ld_tagged(&src[(size_t)rowc[i] * D]);
           bool here = true;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) here &= (unsigned)(wv[i] >> 32) == a.epoch;
+          for (int i = 0; i < 4; ++i) here &= (unsigned)(wv[i] >> 32) == tag_of(a);
           for (int spins = 0; __builtin_amdgcn_ballot_w64(!here) != 0ull; ++spins) {
             if (spins > a.spin_limit) break;
             __builtin_amdgcn_s_sleep(1);
@@ -455,7 +455,7 @@ void attend_wide_kernel(CacheView cv, AttendLaunch a_in, int ns, int /*unused*/)
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
                 wv[i] = ld_tagged(&src[(size_t)rowc[i] * D]);
-                here &= (unsigned)(wv[i] >> 32) == a.epoch;
+                here &= (unsigned)(wv[i] >> 32) == tag_of(a);
               }
             }
           }

@@ -48,7 +48,8 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
     uint8_t *__restrict__ sel, CacheView cv, double tau, double wH, double wm, double wp) {
   // the words' tag: the launch's number plus, for the handle's own words, the base the commit
   // at the end of conf_kv_evict_compact advances (so that a recorded launch can be replayed)
-  const unsigned epoch = launch_no + (device_base ? __builtin_amdgcn_readfirstlane(cv.ctl[kCtlConfTag]) : 0u);
+  // (requested now, added where the partial is published: the logits loads go out first)
+  const unsigned tag_base = device_base ? cv.ctl[kCtlConfTag] : 0u;
   __shared__ float s_f[4 * 4];
   __shared__ double s_d[4 * 2];
   __shared__ int s_ok;
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(kConfThreads) void conf_reduce_kernel(
   T = wave_sum(T);
   if (lane == 0) { s_f[8 + w] = S; s_f[12 + w] = T; }
   __syncthreads();
+  const unsigned epoch = launch_no + tag_base;
   if (tid == 0 && withhold && c == 0) s_ok = 1;       // (test hook: chunk 0 keeps its words to itself)
   if (tid == 0 && !(withhold && c == 0)) {
     unsigned long long *p = partial + ((size_t)b * nchunk + c) * kPartialStride;

@@ -53,6 +53,7 @@ struct AttendLaunch {
   int max_splits;
   float sm_scale, ema_decay;
   double mass_gain;        // weight of the step's mass in the EMA update
+  unsigned tag_base;       // filled in by the kernels from cv.ctl
   int pos_new;             // position of the first appended token (the kernels read it from cv.ctl)
   int tq;                  // tokens appended (and queries per head) in this call
   int q_tokens;            // tokens per sequence in the q tensor: q is [B][q_tokens][Hq][D] and the call's
