@@ -12,8 +12,9 @@
 //   stream   running (max, normaliser, output) per head (online softmax); the raw scores
 //            s[h][i] of the slice stay in LDS
 //   publish  the workgroup's (m, l) per head go out first, then its merged output partial;
-//            every published 8-byte word carries the epoch of the launch, so nothing waits for
-//            stores to land and no counter is shared
+//            every published 8-byte word carries the launch's tag (its number since the last
+//            commit plus a base kept on the device), so nothing waits for stores to land, no
+//            counter is shared, and a recorded launch can be replayed
 //   mass     gather the (m, l) words of every split of the unit (a bounded poll on their
 //            tags: they all publish at about the same time), form the exact global (M, L),
 //            then per slot A_i = sum_h e^{s[h][i]-M[h]} / L[h] and
@@ -100,10 +101,9 @@ __device__ __forceinline__ unsigned dword_of(const int4 &v, int q) {
 // coherent for ordinary accesses) through agent-scope relaxed atomics: such loads and
 // stores are coherent across the device by themselves, so no cache-wide release/acquire
 // fence (an L2 write-back plus invalidate on this hardware) is ever issued.  No ordering
-// between different words is needed either: every published word carries the epoch of the
+// between different words is needed either: every published word carries the tag of the
 // launch that wrote it, so a reader can tell on its own whether the word it got is current.
-// A float that travels with the epoch of the launch that wrote it: one 8-byte word, so a
-// reader sees value and tag together or neither.
+
 // The host passes a launch's number since the last commit and the device completes it: the
 // tag base and the position of the next appended token live in cv.ctl, where the commit at the
 // end of conf_kv_evict_compact advances them.  A recorded sequence of launches can therefore be
@@ -118,6 +118,8 @@ __device__ __forceinline__ AttendLaunch resolve_launch(const CacheView &cv, Atte
 }
 __device__ __forceinline__ unsigned tag_of(const AttendLaunch &a) { return a.tag_base + a.epoch; }
 
+// A float that travels with the tag of the launch that wrote it: one 8-byte word, so a
+// reader sees value and tag together or neither.
 __device__ __forceinline__ void st_tagged(unsigned long long *p, unsigned epoch, float v) {
   __hip_atomic_store(p, ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(v),
                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -475,9 +477,10 @@ __device__ __forceinline__ void store_stream_partial(Stream<G> &st, int pidx, fl
 }
 
 // Arrival and the gather of the softmax statistics in one: every split publishes its (m, l)
-// per head as words tagged with the launch's epoch -- after its output partial is complete in
-// memory -- and thread k polls word k of the unit until the tag is this launch's, then drops
-// the value into LDS.  Seeing a split's words therefore means its output partial may be read.
+// per head as words tagged with the launch's tag (tag_of: the launch's number plus the base
+// on the device), and thread k polls word k of the unit until the tag is this launch's, then
+// drops the value into LDS.  The output partials travel as tagged words of their own and are
+// polled where they are used, so seeing a split's statistics says nothing about its partial.
 // Nobody does a read-modify-write, so arrivals do not serialise at the memory side.  The wait
 // is bounded; false means it expired (counted as a device error).  Contains a workgroup
 // barrier; *s_ok must have been set to 1 before the barrier that precedes the call.
