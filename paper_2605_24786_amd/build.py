@@ -25,6 +25,12 @@ FLAGS = [
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     extra = ["-DCONFKV_TRACE"] if os.environ.get("CONFKV_TRACE") else []   # in-kernel phase trace
+    # Leading scalar kernel arguments arrive in registers when a wavefront starts (kernarg preload;
+    # the code objects keep the ordinary fetch as their fall-back entry): the attention and the
+    # confidence kernels put what their first memory request needs there.  CONFKV_PRELOAD=0: off.
+    preload = os.environ.get("CONFKV_PRELOAD", "7")
+    if preload != "0":
+        extra += ["-mllvm", "-amdgpu-kernarg-preload-count=" + preload]
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -188,7 +188,9 @@ __device__ __forceinline__ int unit_in_layer(const CacheView &cv, const AttendLa
 // Every split takes an equal share of the INT8 slots (cut at multiples of 32, the tile of
 // the matrix-core body) and an equal share of the FP16 slots, so all splits of a unit carry
 // the same mix of work and reach the arrival point together.
-__device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLaunch &a, int ns, int S) {
+// words: the unit's counters when the kernel has requested them already (see unit_words), else null.
+__device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLaunch &a, int ns, int S,
+                                            const int *words = nullptr) {
   Slice s;
   s.g = kv_head_index(a);
   s.b = blockIdx.z;
@@ -201,7 +203,7 @@ __device__ __forceinline__ Slice make_slice(const CacheView &cv, const AttendLau
   // compiler, each waiting for the one before).
   const int k4 = threadIdx.x & 3;
   const int32_t *arr = k4 == 0 ? cv.len : k4 == 1 ? cv.n8 : k4 == 2 ? cv.head16 : cv.head8;
-  const int mv = arr[s.u];
+  const int mv = words ? *words : arr[s.u];
   const int len = __builtin_amdgcn_readlane(mv, 0), n8 = __builtin_amdgcn_readlane(mv, 1);
   s.h16 = __builtin_amdgcn_readlane(mv, 2);
   s.h8 = __builtin_amdgcn_readlane(mv, 3);
@@ -823,7 +825,7 @@ __device__ __forceinline__ void attend_epilogue(const CacheView &cv, const Atten
 // kSpill: the first launch of the two-launch form -- the slice's raw scores go to device
 // scratch instead of LDS and the kernel ends after publishing its partial.
 template <int D, int G, bool kSpill = false>
-__global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, AttendLaunch a_in, int ns,
+__global__ __launch_bounds__(kAttThreads) void attend_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t *w_h16, const int32_t *w_h8, int w_unit0, int w_hkv, int w_kvm, CacheView cv, AttendLaunch a_in, int ns,
                                                              int S) {
   const AttendLaunch a = resolve_launch(cv, a_in);
   constexpr int NP = kAttWaves;
@@ -876,7 +878,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(CacheView cv, Atten
 // Second launch of the two-launch form: same grid; merges the published partials of the unit,
 // updates the EMA of its slice from the spilled scores and normalises its share of the output.
 template <int D, int G, int DR = D>
-__global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(CacheView cv, AttendLaunch a_in, int ns,
+__global__ __launch_bounds__(kAttThreads) void attend_finish_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t *w_h16, const int32_t *w_h8, int w_unit0, int w_hkv, int w_kvm, CacheView cv, AttendLaunch a_in, int ns,
                                                                     int S) {
   const AttendLaunch a = resolve_launch(cv, a_in);
   extern __shared__ __align__(16) float smem[];
@@ -1025,7 +1027,13 @@ __device__ __forceinline__ float rows_to_tile(const float (&x)[RowMap<G>::NV], i
 template <int G, bool kChan = false, bool kSpill = false, int DR = 128>
 __global__ __launch_bounds__(kAttThreads)
 __attribute__((amdgpu_waves_per_eu((kChan || G > 8) ? 2 : 3, (kChan || G > 8) ? 2 : 3)))
-void attend_mfma_kernel(CacheView cv, AttendLaunch a_in, int ns, int S) {
+void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t *w_h16, const int32_t *w_h8, int w_unit0, int w_hkv, int w_kvm, CacheView cv, AttendLaunch a_in, int ns, int S) {
+  // The unit's counters are requested before anything else, from leading scalar kernel arguments
+  // (the four arrays, the layer's first unit, the kv-head count, the grid order): the hardware
+  // can hand those over in registers when the wavefront starts, so this request does not wait
+  // for the fetch of the argument block as everything else does.
+  const int w_words = (((threadIdx.x & 3) == 0 ? w_len : (threadIdx.x & 3) == 1 ? w_n8 : (threadIdx.x & 3) == 2 ? w_h16 : w_h8))
+      [w_unit0 + blockIdx.z * w_hkv + (w_kvm ? blockIdx.x : blockIdx.y)];
   const AttendLaunch a = resolve_launch(cv, a_in);
   // D: channels of the tiles and partials on chip.  DR: the head dimension in memory; a 64-channel
   // head runs on the same tiles with channels 64..127 holding a second copy of its rows against
@@ -1064,7 +1072,7 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a_in, int ns, int S) {
     const int32_t *gt = cv.pt + (size_t)(a.layer * cv.B * cv.Hkv + unit_in_layer(cv, a)) * cv.npages;
     for (int i = tid; i < cv.npages; i += kAttThreads) tab[i] = gt[i];
   }
-  Slice sl = make_slice(cv, a, ns, S);
+  Slice sl = make_slice(cv, a, ns, S, &w_words);
   if (cv.page_lg) {
     sl.tab = tab;
     __syncthreads();
@@ -1471,7 +1479,8 @@ void attend_mfma_kernel(CacheView cv, AttendLaunch a_in, int ns, int S) {
 // host side
 // ---------------------------------------------------------------------------------------
 
-typedef void (*AttendFn)(CacheView, AttendLaunch, int, int);
+typedef void (*AttendFn)(const int32_t *, const int32_t *, const int32_t *, const int32_t *, int, int, int, CacheView,
+                         AttendLaunch, int, int);
 
 static std::atomic<bool> g_use_mfma{true};
 
@@ -1741,10 +1750,10 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a_in, const At
     AttendFn first = plan.mfma ? attend_fn_mfma_spill(cv.D, rows2, cv.chan != 0) : attend_fn_spill(cv.D, cv.G, false);
     AttendFn second = plan.mfma && cv.D == 64 ? attend_fn_finish_padded(rows2) : attend_fn_spill(cv.D, rows2, true);
     if (!first || !second || !a.spill) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
+    hipLaunchKernelGGL(first, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv.len, cv.n8, cv.head16, cv.head8, a.layer * cv.B * cv.Hkv, cv.Hkv, a.kv_major, cv, a, plan.splits,
                        plan.stash_tokens);
     const size_t lds2 = ((size_t)plan.splits * rows2 * 2 + rows2 + 2) * sizeof(float) + 2 * rows2 * sizeof(double);
-    hipLaunchKernelGGL(second, grid, dim3(kAttThreads), lds2, stream, cv, a, plan.splits,
+    hipLaunchKernelGGL(second, grid, dim3(kAttThreads), lds2, stream, cv.len, cv.n8, cv.head16, cv.head8, a.layer * cv.B * cv.Hkv, cv.Hkv, a.kv_major, cv, a, plan.splits,
                        plan.stash_tokens);
     return hipGetLastError();
   }
@@ -1753,7 +1762,7 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a_in, const At
                     : plan.wide_rb == 4 ? (AttendFn)attend_wide_kernel<4> : (AttendFn)attend_wide_kernel<8>;
     a.dbg = nullptr;
     a.max_splits = kWideMaxSplits;
-    hipLaunchKernelGGL(wide, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits, 0);
+    hipLaunchKernelGGL(wide, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv.len, cv.n8, cv.head16, cv.head8, a.layer * cv.B * cv.Hkv, cv.Hkv, a.kv_major, cv, a, plan.splits, 0);
     return hipGetLastError();
   }
   const bool rows16 = a.tq > 1 || a.observe_first >= 0 || cv.G > 8;
@@ -1767,11 +1776,11 @@ hipError_t launch_attend(const CacheView &cv, const AttendLaunch &a_in, const At
     at.trace_off = (int)((plan.lds_bytes + 15) / 16 * 16);
     const size_t lds = at.trace_off + kAttWaves * 32 * 8;
     (void)hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), lds, stream, cv, at, plan.splits, plan.stash_tokens);
+    hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), lds, stream, cv.len, cv.n8, cv.head16, cv.head8, a.layer * cv.B * cv.Hkv, cv.Hkv, a.kv_major, cv, at, plan.splits, plan.stash_tokens);
     return hipGetLastError();
   }
 #endif
-  hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv, a, plan.splits,
+  hipLaunchKernelGGL(fn, grid, dim3(kAttThreads), plan.lds_bytes, stream, cv.len, cv.n8, cv.head16, cv.head8, a.layer * cv.B * cv.Hkv, cv.Hkv, a.kv_major, cv, a, plan.splits,
                      plan.stash_tokens);
   return hipGetLastError();
 }

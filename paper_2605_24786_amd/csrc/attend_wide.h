@@ -27,7 +27,7 @@ __host__ __device__ constexpr size_t attend_wide_lds_bytes(int R, int ns) {
 
 template <int RB>
 __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void attend_wide_kernel(CacheView cv, AttendLaunch a_in, int ns, int /*unused*/) {
+void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const int32_t *, int , int , int , CacheView cv, AttendLaunch a_in, int ns, int /*unused*/) {
   const AttendLaunch a = resolve_launch(cv, a_in);
   constexpr int D = 128, NS = kAttWaves / RB, R = RB * 16;
   constexpr int kPartFloats = 16 * D + 32;                   // a wavefront's (o, m, l) for the stream merge
