@@ -7,7 +7,8 @@
 // head are cut into RB blocks of 16; a workgroup of eight wavefronts is RB row blocks times
 // NS = 8 / RB tile streams.  The slice's K/V tiles (32 INT8 slots or 16 FP16 slots each) are
 // brought into LDS eight at a time, one per wavefront -- every K/V byte is read from memory
-// once per pass whatever the number of rows -- and each wavefront then runs ITS row block
+// once per pass whatever the number of rows, and INT8 keys become fp16 once, when the tile is
+// stored -- and each wavefront then runs ITS row block
 // against the tiles of its stream: scores by matrix core, online softmax per row, P V by matrix
 // core.  No score is stashed (R x slots floats would not fit anywhere): after the splits have
 // exchanged their (m, l, o) per row, a second pass streams the keys again, recomputes the same
@@ -16,8 +17,14 @@
 // updates the EMA.  Key bytes are therefore read twice, value bytes once.
 #pragma once
 
-constexpr int kWideScaleBytes = 2 * kTile * 4;              // per-slot score factor and value scale of a tile
-constexpr int kWideTileBytes = kTileBytes + kWideScaleBytes;
+// A tile in LDS: K as fp16 rows (the codes of an INT8 tile are converted once, by the wavefront
+// that stores the tile, not once per row block that reads it), V transposed as stored (its
+// conversion is three instructions per four codes and stays with the reader), the reading
+// wavefront's probability tile, and per slot the score factor and the value scale.
+constexpr int kWideKBytes = kTile * kKRow16;
+constexpr int kWideCoreBytes = kWideKBytes + kVBytes + 16 * kPRow * 2;
+constexpr int kWideScaleBytes = 2 * kTile * 4;
+constexpr int kWideTileBytes = kWideCoreBytes + kWideScaleBytes;
 constexpr int kWideMaxRows = 128;
 constexpr int kWideMaxSplits = 8;
 
@@ -137,13 +144,19 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
   // and per slot the factor of the raw score (key scale times softmax scale) and the value scale
   auto store_item = [&](int it, const TileRegs &tr, bool with_v) {
     uint8_t *Kt = tiles + (size_t)w * kWideTileBytes;
-    uint8_t *Vt = Kt + kTile * kKRow;
-    float *sc = (float *)(Kt + kTileBytes);
+    uint8_t *Vt = Kt + kWideKBytes;
+    float *sc = (float *)(Kt + kWideCoreBytes);
     if (it < ntiles) {
-      *(int4 *)(Kt + (r8)*kKRow + c8 * 16) = tr.k0;
-      *(int4 *)(Kt + (8 + r8) * kKRow + c8 * 16) = tr.k1;
-      *(int4 *)(Kt + (16 + r8) * kKRow + c8 * 16) = tr.k2;
-      *(int4 *)(Kt + (24 + r8) * kKRow + c8 * 16) = tr.k3;
+      // sixteen codes of a row per lane -> sixteen fp16 values (exact)
+      auto put_k = [&](int row, const int4 &k) {
+        half8_t *dst = (half8_t *)(Kt + row * kKRow16 + c8 * 32);
+        dst[0] = cvt_i8x8_f16x8((unsigned)k.x, (unsigned)k.y);
+        dst[1] = cvt_i8x8_f16x8((unsigned)k.z, (unsigned)k.w);
+      };
+      put_k(r8, tr.k0);
+      put_k(8 + r8, tr.k1);
+      put_k(16 + r8, tr.k2);
+      put_k(24 + r8, tr.k3);
       if (with_v) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -204,13 +217,11 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
   // raw scores of the 16 rows against the 16 slots [16 sb, 16 sb + 16) of INT8 tile buffer Kt,
   // or against the 16 slots of an FP16 tile; masked entries come back as -inf
   auto scores8 = [&](const uint8_t *Kt, const float *sc, int base, int sb, float (&sv)[4]) {
-    const uint8_t *krow = Kt + (16 * sb + t16) * kKRow + g4 * 32;
-    const int4 b0 = *(const int4 *)(krow), b1 = *(const int4 *)(krow + 16);
+    const uint8_t *krow = Kt + (16 * sb + t16) * kKRow16 + g4 * 64;
     floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[0], cvt_i8x8_f16x8(b0.x, b0.y), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[1], cvt_i8x8_f16x8(b0.z, b0.w), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[2], cvt_i8x8_f16x8(b1.x, b1.y), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[3], cvt_i8x8_f16x8(b1.z, b1.w), acc, 0, 0, 0);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[s], *(const half8_t *)(krow + 16 * s), acc, 0, 0, 0);
     const int slot = base + 16 * sb + t16;
     const float f = sc[16 * sb + t16];
 #pragma unroll
@@ -231,7 +242,7 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
   TileRegs tr = {};
   if (w < nitems) tr = load_item(w, true);
   append_new_token<D, false>(cv, a, sl, ns);
-  _Float16 *Pb = (_Float16 *)(tiles + (size_t)w * kWideTileBytes + kTile * kKRow + kVBytes);   // [16][kPRow], this wavefront's own
+  _Float16 *Pb = (_Float16 *)(tiles + (size_t)w * kWideTileBytes + kWideKBytes + kVBytes);   // [16][kPRow], this wavefront's own
   for (int i = lane; i < 16 * kPRow / 2; i += kWave) ((unsigned *)Pb)[i] = 0u;
   floatx4_t O[8];
 #pragma unroll
@@ -250,8 +261,8 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
       const int it = sup * kAttWaves + j;
       if (it >= nitems) break;
       const uint8_t *Kt = tiles + (size_t)j * kWideTileBytes;
-      const uint8_t *Vt = Kt + kTile * kKRow;
-      const float *sc = (const float *)(Kt + kTileBytes);
+      const uint8_t *Vt = Kt + kWideKBytes;
+      const float *sc = (const float *)(Kt + kWideCoreBytes);
       if (it < ntiles) {
         const int base = sl.lo8 + it * kTile;
         float sv[2][4];
@@ -528,7 +539,7 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
       const int it = sup * kAttWaves + j;
       if (it >= nitems) break;
       const uint8_t *Kt = tiles + (size_t)j * kWideTileBytes;
-      const float *sc = (const float *)(Kt + kTileBytes);
+      const float *sc = (const float *)(Kt + kWideCoreBytes);
       const int halves = it < ntiles ? 2 : 1;
       for (int sb = 0; sb < halves; ++sb) {
         float sv[4];
