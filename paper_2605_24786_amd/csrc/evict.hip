@@ -857,7 +857,9 @@ constexpr int kSmallE = 4;
 
 // kShared: the importance is the float64 sum over the kv-heads of the (layer, sequence), which
 // shared_mass_kernel left in shared_all (indexed by slot, not by ring row).
-template <bool kShared>
+// kBatch: loads a lane has in flight at a time (8 keeps the registers few enough for thousands of
+// units per launch; 32 covers a 2048-slot unit in one round trip per pass when there are few units).
+template <bool kShared, int kBatch = 8>
 __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, LayerMask appended,
                                                                 double alpha,
                                                                 const double *__restrict__ shared_all,
@@ -897,7 +899,6 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
   const int nx = cv.cap8 == 0 ? n : n8;              // slots of the ring a right shift could serve
   // loads go out in batches of kBatch (indices past the end re-read the last candidate), so a
   // long unit costs a few memory round trips per pass and not one per 64 slots
-  constexpr int kBatch = 8;
   typedef typename std::conditional<kShared, double, float>::type Imp;   // importance as stored
   Imp fmin_ = INFINITY, fmax_ = -INFINITY;
   for (int base = 0; base < ncand; base += kBatch * kWave) {
@@ -1317,8 +1318,12 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
       hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
                          1, score, src, sel);
   } else {
-  hipLaunchKernelGGL(rank_small_kernel<false>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                     (const double *)nullptr, src, sel, U, 0);
+  if (U <= 4096)    // few wavefronts per SIMD: registers to spare for deeper batches
+    hipLaunchKernelGGL((rank_small_kernel<false, 32>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended,
+                       alpha, (const double *)nullptr, src, sel, U, 0);
+  else
+    hipLaunchKernelGGL((rank_small_kernel<false, 8>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended,
+                       alpha, (const double *)nullptr, src, sel, U, 0);
   // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
   // nothing); with few units the chip is filled by giving each unit four wavefronts.
   if (n_max <= 64 * 33 && U >= 2048)
