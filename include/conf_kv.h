@@ -191,7 +191,7 @@ typedef struct conf_kv_stats {
  * of 0, so that a test reaches the clearing of the exchange words in a few steps. */
 
 /* Bytes of device memory the caller must provide for the cache state and for scratch
- * (split partials, arrival counters, ranking work arrays).  0 on an invalid config. */
+ * (tagged exchange words of the splits and chunks, ranking work arrays).  0 on an invalid config. */
 size_t conf_kv_state_bytes(const conf_kv_config *cfg);
 size_t conf_kv_scratch_bytes(const conf_kv_config *cfg);
 
