@@ -194,31 +194,45 @@ class Lockstep:
         self.compare_state(f"after observe {first}+{tq}")
 
     # ---- a decode step recorded once into a HIP graph and replayed ----
-    def record_step(self):
-        """Record the calls of one decode step (one conf_kv_attend per layer, conf_kv_step,
-        conf_kv_evict_compact) into a graph over fixed input / output tensors.  Nothing runs
-        while recording; every later ``step`` fills the tensors and replays the graph."""
+    def record_step(self, tq: int = 1):
+        """Record the calls of one decode step (one conf_kv_attend -- or, with tq > 1, one
+        conf_kv_attend_chunk of tq tokens -- per layer, conf_kv_step, conf_kv_evict_compact) into
+        a graph over fixed input / output tensors.  Nothing runs while recording; every later
+        ``step`` fills the tensors and replays the graph."""
         torch, wl, kv = self.torch, self.wl, self.kv
         L, B, Hq, Hkv, D = wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
-        self.gq = torch.zeros((L, B, Hq, D), dtype=torch.float16, device="cuda")
-        self.gk = torch.zeros((L, B, Hkv, D), dtype=torch.float16, device="cuda")
-        self.gv = torch.zeros((L, B, Hkv, D), dtype=torch.float16, device="cuda")
-        self.gout = torch.zeros((L, B, Hq, D), dtype=torch.float16, device="cuda")
+        tok = () if tq == 1 else (tq,)
+        self.gq = torch.zeros((L, B) + tok + (Hq, D), dtype=torch.float16, device="cuda")
+        self.gk = torch.zeros((L, B) + tok + (Hkv, D), dtype=torch.float16, device="cuda")
+        self.gv = torch.zeros((L, B) + tok + (Hkv, D), dtype=torch.float16, device="cuda")
+        self.gout = torch.zeros((L, B) + tok + (Hq, D), dtype=torch.float16, device="cuda")
         self.glogits = torch.zeros((B, wl.vocab), dtype=torch.float32, device="cuda")
         self.graph = torch.cuda.CUDAGraph()
+        self.graph_tq = tq
         with torch.cuda.graph(self.graph):
             for l in range(L):
-                kv.attend(l, self.gq[l], self.gk[l], self.gv[l], self.gout[l])
+                if tq == 1:
+                    kv.attend(l, self.gq[l], self.gk[l], self.gv[l], self.gout[l])
+                else:
+                    kv.attend_chunk(l, self.gq[l], self.gk[l], self.gv[l], self.gout[l])
             kv.step(self.glogits, self.conf, self.sel)
             kv.evict_compact()
         self.replays = 0
 
     def _replay(self):
-        torch, wl = self.torch, self.wl
-        ins = [gen.step_inputs(wl, self.seed, l, self.t) for l in range(wl.n_layers)]
+        """Fill the recorded tensors with this step's inputs and replay; returns the per-layer
+        (q, k, v) the oracle gets and the outputs ([L][B][Hq][D], or [L][B][tq][Hq][D])."""
+        torch, wl, tq = self.torch, self.wl, self.graph_tq
+        if tq == 1:
+            ins = [gen.step_inputs(wl, self.seed, l, self.t) for l in range(wl.n_layers)]
+        else:
+            ins = []
+            for l in range(wl.n_layers):
+                parts = [gen.step_inputs(wl, self.seed, l, self.t + i) for i in range(tq)]
+                ins.append(tuple(np.ascontiguousarray(np.stack([p[j] for p in parts], axis=1)) for j in range(3)))
         for j, dst in enumerate((self.gq, self.gk, self.gv)):
             dst.copy_(torch.from_numpy(np.stack([x[j] for x in ins])))
-        self.glogits.copy_(torch.from_numpy(gen.step_logits(wl, self.seed, self.t)))
+        self.glogits.copy_(torch.from_numpy(gen.step_logits(wl, self.seed, self.t + tq - 1)))
         self.gout.zero_()
         self.graph.replay()
         self.replays += 1
@@ -233,13 +247,18 @@ class Lockstep:
         G = wl.group
         replayed = None
         if getattr(self, "graph", None) is not None:
-            assert tq == 1
+            assert tq == self.graph_tq, "a recorded step is replayed with the token count it was recorded with"
             replayed = self._replay()
         for l in range(wl.n_layers):
-            if replayed is not None:
+            if replayed is not None and tq == 1:
                 q, k, v = replayed[0][l]
                 ref = self.run.attend(l, q, k, v, G)
                 got = replayed[1][l]
+            elif replayed is not None:
+                q, k, v = replayed[0][l]
+                ref = self.run.attend_chunk(l, q, k, v, G)
+                got = replayed[1][l].transpose(0, 2, 1, 3)                       # [B][Hq][tq][D]
+                ref = {key: r.transpose(1, 0, 2) for key, r in ref.items()}      # [G][tq][D]
             elif tq == 1:
                 q, k, v = gen.step_inputs(wl, self.seed, l, self.t)
                 kv.attend(l, torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(),

@@ -61,6 +61,28 @@ def test_replayed_steps_match_the_oracle(lib, case):
     ls.close()
 
 
+@pytest.mark.parametrize("G,tq,mc", [(4, 4, 4), (4, 16, 16)])
+def test_replayed_multi_token_steps(lib, G, tq, mc):
+    """Steps of tq tokens per call (the 16-row kernel, and the many-rows kernel at 64 rows per
+    kv-head) recorded once and replayed: positions move on by tq per replay, the telescoped
+    importance update and the eviction behind it match the oracle at every step."""
+    wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=128, vocab=3001, prefill=300,
+                         steps=40, n_tight=(180, 150), n_loose=(330, 300), protected=40, fp16_window=24, alpha=0.5,
+                         logit_std=(0.5, 6.0), logit_run=3, max_chunk=mc)
+    say(f"graph replay of {tq}-token steps: G={G}")
+    ls = Lockstep(lib, wl, seed=47)
+    ls.kv.static_plan(True)
+    ls.step(tq=tq)
+    ls.record_step(tq)
+    for t in range(1, wl.steps):
+        ls.step(check_state=(t % 8 == 0 or t == wl.steps - 1), tq=tq)
+    rep = ls.report
+    say(f"  {ls.replays} replays: evictions {rep.evictions}, lengths {min(rep.lengths)}..{max(rep.lengths)}")
+    assert ls.replays == wl.steps - 1 and rep.ok() and rep.evictions > 0
+    assert ls.kv.counters().device_errors == 0
+    ls.close()
+
+
 def test_static_plan_changes_no_result(lib):
     """The same eager run of a growing cache with and without conf_kv_static_plan (more splits
     from the first step on): same kept sets, outputs and EMA equal up to the summation order."""
