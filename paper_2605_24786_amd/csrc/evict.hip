@@ -300,6 +300,22 @@ __device__ __forceinline__ unsigned long long splitmix64(unsigned long long x) {
   return z ^ (z >> 31);
 }
 
+// Random ranker: the score of a slot is a counter-based uniform draw keyed by (seed, unit or
+// (layer, sequence), original position), as the bits of the double it is: exact (53 bits, a
+// power-of-two scale), so it orders like the oracle's draw.
+struct RandomRank {
+  int on;                      // 0: the composite score
+  int layer_scope;             // the kv-heads of a (layer, sequence) draw the same numbers
+  unsigned long long seed;
+};
+__device__ __forceinline__ unsigned long long random_unit_key(const CacheView &cv, const RandomRank &rr, int u) {
+  return rr.layer_scope ? (1ull << 40) + (unsigned long long)(u / cv.Hkv) : (unsigned long long)u;
+}
+__device__ __forceinline__ unsigned long long random_key(const RandomRank &rr, unsigned long long unit_key, int pos) {
+  const unsigned long long r = splitmix64(rr.seed + (unit_key << 32) + (unsigned long long)(long long)pos);
+  return (unsigned long long)__double_as_longlong((double)(r >> 11) * 0x1.0p-53);
+}
+
 // Layer scope: shared[(layer, b)][slot] = sum over the kv-heads, in kv-head order, of the
 // unit's EMA as float64.  Grid (L * B, ceil(cap / 256)).
 __global__ __launch_bounds__(kEvThreads) void shared_mass_kernel(CacheView cv, LayerMask appended,
@@ -581,7 +597,7 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
                                                             double alpha,
                                                             int32_t *__restrict__ src_all,
                                                             int32_t *__restrict__ sel_all,
-                                                            const double *__restrict__ shared_all = nullptr) {
+                                                            const double *__restrict__ shared_all, RandomRank rr) {
   typedef typename std::conditional<kShared, double, float>::type Imp;   // importance as stored
   constexpr int kRsWaves = T / kWave;
   __shared__ int hist[512];                         // two histograms, used alternately
@@ -669,6 +685,7 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
       const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)av[k], a_lo), a_div);
       const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pv[k], p_lo), p_div);
       key[k] = (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
+      if (rr.on) key[k] = random_key(rr, random_unit_key(cv, rr, u), pv[k]);
       kmin = key[k] < kmin ? key[k] : kmin;
       kmax = key[k] > kmax ? key[k] : kmax;
     }
@@ -865,7 +882,7 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
                                                                 const double *__restrict__ shared_all,
                                                                 int32_t *__restrict__ src_all,
                                                                 int32_t *__restrict__ sel_all, int U,
-                                                                int idle_only) {
+                                                                int idle_only, RandomRank rr) {
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * (kEvThreads / kWave) + (threadIdx.x >> 6);
   if (u >= U) return;
@@ -886,8 +903,8 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
     if (lane == 0) write_selection(cv, u, sel, n, n8, n8, n, 0, -1);
     return;
   }
-  // (idle_only: the ranker variants -- random draws, whole pages -- are the general kernel's; this
-  // one then only settles the units that evict nothing, most of them in a decode loop)
+  // (idle_only: whole pages are the general kernel's; this one then only settles the units that
+  // evict nothing, most of them in a decode loop)
   if (e > kSmallE || idle_only) {
     if (lane == 0) sel[7] = 0;                       // left to the general kernel
     return;
@@ -948,7 +965,8 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
           const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)a[r], a_lo), a_div);
           const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)ps[r], p_lo), p_div);
           const unsigned long long key =
-              (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
+              rr.on ? random_key(rr, random_unit_key(cv, rr, u), ps[r])
+                    : (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
           const bool above = key > prev_key || (key == prev_key && i > prev_idx);
           if (i < ncand && above && key < best_key) {  // slots rise within a lane: first one wins a tie
             best_key = key;
@@ -1291,50 +1309,60 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 int n_max, unsigned attend_launches, unsigned conf_launches,
                                 hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
-  if (opt.random || opt.shared || opt.page > 1) {
-    // ranker variants: the one-wavefront kernel first settles the units that evict nothing (with
-    // the layer-shared importance alone, also those that evict a few slots: the steady state),
-    // the general kernel serves the rest
-    if (opt.shared)
+  // The random ranker runs on the same kernels as the composite one (a different key per slot);
+  // with the layer scope it needs no shared importance, only a key common to the kv-heads.
+  RandomRank rr{};
+  rr.on = opt.random;
+  rr.layer_scope = opt.shared != nullptr;
+  rr.seed = opt.seed;
+  const bool shared_imp = opt.shared && !opt.random;          // the ranking reads the summed importance
+  if (opt.page > 1) {
+    // whole pages: the general kernel, behind the one-wavefront kernel that settles the units
+    // that evict nothing (with pages of g slots a unit evicts once in g steps)
+    if (shared_imp)
       hipLaunchKernelGGL(shared_mass_kernel, dim3(cv.L * cv.B, (cv.cap + kEvThreads - 1) / kEvThreads),
                          dim3(kEvThreads), 0, stream, cv, appended, opt.shared);
-    const int pre = opt.shared && !opt.random && opt.page <= 1;
-    if (opt.shared)
-      hipLaunchKernelGGL(rank_small_kernel<true>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                         (const double *)opt.shared, src, sel, U, !pre);
-    else
-      hipLaunchKernelGGL(rank_small_kernel<false>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
-                         (const double *)nullptr, src, sel, U, 1);
-    if (pre && n_max <= 256 * 20)
-      hipLaunchKernelGGL((rank_select_reg_kernel<256, 20, true>), dim3(U), dim3(256), 0, stream, cv, appended,
-                         alpha, src, sel, (const double *)opt.shared);
-    else if (pre && n_max <= 1024 * 33)
-      hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33, true>), dim3(U), dim3(1024), 0, stream, cv, appended,
-                         alpha, src, sel, (const double *)opt.shared);
-    else if (n_max <= 256 * 16)    // (a short unit does not fill 1024 threads, and most units return at once)
+    hipLaunchKernelGGL((rank_small_kernel<false, 8>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                       (const double *)nullptr, src, sel, U, 1, rr);
+    if (n_max <= 256 * 16)    // (a short unit does not fill 1024 threads, and most units return at once)
       hipLaunchKernelGGL(rank_select_kernel<256>, dim3(U), dim3(256), 0, stream, cv, appended, alpha, opt,
                          1, score, src, sel);
+    else
+      hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
+                         1, score, src, sel);
+  } else if (shared_imp) {
+    // layer-shared importance: the summed mass first, then the same three kernel shapes reading it
+    hipLaunchKernelGGL(shared_mass_kernel, dim3(cv.L * cv.B, (cv.cap + kEvThreads - 1) / kEvThreads),
+                       dim3(kEvThreads), 0, stream, cv, appended, opt.shared);
+    hipLaunchKernelGGL((rank_small_kernel<true, 8>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
+                       (const double *)opt.shared, src, sel, U, 0, rr);
+    if (n_max <= 256 * 20)
+      hipLaunchKernelGGL((rank_select_reg_kernel<256, 20, true>), dim3(U), dim3(256), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)opt.shared, rr);
+    else if (n_max <= 1024 * 33)
+      hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33, true>), dim3(U), dim3(1024), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)opt.shared, rr);
     else
       hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
                          1, score, src, sel);
   } else {
   if (U <= 4096)    // few wavefronts per SIMD: registers to spare for deeper batches
     hipLaunchKernelGGL((rank_small_kernel<false, 32>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended,
-                       alpha, (const double *)nullptr, src, sel, U, 0);
+                       alpha, (const double *)nullptr, src, sel, U, 0, rr);
   else
     hipLaunchKernelGGL((rank_small_kernel<false, 8>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended,
-                       alpha, (const double *)nullptr, src, sel, U, 0);
+                       alpha, (const double *)nullptr, src, sel, U, 0, rr);
   // With thousands of short units one wavefront per unit is faster (its workgroup barriers cost
   // nothing); with few units the chip is filled by giving each unit four wavefronts.
   if (n_max <= 64 * 33 && U >= 2048)
     hipLaunchKernelGGL((rank_select_reg_kernel<64, 33>), dim3(U), dim3(64), 0, stream, cv, appended,
-                       alpha, src, sel);
+                       alpha, src, sel, (const double *)nullptr, rr);
   else if (n_max <= 256 * 20)
     hipLaunchKernelGGL((rank_select_reg_kernel<256, 20>), dim3(U), dim3(256), 0, stream, cv, appended,
-                       alpha, src, sel);
+                       alpha, src, sel, (const double *)nullptr, rr);
   else if (n_max <= 1024 * 33)
     hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33>), dim3(U), dim3(1024), 0, stream, cv, appended,
-                       alpha, src, sel);
+                       alpha, src, sel, (const double *)nullptr, rr);
   else
     hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
                        1, score, src, sel);
