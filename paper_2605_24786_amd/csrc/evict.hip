@@ -426,9 +426,26 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
       if (i == 0 || pos[row_of(i - 1)] / pg != pid) {
         double tot = 0.0;
         int m = i;
-        while (m < n && pos[row_of(m)] / pg == pid) {
-          if (m < ncand) tot = __dadd_rn(tot, score[m]);
-          ++m;
+        // the page's slots in slot order, eight requested at a time (positions rise with the
+        // slots, so the page ends at the first position at or past its upper bound)
+        const int pend = (pid + 1) * pg;
+        for (bool open = true; open;) {
+          int pp[8];
+          double sc8[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            pp[k] = pos[row_of(min(m + k, n - 1))];
+            sc8[k] = score[min(m + k, ncand - 1)];
+          }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            if (open && m < n && pp[k] < pend) {
+              if (m < ncand) tot = __dadd_rn(tot, sc8[k]);
+              ++m;
+            } else {
+              open = false;
+            }
+          }
         }
         if (m <= ncand) {
           score[i] = __ddiv_rn(tot, (double)(m - i));
@@ -459,8 +476,10 @@ __global__ __launch_bounds__(kRsThreads) void rank_select_kernel(CacheView cv, L
     const unsigned long long prefix = s_prefix;
     for (int i = tid; i < ncand; i += kRsThreads) {
       const int wgt = pg > 1 ? src[i] : 1;
-      const unsigned long long key = (unsigned long long)__double_as_longlong(score[i]);
-      if (wgt > 0 && (key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255ull)], wgt);
+      if (wgt > 0) {                                  // (with pages only a page's first slot carries a score)
+        const unsigned long long key = (unsigned long long)__double_as_longlong(score[i]);
+        if ((key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 255ull)], wgt);
+      }
     }
     __syncthreads();
     const int cnt = tid < 256 ? hist[tid] : 0;
