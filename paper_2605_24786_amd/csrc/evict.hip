@@ -1343,7 +1343,7 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                          dim3(kEvThreads), 0, stream, cv, appended, opt.shared);
     hipLaunchKernelGGL((rank_small_kernel<false, 8>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, appended, alpha,
                        (const double *)nullptr, src, sel, U, 1, rr);
-    if (n_max <= 256 * 16)    // (a short unit does not fill 1024 threads, and most units return at once)
+    if (n_max <= 256 * 20)    // (a short unit does not fill 1024 threads, and most units return at once)
       hipLaunchKernelGGL(rank_select_kernel<256>, dim3(U), dim3(256), 0, stream, cv, appended, alpha, opt,
                          1, score, src, sel);
     else
