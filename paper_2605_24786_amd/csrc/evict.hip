@@ -1126,6 +1126,60 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
   const int jr = sel[4] + 1 - (fp16_only ? evicted : e8);   // right shift: survivors [0, jr) move
   const int h0_new = sel[6];
 
+  // A mixed cache that moves a few slots and no FP16 row -- a unit of a decode loop in its steady
+  // state -- is served by the unit's first workgroup alone, in one pass: the sources of all
+  // planes are looked up together, then all rows are requested together, so the unit costs two
+  // memory round trips however many planes it has; its other workgroups leave at once.
+  if (!fp16_only && evicted == e8) {
+    constexpr int LPR = D / 16, RPP = kEvThreads / LPR;
+    const int lo = right ? 0 : hole, hi_m = right ? jr : n_new, hi_8 = right ? jr : n8_new;
+    const int cnt_m = hi_m - lo, cnt_8 = max(0, hi_8 - lo);
+    if (cnt_m <= kEvThreads && cnt_8 <= RPP * 4) {
+      if (y != 0) return;
+      uint8_t *pk = (uint8_t *)(cv.k8 + (size_t)u * cap8 * D), *pv = (uint8_t *)(cv.v8 + (size_t)u * cap8 * D);
+      float *ema = cv.ema + (size_t)u * cap;
+      int32_t *pos = cv.pos + (size_t)u * cap;
+      unsigned short *ks = (unsigned short *)(cv.ks + (size_t)u * cap8), *vs = (unsigned short *)(cv.vs + (size_t)u * cap8);
+      const int c = tid % LPR, r0 = tid / LPR;
+      // (four passes written out with scalar variables: see move_rows)
+      const int k0 = r0, k1 = k0 + RPP, k2 = k1 + RPP, k3 = k2 + RPP;
+      const int j0 = right ? hi_8 - 1 - k0 : lo + k0, j1 = right ? hi_8 - 1 - k1 : lo + k1;
+      const int j2 = right ? hi_8 - 1 - k2 : lo + k2, j3 = right ? hi_8 - 1 - k3 : lo + k3;
+      const int jm = right ? hi_m - 1 - tid : lo + tid;
+      int f0 = 0, f1 = 0, f2 = 0, f3 = 0, fm = 0;
+      if (k0 < cnt_8) f0 = src[j0];
+      if (k1 < cnt_8) f1 = src[j1];
+      if (k2 < cnt_8) f2 = src[j2];
+      if (k3 < cnt_8) f3 = src[j3];
+      if (tid < cnt_m) fm = ring_row(h0, src[jm], cap);
+      int4 b0, b1, b2, b3, c0, c1, c2, c3;
+      float fa = 0.f;
+      int32_t fp = 0;
+      unsigned short fk = 0, fv = 0;
+      if (k0 < cnt_8) { b0 = *(const int4 *)(pk + (size_t)ring_row(h0, f0, cap8) * D + c * 16); c0 = *(const int4 *)(pv + (size_t)ring_row(h0, f0, cap8) * D + c * 16); }
+      if (k1 < cnt_8) { b1 = *(const int4 *)(pk + (size_t)ring_row(h0, f1, cap8) * D + c * 16); c1 = *(const int4 *)(pv + (size_t)ring_row(h0, f1, cap8) * D + c * 16); }
+      if (k2 < cnt_8) { b2 = *(const int4 *)(pk + (size_t)ring_row(h0, f2, cap8) * D + c * 16); c2 = *(const int4 *)(pv + (size_t)ring_row(h0, f2, cap8) * D + c * 16); }
+      if (k3 < cnt_8) { b3 = *(const int4 *)(pk + (size_t)ring_row(h0, f3, cap8) * D + c * 16); c3 = *(const int4 *)(pv + (size_t)ring_row(h0, f3, cap8) * D + c * 16); }
+      if (tid < cnt_m) {
+        fa = ema[fm];
+        fp = pos[fm];
+        if (!cv.chan && jm < n8_new) { fk = ks[fm]; fv = vs[fm]; }
+      }
+      __syncthreads();
+      if (k0 < cnt_8) { *(int4 *)(pk + (size_t)ring_row(h0_new, j0, cap8) * D + c * 16) = b0; *(int4 *)(pv + (size_t)ring_row(h0_new, j0, cap8) * D + c * 16) = c0; }
+      if (k1 < cnt_8) { *(int4 *)(pk + (size_t)ring_row(h0_new, j1, cap8) * D + c * 16) = b1; *(int4 *)(pv + (size_t)ring_row(h0_new, j1, cap8) * D + c * 16) = c1; }
+      if (k2 < cnt_8) { *(int4 *)(pk + (size_t)ring_row(h0_new, j2, cap8) * D + c * 16) = b2; *(int4 *)(pv + (size_t)ring_row(h0_new, j2, cap8) * D + c * 16) = c2; }
+      if (k3 < cnt_8) { *(int4 *)(pk + (size_t)ring_row(h0_new, j3, cap8) * D + c * 16) = b3; *(int4 *)(pv + (size_t)ring_row(h0_new, j3, cap8) * D + c * 16) = c3; }
+      if (tid < cnt_m) {
+        const int d = ring_row(h0_new, jm, cap);
+        ema[d] = fa;
+        pos[d] = fp;
+        if (!cv.chan && jm < n8_new) { ks[d] = fk; vs[d] = fv; }
+      }
+      return;
+    }
+  }
+
   // FP16 ring rows.  Mixed cache: they only move (left) when an FP16 slot was evicted.
   // FP16-only cache: either side.
   auto move_fp16_rows = [&](bool k, bool v) {
