@@ -1644,8 +1644,8 @@ bool attend_plan(int D, int G, bool chan, bool chunk, int units_per_layer, int n
   const bool mfma = chunk || wants_mfma(D, G, n16_ub < n_ub);
   AttendFn fn = mfma ? attend_fn_mfma(D, G, chan) : attend_fn_valu(D, G);
   const long long nv = (long long)n_ub + n16_ub;
-  // One workgroup per CU measured best: the exchange between the splits of a unit (arrival
-  // counter, partial gather) gets slower with more participants, and a grid that is not a
+  // One workgroup per CU measured best: the exchange between the splits of a unit (statistics
+  // and partial gather) gets slower with more participants, and a grid that is not a
   // whole number of waves over the CUs leaves a straggler round.  Two per CU only when a
   // single split per unit would leave half of the chip idle.
   int want = lim.cus / units_per_layer;
