@@ -170,6 +170,7 @@ struct conf_kv_handle {
   // from one decode step to the next, so a recorded step can be replayed.
   uint32_t attend_launches = 0;
   uint32_t conf_launches = 0;
+  bool prompt_loaded = false;        // conf_kv_load_prefill / conf_kv_import since the last commit
   bool static_plan = false;          // conf_kv_static_plan: launch shapes from the budgets, not the lengths so far
   int forced_splits = 0;            // CONF_KV_SPLITS at create (tests, sweeps)
   bool force_two_launch = false;    // CONF_KV_TWO_LAUNCH at create (tests)
@@ -330,6 +331,7 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   CK_HIP(h, launch_load_prefill(h->cv, layer, (const __half *)dev_k16, (const __half *)dev_v16, T0,
                                 dev_ema0, (hipStream_t)stream));
   h->len_ub[layer] = T0;
+  h->prompt_loaded = true;
   h->appended[layer] = 0;
   const size_t UPL = (size_t)h->cfg.batch * h->cfg.n_kv_heads;
   std::fill(h->scaled.begin() + layer * UPL, h->scaled.begin() + (layer + 1) * UPL, (uint8_t)1);
@@ -524,8 +526,9 @@ int conf_kv_evict_compact(conf_kv_handle *h, conf_kv_stream stream) {
   CK_HIP(h, launch_evict_compact(h->cv, m, (double)h->cfg.alpha, opt, (double *)(h->scratch + h->kl.score),
                                  (int32_t *)(h->scratch + h->kl.src),
                                  (int32_t *)(h->scratch + h->kl.sel), n_max, h->attend_launches, h->conf_launches,
-                                 (hipStream_t)stream));
+                                 h->prompt_loaded, (hipStream_t)stream));
   h->attend_launches = h->conf_launches = 0;
+  h->prompt_loaded = false;
   const int P = h->cfg.protected_window;
   for (int l = 0; l < h->cfg.n_layers; ++l) {
     h->len_ub[l] += h->appended[l];
@@ -752,6 +755,7 @@ int conf_kv_import(conf_kv_handle *h, int32_t layer, int32_t b, int32_t kv_head,
   CK_HIP(h, hipMemcpy(cv.head16 + u, &zero, 4, hipMemcpyHostToDevice));
   CK_HIP(h, hipMemcpy(cv.head8 + u, &zero, 4, hipMemcpyHostToDevice));
   h->len_ub[layer] = std::max(h->len_ub[layer], n);
+  h->prompt_loaded = true;
   h->fresh_len[layer] = -1;
   if (n > 0) {                       // later tokens get positions behind the imported ones
     unsigned next = 0;

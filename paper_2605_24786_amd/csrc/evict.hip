@@ -610,7 +610,8 @@ __device__ __forceinline__ int lanes_below(unsigned long long m) {   // set bits
 }
 
 // kShared: the importance is the layer-shared float64 sum in shared_all (see rank_small_kernel).
-template <int T, int E, bool kShared = false>
+// kRandom: the random ranker's key per slot instead of the composite score (rr says how it is drawn).
+template <int T, int E, bool kShared = false, bool kRandom = false>
 __global__ __launch_bounds__(T) __attribute__((amdgpu_waves_per_eu(T == 256 && !kShared ? 4 : 1, T == 256 && !kShared ? 4 : 8)))
 void rank_select_reg_kernel(CacheView cv, LayerMask appended,
                                                             double alpha,
@@ -704,7 +705,7 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
       const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)av[k], a_lo), a_div);
       const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)pv[k], p_lo), p_div);
       key[k] = (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
-      if (rr.on) key[k] = random_key(rr, random_unit_key(cv, rr, u), pv[k]);
+      if constexpr (kRandom) key[k] = random_key(rr, random_unit_key(cv, rr, u), pv[k]);
       kmin = key[k] < kmin ? key[k] : kmin;
       kmax = key[k] > kmax ? key[k] : kmax;
     }
@@ -895,7 +896,7 @@ constexpr int kSmallE = 4;
 // shared_mass_kernel left in shared_all (indexed by slot, not by ring row).
 // kBatch: loads a lane has in flight at a time (8 keeps the registers few enough for thousands of
 // units per launch; 32 covers a 2048-slot unit in one round trip per pass when there are few units).
-template <bool kShared, int kBatch = 8>
+template <bool kShared, int kBatch = 8, bool kRandom = false>
 __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, LayerMask appended,
                                                                 double alpha,
                                                                 const double *__restrict__ shared_all,
@@ -984,8 +985,8 @@ __global__ __launch_bounds__(kEvThreads) void rank_small_kernel(CacheView cv, La
           const double ah = (a_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)a[r], a_lo), a_div);
           const double rh = (p_rng == 0.0) ? 0.0 : quotient(__dsub_rn((double)ps[r], p_lo), p_div);
           const unsigned long long key =
-              rr.on ? random_key(rr, random_unit_key(cv, rr, u), ps[r])
-                    : (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
+              kRandom ? random_key(rr, random_unit_key(cv, rr, u), ps[r])
+                      : (unsigned long long)__double_as_longlong(__dadd_rn(__dmul_rn(alpha, ah), __dmul_rn(oma, rh)));
           const bool above = key > prev_key || (key == prev_key && i > prev_idx);
           if (i < ncand && above && key < best_key) {  // slots rise within a lane: first one wins a tie
             best_key = key;
@@ -1101,7 +1102,10 @@ __device__ __forceinline__ void clear_tagged_if_asked(const CacheView &cv) {
   for (size_t i = wg * blockDim.x + threadIdx.x; i < cv.n_tagged; i += nwg * blockDim.x) cv.tagged[i] = 0ull;
 }
 
-template <int D>
+// kSmall: with the one-pass path for units that move a few slots (below).  The host picks the
+// instance without it for the step that follows a prompt load, where every unit moves hundreds of
+// rows and the extra path only costs the chunked walk registers and schedule.
+template <int D, bool kSmall>
 __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
                                                              const int32_t *__restrict__ src_all,
                                                              const int32_t *__restrict__ sel_all, int paired) {
@@ -1130,7 +1134,7 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
   // state -- is served by the unit's first workgroup alone, in one pass: the sources of all
   // planes are looked up together, then all rows are requested together, so the unit costs two
   // memory round trips however many planes it has; its other workgroups leave at once.
-  if (!fp16_only && evicted == e8) {
+  if (kSmall && !fp16_only && evicted == e8) {
     constexpr int LPR = D / 16, RPP = kEvThreads / LPR;
     const int lo = right ? 0 : hole, hi_m = right ? jr : n_new, hi_8 = right ? jr : n8_new;
     const int cnt_m = hi_m - lo, cnt_8 = max(0, hi_8 - lo);
@@ -1379,7 +1383,7 @@ hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16
 
 hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, double alpha,
                                 const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
-                                int n_max, unsigned attend_launches, unsigned conf_launches,
+                                int n_max, unsigned attend_launches, unsigned conf_launches, int after_prompt,
                                 hipStream_t stream) {
   const int U = cv.L * cv.B * cv.Hkv;
   // The random ranker runs on the same kernels as the composite one (a different key per slot);
@@ -1415,6 +1419,26 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
     else if (n_max <= 1024 * 33)
       hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33, true>), dim3(U), dim3(1024), 0, stream, cv, appended,
                          alpha, src, sel, (const double *)opt.shared, rr);
+    else
+      hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
+                         1, score, src, sel);
+  } else if (opt.random) {
+    // the random ranker: the same kernel shapes with the drawn key in place of the composite score
+    if (U <= 4096)
+      hipLaunchKernelGGL((rank_small_kernel<false, 32, true>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv,
+                         appended, alpha, (const double *)nullptr, src, sel, U, 0, rr);
+    else
+      hipLaunchKernelGGL((rank_small_kernel<false, 8, true>), dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv,
+                         appended, alpha, (const double *)nullptr, src, sel, U, 0, rr);
+    if (n_max <= 64 * 33 && U >= 2048)
+      hipLaunchKernelGGL((rank_select_reg_kernel<64, 33, false, true>), dim3(U), dim3(64), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)nullptr, rr);
+    else if (n_max <= 256 * 20)
+      hipLaunchKernelGGL((rank_select_reg_kernel<256, 20, false, true>), dim3(U), dim3(256), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)nullptr, rr);
+    else if (n_max <= 1024 * 33)
+      hipLaunchKernelGGL((rank_select_reg_kernel<1024, 33, false, true>), dim3(U), dim3(1024), 0, stream, cv, appended,
+                         alpha, src, sel, (const double *)nullptr, rr);
     else
       hipLaunchKernelGGL(rank_select_kernel<1024>, dim3(U), dim3(1024), 0, stream, cv, appended, alpha, opt,
                          1, score, src, sel);
@@ -1458,14 +1482,21 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                          attend_launches, conf_launches);
     return hipGetLastError();
   }
+  const dim3 cgrid(U, paired ? 2 : 5);
   if (cv.D == 64) {
-    hipLaunchKernelGGL(compact_kernel<64>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
+    if (after_prompt)
+      hipLaunchKernelGGL((compact_kernel<64, false>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
+    else
+      hipLaunchKernelGGL((compact_kernel<64, true>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
-                         attend_launches, conf_launches);
+                       attend_launches, conf_launches);
   } else {
-    hipLaunchKernelGGL(compact_kernel<128>, dim3(U, paired ? 2 : 5), dim3(kEvThreads), 0, stream, cv, src, sel, paired);
+    if (after_prompt)
+      hipLaunchKernelGGL((compact_kernel<128, false>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
+    else
+      hipLaunchKernelGGL((compact_kernel<128, true>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
-                         attend_launches, conf_launches);
+                       attend_launches, conf_launches);
   }
   return hipGetLastError();
 }

@@ -106,6 +106,7 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
                                 const RankOptions &opt, double *score, int32_t *src, int32_t *sel,
                                 int n_max /* longest unit */,
                                 unsigned attend_launches, unsigned conf_launches /* since the last commit */,
+                                int after_prompt /* a layer's prompt was loaded since the last commit: long moves */,
                                 hipStream_t stream);
 
 }  // namespace confkv
