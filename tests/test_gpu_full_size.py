@@ -100,6 +100,29 @@ def test_full_size_many_row_chunks(lib):
     ls.close()
 
 
+def test_full_size_replayed_steps(lib):
+    """A recorded decode step replayed at the roofline workload's shape (4 of its layers, four
+    splits per unit, the launch configuration the benchmark times): the first step runs outside
+    the graph (4097 -> 2048 or 1024 slots per unit), the following ones are replays whose
+    caches shrink and grow with the budget choices; outputs, kept sets and state of the
+    followed units against the oracle, invariants on all units."""
+    wl = workload(1).scaled(name="llama3_8b_b8_t4096_replay", n_layers=4, n_tight=(1024,) * 4, n_loose=(2048,) * 4,
+                            steps=10, logit_std=(0.5, 6.0), logit_run=2)
+    print(f"replayed steps at full size: {wl.units} units of {wl.prefill} slots", flush=True)
+    ls = Lockstep(lib, wl, seed=2, units=6, threads=16)
+    ls.kv.static_plan(True)
+    ls.step()
+    ls.record_step()
+    for t in range(1, wl.steps):
+        ls.step(check_state=(t % 3 == 0 or t == wl.steps - 1))
+        _invariants_all_units(ls, wl, t)
+        print(f"  replay {t}: len={ls.report.lengths[-1]} out_err={ls.report.max_out_err:.3f}xtol", flush=True)
+    rep = ls.report
+    assert ls.replays == wl.steps - 1 and rep.ok(), (rep.evict_flips, rep.budget_flips)
+    assert ls.kv.counters().device_errors == 0 and rep.evictions > 0 and 0 < rep.tight_steps < rep.steps * wl.batch
+    ls.close()
+
+
 def test_full_size_grouped_heads_of_64_channels(lib):
     """Eight query heads of 64 channels per kv-head (the shape of the 20B mixture-of-experts model
     the paper evaluates) at the roofline workload's batch and length, 4 layers: the matrix-core
