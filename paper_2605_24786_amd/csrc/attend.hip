@@ -1312,8 +1312,9 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
       }
       wave_lds_sync();
       const half4_t pa = *(const half4_t *)(Pb + t16 * kPRow + 4 * g4);
+      // (a 64-channel head has four real channel groups: the copies in groups 4..7 are not multiplied)
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) {
+      for (int nt = 0; nt < DR / 16; ++nt) {
         const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + kVSkew(nt) + 8 * g4);
         const uint2 v2 = make_uint2(vb[0], vb[1]);
         O[nt] = __builtin_amdgcn_mfma_f32_16x16x16f16(pa, __builtin_bit_cast(half4_t, v2), O[nt], 0, 0, 0);
@@ -1435,7 +1436,7 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
     // ---- output: O[head][channel] += P[head][slot] V[slot][channel] ----
     const half8_t pa = *(const half8_t *)(Pb + t16 * kPRow + 8 * g4);
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) {
+    for (int nt = 0; nt < DR / 16; ++nt) {
       const unsigned *vb = (const unsigned *)(Vt + (16 * nt + t16) * kVRow + kVSkew(nt) + 8 * g4);   // 4-byte aligned
       O[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, cvt_i8x8_f16x8_biased(vb[0], vb[1]), O[nt], 0, 0, 0);
     }
