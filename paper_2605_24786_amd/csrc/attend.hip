@@ -1039,6 +1039,7 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
   // head runs on the same tiles with channels 64..127 holding a second copy of its rows against
   // zero query channels (their products are 0, their outputs are dropped).
   constexpr int D = 128;
+  constexpr int kSteps = DR / 32;               // k-steps of 32 channels in the score contraction
   static_assert(DR == 64 || DR == 128, "head dimension");
   static_assert(!(kChan && DR != 128), "per-channel scales need 128 channels");
   static_assert(G * D * 4 <= kTileBytes, "a wavefront's output partial must fit its tile buffer");
@@ -1154,7 +1155,8 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       int4 raw = make_int4(0, 0, 0, 0);
-      if (t16 < G && q_tok < tq && g4 * 32 + 8 * s < DR) raw = *(const int4 *)(qrow + g4 * 32 + 8 * s);
+      // (a 64-channel head: two k-steps, step s of lane group g4 covers channels 16 g4 + 8 s + [0, 8))
+      if (t16 < G && q_tok < tq && s < kSteps) raw = *(const int4 *)(qrow + g4 * (8 * kSteps) + 8 * s);
       qa[s] = __builtin_bit_cast(half8_t, raw);
     }
   }
@@ -1279,10 +1281,10 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
       }
       wave_lds_sync();
       if (item + kAttWaves < nitems) tr = load_item(item + kAttWaves);
-      const uint8_t *krow = Kt + t16 * kKRow16 + g4 * 64;
+      const uint8_t *krow = Kt + t16 * kKRow16 + g4 * (16 * kSteps);
       floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
+      for (int s = 0; s < kSteps; ++s)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[s], *(const half8_t *)(krow + 16 * s), acc, 0, 0, 0);
       const bool valid = base + t16 < sl.hi16;
       float z[NV], corr[NV];
@@ -1358,10 +1360,15 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
     float sc[2][NV];
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
-      const uint8_t *krow = Kt + (16 * sb + t16) * kKRow + g4 * 32;
-      const int4 b0 = *(const int4 *)(krow), b1 = *(const int4 *)(krow + 16);
+      const uint8_t *krow = Kt + (16 * sb + t16) * kKRow + g4 * (8 * kSteps);
+      const int4 b0 = *(const int4 *)(krow);
+      int4 b1 = b0;
+      if constexpr (kSteps == 4) b1 = *(const int4 *)(krow + 16);
       floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
-      if constexpr (kChan) {
+      if constexpr (kSteps == 2) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[0], cvt_i8x8_f16x8(b0.x, b0.y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[1], cvt_i8x8_f16x8(b0.z, b0.w), acc, 0, 0, 0);
+      } else if constexpr (kChan) {
         const half8_t kb[4] = {cvt_i8x8_f16x8(b0.x, b0.y), cvt_i8x8_f16x8(b0.z, b0.w),
                                cvt_i8x8_f16x8(b1.x, b1.y), cvt_i8x8_f16x8(b1.z, b1.w)};
 #pragma unroll
