@@ -1038,7 +1038,7 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
   // D: channels of the tiles and partials on chip.  DR: the head dimension in memory; a 64-channel
   // head runs on the same tiles with channels 64..127 holding a second copy of its rows, which the
   // contractions leave out (two k-steps over the real channels for the scores, four channel
-  // groups for the output; the partial's other channels stay zero and are never written out).
+  // groups for the output; the other channels of the partial are never written out).
   constexpr int D = 128;
   constexpr int kSteps = DR / 32;               // k-steps of 32 channels in the score contraction
   static_assert(DR == 64 || DR == 128, "head dimension");
