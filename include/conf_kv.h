@@ -213,7 +213,8 @@ int conf_kv_pyramid_budgets(int32_t n0, int32_t n_layers, double beta, int32_t n
 int conf_kv_destroy(conf_kv_handle *h);
 
 /* Replaces the cache of one layer by T0 prompt tokens at positions 0..T0-1
- * (Algorithm 1's input cache).  dev_k16 / dev_v16: fp16 [B][Hkv][T0][D].
+ * (Algorithm 1's input cache).  dev_k16 / dev_v16: fp16 [B][Hkv][T0][D], 16-byte aligned
+ * (CONF_KV_ERR_INVALID_ARG otherwise).
  * dev_ema0: fp32 [B][Hkv][T0] initial EMA importance, or NULL for zeros.
  * All but the newest W tokens are quantised to INT8 ("Tiled attention and mixed
  * precision": symmetric, scale = max|x|/127, per token and kv-head, or per kv-head and

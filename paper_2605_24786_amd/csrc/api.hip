@@ -326,6 +326,7 @@ int conf_kv_load_prefill(conf_kv_handle *h, int32_t layer, const void *dev_k16, 
   if (layer < 0 || layer >= h->cfg.n_layers) return CONF_KV_ERR_BAD_LAYER;
   if (T0 < 0) return CONF_KV_ERR_INVALID_ARG;
   if (T0 > 0 && (!dev_k16 || !dev_v16)) return CONF_KV_ERR_INVALID_ARG;
+  if (((uintptr_t)dev_k16 | (uintptr_t)dev_v16) & 15) return CONF_KV_ERR_INVALID_ARG;   // rows are read in 16-byte pieces
   if (T0 > h->cfg.capacity - 1) return CONF_KV_ERR_CAPACITY;
   if (h->cv.page_lg && T0 - h->cfg.fp16_window > (h->cv.npages << h->cv.page_lg)) return CONF_KV_ERR_CAPACITY;
   CK_HIP(h, launch_load_prefill(h->cv, layer, (const __half *)dev_k16, (const __half *)dev_v16, T0,

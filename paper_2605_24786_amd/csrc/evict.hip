@@ -121,16 +121,75 @@ __global__ __launch_bounds__(1024) void channel_scales_kernel(CacheView cv, int 
 }
 
 // ---------------------------------------------------------------------------------------
-// Prompt loader: grid (ceil(T0 / 4), B * Hkv), one wavefront per token.
+// Prompt loader: grid (ceil(T0 / RW), B * Hkv), 256 threads.  D / 8 lanes own one token row in
+// 16-byte pieces (eight fp16 values each), so a workgroup takes RW = 2048 / D tokens and every
+// load and store instruction covers whole rows.  Same arithmetic per element as
+// quantize_row_wave (the maximum does not depend on the order it is taken in), so the stored
+// bits are those of the one-row-per-wavefront quantiser the demotion kernel uses.
 // ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void unpack_h8(const int4 &raw, float (&x)[8]) {
+  const unsigned w[4] = {(unsigned)raw.x, (unsigned)raw.y, (unsigned)raw.z, (unsigned)raw.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    x[2 * e] = __half2float(__ushort_as_half((unsigned short)(w[e] & 0xffffu)));
+    x[2 * e + 1] = __half2float(__ushort_as_half((unsigned short)(w[e] >> 16)));
+  }
+}
+__device__ __forceinline__ uint2 pack_codes8(const int (&code)[8]) {
+  uint2 r;
+  r.x = (unsigned)(code[0] & 0xff) | ((unsigned)(code[1] & 0xff) << 8) | ((unsigned)(code[2] & 0xff) << 16) |
+        ((unsigned)(code[3] & 0xff) << 24);
+  r.y = (unsigned)(code[4] & 0xff) | ((unsigned)(code[5] & 0xff) << 8) | ((unsigned)(code[6] & 0xff) << 16) |
+        ((unsigned)(code[7] & 0xff) << 24);
+  return r;
+}
+// Eight values of a row per lane, LPR lanes per row: per-token scale of the row and the codes.
+template <int LPR>
+__device__ __forceinline__ uint2 quantize_piece(const int4 &raw, __half *scale_out) {
+  float x[8];
+  unpack_h8(raw, x);
+  float amax = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+#pragma unroll
+  for (int m = LPR / 2; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, kWave));
+  const __half hs = __float2half_rn(__fdiv_rn(amax, 127.0f));
+  const float sf = __half2float(hs);
+  const bool dead = !(sf > 0.f) || isinf(sf);
+  int code[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float r = dead ? 0.f : rintf(__fdiv_rn(x[e], sf));
+    r = fminf(fmaxf(r, -127.f), 127.f);
+    code[e] = (int)r;
+  }
+  *scale_out = dead ? __float2half_rn(0.f) : hs;
+  return pack_codes8(code);
+}
+// The same piece against fixed per-channel scales (eight fp16 scales of the lane's channels).
+__device__ __forceinline__ uint2 quantize_piece_channels(const int4 &raw, const int4 &scales) {
+  float x[8], sf[8];
+  unpack_h8(raw, x);
+  unpack_h8(scales, sf);
+  int code[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float r = (sf[e] > 0.f) ? rintf(__fdiv_rn(x[e], sf[e])) : 0.f;
+    r = fminf(fmaxf(r, -127.f), 127.f);
+    code[e] = (int)r;
+  }
+  return pack_codes8(code);
+}
+
 template <int D>
 __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
     CacheView cv, int layer, const __half *__restrict__ k16, const __half *__restrict__ v16, int T0,
     const float *__restrict__ ema0) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  constexpr int LPR = D / 8, RW = kEvThreads / LPR;
+  const int c = threadIdx.x % LPR;
   const int ul = blockIdx.y;
   const int u = layer * cv.B * cv.Hkv + ul;
-  const int t = blockIdx.x * 4 + w;
+  const int t = blockIdx.x * RW + threadIdx.x / LPR;
   const int n8 = (cv.W < 0) ? 0 : max(0, T0 - cv.W);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     cv.len[u] = T0;
@@ -141,35 +200,33 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
   }
   if (cv.page_lg && blockIdx.x == 0)                // paged layout: the block table starts over as the identity
     for (int i = threadIdx.x; i < cv.npages; i += kEvThreads) cv.pt[(size_t)u * cv.npages + i] = i;
-  if (t >= T0) return;
-  const __half *ksrc = k16 + ((size_t)ul * T0 + t) * D;
-  const __half *vsrc = v16 + ((size_t)ul * T0 + t) * D;
-  if (lane == 0) {
+  if (t >= T0) return;                              // (the LPR lanes of a row leave together)
+  const int4 kraw = *(const int4 *)(k16 + ((size_t)ul * T0 + t) * D + c * 8);
+  const int4 vraw = *(const int4 *)(v16 + ((size_t)ul * T0 + t) * D + c * 8);
+  if (c == 0) {
     // (identity table, ring heads 0: INT8 slot t sits in row t, FP16 slot t in metadata row t - n8)
     const int mrow = (cv.page_lg && t >= n8) ? cv.cap - cv.cap16 + (t - n8) : t;
     cv.pos[(size_t)u * cv.cap + mrow] = t;
     cv.ema[(size_t)u * cv.cap + mrow] = ema0 ? ema0[(size_t)ul * T0 + t] : 0.f;
   }
   if (t < n8) {
-    if constexpr (D == 128) {
-      if (cv.chan) {                              // scales were fixed by channel_scales_kernel
-        quantize_row_channels<D>(ksrc, cv.k8 + ((size_t)u * cv.cap8 + t) * D, cv.ks + (size_t)u * D, lane);
-        quantize_row_channels<D>(vsrc, cv.v8 + ((size_t)u * cv.cap8 + t) * D, cv.vs + (size_t)u * D, lane);
-        return;
-      }
+    const size_t row = (size_t)u * cv.cap8 + t;
+    uint2 kc, vc;
+    if (D == 128 && cv.chan) {                      // scales were fixed by channel_scales_kernel
+      kc = quantize_piece_channels(kraw, *(const int4 *)(cv.ks + (size_t)u * D + c * 8));
+      vc = quantize_piece_channels(vraw, *(const int4 *)(cv.vs + (size_t)u * D + c * 8));
+    } else {
+      __half ksc, vsc;
+      kc = quantize_piece<LPR>(kraw, &ksc);
+      vc = quantize_piece<LPR>(vraw, &vsc);
+      if (c == 0) { cv.ks[row] = ksc; cv.vs[row] = vsc; }
     }
-    quantize_row_wave<D>(ksrc, cv.k8 + ((size_t)u * cv.cap8 + t) * D, cv.ks + (size_t)u * cv.cap8 + t, lane);
-    quantize_row_wave<D>(vsrc, cv.v8 + ((size_t)u * cv.cap8 + t) * D, cv.vs + (size_t)u * cv.cap8 + t, lane);
+    *(uint2 *)(cv.k8 + row * D + c * 8) = kc;
+    *(uint2 *)(cv.v8 + row * D + c * 8) = vc;
   } else {
-    constexpr int EPL = D / kWave;
-    const int row = t - n8;                       // both ring heads are 0 after a load
-    __half *kd = cv.k16 + ((size_t)u * cv.cap16 + row) * D;
-    __half *vd = cv.v16 + ((size_t)u * cv.cap16 + row) * D;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      kd[lane * EPL + e] = ksrc[lane * EPL + e];
-      vd[lane * EPL + e] = vsrc[lane * EPL + e];
-    }
+    const size_t row = (size_t)u * cv.cap16 + (t - n8);   // both ring heads are 0 after a load
+    *(int4 *)(cv.k16 + row * D + c * 8) = kraw;
+    *(int4 *)(cv.v16 + row * D + c * 8) = vraw;
   }
 }
 
@@ -1371,7 +1428,8 @@ __global__ __launch_bounds__(kEvThreads) void demote_kernel(CacheView cv,
 
 hipError_t launch_load_prefill(const CacheView &cv, int layer, const __half *k16, const __half *v16,
                                int T0, const float *ema0, hipStream_t stream) {
-  dim3 grid((T0 + 3) / 4 > 0 ? (T0 + 3) / 4 : 1, cv.B * cv.Hkv);
+  const int rw = kEvThreads / (cv.D / 8);            // tokens per workgroup of the loader
+  dim3 grid(T0 > 0 ? (T0 + rw - 1) / rw : 1, cv.B * cv.Hkv);
   if (cv.chan)      // D = 128 by construction of the handle
     hipLaunchKernelGGL(channel_scales_kernel, dim3(cv.B * cv.Hkv, 2), dim3(1024), 0, stream, cv, layer, k16, v16, T0);
   if (cv.D == 64)
