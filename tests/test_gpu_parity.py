@@ -1234,6 +1234,11 @@ def test_call_order_and_capacity_errors(lib, torch_cuda):
     with pytest.raises(lib.ConfKVError) as e:
         kv.load_prefill(0, torch.zeros((1, 1, 64, 128), dtype=torch.float16, device="cuda"), kn)
     assert e.value.status == -4
+    flat = torch.zeros(8 * 128 + 8, dtype=torch.float16, device="cuda")
+    ok_k, off_k = flat[:8 * 128].view(1, 1, 8, 128), flat[1:8 * 128 + 1].view(1, 1, 8, 128)
+    with pytest.raises(lib.ConfKVError) as e:
+        kv.load_prefill(0, off_k, ok_k)                 # prompt rows are read in 16-byte pieces
+    assert e.value.status == -1
     kv.attend(0, z, kn, kn, z)
     with pytest.raises(lib.ConfKVError) as e:
         kv.attend(0, z, kn, kn, z)                      # second append before the commit
