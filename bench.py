@@ -7,8 +7,9 @@ D = 128, V = 128256, batch 8, 4096-token cache per unit with the newest 128 toke
 and the rest INT8; budgets 1024/2048; protected window 128; logits N(0, 3)).
 
 The step shrinks every cache (4097 -> 2048 or 1024 slots), so the cache is re-loaded from
-the resident FP16 prompt tensors between timed steps; the re-load is outside the timed
-region.  Each step is bracketed by HIP events on the launch stream with a device
+the resident FP16 prompt tensors between timed steps; the re-load (layer by layer, followed by
+a read of 512 MiB of unrelated memory that writes the re-load's dirty cache lines back) is
+outside the timed region.  Each step is bracketed by HIP events on the launch stream with a device
 synchronisation on both sides; `ms_per_step` is the mean event time of the K steps.
 
 Prints ONE JSON line.  `roofline` describes the attention + mass-EMA kernel (the dominant
@@ -382,9 +383,22 @@ def main():
     sel = torch.empty(wl.batch, dtype=torch.uint8, device="cuda")
     print(f"# setup {time.time() - t_setup:.1f}s: {wl.name}, state {kv.state.numel() / 2**30:.2f} GiB", file=sys.stderr, flush=True)
 
+    # Between timed steps (outside the timed region) the caches are loaded again, one layer at a
+    # time with a synchronisation after each, and then 512 MiB of unrelated memory are read once.
+    # The re-load writes gigabytes at several TB/s: issued back to back it leaves the power
+    # management throttling and some 290 MB of dirty lines in L2 and the Infinity Cache, which the
+    # first launches of the timed step then pay for (measured: 21.6 instead of 20.4 us per
+    # attention launch).  A decode step in a serving loop follows other work, not a bulk write of
+    # its own cache, so the timed step starts from clean caches and a settled clock.
+    scrub = torch.empty(1 << 27, dtype=torch.float32, device="cuda").normal_() if not args.steady else None
+    scrub_out = torch.zeros(4096, dtype=torch.int32, device="cuda")
+
     def reload():
         for l in range(L):
             kv.load_prefill(l, prompts[l][0], prompts[l][1])
+            torch.cuda.synchronize()
+        if scrub is not None:
+            pkg.probe_read(scrub, scrub_out, 4096)
 
     def one_step(ev=None):
         # returns per-phase events when ev is given: [start, after attends, after step, end]
@@ -446,7 +460,8 @@ def main():
                    "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "vocab": wl.vocab,
                    "cache_len": wl.prefill, "fp16_window": wl.fp16_window, "budgets": [wl.n_tight[0], wl.n_loose[0]],
                    "protected": wl.protected, "kv_storage": "int8+fp16", "int8_scales": "per " + args.scales, "tokens_per_call": tq, "evict_page": args.evict_page, "layout": args.layout, "rank_scope": args.rank_scope, "attend_splits": kv.attend_splits(0),
-                   "len_after": n_after, "tight_sequences": int(st.tight_steps > 0)},
+                   "len_after": n_after, "tight_sequences": int(st.tight_steps > 0),
+                   "between_steps": "cache re-loaded layer by layer, then 512 MiB of unrelated memory read (untimed)"},
         "roofline": {"bound": "hbm", "kernel": ("attend_wide_kernel" if tq * wl.group > 16 else "attend_mfma_kernel<16>" if tq > 1 else f"attend_mfma_kernel<{wl.group}>") if (tq > 1 or wl.group > 1) and wl.fp16_window >= 0 and wl.head_dim == 128 else "attend_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_file, "bytes_per_launch": att_bytes,

@@ -201,8 +201,13 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
   if (cv.page_lg && blockIdx.x == 0)                // paged layout: the block table starts over as the identity
     for (int i = threadIdx.x; i < cv.npages; i += kEvThreads) cv.pt[(size_t)u * cv.npages + i] = i;
   if (t >= T0) return;                              // (the LPR lanes of a row leave together)
-  const int4 kraw = *(const int4 *)(k16 + ((size_t)ul * T0 + t) * D + c * 8);
-  const int4 vraw = *(const int4 *)(v16 + ((size_t)ul * T0 + t) * D + c * 8);
+  // the prompt is read once and the cache rows are not read again before gigabytes of other
+  // traffic: streaming loads and stores, so the loader leaves the caches to the decode kernels
+  typedef int v4i_t __attribute__((ext_vector_type(4)));
+  typedef unsigned v2u_t __attribute__((ext_vector_type(2)));
+  const v4i_t kl = __builtin_nontemporal_load((const v4i_t *)(k16 + ((size_t)ul * T0 + t) * D + c * 8));
+  const v4i_t vl = __builtin_nontemporal_load((const v4i_t *)(v16 + ((size_t)ul * T0 + t) * D + c * 8));
+  const int4 kraw = make_int4(kl.x, kl.y, kl.z, kl.w), vraw = make_int4(vl.x, vl.y, vl.z, vl.w);
   if (c == 0) {
     // (identity table, ring heads 0: INT8 slot t sits in row t, FP16 slot t in metadata row t - n8)
     const int mrow = (cv.page_lg && t >= n8) ? cv.cap - cv.cap16 + (t - n8) : t;
@@ -221,12 +226,12 @@ __global__ __launch_bounds__(kEvThreads) void load_prefill_kernel(
       vc = quantize_piece<LPR>(vraw, &vsc);
       if (c == 0) { cv.ks[row] = ksc; cv.vs[row] = vsc; }
     }
-    *(uint2 *)(cv.k8 + row * D + c * 8) = kc;
-    *(uint2 *)(cv.v8 + row * D + c * 8) = vc;
+    __builtin_nontemporal_store(v2u_t{kc.x, kc.y}, (v2u_t *)(cv.k8 + row * D + c * 8));
+    __builtin_nontemporal_store(v2u_t{vc.x, vc.y}, (v2u_t *)(cv.v8 + row * D + c * 8));
   } else {
     const size_t row = (size_t)u * cv.cap16 + (t - n8);   // both ring heads are 0 after a load
-    *(int4 *)(cv.k16 + row * D + c * 8) = kraw;
-    *(int4 *)(cv.v16 + row * D + c * 8) = vraw;
+    __builtin_nontemporal_store(kl, (v4i_t *)(cv.k16 + row * D + c * 8));
+    __builtin_nontemporal_store(vl, (v4i_t *)(cv.v16 + row * D + c * 8));
   }
 }
 
