@@ -1110,21 +1110,21 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
     const unsigned o1 = row8(min(base + 8 + r8, last)) * DR + col;
     const unsigned o2 = row8(min(base + 16 + r8, last)) * DR + col;
     const unsigned o3 = row8(min(base + 24 + r8, last)) * DR + col;
-    t.k0 = *(const int4 *)(K8 + o0);
-    t.v0 = *(const int4 *)(V8 + o0);
-    t.k1 = *(const int4 *)(K8 + o1);
-    t.v1 = *(const int4 *)(V8 + o1);
-    t.k2 = *(const int4 *)(K8 + o2);
-    t.v2 = *(const int4 *)(V8 + o2);
-    t.k3 = *(const int4 *)(K8 + o3);
-    t.v3 = *(const int4 *)(V8 + o3);
+    t.k0 = ld_stream16(K8 + o0);
+    t.v0 = ld_stream16(V8 + o0);
+    t.k1 = ld_stream16(K8 + o1);
+    t.v1 = ld_stream16(V8 + o1);
+    t.k2 = ld_stream16(K8 + o2);
+    t.v2 = ld_stream16(V8 + o2);
+    t.k3 = ld_stream16(K8 + o3);
+    t.v3 = ld_stream16(V8 + o3);
     if constexpr (!kChan) {
       const unsigned j0 = row8(min(base + t16, last));
       const unsigned j1 = row8(min(base + 16 + t16, last));
-      t.ks0 = ((const unsigned short *)KS)[j0];
-      t.vs0 = ((const unsigned short *)VS)[j0];
-      t.ks1 = ((const unsigned short *)KS)[j1];
-      t.vs1 = ((const unsigned short *)VS)[j1];
+      t.ks0 = ld_stream((const unsigned short *)KS + j0);
+      t.vs0 = ld_stream((const unsigned short *)VS + j0);
+      t.ks1 = ld_stream((const unsigned short *)KS + j1);
+      t.vs1 = ld_stream((const unsigned short *)VS + j1);
     } else {
       t.ks0 = t.ks1 = t.vs0 = t.vs1 = 0;
     }
@@ -1227,14 +1227,14 @@ void attend_mfma_kernel(const int32_t *w_len, const int32_t *w_n8, const int32_t
     const __half *vn = a.vnew + ((size_t)sl.b * tq * cv.Hkv + sl.g) * DR + col;
     const int s0 = min(base + r4, last) - first_new, s1 = min(base + 4 + r4, last) - first_new;
     const int s2 = min(base + 8 + r4, last) - first_new, s3 = min(base + 12 + r4, last) - first_new;
-    t.k0 = *(const int4 *)(s0 >= 0 ? kn + s0 * tok : K16 + o0);
-    t.v0 = *(const int4 *)(s0 >= 0 ? vn + s0 * tok : V16 + o0);
-    t.k1 = *(const int4 *)(s1 >= 0 ? kn + s1 * tok : K16 + o1);
-    t.v1 = *(const int4 *)(s1 >= 0 ? vn + s1 * tok : V16 + o1);
-    t.k2 = *(const int4 *)(s2 >= 0 ? kn + s2 * tok : K16 + o2);
-    t.v2 = *(const int4 *)(s2 >= 0 ? vn + s2 * tok : V16 + o2);
-    t.k3 = *(const int4 *)(s3 >= 0 ? kn + s3 * tok : K16 + o3);
-    t.v3 = *(const int4 *)(s3 >= 0 ? vn + s3 * tok : V16 + o3);
+    t.k0 = ld_stream16(s0 >= 0 ? kn + s0 * tok : K16 + o0);
+    t.v0 = ld_stream16(s0 >= 0 ? vn + s0 * tok : V16 + o0);
+    t.k1 = ld_stream16(s1 >= 0 ? kn + s1 * tok : K16 + o1);
+    t.v1 = ld_stream16(s1 >= 0 ? vn + s1 * tok : V16 + o1);
+    t.k2 = ld_stream16(s2 >= 0 ? kn + s2 * tok : K16 + o2);
+    t.v2 = ld_stream16(s2 >= 0 ? vn + s2 * tok : V16 + o2);
+    t.k3 = ld_stream16(s3 >= 0 ? kn + s3 * tok : K16 + o3);
+    t.v3 = ld_stream16(s3 >= 0 ? vn + s3 * tok : V16 + o3);
     t.ks0 = t.ks1 = t.vs0 = t.vs1 = 0;
     return t;
   };
