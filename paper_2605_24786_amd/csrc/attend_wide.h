@@ -95,15 +95,15 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
       const unsigned o1 = (unsigned)ring_row_u(h8, min(base + 8 + r8, last), cap8) * D + col;
       const unsigned o2 = (unsigned)ring_row_u(h8, min(base + 16 + r8, last), cap8) * D + col;
       const unsigned o3 = (unsigned)ring_row_u(h8, min(base + 24 + r8, last), cap8) * D + col;
-      t.k0 = *(const int4 *)(K8 + o0);
-      t.k1 = *(const int4 *)(K8 + o1);
-      t.k2 = *(const int4 *)(K8 + o2);
-      t.k3 = *(const int4 *)(K8 + o3);
+      t.k0 = ld_stream16(K8 + o0);
+      t.k1 = ld_stream16(K8 + o1);
+      t.k2 = ld_stream16(K8 + o2);
+      t.k3 = ld_stream16(K8 + o3);
       if (with_v) {
-        t.v0 = *(const int4 *)(V8 + o0);
-        t.v1 = *(const int4 *)(V8 + o1);
-        t.v2 = *(const int4 *)(V8 + o2);
-        t.v3 = *(const int4 *)(V8 + o3);
+        t.v0 = ld_stream16(V8 + o0);
+        t.v1 = ld_stream16(V8 + o1);
+        t.v2 = ld_stream16(V8 + o2);
+        t.v3 = ld_stream16(V8 + o3);
       }
       const unsigned j0 = (unsigned)ring_row_u(h8, min(base + t16, last), cap8);
       const unsigned j1 = (unsigned)ring_row_u(h8, min(base + 16 + t16, last), cap8);
@@ -127,15 +127,15 @@ void attend_wide_kernel(const int32_t *, const int32_t *, const int32_t *, const
       const unsigned o0 = (unsigned)ring_row(h16, s0 - n8, cap16) * D + col, o1 = (unsigned)ring_row(h16, s1 - n8, cap16) * D + col;
       const unsigned o2 = (unsigned)ring_row(h16, s2 - n8, cap16) * D + col, o3 = (unsigned)ring_row(h16, s3 - n8, cap16) * D + col;
       const int n0 = s0 - first_new, n1 = s1 - first_new, n2 = s2 - first_new, n3 = s3 - first_new;
-      t.k0 = *(const int4 *)(n0 >= 0 ? kn + n0 * tok : K16 + o0);
-      t.k1 = *(const int4 *)(n1 >= 0 ? kn + n1 * tok : K16 + o1);
-      t.k2 = *(const int4 *)(n2 >= 0 ? kn + n2 * tok : K16 + o2);
-      t.k3 = *(const int4 *)(n3 >= 0 ? kn + n3 * tok : K16 + o3);
+      t.k0 = ld_stream16(n0 >= 0 ? kn + n0 * tok : K16 + o0);
+      t.k1 = ld_stream16(n1 >= 0 ? kn + n1 * tok : K16 + o1);
+      t.k2 = ld_stream16(n2 >= 0 ? kn + n2 * tok : K16 + o2);
+      t.k3 = ld_stream16(n3 >= 0 ? kn + n3 * tok : K16 + o3);
       if (with_v) {
-        t.v0 = *(const int4 *)(n0 >= 0 ? vn + n0 * tok : V16 + o0);
-        t.v1 = *(const int4 *)(n1 >= 0 ? vn + n1 * tok : V16 + o1);
-        t.v2 = *(const int4 *)(n2 >= 0 ? vn + n2 * tok : V16 + o2);
-        t.v3 = *(const int4 *)(n3 >= 0 ? vn + n3 * tok : V16 + o3);
+        t.v0 = ld_stream16(n0 >= 0 ? vn + n0 * tok : V16 + o0);
+        t.v1 = ld_stream16(n1 >= 0 ? vn + n1 * tok : V16 + o1);
+        t.v2 = ld_stream16(n2 >= 0 ? vn + n2 * tok : V16 + o2);
+        t.v3 = ld_stream16(n3 >= 0 ? vn + n3 * tok : V16 + o3);
       }
     }
     return t;
