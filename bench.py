@@ -478,6 +478,11 @@ def main():
     del kv, prompts
     torch.cuda.empty_cache()
     result["roofline"]["read_probe"] = read_probe(torch, pkg, att_bytes)
+    result["roofline"]["frac_of_read_probe"] = achieved / result["roofline"]["read_probe"]["stream_2GiB_GBps"]
+    prop = torch.cuda.get_device_properties(0)
+    result["device"] = {"name": prop.name, "arch": prop.gcnArchName, "compute_units": prop.multi_processor_count,
+                        "wavefront": prop.warp_size, "lds_bytes_per_workgroup": prop.shared_memory_per_block,
+                        "l2_bytes": prop.L2_cache_size, "hbm_bytes": prop.total_memory}
     print(json.dumps(result))
 
 
