@@ -682,7 +682,14 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
                                                             const double *__restrict__ shared_all, RandomRank rr) {
   typedef typename std::conditional<kShared, double, float>::type Imp;   // importance as stored
   constexpr int kRsWaves = T / kWave;
+  // width of the first radix pass: 11 bits where a workgroup has the threads to scan 2048 bins
+  // (the one-wavefront instance keeps 8: its many small workgroups share a CU's LDS; so do the
+  // layer-scope instances, which measured 6 us slower with the separate first pass: those start
+  // with the 8-bit passes below)
+  constexpr bool kWide0 = T >= 256 && !kShared;
+  constexpr int kRadix0Bits = kWide0 ? 11 : 8, kRadix0Bins = kWide0 ? 1 << kRadix0Bits : 1;
   __shared__ int hist[512];                         // two histograms, used alternately
+  __shared__ int hist0[kRadix0Bins];                // the wider histogram of the first pass
   __shared__ int s_tmp[kRsWaves];
   __shared__ int s_cnt[E * kRsWaves];               // tied lanes per (round, wavefront)
   __shared__ int s_keep[E * kRsWaves + 1];          // kept lanes per (round, wavefront), then their prefix sums
@@ -794,15 +801,60 @@ void rank_select_reg_kernel(CacheView cv, LayerMask appended,
   const unsigned long long span = kmax - kmin;
   const int top = span ? 63 - __clzll((long long)span) : 0;   // highest differing bit
 
-  // radix select of the e-th smallest key, 8 bits (or what is left) per pass.  Two barriers
+  // radix select of the e-th smallest key.  The first pass takes 11 bits (or what there is): with
+  // a few thousand candidates its bin then holds a handful of keys and the second pass usually
+  // ends the search, where 8-bit passes need three.  Every thread scans its share of the 2048
+  // bins (contiguous, so that one prefix sum over the workgroup orders them).
+  unsigned long long mask = 0ull;
+  for (int bin = tid; bin < 512; bin += T) hist[bin] = 0;
+  if constexpr (kWide0)
+    for (int bin = tid; bin < kRadix0Bins; bin += T) hist0[bin] = 0;
+  __syncthreads();
+  int hi_bit = top + 1;
+  if constexpr (kWide0) {
+    const int shift = hi_bit > kRadix0Bits ? hi_bit - kRadix0Bits : 0;
+    const unsigned dmask = (1u << (hi_bit - shift)) - 1u;
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+      if (k < Ed && tid + k * T < ncand) {
+        // (lanes that share the first active lane's bin add once: see below)
+        const int bin = (int)((unsigned)(key[k] >> shift) & dmask);
+        const int b0 = __builtin_amdgcn_readfirstlane(bin);
+        const unsigned long long same = __builtin_amdgcn_ballot_w64(bin == b0);
+        if (bin != b0) atomicAdd(&hist0[bin], 1);
+        else if (lanes_below(same) == 0) atomicAdd(&hist0[b0], __builtin_popcountll(same));
+      }
+    }
+    __syncthreads();
+    constexpr int BPT = kRadix0Bins / T;              // bins per thread
+    int cnt[BPT], mine = 0;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      cnt[j] = hist0[BPT * tid + j];
+      mine += cnt[j];
+    }
+    int total;
+    int before = block_scan_excl<kRsWaves>(mine, s_tmp, &total);
+    const int krem = e;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      if (before < krem && krem <= before + cnt[j]) {     // exactly one bin holds the cut-off
+        s_prefix = (unsigned long long)(BPT * tid + j) << shift;
+        s_krem = krem - before;
+        s_done = (krem - before == cnt[j]);               // the whole bucket goes
+      }
+      before += cnt[j];
+    }
+    mask = ~0ull << shift;
+    hi_bit = shift;
+    __syncthreads();
+  }
+  // the following passes: 8 bits (or what is left) each.  Two barriers
   // per pass: the histogram of the next pass (the other of two buffers) is cleared while this
   // one is filled, and the first wavefront alone scans the 256 bins (four per lane) and picks
   // the bin that holds the cut-off.
-  unsigned long long mask = 0ull;
-  for (int bin = tid; bin < 512; bin += T) hist[bin] = 0;
-  __syncthreads();
   int pass = 0;
-  for (int hi_bit = top + 1; hi_bit > 0; ++pass) {
+  for (; hi_bit > 0 && !s_done; ++pass) {
     const int shift = hi_bit > 8 ? hi_bit - 8 : 0;
     const unsigned dmask = (1u << (hi_bit - shift)) - 1u;
     int *hcur = hist + 256 * (pass & 1), *hnext = hist + 256 * ((pass + 1) & 1);
