@@ -187,9 +187,6 @@ typedef struct conf_kv_stats {
  * splits of a unit on one XCD and is the default when the number of kv-heads is a multiple of 8);
  * CONF_KV_COMPACT_PAIRED=0/1 (read at every conf_kv_evict_compact) forces one of the two grid
  * shapes of the compaction kernel, which is otherwise chosen by the number of units;
- * CONF_KV_COMPACT_SOLO=0/1 (read the same way) forces, outside the step that follows a prompt
- * load, the roles of a unit's compaction side by side (0) or one workgroup per unit that takes
- * them in turn (1), which is otherwise chosen by the number of units;
  * CONF_KV_TEST_TAG_BASE=n starts the device-side tag bases (see conf_kv_tag_state) at n instead
  * of 0, so that a test reaches the clearing of the exchange words in a few steps. */
 

@@ -1225,6 +1225,13 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
                                                              const int32_t *__restrict__ sel_all, int paired) {
   const int u = blockIdx.x, tid = threadIdx.x;
   clear_tagged_if_asked(cv);
+  // what this workgroup moves: the payload rows of the ring the holes lie in (K, V or both),
+  // the per-slot planes, the FP16 rows of a mixed cache (K, V or both)
+  const int y = blockIdx.y;
+  const bool do_k = paired ? y == 0 : (y == 0 || y == 3), do_v = paired ? y == 0 : (y == 1 || y == 4);
+  const bool do_meta = paired ? y == 1 : y == 2;
+  const bool late16 = paired ? y == 1 : y >= 3;     // FP16 rows of a mixed cache
+  const bool main_rows = paired ? y == 0 : y <= 1;
   const int32_t *sel = sel_all + (size_t)u * kSelInts;
   const int n_new = sel[0], n8_new = sel[1], hole = sel[2], evicted = sel[3];
   if (hole >= n_new) return;                          // nothing moves
@@ -1236,17 +1243,6 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
   const int e8 = n8_old - n8_new;
   const int jr = sel[4] + 1 - (fp16_only ? evicted : e8);   // right shift: survivors [0, jr) move
   const int h0_new = sel[6];
-
-  // what this workgroup moves: the payload rows of the ring the holes lie in (K, V or both),
-  // the per-slot planes, the FP16 rows of a mixed cache (K, V or both).  A grid with one
-  // workgroup per unit takes every role in turn.
-  const bool solo = gridDim.y == 1;
-  const int roles = paired ? 2 : 5;
-  for (int y = solo ? 0 : (int)blockIdx.y; y < (solo ? roles : (int)blockIdx.y + 1); ++y) {
-  const bool do_k = paired ? y == 0 : (y == 0 || y == 3), do_v = paired ? y == 0 : (y == 1 || y == 4);
-  const bool do_meta = paired ? y == 1 : y == 2;
-  const bool late16 = paired ? y == 1 : y >= 3;     // FP16 rows of a mixed cache
-  const bool main_rows = paired ? y == 0 : y <= 1;
 
   // A mixed cache that moves a few slots and no FP16 row -- a unit of a decode loop in its steady
   // state -- is served by the unit's first workgroup alone, in one pass: the sources of all
@@ -1373,8 +1369,6 @@ __global__ __launch_bounds__(kEvThreads) void compact_kernel(CacheView cv,
     }
   }
   if (!fp16_only && late16 && evicted != e8) move_fp16_rows(paired || y == 3, paired || y == 4);
-  if (solo) __syncthreads();
-  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1604,25 +1598,18 @@ hipError_t launch_evict_compact(const CacheView &cv, const LayerMask &appended, 
     return hipGetLastError();
   }
   const dim3 cgrid(U, paired ? 2 : 5);
-  // steady state with thousands of units: one workgroup per unit (its one-pass path serves nearly
-  // every unit, and the other roles' workgroups would only start and leave; a unit that moves
-  // more takes the roles in turn).  Measured per step: 8192 units 85 -> 76 us, 2048 units 47 -> 42.5;
-  // with a few hundred units of long moves the roles side by side are faster (256 units: 32 against 37).
-  int solo = U >= 2048;
-  if (const char *e = getenv("CONF_KV_COMPACT_SOLO")) solo = atoi(e) != 0;         // test hook: force a form
-  const dim3 sgrid(U, solo ? 1 : (paired ? 2 : 5));
   if (cv.D == 64) {
     if (after_prompt)
       hipLaunchKernelGGL((compact_kernel<64, false>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     else
-      hipLaunchKernelGGL((compact_kernel<64, true>), sgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
+      hipLaunchKernelGGL((compact_kernel<64, true>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<64>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
                        attend_launches, conf_launches);
   } else {
     if (after_prompt)
       hipLaunchKernelGGL((compact_kernel<128, false>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     else
-      hipLaunchKernelGGL((compact_kernel<128, true>), sgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
+      hipLaunchKernelGGL((compact_kernel<128, true>), cgrid, dim3(kEvThreads), 0, stream, cv, src, sel, paired);
     hipLaunchKernelGGL(demote_kernel<128>, dim3((U + 3) / 4), dim3(kEvThreads), 0, stream, cv, sel, U, appended,
                        attend_launches, conf_launches);
   }

@@ -729,24 +729,20 @@ def test_evict_pages_ties_and_degenerate(lib, torch_cuda):
     assert np.array_equal(a.pos, b.pos)
 
 
-@pytest.mark.parametrize("paired,solo", [(0, 0), (1, 0), (0, 1), (1, 1)])
+@pytest.mark.parametrize("paired", [0, 1])
 @pytest.mark.parametrize("G,D,W,N", [(4, 128, 16, (150, 230)), (1, 64, -1, (150, 230)), (2, 128, 120, (60, 100)),
                                      (3, 64, 12, (150, 230))])
-def test_lockstep_both_compaction_forms(lib, torch_cuda, paired, solo, G, D, W, N):
+def test_lockstep_both_compaction_forms(lib, torch_cuda, paired, G, D, W, N):
     """The compaction kernel has a form with one workgroup per plane and one that pairs K with V
-    (chosen by the unit count), and outside the step after a prompt load either the roles of a
-    unit run side by side or one workgroup takes them in turn (chosen by the unit count too); all
-    four combinations are forced here on the same runs, the third of which evicts FP16 slots (the
-    FP16 window is wider than the budgets).  Each run has a first step that moves hundreds of rows
-    per unit (the chunked walk), steady steps that move a few (the one-pass path of the unit's
-    first workgroup) and steps where the budget drops and a unit moves many rows again (the roles
-    in turn, when forced), at both head dimensions."""
+    (chosen by the unit count); both are forced here on the same runs, the third of which evicts
+    FP16 slots (the FP16 window is wider than the budgets).  Each run has a first step that moves
+    hundreds of rows per unit (the chunked walk) and steady steps that move a few (the one-pass
+    path of the unit's first workgroup), at both head dimensions."""
     wl = small(1).scaled(n_layers=2, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=D, vocab=2003, prefill=260,
                          steps=24, n_tight=(N[0],) * 2, n_loose=(N[1],) * 2, protected=20, fp16_window=W,
                          alpha=0.5, logit_std=(0.5, 6.0), logit_run=4)
-    say(f"lockstep compaction form paired={paired} solo={solo} G={G} D={D} W={W} N={N}")
+    say(f"lockstep compaction form paired={paired} G={G} D={D} W={W} N={N}")
     os.environ["CONF_KV_COMPACT_PAIRED"] = str(paired)
-    os.environ["CONF_KV_COMPACT_SOLO"] = str(solo)
     try:
         ls = Lockstep(lib, wl, seed=21)
         for t in range(wl.steps):
@@ -757,7 +753,6 @@ def test_lockstep_both_compaction_forms(lib, torch_cuda, paired, solo, G, D, W, 
         ls.close()
     finally:
         os.environ.pop("CONF_KV_COMPACT_PAIRED", None)
-        os.environ.pop("CONF_KV_COMPACT_SOLO", None)
 
 
 @pytest.mark.parametrize("prefill,D,W", [(6000, 128, 64), (1200, 64, -1), (40000, 128, 32)])
